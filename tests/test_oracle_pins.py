@@ -1,0 +1,285 @@
+"""Pins of the float64 oracle against facts fixed by the paper and by mathematics
+(no GPU, no product code).  Each test names what it would catch."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.fft
+import torch
+
+from oracle import demo_oracle as O
+
+
+# ---- projection matrix ----------------------------------------------------
+@pytest.mark.parametrize("s", [4, 32, 64, 128])
+def test_basis_orthonormal(s):
+    # appendix "Multilinear Transforms ...": the DCT matrix is unitary, P^T = P^-1
+    P = O.dct_basis(s)
+    assert np.abs(P @ P.T - np.eye(s)).max() < 1e-13
+    assert np.abs(P.T @ P - np.eye(s)).max() < 1e-13
+
+
+@pytest.mark.parametrize("s", [4, 32, 64, 128])
+def test_dct_matches_library_routine(s):
+    # the transform reduces to the library's orthonormal DCT-II; catches a wrong
+    # normalisation, a wrong phase (2n+1) and a transposed operand (P^T B P)
+    rng = np.random.default_rng(s)
+    b1 = rng.standard_normal((5, s))
+    b2 = rng.standard_normal((2, 3, s, s))
+    P = O.dct_basis(s)
+    assert np.allclose(O.dct_chunks(b1, P), scipy.fft.dct(b1, type=2, norm="ortho", axis=-1), atol=1e-12)
+    assert np.allclose(O.dct_chunks(b2, P), scipy.fft.dctn(b2, type=2, norm="ortho", axes=(-2, -1)), atol=1e-12)
+    assert np.allclose(O.idct_chunks(b1, P), scipy.fft.idct(b1, type=2, norm="ortho", axis=-1), atol=1e-12)
+    assert np.allclose(O.idct_chunks(b2, P), scipy.fft.idctn(b2, type=2, norm="ortho", axes=(-2, -1)), atol=1e-12)
+
+
+def test_dct_closed_forms():
+    s = 64
+    P = O.dct_basis(s)
+    # constant chunk c -> only the DC coefficient: c*s (2-D), c*sqrt(s) (1-D)
+    q2 = O.dct_chunks(np.full((1, 1, s, s), 0.25), P)[0, 0]
+    assert abs(q2[0, 0] - 0.25 * s) < 1e-12 and np.abs(q2).sum() - abs(q2[0, 0]) < 1e-10
+    q1 = O.dct_chunks(np.full((1, s), 0.25), P)[0]
+    assert abs(q1[0] - 0.25 * np.sqrt(s)) < 1e-12 and np.abs(q1[1:]).max() < 1e-12
+    # a separable cosine  cos(pi(2i+1)u/2s) cos(pi(2j+1)v/2s)  -> a single coefficient at (u, v),
+    # u along dimension 0: catches swapped frequency axes
+    u, v = 3, 10
+    i = np.arange(s)
+    blk = np.outer(np.cos(np.pi * (2 * i + 1) * u / (2 * s)), np.cos(np.pi * (2 * i + 1) * v / (2 * s)))
+    Q = O.dct_chunks(blk[None, None], P)[0, 0]
+    assert abs(Q[u, v] - s / 2) < 1e-10
+    Q[u, v] = 0
+    assert np.abs(Q).max() < 1e-10
+
+
+def test_parseval():
+    rng = np.random.default_rng(1)
+    for s in (32, 64):
+        P = O.dct_basis(s)
+        b = rng.standard_normal((2, 2, s, s))
+        Q = O.dct_chunks(b, P)
+        assert np.allclose((Q ** 2).sum((-1, -2)), (b ** 2).sum((-1, -2)), rtol=1e-12)
+
+
+# ---- blocking operator ------------------------------------------------------
+def test_blocking_example_128x512():
+    # appendix "Example (Matrix Blocking)": 128 x 512 into 16 x 32 blocks,
+    # (B_{k0,k1})_{j0,j1} = X[16 k0 + j0, 32 k1 + j1], k0 in [0,8), k1 in [0,16)
+    X = np.arange(128 * 512, dtype=np.float64).reshape(128, 512)
+    B = O.chunk(X, 16, 32)
+    assert B.shape == (8, 16, 16, 32)
+    for k0, k1, j0, j1 in [(0, 0, 0, 0), (0, 0, 15, 31), (7, 15, 15, 31), (3, 9, 4, 17), (1, 0, 0, 5)]:
+        assert B[k0, k1, j0, j1] == X[16 * k0 + j0, 32 * k1 + j1]
+    assert np.array_equal(O.unchunk(B), X)
+    with pytest.raises(ValueError):
+        O.chunk(X, 24, 32)
+
+
+# ---- hand-worked examples ---------------------------------------------------
+def test_hand_example_1d(golden):
+    G = golden("hand_1d_s4.txt")
+    e = O.encode(np.array(G["m_prev"]), np.array(G["g"]), G["beta"][0], 4, 2)
+    assert np.allclose(e["m_mid"], G["m_mid"], atol=1e-15)
+    assert np.allclose(e["Q"][0], G["q"], atol=1e-13)
+    assert e["idx"][0].tolist() == [int(v) for v in G["idx"]]
+    assert np.allclose(e["val"][0], [G["q"][0], G["q"][1]], atol=1e-13)
+    assert np.allclose(e["m_new"], G["m_new"], atol=1e-13)
+    # decode of the own payload reproduces IDCT(q_hat); all positive -> x <- x - lr
+    x = np.array([0.5, -0.25, 0.0, 1.0])
+    d = O.decode(x, e["idx"][None], e["val"][None], 2.0 ** -10, 0.0, 4)
+    assert np.allclose(d["R"], G["idct_qhat"], atol=1e-13)
+    assert np.array_equal(d["x_new"], (x - 2.0 ** -10).astype(np.float32))
+    # near tie (equal in exact arithmetic): either completion is legitimate
+    t = O.encode(np.zeros(4), np.array(G["tie_m_mid"]), 0.9, 4, 2)
+    assert np.allclose(t["Q"][0], G["tie_q"], atol=1e-13)
+    assert t["idx"][0, 0] == int(G["tie_idx_first"][0])
+    assert t["idx"][0, 1] in [int(v) for v in G["tie_idx_second_any_of"]]
+    # exact tie (all-zero chunk): lowest flat indices first, zero values, momentum untouched
+    z = O.encode(np.zeros(8), np.zeros(8), 0.9, 4, 2)
+    assert z["idx"].tolist() == [[0, 1], [0, 1]] and not z["val"].any() and not z["m_new"].any()
+
+
+def test_hand_example_2d(golden):
+    G = golden("hand_2d_s4.txt")
+    B = np.array(G["B"]).reshape(4, 4)
+    e = O.encode(np.zeros((4, 4)), B, 0.999, 4, 3)
+    Q = e["Q"][0].reshape(4, 4)
+    assert np.allclose(Q[0], G["Q_row0"], atol=1e-12)
+    assert np.allclose(Q[:, 0], G["Q_col0"], atol=1e-12)
+    assert np.abs(Q[1:, 1:]).max() < 1e-12
+    assert e["idx"][0].tolist() == [int(v) for v in G["idx"]]
+    assert np.allclose(e["m_new"][0], G["resid_row0"], atol=1e-12)
+    assert np.allclose(e["m_new"][1], G["resid_row1"], atol=1e-12)
+    assert np.allclose(e["m_new"][::-1, ::-1], -e["m_new"], atol=1e-12)
+
+
+# ---- top-k --------------------------------------------------------------------
+def test_topk_brute_force():
+    # all k on tiny chunks, with repeated magnitudes: compare with an explicit
+    # search over all k-subsets for the maximal (magnitude desc, index asc) choice
+    rng = np.random.default_rng(7)
+    for trial in range(40):
+        q = rng.integers(-3, 4, size=6).astype(np.float64)        # many ties
+        for k in range(1, 7):
+            got = O.topk_indices(q, k).tolist()
+            assert len(set(got)) == k
+            best = max(itertools.combinations(range(6), k),
+                       key=lambda c: (sum(abs(q[i]) for i in c), [-i for i in c]))
+            thr = min(abs(q[i]) for i in got)
+            assert all(abs(q[i]) <= thr for i in range(6) if i not in got)
+            assert sum(abs(q[i]) for i in got) == sum(abs(q[i]) for i in best)
+            # ties resolved towards the lowest index, output by descending magnitude
+            keyed = sorted(range(6), key=lambda i: (-abs(q[i]), i))[:k]
+            assert got == keyed
+
+
+def test_topk_domain():
+    with pytest.raises(ValueError):
+        O.topk_indices(np.ones(4), 0)
+    with pytest.raises(ValueError):
+        O.topk_indices(np.ones(4), 5)
+
+
+# ---- encode invariants ------------------------------------------------------
+@pytest.mark.parametrize("shape,s", [((128,), 32), ((64, 128), 32), ((128, 64), 64)])
+def test_k_equals_M_exact_recovery(shape, s):
+    # appendix remark on isometric transformations: k = M gives perfect reconstruction,
+    # so the residual momentum is zero and decode of the own payload returns m_mid
+    rng = np.random.default_rng(3)
+    m, g = rng.standard_normal(shape), rng.standard_normal(shape)
+    M = s if len(shape) == 1 else s * s
+    e = O.encode(m, g, 0.999, s, M)
+    assert np.abs(e["m_new"]).max() < 1e-12
+    assert sorted(e["idx"][0].tolist()) == list(range(M))
+    d = O.decode(np.zeros(shape), e["idx"][None], e["val"][None], 1e-3, 0.0, s)
+    assert np.allclose(d["R"], e["m_mid"], atol=1e-12)
+
+
+@pytest.mark.parametrize("k", [1, 8, 32])
+def test_residual_bounds_and_split(k):
+    rng = np.random.default_rng(11)
+    s = 32
+    m, g = rng.standard_normal((64, 96)) * 1e-3, rng.standard_normal((64, 96)) * 1e-2
+    e = O.encode(m, g, 0.999, s, k)
+    M = s * s
+    P = O.dct_basis(s)
+    Q = e["Q"]
+    Qhat = np.zeros_like(Q)
+    np.put_along_axis(Qhat, e["idx"].astype(np.int64), e["val"], axis=1)
+    # lemma "Optimal Universal l1-norm Bound": ||X* - X||_1 <= (1 - k/M) ||X||_1
+    assert np.all(np.abs(Q - Qhat).sum(1) <= (1 - k / M) * np.abs(Q).sum(1) + 1e-15)
+    # l2 remark through the isometry, per chunk, plus the exact Pythagoras split
+    b_mid = O.chunk(e["m_mid"], s).reshape(-1, M)
+    b_new = O.chunk(e["m_new"], s).reshape(-1, M)
+    n_mid, n_new = (b_mid ** 2).sum(1), (b_new ** 2).sum(1)
+    assert np.all(np.sqrt(n_new) <= np.sqrt(1 - k / M) * np.sqrt(n_mid) + 1e-15)
+    assert np.allclose(n_mid, (e["val"] ** 2).sum(1) + n_new, rtol=1e-11)
+    # the DCT of the residual vanishes at the selected slots and is below the threshold elsewhere
+    Qres = O.dct_chunks(O.chunk(e["m_new"], s), P).reshape(-1, M)
+    thr = np.abs(e["val"]).min(1)
+    assert np.abs(np.take_along_axis(Qres, e["idx"].astype(np.int64), 1)).max() < 1e-14
+    assert np.all(np.abs(Qres).max(1) <= thr + 1e-15)
+    # payload size: nchunks*k pairs, reduction M/k  (Sec. 2.1 "Top-k Sparsification")
+    assert e["idx"].shape == (6, k) and e["val"].shape == (6, k)
+
+
+def test_momentum_update_form():
+    # Algorithm 1: m <- beta m + g (gradient unweighted)
+    e = O.encode(np.full(4, 2.0), np.full(4, 1.0), 0.5, 4, 4)
+    assert np.array_equal(e["m_mid"], np.full(4, 2.0))
+
+
+def test_forced_indices():
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal((32, 32))
+    e0 = O.encode(np.zeros((32, 32)), g, 0.9, 32, 4)
+    alt = e0["idx"].copy()
+    alt[0, 3] = (int(alt[0, 0]) + 1) % 1024 if (int(alt[0, 0]) + 1) % 1024 not in alt[0] else 1023
+    e1 = O.encode(np.zeros((32, 32)), g, 0.9, 32, 4, forced_idx=alt)
+    assert np.array_equal(e1["val"][0], e0["Q"][0, alt[0]])
+
+
+# ---- decode -------------------------------------------------------------------
+def test_aggregate_is_ordered_sum_and_linear():
+    rng = np.random.default_rng(2)
+    W, nch, k, s = 5, 4, 6, 8
+    idx = np.stack([np.stack([rng.permutation(s * s)[:k] for _ in range(nch)]) for _ in range(W)]).astype(np.int32)
+    idx[1] = idx[0]                                     # forced collisions between workers
+    val = rng.standard_normal((W, nch, k))
+    S = O.aggregate(idx, val, s * s)
+    ref = np.zeros((nch, s * s))
+    for w in range(W):
+        for c in range(nch):
+            for t in range(k):
+                ref[c, idx[w, c, t]] += val[w, c, t]
+    assert np.array_equal(S, ref)
+    # linearity (Sec. 2.1): decoding W payloads = sum of the single-payload reconstructions,
+    # and mean instead of sum leaves every sign unchanged
+    x = np.zeros((16, 16))
+    d_all = O.decode(x, idx, val, 1e-3, 0.0, s)
+    parts = sum(O.decode(x, idx[w:w + 1], val[w:w + 1], 1e-3, 0.0, s)["R"] for w in range(W))
+    assert np.allclose(d_all["R"], parts, atol=1e-13)
+    d_mean = O.decode(x, idx, val / W, 1e-3, 0.0, s)
+    assert np.array_equal(np.sign(d_mean["R"]), np.sign(d_all["R"]))
+    # out-of-range indices are ignored
+    bad = idx.copy()
+    bad[0, 0, 0] = s * s
+    bad[0, 0, 1] = -1
+    S2 = O.aggregate(bad, val, s * s)
+    fix = val.copy()
+    fix[0, 0, :2] = 0.0
+    assert np.allclose(S2, O.aggregate(idx, fix, s * s))
+
+
+def test_sign_update_closed_form():
+    s = 4
+    P = O.dct_basis(s)
+    # one DC coefficient -> constant positive block; one negative; one empty (sgn 0 = 0)
+    idx = np.zeros((1, 3, 1), np.int32)
+    val = np.array([[[2.0], [-3.0], [0.0]]])
+    x = np.linspace(-1, 1, 12)
+    d = O.decode(x, idx, val, 0.125, 0.0, s)
+    assert np.array_equal(np.sign(d["R"]), np.repeat([1.0, -1.0, 0.0], 4))
+    assert np.allclose(d["x_new"], x - 0.125 * np.repeat([1.0, -1.0, 0.0], 4), atol=1e-7)
+    # weight decay: x' = x - eta (sgn + lambda x); empty chunk only shrinks x
+    d = O.decode(x, idx, val, 0.125, 0.5, s)
+    expect = x - 0.125 * (np.repeat([1.0, -1.0, 0.0], 4) + 0.5 * x)
+    assert np.allclose(d["x_new"], expect, atol=1e-7)
+    # 2-D placement: coefficient (u=1, v=0) varies along dimension 0 only
+    idx2 = np.full((1, 1, 1), 1 * s + 0, np.int32)
+    d2 = O.decode(np.zeros((4, 4)), idx2, np.ones((1, 1, 1)), 1.0, 0.0, s)
+    assert np.allclose(d2["R"], np.outer(P[1], P[0]), atol=1e-14)
+    assert np.array_equal(d2["x_new"], -np.sign(np.outer(P[1], P[0])).astype(np.float32))
+
+
+def test_bf16_rounding_matches_library():
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000) * 0.02,
+                        np.array([1.0, 1.00390625, 1.005859375, 1.001953125, -1.001953125, 0.0, 3.0e38])])
+    x = x.astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(O.round_to_bf16(x), ref)
+    # exact half-way cases go to the even neighbour
+    assert O.round_to_bf16(np.float32(1.00390625)) == np.float32(1.0)          # 1 + 2^-8 -> 1
+    assert O.round_to_bf16(np.float32(1.01171875)) == np.float32(1.015625)     # 1 + 3*2^-8 -> 1 + 2^-6
+
+
+def test_bf16_param_update():
+    # lr = 1e-3 from -0.5 towards -0.501: below half a bfloat16 ulp (2^-9), rounded away;
+    # from +0.5 downwards the ulp is 2^-9 and the step survives; small |x| moves.  Values are those of float32 arithmetic followed by one RNE rounding.
+    x = O.round_to_bf16(np.array([0.5, -0.5, 0.01, -0.01, 0.0], np.float32)).astype(np.float64)
+    idx = np.zeros((1, 5, 1), np.int32)
+    val = np.ones((1, 5, 1))
+    d = O.decode(np.repeat(x, 4), idx, val, 1e-3, 0.0, 4, "bf16")["x_new"].reshape(5, 4)[:, 0]
+    ref = (torch.tensor(x, dtype=torch.float32) - torch.tensor(1e-3, dtype=torch.float32)).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(d, ref)
+    assert d[1] == np.float32(-0.5) and d[0] == np.float32(0.5 - 2.0 ** -9) and d[2] < np.float32(0.01)
+
+
+def test_step_is_encode_then_decode():
+    rng = np.random.default_rng(9)
+    m, g, x = rng.standard_normal((32, 64)), rng.standard_normal((32, 64)), rng.standard_normal((32, 64))
+    st = O.step(m, g, x, 0.999, 1e-3, 0.1, 32, 8)
+    e = O.encode(m, g, 0.999, 32, 8)
+    d = O.decode(x, e["idx"][None], e["val"].astype(np.float32)[None], 1e-3, 0.1, 32)
+    assert np.array_equal(st["m_new"], e["m_new"]) and np.array_equal(st["x_new"], d["x_new"])
