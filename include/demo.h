@@ -1,0 +1,130 @@
+/*
+ * demo.h -- C ABI of the MI355X (gfx950) implementation of DeMo's per-step
+ * compression path (arXiv 2411.19870).
+ *
+ * The entry points follow the paper's algorithm statement: Algorithm 1 ("DeMo:
+ * Decoupled Momentum") takes learning rate eta, momentum coefficient beta, weight
+ * decay lambda, sparsity budget k and the DCT matrices (fixed by the chunk size
+ * s); the appendix algorithm "Decoupled Momentum Optimization" lists the same
+ * inputs plus the chunk sizes.  One call processes a whole list of tensors.
+ *
+ * Conventions
+ *   - All tensor and payload pointers are DEVICE pointers owned by the caller; the
+ *     library never frees or keeps them after the call returns.  `demo_tensor`
+ *     arrays themselves are HOST memory and are copied during the call.
+ *   - Tensors are dense row-major.  cols == 0 marks an order-1 tensor of `rows`
+ *     elements, chunked into pieces of s; otherwise the tensor is rows x cols and
+ *     is chunked into s x s blocks (appendix "Multilinear Transforms and
+ *     Chunk-wise Tensor Blocking": block (k0,k1) holds X[k0*s+j0, k1*s+j1]).
+ *     rows and cols must be multiples of s.  Chunks are numbered row-major over
+ *     (k0, k1).
+ *   - Payload of one worker for one tensor: idx[nchunks][k] (int32) and
+ *     val[nchunks][k] (float32).  idx is the flat position u*s + v of a DCT
+ *     coefficient inside its chunk, u being the frequency along dimension 0 (for
+ *     order-1 tensors simply u).  Encode lists the k pairs of a chunk by
+ *     descending magnitude, equal magnitudes by ascending index.  For decode the
+ *     payloads of W workers are stacked worker-major: idx[W][nchunks][k],
+ *     val[W][nchunks][k]; encode writes worker slot 0 of such a buffer.
+ *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = default stream) and results are valid after that
+ *     stream has been synchronised.  The first call that presents a new tensor
+ *     list synchronises once to upload its descriptor table; repeating the same
+ *     list does not.
+ *   - Every function returns DEMO_OK (0) or a negative demo_status.  Arguments
+ *     are validated on the host before anything is enqueued; on error nothing
+ *     was launched.  No exceptions cross this boundary.
+ *   - A context may be used from one host thread at a time.
+ */
+#ifndef DEMO_H_
+#define DEMO_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct demo_ctx demo_ctx;
+
+typedef enum demo_status {
+  DEMO_OK = 0,
+  DEMO_ERR_ARG = -1,         /* null pointer, n < 0, W < 1, k < 1, k > M (M = s or s*s)   */
+  DEMO_ERR_SHAPE = -2,       /* rows or cols not a positive multiple of s                 */
+  DEMO_ERR_UNSUPPORTED = -3, /* s not in {32,64,128}, unknown dtype, k > DEMO_MAX_K       */
+  DEMO_ERR_HIP = -4,         /* a HIP runtime call failed (see demo_last_hip_error)       */
+  DEMO_ERR_NOMEM = -5        /* host or device allocation for the context's tables failed */
+} demo_status;
+
+typedef enum demo_dtype { DEMO_F32 = 0, DEMO_BF16 = 1 } demo_dtype;
+
+/* Largest supported sparsity budget per chunk (the paper uses k <= 32). */
+#define DEMO_MAX_K 256
+
+/* One tensor of the list.  64 bytes, no implicit padding. */
+typedef struct demo_tensor {
+  const void* grad;    /* device; gradient g, grad_dtype; read by encode/step; may be NULL for decode  */
+  float*      mom;     /* device; momentum m (float32); updated in place by encode/step; NULL for decode */
+  void*       param;   /* device; parameters x, param_dtype; updated in place by decode/step; NULL for encode */
+  int32_t*    idx;     /* device; payload indices, see above                                           */
+  float*      val;     /* device; payload values, see above                                            */
+  int64_t     rows;    /* > 0                                                                           */
+  int64_t     cols;    /* 0 for an order-1 tensor                                                       */
+  int32_t     grad_dtype;   /* demo_dtype */
+  int32_t     param_dtype;  /* demo_dtype */
+} demo_tensor;
+
+/* Create / destroy a context.  The context owns the DCT basis tables (built on
+ * the host in double precision, rounded once to float32, one per chunk size) and
+ * the cached device copies of tensor descriptor tables.  demo_create performs no
+ * GPU call; device memory is allocated on first use.  */
+int demo_create(demo_ctx** out);
+int demo_destroy(demo_ctx* ctx);
+
+/* Host-only helper: number of (idx, val) pairs one worker's payload has for a
+ * tensor, nchunks * k (Sec. 2.1 "Top-k Sparsification": k coefficients per chunk,
+ * a reduction of (prod s_i)/k).  Validates shape, s and k like the calls below. */
+int demo_payload_elems(int64_t rows, int64_t cols, int s, int k, int64_t* out);
+
+/* Worker side of Algorithm 1 for every tensor of the list (appendix algorithm
+ * CompressChunks):   m <- beta*m + g;  per chunk Q = DCT(m), keep the k
+ * largest-magnitude coefficients (exactly k), write them to idx/val (worker slot
+ * 0), and m <- m - IDCT(kept).  Requires grad, mom, idx, val.  */
+int demo_encode(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k,
+                void* hip_stream);
+
+/* Server side of Algorithm 1 (appendix algorithm Decompress&Aggregate followed by
+ * the update line):  per chunk sum the coefficients of the W payloads (workers
+ * added in order 0..W-1, pairs whose index is outside [0, M) are skipped),
+ * m_t = IDCT(sum), then x <- x - lr*(sgn(m_t) + weight_decay*x) with sgn(0) = 0,
+ * evaluated in float32 as t = fma(weight_decay, x, sgn), x' = fma(-lr, t, x) and
+ * rounded to param_dtype (nearest-even).  Requires param, idx, val.  */
+int demo_decode(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, float lr,
+                float weight_decay, int s, int k, void* hip_stream);
+
+/* One full single-worker step: demo_encode followed by demo_decode with W = 1 on
+ * the payload just written.  Requires every pointer of demo_tensor.  */
+int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, float lr,
+              float weight_decay, int s, int k, void* hip_stream);
+
+/* Average duration in milliseconds of the kernels launched by the most recent
+ * encode / decode call on this context, measured with HIP events recorded on the
+ * call's own stream (blocks until those events complete).  which: 0 = encode
+ * order-2 kernel, 1 = encode order-1 kernel, 2 = decode order-2, 3 = decode
+ * order-1.  Timing is recorded only while enabled with demo_set_timing(ctx, 1).
+ * Returns DEMO_ERR_ARG if nothing was recorded for `which`.  */
+int demo_set_timing(demo_ctx* ctx, int enabled);
+int demo_last_kernel_ms(demo_ctx* ctx, int which, float* ms);
+
+/* Kernel family used by later calls: 1 (default) = the fastest kernels available
+ * for the chunk size, 0 = the generic LDS-staged kernels only (kept selectable so
+ * that the two families can be checked against each other).  */
+int demo_set_variant(demo_ctx* ctx, int variant);
+
+/* Static text for a status code; hipGetErrorString of the last failing HIP call. */
+const char* demo_strerror(int status);
+const char* demo_last_hip_error(demo_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEMO_H_ */

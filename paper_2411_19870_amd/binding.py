@@ -1,0 +1,205 @@
+"""ctypes binding of libdemo.so: argument marshalling only.
+
+Every function mirrors an entry point of include/demo.h.  Tensors are torch
+tensors living on the GPU; torch is used for device memory and streams only, all
+arithmetic runs in the HIP kernels.  There is no CPU fallback: if the library is
+missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdemo.so")
+
+DEMO_OK, DEMO_ERR_ARG, DEMO_ERR_SHAPE, DEMO_ERR_UNSUPPORTED, DEMO_ERR_HIP, DEMO_ERR_NOMEM = 0, -1, -2, -3, -4, -5
+DEMO_F32, DEMO_BF16 = 0, 1
+DEMO_MAX_K = 256
+
+EXPORTS = [
+    "demo_create", "demo_destroy", "demo_payload_elems", "demo_encode", "demo_decode", "demo_step",
+    "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_strerror", "demo_last_hip_error",
+]
+
+
+class DemoTensor(ctypes.Structure):
+    _fields_ = [
+        ("grad", ctypes.c_void_p), ("mom", ctypes.c_void_p), ("param", ctypes.c_void_p),
+        ("idx", ctypes.c_void_p), ("val", ctypes.c_void_p),
+        ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+        ("grad_dtype", ctypes.c_int32), ("param_dtype", ctypes.c_int32),
+    ]
+
+
+class DemoError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libdemo status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libdemo.so (built by paper_2411_19870_amd/build.py).  Fails loudly."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2411_19870_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int64
+    lib.demo_create.argtypes = [ctypes.POINTER(vp)]
+    lib.demo_destroy.argtypes = [vp]
+    lib.demo_payload_elems.argtypes = [i64, i64, ci, ci, ctypes.POINTER(i64)]
+    lib.demo_encode.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, cf, ci, ci, vp]
+    lib.demo_decode.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, ci, cf, cf, ci, ci, vp]
+    lib.demo_step.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, cf, cf, cf, ci, ci, vp]
+    lib.demo_set_timing.argtypes = [vp, ci]
+    lib.demo_last_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(cf)]
+    lib.demo_set_variant.argtypes = [vp, ci]
+    lib.demo_strerror.argtypes = [ci]
+    lib.demo_strerror.restype = ctypes.c_char_p
+    lib.demo_last_hip_error.argtypes = [vp]
+    lib.demo_last_hip_error.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("demo_strerror", "demo_last_hip_error"):
+            getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def demo_strerror(status: int) -> str:
+    return load_library().demo_strerror(status).decode()
+
+
+def demo_payload_elems(rows: int, cols: int, s: int, k: int) -> int:
+    out = ctypes.c_int64(0)
+    rc = load_library().demo_payload_elems(rows, cols, s, k, ctypes.byref(out))
+    if rc != DEMO_OK:
+        raise DemoError(rc, demo_strerror(rc))
+    return out.value
+
+
+@dataclass
+class TensorArgs:
+    """Device buffers of one tensor (any of grad / mom / param may be None)."""
+    grad: Optional[torch.Tensor]
+    mom: Optional[torch.Tensor]
+    param: Optional[torch.Tensor]
+    idx: torch.Tensor          # int32 [W, nchunks, k] (or [nchunks, k])
+    val: torch.Tensor          # float32, same shape
+    rows: int = 0
+    cols: int = 0
+
+    def __post_init__(self):
+        ref = next(t for t in (self.mom, self.param, self.grad) if t is not None)
+        if self.rows == 0:
+            self.rows = ref.shape[0]
+            self.cols = ref.shape[1] if ref.dim() == 2 else 0
+
+
+def _dtype_code(t: Optional[torch.Tensor]) -> int:
+    if t is None or t.dtype == torch.float32:
+        return DEMO_F32
+    if t.dtype == torch.bfloat16:
+        return DEMO_BF16
+    return 99   # rejected by the library as unsupported
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to libdemo must be contiguous")
+    return t.data_ptr()
+
+
+def marshal(tensors: Sequence[TensorArgs]):
+    arr = (DemoTensor * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i].grad, arr[i].mom, arr[i].param = _ptr(t.grad), _ptr(t.mom), _ptr(t.param)
+        arr[i].idx, arr[i].val = _ptr(t.idx), _ptr(t.val)
+        arr[i].rows, arr[i].cols = t.rows, t.cols
+        arr[i].grad_dtype, arr[i].param_dtype = _dtype_code(t.grad), _dtype_code(t.param)
+    return arr
+
+
+class TensorList:
+    """A tensor list marshalled once (the ctypes array plus the tensors it points
+    into, kept alive).  Pass it instead of a sequence to skip per-call marshalling."""
+
+    def __init__(self, tensors: Sequence[TensorArgs]):
+        self.items = list(tensors)
+        self.arr = marshal(self.items)
+        self.n = len(self.items)
+
+
+def _as_list(tensors) -> TensorList:
+    return tensors if isinstance(tensors, TensorList) else TensorList(tensors)
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+class Context:
+    """Owns a demo_ctx.  Methods carry the names of the C entry points."""
+
+    def __init__(self):
+        self._lib = load_library()
+        h = ctypes.c_void_p()
+        self._check(self._lib.demo_create(ctypes.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.demo_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != DEMO_OK:
+            text = demo_strerror(rc)
+            if rc == DEMO_ERR_HIP and getattr(self, "_h", None):
+                text += ": " + self._lib.demo_last_hip_error(self._h).decode()
+            raise DemoError(rc, text)
+
+    def demo_encode(self, tensors: Sequence[TensorArgs], beta: float, s: int, k: int, stream=None):
+        tl = _as_list(tensors)
+        self._check(self._lib.demo_encode(self._h, tl.arr, tl.n, beta, s, k, _stream_ptr(stream)))
+
+    def demo_decode(self, tensors: Sequence[TensorArgs], W: int, lr: float, weight_decay: float, s: int, k: int,
+                    stream=None):
+        tl = _as_list(tensors)
+        self._check(self._lib.demo_decode(self._h, tl.arr, tl.n, W, lr, weight_decay, s, k, _stream_ptr(stream)))
+
+    def demo_step(self, tensors: Sequence[TensorArgs], beta: float, lr: float, weight_decay: float, s: int, k: int,
+                  stream=None):
+        tl = _as_list(tensors)
+        self._check(self._lib.demo_step(self._h, tl.arr, tl.n, beta, lr, weight_decay, s, k, _stream_ptr(stream)))
+
+    def demo_set_timing(self, enabled: bool):
+        self._check(self._lib.demo_set_timing(self._h, int(enabled)))
+
+    def demo_set_variant(self, variant: int):
+        self._check(self._lib.demo_set_variant(self._h, variant))
+
+    def demo_last_kernel_ms(self, which: int) -> float:
+        ms = ctypes.c_float(0)
+        self._check(self._lib.demo_last_kernel_ms(self._h, which, ctypes.byref(ms)))
+        return ms.value

@@ -1,0 +1,403 @@
+// Host side of the C ABI declared in include/demo.h: argument validation,
+// context (DCT basis tables, cached device descriptor tables), dispatch.
+#include "demo.h"
+#include "demo_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+static_assert(DEMO_MAX_K == DEMO_MAXK_INTERNAL, "public and internal k limits must agree");
+static_assert(sizeof(demo_tensor) == 64, "demo_tensor layout is part of the ABI");
+
+namespace {
+
+using demo::TableView;
+using demo::TensorDev;
+
+struct BasisTable {
+  int s = 0;
+  float* dev = nullptr;
+};
+
+// One cached descriptor upload: the host bytes it was built from and the device copy.
+struct TableCache {
+  std::vector<char> key;      // raw demo_tensor bytes + s
+  void* dev = nullptr;        // [TensorDev x n2][int32 x (n2+1)] [TensorDev x n1][int32 x (n1+1)]
+  size_t dev_bytes = 0;
+  TableView tv2{}, tv1{};
+  uint64_t last_use = 0;
+};
+
+constexpr int kMaxCachedTables = 8;
+constexpr int kNumTimers = 4;
+
+}  // namespace
+
+struct demo_ctx {
+  int device = -1;            // bound at first GPU use
+  int num_cus = 0;
+  std::vector<BasisTable> bases;
+  std::vector<TableCache> tables;
+  uint64_t use_counter = 0;
+  bool timing = false;
+  hipEvent_t ev[kNumTimers][2] = {};
+  bool ev_valid[kNumTimers] = {};
+  bool ev_created = false;
+  hipError_t last_hip = hipSuccess;
+  int variant = 1;            // 0 = generic kernels only
+};
+
+namespace {
+
+int fail_hip(demo_ctx* ctx, hipError_t e) {
+  ctx->last_hip = e;
+  return DEMO_ERR_HIP;
+}
+
+bool s_supported(int s) { return s == 32 || s == 64 || s == 128; }
+
+// Shape / s / k checks shared by every entry point.  Order of checks is part of
+// the documented behaviour: unsupported s first, then k < 1, then shape, then
+// k against the chunk size, then the k limit.
+int check_shape(int64_t rows, int64_t cols, int s, int k) {
+  if (!s_supported(s)) return DEMO_ERR_UNSUPPORTED;
+  if (k < 1) return DEMO_ERR_ARG;
+  if (rows <= 0 || cols < 0) return DEMO_ERR_SHAPE;
+  if (rows % s != 0 || cols % s != 0) return DEMO_ERR_SHAPE;
+  const int64_t M = cols == 0 ? (int64_t)s : (int64_t)s * s;
+  if (k > M) return DEMO_ERR_ARG;
+  if (k > DEMO_MAX_K) return DEMO_ERR_UNSUPPORTED;
+  return DEMO_OK;
+}
+
+enum Need { NEED_ENCODE = 1, NEED_DECODE = 2 };
+
+int validate(const demo_ctx* ctx, const demo_tensor* t, int n, int s, int k, int need) {
+  if (ctx == nullptr || n < 0 || (n > 0 && t == nullptr)) return DEMO_ERR_ARG;
+  if (!s_supported(s)) return DEMO_ERR_UNSUPPORTED;
+  if (k < 1) return DEMO_ERR_ARG;
+  int64_t total2 = 0, total1 = 0;
+  for (int i = 0; i < n; ++i) {
+    const int rc = check_shape(t[i].rows, t[i].cols, s, k);
+    if (rc != DEMO_OK) return rc;
+    if ((need & NEED_ENCODE) && (t[i].grad_dtype != DEMO_F32 && t[i].grad_dtype != DEMO_BF16))
+      return DEMO_ERR_UNSUPPORTED;
+    if ((need & NEED_DECODE) && (t[i].param_dtype != DEMO_F32 && t[i].param_dtype != DEMO_BF16))
+      return DEMO_ERR_UNSUPPORTED;
+    if (t[i].idx == nullptr || t[i].val == nullptr) return DEMO_ERR_ARG;
+    if ((need & NEED_ENCODE) && (t[i].grad == nullptr || t[i].mom == nullptr)) return DEMO_ERR_ARG;
+    if ((need & NEED_DECODE) && t[i].param == nullptr) return DEMO_ERR_ARG;
+    if (t[i].cols == 0) total1 += t[i].rows / s;
+    else total2 += (t[i].rows / s) * (t[i].cols / s);
+    if (total1 > INT32_MAX || total2 > INT32_MAX) return DEMO_ERR_UNSUPPORTED;
+  }
+  return DEMO_OK;
+}
+
+int bind_device(demo_ctx* ctx) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  if (ctx->device < 0) {
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    ctx->device = dev;
+    ctx->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  } else if (ctx->device != dev) {
+    return DEMO_ERR_ARG;  // a context stays on the device it first ran on
+  }
+  return DEMO_OK;
+}
+
+// Orthonormal DCT-II matrix P[u][n] = c_u cos(pi (2n+1) u / (2s)), evaluated in
+// double precision and rounded once to float32 (Sec. 2.1 "Blockwise Linear
+// Projection": the matrices are precomputed once and shared by all tensors).
+int get_basis(demo_ctx* ctx, int s, const float** out) {
+  for (const BasisTable& b : ctx->bases)
+    if (b.s == s) { *out = b.dev; return DEMO_OK; }
+  std::vector<float> host((size_t)s * s);
+  const double pi = 3.14159265358979323846;
+  for (int u = 0; u < s; ++u) {
+    const double cu = u == 0 ? std::sqrt(1.0 / s) : std::sqrt(2.0 / s);
+    for (int n = 0; n < s; ++n) host[(size_t)u * s + n] = (float)(cu * std::cos(pi * (2.0 * n + 1.0) * u / (2.0 * s)));
+  }
+  BasisTable b;
+  b.s = s;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&b.dev), host.size() * sizeof(float));
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  e = hipMemcpy(b.dev, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (e != hipSuccess) { (void)hipFree(b.dev); return fail_hip(ctx, e); }
+  ctx->bases.push_back(b);
+  *out = b.dev;
+  return DEMO_OK;
+}
+
+// Find or build the device descriptor tables of a tensor list.
+int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** out) {
+  const size_t raw = sizeof(demo_tensor) * (size_t)n;
+  std::vector<char> key(raw + sizeof(int));
+  std::memcpy(key.data(), t, raw);
+  std::memcpy(key.data() + raw, &s, sizeof(int));
+  for (TableCache& tc : ctx->tables) {
+    if (tc.key.size() == key.size() && std::memcmp(tc.key.data(), key.data(), key.size()) == 0) {
+      tc.last_use = ++ctx->use_counter;
+      *out = &tc;
+      return DEMO_OK;
+    }
+  }
+  std::vector<TensorDev> d2, d1;
+  std::vector<int32_t> p2(1, 0), p1(1, 0);
+  for (int i = 0; i < n; ++i) {
+    TensorDev d{};
+    d.grad = t[i].grad;
+    d.mom = t[i].mom;
+    d.param = t[i].param;
+    d.idx = t[i].idx;
+    d.val = t[i].val;
+    d.rows = t[i].rows;
+    d.cols = t[i].cols;
+    d.grad_bf16 = t[i].grad_dtype == DEMO_BF16;
+    d.param_bf16 = t[i].param_dtype == DEMO_BF16;
+    if (t[i].cols == 0) {
+      d.cchunks = 1;
+      d.nchunks = (int32_t)(t[i].rows / s);
+      d1.push_back(d);
+      p1.push_back(p1.back() + d.nchunks);
+    } else {
+      d.cchunks = (int32_t)(t[i].cols / s);
+      d.nchunks = (int32_t)((t[i].rows / s) * (t[i].cols / s));
+      d2.push_back(d);
+      p2.push_back(p2.back() + d.nchunks);
+    }
+  }
+  auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+  const size_t o_d2 = 0;
+  const size_t o_p2 = align16(o_d2 + d2.size() * sizeof(TensorDev));
+  const size_t o_d1 = align16(o_p2 + p2.size() * sizeof(int32_t));
+  const size_t o_p1 = align16(o_d1 + d1.size() * sizeof(TensorDev));
+  const size_t total = align16(o_p1 + p1.size() * sizeof(int32_t));
+  std::vector<char> host(total, 0);
+  if (!d2.empty()) std::memcpy(host.data() + o_d2, d2.data(), d2.size() * sizeof(TensorDev));
+  std::memcpy(host.data() + o_p2, p2.data(), p2.size() * sizeof(int32_t));
+  if (!d1.empty()) std::memcpy(host.data() + o_d1, d1.data(), d1.size() * sizeof(TensorDev));
+  std::memcpy(host.data() + o_p1, p1.data(), p1.size() * sizeof(int32_t));
+
+  TableCache* slot = nullptr;
+  if ((int)ctx->tables.size() < kMaxCachedTables) {
+    ctx->tables.emplace_back();
+    slot = &ctx->tables.back();
+  } else {
+    slot = &ctx->tables[0];
+    for (TableCache& tc : ctx->tables)
+      if (tc.last_use < slot->last_use) slot = &tc;
+    // the evicted table may still be read by kernels in flight
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail_hip(ctx, e);
+  }
+  if (slot->dev_bytes < total) {
+    if (slot->dev) (void)hipFree(slot->dev);
+    slot->dev = nullptr;
+    slot->dev_bytes = 0;
+    hipError_t e = hipMalloc(&slot->dev, total);
+    if (e != hipSuccess) { slot->key.clear(); return fail_hip(ctx, e); }
+    slot->dev_bytes = total;
+  }
+  // blocking copy: the table is complete before any launch on any stream reads it
+  hipError_t e = hipMemcpy(slot->dev, host.data(), total, hipMemcpyHostToDevice);
+  if (e != hipSuccess) { slot->key.clear(); return fail_hip(ctx, e); }
+  char* base = static_cast<char*>(slot->dev);
+  slot->tv2.descs = reinterpret_cast<const TensorDev*>(base + o_d2);
+  slot->tv2.prefix = reinterpret_cast<const int32_t*>(base + o_p2);
+  slot->tv2.n = (int32_t)d2.size();
+  slot->tv2.total_chunks = p2.back();
+  slot->tv1.descs = reinterpret_cast<const TensorDev*>(base + o_d1);
+  slot->tv1.prefix = reinterpret_cast<const int32_t*>(base + o_p1);
+  slot->tv1.n = (int32_t)d1.size();
+  slot->tv1.total_chunks = p1.back();
+  slot->key.swap(key);
+  slot->last_use = ++ctx->use_counter;
+  *out = slot;
+  return DEMO_OK;
+}
+
+int timer_begin(demo_ctx* ctx, int which, hipStream_t st) {
+  if (!ctx->timing) return DEMO_OK;
+  if (!ctx->ev_created) {
+    for (int i = 0; i < kNumTimers; ++i)
+      for (int j = 0; j < 2; ++j) {
+        hipError_t e = hipEventCreate(&ctx->ev[i][j]);
+        if (e != hipSuccess) return fail_hip(ctx, e);
+      }
+    ctx->ev_created = true;
+  }
+  hipError_t e = hipEventRecord(ctx->ev[which][0], st);
+  return e == hipSuccess ? DEMO_OK : fail_hip(ctx, e);
+}
+
+int timer_end(demo_ctx* ctx, int which, hipStream_t st) {
+  if (!ctx->timing) return DEMO_OK;
+  hipError_t e = hipEventRecord(ctx->ev[which][1], st);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  ctx->ev_valid[which] = true;
+  return DEMO_OK;
+}
+
+int run_encode(demo_ctx* ctx, TableCache* tc, const float* basis, float beta, int s, int k, hipStream_t st) {
+  demo::EncodeArgs a{beta, k};
+  int rc;
+  if (tc->tv2.total_chunks > 0) {
+    if ((rc = timer_begin(ctx, 0, st)) != DEMO_OK) return rc;
+    hipError_t e = demo::launch_encode2d(tc->tv2, basis, s, a, ctx->num_cus, ctx->variant, st);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    if ((rc = timer_end(ctx, 0, st)) != DEMO_OK) return rc;
+  }
+  if (tc->tv1.total_chunks > 0) {
+    if ((rc = timer_begin(ctx, 1, st)) != DEMO_OK) return rc;
+    hipError_t e = demo::launch_encode1d(tc->tv1, basis, s, a, st);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    if ((rc = timer_end(ctx, 1, st)) != DEMO_OK) return rc;
+  }
+  return DEMO_OK;
+}
+
+int run_decode(demo_ctx* ctx, TableCache* tc, const float* basis, int W, float lr, float wd, int s, int k,
+               hipStream_t st) {
+  demo::DecodeArgs a{lr, wd, k, W};
+  int rc;
+  if (tc->tv2.total_chunks > 0) {
+    if ((rc = timer_begin(ctx, 2, st)) != DEMO_OK) return rc;
+    hipError_t e = demo::launch_decode2d(tc->tv2, basis, s, a, ctx->num_cus, ctx->variant, st);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    if ((rc = timer_end(ctx, 2, st)) != DEMO_OK) return rc;
+  }
+  if (tc->tv1.total_chunks > 0) {
+    if ((rc = timer_begin(ctx, 3, st)) != DEMO_OK) return rc;
+    hipError_t e = demo::launch_decode1d(tc->tv1, basis, s, a, st);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    if ((rc = timer_end(ctx, 3, st)) != DEMO_OK) return rc;
+  }
+  return DEMO_OK;
+}
+
+int prepare(demo_ctx* ctx, const demo_tensor* t, int n, int s, const float** basis, TableCache** tc) {
+  int rc = bind_device(ctx);
+  if (rc != DEMO_OK) return rc;
+  if ((rc = get_basis(ctx, s, basis)) != DEMO_OK) return rc;
+  return get_tables(ctx, t, n, s, tc);
+}
+
+}  // namespace
+
+extern "C" {
+
+int demo_create(demo_ctx** out) {
+  if (out == nullptr) return DEMO_ERR_ARG;
+  demo_ctx* c = new (std::nothrow) demo_ctx();
+  if (c == nullptr) return DEMO_ERR_NOMEM;
+  *out = c;
+  return DEMO_OK;
+}
+
+int demo_destroy(demo_ctx* ctx) {
+  if (ctx == nullptr) return DEMO_ERR_ARG;
+  if (ctx->device >= 0) {
+    (void)hipDeviceSynchronize();
+    for (BasisTable& b : ctx->bases) (void)hipFree(b.dev);
+    for (TableCache& tc : ctx->tables)
+      if (tc.dev) (void)hipFree(tc.dev);
+    if (ctx->ev_created)
+      for (int i = 0; i < kNumTimers; ++i)
+        for (int j = 0; j < 2; ++j) (void)hipEventDestroy(ctx->ev[i][j]);
+  }
+  delete ctx;
+  return DEMO_OK;
+}
+
+int demo_payload_elems(int64_t rows, int64_t cols, int s, int k, int64_t* out) {
+  if (out == nullptr) return DEMO_ERR_ARG;
+  const int rc = check_shape(rows, cols, s, k);
+  if (rc != DEMO_OK) return rc;
+  const int64_t nchunks = cols == 0 ? rows / s : (rows / s) * (cols / s);
+  *out = nchunks * k;
+  return DEMO_OK;
+}
+
+int demo_encode(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k, void* hip_stream) {
+  int rc = validate(ctx, tensors, n, s, k, NEED_ENCODE);
+  if (rc != DEMO_OK || n == 0) return rc;
+  const float* basis = nullptr;
+  TableCache* tc = nullptr;
+  if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
+  return run_encode(ctx, tc, basis, beta, s, k, static_cast<hipStream_t>(hip_stream));
+}
+
+int demo_decode(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, float lr, float weight_decay, int s,
+                int k, void* hip_stream) {
+  int rc = validate(ctx, tensors, n, s, k, NEED_DECODE);
+  if (rc != DEMO_OK) return rc;
+  if (W < 1) return DEMO_ERR_ARG;
+  if (n == 0) return DEMO_OK;
+  const float* basis = nullptr;
+  TableCache* tc = nullptr;
+  if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
+  return run_decode(ctx, tc, basis, W, lr, weight_decay, s, k, static_cast<hipStream_t>(hip_stream));
+}
+
+int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, float lr, float weight_decay, int s,
+              int k, void* hip_stream) {
+  int rc = validate(ctx, tensors, n, s, k, NEED_ENCODE | NEED_DECODE);
+  if (rc != DEMO_OK || n == 0) return rc;
+  const float* basis = nullptr;
+  TableCache* tc = nullptr;
+  if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if ((rc = run_encode(ctx, tc, basis, beta, s, k, st)) != DEMO_OK) return rc;
+  return run_decode(ctx, tc, basis, 1, lr, weight_decay, s, k, st);
+}
+
+int demo_set_timing(demo_ctx* ctx, int enabled) {
+  if (ctx == nullptr) return DEMO_ERR_ARG;
+  ctx->timing = enabled != 0;
+  if (!ctx->timing)
+    for (int i = 0; i < kNumTimers; ++i) ctx->ev_valid[i] = false;
+  return DEMO_OK;
+}
+
+int demo_last_kernel_ms(demo_ctx* ctx, int which, float* ms) {
+  if (ctx == nullptr || ms == nullptr || which < 0 || which >= kNumTimers) return DEMO_ERR_ARG;
+  if (!ctx->ev_valid[which]) return DEMO_ERR_ARG;
+  hipError_t e = hipEventSynchronize(ctx->ev[which][1]);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  e = hipEventElapsedTime(ms, ctx->ev[which][0], ctx->ev[which][1]);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  return DEMO_OK;
+}
+
+int demo_set_variant(demo_ctx* ctx, int variant) {
+  if (ctx == nullptr || variant < 0 || variant > 1) return DEMO_ERR_ARG;
+  ctx->variant = variant;
+  return DEMO_OK;
+}
+
+const char* demo_strerror(int status) {
+  switch (status) {
+    case DEMO_OK: return "ok";
+    case DEMO_ERR_ARG: return "invalid argument (null pointer, n < 0, W < 1, k < 1 or k > chunk elements)";
+    case DEMO_ERR_SHAPE: return "tensor shape is not a positive multiple of the chunk size";
+    case DEMO_ERR_UNSUPPORTED: return "unsupported chunk size, dtype or k above DEMO_MAX_K";
+    case DEMO_ERR_HIP: return "HIP runtime error";
+    case DEMO_ERR_NOMEM: return "out of memory";
+  }
+  return "unknown status";
+}
+
+const char* demo_last_hip_error(demo_ctx* ctx) {
+  if (ctx == nullptr) return "no context";
+  return hipGetErrorString(ctx->last_hip);
+}
+
+}  // extern "C"

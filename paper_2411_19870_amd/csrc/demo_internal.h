@@ -1,0 +1,59 @@
+// Internal interface between the C-ABI host layer and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// Largest sparsity budget per chunk the kernels accept (equals DEMO_MAX_K of the public header).
+#define DEMO_MAXK_INTERNAL 256
+
+namespace demo {
+
+// Device-side tensor descriptor (one per tensor of a call; order-2 and order-1
+// tensors are kept in two separate tables).
+struct TensorDev {
+  const void* grad;
+  float* mom;
+  void* param;
+  int32_t* idx;
+  float* val;
+  int64_t rows;
+  int64_t cols;       // 0 for order-1
+  int32_t cchunks;    // chunks along dimension 1 (order-2 only)
+  int32_t nchunks;    // chunks of this tensor
+  int32_t grad_bf16;
+  int32_t param_bf16;
+};
+
+// A table on the device: `n` descriptors followed by n+1 int32 chunk prefix sums.
+struct TableView {
+  const TensorDev* descs;
+  const int32_t* prefix;   // prefix[t] = first global chunk id of tensor t; prefix[n] = total
+  int32_t n;
+  int32_t total_chunks;
+};
+
+struct EncodeArgs {
+  float beta;
+  int k;
+};
+
+struct DecodeArgs {
+  float lr;
+  float weight_decay;
+  int k;
+  int W;
+};
+
+// Launch wrappers (demo_kernels.hip).  `basis` is the s x s orthonormal DCT-II
+// matrix P, row-major float32, in device memory.  `variant` selects the kernel
+// family: 0 = generic LDS-staged kernels, 1 = fastest available for this s.
+hipError_t launch_encode2d(const TableView& tv, const float* basis, int s, const EncodeArgs& a,
+                           int num_cus, int variant, hipStream_t stream);
+hipError_t launch_encode1d(const TableView& tv, const float* basis, int s, const EncodeArgs& a,
+                           hipStream_t stream);
+hipError_t launch_decode2d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
+                           int num_cus, int variant, hipStream_t stream);
+hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
+                           hipStream_t stream);
+
+}  // namespace demo

@@ -1,0 +1,656 @@
+// HIP kernels (gfx950) for DeMo's per-step compression path.
+//
+// encode (worker side of Algorithm 1 / appendix CompressChunks), per chunk:
+//     m <- beta*m + g ; Q = P B P^T ; keep the k largest |Q| ; m <- m - P^T Q^ P
+// decode (server side / appendix Decompress&Aggregate + update line), per chunk:
+//     S = sum_w payload_w ; R = P^T S P ; x <- x - lr*(sgn(R) + wd*x)
+//
+// This file holds the generic kernel family: one 256-thread workgroup per s x s
+// chunk (s in {32,64,128}), tiles staged in LDS, all contractions on the fp32
+// matrix cores (v_mfma_f32_16x16x4_f32), and one wavefront per order-1 chunk.
+#include "demo_internal.h"
+
+namespace demo {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int find_tensor(const int32_t* __restrict__ prefix, int n, int chunk) {
+  int lo = 0, hi = n;  // invariant: prefix[lo] <= chunk < prefix[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (prefix[mid] <= chunk) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t b = __float_as_uint(f);
+  if ((b & 0x7fffffffu) > 0x7f800000u) return (b >> 16) | 0x40u;  // NaN stays NaN
+  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ float4 load4(const void* __restrict__ base, int64_t off, int is_bf16) {
+  if (is_bf16) {
+    uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + off);
+    return make_float4(bf16_to_f32(r.x & 0xffffu), bf16_to_f32(r.x >> 16), bf16_to_f32(r.y & 0xffffu),
+                       bf16_to_f32(r.y >> 16));
+  }
+  return *reinterpret_cast<const float4*>(static_cast<const float*>(base) + off);
+}
+
+__device__ __forceinline__ void store4(void* __restrict__ base, int64_t off, int is_bf16, float4 v) {
+  if (is_bf16) {
+    uint2 r;
+    r.x = f32_to_bf16_rne(v.x) | (f32_to_bf16_rne(v.y) << 16);
+    r.y = f32_to_bf16_rne(v.z) | (f32_to_bf16_rne(v.w) << 16);
+    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + off) = r;
+  } else {
+    *reinterpret_cast<float4*>(static_cast<float*>(base) + off) = v;
+  }
+}
+
+__device__ __forceinline__ float sgnf(float r) { return (r > 0.0f ? 1.0f : 0.0f) - (r < 0.0f ? 1.0f : 0.0f); }
+
+// x' = x - lr*(sgn + wd*x) with two float32 fused multiply-adds (update line of Algorithm 1).
+__device__ __forceinline__ float sign_update(float x, float sg, float lr, float wd) {
+  float t = __fmaf_rn(wd, x, sg);
+  return __fmaf_rn(-lr, t, x);
+}
+
+// ---------------------------------------------------------------------------
+// Geometry of the generic order-2 kernels
+// ---------------------------------------------------------------------------
+template <int S>
+struct Geo {
+  static constexpr int NT = 256;                     // threads per workgroup (4 wavefronts)
+  static constexpr int LD = S + 4;                   // LDS row stride in floats
+  static constexpr int F4_PER_ROW = S / 4;
+  static constexpr int ROWS_PER_PASS = NT / F4_PER_ROW;
+  static constexpr int PASSES = S / ROWS_PER_PASS;   // float4 per thread
+  static constexpr int TN = S / 16;                  // 16x16 tiles per dimension
+  static constexpr int TPW = TN * TN / 4;            // tiles per wavefront
+  static constexpr int CW = (TN >= 4) ? TN / 4 : 1;  // column tiles per wavefront (column strips when S >= 64)
+  static constexpr bool INPLACE = (S >= 64);         // first product may overwrite its data operand
+  static constexpr int M = S * S;
+  static constexpr int TILE_FLOATS = S * LD;
+  // LDS: basis, data tile, (second tile when not in place), selection scratch
+  static constexpr int LDS_FLOATS = TILE_FLOATS * (INPLACE ? 2 : 3) + 3 * DEMO_MAXK_INTERNAL + 32;
+};
+
+// tile i of wavefront w -> (mt, nt)
+template <int S>
+__device__ __forceinline__ void tile_of(int w, int i, int& mt, int& nt) {
+  using G = Geo<S>;
+  if (G::TN >= 4) {
+    nt = w * G::CW + (i % G::CW);
+    mt = i / G::CW;
+  } else {
+    mt = w >> 1;
+    nt = w & 1;
+  }
+}
+
+// acc[i] (+)= A(rows of tile) * B(cols of tile), K = S, operands read from LDS.
+//   a_at(m, kk) and b_at(kk, n) give the LDS float offsets of A[m][kk] and B[kk][n].
+template <int S, class FA, class FB>
+__device__ __forceinline__ void gemm_lds(f32x4* acc, int wave, int lane, const float* lds, FA a_at, FB b_at) {
+  using G = Geo<S>;
+  const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < G::TPW; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int ks = 0; ks < S / 4; ++ks) {
+    const int kk = 4 * ks + lq;
+#pragma unroll
+    for (int i = 0; i < G::TPW; ++i) {
+      int mt, nt;
+      tile_of<S>(wave, i, mt, nt);
+      float a = lds[a_at(16 * mt + l16, kk)];
+      float b = lds[b_at(kk, 16 * nt + l16)];
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+    }
+  }
+}
+
+// Write a wavefront's accumulators (C layout: row 16mt + 4*(lane/16) + r, col 16nt + lane%16)
+// to an LDS tile with row stride LD.
+template <int S>
+__device__ __forceinline__ void store_acc(const f32x4* acc, int wave, int lane, float* tile) {
+  using G = Geo<S>;
+  const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < G::TPW; ++i) {
+    int mt, nt;
+    tile_of<S>(wave, i, mt, nt);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) tile[(16 * mt + 4 * lq + r) * G::LD + 16 * nt + l16] = acc[i][r];
+  }
+}
+
+// Workgroup-wide sum of a per-wavefront count (4 wavefronts).  `slot` must
+// alternate between consecutive calls; one barrier per call.
+__device__ __forceinline__ int block_sum4(int wave_count, int wave, int lane, int* s_cnt, int slot) {
+  if (lane == 0) s_cnt[slot * 4 + wave] = wave_count;
+  __syncthreads();
+  return s_cnt[slot * 4 + 0] + s_cnt[slot * 4 + 1] + s_cnt[slot * 4 + 2] + s_cnt[slot * 4 + 3];
+}
+
+// ---------------------------------------------------------------------------
+// encode, order-2 tensors, generic
+// ---------------------------------------------------------------------------
+template <int S>
+__global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const float* __restrict__ basis,
+                                                        EncodeArgs args) {
+  using G = Geo<S>;
+  extern __shared__ float lds[];
+  float* sP = lds;                                     // basis P[u][n], stride LD
+  float* sX = sP + G::TILE_FLOATS;                     // data tile / first product / reconstruction
+  float* sT = G::INPLACE ? sX : sX + G::TILE_FLOATS;   // first product when not in place
+  float* scratch = sX + G::TILE_FLOATS * (G::INPLACE ? 1 : 2);
+  uint32_t* sel_mag = reinterpret_cast<uint32_t*>(scratch);            // [MAXK]
+  int32_t* sel_idx = reinterpret_cast<int32_t*>(scratch + DEMO_MAXK_INTERNAL);
+  float* sel_val = scratch + 2 * DEMO_MAXK_INTERNAL;
+  int* s_cnt = reinterpret_cast<int*>(scratch + 3 * DEMO_MAXK_INTERNAL);  // [8] counters + [1] list cursor
+  int* s_cursor = s_cnt + 8;
+  // second list (rank-sorted) overlays the head of the first product tile after it is dead
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int k = args.k;
+  const int kpad = (k + 3) & ~3;
+
+  for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
+
+  for (int chunk = blockIdx.x; chunk < tv.total_chunks; chunk += gridDim.x) {
+    const int t = find_tensor(tv.prefix, tv.n, chunk);
+    const TensorDev d = tv.descs[t];
+    const int c = chunk - tv.prefix[t];
+    const int k0 = c / d.cchunks, k1 = c - k0 * d.cchunks;
+    const int64_t base = (int64_t)k0 * S * d.cols + (int64_t)k1 * S;
+
+    // ---- load, momentum update, stage -------------------------------------------------
+    float4 mid[G::PASSES];
+    const int lrow = tid / G::F4_PER_ROW, lcol = (tid % G::F4_PER_ROW) * 4;
+    __syncthreads();  // previous chunk's readers of sX are done
+#pragma unroll
+    for (int p = 0; p < G::PASSES; ++p) {
+      const int row = p * G::ROWS_PER_PASS + lrow;
+      const int64_t off = base + (int64_t)row * d.cols + lcol;
+      float4 g = load4(d.grad, off, d.grad_bf16);
+      float4 m = *reinterpret_cast<const float4*>(d.mom + off);
+      float4 v;
+      v.x = __fmaf_rn(args.beta, m.x, g.x);
+      v.y = __fmaf_rn(args.beta, m.y, g.y);
+      v.z = __fmaf_rn(args.beta, m.z, g.z);
+      v.w = __fmaf_rn(args.beta, m.w, g.w);
+      mid[p] = v;
+      *reinterpret_cast<float4*>(&sX[row * G::LD + lcol]) = v;
+    }
+    if (tid == 0) *s_cursor = 0;
+    __syncthreads();
+
+    // ---- T = P * X -----------------------------------------------------------------------
+    f32x4 acc[G::TPW];
+    gemm_lds<S>(acc, wave, lane, lds,
+                [&](int m, int kk) { return m * G::LD + kk; },                              // P[u][i]
+                [&](int kk, int n) { return G::TILE_FLOATS + kk * G::LD + n; });           // X[i][j]
+    if (!G::INPLACE) {
+      store_acc<S>(acc, wave, lane, sT);
+    } else {
+      // every read of this wavefront's column strip is its own: overwrite in place
+      store_acc<S>(acc, wave, lane, sX);
+    }
+    __syncthreads();
+
+    // ---- Q = T * P^T ---------------------------------------------------------------------
+    const int t_off = (int)(sT - lds);
+    gemm_lds<S>(acc, wave, lane, lds,
+                [&](int m, int kk) { return t_off + m * G::LD + kk; },                     // T[u][j]
+                [&](int kk, int n) { return n * G::LD + kk; });                             // P[v][j]
+
+    // ---- exact top-k over the chunk (magnitude bits are order preserving as unsigned) ------
+    uint32_t mag[G::TPW * 4];
+#pragma unroll
+    for (int i = 0; i < G::TPW; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) mag[i * 4 + r] = __float_as_uint(acc[i][r]) & 0x7fffffffu;
+
+    int slot = 0;
+    uint32_t thr = 0;  // becomes the k-th largest magnitude
+    for (int bit = 30; bit >= 0; --bit) {
+      const uint32_t cand = thr | (1u << bit);
+      int cw = 0;
+#pragma unroll
+      for (int e = 0; e < G::TPW * 4; ++e) cw += __popcll(__ballot(mag[e] >= cand));
+      const int tot = block_sum4(cw, wave, lane, s_cnt, slot);
+      slot ^= 1;
+      if (tot >= k) thr = cand;
+    }
+    int cw_gt = 0, cw_ge = 0;
+#pragma unroll
+    for (int e = 0; e < G::TPW * 4; ++e) {
+      cw_gt += __popcll(__ballot(mag[e] > thr));
+      cw_ge += __popcll(__ballot(mag[e] >= thr));
+    }
+    const int n_gt = block_sum4(cw_gt, wave, lane, s_cnt, slot);
+    slot ^= 1;
+    const int n_ge = block_sum4(cw_ge, wave, lane, s_cnt, slot);
+    slot ^= 1;
+    const int need = k - n_gt;          // ties to take, >= 1
+    uint32_t tie_last = 0xffffffffu;    // largest flat index among the ties taken
+    if (n_ge - n_gt != need) {
+      // more equal magnitudes than places: take the `need` lowest flat indices
+      uint32_t lo = 0;
+      for (int bit = 31 - __builtin_clz(G::M - 1); bit >= 0; --bit) {
+        const uint32_t cand = lo | (1u << bit);
+        int cw = 0;
+#pragma unroll
+        for (int i = 0; i < G::TPW; ++i) {
+          int mt, nt;
+          tile_of<S>(wave, i, mt, nt);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+            cw += __popcll(__ballot(mag[i * 4 + r] == thr && flat < cand));
+          }
+        }
+        const int tot = block_sum4(cw, wave, lane, s_cnt, slot);
+        slot ^= 1;
+        if (tot < need) lo = cand;
+      }
+      tie_last = lo;
+    }
+    // gather the k selected coefficients (arrival order), then rank them
+#pragma unroll
+    for (int i = 0; i < G::TPW; ++i) {
+      int mt, nt;
+      tile_of<S>(wave, i, mt, nt);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+        const uint32_t mg = mag[i * 4 + r];
+        if (mg > thr || (mg == thr && flat <= tie_last)) {
+          const int pos = atomicAdd(s_cursor, 1);
+          if (pos < DEMO_MAXK_INTERNAL) {
+            sel_mag[pos] = mg;
+            sel_idx[pos] = (int32_t)flat;
+            sel_val[pos] = acc[i][r];
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // rank = number of selected entries that precede this one (magnitude desc, index asc)
+    int my_rank = -1, my_idx = 0;
+    float my_val = 0.f;
+    if (tid < k) {
+      const uint32_t mg = sel_mag[tid];
+      my_idx = sel_idx[tid];
+      my_val = sel_val[tid];
+      int rk = 0;
+      for (int j = 0; j < k; ++j) {
+        const uint32_t mj = sel_mag[j];
+        rk += (mj > mg || (mj == mg && sel_idx[j] < my_idx)) ? 1 : 0;
+      }
+      my_rank = rk;
+      const int64_t po = (int64_t)c * k + rk;
+      d.idx[po] = my_idx;
+      d.val[po] = my_val;
+    }
+    __syncthreads();
+    // sorted list for the reconstruction (deterministic summation order); padded to a multiple of 4
+    if (tid < k) {
+      sel_idx[my_rank] = my_idx;
+      sel_val[my_rank] = my_val;
+    } else if (tid < kpad) {
+      sel_idx[tid] = 0;
+      sel_val[tid] = 0.f;
+    }
+    __syncthreads();
+
+    // ---- R = P^T Q^ P = sum_t val_t * P[u_t][:]^T P[v_t][:]  (contraction length k) ----------
+#pragma unroll
+    for (int i = 0; i < G::TPW; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < kpad / 4; ++ks) {
+      const int tt = 4 * ks + lq;
+      const int fi = sel_idx[tt];
+      const float fv = sel_val[tt];
+      const int u = fi / S, v = fi - u * S;
+#pragma unroll
+      for (int i = 0; i < G::TPW; ++i) {
+        int mt, nt;
+        tile_of<S>(wave, i, mt, nt);
+        const float a = fv * sP[u * G::LD + 16 * mt + l16];
+        const float b = sP[v * G::LD + 16 * nt + l16];
+        acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+      }
+    }
+    store_acc<S>(acc, wave, lane, sX);   // sX (and sT) are dead since the barriers above
+    __syncthreads();
+
+    // ---- m <- m - R ----------------------------------------------------------------------
+#pragma unroll
+    for (int p = 0; p < G::PASSES; ++p) {
+      const int row = p * G::ROWS_PER_PASS + lrow;
+      const int64_t off = base + (int64_t)row * d.cols + lcol;
+      const float4 r = *reinterpret_cast<const float4*>(&sX[row * G::LD + lcol]);
+      float4 o;
+      o.x = mid[p].x - r.x;
+      o.y = mid[p].y - r.y;
+      o.z = mid[p].z - r.z;
+      o.w = mid[p].w - r.w;
+      *reinterpret_cast<float4*>(d.mom + off) = o;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// decode, order-2 tensors, generic
+// ---------------------------------------------------------------------------
+template <int S>
+__global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const float* __restrict__ basis,
+                                                        DecodeArgs args) {
+  using G = Geo<S>;
+  extern __shared__ float lds[];
+  float* sP = lds;
+  float* sX = sP + G::TILE_FLOATS;                     // coefficient sums / first product / signs
+  float* sT = G::INPLACE ? sX : sX + G::TILE_FLOATS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int k = args.k, W = args.W;
+
+  for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
+
+  for (int chunk = blockIdx.x; chunk < tv.total_chunks; chunk += gridDim.x) {
+    const int t = find_tensor(tv.prefix, tv.n, chunk);
+    const TensorDev d = tv.descs[t];
+    const int c = chunk - tv.prefix[t];
+    const int k0 = c / d.cchunks, k1 = c - k0 * d.cchunks;
+    const int64_t base = (int64_t)k0 * S * d.cols + (int64_t)k1 * S;
+    const int lrow = tid / G::F4_PER_ROW, lcol = (tid % G::F4_PER_ROW) * 4;
+
+    __syncthreads();
+    for (int e = tid; e < S * G::LD; e += G::NT) sX[e] = 0.f;
+    __syncthreads();
+
+    // ---- S[idx] += val, workers in order (one wavefront issues them in program order;
+    //      indices inside one worker's chunk are distinct) -----------------------------------
+    if (wave == 0) {
+      const int64_t wstride = (int64_t)d.nchunks * k;
+      if (k <= 64) {
+        constexpr int UW = 8;   // workers whose pairs are in flight together
+        const bool act = lane < k;
+        for (int w0 = 0; w0 < W; w0 += UW) {
+          int32_t fi[UW];
+          float fv[UW];
+#pragma unroll
+          for (int j = 0; j < UW; ++j) {
+            const bool ok = act && (w0 + j < W);
+            const int64_t po = (int64_t)(w0 + j) * wstride + (int64_t)c * k + lane;
+            fi[j] = ok ? d.idx[po] : -1;
+            fv[j] = ok ? d.val[po] : 0.f;
+          }
+#pragma unroll
+          for (int j = 0; j < UW; ++j) {
+            if (fi[j] >= 0 && fi[j] < G::M) {
+              const int u = fi[j] / S, v = fi[j] - u * S;
+              atomicAdd(&sX[u * G::LD + v], fv[j]);
+            }
+          }
+        }
+      } else {
+        for (int w = 0; w < W; ++w) {
+          for (int tt = lane; tt < k; tt += 64) {
+            const int64_t po = (int64_t)w * wstride + (int64_t)c * k + tt;
+            const int fi = d.idx[po];
+            const float fv = d.val[po];
+            if (fi >= 0 && fi < G::M) {
+              const int u = fi / S, v = fi - u * S;
+              atomicAdd(&sX[u * G::LD + v], fv);
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+
+    // ---- Y = P^T * S ------------------------------------------------------------------------
+    f32x4 acc[G::TPW];
+    gemm_lds<S>(acc, wave, lane, lds,
+                [&](int m, int kk) { return kk * G::LD + m; },                              // P[u][i]
+                [&](int kk, int n) { return G::TILE_FLOATS + kk * G::LD + n; });           // S[u][v]
+    store_acc<S>(acc, wave, lane, sT);
+    __syncthreads();
+    // ---- R = Y * P --------------------------------------------------------------------------
+    const int t_off = (int)(sT - lds);
+    gemm_lds<S>(acc, wave, lane, lds,
+                [&](int m, int kk) { return t_off + m * G::LD + kk; },                     // Y[i][v]
+                [&](int kk, int n) { return kk * G::LD + n; });                             // P[v][j]
+#pragma unroll
+    for (int i = 0; i < G::TPW; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][r] = sgnf(acc[i][r]);
+    __syncthreads();                       // all reads of Y are done
+    store_acc<S>(acc, wave, lane, sX);
+    __syncthreads();
+
+    // ---- x <- x - lr*(sgn + wd*x) -----------------------------------------------------------
+#pragma unroll
+    for (int p = 0; p < G::PASSES; ++p) {
+      const int row = p * G::ROWS_PER_PASS + lrow;
+      const int64_t off = base + (int64_t)row * d.cols + lcol;
+      const float4 sg = *reinterpret_cast<const float4*>(&sX[row * G::LD + lcol]);
+      float4 x = load4(d.param, off, d.param_bf16);
+      x.x = sign_update(x.x, sg.x, args.lr, args.weight_decay);
+      x.y = sign_update(x.y, sg.y, args.lr, args.weight_decay);
+      x.z = sign_update(x.z, sg.z, args.lr, args.weight_decay);
+      x.w = sign_update(x.w, sg.w, args.lr, args.weight_decay);
+      store4(d.param, off, d.param_bf16, x);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// order-1 tensors: one wavefront per chunk of S elements
+// ---------------------------------------------------------------------------
+template <int S>
+__global__ __launch_bounds__(64) void encode1d_wave(TableView tv, const float* __restrict__ basis,
+                                                    EncodeArgs args) {
+  constexpr int EPL = (S + 63) / 64;
+  __shared__ float s_b[S];
+  __shared__ float s_q[S];
+  __shared__ int32_t s_sel_idx[S];
+  __shared__ float s_sel_val[S];
+  const int lane = threadIdx.x;
+  const int k = args.k;
+  const int chunk = blockIdx.x;
+  const int t = find_tensor(tv.prefix, tv.n, chunk);
+  const TensorDev d = tv.descs[t];
+  const int c = chunk - tv.prefix[t];
+  const int64_t base = (int64_t)c * S;
+
+  float b[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const int n = lane + 64 * e;
+    b[e] = 0.f;
+    if (n < S) {
+      const float g = d.grad_bf16 ? bf16_to_f32(static_cast<const uint16_t*>(d.grad)[base + n])
+                                  : static_cast<const float*>(d.grad)[base + n];
+      b[e] = __fmaf_rn(args.beta, d.mom[base + n], g);
+      s_b[n] = b[e];
+    }
+  }
+  __syncthreads();
+  float q[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const int u = lane + 64 * e;
+    q[e] = 0.f;
+    if (u < S) {
+      float a = 0.f;
+      for (int n = 0; n < S; ++n) a = __fmaf_rn(basis[u * S + n], s_b[n], a);   // q = P b
+      q[e] = a;
+      s_q[u] = a;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const int u = lane + 64 * e;
+    if (u < S) {
+      const uint32_t mg = __float_as_uint(q[e]) & 0x7fffffffu;
+      int rk = 0;
+      for (int j = 0; j < S; ++j) {
+        const uint32_t mj = __float_as_uint(s_q[j]) & 0x7fffffffu;
+        rk += (mj > mg || (mj == mg && j < u)) ? 1 : 0;
+      }
+      if (rk < k) {
+        d.idx[(int64_t)c * k + rk] = u;
+        d.val[(int64_t)c * k + rk] = q[e];
+        s_sel_idx[rk] = u;
+        s_sel_val[rk] = q[e];
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const int n = lane + 64 * e;
+    if (n < S) {
+      float r = 0.f;
+      for (int j = 0; j < k; ++j) r = __fmaf_rn(s_sel_val[j], basis[s_sel_idx[j] * S + n], r);   // P^T q^
+      d.mom[base + n] = b[e] - r;
+    }
+  }
+}
+
+template <int S>
+__global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* __restrict__ basis,
+                                                    DecodeArgs args) {
+  constexpr int EPL = (S + 63) / 64;
+  __shared__ float s_acc[S];
+  const int lane = threadIdx.x;
+  const int k = args.k, W = args.W;
+  const int chunk = blockIdx.x;
+  const int t = find_tensor(tv.prefix, tv.n, chunk);
+  const TensorDev d = tv.descs[t];
+  const int c = chunk - tv.prefix[t];
+  const int64_t base = (int64_t)c * S;
+  for (int n = lane; n < S; n += 64) s_acc[n] = 0.f;
+  __syncthreads();
+  const int64_t wstride = (int64_t)d.nchunks * k;
+  for (int w = 0; w < W; ++w) {
+    for (int tt = lane; tt < k; tt += 64) {
+      const int64_t po = (int64_t)w * wstride + (int64_t)c * k + tt;
+      const int fi = d.idx[po];
+      const float fv = d.val[po];
+      if (fi >= 0 && fi < S) atomicAdd(&s_acc[fi], fv);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) {
+    const int n = lane + 64 * e;
+    if (n < S) {
+      float r = 0.f;
+      for (int u = 0; u < S; ++u) r = __fmaf_rn(s_acc[u], basis[u * S + n], r);   // P^T s
+      const float sg = sgnf(r);
+      if (d.param_bf16) {
+        uint16_t* xp = static_cast<uint16_t*>(d.param) + base + n;
+        *xp = (uint16_t)f32_to_bf16_rne(sign_update(bf16_to_f32(*xp), sg, args.lr, args.weight_decay));
+      } else {
+        float* xp = static_cast<float*>(d.param) + base + n;
+        *xp = sign_update(*xp, sg, args.lr, args.weight_decay);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// launch wrappers
+// ---------------------------------------------------------------------------
+template <int S>
+static hipError_t launch_enc2d_generic(const TableView& tv, const float* basis, const EncodeArgs& a, int num_cus,
+                                       hipStream_t stream) {
+  using G = Geo<S>;
+  const size_t lds_bytes = sizeof(float) * G::LDS_FLOATS;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_generic<S>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (e != hipSuccess) return e;
+  const int per_cu = (int)((160 * 1024) / lds_bytes) < 1 ? 1 : (int)((160 * 1024) / lds_bytes);
+  int64_t grid = (int64_t)num_cus * (per_cu > 8 ? 8 : per_cu);
+  if (grid > tv.total_chunks) grid = tv.total_chunks;
+  hipLaunchKernelGGL(encode2d_generic<S>, dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a);
+  return hipGetLastError();
+}
+
+template <int S>
+static hipError_t launch_dec2d_generic(const TableView& tv, const float* basis, const DecodeArgs& a, int num_cus,
+                                       hipStream_t stream) {
+  using G = Geo<S>;
+  const size_t lds_bytes = sizeof(float) * (G::TILE_FLOATS * (G::INPLACE ? 2 : 3));
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_generic<S>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (e != hipSuccess) return e;
+  const int per_cu = (int)((160 * 1024) / lds_bytes) < 1 ? 1 : (int)((160 * 1024) / lds_bytes);
+  int64_t grid = (int64_t)num_cus * (per_cu > 8 ? 8 : per_cu);
+  if (grid > tv.total_chunks) grid = tv.total_chunks;
+  hipLaunchKernelGGL(decode2d_generic<S>, dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_encode2d(const TableView& tv, const float* basis, int s, const EncodeArgs& a, int num_cus,
+                           int variant, hipStream_t stream) {
+  (void)variant;
+  if (tv.total_chunks == 0) return hipSuccess;
+  switch (s) {
+    case 32: return launch_enc2d_generic<32>(tv, basis, a, num_cus, stream);
+    case 64: return launch_enc2d_generic<64>(tv, basis, a, num_cus, stream);
+    case 128: return launch_enc2d_generic<128>(tv, basis, a, num_cus, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_decode2d(const TableView& tv, const float* basis, int s, const DecodeArgs& a, int num_cus,
+                           int variant, hipStream_t stream) {
+  (void)variant;
+  if (tv.total_chunks == 0) return hipSuccess;
+  switch (s) {
+    case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);
+    case 64: return launch_dec2d_generic<64>(tv, basis, a, num_cus, stream);
+    case 128: return launch_dec2d_generic<128>(tv, basis, a, num_cus, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_encode1d(const TableView& tv, const float* basis, int s, const EncodeArgs& a,
+                           hipStream_t stream) {
+  if (tv.total_chunks == 0) return hipSuccess;
+  const dim3 grid((unsigned)tv.total_chunks), block(64);
+  switch (s) {
+    case 32: hipLaunchKernelGGL(encode1d_wave<32>, grid, block, 0, stream, tv, basis, a); break;
+    case 64: hipLaunchKernelGGL(encode1d_wave<64>, grid, block, 0, stream, tv, basis, a); break;
+    case 128: hipLaunchKernelGGL(encode1d_wave<128>, grid, block, 0, stream, tv, basis, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
+                           hipStream_t stream) {
+  if (tv.total_chunks == 0) return hipSuccess;
+  const dim3 grid((unsigned)tv.total_chunks), block(64);
+  switch (s) {
+    case 32: hipLaunchKernelGGL(decode1d_wave<32>, grid, block, 0, stream, tv, basis, a); break;
+    case 64: hipLaunchKernelGGL(decode1d_wave<64>, grid, block, 0, stream, tv, basis, a); break;
+    case 128: hipLaunchKernelGGL(decode1d_wave<128>, grid, block, 0, stream, tv, basis, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace demo

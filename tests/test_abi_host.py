@@ -1,0 +1,112 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every
+function include/demo.h declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2411_19870_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "demo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(demo_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = declared_functions()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in demo.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_layout():
+    assert ctypes.sizeof(B.DemoTensor) == 64
+    assert B.DemoTensor.rows.offset == 40 and B.DemoTensor.grad_dtype.offset == 56
+
+
+def test_payload_elems_and_shape_errors():
+    assert B.demo_payload_elems(1024, 1024, 64, 32) == 256 * 32
+    assert B.demo_payload_elems(2048, 0, 64, 32) == 32 * 32
+    # Sec. 2.1 "Top-k Sparsification": reduction (prod s_i)/k, 4096/32 = 128 at 64 x 64
+    assert (1024 * 1024) // B.demo_payload_elems(1024, 1024, 64, 32) == 128
+    for args, code in [
+        ((1000, 1024, 64, 32), B.DEMO_ERR_SHAPE),
+        ((1024, 1000, 64, 32), B.DEMO_ERR_SHAPE),
+        ((0, 64, 64, 32), B.DEMO_ERR_SHAPE),
+        ((-64, 64, 64, 32), B.DEMO_ERR_SHAPE),
+        ((1024, 1024, 48, 32), B.DEMO_ERR_UNSUPPORTED),
+        ((1024, 1024, 64, 0), B.DEMO_ERR_ARG),
+        ((1024, 0, 64, 65), B.DEMO_ERR_ARG),           # k > M = s
+        ((1024, 1024, 32, 1025), B.DEMO_ERR_ARG),      # k > M = s*s
+        ((1024, 1024, 64, 257), B.DEMO_ERR_UNSUPPORTED),
+    ]:
+        with pytest.raises(B.DemoError) as e:
+            B.demo_payload_elems(*args)
+        assert e.value.status == code, args
+
+
+def _tensor(**kw):
+    t = B.DemoTensor()
+    t.grad, t.mom, t.param, t.idx, t.val = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000   # never dereferenced
+    t.rows, t.cols, t.grad_dtype, t.param_dtype = 128, 128, B.DEMO_F32, B.DEMO_F32
+    for k, v in kw.items():
+        setattr(t, k, v)
+    return t
+
+
+def test_validation_happens_before_any_launch():
+    lib = B.load_library()
+    h = ctypes.c_void_p()
+    assert lib.demo_create(ctypes.byref(h)) == B.DEMO_OK
+    arr1 = (B.DemoTensor * 1)
+
+    def enc(t, s=64, k=32, n=1):
+        return lib.demo_encode(h, arr1(t), n, 0.999, s, k, None)
+
+    def dec(t, s=64, k=32, W=1):
+        return lib.demo_decode(h, arr1(t), 1, W, 1e-3, 0.0, s, k, None)
+
+    def step(t, s=64, k=32):
+        return lib.demo_step(h, arr1(t), 1, 0.999, 1e-3, 0.0, s, k, None)
+
+    assert lib.demo_encode(None, arr1(_tensor()), 1, 0.999, 64, 32, None) == B.DEMO_ERR_ARG
+    assert lib.demo_encode(h, None, 1, 0.999, 64, 32, None) == B.DEMO_ERR_ARG
+    assert enc(_tensor(), n=-1) == B.DEMO_ERR_ARG
+    assert enc(_tensor(), n=0) == B.DEMO_OK                       # empty list: nothing to do
+    assert enc(_tensor(), s=48) == B.DEMO_ERR_UNSUPPORTED
+    assert enc(_tensor(), k=0) == B.DEMO_ERR_ARG
+    assert enc(_tensor(rows=100)) == B.DEMO_ERR_SHAPE
+    assert enc(_tensor(cols=96)) == B.DEMO_ERR_SHAPE
+    assert enc(_tensor(cols=0), k=65) == B.DEMO_ERR_ARG
+    assert enc(_tensor(), k=300) == B.DEMO_ERR_UNSUPPORTED
+    assert enc(_tensor(grad_dtype=7)) == B.DEMO_ERR_UNSUPPORTED
+    assert enc(_tensor(grad=None)) == B.DEMO_ERR_ARG
+    assert enc(_tensor(mom=None)) == B.DEMO_ERR_ARG
+    assert enc(_tensor(idx=None)) == B.DEMO_ERR_ARG
+    assert enc(_tensor(val=None)) == B.DEMO_ERR_ARG
+    assert dec(_tensor(param=None)) == B.DEMO_ERR_ARG
+    assert dec(_tensor(param_dtype=5)) == B.DEMO_ERR_UNSUPPORTED
+    assert dec(_tensor(), W=0) == B.DEMO_ERR_ARG
+    assert dec(_tensor(rows=64, cols=96)) == B.DEMO_ERR_SHAPE
+    assert step(_tensor(param=None)) == B.DEMO_ERR_ARG
+    assert step(_tensor(grad=None)) == B.DEMO_ERR_ARG
+    assert lib.demo_set_variant(h, 5) == B.DEMO_ERR_ARG
+    ms = ctypes.c_float()
+    assert lib.demo_last_kernel_ms(h, 0, ctypes.byref(ms)) == B.DEMO_ERR_ARG   # nothing recorded
+    assert lib.demo_destroy(h) == B.DEMO_OK
+    assert lib.demo_destroy(None) == B.DEMO_ERR_ARG
+    assert lib.demo_strerror(B.DEMO_ERR_SHAPE) and lib.demo_strerror(12345)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libdemo.so"))
+    with pytest.raises(FileNotFoundError):
+        B.load_library()

@@ -1,0 +1,230 @@
+"""Element-by-element parity of the HIP path (through the C ABI) with the float64
+oracle on seeded inputs small enough for the oracle to finish in seconds, spanning
+several chunks per tensor, ragged chunk grids, both dtypes and the edge cases."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2411_19870_amd import binding as B
+from paper_2411_19870_amd import synth
+from tests import compare as C
+from tests.gpu_harness import Case, np64, DEV
+
+pytestmark = pytest.mark.gpu
+
+BETA, LR = 0.999, 1e-3
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available()
+    c = B.Context()
+    yield c
+    c.close()
+
+
+def run_encode_check(ctx, case, beta=BETA):
+    before = case.snapshot()
+    ctx.demo_encode(case.args, beta, case.s, case.k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    stats = []
+    for ti in range(len(case.specs)):
+        st = C.check_encode(before["m"][ti], before["g"][ti], beta, case.s, case.k,
+                            after["idx"][ti][0], after["val"][ti][0], after["m"][ti])
+        stats.append(st)
+        assert np.array_equal(after["g"][ti], before["g"][ti])          # encode leaves g and x alone
+        assert np.array_equal(after["x"][ti], before["x"][ti])
+    return stats
+
+
+def run_decode_check(ctx, case, W, lr=LR, wd=0.0):
+    before = case.snapshot()
+    ctx.demo_decode(case.args, W, lr, wd, case.s, case.k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    pd = "bf16" if case.x[0].dtype == torch.bfloat16 else "f32"
+    stats = []
+    for ti in range(len(case.specs)):
+        st = C.check_decode(before["x"][ti], before["idx"][ti][:W], before["val"][ti][:W], lr, wd, case.s, pd,
+                            after["x"][ti])
+        stats.append(st)
+        assert np.array_equal(after["m"][ti], before["m"][ti])          # decode leaves m and the payload alone
+        assert np.array_equal(after["idx"][ti], before["idx"][ti])
+    return stats
+
+
+# ---- config 1: single fp32 1024 x 1024, s = 64, k = 32, W = 1 ------------------------------
+@pytest.mark.parametrize("variant", [0, 1])
+def test_config1_single_matrix(ctx, variant):
+    ctx.demo_set_variant(variant)
+    case = Case(synth.tensor_set("single"), 64, 32, seed=0)
+    st = run_encode_check(ctx, case)[0]
+    print("config1 encode", st)
+    assert st["chunks"] == 256
+    st = run_decode_check(ctx, case, W=1)[0]
+    print("config1 decode", st)
+    ctx.demo_set_variant(1)
+
+
+# ---- tiny ragged set: all chunk sizes, budgets, dtypes ---------------------------------------
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("s", [32, 64, 128])
+@pytest.mark.parametrize("k", [1, 8, 32])
+@pytest.mark.parametrize("gdt,pdt", [(torch.float32, torch.float32), (torch.bfloat16, torch.bfloat16)])
+def test_tiny_set_encode_decode(ctx, variant, s, k, gdt, pdt):
+    ctx.demo_set_variant(variant)
+    case = Case(synth.tensor_set("tiny"), s, k, W=3, grad_dtype=gdt, param_dtype=pdt, seed=s + k)
+    run_encode_check(ctx, case)
+    # decode of the own payload (W = 1), then of three workers' payloads with weight decay
+    run_decode_check(ctx, case, W=1)
+    case.fill_payloads()
+    run_decode_check(ctx, case, W=3, wd=0.1)
+    ctx.demo_set_variant(1)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_step_equals_encode_then_decode(ctx, variant):
+    ctx.demo_set_variant(variant)
+    a = Case(synth.tensor_set("tiny"), 64, 8, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, seed=5)
+    b = Case(synth.tensor_set("tiny"), 64, 8, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, seed=5)
+    ctx.demo_step(a.args, BETA, LR, 0.01, 64, 8)
+    ctx.demo_encode(b.args, BETA, 64, 8)
+    ctx.demo_decode(b.args, 1, LR, 0.01, 64, 8)
+    torch.cuda.synchronize()
+    for ti in range(len(a.specs)):
+        assert torch.equal(a.m[ti], b.m[ti]) and torch.equal(a.x[ti], b.x[ti])
+        assert torch.equal(a.idx[ti], b.idx[ti]) and torch.equal(a.val[ti], b.val[ti])
+    ctx.demo_set_variant(1)
+
+
+# ---- many workers with collisions (decode-heavy shape, small) ----------------------------------
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("s,W", [(64, 64), (32, 16), (128, 8)])
+def test_decode_many_workers(ctx, variant, s, W):
+    ctx.demo_set_variant(variant)
+    specs = [synth.TensorSpec("a", 2 * s, 3 * s), synth.TensorSpec("v", 4 * s, 0)]
+    case = Case(specs, s, 32, W=W, param_dtype=torch.bfloat16, seed=W)
+    case.fill_payloads()
+    st = run_decode_check(ctx, case, W=W)
+    print("decode W", W, st)
+    ctx.demo_set_variant(1)
+
+
+def test_decode_is_run_to_run_deterministic(ctx):
+    specs = [synth.TensorSpec("a", 128, 256)]
+    outs = []
+    for rep in range(3):
+        case = Case(specs, 64, 32, W=64, param_dtype=torch.float32, seed=1)
+        case.fill_payloads()
+        ctx.demo_decode(case.args, 64, LR, 0.0, 64, 32)
+        torch.cuda.synchronize()
+        outs.append(case.x[0].clone())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_decode_ignores_out_of_range_indices(ctx):
+    specs = [synth.TensorSpec("a", 64, 64), synth.TensorSpec("v", 64, 0)]
+    case = Case(specs, 64, 8, W=2, seed=2)
+    case.fill_payloads()
+    case.idx[0][1, 0, 0] = 4096
+    case.idx[0][1, 0, 1] = -5
+    case.idx[1][0, 0, 0] = 64
+    run_decode_check(ctx, case, W=2)
+
+
+# ---- degenerate inputs -----------------------------------------------------------------------------
+@pytest.mark.parametrize("variant", [0, 1])
+def test_all_zero_chunks(ctx, variant):
+    # zero gradient and zero momentum: every magnitude ties at 0 -> lowest indices, zero values,
+    # momentum stays zero; decode of that payload has sgn = 0 and only applies weight decay
+    ctx.demo_set_variant(variant)
+    case = Case(synth.tensor_set("tiny"), 64, 8, grad="zero", mom_std=0, seed=3)
+    run_encode_check(ctx, case)
+    for ti in range(len(case.specs)):
+        assert torch.equal(case.idx[ti][0], torch.arange(8, dtype=torch.int32, device=DEV).expand_as(case.idx[ti][0]))
+        assert not case.val[ti].any() and not case.m[ti].any()
+    x0 = [t.clone() for t in case.x]
+    run_decode_check(ctx, case, W=1, wd=0.5)
+    for ti in range(len(case.specs)):
+        expect = torch.addcmul(x0[ti], x0[ti], torch.tensor(-LR * 0.5, device=DEV))
+        assert torch.allclose(case.x[ti], expect, rtol=1e-6, atol=0)
+    ctx.demo_set_variant(1)
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+def test_exact_ties_take_lowest_indices(ctx, variant):
+    # a chunk whose only non-zero is a constant block: one DC coefficient, all others exactly 0
+    ctx.demo_set_variant(variant)
+    sp = [synth.TensorSpec("a", 64, 128), synth.TensorSpec("v", 128, 0)]
+    case = Case(sp, 64, 4, grad="zero", mom_std=0, seed=4)
+    case.g[0].fill_(0.5)
+    case.g[1].fill_(-0.25)
+    ctx.demo_encode(case.args, BETA, 64, 4)
+    torch.cuda.synchronize()
+    # the DC coefficient first, then ties among (numerically tiny) others: only check the head and legitimacy
+    assert (case.idx[0][0, :, 0] == 0).all() and (case.idx[1][0, :, 0] == 0).all()
+    assert torch.allclose(case.val[0][0, :, 0], torch.full((2,), 0.5 * 64, device=DEV), rtol=1e-6)
+    assert torch.allclose(case.val[1][0, :, 0], torch.full((2,), -0.25 * 8, device=DEV), rtol=1e-6)
+    ctx.demo_set_variant(1)
+
+
+@pytest.mark.parametrize("s", [32, 64, 128])
+def test_k_equals_M_exact_recovery_1d(ctx, s):
+    # k = M on order-1 chunks: the payload is the whole spectrum, the residual momentum vanishes
+    # (appendix remark on isometric transformations) and decode of the payload returns sgn(m_mid)
+    sp = [synth.TensorSpec("v", 8 * s, 0)]
+    case = Case(sp, s, s, seed=6)
+    before = case.snapshot()
+    run_encode_check(ctx, case)
+    m_mid = np.float32(BETA).astype(np.float64) * before["m"][0] + before["g"][0]
+    assert np.abs(np64(case.m[0])).max() <= 1e-5 * np.abs(m_mid).max()
+    assert sorted(case.idx[0][0, 0].tolist()) == list(range(s))
+    run_decode_check(ctx, case, W=1)
+
+
+# ---- momentum carried over consecutive steps (teacher forced) ---------------------------------------
+@pytest.mark.parametrize("s,k", [(32, 1), (64, 8), (128, 32), (64, 32)])
+def test_ten_steps_student_t_bf16(ctx, s, k):
+    specs = [synth.TensorSpec("a", 256, 384), synth.TensorSpec("v", 512, 0)]
+    case = Case(specs, s, k, grad="student", grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, mom_std=0, seed=7)
+    swaps = 0
+    for step in range(10):
+        case.new_grads(step)
+        sts = run_encode_check(ctx, case)          # oracle restarts from the GPU's momentum each step
+        swaps += sum(st["tie_swaps"] for st in sts)
+        run_decode_check(ctx, case, W=1)
+    print(f"s={s} k={k}: tie swaps over 10 steps: {swaps}")
+
+
+# ---- resume: 10 steps == 5 steps, reload state, 5 steps ----------------------------------------------
+def test_resume_is_bit_exact(ctx):
+    specs = synth.tensor_set("tiny")
+
+    def run(split):
+        case = Case(specs, 64, 8, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, mom_std=0, seed=8)
+        for step in range(10):
+            if split and step == 5:
+                saved = ([t.cpu() for t in case.m], [t.cpu() for t in case.x])
+                case = Case(specs, 64, 8, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, mom_std=0, seed=8)
+                for ti in range(len(specs)):
+                    case.m[ti].copy_(saved[0][ti])
+                    case.x[ti].copy_(saved[1][ti])
+            case.new_grads(step)
+            ctx.demo_step(case.args, BETA, LR, 0.0, 64, 8)
+        torch.cuda.synchronize()
+        return case
+
+    a, b = run(False), run(True)
+    for ti in range(len(specs)):
+        assert torch.equal(a.m[ti], b.m[ti]) and torch.equal(a.x[ti], b.x[ti])
+
+
+def test_timing_hooks(ctx):
+    case = Case(synth.tensor_set("tiny"), 64, 8, seed=9)
+    ctx.demo_set_timing(True)
+    ctx.demo_encode(case.args, BETA, 64, 8)
+    ctx.demo_decode(case.args, 1, LR, 0.0, 64, 8)
+    for which in range(4):
+        assert ctx.demo_last_kernel_ms(which) > 0
+    ctx.demo_set_timing(False)
