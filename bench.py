@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of DeMo's per-step compression path on one MI355X.
+
+One step = one pass of the whole hot path over the 1B-like tensor set:
+  demo_encode  (bf16 gradients, fp32 momentum, s = 64, k = 32; writes worker slot 0
+                of the payload buffers)
+  demo_decode  (W = 64 workers' payloads: slot 0 from the encode above, 63 synthetic;
+                bf16 parameters, lr = 1e-3)
+Inputs are synthetic and resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-step throughput in GB/s of algorithmic traffic (and
+params/s), the roofline record of the dominant kernel measured with HIP events on
+the launch stream inside the timed region, and the float64 CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+S, K, W = 64, 32, 64
+BETA, LR, WD = 0.999, 1e-3, 0.0
+
+
+def algorithmic_bytes(specs, s, k, W, grad_bytes, param_bytes):
+    """Bytes the method itself must move per step (every tensor read once, written once)."""
+    enc2 = enc1 = dec2 = dec1 = 0
+    p2 = p1 = 0
+    for sp in specs:
+        n, pairs = sp.numel, sp.nchunks(s) * k
+        e = n * (grad_bytes + 4 + 4) + pairs * 8            # g read, m read, m write, payload write
+        d = n * (2 * param_bytes) + W * pairs * 8           # x read, x write, W payloads read
+        if sp.cols == 0:
+            enc1 += e; dec1 += d; p1 += n
+        else:
+            enc2 += e; dec2 += d; p2 += n
+    return {"enc2d": enc2, "enc1d": enc1, "dec2d": dec2, "dec1d": dec1, "params2d": p2, "params1d": p1}
+
+
+def cpu_baseline(specs, seed):
+    """Time the oracle (as it stands) on a bounded sample of the workload: the first
+    transformer layer's attention output matrix (2048 x 2048, 1024 chunks) and one
+    norm vector, encode + W = 64 decode."""
+    import numpy as np
+    import torch
+    from oracle import demo_oracle as O
+    from paper_2411_19870_amd import synth
+
+    sample = [next(sp for sp in specs if sp.name.endswith(".wo")), next(sp for sp in specs if sp.cols == 0)]
+    data = []
+    for ti, sp in enumerate(sample):
+        g = synth.gaussian(sp, 1e-2, seed, ti, 0, "grad", dtype=torch.bfloat16).double().numpy()
+        m = synth.gaussian(sp, 1e-3, seed, ti, 0, "mom").double().numpy()
+        x = synth.gaussian(sp, 0.02, seed, ti, 0, "param", dtype=torch.bfloat16).double().numpy()
+        idx, val = synth.payload_fast(sp, S, K, W, 1e-3, seed, ti)
+        data.append((g, m, x, idx.numpy(), val.numpy()))
+    ab = algorithmic_bytes(sample, S, K, W, 2, 2)
+    nbytes = sum(ab[k] for k in ("enc2d", "enc1d", "dec2d", "dec1d"))
+    nparams = ab["params2d"] + ab["params1d"]
+    reps, t_wall, t_cpu = 0, 0.0, 0.0
+    while t_wall < 10.0 and reps < 50:
+        w0, c0 = time.perf_counter(), time.process_time()
+        for g, m, x, idx, val in data:
+            e = O.encode(m, g, float(np.float32(BETA)), S, K)
+            idx[0], val[0] = e["idx"], e["val"].astype(np.float32)
+            O.decode(x, idx, val, LR, WD, S, "bf16")
+        t_wall += time.perf_counter() - w0
+        t_cpu += time.process_time() - c0
+        reps += 1
+    cores = max(1, int(round(t_cpu / t_wall)))
+    return {
+        "value": nbytes * reps / t_wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "params_per_s": nparams * reps / t_wall,
+        "sample": f"{reps} passes of encode + W=64 decode over {sample[0].rows}x{sample[0].cols} "
+                  f"({sample[0].nchunks(S)} chunks) and one vector of {sample[1].rows}; {t_wall:.1f} s wall",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="1b", choices=["1b", "300m", "single"])
+    ap.add_argument("--variant", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the W workers' payloads are synthesised on-device); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2411_19870_amd import binding as B
+    from paper_2411_19870_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    specs = synth.tensor_set(a.workload)
+    gdt = torch.bfloat16 if a.workload == "1b" else torch.float32
+    pdt = gdt
+    gb = 2 if gdt == torch.bfloat16 else 4
+
+    tensors = []
+    for ti, sp in enumerate(specs):
+        g = synth.gaussian(sp, 1e-2, a.seed, ti, 0, "grad", dtype=gdt, device=dev)
+        m = synth.gaussian(sp, 1e-3, a.seed, ti, 0, "mom", device=dev)
+        x = synth.gaussian(sp, 0.02, a.seed, ti, 0, "param", dtype=pdt, device=dev)
+        idx, val = synth.payload_fast(sp, S, K, W, 1e-3, a.seed, ti, device=dev)
+        tensors.append(B.TensorArgs(g, m, x, idx, val))
+    tl = B.TensorList(tensors)
+    ab = algorithmic_bytes(specs, S, K, W, gb, gb)
+    step_bytes = ab["enc2d"] + ab["enc1d"] + ab["dec2d"] + ab["dec1d"]
+    nparams = ab["params2d"] + ab["params1d"]
+
+    ctx = B.Context()
+    ctx.demo_set_variant(a.variant)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ctx.demo_encode(tl, BETA, S, K, stream)
+        ctx.demo_decode(tl, W, LR, WD, S, K, stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.demo_set_timing(True)                 # per-kernel HIP events on the launch stream, no syncs
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / a.steps
+    kms = {}
+    for which, name in enumerate(("enc2d", "enc1d", "dec2d", "dec1d")):
+        try:
+            kms[name] = ctx.demo_last_kernel_ms(which)
+        except B.DemoError:
+            kms[name] = None
+    ctx.demo_set_timing(False)
+
+    dom = "enc2d" if (kms["enc2d"] or 0) >= (kms["dec2d"] or 0) else "dec2d"
+    achieved = ab[dom] / (kms[dom] * 1e-3) / 1e9
+    out = {
+        "metric": "DeMo encode+decode throughput at 1B shape" if a.workload == "1b" else f"DeMo encode+decode throughput ({a.workload})",
+        "value": step_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s",
+        "params_per_s": nparams / (ms_step * 1e-3),
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{a.workload}-like tensor set: encode (grad {'bf16' if gb == 2 else 'f32'}, momentum f32) "
+                               f"+ decode of W={W} payloads (param {'bf16' if gb == 2 else 'f32'})",
+                   "tensors": len(specs), "params": nparams, "s": S, "k": K, "W": W, "beta": BETA, "lr": LR,
+                   "kernel_variant": a.variant},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": ab[dom], "avg_launch_ms": kms[dom]},
+        "kernels_ms": kms,
+        "kernels_gbs": {k: (ab[k] / (v * 1e-3) / 1e9 if v else None) for k, v in kms.items()},
+        "encode_params_per_s": nparams / (((kms["enc2d"] or 0) + (kms["enc1d"] or 0)) * 1e-3),
+        "decode_params_per_s": nparams / (((kms["dec2d"] or 0) + (kms["dec1d"] or 0)) * 1e-3),
+        "algorithmic_bytes_per_step": step_bytes,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(specs, a.seed)
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

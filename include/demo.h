@@ -106,12 +106,14 @@ int demo_decode(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, float l
 int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, float lr,
               float weight_decay, int s, int k, void* hip_stream);
 
-/* Average duration in milliseconds of the kernels launched by the most recent
- * encode / decode call on this context, measured with HIP events recorded on the
- * call's own stream (blocks until those events complete).  which: 0 = encode
- * order-2 kernel, 1 = encode order-1 kernel, 2 = decode order-2, 3 = decode
- * order-1.  Timing is recorded only while enabled with demo_set_timing(ctx, 1).
- * Returns DEMO_ERR_ARG if nothing was recorded for `which`.  */
+/* Kernel timing with HIP events recorded on the call's own stream around each
+ * kernel launch.  demo_set_timing(ctx, 1) opens a measurement window (and clears
+ * the previous one); every encode / decode / step call then records one event
+ * pair per kernel it launches, without synchronising.  demo_last_kernel_ms blocks
+ * until the recorded events have completed and returns the average duration in
+ * milliseconds over the launches of the window (the 256 most recent at most).
+ * which: 0 = encode order-2 kernel, 1 = encode order-1, 2 = decode order-2,
+ * 3 = decode order-1.  DEMO_ERR_ARG if nothing was recorded for `which`.  */
 int demo_set_timing(demo_ctx* ctx, int enabled);
 int demo_last_kernel_ms(demo_ctx* ctx, int which, float* ms);
 

@@ -33,6 +33,7 @@ struct TableCache {
 
 constexpr int kMaxCachedTables = 8;
 constexpr int kNumTimers = 4;
+constexpr int kMaxTimedLaunches = 256;
 
 }  // namespace
 
@@ -43,9 +44,8 @@ struct demo_ctx {
   std::vector<TableCache> tables;
   uint64_t use_counter = 0;
   bool timing = false;
-  hipEvent_t ev[kNumTimers][2] = {};
-  bool ev_valid[kNumTimers] = {};
-  bool ev_created = false;
+  std::vector<hipEvent_t> ev[kNumTimers][2];   // event pairs, one per recorded launch
+  int ev_count[kNumTimers] = {};               // launches recorded since timing was enabled
   hipError_t last_hip = hipSuccess;
   int variant = 1;            // 0 = generic kernels only
 };
@@ -226,23 +226,25 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
 
 int timer_begin(demo_ctx* ctx, int which, hipStream_t st) {
   if (!ctx->timing) return DEMO_OK;
-  if (!ctx->ev_created) {
-    for (int i = 0; i < kNumTimers; ++i)
-      for (int j = 0; j < 2; ++j) {
-        hipError_t e = hipEventCreate(&ctx->ev[i][j]);
-        if (e != hipSuccess) return fail_hip(ctx, e);
-      }
-    ctx->ev_created = true;
+  const int slot = ctx->ev_count[which] % kMaxTimedLaunches;
+  while ((int)ctx->ev[which][0].size() <= slot) {
+    for (int j = 0; j < 2; ++j) {
+      hipEvent_t e;
+      hipError_t rc = hipEventCreate(&e);
+      if (rc != hipSuccess) return fail_hip(ctx, rc);
+      ctx->ev[which][j].push_back(e);
+    }
   }
-  hipError_t e = hipEventRecord(ctx->ev[which][0], st);
+  hipError_t e = hipEventRecord(ctx->ev[which][0][slot], st);
   return e == hipSuccess ? DEMO_OK : fail_hip(ctx, e);
 }
 
 int timer_end(demo_ctx* ctx, int which, hipStream_t st) {
   if (!ctx->timing) return DEMO_OK;
-  hipError_t e = hipEventRecord(ctx->ev[which][1], st);
+  const int slot = ctx->ev_count[which] % kMaxTimedLaunches;
+  hipError_t e = hipEventRecord(ctx->ev[which][1][slot], st);
   if (e != hipSuccess) return fail_hip(ctx, e);
-  ctx->ev_valid[which] = true;
+  ctx->ev_count[which]++;
   return DEMO_OK;
 }
 
@@ -309,9 +311,9 @@ int demo_destroy(demo_ctx* ctx) {
     for (BasisTable& b : ctx->bases) (void)hipFree(b.dev);
     for (TableCache& tc : ctx->tables)
       if (tc.dev) (void)hipFree(tc.dev);
-    if (ctx->ev_created)
-      for (int i = 0; i < kNumTimers; ++i)
-        for (int j = 0; j < 2; ++j) (void)hipEventDestroy(ctx->ev[i][j]);
+    for (int i = 0; i < kNumTimers; ++i)
+      for (int j = 0; j < 2; ++j)
+        for (hipEvent_t e : ctx->ev[i][j]) (void)hipEventDestroy(e);
   }
   delete ctx;
   return DEMO_OK;
@@ -362,18 +364,24 @@ int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, floa
 int demo_set_timing(demo_ctx* ctx, int enabled) {
   if (ctx == nullptr) return DEMO_ERR_ARG;
   ctx->timing = enabled != 0;
-  if (!ctx->timing)
-    for (int i = 0; i < kNumTimers; ++i) ctx->ev_valid[i] = false;
+  for (int i = 0; i < kNumTimers; ++i) ctx->ev_count[i] = 0;   // a new measurement window starts
   return DEMO_OK;
 }
 
 int demo_last_kernel_ms(demo_ctx* ctx, int which, float* ms) {
   if (ctx == nullptr || ms == nullptr || which < 0 || which >= kNumTimers) return DEMO_ERR_ARG;
-  if (!ctx->ev_valid[which]) return DEMO_ERR_ARG;
-  hipError_t e = hipEventSynchronize(ctx->ev[which][1]);
-  if (e != hipSuccess) return fail_hip(ctx, e);
-  e = hipEventElapsedTime(ms, ctx->ev[which][0], ctx->ev[which][1]);
-  if (e != hipSuccess) return fail_hip(ctx, e);
+  const int n = ctx->ev_count[which] < kMaxTimedLaunches ? ctx->ev_count[which] : kMaxTimedLaunches;
+  if (n == 0) return DEMO_ERR_ARG;
+  double sum = 0.0;
+  for (int i = 0; i < n; ++i) {
+    hipError_t e = hipEventSynchronize(ctx->ev[which][1][i]);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    float one = 0.f;
+    e = hipEventElapsedTime(&one, ctx->ev[which][0][i], ctx->ev[which][1][i]);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    sum += one;
+  }
+  *ms = (float)(sum / n);
   return DEMO_OK;
 }
 
