@@ -19,7 +19,8 @@ using demo::TensorDev;
 
 struct BasisTable {
   int s = 0;
-  float* dev = nullptr;
+  float* dev = nullptr;      // P, s x s
+  float* fast64 = nullptr;   // fragment tables of the s = 64 wavefront-per-chunk kernels
 };
 
 // One cached descriptor upload: the host bytes it was built from and the device copy.
@@ -28,6 +29,7 @@ struct TableCache {
   void* dev = nullptr;        // [TensorDev x n2][int32 x (n2+1)] [TensorDev x n1][int32 x (n1+1)]
   size_t dev_bytes = 0;
   TableView tv2{}, tv1{};
+  demo::Worklist wl{};        // queue of order-2 chunks for the exact fallback kernel
   uint64_t last_use = 0;
 };
 
@@ -116,23 +118,40 @@ int bind_device(demo_ctx* ctx) {
 // Orthonormal DCT-II matrix P[u][n] = c_u cos(pi (2n+1) u / (2s)), evaluated in
 // double precision and rounded once to float32 (Sec. 2.1 "Blockwise Linear
 // Projection": the matrices are precomputed once and shared by all tensors).
-int get_basis(demo_ctx* ctx, int s, const float** out) {
+int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(dev), host.size() * sizeof(float));
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  e = hipMemcpy(*dev, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    (void)hipFree(*dev);
+    *dev = nullptr;
+    return fail_hip(ctx, e);
+  }
+  return DEMO_OK;
+}
+
+int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   for (const BasisTable& b : ctx->bases)
-    if (b.s == s) { *out = b.dev; return DEMO_OK; }
-  std::vector<float> host((size_t)s * s);
+    if (b.s == s) { out->basis = b.dev; out->fast64 = b.fast64; return DEMO_OK; }
+  std::vector<double> P((size_t)s * s);
   const double pi = 3.14159265358979323846;
   for (int u = 0; u < s; ++u) {
     const double cu = u == 0 ? std::sqrt(1.0 / s) : std::sqrt(2.0 / s);
-    for (int n = 0; n < s; ++n) host[(size_t)u * s + n] = (float)(cu * std::cos(pi * (2.0 * n + 1.0) * u / (2.0 * s)));
+    for (int n = 0; n < s; ++n) P[(size_t)u * s + n] = cu * std::cos(pi * (2.0 * n + 1.0) * u / (2.0 * s));
   }
+  std::vector<float> host(P.begin(), P.end());   // one rounding to float32
   BasisTable b;
   b.s = s;
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&b.dev), host.size() * sizeof(float));
-  if (e != hipSuccess) return fail_hip(ctx, e);
-  e = hipMemcpy(b.dev, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice);
-  if (e != hipSuccess) { (void)hipFree(b.dev); return fail_hip(ctx, e); }
+  int rc = upload(ctx, host, &b.dev);
+  if (rc != DEMO_OK) return rc;
+  if (s == 64) {
+    std::vector<float> ft(demo::kFast64TableFloats);
+    demo::build_fast64_tables(P.data(), ft.data());
+    if ((rc = upload(ctx, ft, &b.fast64)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
+  }
   ctx->bases.push_back(b);
-  *out = b.dev;
+  out->basis = b.dev;
+  out->fast64 = b.fast64;
   return DEMO_OK;
 }
 
@@ -179,7 +198,8 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   const size_t o_p2 = align16(o_d2 + d2.size() * sizeof(TensorDev));
   const size_t o_d1 = align16(o_p2 + p2.size() * sizeof(int32_t));
   const size_t o_p1 = align16(o_d1 + d1.size() * sizeof(TensorDev));
-  const size_t total = align16(o_p1 + p1.size() * sizeof(int32_t));
+  const size_t o_wl = align16(o_p1 + p1.size() * sizeof(int32_t));   // count, ticket, pad, pad, list[]
+  const size_t total = align16(o_wl + (4 + (size_t)p2.back()) * sizeof(int32_t));
   std::vector<char> host(total, 0);
   if (!d2.empty()) std::memcpy(host.data() + o_d2, d2.data(), d2.size() * sizeof(TensorDev));
   std::memcpy(host.data() + o_p2, p2.data(), p2.size() * sizeof(int32_t));
@@ -218,6 +238,8 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   slot->tv1.prefix = reinterpret_cast<const int32_t*>(base + o_p1);
   slot->tv1.n = (int32_t)d1.size();
   slot->tv1.total_chunks = p1.back();
+  int32_t* wl = reinterpret_cast<int32_t*>(base + o_wl);   // zero-filled by the copy above
+  slot->wl = demo::Worklist{wl, wl + 1, wl + 4};
   slot->key.swap(key);
   slot->last_use = ++ctx->use_counter;
   *out = slot;
@@ -248,25 +270,25 @@ int timer_end(demo_ctx* ctx, int which, hipStream_t st) {
   return DEMO_OK;
 }
 
-int run_encode(demo_ctx* ctx, TableCache* tc, const float* basis, float beta, int s, int k, hipStream_t st) {
+int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, float beta, int s, int k, hipStream_t st) {
   demo::EncodeArgs a{beta, k};
   int rc;
   if (tc->tv2.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 0, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_encode2d(tc->tv2, basis, s, a, ctx->num_cus, ctx->variant, st);
+    hipError_t e = demo::launch_encode2d(tc->tv2, basis, s, a, tc->wl, ctx->num_cus, ctx->variant, st);
     if (e != hipSuccess) return fail_hip(ctx, e);
     if ((rc = timer_end(ctx, 0, st)) != DEMO_OK) return rc;
   }
   if (tc->tv1.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 1, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_encode1d(tc->tv1, basis, s, a, st);
+    hipError_t e = demo::launch_encode1d(tc->tv1, basis.basis, s, a, st);
     if (e != hipSuccess) return fail_hip(ctx, e);
     if ((rc = timer_end(ctx, 1, st)) != DEMO_OK) return rc;
   }
   return DEMO_OK;
 }
 
-int run_decode(demo_ctx* ctx, TableCache* tc, const float* basis, int W, float lr, float wd, int s, int k,
+int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, int W, float lr, float wd, int s, int k,
                hipStream_t st) {
   demo::DecodeArgs a{lr, wd, k, W};
   int rc;
@@ -278,14 +300,14 @@ int run_decode(demo_ctx* ctx, TableCache* tc, const float* basis, int W, float l
   }
   if (tc->tv1.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 3, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_decode1d(tc->tv1, basis, s, a, st);
+    hipError_t e = demo::launch_decode1d(tc->tv1, basis.basis, s, a, st);
     if (e != hipSuccess) return fail_hip(ctx, e);
     if ((rc = timer_end(ctx, 3, st)) != DEMO_OK) return rc;
   }
   return DEMO_OK;
 }
 
-int prepare(demo_ctx* ctx, const demo_tensor* t, int n, int s, const float** basis, TableCache** tc) {
+int prepare(demo_ctx* ctx, const demo_tensor* t, int n, int s, demo::BasisTables* basis, TableCache** tc) {
   int rc = bind_device(ctx);
   if (rc != DEMO_OK) return rc;
   if ((rc = get_basis(ctx, s, basis)) != DEMO_OK) return rc;
@@ -308,7 +330,7 @@ int demo_destroy(demo_ctx* ctx) {
   if (ctx == nullptr) return DEMO_ERR_ARG;
   if (ctx->device >= 0) {
     (void)hipDeviceSynchronize();
-    for (BasisTable& b : ctx->bases) (void)hipFree(b.dev);
+    for (BasisTable& b : ctx->bases) { (void)hipFree(b.dev); if (b.fast64) (void)hipFree(b.fast64); }
     for (TableCache& tc : ctx->tables)
       if (tc.dev) (void)hipFree(tc.dev);
     for (int i = 0; i < kNumTimers; ++i)
@@ -331,7 +353,7 @@ int demo_payload_elems(int64_t rows, int64_t cols, int s, int k, int64_t* out) {
 int demo_encode(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k, void* hip_stream) {
   int rc = validate(ctx, tensors, n, s, k, NEED_ENCODE);
   if (rc != DEMO_OK || n == 0) return rc;
-  const float* basis = nullptr;
+  demo::BasisTables basis{};
   TableCache* tc = nullptr;
   if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
   return run_encode(ctx, tc, basis, beta, s, k, static_cast<hipStream_t>(hip_stream));
@@ -343,7 +365,7 @@ int demo_decode(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, float l
   if (rc != DEMO_OK) return rc;
   if (W < 1) return DEMO_ERR_ARG;
   if (n == 0) return DEMO_OK;
-  const float* basis = nullptr;
+  demo::BasisTables basis{};
   TableCache* tc = nullptr;
   if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
   return run_decode(ctx, tc, basis, W, lr, weight_decay, s, k, static_cast<hipStream_t>(hip_stream));
@@ -353,7 +375,7 @@ int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, floa
               int k, void* hip_stream) {
   int rc = validate(ctx, tensors, n, s, k, NEED_ENCODE | NEED_DECODE);
   if (rc != DEMO_OK || n == 0) return rc;
-  const float* basis = nullptr;
+  demo::BasisTables basis{};
   TableCache* tc = nullptr;
   if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);

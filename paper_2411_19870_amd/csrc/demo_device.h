@@ -1,0 +1,71 @@
+// Device-side helpers shared by the kernel files.
+#pragma once
+#include "demo_internal.h"
+
+namespace demo {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Pointers read from a descriptor table are generic; these casts tell the compiler they
+// are global memory so that it emits global_* rather than flat_* accesses.
+#define DEMO_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ DEMO_GLOBAL T* as_global(T* p) {
+  return (DEMO_GLOBAL T*)(p);
+}
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ f32x4 gload_f4(const float* p) { return *(const DEMO_GLOBAL f32x4*)(p); }
+__device__ __forceinline__ u32x2 gload_u2(const void* p) { return *(const DEMO_GLOBAL u32x2*)(p); }
+__device__ __forceinline__ void gstore_f4(float* p, f32x4 v) { *(DEMO_GLOBAL f32x4*)(p) = v; }
+__device__ __forceinline__ void gstore_u2(void* p, u32x2 v) { *(DEMO_GLOBAL u32x2*)(p) = v; }
+
+// ---------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int find_tensor(const int32_t* __restrict__ prefix, int n, int chunk) {
+  int lo = 0, hi = n;  // invariant: prefix[lo] <= chunk < prefix[hi]
+  while (hi - lo > 1) {
+    int mid = (lo + hi) >> 1;
+    if (prefix[mid] <= chunk) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t b = __float_as_uint(f);
+  if ((b & 0x7fffffffu) > 0x7f800000u) return (b >> 16) | 0x40u;  // NaN stays NaN
+  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ float4 load4(const void* __restrict__ base, int64_t off, int is_bf16) {
+  if (is_bf16) {
+    uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + off);
+    return make_float4(bf16_to_f32(r.x & 0xffffu), bf16_to_f32(r.x >> 16), bf16_to_f32(r.y & 0xffffu),
+                       bf16_to_f32(r.y >> 16));
+  }
+  return *reinterpret_cast<const float4*>(static_cast<const float*>(base) + off);
+}
+
+__device__ __forceinline__ void store4(void* __restrict__ base, int64_t off, int is_bf16, float4 v) {
+  if (is_bf16) {
+    uint2 r;
+    r.x = f32_to_bf16_rne(v.x) | (f32_to_bf16_rne(v.y) << 16);
+    r.y = f32_to_bf16_rne(v.z) | (f32_to_bf16_rne(v.w) << 16);
+    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + off) = r;
+  } else {
+    *reinterpret_cast<float4*>(static_cast<float*>(base) + off) = v;
+  }
+}
+
+__device__ __forceinline__ float sgnf(float r) { return (r > 0.0f ? 1.0f : 0.0f) - (r < 0.0f ? 1.0f : 0.0f); }
+
+// x' = x - lr*(sgn + wd*x) with two float32 fused multiply-adds (update line of Algorithm 1).
+__device__ __forceinline__ float sign_update(float x, float sg, float lr, float wd) {
+  float t = __fmaf_rn(wd, x, sg);
+  return __fmaf_rn(-lr, t, x);
+}
+
+}  // namespace demo

@@ -32,6 +32,14 @@ struct TableView {
   int32_t total_chunks;
 };
 
+// Chunks a fast kernel hands over to the exact generic kernel (device memory owned by the
+// context, one per cached tensor list).  `count` and `ticket` are zero between calls.
+struct Worklist {
+  int32_t* count;
+  int32_t* ticket;
+  int32_t* list;     // capacity: total order-2 chunks of the tensor list
+};
+
 struct EncodeArgs {
   float beta;
   int k;
@@ -44,16 +52,28 @@ struct DecodeArgs {
   int W;
 };
 
-// Launch wrappers (demo_kernels.hip).  `basis` is the s x s orthonormal DCT-II
-// matrix P, row-major float32, in device memory.  `variant` selects the kernel
-// family: 0 = generic LDS-staged kernels, 1 = fastest available for this s.
-hipError_t launch_encode2d(const TableView& tv, const float* basis, int s, const EncodeArgs& a,
-                           int num_cus, int variant, hipStream_t stream);
+// Device tables of one chunk size.
+struct BasisTables {
+  const float* basis;    // s x s orthonormal DCT-II matrix P, row-major float32
+  const float* fast64;   // fragment tables of the wavefront-per-chunk kernels (s = 64 only, else null)
+};
+
+// Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:
+// 0 = generic LDS-staged kernels, 1 = fastest available for this s and k.
+hipError_t launch_encode2d(const TableView& tv, const BasisTables& bt, int s, const EncodeArgs& a,
+                           const Worklist& wl, int num_cus, int variant, hipStream_t stream);
 hipError_t launch_encode1d(const TableView& tv, const float* basis, int s, const EncodeArgs& a,
                            hipStream_t stream);
-hipError_t launch_decode2d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
+hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, const DecodeArgs& a,
                            int num_cus, int variant, hipStream_t stream);
 hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
                            hipStream_t stream);
+
+// s = 64 wavefront-per-chunk kernels (demo_fast64.hip).
+constexpr int kFast64TableFloats = 4 * 4096;
+constexpr int kFast64MaxK = 64;
+void build_fast64_tables(const double* P, float* out /* kFast64TableFloats */);
+hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
+                                  int num_cus, hipStream_t stream);
 
 }  // namespace demo

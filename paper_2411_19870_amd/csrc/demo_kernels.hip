@@ -9,58 +9,9 @@
 // chunk (s in {32,64,128}), tiles staged in LDS, all contractions on the fp32
 // matrix cores (v_mfma_f32_16x16x4_f32), and one wavefront per order-1 chunk.
 #include "demo_internal.h"
+#include "demo_device.h"
 
 namespace demo {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-// ---------------------------------------------------------------------------
-// small helpers
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ int find_tensor(const int32_t* __restrict__ prefix, int n, int chunk) {
-  int lo = 0, hi = n;  // invariant: prefix[lo] <= chunk < prefix[hi]
-  while (hi - lo > 1) {
-    int mid = (lo + hi) >> 1;
-    if (prefix[mid] <= chunk) lo = mid; else hi = mid;
-  }
-  return lo;
-}
-
-__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
-
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-  uint32_t b = __float_as_uint(f);
-  if ((b & 0x7fffffffu) > 0x7f800000u) return (b >> 16) | 0x40u;  // NaN stays NaN
-  return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
-}
-
-__device__ __forceinline__ float4 load4(const void* __restrict__ base, int64_t off, int is_bf16) {
-  if (is_bf16) {
-    uint2 r = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(base) + off);
-    return make_float4(bf16_to_f32(r.x & 0xffffu), bf16_to_f32(r.x >> 16), bf16_to_f32(r.y & 0xffffu),
-                       bf16_to_f32(r.y >> 16));
-  }
-  return *reinterpret_cast<const float4*>(static_cast<const float*>(base) + off);
-}
-
-__device__ __forceinline__ void store4(void* __restrict__ base, int64_t off, int is_bf16, float4 v) {
-  if (is_bf16) {
-    uint2 r;
-    r.x = f32_to_bf16_rne(v.x) | (f32_to_bf16_rne(v.y) << 16);
-    r.y = f32_to_bf16_rne(v.z) | (f32_to_bf16_rne(v.w) << 16);
-    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + off) = r;
-  } else {
-    *reinterpret_cast<float4*>(static_cast<float*>(base) + off) = v;
-  }
-}
-
-__device__ __forceinline__ float sgnf(float r) { return (r > 0.0f ? 1.0f : 0.0f) - (r < 0.0f ? 1.0f : 0.0f); }
-
-// x' = x - lr*(sgn + wd*x) with two float32 fused multiply-adds (update line of Algorithm 1).
-__device__ __forceinline__ float sign_update(float x, float sg, float lr, float wd) {
-  float t = __fmaf_rn(wd, x, sg);
-  return __fmaf_rn(-lr, t, x);
-}
 
 // ---------------------------------------------------------------------------
 // Geometry of the generic order-2 kernels
@@ -143,9 +94,11 @@ __device__ __forceinline__ int block_sum4(int wave_count, int wave, int lane, in
 // ---------------------------------------------------------------------------
 // encode, order-2 tensors, generic
 // ---------------------------------------------------------------------------
+// With a worklist (wl.list != nullptr) only the chunks queued there are processed, and the
+// last workgroup to finish clears the queue for the next call.
 template <int S>
 __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const float* __restrict__ basis,
-                                                        EncodeArgs args) {
+                                                        EncodeArgs args, Worklist wl) {
   using G = Geo<S>;
   extern __shared__ float lds[];
   float* sP = lds;                                     // basis P[u][n], stride LD
@@ -157,15 +110,17 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
   float* sel_val = scratch + 2 * DEMO_MAXK_INTERNAL;
   int* s_cnt = reinterpret_cast<int*>(scratch + 3 * DEMO_MAXK_INTERNAL);  // [8] counters + [1] list cursor
   int* s_cursor = s_cnt + 8;
-  // second list (rank-sorted) overlays the head of the first product tile after it is dead
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lq = lane >> 4;
   const int k = args.k;
   const int kpad = (k + 3) & ~3;
 
-  for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
+  const int nwork = wl.list != nullptr ? *wl.count : tv.total_chunks;
+  if (nwork > 0)
+    for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
 
-  for (int chunk = blockIdx.x; chunk < tv.total_chunks; chunk += gridDim.x) {
+  for (int wi = blockIdx.x; wi < nwork; wi += gridDim.x) {
+    const int chunk = wl.list != nullptr ? wl.list[wi] : wi;
     const int t = find_tensor(tv.prefix, tv.n, chunk);
     const TensorDev d = tv.descs[t];
     const int c = chunk - tv.prefix[t];
@@ -344,6 +299,16 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
       o.z = mid[p].z - r.z;
       o.w = mid[p].w - r.w;
       *reinterpret_cast<float4*>(d.mom + off) = o;
+    }
+  }
+  if (wl.list != nullptr) {
+    __syncthreads();   // every thread has read *wl.count
+    if (tid == 0) {
+      __threadfence();
+      if (atomicAdd(wl.ticket, 1) == (int)gridDim.x - 1) {
+        *wl.count = 0;
+        *wl.ticket = 0;
+      }
     }
   }
 }
@@ -574,8 +539,8 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <int S>
-static hipError_t launch_enc2d_generic(const TableView& tv, const float* basis, const EncodeArgs& a, int num_cus,
-                                       hipStream_t stream) {
+static hipError_t launch_enc2d_generic(const TableView& tv, const float* basis, const EncodeArgs& a,
+                                       const Worklist& wl, int num_cus, hipStream_t stream) {
   using G = Geo<S>;
   const size_t lds_bytes = sizeof(float) * G::LDS_FLOATS;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_generic<S>),
@@ -584,7 +549,8 @@ static hipError_t launch_enc2d_generic(const TableView& tv, const float* basis, 
   const int per_cu = (int)((160 * 1024) / lds_bytes) < 1 ? 1 : (int)((160 * 1024) / lds_bytes);
   int64_t grid = (int64_t)num_cus * (per_cu > 8 ? 8 : per_cu);
   if (grid > tv.total_chunks) grid = tv.total_chunks;
-  hipLaunchKernelGGL(encode2d_generic<S>, dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a);
+  if (wl.list != nullptr && grid > 64) grid = 64;   // the queue is short; an empty one costs one launch
+  hipLaunchKernelGGL(encode2d_generic<S>, dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a, wl);
   return hipGetLastError();
 }
 
@@ -603,22 +569,30 @@ static hipError_t launch_dec2d_generic(const TableView& tv, const float* basis, 
   return hipGetLastError();
 }
 
-hipError_t launch_encode2d(const TableView& tv, const float* basis, int s, const EncodeArgs& a, int num_cus,
-                           int variant, hipStream_t stream) {
-  (void)variant;
+hipError_t launch_encode2d(const TableView& tv, const BasisTables& bt, int s, const EncodeArgs& a,
+                           const Worklist& wl, int num_cus, int variant, hipStream_t stream) {
   if (tv.total_chunks == 0) return hipSuccess;
+  const float* basis = bt.basis;
+  if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.fast64 != nullptr && wl.list != nullptr) {
+    // wavefront-per-chunk kernel, then the exact generic kernel over whatever it queued
+    hipError_t e = launch_encode2d_wave64(tv, bt.fast64, a, wl, num_cus, stream);
+    if (e != hipSuccess) return e;
+    return launch_enc2d_generic<64>(tv, basis, a, wl, num_cus, stream);
+  }
+  const Worklist none{nullptr, nullptr, nullptr};
   switch (s) {
-    case 32: return launch_enc2d_generic<32>(tv, basis, a, num_cus, stream);
-    case 64: return launch_enc2d_generic<64>(tv, basis, a, num_cus, stream);
-    case 128: return launch_enc2d_generic<128>(tv, basis, a, num_cus, stream);
+    case 32: return launch_enc2d_generic<32>(tv, basis, a, none, num_cus, stream);
+    case 64: return launch_enc2d_generic<64>(tv, basis, a, none, num_cus, stream);
+    case 128: return launch_enc2d_generic<128>(tv, basis, a, none, num_cus, stream);
   }
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_decode2d(const TableView& tv, const float* basis, int s, const DecodeArgs& a, int num_cus,
+hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, const DecodeArgs& a, int num_cus,
                            int variant, hipStream_t stream) {
   (void)variant;
   if (tv.total_chunks == 0) return hipSuccess;
+  const float* basis = bt.basis;
   switch (s) {
     case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);
     case 64: return launch_dec2d_generic<64>(tv, basis, a, num_cus, stream);

@@ -169,6 +169,32 @@ def test_exact_ties_take_lowest_indices(ctx, variant):
     ctx.demo_set_variant(1)
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("nequal", [40, 300, 2000])
+def test_many_near_equal_magnitudes(ctx, variant, nequal):
+    # chunks built as the inverse DCT of `nequal` coefficients of magnitude exactly 1: after the
+    # forward transform they agree to rounding noise, far more candidates than k sit at the threshold
+    # (the wavefront kernel hands such chunks to the exact workgroup kernel)
+    import scipy.fft
+    ctx.demo_set_variant(variant)
+    rng = np.random.default_rng(nequal)
+    sp = [synth.TensorSpec("a", 128, 192)]
+    case = Case(sp, 64, 32, grad="zero", mom_std=0, seed=11)
+    blocks = np.zeros((2, 3, 64, 64))
+    for a in range(2):
+        for b in range(3):
+            q = np.zeros(4096)
+            pos = rng.permutation(4096)[:nequal]
+            q[pos] = rng.choice([-1.0, 1.0], size=nequal)
+            q[rng.integers(0, 4096)] = 3.0                      # one clear winner
+            blocks[a, b] = scipy.fft.idctn(q.reshape(64, 64), type=2, norm="ortho")
+    g = blocks.transpose(0, 2, 1, 3).reshape(128, 192)
+    case.g[0].copy_(torch.from_numpy(g).float())
+    st = run_encode_check(ctx, case, beta=0.0)[0]
+    print("near-equal magnitudes", nequal, st)
+    ctx.demo_set_variant(1)
+
+
 @pytest.mark.parametrize("s", [32, 64, 128])
 def test_k_equals_M_exact_recovery_1d(ctx, s):
     # k = M on order-1 chunks: the payload is the whole spectrum, the residual momentum vanishes
