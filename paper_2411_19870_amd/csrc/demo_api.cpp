@@ -170,7 +170,10 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   }
   std::vector<TensorDev> d2, d1;
   std::vector<int32_t> p2(1, 0), p1(1, 0);
+  uint32_t mix2 = 0, mix1 = 0;
   for (int i = 0; i < n; ++i) {
+    const uint32_t mix = (t[i].grad_dtype == DEMO_BF16 ? 1u : 2u) | (t[i].param_dtype == DEMO_BF16 ? 4u : 8u);
+    (t[i].cols == 0 ? mix1 : mix2) |= mix;
     TensorDev d{};
     d.grad = t[i].grad;
     d.mom = t[i].mom;
@@ -234,10 +237,12 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   slot->tv2.prefix = reinterpret_cast<const int32_t*>(base + o_p2);
   slot->tv2.n = (int32_t)d2.size();
   slot->tv2.total_chunks = p2.back();
+  slot->tv2.dtypes = mix2;
   slot->tv1.descs = reinterpret_cast<const TensorDev*>(base + o_d1);
   slot->tv1.prefix = reinterpret_cast<const int32_t*>(base + o_p1);
   slot->tv1.n = (int32_t)d1.size();
   slot->tv1.total_chunks = p1.back();
+  slot->tv1.dtypes = mix1;
   int32_t* wl = reinterpret_cast<int32_t*>(base + o_wl);   // zero-filled by the copy above
   slot->wl = demo::Worklist{wl, wl + 1, wl + 4};
   slot->key.swap(key);

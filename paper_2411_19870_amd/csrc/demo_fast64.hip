@@ -295,6 +295,229 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
   }
 }
 
+// ---------------------------------------------------------------------------
+// decode
+// ---------------------------------------------------------------------------
+// One wavefront per chunk.  The coefficient sums S live in a private LDS tile (row stride
+// 68 floats); R = P^T (S P) runs as two MFMA chains:
+//   product a   Y[u][j] = sum_v S[u][v] P[v][j]     A = S from LDS, B = rows of P
+//   product b   R[i][j] = sum_u P[u][i] Y[u][j]     A = permuted rows of P, B = product-a accumulators
+// and lands in the same register layout the parameters are loaded and stored with.
+namespace {
+constexpr int F64D_WAVES = 7;                       // 7 private tiles + the two basis tables fill the LDS
+constexpr int F64D_THREADS = F64D_WAVES * 64;
+constexpr int F64D_LDT = 68;
+constexpr int F64D_TILE_FLOATS = 64 * F64D_LDT;
+constexpr int F64D_LDS_BYTES = 4 * (2 * 4096 + F64D_WAVES * F64D_TILE_FLOATS);
+}  // namespace
+
+template <bool PBF16>   // parameter dtype of every tensor in the table
+__global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
+                                                                DecodeArgs args) {
+  extern __shared__ float lds[];
+  const float* sPplain = lds;
+  const float* sPperm = lds + 4096;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c = lane & 15;
+  float* tile = lds + 2 * 4096 + wave * F64D_TILE_FLOATS;
+  const int k = args.k, W = args.W;
+
+  for (int e = tid; e < 2 * 4096 / 4; e += F64D_THREADS)
+    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + 2 * 4096)[e];
+  __syncthreads();
+
+  const int nwaves = gridDim.x * F64D_WAVES;
+  const int wid = blockIdx.x * F64D_WAVES + wave;
+  const int total = tv.total_chunks;
+  const int per = total / nwaves, rem = total - per * nwaves;
+  int chunk = wid * per + (wid < rem ? wid : rem);
+  const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
+  if (chunk >= chunk_end) return;
+
+  // payload lanes: with k <= 32 one load instruction fetches the pairs of two workers
+  const int wpi = k <= 32 ? 2 : 1;                       // workers per load instruction
+  const int sub = wpi == 2 ? (lane >> 5) : 0;            // which of them this lane serves
+  const int pt = wpi == 2 ? (lane & 31) : lane;          // pair index inside the chunk
+  const bool pact = pt < k;
+  constexpr int NLI = 32;                                // load instructions per group of workers
+  int32_t pi[NLI];
+  float pv[NLI];
+  auto load_payload = [&](const TensorDev& dd, int ccc, int wbase) {
+    // uniform 64-bit base per load instruction + one 32-bit per-lane offset
+    const int64_t wstride = (int64_t)dd.nchunks * k;
+    const uint32_t lane_off = (uint32_t)(sub * (int)wstride + pt);
+    const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)ccc * k + (int64_t)wbase * wstride;
+    const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)ccc * k + (int64_t)wbase * wstride;
+#pragma unroll
+    for (int j = 0; j < NLI; ++j) {
+      const bool ok = pact && wbase + j * wpi + sub < W;
+      pi[j] = ok ? ip[lane_off] : -1;
+      pv[j] = ok ? vp[lane_off] : 0.f;
+      ip += wpi * wstride;
+      vp += wpi * wstride;
+    }
+  };
+  // S[idx] += val with one worker per LDS instruction, in worker order: indices inside one
+  // worker's chunk are distinct, so every slot receives its additions in worker order
+  auto scatter = [&]() {
+#pragma unroll
+    for (int j = 0; j < NLI; ++j) {
+      const bool ok = pi[j] >= 0 && pi[j] < 4096;
+      const int a = (pi[j] >> 6) * F64D_LDT + (pi[j] & 63);
+      if (ok && sub == 0) atomicAdd(&tile[a], pv[j]);
+      if (wpi == 2) {
+        wave_lds_sync();   // keeps the two workers in two separate, ordered LDS instructions
+        if (ok && sub == 1) atomicAdd(&tile[a], pv[j]);
+      }
+      wave_lds_sync();
+    }
+  };
+
+  int t = find_tensor(tv.prefix, tv.n, chunk);
+  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
+  TensorDev d = tv.descs[t];
+  load_payload(d, chunk - t_first, 0);
+
+  for (; chunk < chunk_end; ++chunk) {
+    const int cc = chunk - t_first;
+    const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
+    const int64_t base = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64 + (int64_t)g * d.cols + 4 * c;
+    const TensorDev dcur = d;
+
+    // ---- S = sum over workers ---------------------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
+    wave_lds_sync();
+    scatter();
+    for (int wbase = NLI * wpi; wbase < W; wbase += NLI * wpi) {   // more workers than one group holds
+      load_payload(dcur, cc, wbase);
+      scatter();
+    }
+    // ---- payload of the next chunk, in flight during the products -----------------------------------------
+    if (chunk + 1 < chunk_end) {
+      while (chunk + 1 >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = tv.prefix[t + 1];
+        d = tv.descs[t];
+      }
+      load_payload(d, chunk + 1 - t_first, 0);
+    }
+    wave_lds_sync();
+
+    // ---- product a: Ya[mt][e] (rows u = 16mt+4g+r, cols j = 4c+e) --------------------------------------
+    f32x4 Ya[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) Ya[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kg = 0; kg < 4; ++kg) {
+      // k-step ks = 4kg + kr contracts v = 16kg + 4g + kr: four k-steps per 16-byte LDS read of S
+      float4 sa[4];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+        sa[mt] = *reinterpret_cast<const float4*>(&tile[(16 * mt + c) * F64D_LDT + 16 * kg + 4 * g]);
+#pragma unroll
+      for (int kr = 0; kr < 4; ++kr) {
+        const float4 pb = *reinterpret_cast<const float4*>(&sPplain[(16 * kg + 4 * g + kr) * 64 + 4 * c]);
+        const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const float a = kr == 0 ? sa[mt].x : kr == 1 ? sa[mt].y : kr == 2 ? sa[mt].z : sa[mt].w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) Ya[mt][e] = mfma4(a, bf[e], Ya[mt][e]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    // ---- product b: R[mt'][e] component r' = element (row 4(4mt'+r')+g, col 4c+e) --------------------------
+    f32x4 R[4][4];
+    u32x2 Xh[16];   // bf16 parameters, raw
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) R[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int mr = 0; mr < 16; ++mr) {
+      const int mt = mr >> 2, r = mr & 3;
+      const float4 pa = *reinterpret_cast<const float4*>(&sPperm[(16 * mt + 4 * g + r) * 64 + 4 * c]);
+      const float af[4] = {pa.x, pa.y, pa.z, pa.w};
+#pragma unroll
+      for (int m2 = 0; m2 < 4; ++m2)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) R[m2][e] = mfma4(af[m2], Ya[mt][e][r], R[m2][e]);
+      if (PBF16 && r == 3) {
+        // a quarter of the product-a accumulators is dead: use the registers for the parameters
+        const uint16_t* xp = static_cast<const uint16_t*>(dcur.param) + base;
+#pragma unroll
+        for (int q = 4 * mt; q < 4 * mt + 4; ++q) Xh[q] = gload_u2(xp + (int64_t)(4 * q) * dcur.cols);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- x <- x - lr*(sgn(R) + wd*x) ---------------------------------------------------------------------
+    if (PBF16) {
+      uint16_t* xp = static_cast<uint16_t*>(dcur.param) + base;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float x[4] = {bf16_to_f32(Xh[q][0] & 0xffffu), bf16_to_f32(Xh[q][0] >> 16),
+                            bf16_to_f32(Xh[q][1] & 0xffffu), bf16_to_f32(Xh[q][1] >> 16)};
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = sign_update(x[e], sgnf(R[q >> 2][e][q & 3]), args.lr, args.weight_decay);
+        const u32x2 pk = {f32_to_bf16_rne(o[0]) | (f32_to_bf16_rne(o[1]) << 16),
+                          f32_to_bf16_rne(o[2]) | (f32_to_bf16_rne(o[3]) << 16)};
+        gstore_u2(xp + (int64_t)(4 * q) * dcur.cols, pk);
+      }
+    } else {
+      // fp32 parameters are read here, four rows at a time, to stay inside the register budget
+      float* xp = static_cast<float*>(dcur.param) + base;
+#pragma unroll
+      for (int qb = 0; qb < 16; qb += 4) {
+        f32x4 xin[4];
+#pragma unroll
+        for (int q = qb; q < qb + 4; ++q) xin[q - qb] = gload_f4(xp + (int64_t)(4 * q) * dcur.cols);
+#pragma unroll
+        for (int q = qb; q < qb + 4; ++q) {
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            o[e] = sign_update(xin[q - qb][e], sgnf(R[q >> 2][e][q & 3]), args.lr, args.weight_decay);
+          gstore_f4(xp + (int64_t)(4 * q) * dcur.cols, o);
+        }
+      }
+    }
+    wave_lds_sync();
+  }
+}
+
+hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
+                                  int num_cus, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, F64D_LDS_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<false>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, F64D_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  int64_t grid = num_cus;
+  const int64_t max_grid = ((int64_t)tv.total_chunks + F64D_WAVES - 1) / F64D_WAVES;
+  if (grid > max_grid) grid = max_grid;
+  if (param_bf16)
+    hipLaunchKernelGGL(decode2d_wave64<true>, dim3((unsigned)grid), dim3(F64D_THREADS), F64D_LDS_BYTES, stream, tv,
+                       tables, a);
+  else
+    hipLaunchKernelGGL(decode2d_wave64<false>, dim3((unsigned)grid), dim3(F64D_THREADS), F64D_LDS_BYTES, stream, tv,
+                       tables, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                   int num_cus, hipStream_t stream) {
   static bool attr_set = false;

@@ -30,6 +30,7 @@ struct TableView {
   const int32_t* prefix;   // prefix[t] = first global chunk id of tensor t; prefix[n] = total
   int32_t n;
   int32_t total_chunks;
+  uint32_t dtypes;         // bit 0: some gradient is bf16, 1: some is f32, 2: some parameter is bf16, 3: some is f32
 };
 
 // Chunks a fast kernel hands over to the exact generic kernel (device memory owned by the
@@ -74,6 +75,9 @@ constexpr int kFast64TableFloats = 4 * 4096;
 constexpr int kFast64MaxK = 64;
 void build_fast64_tables(const double* P, float* out /* kFast64TableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
+                                  int num_cus, hipStream_t stream);
+
+hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   int num_cus, hipStream_t stream);
 
 }  // namespace demo

@@ -590,8 +590,10 @@ hipError_t launch_encode2d(const TableView& tv, const BasisTables& bt, int s, co
 
 hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, const DecodeArgs& a, int num_cus,
                            int variant, hipStream_t stream) {
-  (void)variant;
   if (tv.total_chunks == 0) return hipSuccess;
+  const uint32_t pmix = (tv.dtypes >> 2) & 3u;   // parameter dtypes present: the wavefront kernel wants one
+  if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.fast64 != nullptr && (pmix == 1u || pmix == 2u))
+    return launch_decode2d_wave64(tv, bt.fast64, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {
     case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);
