@@ -15,7 +15,7 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdemo.so")
+LIB_PATH = os.environ.get("DEMO_LIBRARY_PATH") or os.path.join(_HERE, "libdemo.so")
 
 DEMO_OK, DEMO_ERR_ARG, DEMO_ERR_SHAPE, DEMO_ERR_UNSUPPORTED, DEMO_ERR_HIP, DEMO_ERR_NOMEM = 0, -1, -2, -3, -4, -5
 DEMO_F32, DEMO_BF16 = 0, 1

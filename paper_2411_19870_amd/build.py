@@ -11,7 +11,7 @@ LIB = os.path.join(PKG, "libdemo.so")
 SOURCES = [os.path.join(PKG, "csrc", f) for f in ("demo_kernels.hip", "demo_fast64.hip", "demo_api.cpp")]
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, out: str = LIB, defines=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [
         hipcc, "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
@@ -19,12 +19,12 @@ def build(verbose: bool = True) -> str:
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
-        "-o", LIB,
-    ] + SOURCES
+        "-o", out,
+    ] + [f"-D{d}" for d in defines] + SOURCES
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -60,12 +60,49 @@ __device__ __forceinline__ void store4(void* __restrict__ base, int64_t off, int
   }
 }
 
-__device__ __forceinline__ float sgnf(float r) { return (r > 0.0f ? 1.0f : 0.0f) - (r < 0.0f ? 1.0f : 0.0f); }
+// sgn(r) in {-1, 0, +1}: copy the sign bit onto 1.0, then zero it for r == +-0.
+__device__ __forceinline__ float sgnf(float r) {
+  const float s = __uint_as_float((__float_as_uint(r) & 0x80000000u) | 0x3f800000u);
+  return r == 0.0f ? 0.0f : s;
+}
+
+// Two floats to packed bfloat16 (round to nearest even, hardware conversion on gfx950).
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 // x' = x - lr*(sgn + wd*x) with two float32 fused multiply-adds (update line of Algorithm 1).
 __device__ __forceinline__ float sign_update(float x, float sg, float lr, float wd) {
   float t = __fmaf_rn(wd, x, sg);
   return __fmaf_rn(-lr, t, x);
 }
+
+// Optional per-phase cycle accounting (profiling builds only: -DDEMO_PHASE_CLOCKS).  A kernel
+// marks phase boundaries with DEMO_PHASE(i); lane 0 of every wavefront adds its totals to
+// demo_phase_clocks[] when the kernel ends.
+#ifdef DEMO_PHASE_CLOCKS
+extern __device__ unsigned long long demo_phase_clocks[16];
+#define DEMO_PHASE_DECL unsigned long long ph_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long ph_t = __builtin_readcyclecounter();
+#define DEMO_PHASE(i)                                             \
+  do {                                                            \
+    __builtin_amdgcn_sched_barrier(0);                            \
+    const unsigned long long ph_now = __builtin_readcyclecounter(); \
+    ph_acc[i] += ph_now - ph_t;                                   \
+    ph_t = ph_now;                                                \
+    __builtin_amdgcn_sched_barrier(0);                            \
+  } while (0)
+#define DEMO_PHASE_FLUSH(off)                                                              \
+  do {                                                                                     \
+    if ((threadIdx.x & 63) == 0)                                                           \
+      for (int ph_i = 0; ph_i < 8; ++ph_i) atomicAdd(&demo_phase_clocks[(off) + ph_i], ph_acc[ph_i]); \
+  } while (0)
+#else
+#define DEMO_PHASE_DECL
+#define DEMO_PHASE(i)
+#define DEMO_PHASE_FLUSH(off)
+#endif
 
 }  // namespace demo

@@ -19,6 +19,18 @@
 
 namespace demo {
 
+#ifdef DEMO_PHASE_CLOCKS
+__device__ unsigned long long demo_phase_clocks[16];
+extern "C" int demo_debug_phase_clocks(unsigned long long* out16, int reset) {
+  hipError_t e = hipMemcpyFromSymbol(out16, HIP_SYMBOL(demo_phase_clocks), 16 * sizeof(unsigned long long));
+  if (e == hipSuccess && reset) {
+    unsigned long long z[16] = {};
+    e = hipMemcpyToSymbol(HIP_SYMBOL(demo_phase_clocks), z, sizeof(z));
+  }
+  return e == hipSuccess ? 0 : -4;
+}
+#endif
+
 namespace {
 
 constexpr int F64_WAVES = 8;                      // wavefronts per workgroup (2 per SIMD)
@@ -105,6 +117,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
   int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
   TensorDev d = tv.descs[t];
 
+  DEMO_PHASE_DECL
   for (; chunk < chunk_end; ++chunk) {
     while (chunk >= t_next) {
       ++t;
@@ -145,6 +158,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
     }
     __builtin_amdgcn_sched_barrier(0);
 
+    DEMO_PHASE(0);
     // ---- product 1: C1[e][nt] (rows j = 4(4g+r)+e, cols u = 16nt+c) ---------------------------
     f32x4 C1[4][4];
 #pragma unroll
@@ -165,6 +179,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
       }
     }
 
+    DEMO_PHASE(1);
     // ---- product 2: C2[mt][nt] (rows v = 16mt+4g+r, cols u = 16nt+c) = Q[u][v] -----------------
     f32x4 C2[4][4];
 #pragma unroll
@@ -186,6 +201,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
       }
     }
 
+    DEMO_PHASE(2);
     // ---- top-k inside the wavefront ------------------------------------------------------------
     // flat index of C2[mt][nt][r] in this lane: u*64 + v = (16nt+c)*64 + 16mt + 4g + r
     uint32_t flat0 = (uint32_t)(c * 64 + 4 * g);
@@ -204,6 +220,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
       const uint32_t cand = thr | (1u << bit);
       if (__popcll(__ballot(lm >= cand)) >= k) thr = cand;
     }
+    DEMO_PHASE(3);
     // (2) gather candidates |q| >= thr (one compare and one scalar branch per coefficient)
     int ncand = 0;
     {
@@ -247,6 +264,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
       }
       continue;
     }
+    DEMO_PHASE(4);
     // pad the list to an even count for the paired reads below
     if (lane == 0 && (ncand & 1)) cand_key[ncand] = make_uint2(0u, 0xffffffffu);
     wave_lds_sync();
@@ -270,6 +288,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
     if (lane >= k && lane < kpad) sel[lane] = make_uint2(0u, 0u);
     wave_lds_sync();
 
+    DEMO_PHASE(5);
     // ---- reconstruction accumulated into D: D -= sum_t val_t P[u_t][i] P[v_t][j] ----------------
     for (int ks = 0; ks < kpad / 4; ++ks) {
       const uint2 s = sel[4 * ks + g];
@@ -285,6 +304,7 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
         for (int e = 0; e < 4; ++e) D[mt][e] = mfma4(af[mt], bf[e], D[mt][e]);
     }
 
+    DEMO_PHASE(6);
     // ---- store the residual momentum -------------------------------------------------------------
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
@@ -292,7 +312,9 @@ __global__ __launch_bounds__(F64_THREADS) void encode2d_wave64(TableView tv, con
       gstore_f4(d.mom + base + (int64_t)(4 * q) * d.cols, o);
     }
     wave_lds_sync();   // the lists are rewritten by the next chunk
+    DEMO_PHASE(7);
   }
+  DEMO_PHASE_FLUSH(0);
 }
 
 // ---------------------------------------------------------------------------
@@ -311,7 +333,9 @@ constexpr int F64D_TILE_FLOATS = 64 * F64D_LDT;
 constexpr int F64D_LDS_BYTES = 4 * (2 * 4096 + F64D_WAVES * F64D_TILE_FLOATS);
 }  // namespace
 
-template <bool PBF16>   // parameter dtype of every tensor in the table
+// PBF16: parameter dtype of every tensor in the table.  FULL: k == 32 and W a multiple of 64, so
+// every payload load instruction is fully populated (two workers x 32 pairs) and needs no predicate.
+template <bool PBF16, bool FULL>
 __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                 DecodeArgs args) {
   extern __shared__ float lds[];
@@ -321,7 +345,7 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
   float* tile = lds + 2 * 4096 + wave * F64D_TILE_FLOATS;
-  const int k = args.k, W = args.W;
+  const int k = FULL ? 32 : args.k, W = args.W;
 
   for (int e = tid; e < 2 * 4096 / 4; e += F64D_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + 2 * 4096)[e];
@@ -336,10 +360,11 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
   if (chunk >= chunk_end) return;
 
   // payload lanes: with k <= 32 one load instruction fetches the pairs of two workers
-  const int wpi = k <= 32 ? 2 : 1;                       // workers per load instruction
+  const int wpi = (FULL || k <= 32) ? 2 : 1;             // workers per load instruction
   const int sub = wpi == 2 ? (lane >> 5) : 0;            // which of them this lane serves
   const int pt = wpi == 2 ? (lane & 31) : lane;          // pair index inside the chunk
-  const bool pact = pt < k;
+  const bool pact = FULL || pt < k;
+  const uint32_t dummy = (uint32_t)(lane * F64D_LDT + 64);   // a pad slot of this lane: absorbs masked-off additions
   constexpr int NLI = 32;                                // load instructions per group of workers
   int32_t pi[NLI];
   float pv[NLI];
@@ -351,26 +376,47 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
     const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)ccc * k + (int64_t)wbase * wstride;
 #pragma unroll
     for (int j = 0; j < NLI; ++j) {
-      const bool ok = pact && wbase + j * wpi + sub < W;
-      pi[j] = ok ? ip[lane_off] : -1;
-      pv[j] = ok ? vp[lane_off] : 0.f;
+      if (FULL) {
+        pi[j] = ip[lane_off];
+        pv[j] = vp[lane_off];
+      } else {
+        const bool ok = pact && wbase + j * wpi + sub < W;
+        pi[j] = ok ? ip[lane_off] : -1;
+        pv[j] = ok ? vp[lane_off] : 0.f;
+      }
       ip += wpi * wstride;
       vp += wpi * wstride;
     }
   };
-  // S[idx] += val with one worker per LDS instruction, in worker order: indices inside one
-  // worker's chunk are distinct, so every slot receives its additions in worker order
+  // S[idx] += val in block fixed point.  LDS float atomics are an order of magnitude slower than
+  // integer ones on this part, and an integer sum does not depend on the order of arrival, so the
+  // coefficients are scaled by a power of two taken from the largest magnitude of the chunk's
+  // payload (exact), rounded to integers of `vbits` bits and added with ds_add_u32; W such
+  // values cannot overflow 31 bits.  Only sgn(IDCT(S)) is used, so the scale is never undone.
+  // Lanes with nothing to add (inactive pair, index out of range) add zero into their pad slot.
+  int* itile = reinterpret_cast<int*>(tile);
+  int vbits = 30;
+  for (int w = 1; w < W; w <<= 1) --vbits;                // 30 - ceil(log2 W)
   auto scatter = [&]() {
+    float mx = 0.f;
+#pragma unroll
+    for (int j = 0; j < NLI; ++j) mx = fmaxf(mx, fabsf(pv[j]));
+    uint32_t mb = __float_as_uint(mx);
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x141, 0xf, 0xf, false));  // row_half_mirror
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
+    const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
+    const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
+    int ex = (int)(max(m01, m23) >> 23);                  // biased exponent of the largest magnitude
+    ex = ex < 1 ? 1 : ex;
+    const int sh = vbits + 126 - ex;                      // max |val| * 2^sh < 2^vbits
 #pragma unroll
     for (int j = 0; j < NLI; ++j) {
-      const bool ok = pi[j] >= 0 && pi[j] < 4096;
-      const int a = (pi[j] >> 6) * F64D_LDT + (pi[j] & 63);
-      if (ok && sub == 0) atomicAdd(&tile[a], pv[j]);
-      if (wpi == 2) {
-        wave_lds_sync();   // keeps the two workers in two separate, ordered LDS instructions
-        if (ok && sub == 1) atomicAdd(&tile[a], pv[j]);
-      }
-      wave_lds_sync();
+      const uint32_t u = (uint32_t)pi[j];
+      const uint32_t a = u < 4096u ? u + ((u >> 6) << 2) : dummy;   // (u / 64) * 68 + u % 64
+      const int q = __float2int_rn(ldexpf(pv[j], sh));
+      atomicAdd(&itile[a], q);
     }
   };
 
@@ -378,22 +424,21 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
   int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
   TensorDev d = tv.descs[t];
   load_payload(d, chunk - t_first, 0);
+  DEMO_PHASE_DECL
 
   for (; chunk < chunk_end; ++chunk) {
     const int cc = chunk - t_first;
     const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
     const int64_t base = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64 + (int64_t)g * d.cols + 4 * c;
     const TensorDev dcur = d;
+    DEMO_PHASE(0);
 
     // ---- S = sum over workers ---------------------------------------------------------------------------
 #pragma unroll
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    scatter();
-    for (int wbase = NLI * wpi; wbase < W; wbase += NLI * wpi) {   // more workers than one group holds
-      load_payload(dcur, cc, wbase);
-      scatter();
-    }
+    scatter();   // the launch wrapper guarantees that one group of NLI load instructions holds all W workers
+    DEMO_PHASE(1);
     // ---- payload of the next chunk, in flight during the products -----------------------------------------
     if (chunk + 1 < chunk_end) {
       while (chunk + 1 >= t_next) {
@@ -406,26 +451,41 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
     }
     wave_lds_sync();
 
+    DEMO_PHASE(2);
     // ---- product a: Ya[mt][e] (rows u = 16mt+4g+r, cols j = 4c+e) --------------------------------------
+    // k-step 4kg + kr contracts v = 16kg + 4g + kr: four k-steps per 16-byte LDS read of S.
+    // Operands of the next k-step are read while the MFMAs of the current one run.
     f32x4 Ya[4][4];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
       for (int e = 0; e < 4; ++e) Ya[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      float4 sa[4], sn[4];
 #pragma unroll
-    for (int kg = 0; kg < 4; ++kg) {
-      // k-step ks = 4kg + kr contracts v = 16kg + 4g + kr: four k-steps per 16-byte LDS read of S
-      float4 sa[4];
+      for (int mt = 0; mt < 4; ++mt) sn[mt] = *reinterpret_cast<const float4*>(&tile[(16 * mt + c) * F64D_LDT + 4 * g]);
+      float4 pn = *reinterpret_cast<const float4*>(&sPplain[(4 * g) * 64 + 4 * c]);
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-        sa[mt] = *reinterpret_cast<const float4*>(&tile[(16 * mt + c) * F64D_LDT + 16 * kg + 4 * g]);
+      for (int ks = 0; ks < 16; ++ks) {
+        const int kg = ks >> 2, kr = ks & 3;
+        if (kr == 0) {
 #pragma unroll
-      for (int kr = 0; kr < 4; ++kr) {
-        const float4 pb = *reinterpret_cast<const float4*>(&sPplain[(16 * kg + 4 * g + kr) * 64 + 4 * c]);
-        const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+          for (int mt = 0; mt < 4; ++mt) sa[mt] = sn[mt];
+          if (kg + 1 < 4) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+              sn[mt] = *reinterpret_cast<const float4*>(&tile[(16 * mt + c) * F64D_LDT + 16 * (kg + 1) + 4 * g]);
+          }
+        }
+        const float bf[4] = {pn.x, pn.y, pn.z, pn.w};
+        if (ks + 1 < 16) {
+          const int kg2 = (ks + 1) >> 2, kr2 = (ks + 1) & 3;
+          pn = *reinterpret_cast<const float4*>(&sPplain[(16 * kg2 + 4 * g + kr2) * 64 + 4 * c]);
+        }
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
-          const float a = kr == 0 ? sa[mt].x : kr == 1 ? sa[mt].y : kr == 2 ? sa[mt].z : sa[mt].w;
+          const float ai = kr == 0 ? sa[mt].x : kr == 1 ? sa[mt].y : kr == 2 ? sa[mt].z : sa[mt].w;
+          const float a = (float)__float_as_int(ai);      // the tile holds fixed-point sums
 #pragma unroll
           for (int e = 0; e < 4; ++e) Ya[mt][e] = mfma4(a, bf[e], Ya[mt][e]);
         }
@@ -433,6 +493,7 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
       }
     }
 
+    DEMO_PHASE(3);
     // ---- product b: R[mt'][e] component r' = element (row 4(4mt'+r')+g, col 4c+e) --------------------------
     f32x4 R[4][4];
     u32x2 Xh[16];   // bf16 parameters, raw
@@ -440,36 +501,42 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
       for (int e = 0; e < 4; ++e) R[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      float4 pn = *reinterpret_cast<const float4*>(&sPperm[(4 * g) * 64 + 4 * c]);
 #pragma unroll
-    for (int mr = 0; mr < 16; ++mr) {
-      const int mt = mr >> 2, r = mr & 3;
-      const float4 pa = *reinterpret_cast<const float4*>(&sPperm[(16 * mt + 4 * g + r) * 64 + 4 * c]);
-      const float af[4] = {pa.x, pa.y, pa.z, pa.w};
+      for (int mr = 0; mr < 16; ++mr) {
+        const int mt = mr >> 2, r = mr & 3;
+        const float af[4] = {pn.x, pn.y, pn.z, pn.w};
+        if (mr + 1 < 16) {
+          const int mt2 = (mr + 1) >> 2, r2 = (mr + 1) & 3;
+          pn = *reinterpret_cast<const float4*>(&sPperm[(16 * mt2 + 4 * g + r2) * 64 + 4 * c]);
+        }
 #pragma unroll
-      for (int m2 = 0; m2 < 4; ++m2)
+        for (int m2 = 0; m2 < 4; ++m2)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) R[m2][e] = mfma4(af[m2], Ya[mt][e][r], R[m2][e]);
-      if (PBF16 && r == 3) {
-        // a quarter of the product-a accumulators is dead: use the registers for the parameters
-        const uint16_t* xp = static_cast<const uint16_t*>(dcur.param) + base;
+          for (int e = 0; e < 4; ++e) R[m2][e] = mfma4(af[m2], Ya[mt][e][r], R[m2][e]);
+        if (PBF16 && r == 3) {
+          // a quarter of the product-a accumulators is dead: use the registers for the parameters
+          const uint16_t* xp = static_cast<const uint16_t*>(dcur.param) + base;
 #pragma unroll
-        for (int q = 4 * mt; q < 4 * mt + 4; ++q) Xh[q] = gload_u2(xp + (int64_t)(4 * q) * dcur.cols);
+          for (int q = 4 * mt; q < 4 * mt + 4; ++q) Xh[q] = gload_u2(xp + (int64_t)(4 * q) * dcur.cols);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
 
+    DEMO_PHASE(4);
     // ---- x <- x - lr*(sgn(R) + wd*x) ---------------------------------------------------------------------
     if (PBF16) {
       uint16_t* xp = static_cast<uint16_t*>(dcur.param) + base;
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
-        const float x[4] = {bf16_to_f32(Xh[q][0] & 0xffffu), bf16_to_f32(Xh[q][0] >> 16),
-                            bf16_to_f32(Xh[q][1] & 0xffffu), bf16_to_f32(Xh[q][1] >> 16)};
+        const float x[4] = {__uint_as_float(Xh[q][0] << 16), __uint_as_float(Xh[q][0] & 0xffff0000u),
+                            __uint_as_float(Xh[q][1] << 16), __uint_as_float(Xh[q][1] & 0xffff0000u)};
         float o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = sign_update(x[e], sgnf(R[q >> 2][e][q & 3]), args.lr, args.weight_decay);
-        const u32x2 pk = {f32_to_bf16_rne(o[0]) | (f32_to_bf16_rne(o[1]) << 16),
-                          f32_to_bf16_rne(o[2]) | (f32_to_bf16_rne(o[3]) << 16)};
+        const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
         gstore_u2(xp + (int64_t)(4 * q) * dcur.cols, pk);
       }
     } else {
@@ -491,31 +558,37 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
       }
     }
     wave_lds_sync();
+    DEMO_PHASE(5);
   }
+  DEMO_PHASE_FLUSH(8);
+}
+
+template <bool PBF16, bool FULL>
+static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
+                                    hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, FULL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, F64D_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((decode2d_wave64<PBF16, FULL>), dim3((unsigned)grid), dim3(F64D_THREADS), F64D_LDS_BYTES, stream,
+                     tv, tables, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   int num_cus, hipStream_t stream) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, F64D_LDS_BYTES);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<false>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, F64D_LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tv.total_chunks + F64D_WAVES - 1) / F64D_WAVES;
   if (grid > max_grid) grid = max_grid;
+  const bool full = a.k == 32 && a.W == 64;
   if (param_bf16)
-    hipLaunchKernelGGL(decode2d_wave64<true>, dim3((unsigned)grid), dim3(F64D_THREADS), F64D_LDS_BYTES, stream, tv,
-                       tables, a);
-  else
-    hipLaunchKernelGGL(decode2d_wave64<false>, dim3((unsigned)grid), dim3(F64D_THREADS), F64D_LDS_BYTES, stream, tv,
-                       tables, a);
-  return hipGetLastError();
+    return full ? launch_dec_wave64<true, true>(tv, tables, a, grid, stream)
+                : launch_dec_wave64<true, false>(tv, tables, a, grid, stream);
+  return full ? launch_dec_wave64<false, true>(tv, tables, a, grid, stream)
+              : launch_dec_wave64<false, false>(tv, tables, a, grid, stream);
 }
 
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,

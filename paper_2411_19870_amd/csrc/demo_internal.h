@@ -77,6 +77,8 @@ void build_fast64_tables(const double* P, float* out /* kFast64TableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                   int num_cus, hipStream_t stream);
 
+// The decode kernel keeps all W workers' pairs of a chunk in registers: W <= 64 when k <= 32, W <= 32 above.
+inline bool fast64_decode_supports(int W, int k) { return k <= kFast64MaxK && W <= (k <= 32 ? 64 : 32); }
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   int num_cus, hipStream_t stream);
 

@@ -592,7 +592,7 @@ hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, co
                            int variant, hipStream_t stream) {
   if (tv.total_chunks == 0) return hipSuccess;
   const uint32_t pmix = (tv.dtypes >> 2) & 3u;   // parameter dtypes present: the wavefront kernel wants one
-  if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.fast64 != nullptr && (pmix == 1u || pmix == 2u))
+  if (variant >= 1 && s == 64 && fast64_decode_supports(a.W, a.k) && bt.fast64 != nullptr && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wave64(tv, bt.fast64, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {
