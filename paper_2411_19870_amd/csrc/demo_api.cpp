@@ -20,7 +20,8 @@ using demo::TensorDev;
 struct BasisTable {
   int s = 0;
   float* dev = nullptr;      // P, s x s
-  float* fast64 = nullptr;   // fragment tables of the s = 64 wavefront-per-chunk kernels
+  float* enc64 = nullptr;    // tables of the s = 64 wavefront-per-chunk kernels
+  float* dec64 = nullptr;
 };
 
 // One cached descriptor upload: the host bytes it was built from and the device copy.
@@ -132,7 +133,7 @@ int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
 
 int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   for (const BasisTable& b : ctx->bases)
-    if (b.s == s) { out->basis = b.dev; out->fast64 = b.fast64; return DEMO_OK; }
+    if (b.s == s) { *out = demo::BasisTables{b.dev, b.enc64, b.dec64}; return DEMO_OK; }
   std::vector<double> P((size_t)s * s);
   const double pi = 3.14159265358979323846;
   for (int u = 0; u < s; ++u) {
@@ -145,13 +146,14 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   int rc = upload(ctx, host, &b.dev);
   if (rc != DEMO_OK) return rc;
   if (s == 64) {
-    std::vector<float> ft(demo::kFast64TableFloats);
-    demo::build_fast64_tables(P.data(), ft.data());
-    if ((rc = upload(ctx, ft, &b.fast64)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
+    std::vector<float> et(demo::kEnc64TableFloats), dt(demo::kDec64TableFloats);
+    demo::build_enc64_tables(P.data(), et.data());
+    demo::build_dec64_tables(P.data(), dt.data());
+    if ((rc = upload(ctx, et, &b.enc64)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
+    if ((rc = upload(ctx, dt, &b.dec64)) != DEMO_OK) { (void)hipFree(b.dev); (void)hipFree(b.enc64); return rc; }
   }
   ctx->bases.push_back(b);
-  out->basis = b.dev;
-  out->fast64 = b.fast64;
+  *out = demo::BasisTables{b.dev, b.enc64, b.dec64};
   return DEMO_OK;
 }
 
@@ -335,7 +337,11 @@ int demo_destroy(demo_ctx* ctx) {
   if (ctx == nullptr) return DEMO_ERR_ARG;
   if (ctx->device >= 0) {
     (void)hipDeviceSynchronize();
-    for (BasisTable& b : ctx->bases) { (void)hipFree(b.dev); if (b.fast64) (void)hipFree(b.fast64); }
+    for (BasisTable& b : ctx->bases) {
+      (void)hipFree(b.dev);
+      if (b.enc64) (void)hipFree(b.enc64);
+      if (b.dec64) (void)hipFree(b.dec64);
+    }
     for (TableCache& tc : ctx->tables)
       if (tc.dev) (void)hipFree(tc.dev);
     for (int i = 0; i < kNumTimers; ++i)

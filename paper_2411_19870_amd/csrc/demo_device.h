@@ -80,11 +80,54 @@ __device__ __forceinline__ float sign_update(float x, float sg, float lr, float 
   return __fmaf_rn(-lr, t, x);
 }
 
+// Raw buffer access: a uniform base (resource descriptor in SGPRs) plus a 32-bit per-lane byte
+// offset and a uniform byte offset.  Keeps per-lane addressing to one VGPR per access pattern.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ f32x4 bload_f4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ u32x2 bload_u2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ void bstore_f4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, f32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)voff, (int)soff, 0);
+}
+__device__ __forceinline__ void bstore_u2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, u32x2 v) {
+  __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, 0);
+}
+
+__device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// LDS operations of one wavefront execute in order; this only stops the compiler from moving
+// LDS accesses across the point.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// number of lanes below this one whose bit is set in mask
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
 // Optional per-phase cycle accounting (profiling builds only: -DDEMO_PHASE_CLOCKS).  A kernel
 // marks phase boundaries with DEMO_PHASE(i); lane 0 of every wavefront adds its totals to
 // demo_phase_clocks[] when the kernel ends.
 #ifdef DEMO_PHASE_CLOCKS
-extern __device__ unsigned long long demo_phase_clocks[16];
+static __device__ unsigned long long demo_phase_clocks[16];   // one copy per translation unit
+#define DEMO_PHASE_GETTER(name)                                                                              \
+  extern "C" int name(unsigned long long* out16, int reset) {                                               \
+    hipError_t e = hipMemcpyFromSymbol(out16, HIP_SYMBOL(demo::demo_phase_clocks), 16 * sizeof(unsigned long long)); \
+    if (e == hipSuccess && reset) {                                                                         \
+      unsigned long long z[16] = {};                                                                        \
+      e = hipMemcpyToSymbol(HIP_SYMBOL(demo::demo_phase_clocks), z, sizeof(z));                             \
+    }                                                                                                       \
+    return e == hipSuccess ? 0 : -4;                                                                        \
+  }
 #define DEMO_PHASE_DECL unsigned long long ph_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long ph_t = __builtin_readcyclecounter();
 #define DEMO_PHASE(i)                                             \
   do {                                                            \
@@ -100,6 +143,7 @@ extern __device__ unsigned long long demo_phase_clocks[16];
       for (int ph_i = 0; ph_i < 8; ++ph_i) atomicAdd(&demo_phase_clocks[(off) + ph_i], ph_acc[ph_i]); \
   } while (0)
 #else
+#define DEMO_PHASE_GETTER(name)
 #define DEMO_PHASE_DECL
 #define DEMO_PHASE(i)
 #define DEMO_PHASE_FLUSH(off)

@@ -1,0 +1,402 @@
+// s = 64 encode kernel: one wavefront per 64 x 64 chunk, everything register resident.
+//
+// Register layout.  Lane l = 16 g + c.  For q = 4 s + w (s, w in 0..3) the lane loads the four
+// consecutive floats  D[q][e] = B[rho(q,g)][4 chi(c) + e],  e = 0..3, where
+//     rho(4s+w, g) = { i0, 31-i0, 32+i0, 63-i0 }[w],  i0 = 4s + g          (rows)
+//     chi(4a+b)    = { a, 7-a, 8+a, 15-a }[b]                              (16-byte column groups)
+// so 16 lanes still cover one 256-byte row per load instruction, and every lane holds, for each
+// of its columns, complete mirror quadruples {i, 31-i, 32+i, 63-i} of rows.
+//
+// Transform.  Row u of the orthonormal DCT-II matrix P is even or odd under i -> 63-i according
+// to the parity of u, and rows u = 0 mod 4 / 2 mod 4 are even / odd under i -> 31-i as well.  Two
+// in-lane butterfly levels on each quadruple therefore split the 64-point transform into a
+// 16 x 16 product (u = 4b), another 16 x 16 (u = 4b+2) and a 32 x 32 one (u odd): 3/8 of the
+// multiply-adds of the dense product.  Q = P B P^T is computed as two chains of
+// v_mfma_f32_16x16x4_f32 whose data operands never leave the register file:
+//     product 1   T^T[j][u] = sum_i B[i][j] P[u][i]     A = butterflies of D,  B = basis fragments
+//     product 2   Q^T[v][u] = sum_j P[v][j] T^T[j][u]   A = basis fragments,   B = butterflies of the
+//                                                       product-1 accumulators
+// (an accumulator tile holds rows 4g + r in lane group g, the k-slot layout of a B operand; the
+// column-group map chi makes the mirror quadruples of j land in one lane as well).  Coefficient
+// tiles come out in the order u = {4c, 4c+2, 2c+1, 2c+33}, v likewise with c -> 4g + r.
+//
+// Top-k runs inside the wavefront on the 64 coefficients each lane holds; the reconstruction
+// m - P^T Q^ P is one more MFMA chain of contraction length k that accumulates straight into D,
+// which is then stored with the load pattern.  LDS holds the basis fragment tables and a small
+// candidate list per wavefront.
+#include "demo_device.h"
+
+namespace demo {
+
+
+namespace {
+
+constexpr int E64_WAVES = 8;                      // wavefronts per workgroup (2 per SIMD)
+constexpr int E64_THREADS = E64_WAVES * 64;
+constexpr int E64_CAP = 128;                      // candidate list capacity per wavefront
+constexpr int E64_T1 = 0;                         // product-1 fragments: 6 groups x 64 lanes x 4
+constexpr int E64_T2 = 1536;                      // product-2 fragments
+constexpr int E64_PCOL = 3072;                    // pcol[v*64 + 4c + e]  = P[v][4 chi(c) + e]
+constexpr int E64_PROW = 3072 + 4096;             // prow[u*64 + 4c + m]  = P[u][rho(4m + c%4, c/4)]
+constexpr int E64_TABLE_FLOATS = 3072 + 2 * 4096;
+// per-wavefront scratch: candidates {value bits, flat index} [CAP + 2], selected {flat, value bits} [64]
+constexpr int E64_SCRATCH_WORDS = 2 * (E64_CAP + 2) + 2 * 64;
+constexpr int E64_LDS_BYTES = 4 * (E64_TABLE_FLOATS + E64_WAVES * E64_SCRATCH_WORDS);
+static_assert(E64_TABLE_FLOATS == kEnc64TableFloats, "table size");
+
+// host and device agree on these maps
+__host__ __device__ constexpr int rho(int q, int g) {
+  return (q & 3) == 0 ? 4 * (q >> 2) + g : (q & 3) == 1 ? 31 - (4 * (q >> 2) + g) : (q & 3) == 2 ? 32 + 4 * (q >> 2) + g
+                                                                                                   : 63 - (4 * (q >> 2) + g);
+}
+__host__ __device__ constexpr int chi(int c) {
+  return (c & 3) == 0 ? (c >> 2) : (c & 3) == 1 ? 7 - (c >> 2) : (c & 3) == 2 ? 8 + (c >> 2) : 15 - (c >> 2);
+}
+// frequency held by column / row m (0..15) of coefficient tile t (0..3)
+__host__ __device__ constexpr int freq(int t, int m) { return t == 0 ? 4 * m : t == 1 ? 4 * m + 2 : t == 2 ? 2 * m + 1 : 2 * m + 33; }
+
+}  // namespace
+
+void build_enc64_tables(const double* P, float* out) {
+  auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
+  for (int lane = 0; lane < 64; ++lane) {
+    const int g = lane >> 4, c = lane & 15;
+    for (int s = 0; s < 4; ++s) {
+      // product 1: k-slot g of step s contracts row index i0 = 4s + g (or its mirror 31 - i0)
+      const int i0 = 4 * s + g;
+      out[E64_T1 + (0 * 64 + lane) * 4 + s] = Pm(4 * c, i0);
+      out[E64_T1 + (1 * 64 + lane) * 4 + s] = Pm(4 * c + 2, i0);
+      for (int w = 0; w < 2; ++w)
+        for (int nt = 0; nt < 2; ++nt)
+          out[E64_T1 + ((2 + s) * 64 + lane) * 4 + 2 * w + nt] = Pm(2 * (16 * nt + c) + 1, w ? 31 - i0 : i0);
+      // product 2: k-slot g of step s contracts column index j0 = 4g + s (or 31 - j0); A rows = v
+      const int j0 = 4 * g + s;
+      out[E64_T2 + (0 * 64 + lane) * 4 + s] = Pm(4 * c, j0);
+      out[E64_T2 + (1 * 64 + lane) * 4 + s] = Pm(4 * c + 2, j0);
+      for (int w = 0; w < 2; ++w)
+        for (int mt = 0; mt < 2; ++mt)
+          out[E64_T2 + ((2 + s) * 64 + lane) * 4 + 2 * w + mt] = Pm(2 * (16 * mt + c) + 1, w ? 31 - j0 : j0);
+    }
+  }
+  for (int u = 0; u < 64; ++u)
+    for (int cc = 0; cc < 16; ++cc)
+      for (int x = 0; x < 4; ++x) {
+        out[E64_PCOL + u * 64 + 4 * cc + x] = Pm(u, 4 * chi(cc) + x);
+        out[E64_PROW + u * 64 + 4 * cc + x] = Pm(u, rho(4 * x + (cc & 3), cc >> 2));
+      }
+}
+
+// the six values two butterfly levels make of a mirror quadruple (x[i], x[31-i], x[32+i], x[63-i])
+struct Bfly {
+  float ee, eo, o0, o1;
+};
+__device__ __forceinline__ Bfly butterfly(float x0, float x1, float x2, float x3) {
+  const float e0 = x0 + x3, e1 = x1 + x2;
+  return Bfly{e0 + e1, e0 - e1, x0 - x3, x1 - x2};
+}
+
+template <bool GBF16>   // gradient dtype of every tensor in the table
+__global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, const float* __restrict__ tables,
+                                                               EncodeArgs args, Worklist wl) {
+  extern __shared__ float lds[];
+  const float* sT1 = lds + E64_T1;
+  const float* sT2 = lds + E64_T2;
+  const float* sPcol = lds + E64_PCOL;
+  const float* sProw = lds + E64_PROW;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c = lane & 15;
+  uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + E64_TABLE_FLOATS) + wave * E64_SCRATCH_WORDS;
+  uint2* cand = reinterpret_cast<uint2*>(scratch);                       // {value bits, flat index}
+  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (E64_CAP + 2));    // {flat index, value bits}, rank order
+  const int k = args.k;
+  const int kpad = (k + 3) & ~3;
+
+  for (int e = tid; e < E64_TABLE_FLOATS / 4; e += E64_THREADS)
+    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
+  __syncthreads();
+
+  // contiguous range of chunks for this wavefront
+  const int nwaves = gridDim.x * E64_WAVES;
+  const int wid = blockIdx.x * E64_WAVES + wave;
+  const int total = tv.total_chunks;
+  const int per = total / nwaves, rem = total - per * nwaves;
+  int chunk = wid * per + (wid < rem ? wid : rem);
+  const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
+  if (chunk >= chunk_end) return;
+  int t = find_tensor(tv.prefix, tv.n, chunk);
+  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
+  TensorDev d = tv.descs[t];
+
+  // lane constants: column offset, and flat-index bases u(t,c)*64 + v(vt,4g) of the coefficient tiles
+  const int col4 = 4 * chi(c);
+  uint32_t fb_a = (uint32_t)(256 * c + 16 * g), fb_b = (uint32_t)(256 * c + 8 * g);
+  uint32_t fb_c = (uint32_t)(128 * c + 16 * g), fb_d = (uint32_t)(128 * c + 8 * g);
+
+  DEMO_PHASE_DECL
+  for (; chunk < chunk_end; ++chunk) {
+    while (chunk >= t_next) {
+      ++t;
+      t_first = t_next;
+      t_next = tv.prefix[t + 1];
+      d = tv.descs[t];
+    }
+    const int cc = chunk - t_first;
+    const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
+    const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
+    // row rho(4s+w, g) = rbase(s,w) + (w even ? g : 3 - g): a uniform part (scalar offset) and one of
+    // two per-lane offsets
+    const uint32_t ucols = (uint32_t)d.cols;
+    const uint32_t vo_up = (uint32_t)g * ucols + (uint32_t)col4;         // elements
+    const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
+    const __amdgpu_buffer_rsrc_t mres = make_rsrc(d.mom + origin);
+    auto rbase = [](int q) { return (q & 3) == 0 ? 4 * (q >> 2) : (q & 3) == 1 ? 28 - 4 * (q >> 2) : (q & 3) == 2 ? 32 + 4 * (q >> 2) : 60 - 4 * (q >> 2); };
+
+    // ---- load and momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ----
+    f32x4 D[4][4];
+    if (GBF16) {
+      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const uint16_t*>(d.grad) + origin);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rbase(q) * ucols;
+        const u32x2 gr = bload_u2(gres, vo * 2, so * 2);
+        const f32x4 mo = bload_f4(mres, vo * 4, so * 4);
+        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, mo[0], __uint_as_float(gr[0] << 16));
+        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, mo[1], __uint_as_float(gr[0] & 0xffff0000u));
+        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, mo[2], __uint_as_float(gr[1] << 16));
+        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, mo[3], __uint_as_float(gr[1] & 0xffff0000u));
+      }
+    } else {
+      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const float*>(d.grad) + origin);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rbase(q) * ucols;
+        const f32x4 gr = bload_f4(gres, vo * 4, so * 4);
+        const f32x4 mo = bload_f4(mres, vo * 4, so * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, mo[e], gr[e]);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    DEMO_PHASE(0);
+    // ---- product 1: C1[e][t] rows j = 4 chi(4g+r) + e, cols u = freq(t, c) ------------------------
+    f32x4 C1[4][4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) C1[e][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      const float4 pee4 = *reinterpret_cast<const float4*>(&sT1[(0 * 64 + lane) * 4]);
+      const float4 peo4 = *reinterpret_cast<const float4*>(&sT1[(1 * 64 + lane) * 4]);
+      const float pee[4] = {pee4.x, pee4.y, pee4.z, pee4.w}, peo[4] = {peo4.x, peo4.y, peo4.z, peo4.w};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float4 po4 = *reinterpret_cast<const float4*>(&sT1[((2 + s) * 64 + lane) * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const Bfly b = butterfly(D[s][e][0], D[s][e][1], D[s][e][2], D[s][e][3]);
+          C1[e][0] = mfma4(b.ee, pee[s], C1[e][0]);
+          C1[e][1] = mfma4(b.eo, peo[s], C1[e][1]);
+          C1[e][2] = mfma4(b.o0, po4.x, C1[e][2]);
+          C1[e][3] = mfma4(b.o0, po4.y, C1[e][3]);
+          C1[e][2] = mfma4(b.o1, po4.z, C1[e][2]);
+          C1[e][3] = mfma4(b.o1, po4.w, C1[e][3]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    DEMO_PHASE(1);
+    // ---- product 2: C2[vt][t] rows v = freq(vt, 4g+r), cols u = freq(t, c): Q[u][v] ----------------
+    f32x4 C2[4][4];
+#pragma unroll
+    for (int vt = 0; vt < 4; ++vt)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      const float4 pee4 = *reinterpret_cast<const float4*>(&sT2[(0 * 64 + lane) * 4]);
+      const float4 peo4 = *reinterpret_cast<const float4*>(&sT2[(1 * 64 + lane) * 4]);
+      const float pee[4] = {pee4.x, pee4.y, pee4.z, pee4.w}, peo[4] = {peo4.x, peo4.y, peo4.z, peo4.w};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float4 po4 = *reinterpret_cast<const float4*>(&sT2[((2 + s) * 64 + lane) * 4]);
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+          // mirror quadruple of j0 = 4g + s: registers (e, r) = (s,0), (3-s,1), (s,2), (3-s,3)
+          const Bfly b = butterfly(C1[s][tt][0], C1[3 - s][tt][1], C1[s][tt][2], C1[3 - s][tt][3]);
+          C2[0][tt] = mfma4(pee[s], b.ee, C2[0][tt]);
+          C2[1][tt] = mfma4(peo[s], b.eo, C2[1][tt]);
+          C2[2][tt] = mfma4(po4.x, b.o0, C2[2][tt]);
+          C2[3][tt] = mfma4(po4.y, b.o0, C2[3][tt]);
+          C2[2][tt] = mfma4(po4.z, b.o1, C2[2][tt]);
+          C2[3][tt] = mfma4(po4.w, b.o1, C2[3][tt]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    DEMO_PHASE(2);
+    // ---- top-k inside the wavefront ------------------------------------------------------------
+    // (1) a lower bound of the k-th largest magnitude: the k-th largest of the 64 per-lane maxima,
+    //     resolved to its upper 16 bits
+    float lmax = 0.f;
+#pragma unroll
+    for (int vt = 0; vt < 4; ++vt)
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) lmax = fmaxf(lmax, fabsf(C2[vt][tt][r]));
+    const uint32_t lm = __float_as_uint(lmax);
+    uint32_t thr = 0;
+    for (int bit = 30; bit >= 16; --bit) {
+      const uint32_t cnd = thr | (1u << bit);
+      if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
+    }
+    DEMO_PHASE(3);
+    // (2) gather candidates |q| >= thr: one compare and one scalar branch per coefficient
+    int ncand = 0;
+    // (keeps the 64 per-register flat indices from being precomputed outside the chunk loop)
+    asm volatile("" : "+v"(fb_a), "+v"(fb_b), "+v"(fb_c), "+v"(fb_d));
+    {
+      const float thr_f = __uint_as_float(thr);
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float q = C2[vt][tt][r];
+            const bool is = fabsf(q) >= thr_f;
+            const uint64_t mask = __ballot(is);
+            if (mask != 0) {
+              if (is) {
+                const int pos = min(ncand + lanes_below(mask), E64_CAP);
+                const uint32_t fbase = tt < 2 ? (vt < 2 ? fb_a : fb_b) : (vt < 2 ? fb_c : fb_d);
+                const uint32_t fconst = (uint32_t)(64 * freq(tt, 0) + freq(vt, r));
+                cand[pos] = make_uint2(__float_as_uint(q), fbase + fconst);
+              }
+              ncand += __popcll(mask);
+            }
+          }
+    }
+    if (ncand > E64_CAP) {
+      // Many (near-)equal magnitudes at the threshold (an all-zero chunk is the common case).
+      if (__ballot(lm != 0u) == 0) {
+        // every coefficient is zero: the k lowest flat indices, zero values, momentum stays zero
+        if (lane < k) {
+          const int64_t po = (int64_t)cc * k + lane;
+          as_global(d.idx)[po] = lane;
+          as_global(d.val)[po] = 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
+          bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
+        }
+      } else {
+        // leave the chunk untouched and queue it for the exact workgroup kernel that runs next
+        if (lane == 0) wl.list[atomicAdd(wl.count, 1)] = chunk;
+      }
+      continue;
+    }
+    DEMO_PHASE(4);
+    wave_lds_sync();
+    // (3) rank candidates (magnitude descending, flat index ascending); ranks < k are the payload
+    if (ncand <= 64) {
+      // one candidate per lane; the others' keys come through v_readlane
+      const uint2 me = cand[lane < ncand ? lane : 0];
+      const uint32_t mag = me.x & 0x7fffffffu, nfl = ~me.y;
+      const uint64_t key = ((uint64_t)mag << 32) | nfl;
+      int rank = 0;
+      for (int j = 0; j < ncand; ++j) {
+        const uint64_t kj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mag, j) << 32) |
+                            (uint32_t)__builtin_amdgcn_readlane((int)nfl, j);
+        rank += kj > key ? 1 : 0;
+      }
+      if (lane < ncand && rank < k) {
+        const int64_t po = (int64_t)cc * k + rank;
+        as_global(d.idx)[po] = (int32_t)me.y;
+        as_global(d.val)[po] = __uint_as_float(me.x);
+        sel[rank] = make_uint2(me.y, me.x);
+      }
+    } else {
+      if (lane == 0 && (ncand & 1)) cand[ncand] = make_uint2(0u, 0xffffffffu);
+      wave_lds_sync();
+      for (int i = lane; i < ncand; i += 64) {
+        const uint2 me = cand[i];
+        const uint32_t mag = me.x & 0x7fffffffu;
+        int rank = 0;
+        for (int j = 0; j < ncand; j += 2) {
+          const uint4 o = *reinterpret_cast<const uint4*>(&cand[j]);
+          const uint32_t m0 = o.x & 0x7fffffffu, m1 = o.z & 0x7fffffffu;
+          rank += (m0 > mag || (m0 == mag && o.y < me.y)) ? 1 : 0;
+          rank += (m1 > mag || (m1 == mag && o.w < me.y)) ? 1 : 0;
+        }
+        if (rank < k) {
+          const int64_t po = (int64_t)cc * k + rank;
+          as_global(d.idx)[po] = (int32_t)me.y;
+          as_global(d.val)[po] = __uint_as_float(me.x);
+          sel[rank] = make_uint2(me.y, me.x);
+        }
+      }
+    }
+    if (lane >= k && lane < kpad) sel[lane] = make_uint2(0u, 0u);
+    wave_lds_sync();
+
+    DEMO_PHASE(5);
+    // ---- reconstruction accumulated into D: D -= sum_t val_t P[u_t][i] P[v_t][j] ----------------
+    for (int ks = 0; ks < kpad / 4; ++ks) {
+      const uint2 sv = sel[4 * ks + g];
+      const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
+      const float nv = -__uint_as_float(sv.y);
+      const float4 pa = *reinterpret_cast<const float4*>(&sProw[u * 64 + 4 * c]);
+      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[v * 64 + 4 * c]);
+      const float af[4] = {nv * pa.x, nv * pa.y, nv * pa.z, nv * pa.w};
+      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) D[mt][e] = mfma4(af[mt], bf[e], D[mt][e]);
+    }
+
+    DEMO_PHASE(6);
+    // ---- store the residual momentum -------------------------------------------------------------
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
+      bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
+    }
+    wave_lds_sync();   // the lists are rewritten by the next chunk
+    DEMO_PHASE(7);
+  }
+  DEMO_PHASE_FLUSH(0);
+}
+
+template <bool GBF16>
+static hipError_t launch_enc_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
+                                    int64_t grid, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_wave64<GBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, E64_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(encode2d_wave64<GBF16>, dim3((unsigned)grid), dim3(E64_THREADS), E64_LDS_BYTES, stream, tv, tables,
+                     a, wl);
+  return hipGetLastError();
+}
+
+hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
+                                  bool grad_bf16, int num_cus, hipStream_t stream) {
+  int64_t grid = num_cus;
+  const int64_t max_grid = ((int64_t)tv.total_chunks + E64_WAVES - 1) / E64_WAVES;
+  if (grid > max_grid) grid = max_grid;
+  return grad_bf16 ? launch_enc_wave64<true>(tv, tables, a, wl, grid, stream)
+                   : launch_enc_wave64<false>(tv, tables, a, wl, grid, stream);
+}
+
+}  // namespace demo
+
+DEMO_PHASE_GETTER(demo_debug_phase_clocks_enc)

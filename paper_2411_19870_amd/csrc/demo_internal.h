@@ -56,7 +56,8 @@ struct DecodeArgs {
 // Device tables of one chunk size.
 struct BasisTables {
   const float* basis;    // s x s orthonormal DCT-II matrix P, row-major float32
-  const float* fast64;   // fragment tables of the wavefront-per-chunk kernels (s = 64 only, else null)
+  const float* enc64;    // fragment tables of the wavefront-per-chunk encode kernel (s = 64 only, else null)
+  const float* dec64;    // tables of the wavefront-per-chunk decode kernel (s = 64 only, else null)
 };
 
 // Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:
@@ -70,13 +71,14 @@ hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, co
 hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
                            hipStream_t stream);
 
-// s = 64 wavefront-per-chunk kernels (demo_fast64.hip).
-constexpr int kFast64TableFloats = 4 * 4096;
+// s = 64 wavefront-per-chunk kernels (demo_enc64.hip, demo_dec64.hip).
+constexpr int kEnc64TableFloats = 3072 + 2 * 4096;
+constexpr int kDec64TableFloats = 2 * 4096;
 constexpr int kFast64MaxK = 64;
-void build_fast64_tables(const double* P, float* out /* kFast64TableFloats */);
+void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
+void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
-                                  int num_cus, hipStream_t stream);
-
+                                  bool grad_bf16, int num_cus, hipStream_t stream);
 // The decode kernel keeps all W workers' pairs of a chunk in registers: W <= 64 when k <= 32, W <= 32 above.
 inline bool fast64_decode_supports(int W, int k) { return k <= kFast64MaxK && W <= (k <= 32 ? 64 : 32); }
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,

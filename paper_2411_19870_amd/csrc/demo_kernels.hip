@@ -573,9 +573,11 @@ hipError_t launch_encode2d(const TableView& tv, const BasisTables& bt, int s, co
                            const Worklist& wl, int num_cus, int variant, hipStream_t stream) {
   if (tv.total_chunks == 0) return hipSuccess;
   const float* basis = bt.basis;
-  if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.fast64 != nullptr && wl.list != nullptr) {
+  const uint32_t gmix = tv.dtypes & 3u;   // gradient dtypes present: the wavefront kernel wants one
+  if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.enc64 != nullptr && wl.list != nullptr &&
+      (gmix == 1u || gmix == 2u)) {
     // wavefront-per-chunk kernel, then the exact generic kernel over whatever it queued
-    hipError_t e = launch_encode2d_wave64(tv, bt.fast64, a, wl, num_cus, stream);
+    hipError_t e = launch_encode2d_wave64(tv, bt.enc64, a, wl, gmix == 1u, num_cus, stream);
     if (e != hipSuccess) return e;
     return launch_enc2d_generic<64>(tv, basis, a, wl, num_cus, stream);
   }
@@ -592,8 +594,8 @@ hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, co
                            int variant, hipStream_t stream) {
   if (tv.total_chunks == 0) return hipSuccess;
   const uint32_t pmix = (tv.dtypes >> 2) & 3u;   // parameter dtypes present: the wavefront kernel wants one
-  if (variant >= 1 && s == 64 && fast64_decode_supports(a.W, a.k) && bt.fast64 != nullptr && (pmix == 1u || pmix == 2u))
-    return launch_decode2d_wave64(tv, bt.fast64, a, pmix == 1u, num_cus, stream);
+  if (variant >= 1 && s == 64 && fast64_decode_supports(a.W, a.k) && bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
+    return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {
     case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);
