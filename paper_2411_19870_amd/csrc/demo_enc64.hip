@@ -133,48 +133,88 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   uint32_t fb_a = (uint32_t)(256 * c + 16 * g), fb_b = (uint32_t)(256 * c + 8 * g);
   uint32_t fb_c = (uint32_t)(128 * c + 16 * g), fb_d = (uint32_t)(128 * c + 8 * g);
 
+  // Where a chunk lives: row rho(4s+w, g) = rbase(q) + (w even ? g : 3 - g), i.e. a uniform part
+  // (scalar offset of the buffer access) plus one of two per-lane offsets.
+  struct Place {
+    __amdgpu_buffer_rsrc_t mres, gres;
+    uint32_t ucols, vo_up, vo_dn;   // elements
+    int cc;
+    int32_t* idx;
+    float* val;
+  };
+  auto place = [&](const TensorDev& dd, int ccc) {
+    const int k0 = ccc / dd.cchunks, k1 = ccc - k0 * dd.cchunks;
+    const int64_t origin = (int64_t)k0 * 64 * dd.cols + (int64_t)k1 * 64;   // uniform
+    Place p;
+    p.ucols = (uint32_t)dd.cols;
+    p.vo_up = (uint32_t)g * p.ucols + (uint32_t)col4;
+    p.vo_dn = (uint32_t)(3 - g) * p.ucols + (uint32_t)col4;
+    p.mres = make_rsrc(dd.mom + origin);
+    p.gres = GBF16 ? make_rsrc(static_cast<const uint16_t*>(dd.grad) + origin)
+                   : make_rsrc(static_cast<const float*>(dd.grad) + origin);
+    p.cc = ccc;
+    p.idx = dd.idx;
+    p.val = dd.val;
+    return p;
+  };
+  auto rbase = [](int q) {
+    return (q & 3) == 0 ? 4 * (q >> 2) : (q & 3) == 1 ? 28 - 4 * (q >> 2) : (q & 3) == 2 ? 32 + 4 * (q >> 2) : 60 - 4 * (q >> 2);
+  };
+
+  // Raw inputs of the chunk being prefetched: its momentum rows are requested as soon as the
+  // product-1 accumulators of the current chunk are dead, its bf16 gradient rows once top-k is done.
+  f32x4 nm[16];
+  u32x2 ng[16];
+  auto fetch_m = [&](const Place& p) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+      nm[q] = bload_f4(p.mres, ((q & 1) ? p.vo_dn : p.vo_up) * 4, (uint32_t)rbase(q) * p.ucols * 4);
+  };
+  auto fetch_g16 = [&](const Place& p) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+      ng[q] = bload_u2(p.gres, ((q & 1) ? p.vo_dn : p.vo_up) * 2, (uint32_t)rbase(q) * p.ucols * 2);
+  };
+
+  Place cur = place(d, chunk - t_first);
+  fetch_m(cur);
+  if (GBF16) fetch_g16(cur);
+
   DEMO_PHASE_DECL
   for (; chunk < chunk_end; ++chunk) {
-    while (chunk >= t_next) {
-      ++t;
-      t_first = t_next;
-      t_next = tv.prefix[t + 1];
-      d = tv.descs[t];
+    const int cc = cur.cc;
+    const uint32_t ucols = cur.ucols, vo_up = cur.vo_up, vo_dn = cur.vo_dn;
+    const __amdgpu_buffer_rsrc_t mres = cur.mres;
+    // the chunk after this one (if any)
+    const bool has_next = chunk + 1 < chunk_end;
+    Place nxt = cur;
+    if (has_next) {
+      while (chunk + 1 >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = tv.prefix[t + 1];
+        d = tv.descs[t];
+      }
+      nxt = place(d, chunk + 1 - t_first);
     }
-    const int cc = chunk - t_first;
-    const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
-    const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
-    // row rho(4s+w, g) = rbase(s,w) + (w even ? g : 3 - g): a uniform part (scalar offset) and one of
-    // two per-lane offsets
-    const uint32_t ucols = (uint32_t)d.cols;
-    const uint32_t vo_up = (uint32_t)g * ucols + (uint32_t)col4;         // elements
-    const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
-    const __amdgpu_buffer_rsrc_t mres = make_rsrc(d.mom + origin);
-    auto rbase = [](int q) { return (q & 3) == 0 ? 4 * (q >> 2) : (q & 3) == 1 ? 28 - 4 * (q >> 2) : (q & 3) == 2 ? 32 + 4 * (q >> 2) : 60 - 4 * (q >> 2); };
 
-    // ---- load and momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ----
+    // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ------------------
     f32x4 D[4][4];
     if (GBF16) {
-      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const uint16_t*>(d.grad) + origin);
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
-        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rbase(q) * ucols;
-        const u32x2 gr = bload_u2(gres, vo * 2, so * 2);
-        const f32x4 mo = bload_f4(mres, vo * 4, so * 4);
-        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, mo[0], __uint_as_float(gr[0] << 16));
-        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, mo[1], __uint_as_float(gr[0] & 0xffff0000u));
-        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, mo[2], __uint_as_float(gr[1] << 16));
-        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, mo[3], __uint_as_float(gr[1] & 0xffff0000u));
+        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], __uint_as_float(ng[q][0] << 16));
+        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], __uint_as_float(ng[q][0] & 0xffff0000u));
+        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], __uint_as_float(ng[q][1] << 16));
+        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], __uint_as_float(ng[q][1] & 0xffff0000u));
       }
     } else {
-      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const float*>(d.grad) + origin);
+      // fp32 gradients are not prefetched (no registers to park them in): read them now
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
-        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rbase(q) * ucols;
-        const f32x4 gr = bload_f4(gres, vo * 4, so * 4);
-        const f32x4 mo = bload_f4(mres, vo * 4, so * 4);
+        const f32x4 gr = bload_f4(cur.gres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, mo[e], gr[e]);
+        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], gr[e]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -236,6 +276,11 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       }
     }
 
+    // lands while top-k, reconstruction and store of this chunk run (after the last chunk the same
+    // chunk is simply requested again: an unconditional fetch keeps the old registers dead)
+    fetch_m(nxt);
+    __builtin_amdgcn_sched_barrier(0);
+
     DEMO_PHASE(2);
     // ---- top-k inside the wavefront ------------------------------------------------------------
     // (1) a lower bound of the k-th largest magnitude: the k-th largest of the 64 per-lane maxima,
@@ -280,30 +325,28 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
             }
           }
     }
-    if (ncand > E64_CAP) {
-      // Many (near-)equal magnitudes at the threshold (an all-zero chunk is the common case).
-      if (__ballot(lm != 0u) == 0) {
-        // every coefficient is zero: the k lowest flat indices, zero values, momentum stays zero
-        if (lane < k) {
-          const int64_t po = (int64_t)cc * k + lane;
-          as_global(d.idx)[po] = lane;
-          as_global(d.val)[po] = 0.f;
-        }
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
-          bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
-        }
-      } else {
-        // leave the chunk untouched and queue it for the exact workgroup kernel that runs next
-        if (lane == 0) wl.list[atomicAdd(wl.count, 1)] = chunk;
+    const bool overflow = ncand > E64_CAP;   // many (near-)equal magnitudes at the threshold
+    const bool all_zero = overflow && __ballot(lm != 0u) == 0;
+    const bool skip = overflow && !all_zero;
+    if (skip) {
+      // leave the chunk untouched and queue it for the exact workgroup kernel that runs next
+      if (lane == 0) wl.list[atomicAdd(wl.count, 1)] = chunk;
+    }
+    if (all_zero) {
+      // every coefficient is zero: the k lowest flat indices with zero values; D (all zero) is stored below
+      if (lane < k) {
+        const int64_t po = (int64_t)cc * k + lane;
+        as_global(cur.idx)[po] = lane;
+        as_global(cur.val)[po] = 0.f;
       }
-      continue;
+      if (lane < kpad) sel[lane] = make_uint2(0u, 0u);
+      ncand = 0;
     }
     DEMO_PHASE(4);
     wave_lds_sync();
     // (3) rank candidates (magnitude descending, flat index ascending); ranks < k are the payload
-    if (ncand <= 64) {
+    if (all_zero || skip) {
+    } else if (ncand <= 64) {
       // one candidate per lane; the others' keys come through v_readlane
       const uint2 me = cand[lane < ncand ? lane : 0];
       const uint32_t mag = me.x & 0x7fffffffu, nfl = ~me.y;
@@ -316,8 +359,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       }
       if (lane < ncand && rank < k) {
         const int64_t po = (int64_t)cc * k + rank;
-        as_global(d.idx)[po] = (int32_t)me.y;
-        as_global(d.val)[po] = __uint_as_float(me.x);
+        as_global(cur.idx)[po] = (int32_t)me.y;
+        as_global(cur.val)[po] = __uint_as_float(me.x);
         sel[rank] = make_uint2(me.y, me.x);
       }
     } else {
@@ -335,18 +378,20 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
         }
         if (rank < k) {
           const int64_t po = (int64_t)cc * k + rank;
-          as_global(d.idx)[po] = (int32_t)me.y;
-          as_global(d.val)[po] = __uint_as_float(me.x);
+          as_global(cur.idx)[po] = (int32_t)me.y;
+          as_global(cur.val)[po] = __uint_as_float(me.x);
           sel[rank] = make_uint2(me.y, me.x);
         }
       }
     }
     if (lane >= k && lane < kpad) sel[lane] = make_uint2(0u, 0u);
     wave_lds_sync();
+    if (GBF16) fetch_g16(nxt);   // the coefficient registers are dead now
+    __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(5);
     // ---- reconstruction accumulated into D: D -= sum_t val_t P[u_t][i] P[v_t][j] ----------------
-    for (int ks = 0; ks < kpad / 4; ++ks) {
+    for (int ks = 0; ks < (skip ? 0 : kpad / 4); ++ks) {
       const uint2 sv = sel[4 * ks + g];
       const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
       const float nv = -__uint_as_float(sv.y);
@@ -362,12 +407,15 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
 
     DEMO_PHASE(6);
     // ---- store the residual momentum -------------------------------------------------------------
+    if (!skip) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
-      bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
+      for (int q = 0; q < 16; ++q) {
+        const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
+        bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
+      }
     }
     wave_lds_sync();   // the lists are rewritten by the next chunk
+    cur = nxt;
     DEMO_PHASE(7);
   }
   DEMO_PHASE_FLUSH(0);
