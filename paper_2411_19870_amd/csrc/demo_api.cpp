@@ -174,7 +174,8 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   std::vector<int32_t> p2(1, 0), p1(1, 0);
   uint32_t mix2 = 0, mix1 = 0;
   for (int i = 0; i < n; ++i) {
-    const uint32_t mix = (t[i].grad_dtype == DEMO_BF16 ? 1u : 2u) | (t[i].param_dtype == DEMO_BF16 ? 4u : 8u);
+    const bool al16 = ((reinterpret_cast<uintptr_t>(t[i].idx) | reinterpret_cast<uintptr_t>(t[i].val)) & 15u) == 0;
+    const uint32_t mix = (t[i].grad_dtype == DEMO_BF16 ? 1u : 2u) | (t[i].param_dtype == DEMO_BF16 ? 4u : 8u) | (al16 ? 0u : 16u);
     (t[i].cols == 0 ? mix1 : mix2) |= mix;
     TensorDev d{};
     d.grad = t[i].grad;

@@ -1,109 +1,141 @@
 // s = 64 decode kernel: one wavefront per 64 x 64 chunk.
 //
-// Lane l = 16 g + c owns, for q = 0..15, the four consecutive parameters X[4q + g][4c .. 4c+3]
-// (16 lanes cover one row of the chunk).  The coefficient sums S of the W payloads live in a
-// private LDS tile; R = P^T (S P) runs as two chains of v_mfma_f32_16x16x4_f32 and lands in the
-// register layout the parameters are loaded and stored with, so the sign update is fused.
+// The parameters of the chunk use the register layout of the encode kernel (demo_device.h: lane
+// l = 16 g + c holds rows rho(q, g), columns 4 chi(c) .. +3), so every load and store instruction
+// still covers whole 256-byte rows and each lane owns complete mirror quadruples of rows.
+//
+// The coefficient sums S of the W payloads are accumulated in a private LDS tile, in block fixed
+// point with integer atomics (see `scatter` below).  R = P^T (S P) then runs as two chains of
+// v_mfma_f32_16x16x4_f32:
+//   product a   Y[u][j] = sum_v S[u][v] P[v][j]   A = S from LDS (rows taken in the order of the
+//               coefficient tiles: u = 0 mod 4, 2 mod 4, odd), B = rows of P; dense.
+//   product b   R[i][j] = sum_u P[u][i] Y[u][j]   A = basis fragments, B = product-a accumulators.
+//               Rows of P with u = 0 mod 4 are even under both mirrors i -> 63-i and i -> 31-i,
+//               rows with u = 2 mod 4 even / odd, odd rows odd under i -> 63-i, so only the rows
+//               i0 < 16 (two classes) and i < 32 (odd class) are computed -- 3/8 of the dense
+//               product -- and the four members of a quadruple follow from in-lane adds:
+//                 R[i0] = ee+eo+o0, R[31-i0] = ee-eo+o1, R[32+i0] = ee-eo-o1, R[63-i0] = ee+eo-o0.
+// R lands in the register layout of the parameters, so the sign update is fused.
 #include "demo_device.h"
 
 namespace demo {
 
-// Host: basis tables of the decode kernel from the 64 x 64 basis P (double, row-major):
-//   [0, 4096)     rows of P:                 plain[v*64 + j]      = P[v][j]
-//   [4096, 8192)  rows of P, permuted:       perm[u*64 + 4c + m]  = P[u][16m + 4(c%4) + c/4]
-void build_dec64_tables(const double* P, float* out) {
-  for (int u = 0; u < 64; ++u)
-    for (int j = 0; j < 64; ++j) out[u * 64 + j] = (float)P[u * 64 + j];
-  for (int u = 0; u < 64; ++u)
-    for (int cc = 0; cc < 16; ++cc)
-      for (int mt = 0; mt < 4; ++mt)
-        out[4096 + u * 64 + 4 * cc + mt] = (float)P[u * 64 + 16 * mt + 4 * (cc & 3) + (cc >> 2)];
-}
-
-// ---------------------------------------------------------------------------
-// decode
-// ---------------------------------------------------------------------------
-// One wavefront per chunk.  The coefficient sums S live in a private LDS tile (row stride
-// 68 floats); R = P^T (S P) runs as two MFMA chains:
-//   product a   Y[u][j] = sum_v S[u][v] P[v][j]     A = S from LDS, B = rows of P
-//   product b   R[i][j] = sum_u P[u][i] Y[u][j]     A = permuted rows of P, B = product-a accumulators
-// and lands in the same register layout the parameters are loaded and stored with.
 namespace {
-constexpr int F64D_WAVES = 7;                       // 7 private tiles + the two basis tables fill the LDS
-constexpr int F64D_THREADS = F64D_WAVES * 64;
-constexpr int F64D_LDT = 68;
-constexpr int F64D_TILE_FLOATS = 64 * F64D_LDT;
-constexpr int F64D_LDS_BYTES = 4 * (2 * 4096 + F64D_WAVES * F64D_TILE_FLOATS);
+constexpr int D64_WAVES = 7;                       // 7 private tiles + the basis tables fill the LDS
+constexpr int D64_THREADS = D64_WAVES * 64;
+constexpr int D64_LDT = 68;                        // tile row stride (floats); columns 64..67 are pad slots
+constexpr int D64_TILE_FLOATS = 64 * D64_LDT;
+constexpr int D64_PCOL = 0;                        // pcol[v*64 + 4c + e] = P[v][4 chi(c) + e]
+constexpr int D64_TB = 4096;                       // product-b fragments: 6 groups x 64 lanes x 4
+constexpr int D64_TABLE_FLOATS = 4096 + 1536;
+constexpr int D64_LDS_BYTES = 4 * (D64_TABLE_FLOATS + D64_WAVES * D64_TILE_FLOATS);
+static_assert(D64_TABLE_FLOATS == kDec64TableFloats, "table size");
 }  // namespace
 
-// PBF16: parameter dtype of every tensor in the table.  FULL: k == 32 and W a multiple of 64, so
-// every payload load instruction is fully populated (two workers x 32 pairs) and needs no predicate.
+// Host: tables of the decode kernel from the 64 x 64 basis P (double, row-major).
+void build_dec64_tables(const double* P, float* out) {
+  auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
+  for (int v = 0; v < 64; ++v)
+    for (int cc = 0; cc < 16; ++cc)
+      for (int e = 0; e < 4; ++e) out[D64_PCOL + v * 64 + 4 * cc + e] = Pm(v, 4 * chi(cc) + e);
+  // product b: output row m = c of a tile is the quadruple base i0 = 4(c % 4) + c / 4, so that lane
+  // group g, component s of the accumulator is i0 = 4s + g; k-slot g of step r contracts
+  // u = freq(tile, 4g + r)
+  for (int lane = 0; lane < 64; ++lane) {
+    const int g = lane >> 4, c = lane & 15;
+    const int i0 = 4 * (c & 3) + (c >> 2);
+    for (int r = 0; r < 4; ++r) {
+      out[D64_TB + (0 * 64 + lane) * 4 + r] = Pm(freq(0, 4 * g + r), i0);
+      out[D64_TB + (1 * 64 + lane) * 4 + r] = Pm(freq(1, 4 * g + r), i0);
+      out[D64_TB + (2 * 64 + lane) * 4 + r] = Pm(freq(2, 4 * g + r), i0);        // odd rows, output i0
+      out[D64_TB + (3 * 64 + lane) * 4 + r] = Pm(freq(3, 4 * g + r), i0);
+      out[D64_TB + (4 * 64 + lane) * 4 + r] = Pm(freq(2, 4 * g + r), 31 - i0);   // odd rows, output 31 - i0
+      out[D64_TB + (5 * 64 + lane) * 4 + r] = Pm(freq(3, 4 * g + r), 31 - i0);
+    }
+  }
+}
+
+// PBF16: parameter dtype of every tensor in the table.  FULL: k == 32 and W == 64, so the payload
+// of a chunk is read with eight fully populated 16-byte loads per array (eight workers each).
 template <bool PBF16, bool FULL>
-__global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
-                                                                DecodeArgs args) {
+__global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
+                                                               DecodeArgs args) {
   extern __shared__ float lds[];
-  const float* sPplain = lds;
-  const float* sPperm = lds + 4096;
+  const float* sPcol = lds + D64_PCOL;
+  const float* sTb = lds + D64_TB;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
-  float* tile = lds + 2 * 4096 + wave * F64D_TILE_FLOATS;
+  float* tile = lds + D64_TABLE_FLOATS + wave * D64_TILE_FLOATS;
+  int* itile = reinterpret_cast<int*>(tile);
   const int k = FULL ? 32 : args.k, W = args.W;
 
-  for (int e = tid; e < 2 * 4096 / 4; e += F64D_THREADS)
+  for (int e = tid; e < D64_TABLE_FLOATS / 4; e += D64_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
   __syncthreads();
 
-  const int nwaves = gridDim.x * F64D_WAVES;
-  const int wid = blockIdx.x * F64D_WAVES + wave;
+  const int nwaves = gridDim.x * D64_WAVES;
+  const int wid = blockIdx.x * D64_WAVES + wave;
   const int total = tv.total_chunks;
   const int per = total / nwaves, rem = total - per * nwaves;
   int chunk = wid * per + (wid < rem ? wid : rem);
   const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
   if (chunk >= chunk_end) return;
 
-  // payload lanes: with k <= 32 one load instruction fetches the pairs of two workers
-  const int wpi = (FULL || k <= 32) ? 2 : 1;             // workers per load instruction
-  const int sub = wpi == 2 ? (lane >> 5) : 0;            // which of them this lane serves
-  const int pt = wpi == 2 ? (lane & 31) : lane;          // pair index inside the chunk
+  // ---- payload access ---------------------------------------------------------------------------------
+  // 32 (index, value) pairs per lane hold the whole payload of a chunk (W * k <= 2048 pairs).
+  //   FULL:  load j (0..7) fetches pairs 4(l%8) .. +3 of worker 8j + l/8 as one 16-byte load;
+  //   else:  load j (0..31) fetches one pair: with k <= 32 of worker 2j + l/32, else of worker j.
+  constexpr int NP = 32;
+  int32_t pi[NP];
+  float pv[NP];
+  const int wpi = k <= 32 ? 2 : 1;
+  const int sub = FULL ? (lane >> 3) : (wpi == 2 ? (lane >> 5) : 0);
+  const int pt = FULL ? 4 * (lane & 7) : (wpi == 2 ? (lane & 31) : lane);
   const bool pact = FULL || pt < k;
-  const uint32_t dummy = (uint32_t)(lane * F64D_LDT + 64);   // a pad slot of this lane: absorbs masked-off additions
-  constexpr int NLI = 32;                                // load instructions per group of workers
-  int32_t pi[NLI];
-  float pv[NLI];
-  auto load_payload = [&](const TensorDev& dd, int ccc, int wbase) {
-    // uniform 64-bit base per load instruction + one 32-bit per-lane offset
+  auto load_payload = [&](const TensorDev& dd, int ccc) {
     const int64_t wstride = (int64_t)dd.nchunks * k;
     const uint32_t lane_off = (uint32_t)(sub * (int)wstride + pt);
-    const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)ccc * k + (int64_t)wbase * wstride;
-    const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)ccc * k + (int64_t)wbase * wstride;
+    const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)ccc * k;
+    const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)ccc * k;
+    if (FULL) {
 #pragma unroll
-    for (int j = 0; j < NLI; ++j) {
-      if (FULL) {
-        pi[j] = ip[lane_off];
-        pv[j] = vp[lane_off];
-      } else {
-        const bool ok = pact && wbase + j * wpi + sub < W;
+      for (int j = 0; j < 8; ++j) {
+        const u32x4 a = *reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + lane_off);
+        const f32x4 b = *reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + lane_off);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          pi[4 * j + x] = (int32_t)a[x];
+          pv[4 * j + x] = b[x];
+        }
+        ip += 8 * wstride;
+        vp += 8 * wstride;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < NP; ++j) {
+        const bool ok = pact && j * wpi + sub < W;
         pi[j] = ok ? ip[lane_off] : -1;
         pv[j] = ok ? vp[lane_off] : 0.f;
+        ip += wpi * wstride;
+        vp += wpi * wstride;
       }
-      ip += wpi * wstride;
-      vp += wpi * wstride;
     }
   };
+
   // S[idx] += val in block fixed point.  LDS float atomics are an order of magnitude slower than
   // integer ones on this part, and an integer sum does not depend on the order of arrival, so the
   // coefficients are scaled by a power of two taken from the largest magnitude of the chunk's
-  // payload (exact), rounded to integers of `vbits` bits and added with ds_add_u32; W such
-  // values cannot overflow 31 bits.  Only sgn(IDCT(S)) is used, so the scale is never undone.
-  // Lanes with nothing to add (inactive pair, index out of range) add zero into their pad slot.
-  int* itile = reinterpret_cast<int*>(tile);
+  // payload (exact), rounded to integers of `vbits` bits and added with ds_add_u32; W such values
+  // cannot overflow 31 bits.  Only sgn(IDCT(S)) is used, so the scale is never undone.  Lanes with
+  // nothing to add (inactive pair, index out of range) add zero-weight garbage into their pad slot.
+  const uint32_t dummy = (uint32_t)(lane * D64_LDT + 64);
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                // 30 - ceil(log2 W)
   auto scatter = [&]() {
     float mx = 0.f;
 #pragma unroll
-    for (int j = 0; j < NLI; ++j) mx = fmaxf(mx, fabsf(pv[j]));
+    for (int j = 0; j < NP; ++j) mx = fmaxf(mx, fabsf(pv[j]));
     uint32_t mb = __float_as_uint(mx);
     mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
     mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
@@ -115,34 +147,39 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
     ex = ex < 1 ? 1 : ex;
     const int sh = vbits + 126 - ex;                      // max |val| * 2^sh < 2^vbits
 #pragma unroll
-    for (int j = 0; j < NLI; ++j) {
+    for (int j = 0; j < NP; ++j) {
       const uint32_t u = (uint32_t)pi[j];
       const uint32_t a = u < 4096u ? u + ((u >> 6) << 2) : dummy;   // (u / 64) * 68 + u % 64
-      const int q = __float2int_rn(ldexpf(pv[j], sh));
-      atomicAdd(&itile[a], q);
+      atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
     }
   };
 
   int t = find_tensor(tv.prefix, tv.n, chunk);
   int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
   TensorDev d = tv.descs[t];
-  load_payload(d, chunk - t_first, 0);
+  load_payload(d, chunk - t_first);
+  const int col4 = 4 * chi(c);
   DEMO_PHASE_DECL
 
   for (; chunk < chunk_end; ++chunk) {
     const int cc = chunk - t_first;
     const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
-    const int64_t base = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64 + (int64_t)g * d.cols + 4 * c;
-    const TensorDev dcur = d;
+    const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
+    const uint32_t ucols = (uint32_t)d.cols;
+    const uint32_t vo_up = (uint32_t)g * ucols + (uint32_t)col4;           // elements
+    const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
+    const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
+                                              : make_rsrc(static_cast<const float*>(d.param) + origin);
     DEMO_PHASE(0);
 
     // ---- S = sum over workers ---------------------------------------------------------------------------
 #pragma unroll
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    scatter();   // the launch wrapper guarantees that one group of NLI load instructions holds all W workers
+    scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
     DEMO_PHASE(1);
-    // ---- payload of the next chunk, in flight during the products -----------------------------------------
+    // ---- payload of the next chunk, in flight during the products (after the last chunk the same
+    //      chunk is requested again: an unconditional fetch keeps the old registers dead) -----------------
     if (chunk + 1 < chunk_end) {
       while (chunk + 1 >= t_next) {
         ++t;
@@ -150,113 +187,140 @@ __global__ __launch_bounds__(F64D_THREADS) void decode2d_wave64(TableView tv, co
         t_next = tv.prefix[t + 1];
         d = tv.descs[t];
       }
-      load_payload(d, chunk + 1 - t_first, 0);
+      load_payload(d, chunk + 1 - t_first);
+    } else {
+      load_payload(d, cc);
     }
     wave_lds_sync();
 
     DEMO_PHASE(2);
-    // ---- product a: Ya[mt][e] (rows u = 16mt+4g+r, cols j = 4c+e) --------------------------------------
-    // k-step 4kg + kr contracts v = 16kg + 4g + kr: four k-steps per 16-byte LDS read of S.
-    // Operands of the next k-step are read while the MFMAs of the current one run.
-    f32x4 Ya[4][4];
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) Ya[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    {
-      float4 sa[4], sn[4];
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt) sn[mt] = *reinterpret_cast<const float4*>(&tile[(16 * mt + c) * F64D_LDT + 4 * g]);
-      float4 pn = *reinterpret_cast<const float4*>(&sPplain[(4 * g) * 64 + 4 * c]);
-#pragma unroll
-      for (int ks = 0; ks < 16; ++ks) {
-        const int kg = ks >> 2, kr = ks & 3;
-        if (kr == 0) {
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt) sa[mt] = sn[mt];
-          if (kg + 1 < 4) {
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-              sn[mt] = *reinterpret_cast<const float4*>(&tile[(16 * mt + c) * F64D_LDT + 16 * (kg + 1) + 4 * g]);
-          }
-        }
-        const float bf[4] = {pn.x, pn.y, pn.z, pn.w};
-        if (ks + 1 < 16) {
-          const int kg2 = (ks + 1) >> 2, kr2 = (ks + 1) & 3;
-          pn = *reinterpret_cast<const float4*>(&sPplain[(16 * kg2 + 4 * g + kr2) * 64 + 4 * c]);
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const float ai = kr == 0 ? sa[mt].x : kr == 1 ? sa[mt].y : kr == 2 ? sa[mt].z : sa[mt].w;
-          const float a = (float)__float_as_int(ai);      // the tile holds fixed-point sums
-#pragma unroll
-          for (int e = 0; e < 4; ++e) Ya[mt][e] = mfma4(a, bf[e], Ya[mt][e]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-
-    DEMO_PHASE(3);
-    // ---- product b: R[mt'][e] component r' = element (row 4(4mt'+r')+g, col 4c+e) --------------------------
-    f32x4 R[4][4];
+    // ---- products a and b, interleaved by coefficient-tile pair so that only half of the product-a
+    //      accumulators is alive at a time:
+    //        Ya[mh][e] rows u = freq(2*half + mh, 4g+r), cols j = 4 chi(c) + e      (product a, dense)
+    //        half 0 feeds Cee, Ceo; half 1 feeds Co0, Co1 [e], component s = quadruple base i0 = 4s + g
+    // Product a: k-step 4kg + kr contracts v = 16kg + 4g + kr, four k-steps per 16-byte LDS read of S;
+    // operands of the next k-step are read while the MFMAs of the current one run.
+    f32x4 Cee[4], Ceo[4], Co0[4], Co1[4];
     u32x2 Xh[16];   // bf16 parameters, raw
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int e = 0; e < 4; ++e) {
+      Cee[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      Ceo[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      Co0[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      Co1[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
 #pragma unroll
-      for (int e = 0; e < 4; ++e) R[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    {
-      float4 pn = *reinterpret_cast<const float4*>(&sPperm[(4 * g) * 64 + 4 * c]);
+    for (int half = 0; half < 2; ++half) {
+      f32x4 Ya[2][4];
 #pragma unroll
-      for (int mr = 0; mr < 16; ++mr) {
-        const int mt = mr >> 2, r = mr & 3;
-        const float af[4] = {pn.x, pn.y, pn.z, pn.w};
-        if (mr + 1 < 16) {
-          const int mt2 = (mr + 1) >> 2, r2 = (mr + 1) & 3;
-          pn = *reinterpret_cast<const float4*>(&sPperm[(16 * mt2 + 4 * g + r2) * 64 + 4 * c]);
+      for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Ya[mh][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      {
+        int srow[2];   // tile row of A row c of tile 2*half + mh
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) srow[mh] = freq(2 * half + mh, c) * D64_LDT + 4 * g;
+        float4 sa[2], sn[2];
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh) sn[mh] = *reinterpret_cast<const float4*>(&tile[srow[mh]]);
+        float4 pn = *reinterpret_cast<const float4*>(&sPcol[(4 * g) * 64 + 4 * c]);
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) {
+          const int kg = ks >> 2, kr = ks & 3;
+          if (kr == 0) {
+#pragma unroll
+            for (int mh = 0; mh < 2; ++mh) sa[mh] = sn[mh];
+            if (kg + 1 < 4) {
+#pragma unroll
+              for (int mh = 0; mh < 2; ++mh) sn[mh] = *reinterpret_cast<const float4*>(&tile[srow[mh] + 16 * (kg + 1)]);
+            }
+          }
+          const float bf[4] = {pn.x, pn.y, pn.z, pn.w};
+          if (ks + 1 < 16) {
+            const int kg2 = (ks + 1) >> 2, kr2 = (ks + 1) & 3;
+            pn = *reinterpret_cast<const float4*>(&sPcol[(16 * kg2 + 4 * g + kr2) * 64 + 4 * c]);
+          }
+#pragma unroll
+          for (int mh = 0; mh < 2; ++mh) {
+            const float a = (float)__float_as_int(comp(sa[mh], kr));   // the tile holds fixed-point sums
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Ya[mh][e] = mfma4(a, bf[e], Ya[mh][e]);
+          }
+          if (PBF16 && half == 1) {
+            // parameters: requested during the second half, one row per k-step
+            Xh[ks] = bload_u2(xres, ((ks & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(ks) * ucols * 2);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int m2 = 0; m2 < 4; ++m2)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) R[m2][e] = mfma4(af[m2], Ya[mt][e][r], R[m2][e]);
-        if (PBF16 && r == 3) {
-          // a quarter of the product-a accumulators is dead: use the registers for the parameters
-          const uint16_t* xp = static_cast<const uint16_t*>(dcur.param) + base;
-#pragma unroll
-          for (int q = 4 * mt; q < 4 * mt + 4; ++q) Xh[q] = gload_u2(xp + (int64_t)(4 * q) * dcur.cols);
-        }
-        __builtin_amdgcn_sched_barrier(0);
       }
+      // product b for this pair of tiles (3/8 dense over both halves)
+      if (half == 0) {
+        const float4 tee = *reinterpret_cast<const float4*>(&sTb[(0 * 64 + lane) * 4]);
+        const float4 teo = *reinterpret_cast<const float4*>(&sTb[(1 * 64 + lane) * 4]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            Cee[e] = mfma4(comp(tee, r), Ya[0][e][r], Cee[e]);
+            Ceo[e] = mfma4(comp(teo, r), Ya[1][e][r], Ceo[e]);
+          }
+      } else {
+        float4 tb[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tb[i] = *reinterpret_cast<const float4*>(&sTb[((2 + i) * 64 + lane) * 4]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            Co0[e] = mfma4(comp(tb[0], r), Ya[0][e][r], Co0[e]);
+            Co1[e] = mfma4(comp(tb[2], r), Ya[0][e][r], Co1[e]);
+            Co0[e] = mfma4(comp(tb[1], r), Ya[1][e][r], Co0[e]);
+            Co1[e] = mfma4(comp(tb[3], r), Ya[1][e][r], Co1[e]);
+          }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (half == 0) { DEMO_PHASE(3); }
     }
 
     DEMO_PHASE(4);
-    // ---- x <- x - lr*(sgn(R) + wd*x) ---------------------------------------------------------------------
-    if (PBF16) {
-      uint16_t* xp = static_cast<uint16_t*>(dcur.param) + base;
+    // ---- x <- x - lr*(sgn(R) + wd*x), R from the quadruple identities ------------------------------------------
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const float x[4] = {__uint_as_float(Xh[q][0] << 16), __uint_as_float(Xh[q][0] & 0xffff0000u),
-                            __uint_as_float(Xh[q][1] << 16), __uint_as_float(Xh[q][1] & 0xffff0000u)};
-        float o[4];
+    for (int s = 0; s < 4; ++s) {
+      f32x4 xin[4];   // fp32 parameters of the four rows of this quadruple
+      if (!PBF16) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = sign_update(x[e], sgnf(R[q >> 2][e][q & 3]), args.lr, args.weight_decay);
-        const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-        gstore_u2(xp + (int64_t)(4 * q) * dcur.cols, pk);
+        for (int w = 0; w < 4; ++w)
+          xin[w] = bload_f4(xres, ((w & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(4 * s + w) * ucols * 4);
       }
-    } else {
-      // fp32 parameters are read here, four rows at a time, to stay inside the register budget
-      float* xp = static_cast<float*>(dcur.param) + base;
+      float o[4][4];   // [w][e]
 #pragma unroll
-      for (int qb = 0; qb < 16; qb += 4) {
-        f32x4 xin[4];
+      for (int e = 0; e < 4; ++e) {
+        const float t1 = Cee[e][s] + Ceo[e][s], t2 = Cee[e][s] - Ceo[e][s];
+        const float rr[4] = {t1 + Co0[e][s], t2 + Co1[e][s], t2 - Co1[e][s], t1 - Co0[e][s]};
 #pragma unroll
-        for (int q = qb; q < qb + 4; ++q) xin[q - qb] = gload_f4(xp + (int64_t)(4 * q) * dcur.cols);
+        for (int w = 0; w < 4; ++w) {
+          const int q = 4 * s + w;
+          float x;
+          if (PBF16) {
+            const uint32_t raw = Xh[q][e >> 1];
+            x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+          } else {
+            x = xin[w][e];
+          }
+          o[w][e] = sign_update(x, sgnf(rr[w]), args.lr, args.weight_decay);
+        }
+      }
 #pragma unroll
-        for (int q = qb; q < qb + 4; ++q) {
-          f32x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            o[e] = sign_update(xin[q - qb][e], sgnf(R[q >> 2][e][q & 3]), args.lr, args.weight_decay);
-          gstore_f4(xp + (int64_t)(4 * q) * dcur.cols, o);
+      for (int w = 0; w < 4; ++w) {
+        const int q = 4 * s + w;
+        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
+        if (PBF16) {
+          const u32x2 pk = {pack_bf16x2(o[w][0], o[w][1]), pack_bf16x2(o[w][2], o[w][3])};
+          bstore_u2(xres, vo * 2, so * 2, pk);
+        } else {
+          const f32x4 ov = {o[w][0], o[w][1], o[w][2], o[w][3]};
+          bstore_f4(xres, vo * 4, so * 4, ov);
         }
       }
     }
@@ -272,21 +336,21 @@ static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, co
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, FULL>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, F64D_LDS_BYTES);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, D64_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wave64<PBF16, FULL>), dim3((unsigned)grid), dim3(F64D_THREADS), F64D_LDS_BYTES, stream,
+  hipLaunchKernelGGL((decode2d_wave64<PBF16, FULL>), dim3((unsigned)grid), dim3(D64_THREADS), D64_LDS_BYTES, stream,
                      tv, tables, a);
   return hipGetLastError();
 }
 
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
-                                  int num_cus, hipStream_t stream) {
+                                  bool payload_aligned16, int num_cus, hipStream_t stream) {
   int64_t grid = num_cus;
-  const int64_t max_grid = ((int64_t)tv.total_chunks + F64D_WAVES - 1) / F64D_WAVES;
+  const int64_t max_grid = ((int64_t)tv.total_chunks + D64_WAVES - 1) / D64_WAVES;
   if (grid > max_grid) grid = max_grid;
-  const bool full = a.k == 32 && a.W == 64;
+  const bool full = a.k == 32 && a.W == 64 && payload_aligned16;
   if (param_bf16)
     return full ? launch_dec_wave64<true, true>(tv, tables, a, grid, stream)
                 : launch_dec_wave64<true, false>(tv, tables, a, grid, stream);

@@ -80,6 +80,28 @@ __device__ __forceinline__ float sign_update(float x, float sg, float lr, float 
   return __fmaf_rn(-lr, t, x);
 }
 
+// Register layout shared by the s = 64 wavefront-per-chunk kernels.  Lane l = 16 g + c holds, for
+// q = 4 s + w, the four consecutive elements (row rho(q, g), columns 4 chi(c) .. 4 chi(c) + 3), so
+// that mirror quadruples {i, 31-i, 32+i, 63-i} of rows sit in one lane and those of columns in one
+// aligned group of four lanes.  freq(t, m) is the frequency held by row / column m of coefficient
+// tile t (tiles group frequencies by residue: 0 mod 4, 2 mod 4, odd).
+__host__ __device__ constexpr int rho(int q, int g) {
+  return (q & 3) == 0   ? 4 * (q >> 2) + g
+         : (q & 3) == 1 ? 31 - (4 * (q >> 2) + g)
+         : (q & 3) == 2 ? 32 + 4 * (q >> 2) + g
+                        : 63 - (4 * (q >> 2) + g);
+}
+// rho(q, g) = rho_base(q) + (q even ? g : 3 - g)
+__host__ __device__ constexpr int rho_base(int q) {
+  return (q & 3) == 0 ? 4 * (q >> 2) : (q & 3) == 1 ? 28 - 4 * (q >> 2) : (q & 3) == 2 ? 32 + 4 * (q >> 2) : 60 - 4 * (q >> 2);
+}
+__host__ __device__ constexpr int chi(int c) {
+  return (c & 3) == 0 ? (c >> 2) : (c & 3) == 1 ? 7 - (c >> 2) : (c & 3) == 2 ? 8 + (c >> 2) : 15 - (c >> 2);
+}
+__host__ __device__ constexpr int freq(int t, int m) {
+  return t == 0 ? 4 * m : t == 1 ? 4 * m + 2 : t == 2 ? 2 * m + 1 : 2 * m + 33;
+}
+
 // Raw buffer access: a uniform base (resource descriptor in SGPRs) plus a 32-bit per-lane byte
 // offset and a uniform byte offset.  Keeps per-lane addressing to one VGPR per access pattern.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {

@@ -44,17 +44,6 @@ constexpr int E64_SCRATCH_WORDS = 2 * (E64_CAP + 2) + 2 * 64;
 constexpr int E64_LDS_BYTES = 4 * (E64_TABLE_FLOATS + E64_WAVES * E64_SCRATCH_WORDS);
 static_assert(E64_TABLE_FLOATS == kEnc64TableFloats, "table size");
 
-// host and device agree on these maps
-__host__ __device__ constexpr int rho(int q, int g) {
-  return (q & 3) == 0 ? 4 * (q >> 2) + g : (q & 3) == 1 ? 31 - (4 * (q >> 2) + g) : (q & 3) == 2 ? 32 + 4 * (q >> 2) + g
-                                                                                                   : 63 - (4 * (q >> 2) + g);
-}
-__host__ __device__ constexpr int chi(int c) {
-  return (c & 3) == 0 ? (c >> 2) : (c & 3) == 1 ? 7 - (c >> 2) : (c & 3) == 2 ? 8 + (c >> 2) : 15 - (c >> 2);
-}
-// frequency held by column / row m (0..15) of coefficient tile t (0..3)
-__host__ __device__ constexpr int freq(int t, int m) { return t == 0 ? 4 * m : t == 1 ? 4 * m + 2 : t == 2 ? 2 * m + 1 : 2 * m + 33; }
-
 }  // namespace
 
 void build_enc64_tables(const double* P, float* out) {
@@ -157,9 +146,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     p.val = dd.val;
     return p;
   };
-  auto rbase = [](int q) {
-    return (q & 3) == 0 ? 4 * (q >> 2) : (q & 3) == 1 ? 28 - 4 * (q >> 2) : (q & 3) == 2 ? 32 + 4 * (q >> 2) : 60 - 4 * (q >> 2);
-  };
+  auto rbase = [](int q) { return rho_base(q); };
 
   // Raw inputs of the chunk being prefetched: its momentum rows are requested as soon as the
   // product-1 accumulators of the current chunk are dead, its bf16 gradient rows once top-k is done.
@@ -316,7 +303,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
             const uint64_t mask = __ballot(is);
             if (mask != 0) {
               if (is) {
-                const int pos = min(ncand + lanes_below(mask), E64_CAP);
+                const int pos = min((int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)ncand)), E64_CAP);
                 const uint32_t fbase = tt < 2 ? (vt < 2 ? fb_a : fb_b) : (vt < 2 ? fb_c : fb_d);
                 const uint32_t fconst = (uint32_t)(64 * freq(tt, 0) + freq(vt, r));
                 cand[pos] = make_uint2(__float_as_uint(q), fbase + fconst);
@@ -347,15 +334,19 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     // (3) rank candidates (magnitude descending, flat index ascending); ranks < k are the payload
     if (all_zero || skip) {
     } else if (ncand <= 64) {
-      // one candidate per lane; the others' keys come through v_readlane
+      // one candidate per lane; the others' keys come through v_readlane, four per trip (lanes past
+      // the list carry key 0, which precedes nothing)
       const uint2 me = cand[lane < ncand ? lane : 0];
-      const uint32_t mag = me.x & 0x7fffffffu, nfl = ~me.y;
+      const uint32_t mag = lane < ncand ? (me.x & 0x7fffffffu) : 0u, nfl = lane < ncand ? ~me.y : 0u;
       const uint64_t key = ((uint64_t)mag << 32) | nfl;
       int rank = 0;
-      for (int j = 0; j < ncand; ++j) {
-        const uint64_t kj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mag, j) << 32) |
-                            (uint32_t)__builtin_amdgcn_readlane((int)nfl, j);
-        rank += kj > key ? 1 : 0;
+      for (int j = 0; j < ncand; j += 4) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const uint64_t kj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mag, j + jj) << 32) |
+                              (uint32_t)__builtin_amdgcn_readlane((int)nfl, j + jj);
+          rank += kj > key ? 1 : 0;
+        }
       }
       if (lane < ncand && rank < k) {
         const int64_t po = (int64_t)cc * k + rank;

@@ -30,7 +30,8 @@ struct TableView {
   const int32_t* prefix;   // prefix[t] = first global chunk id of tensor t; prefix[n] = total
   int32_t n;
   int32_t total_chunks;
-  uint32_t dtypes;         // bit 0: some gradient is bf16, 1: some is f32, 2: some parameter is bf16, 3: some is f32
+  uint32_t dtypes;         // bit 0: some gradient is bf16, 1: some is f32, 2: some parameter is bf16, 3: some is f32,
+                           // bit 4: some payload pointer is not 16-byte aligned
 };
 
 // Chunks a fast kernel hands over to the exact generic kernel (device memory owned by the
@@ -73,7 +74,7 @@ hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const
 
 // s = 64 wavefront-per-chunk kernels (demo_enc64.hip, demo_dec64.hip).
 constexpr int kEnc64TableFloats = 3072 + 2 * 4096;
-constexpr int kDec64TableFloats = 2 * 4096;
+constexpr int kDec64TableFloats = 4096 + 1536;
 constexpr int kFast64MaxK = 64;
 void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
 void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
@@ -82,6 +83,6 @@ hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, cons
 // The decode kernel keeps all W workers' pairs of a chunk in registers: W <= 64 when k <= 32, W <= 32 above.
 inline bool fast64_decode_supports(int W, int k) { return k <= kFast64MaxK && W <= (k <= 32 ? 64 : 32); }
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
-                                  int num_cus, hipStream_t stream);
+                                  bool payload_aligned16, int num_cus, hipStream_t stream);
 
 }  // namespace demo

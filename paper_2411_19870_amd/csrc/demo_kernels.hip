@@ -595,7 +595,7 @@ hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, co
   if (tv.total_chunks == 0) return hipSuccess;
   const uint32_t pmix = (tv.dtypes >> 2) & 3u;   // parameter dtypes present: the wavefront kernel wants one
   if (variant >= 1 && s == 64 && fast64_decode_supports(a.W, a.k) && bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
-    return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, num_cus, stream);
+    return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {
     case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);
