@@ -149,6 +149,21 @@ def main():
             kms[name] = None
     ctx.demo_set_timing(False)
 
+    # plain copy of known size (outside the timed region): the copy bandwidth this GPU reaches, and the
+    # kernel the HBM traffic counters are calibrated with
+    probe_src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_()     # 4 GiB
+    probe_dst = torch.empty_like(probe_src)
+    for _ in range(2):
+        ctx.demo_copy_probe(probe_dst, probe_src, stream)
+    torch.cuda.synchronize()
+    ctx.demo_set_timing(True)
+    for _ in range(5):
+        ctx.demo_copy_probe(probe_dst, probe_src, stream)
+    probe_ms = ctx.demo_last_kernel_ms(1)
+    ctx.demo_set_timing(False)
+    probe_bytes = 2 * probe_src.numel() * 4
+    del probe_src, probe_dst
+
     dom = "enc2d" if (kms["enc2d"] or 0) >= (kms["dec2d"] or 0) else "dec2d"
     achieved = ab[dom] / (kms[dom] * 1e-3) / 1e9
     out = {
@@ -170,7 +185,16 @@ def main():
         "encode_params_per_s": nparams / (((kms["enc2d"] or 0) + (kms["enc1d"] or 0)) * 1e-3),
         "decode_params_per_s": nparams / (((kms["dec2d"] or 0) + (kms["dec1d"] or 0)) * 1e-3),
         "algorithmic_bytes_per_step": step_bytes,
+        "copy_probe": {"bytes_moved": probe_bytes, "ms": probe_ms, "gbs": probe_bytes / (probe_ms * 1e-3) / 1e9},
     }
+    # HBM traffic of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs (scaled by the
+    # copy probe), recorded under profiles/ when those runs were made for this workload
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{a.workload}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            rec = json.load(f)
+        if rec.get("variant") == a.variant and dom in rec.get("kernels", {}):
+            out["roofline"]["traffic"] = rec["kernels"][dom]["hbm_bytes_per_launch"]
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, a.seed)
     ctx.close()

@@ -117,6 +117,13 @@ int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, floa
 int demo_set_timing(demo_ctx* ctx, int enabled);
 int demo_last_kernel_ms(demo_ctx* ctx, int which, float* ms);
 
+/* Bandwidth probe: one plain streaming copy kernel of nbytes (a multiple of 16, both pointers
+ * 16-byte aligned, device memory) from src to dst.  It is what the HBM traffic counters are
+ * calibrated with (a copy of known size) and gives the copy bandwidth this GPU reaches; while
+ * timing is enabled its duration is recorded in slot 1 of demo_last_kernel_ms.  Not part of the
+ * method.  */
+int demo_copy_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes, void* hip_stream);
+
 /* Kernel family used by later calls: 1 (default) = the fastest kernels available
  * for the chunk size, 0 = the generic LDS-staged kernels only (kept selectable so
  * that the two families can be checked against each other).  */

@@ -23,7 +23,7 @@ DEMO_MAX_K = 256
 
 EXPORTS = [
     "demo_create", "demo_destroy", "demo_payload_elems", "demo_encode", "demo_decode", "demo_step",
-    "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_strerror", "demo_last_hip_error",
+    "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_copy_probe", "demo_strerror", "demo_last_hip_error",
 ]
 
 
@@ -65,6 +65,7 @@ def load_library() -> ctypes.CDLL:
     lib.demo_set_timing.argtypes = [vp, ci]
     lib.demo_last_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(cf)]
     lib.demo_set_variant.argtypes = [vp, ci]
+    lib.demo_copy_probe.argtypes = [vp, vp, vp, i64, vp]
     lib.demo_strerror.argtypes = [ci]
     lib.demo_strerror.restype = ctypes.c_char_p
     lib.demo_last_hip_error.argtypes = [vp]
@@ -198,6 +199,11 @@ class Context:
 
     def demo_set_variant(self, variant: int):
         self._check(self._lib.demo_set_variant(self._h, variant))
+
+    def demo_copy_probe(self, dst: torch.Tensor, src: torch.Tensor, stream=None):
+        nbytes = src.numel() * src.element_size()
+        assert dst.numel() * dst.element_size() >= nbytes
+        self._check(self._lib.demo_copy_probe(self._h, dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)))
 
     def demo_last_kernel_ms(self, which: int) -> float:
         ms = ctypes.c_float(0)

@@ -419,6 +419,20 @@ int demo_last_kernel_ms(demo_ctx* ctx, int which, float* ms) {
   return DEMO_OK;
 }
 
+int demo_copy_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes, void* hip_stream) {
+  if (ctx == nullptr || dst == nullptr || src == nullptr || nbytes < 0 || (nbytes & 15) != 0) return DEMO_ERR_ARG;
+  if (((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) != 0) return DEMO_ERR_ARG;
+  if (nbytes == 0) return DEMO_OK;
+  int rc = bind_device(ctx);
+  if (rc != DEMO_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // timed like an encode order-1 launch would be: slot 1 of the timing window is reused for the probe
+  if ((rc = timer_begin(ctx, 1, st)) != DEMO_OK) return rc;
+  hipError_t e = demo::launch_copy_probe(src, dst, (size_t)nbytes, ctx->num_cus, st);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  return timer_end(ctx, 1, st);
+}
+
 int demo_set_variant(demo_ctx* ctx, int variant) {
   if (ctx == nullptr || variant < 0 || variant > 1) return DEMO_ERR_ARG;
   ctx->variant = variant;

@@ -72,6 +72,8 @@ hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, co
 hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
                            hipStream_t stream);
 
+hipError_t launch_copy_probe(const void* src, void* dst, size_t nbytes, int num_cus, hipStream_t stream);
+
 // s = 64 wavefront-per-chunk kernels (demo_enc64.hip, demo_dec64.hip).
 constexpr int kEnc64TableFloats = 3072 + 2 * 4096;
 constexpr int kDec64TableFloats = 4096 + 1536;

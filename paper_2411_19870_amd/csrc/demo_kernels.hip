@@ -536,6 +536,25 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
 }
 
 // ---------------------------------------------------------------------------
+// plain streaming copy (bandwidth probe / calibration of the HBM traffic counters)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void copy_probe_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                         size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+hipError_t launch_copy_probe(const void* src, void* dst, size_t nbytes, int num_cus, hipStream_t stream) {
+  const size_t n16 = nbytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t grid = (size_t)num_cus * 16;
+  if (grid > (n16 + 255) / 256) grid = (n16 + 255) / 256;
+  hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)grid), dim3(256), 0, stream, static_cast<const float4*>(src),
+                     static_cast<float4*>(dst), n16);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // launch wrappers
 // ---------------------------------------------------------------------------
 template <int S>
