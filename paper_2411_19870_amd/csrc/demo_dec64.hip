@@ -27,9 +27,11 @@ constexpr int D64_LDT = 68;                        // tile row stride (floats); 
 constexpr int D64_TILE_FLOATS = 64 * D64_LDT;
 constexpr int D64_PCOL = 0;                        // pcol[v*64 + 4c + e] = P[v][4 chi(c) + e]
 constexpr int D64_TB = 4096;                       // product-b fragments: 6 groups x 64 lanes x 4
-constexpr int D64_TABLE_FLOATS = 4096 + 1536;
+constexpr int D64_TABLE_FLOATS = 4096 + 1536;  // what the dense kernel keeps in LDS
+constexpr int D64_PROW = 4096 + 1536;              // prow[u*64 + 4c + m] = P[u][rho(4m + c%4, c/4)] (sparse kernel only)
+constexpr int D64_ALL_TABLE_FLOATS = 4096 + 1536 + 4096;
 constexpr int D64_LDS_BYTES = 4 * (D64_TABLE_FLOATS + D64_WAVES * D64_TILE_FLOATS);
-static_assert(D64_TABLE_FLOATS == kDec64TableFloats, "table size");
+static_assert(D64_ALL_TABLE_FLOATS == kDec64TableFloats, "table size");
 }  // namespace
 
 // Host: tables of the decode kernel from the 64 x 64 basis P (double, row-major).
@@ -37,7 +39,10 @@ void build_dec64_tables(const double* P, float* out) {
   auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
   for (int v = 0; v < 64; ++v)
     for (int cc = 0; cc < 16; ++cc)
-      for (int e = 0; e < 4; ++e) out[D64_PCOL + v * 64 + 4 * cc + e] = Pm(v, 4 * chi(cc) + e);
+      for (int e = 0; e < 4; ++e) {
+        out[D64_PCOL + v * 64 + 4 * cc + e] = Pm(v, 4 * chi(cc) + e);
+        out[D64_PROW + v * 64 + 4 * cc + e] = Pm(v, rho(4 * e + (cc & 3), cc >> 2));
+      }
   // product b: output row m = c of a tile is the quadruple base i0 = 4(c % 4) + c / 4, so that lane
   // group g, component s of the accumulator is i0 = 4s + g; k-slot g of step r contracts
   // u = freq(tile, 4g + r)
@@ -330,6 +335,162 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   DEMO_PHASE_FLUSH(8);
 }
 
+// ---------------------------------------------------------------------------
+// Few pairs per chunk (W * k <= 64, e.g. a worker decoding its own payload): no coefficient tile.
+// R = sum_p val_p P[u_p]^T P[v_p] is one MFMA chain of contraction length W*k whose operands are
+// gathered rows of P, exactly like the reconstruction of the encode kernel; pairs of different
+// workers that hit the same coefficient simply add up inside the chain.
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int D64S_WAVES = 4;                     // three workgroups per CU (registers allow 3 wavefronts per SIMD)
+constexpr int D64S_THREADS = D64S_WAVES * 64;
+constexpr int D64S_LDS_BYTES = 4 * (2 * 4096 + D64S_WAVES * 2 * 64);
+}  // namespace
+
+template <bool PBF16>
+__global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, const float* __restrict__ tables,
+                                                                  DecodeArgs args) {
+  extern __shared__ float lds[];
+  const float* sPcol = lds;
+  const float* sProw = lds + 4096;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c = lane & 15;
+  uint2* sel = reinterpret_cast<uint2*>(lds + 2 * 4096) + wave * 64;   // {flat index, value bits}
+  const int k = args.k, W = args.W;
+  const int npairs = W * k, npad = (npairs + 3) & ~3;
+
+  for (int e = tid; e < 4096 / 4; e += D64S_THREADS) {
+    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + D64_PCOL)[e];
+    reinterpret_cast<float4*>(lds + 4096)[e] = reinterpret_cast<const float4*>(tables + D64_PROW)[e];
+  }
+  __syncthreads();
+
+  const int nwaves = gridDim.x * D64S_WAVES;
+  const int wid = blockIdx.x * D64S_WAVES + wave;
+  const int total = tv.total_chunks;
+  const int per = total / nwaves, rem = total - per * nwaves;
+  int chunk = wid * per + (wid < rem ? wid : rem);
+  const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
+  if (chunk >= chunk_end) return;
+
+  // pair `lane` of a chunk: worker lane / k, position lane % k
+  const int pw = lane / k, pt = lane - pw * k;
+  int32_t pi = -1;
+  float pv = 0.f;
+  auto load_pair = [&](const TensorDev& dd, int ccc) {
+    const int64_t off = ((int64_t)pw * dd.nchunks + ccc) * k + pt;
+    pi = lane < npairs ? as_global(dd.idx)[off] : -1;
+    pv = lane < npairs ? as_global(dd.val)[off] : 0.f;
+  };
+
+  int t = find_tensor(tv.prefix, tv.n, chunk);
+  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
+  TensorDev d = tv.descs[t];
+  load_pair(d, chunk - t_first);
+  const int col4 = 4 * chi(c);
+
+  for (; chunk < chunk_end; ++chunk) {
+    const int cc = chunk - t_first;
+    const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
+    const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
+    const uint32_t ucols = (uint32_t)d.cols;
+    const uint32_t vo_up = (uint32_t)g * ucols + (uint32_t)col4;           // elements
+    const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
+    const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
+                                              : make_rsrc(static_cast<const float*>(d.param) + origin);
+    // parameters of this chunk
+    u32x2 Xh[16];
+    f32x4 Xf[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      if (PBF16) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
+      else Xf[q] = bload_f4(xres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(q) * ucols * 4);
+    }
+    // pairs of this chunk -> LDS (out-of-range indices contribute nothing)
+    {
+      const bool ok = (uint32_t)pi < 4096u;
+      sel[lane] = make_uint2(ok ? (uint32_t)pi : 0u, ok ? __float_as_uint(pv) : 0u);
+    }
+    wave_lds_sync();
+    // pair of the next chunk (after the last chunk the same one again: keeps the old registers dead)
+    if (chunk + 1 < chunk_end) {
+      while (chunk + 1 >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = tv.prefix[t + 1];
+        d = tv.descs[t];
+      }
+      load_pair(d, chunk + 1 - t_first);
+    } else {
+      load_pair(d, cc);
+    }
+
+    f32x4 R[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) R[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < npad / 4; ++ks) {
+      const uint2 sv = sel[4 * ks + g];
+      const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
+      const float val = __uint_as_float(sv.y);
+      const float4 pa = *reinterpret_cast<const float4*>(&sProw[u * 64 + 4 * c]);
+      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[v * 64 + 4 * c]);
+      const float af[4] = {val * pa.x, val * pa.y, val * pa.z, val * pa.w};
+      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) R[mt][e] = mfma4(af[mt], bf[e], R[mt][e]);
+    }
+
+    // x <- x - lr*(sgn(R) + wd*x); R[mt][e][r] is the element (row rho(4mt + r, g), col 4 chi(c) + e)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float x;
+        if (PBF16) {
+          const uint32_t raw = Xh[q][e >> 1];
+          x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+        } else {
+          x = Xf[q][e];
+        }
+        o[e] = sign_update(x, sgnf(R[q >> 2][e][q & 3]), args.lr, args.weight_decay);
+      }
+      const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
+      if (PBF16) {
+        const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+        bstore_u2(xres, vo * 2, so * 2, pk);
+      } else {
+        const f32x4 ov = {o[0], o[1], o[2], o[3]};
+        bstore_f4(xres, vo * 4, so * 4, ov);
+      }
+    }
+    wave_lds_sync();
+  }
+}
+
+template <bool PBF16>
+static hipError_t launch_dec_sparse64(const TableView& tv, const float* tables, const DecodeArgs& a, int num_cus,
+                                      hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_sparse64<PBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, D64S_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  int64_t grid = (int64_t)num_cus * 3;
+  const int64_t max_grid = ((int64_t)tv.total_chunks + D64S_WAVES - 1) / D64S_WAVES;
+  if (grid > max_grid) grid = max_grid;
+  hipLaunchKernelGGL(decode2d_sparse64<PBF16>, dim3((unsigned)grid), dim3(D64S_THREADS), D64S_LDS_BYTES, stream, tv,
+                     tables, a);
+  return hipGetLastError();
+}
+
 template <bool PBF16, bool FULL>
 static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
@@ -347,6 +508,9 @@ static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, co
 
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream) {
+  if (a.W * a.k <= 64)
+    return param_bf16 ? launch_dec_sparse64<true>(tv, tables, a, num_cus, stream)
+                      : launch_dec_sparse64<false>(tv, tables, a, num_cus, stream);
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tv.total_chunks + D64_WAVES - 1) / D64_WAVES;
   if (grid > max_grid) grid = max_grid;

@@ -149,23 +149,28 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   auto rbase = [](int q) { return rho_base(q); };
 
   // Raw inputs of the chunk being prefetched: its momentum rows are requested as soon as the
-  // product-1 accumulators of the current chunk are dead, its bf16 gradient rows once top-k is done.
+  // product-1 accumulators of the current chunk are dead, its gradient rows once top-k is done.
   f32x4 nm[16];
-  u32x2 ng[16];
+  u32x2 ng[16];    // bf16 gradients
+  f32x4 ngf[16];   // fp32 gradients
   auto fetch_m = [&](const Place& p) {
 #pragma unroll
     for (int q = 0; q < 16; ++q)
       nm[q] = bload_f4(p.mres, ((q & 1) ? p.vo_dn : p.vo_up) * 4, (uint32_t)rbase(q) * p.ucols * 4);
   };
-  auto fetch_g16 = [&](const Place& p) {
+  auto fetch_g = [&](const Place& p) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q)
-      ng[q] = bload_u2(p.gres, ((q & 1) ? p.vo_dn : p.vo_up) * 2, (uint32_t)rbase(q) * p.ucols * 2);
+    for (int q = 0; q < 16; ++q) {
+      if (GBF16)
+        ng[q] = bload_u2(p.gres, ((q & 1) ? p.vo_dn : p.vo_up) * 2, (uint32_t)rbase(q) * p.ucols * 2);
+      else
+        ngf[q] = bload_f4(p.gres, ((q & 1) ? p.vo_dn : p.vo_up) * 4, (uint32_t)rbase(q) * p.ucols * 4);
+    }
   };
 
   Place cur = place(d, chunk - t_first);
   fetch_m(cur);
-  if (GBF16) fetch_g16(cur);
+  fetch_g(cur);
 
   DEMO_PHASE_DECL
   for (; chunk < chunk_end; ++chunk) {
@@ -196,13 +201,10 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
         D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], __uint_as_float(ng[q][1] & 0xffff0000u));
       }
     } else {
-      // fp32 gradients are not prefetched (no registers to park them in): read them now
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const f32x4 gr = bload_f4(cur.gres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4);
+      for (int q = 0; q < 16; ++q)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], gr[e]);
-      }
+        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], ngf[q][e]);
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -377,7 +379,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     }
     if (lane >= k && lane < kpad) sel[lane] = make_uint2(0u, 0u);
     wave_lds_sync();
-    if (GBF16) fetch_g16(nxt);   // the coefficient registers are dead now
+    fetch_g(nxt);   // the coefficient registers are dead now
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(5);
