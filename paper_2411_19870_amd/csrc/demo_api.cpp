@@ -22,6 +22,7 @@ struct BasisTable {
   float* dev = nullptr;      // P, s x s
   float* enc64 = nullptr;    // tables of the s = 64 wavefront-per-chunk kernels
   float* dec64 = nullptr;
+  float* enc32 = nullptr;    // dense-basis tile tables for s = 32
 };
 
 // One cached descriptor upload: the host bytes it was built from and the device copy.
@@ -30,6 +31,7 @@ struct TableCache {
   void* dev = nullptr;        // [TensorDev x n2][int32 x (n2+1)] [TensorDev x n1][int32 x (n1+1)]
   size_t dev_bytes = 0;
   TableView tv2{}, tv1{};
+  TableView tv2t{};           // order-2 tensors counted in 64 x 64 tiles (s = 32, all dimensions multiples of 64), else n = 0
   demo::Worklist wl{};        // queue of order-2 chunks for the exact fallback kernel
   uint64_t last_use = 0;
 };
@@ -133,7 +135,7 @@ int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
 
 int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   for (const BasisTable& b : ctx->bases)
-    if (b.s == s) { *out = demo::BasisTables{b.dev, b.enc64, b.dec64}; return DEMO_OK; }
+    if (b.s == s) { *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32}; return DEMO_OK; }
   std::vector<double> P((size_t)s * s);
   const double pi = 3.14159265358979323846;
   for (int u = 0; u < s; ++u) {
@@ -152,8 +154,18 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     if ((rc = upload(ctx, et, &b.enc64)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
     if ((rc = upload(ctx, dt, &b.dec64)) != DEMO_OK) { (void)hipFree(b.dev); (void)hipFree(b.enc64); return rc; }
   }
+  if (s == 32) {
+    // 64 x 64 block-diagonal basis diag(P32, P32): a wavefront tile holds 2 x 2 chunks
+    std::vector<double> B2(64 * 64, 0.0);
+    for (int blk = 0; blk < 2; ++blk)
+      for (int u = 0; u < 32; ++u)
+        for (int i = 0; i < 32; ++i) B2[(size_t)(32 * blk + u) * 64 + 32 * blk + i] = P[(size_t)u * 32 + i];
+    std::vector<float> et(demo::kEnc64dTableFloats);
+    demo::build_enc64d_tables(B2.data(), et.data());
+    if ((rc = upload(ctx, et, &b.enc32)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
+  }
   ctx->bases.push_back(b);
-  *out = demo::BasisTables{b.dev, b.enc64, b.dec64};
+  *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32};
   return DEMO_OK;
 }
 
@@ -170,8 +182,9 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
       return DEMO_OK;
     }
   }
-  std::vector<TensorDev> d2, d1;
-  std::vector<int32_t> p2(1, 0), p1(1, 0);
+  std::vector<TensorDev> d2, d1, d2t;
+  std::vector<int32_t> p2(1, 0), p1(1, 0), p2t(1, 0);
+  bool tiles_ok = s == 32;
   uint32_t mix2 = 0, mix1 = 0;
   for (int i = 0; i < n; ++i) {
     const bool al16 = ((reinterpret_cast<uintptr_t>(t[i].idx) | reinterpret_cast<uintptr_t>(t[i].val)) & 15u) == 0;
@@ -197,6 +210,12 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
       d.nchunks = (int32_t)((t[i].rows / s) * (t[i].cols / s));
       d2.push_back(d);
       p2.push_back(p2.back() + d.nchunks);
+      if (t[i].rows % 64 != 0 || t[i].cols % 64 != 0) tiles_ok = false;
+      TensorDev dt = d;
+      dt.cchunks = (int32_t)(t[i].cols / 64);
+      dt.nchunks = (int32_t)((t[i].rows / 64) * (t[i].cols / 64));
+      d2t.push_back(dt);
+      p2t.push_back(p2t.back() + dt.nchunks);
     }
   }
   auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
@@ -205,12 +224,17 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   const size_t o_d1 = align16(o_p2 + p2.size() * sizeof(int32_t));
   const size_t o_p1 = align16(o_d1 + d1.size() * sizeof(TensorDev));
   const size_t o_wl = align16(o_p1 + p1.size() * sizeof(int32_t));   // count, ticket, pad, pad, list[]
-  const size_t total = align16(o_wl + (4 + (size_t)p2.back()) * sizeof(int32_t));
+  const size_t o_d2t = align16(o_wl + (4 + (size_t)p2.back()) * sizeof(int32_t));
+  if (!tiles_ok) { d2t.clear(); p2t.assign(1, 0); }
+  const size_t o_p2t = align16(o_d2t + d2t.size() * sizeof(TensorDev));
+  const size_t total = align16(o_p2t + p2t.size() * sizeof(int32_t));
   std::vector<char> host(total, 0);
   if (!d2.empty()) std::memcpy(host.data() + o_d2, d2.data(), d2.size() * sizeof(TensorDev));
   std::memcpy(host.data() + o_p2, p2.data(), p2.size() * sizeof(int32_t));
   if (!d1.empty()) std::memcpy(host.data() + o_d1, d1.data(), d1.size() * sizeof(TensorDev));
   std::memcpy(host.data() + o_p1, p1.data(), p1.size() * sizeof(int32_t));
+  if (!d2t.empty()) std::memcpy(host.data() + o_d2t, d2t.data(), d2t.size() * sizeof(TensorDev));
+  std::memcpy(host.data() + o_p2t, p2t.data(), p2t.size() * sizeof(int32_t));
 
   TableCache* slot = nullptr;
   if ((int)ctx->tables.size() < kMaxCachedTables) {
@@ -246,6 +270,11 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   slot->tv1.n = (int32_t)d1.size();
   slot->tv1.total_chunks = p1.back();
   slot->tv1.dtypes = mix1;
+  slot->tv2t.descs = reinterpret_cast<const TensorDev*>(base + o_d2t);
+  slot->tv2t.prefix = reinterpret_cast<const int32_t*>(base + o_p2t);
+  slot->tv2t.n = (int32_t)d2t.size();
+  slot->tv2t.total_chunks = p2t.back();
+  slot->tv2t.dtypes = mix2;
   int32_t* wl = reinterpret_cast<int32_t*>(base + o_wl);   // zero-filled by the copy above
   slot->wl = demo::Worklist{wl, wl + 1, wl + 4};
   slot->key.swap(key);
@@ -283,7 +312,7 @@ int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, fl
   int rc;
   if (tc->tv2.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 0, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_encode2d(tc->tv2, basis, s, a, tc->wl, ctx->num_cus, ctx->variant, st);
+    hipError_t e = demo::launch_encode2d(tc->tv2, tc->tv2t.n > 0 ? &tc->tv2t : nullptr, basis, s, a, tc->wl, ctx->num_cus, ctx->variant, st);
     if (e != hipSuccess) return fail_hip(ctx, e);
     if ((rc = timer_end(ctx, 0, st)) != DEMO_OK) return rc;
   }
@@ -342,6 +371,7 @@ int demo_destroy(demo_ctx* ctx) {
       (void)hipFree(b.dev);
       if (b.enc64) (void)hipFree(b.enc64);
       if (b.dec64) (void)hipFree(b.dec64);
+      if (b.enc32) (void)hipFree(b.enc32);
     }
     for (TableCache& tc : ctx->tables)
       if (tc.dev) (void)hipFree(tc.dev);

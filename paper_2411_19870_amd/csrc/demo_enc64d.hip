@@ -1,0 +1,376 @@
+// Dense-basis variant of the wavefront-per-tile encode kernel.
+//
+// Same ownership, register layout, prefetch and in-wavefront top-k as demo_enc64.hip, but the two
+// products are plain dense MFMA chains against an arbitrary 64 x 64 basis B (fragments in LDS), so the
+// kernel does not depend on the symmetries of the 64-point DCT.  It is used for chunk size s = 32:
+// a wavefront owns a 64 x 64 tile = 2 x 2 chunks and B = diag(P32, P32); products with the zero
+// blocks are skipped at compile time (128 MFMAs per product), top-k runs once per chunk on the 16
+// coefficients each lane holds of it, and the reconstruction contracts over all 4k selected
+// coefficients at once (rows of B vanish outside their own chunk, so no masking is needed).
+#include "demo_device.h"
+
+namespace demo {
+
+namespace {
+constexpr int ED_WAVES = 8;
+constexpr int ED_THREADS = ED_WAVES * 64;
+constexpr int ED_CAP = 128;                       // candidate list capacity per wavefront
+constexpr int ED_T1 = 0;                          // t1[(q*64 + lane)*4 + nt]      = B[16nt + c][rho(q, g)]
+constexpr int ED_T2 = 4096;                       // t2[((4e+r)*64 + lane)*4 + mt] = B[16mt + c][4 chi(4g+r) + e]
+constexpr int ED_PCOL = 2 * 4096;                 // pcol[v*64 + 4c + e] = B[v][4 chi(c) + e]
+constexpr int ED_PROW = 3 * 4096;                 // prow[u*64 + 4c + m] = B[u][rho(4m + c%4, c/4)]
+constexpr int ED_TABLE_FLOATS = 4 * 4096;
+constexpr int ED_SELMAX = 4 * 64;                 // selected coefficients of a tile (4 chunks x k <= 64)
+// per-wavefront scratch: candidates {value bits, flat} [CAP + 2], selected {position in tile, value bits} [SELMAX]
+constexpr int ED_SCRATCH_WORDS = 2 * (ED_CAP + 2) + 2 * ED_SELMAX;
+constexpr int ED_LDS_BYTES = 4 * (ED_TABLE_FLOATS + ED_WAVES * ED_SCRATCH_WORDS);
+static_assert(ED_TABLE_FLOATS == kEnc64dTableFloats, "table size");
+}  // namespace
+
+// Host: fragment tables from a 64 x 64 basis B (double, row-major, rows = frequencies).
+void build_enc64d_tables(const double* Bm, float* out) {
+  auto Bf = [&](int u, int i) { return (float)Bm[u * 64 + i]; };
+  for (int lane = 0; lane < 64; ++lane) {
+    const int g = lane >> 4, c = lane & 15;
+    for (int q = 0; q < 16; ++q)
+      for (int nt = 0; nt < 4; ++nt) out[ED_T1 + (q * 64 + lane) * 4 + nt] = Bf(16 * nt + c, rho(q, g));
+    for (int e = 0; e < 4; ++e)
+      for (int r = 0; r < 4; ++r)
+        for (int mt = 0; mt < 4; ++mt)
+          out[ED_T2 + ((4 * e + r) * 64 + lane) * 4 + mt] = Bf(16 * mt + c, 4 * chi(4 * g + r) + e);
+  }
+  for (int u = 0; u < 64; ++u)
+    for (int cc = 0; cc < 16; ++cc)
+      for (int x = 0; x < 4; ++x) {
+        out[ED_PCOL + u * 64 + 4 * cc + x] = Bf(u, 4 * chi(cc) + x);
+        out[ED_PROW + u * 64 + 4 * cc + x] = Bf(u, rho(4 * x + (cc & 3), cc >> 2));
+      }
+}
+
+// The table `tv` lists the order-2 tensors in units of 64 x 64 tiles (cchunks = cols / 64,
+// nchunks = tiles); payload arrays are addressed per 32 x 32 chunk.
+template <bool GBF16>
+__global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, const int32_t* __restrict__ prefix32,
+                                                              const float* __restrict__ tables, EncodeArgs args,
+                                                              Worklist wl) {
+  extern __shared__ float lds[];
+  const float* sT1 = lds + ED_T1;
+  const float* sT2 = lds + ED_T2;
+  const float* sPcol = lds + ED_PCOL;
+  const float* sProw = lds + ED_PROW;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c = lane & 15;
+  uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + ED_TABLE_FLOATS) + wave * ED_SCRATCH_WORDS;
+  uint2* cand = reinterpret_cast<uint2*>(scratch);                      // {value bits, flat index in the chunk}
+  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (ED_CAP + 2));    // {row*64 + col in the tile's coefficient plane, value bits}
+  const int k = args.k;
+  const int kpad = (k + 3) & ~3;
+
+  for (int e = tid; e < ED_TABLE_FLOATS / 4; e += ED_THREADS)
+    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
+  __syncthreads();
+
+  const int nwaves = gridDim.x * ED_WAVES;
+  const int wid = blockIdx.x * ED_WAVES + wave;
+  const int total = tv.total_chunks;
+  const int per = total / nwaves, rem = total - per * nwaves;
+  int tileno = wid * per + (wid < rem ? wid : rem);
+  const int tile_end = tileno + per + (wid < rem ? 1 : 0);
+  if (tileno >= tile_end) return;
+  int t = find_tensor(tv.prefix, tv.n, tileno);
+  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
+  TensorDev d = tv.descs[t];
+
+  const int col4 = 4 * chi(c);
+  // flat index inside a chunk of coefficient C2[mt][nt][r]: (16(nt&1) + c)*32 + 16(mt&1) + 4g + r
+  uint32_t fb = (uint32_t)(32 * c + 4 * g);
+
+  struct Place {
+    __amdgpu_buffer_rsrc_t mres, gres;
+    uint32_t ucols, vo_up, vo_dn;   // elements
+    int K0, K1, cch32;              // tile position, chunks per tensor row (32-grid)
+    int tix;                        // tensor number
+    int32_t* idx;
+    float* val;
+  };
+  auto place = [&](const TensorDev& dd, int tt) {
+    const int k0 = tt / dd.cchunks, k1 = tt - k0 * dd.cchunks;
+    const int64_t origin = (int64_t)k0 * 64 * dd.cols + (int64_t)k1 * 64;   // uniform
+    Place p;
+    p.ucols = (uint32_t)dd.cols;
+    p.vo_up = (uint32_t)g * p.ucols + (uint32_t)col4;
+    p.vo_dn = (uint32_t)(3 - g) * p.ucols + (uint32_t)col4;
+    p.mres = make_rsrc(dd.mom + origin);
+    p.gres = GBF16 ? make_rsrc(static_cast<const uint16_t*>(dd.grad) + origin)
+                   : make_rsrc(static_cast<const float*>(dd.grad) + origin);
+    p.K0 = k0;
+    p.K1 = k1;
+    p.cch32 = 2 * dd.cchunks;
+    p.tix = t;
+    p.idx = dd.idx;
+    p.val = dd.val;
+    return p;
+  };
+
+  f32x4 nm[16];
+  u32x2 ng[16];    // bf16 gradients
+  f32x4 ngf[16];   // fp32 gradients
+  auto fetch_m = [&](const Place& p) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q)
+      nm[q] = bload_f4(p.mres, ((q & 1) ? p.vo_dn : p.vo_up) * 4, (uint32_t)rho_base(q) * p.ucols * 4);
+  };
+  auto fetch_g = [&](const Place& p) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      if (GBF16)
+        ng[q] = bload_u2(p.gres, ((q & 1) ? p.vo_dn : p.vo_up) * 2, (uint32_t)rho_base(q) * p.ucols * 2);
+      else
+        ngf[q] = bload_f4(p.gres, ((q & 1) ? p.vo_dn : p.vo_up) * 4, (uint32_t)rho_base(q) * p.ucols * 4);
+    }
+  };
+
+  Place cur = place(d, tileno - t_first);
+  fetch_m(cur);
+  fetch_g(cur);
+
+  for (; tileno < tile_end; ++tileno) {
+    const uint32_t ucols = cur.ucols, vo_up = cur.vo_up, vo_dn = cur.vo_dn;
+    const __amdgpu_buffer_rsrc_t mres = cur.mres;
+    Place nxt = cur;
+    if (tileno + 1 < tile_end) {
+      while (tileno + 1 >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = tv.prefix[t + 1];
+        d = tv.descs[t];
+      }
+      nxt = place(d, tileno + 1 - t_first);
+    }
+
+    // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ------------------
+    f32x4 D[4][4];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      if (GBF16) {
+        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], __uint_as_float(ng[q][0] << 16));
+        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], __uint_as_float(ng[q][0] & 0xffff0000u));
+        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], __uint_as_float(ng[q][1] << 16));
+        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], __uint_as_float(ng[q][1] & 0xffff0000u));
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], ngf[q][e]);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- product 1: C1[e][nt] rows j = 4 chi(4g+r) + e, cols U = 16nt + c.  Rows rho(q, g) with
+    //      q%4 < 2 lie in the upper chunks, the others in the lower ones: only the matching half of
+    //      the frequency tiles is non-zero.
+    f32x4 C1[4][4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) C1[e][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      float4 pn = *reinterpret_cast<const float4*>(&sT1[lane * 4]);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float pf[4] = {pn.x, pn.y, pn.z, pn.w};
+        if (q + 1 < 16) pn = *reinterpret_cast<const float4*>(&sT1[((q + 1) * 64 + lane) * 4]);
+        const int br = (q & 3) >> 1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int nh = 0; nh < 2; ++nh) {
+            const int nt = 2 * br + nh;
+            C1[e][nt] = mfma4(D[q >> 2][e][q & 3], pf[nt], C1[e][nt]);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+
+    // ---- product 2: C2[mt][nt] rows V = 16mt + 4g + r, cols U = 16nt + c.  k-step (e, r) contracts
+    //      j = 4 chi(4g+r) + e, which lies in the left chunks for r < 2 and in the right ones otherwise.
+    f32x4 C2[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) C2[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      float4 pn = *reinterpret_cast<const float4*>(&sT2[lane * 4]);
+#pragma unroll
+      for (int er = 0; er < 16; ++er) {
+        const int e = er >> 2, r = er & 3;
+        const float pf[4] = {pn.x, pn.y, pn.z, pn.w};
+        if (er + 1 < 16) pn = *reinterpret_cast<const float4*>(&sT2[((er + 1) * 64 + lane) * 4]);
+        const int bc = r >> 1;
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) {
+            const int mt = 2 * bc + mh;
+            C2[mt][nt] = mfma4(pf[mt], C1[e][nt][r], C2[mt][nt]);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // the next tile's momentum rows land while top-k, reconstruction and store of this one run
+    fetch_m(nxt);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- top-k, once per chunk (bu, bv): coefficients C2[2bv + mh][2bu + nh][r] ---------------------------
+    asm volatile("" : "+v"(fb));
+    bool skip = false;
+    int nsel = 0;   // entries written to `sel` so far (kpad per chunk)
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) {
+      const int bu = sub >> 1, bv = sub & 1;
+      float lmax = 0.f;
+#pragma unroll
+      for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+        for (int nh = 0; nh < 2; ++nh)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) lmax = fmaxf(lmax, fabsf(C2[2 * bv + mh][2 * bu + nh][r]));
+      const uint32_t lm = __float_as_uint(lmax);
+      uint32_t thr = 0;
+      for (int bit = 30; bit >= 16; --bit) {
+        const uint32_t cnd = thr | (1u << bit);
+        if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
+      }
+      int ncand = 0;
+      {
+        const float thr_f = __uint_as_float(thr);
+#pragma unroll
+        for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+          for (int nh = 0; nh < 2; ++nh)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float q = C2[2 * bv + mh][2 * bu + nh][r];
+              const bool is = fabsf(q) >= thr_f;
+              const uint64_t mask = __ballot(is);
+              if (mask != 0) {
+                if (is) {
+                  const int pos = min((int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)ncand)), ED_CAP);
+                  cand[pos] = make_uint2(__float_as_uint(q), fb + (uint32_t)(512 * nh + 16 * mh + r));
+                }
+                ncand += __popcll(mask);
+              }
+            }
+      }
+      const bool overflow = ncand > ED_CAP;
+      const bool all_zero = overflow && __ballot(lm != 0u) == 0;
+      if (overflow && !all_zero) skip = true;   // near-ties en masse: the whole tile goes to the exact kernel
+      const int c32 = (2 * cur.K0 + bu) * cur.cch32 + 2 * cur.K1 + bv;   // chunk number in the tensor
+      wave_lds_sync();
+      if (all_zero) {
+        if (lane < k) {
+          const int64_t po = (int64_t)c32 * k + lane;
+          as_global(cur.idx)[po] = lane;
+          as_global(cur.val)[po] = 0.f;
+        }
+        if (lane < kpad) sel[nsel + lane] = make_uint2(0u, 0u);
+      } else if (!overflow) {
+        // rank the candidates (magnitude descending, flat index ascending); ranks < k are the payload
+        for (int i0 = 0; i0 < ncand; i0 += 64) {
+          const int i = i0 + lane;
+          const uint2 me = cand[i < ncand ? i : 0];
+          const uint32_t mag = me.x & 0x7fffffffu;
+          int rank = 0;
+          if (ncand <= 64) {
+            const uint32_t magl = i < ncand ? mag : 0u, nfl = i < ncand ? ~me.y : 0u;
+            const uint64_t key = ((uint64_t)magl << 32) | nfl;
+            for (int j = 0; j < ncand; j += 4) {
+#pragma unroll
+              for (int jj = 0; jj < 4; ++jj) {
+                const uint64_t kj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)magl, j + jj) << 32) |
+                                    (uint32_t)__builtin_amdgcn_readlane((int)nfl, j + jj);
+                rank += kj > key ? 1 : 0;
+              }
+            }
+          } else {
+            for (int j = 0; j < ncand; ++j) {
+              const uint2 o = cand[j];
+              const uint32_t mo = o.x & 0x7fffffffu;
+              rank += (mo > mag || (mo == mag && o.y < me.y)) ? 1 : 0;
+            }
+          }
+          if (i < ncand && rank < k) {
+            const int64_t po = (int64_t)c32 * k + rank;
+            as_global(cur.idx)[po] = (int32_t)me.y;
+            as_global(cur.val)[po] = __uint_as_float(me.x);
+            // position in the tile's coefficient plane: (32bu + u)*64 + 32bv + v
+            const uint32_t u = me.y >> 5, v = me.y & 31u;
+            sel[nsel + rank] = make_uint2((32 * bu + u) * 64 + 32 * bv + v, me.x);
+          }
+        }
+        if (lane >= k && lane < kpad) sel[nsel + lane] = make_uint2(0u, 0u);
+      }
+      nsel += kpad;
+      wave_lds_sync();
+    }
+    if (skip) {
+      // leave the tile untouched (its payload entries are overwritten too) and queue its four chunks
+      if (lane < 4) {
+        const int c32 = (2 * cur.K0 + (lane >> 1)) * cur.cch32 + 2 * cur.K1 + (lane & 1);
+        wl.list[atomicAdd(wl.count, 1)] = prefix32[cur.tix] + c32;   // chunk number in the 32-grid table
+      }
+    }
+    fetch_g(nxt);   // the coefficient registers are dead now
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- reconstruction accumulated into D over all selected coefficients of the tile ----------------
+    for (int ks = 0; ks < (skip ? 0 : nsel / 4); ++ks) {
+      const uint2 sv = sel[4 * ks + g];
+      const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
+      const float nv = -__uint_as_float(sv.y);
+      const float4 pa = *reinterpret_cast<const float4*>(&sProw[u * 64 + 4 * c]);
+      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[v * 64 + 4 * c]);
+      const float af[4] = {nv * pa.x, nv * pa.y, nv * pa.z, nv * pa.w};
+      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) D[mt][e] = mfma4(af[mt], bf[e], D[mt][e]);
+    }
+    if (!skip) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
+        bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(q) * ucols * 4, o);
+      }
+    }
+    wave_lds_sync();
+    cur = nxt;
+  }
+}
+
+template <bool GBF16>
+static hipError_t launch_tile32(const TableView& tiles, const int32_t* prefix32, const float* tables,
+                                const EncodeArgs& a, const Worklist& wl, int64_t grid, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_tile32<GBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, ED_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(encode2d_tile32<GBF16>, dim3((unsigned)grid), dim3(ED_THREADS), ED_LDS_BYTES, stream, tiles,
+                     prefix32, tables, a, wl);
+  return hipGetLastError();
+}
+
+hipError_t launch_encode2d_tile32(const TableView& tiles, const int32_t* prefix32, const float* tables,
+                                  const EncodeArgs& a, const Worklist& wl, bool grad_bf16, int num_cus,
+                                  hipStream_t stream) {
+  int64_t grid = num_cus;
+  const int64_t max_grid = ((int64_t)tiles.total_chunks + ED_WAVES - 1) / ED_WAVES;
+  if (grid > max_grid) grid = max_grid;
+  return grad_bf16 ? launch_tile32<true>(tiles, prefix32, tables, a, wl, grid, stream)
+                   : launch_tile32<false>(tiles, prefix32, tables, a, wl, grid, stream);
+}
+
+}  // namespace demo

@@ -59,12 +59,15 @@ struct BasisTables {
   const float* basis;    // s x s orthonormal DCT-II matrix P, row-major float32
   const float* enc64;    // fragment tables of the wavefront-per-chunk encode kernel (s = 64 only, else null)
   const float* dec64;    // tables of the wavefront-per-chunk decode kernel (s = 64 only, else null)
+  const float* enc32;    // dense-basis tile tables for diag(P32, P32) (s = 32 only, else null)
 };
 
 // Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:
 // 0 = generic LDS-staged kernels, 1 = fastest available for this s and k.
-hipError_t launch_encode2d(const TableView& tv, const BasisTables& bt, int s, const EncodeArgs& a,
-                           const Worklist& wl, int num_cus, int variant, hipStream_t stream);
+// `tiles` (may be null): the same order-2 tensors counted in 64 x 64 tiles, present when s = 32 and
+// every order-2 dimension is a multiple of 64.
+hipError_t launch_encode2d(const TableView& tv, const TableView* tiles, const BasisTables& bt, int s,
+                           const EncodeArgs& a, const Worklist& wl, int num_cus, int variant, hipStream_t stream);
 hipError_t launch_encode1d(const TableView& tv, const float* basis, int s, const EncodeArgs& a,
                            hipStream_t stream);
 hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, const DecodeArgs& a,
@@ -82,6 +85,12 @@ void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
 void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                   bool grad_bf16, int num_cus, hipStream_t stream);
+// dense-basis tile kernel (demo_enc64d.hip)
+constexpr int kEnc64dTableFloats = 4 * 4096;
+void build_enc64d_tables(const double* B64, float* out /* kEnc64dTableFloats */);
+hipError_t launch_encode2d_tile32(const TableView& tiles, const int32_t* prefix32, const float* tables,
+                                  const EncodeArgs& a, const Worklist& wl, bool grad_bf16, int num_cus,
+                                  hipStream_t stream);
 // The decode kernel keeps all W workers' pairs of a chunk in registers: W <= 64 when k <= 32, W <= 32 above.
 inline bool fast64_decode_supports(int W, int k) { return k <= kFast64MaxK && W <= (k <= 32 ? 64 : 32); }
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,

@@ -588,11 +588,18 @@ static hipError_t launch_dec2d_generic(const TableView& tv, const float* basis, 
   return hipGetLastError();
 }
 
-hipError_t launch_encode2d(const TableView& tv, const BasisTables& bt, int s, const EncodeArgs& a,
-                           const Worklist& wl, int num_cus, int variant, hipStream_t stream) {
+hipError_t launch_encode2d(const TableView& tv, const TableView* tiles, const BasisTables& bt, int s,
+                           const EncodeArgs& a, const Worklist& wl, int num_cus, int variant, hipStream_t stream) {
   if (tv.total_chunks == 0) return hipSuccess;
   const float* basis = bt.basis;
-  const uint32_t gmix = tv.dtypes & 3u;   // gradient dtypes present: the wavefront kernel wants one
+  const uint32_t gmix = tv.dtypes & 3u;   // gradient dtypes present: the wavefront kernels want one
+  if (variant >= 1 && s == 32 && a.k <= kFast64MaxK && bt.enc32 != nullptr && tiles != nullptr &&
+      wl.list != nullptr && (gmix == 1u || gmix == 2u)) {
+    // wavefront-per-tile kernel (2 x 2 chunks), then the exact generic kernel over whatever it queued
+    hipError_t e = launch_encode2d_tile32(*tiles, tv.prefix, bt.enc32, a, wl, gmix == 1u, num_cus, stream);
+    if (e != hipSuccess) return e;
+    return launch_enc2d_generic<32>(tv, basis, a, wl, num_cus, stream);
+  }
   if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.enc64 != nullptr && wl.list != nullptr &&
       (gmix == 1u || gmix == 2u)) {
     // wavefront-per-chunk kernel, then the exact generic kernel over whatever it queued
