@@ -1,40 +1,58 @@
 // s = 64 decode kernel: one wavefront per 64 x 64 chunk.
 //
-// The parameters of the chunk use the register layout of the encode kernel (demo_device.h: lane
-// l = 16 g + c holds rows rho(q, g), columns 4 chi(c) .. +3), so every load and store instruction
-// still covers whole 256-byte rows and each lane owns complete mirror quadruples of rows.
+// R = P^T S P for the coefficient sums S of the W payloads, with both basis products reduced to 3/8
+// of their dense size by the mirror symmetries of the DCT-II basis:
+//   rows u = 0 mod 4 of P are even under i -> 63-i and under i -> 31-i,
+//   rows u = 2 mod 4 are even under i -> 63-i and odd under i -> 31-i,
+//   odd rows are odd under i -> 63-i,
+// so for a mirror quadruple {i0, 31-i0, 32+i0, 63-i0} (i0 < 16) only four partial sums are needed
+// (ee: u = 0 mod 4 at i0; eo: u = 2 mod 4 at i0; o0, o1: odd u at i0 and at 31-i0):
+//   out[i0] = ee+eo+o0, out[31-i0] = ee-eo+o1, out[32+i0] = ee-eo-o1, out[63-i0] = ee+eo-o0.
+// The same holds for the columns.  Both products therefore keep the four members of a quadruple
+// in one lane: lane l = 16 g + c ends up with the elements
+//   rows    member(w, 4 s + g)        s, w  = 0..3   (16 rows)
+//   columns member(w', kappa(c))      w'    = 0..3   ( 4 columns)
+// and reads / writes the parameters in exactly that layout.  One access instruction (fixed s, w,
+// w') then covers four rows x sixteen adjacent columns, i.e. whole 32-byte (bf16) or 64-byte (fp32)
+// sectors, and the four w' of a row fill its 128 / 256 bytes.
 //
-// The coefficient sums S of the W payloads are accumulated in a private LDS tile, in block fixed
-// point with integer atomics (see `scatter` below).  R = P^T (S P) then runs as two chains of
+// S is accumulated in a private LDS tile in block fixed point with integer atomics (see `scatter`
+// below); its rows and columns are stored grouped by residue mod 4 (physical index
+// 16 (u % 4) + u / 4), which is what the partial sums contract over.  The products run as chains of
 // v_mfma_f32_16x16x4_f32:
-//   product a   Y[u][j] = sum_v S[u][v] P[v][j]   A = S from LDS (rows taken in the order of the
-//               coefficient tiles: u = 0 mod 4, 2 mod 4, odd), B = rows of P; dense.
-//   product b   R[i][j] = sum_u P[u][i] Y[u][j]   A = basis fragments, B = product-a accumulators.
-//               Rows of P with u = 0 mod 4 are even under both mirrors i -> 63-i and i -> 31-i,
-//               rows with u = 2 mod 4 even / odd, odd rows odd under i -> 63-i, so only the rows
-//               i0 < 16 (two classes) and i < 32 (odd class) are computed -- 3/8 of the dense
-//               product -- and the four members of a quadruple follow from in-lane adds:
-//                 R[i0] = ee+eo+o0, R[31-i0] = ee-eo+o1, R[32+i0] = ee-eo-o1, R[63-i0] = ee+eo-o0.
-// R lands in the register layout of the parameters, so the sign update is fused.
+//   product a   per row tile t (rows u = 4 m + t):  ee/eo/o0/o1[u][j0] = sum over one residue class
+//               of v of S[u][v] P[v][.]; A = S from LDS, B = basis fragments G; then the four
+//               column members Y[u][member(w', j0)] by in-lane adds.
+//   product b   per w':  Cee/Ceo/Co0/Co1[i0][j] += G (as A) * Y tile (accumulators as B operand),
+//               row tile t feeding the class t belongs to; the four row members by in-lane adds.
+// Both products use the same fragment table G (6 groups x 64 lanes x 4 floats).
 #include "demo_device.h"
 
 namespace demo {
 
 namespace {
-constexpr int D64_WAVES = 7;                       // 7 private tiles + the basis tables fill the LDS
+constexpr int D64_WAVES = 8;                       // 8 private tiles + the fragment table fill the LDS
 constexpr int D64_THREADS = D64_WAVES * 64;
 constexpr int D64_LDT = 68;                        // tile row stride (floats); columns 64..67 are pad slots
 constexpr int D64_TILE_FLOATS = 64 * D64_LDT;
-constexpr int D64_PCOL = 0;                        // pcol[v*64 + 4c + e] = P[v][4 chi(c) + e]
-constexpr int D64_TB = 4096;                       // product-b fragments: 6 groups x 64 lanes x 4
-constexpr int D64_TABLE_FLOATS = 4096 + 1536;  // what the dense kernel keeps in LDS
-constexpr int D64_PROW = 4096 + 1536;              // prow[u*64 + 4c + m] = P[u][rho(4m + c%4, c/4)] (sparse kernel only)
+constexpr int D64_PCOL = 0;                        // pcol[v*64 + 4c + e] = P[v][4 chi(c) + e]       (sparse kernel)
+constexpr int D64_G = 4096;                        // fragment table G of the dense kernel
+constexpr int D64_G_FLOATS = 1536;
+constexpr int D64_PROW = 4096 + 1536;              // prow[u*64 + 4c + m] = P[u][rho(4m + c%4, c/4)] (sparse kernel)
 constexpr int D64_ALL_TABLE_FLOATS = 4096 + 1536 + 4096;
-constexpr int D64_LDS_BYTES = 4 * (D64_TABLE_FLOATS + D64_WAVES * D64_TILE_FLOATS);
+constexpr int D64_LDS_BYTES = 4 * (D64_G_FLOATS + D64_WAVES * D64_TILE_FLOATS);
 static_assert(D64_ALL_TABLE_FLOATS == kDec64TableFloats, "table size");
+static_assert(D64_LDS_BYTES <= 160 * 1024, "LDS budget");
+
+// column (and product-b output row) base index served by lane c of a 16-lane group
+__host__ __device__ constexpr int kappa(int c) { return 4 * (c & 3) + (c >> 2); }
+// member w of the mirror quadruple with base i0 < 16
+__host__ __device__ constexpr int member(int w, int i0) {
+  return w == 0 ? i0 : w == 1 ? 31 - i0 : w == 2 ? 32 + i0 : 63 - i0;
+}
 }  // namespace
 
-// Host: tables of the decode kernel from the 64 x 64 basis P (double, row-major).
+// Host: tables of the decode kernels from the 64 x 64 basis P (double, row-major).
 void build_dec64_tables(const double* P, float* out) {
   auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
   for (int v = 0; v < 64; ++v)
@@ -43,21 +61,34 @@ void build_dec64_tables(const double* P, float* out) {
         out[D64_PCOL + v * 64 + 4 * cc + e] = Pm(v, 4 * chi(cc) + e);
         out[D64_PROW + v * 64 + 4 * cc + e] = Pm(v, rho(4 * e + (cc & 3), cc >> 2));
       }
-  // product b: output row m = c of a tile is the quadruple base i0 = 4(c % 4) + c / 4, so that lane
-  // group g, component s of the accumulator is i0 = 4s + g; k-slot g of step r contracts
-  // u = freq(tile, 4g + r)
+  // G: lane (g, c), component r.  The contraction index of k-slot g at step r is 4 (4 g + r) + class,
+  // the other index is kappa(c) (groups 0..3) or 31 - kappa(c) (groups 4, 5: odd classes only).
   for (int lane = 0; lane < 64; ++lane) {
-    const int g = lane >> 4, c = lane & 15;
-    const int i0 = 4 * (c & 3) + (c >> 2);
+    const int g = lane >> 4, c = lane & 15, kap = kappa(c);
     for (int r = 0; r < 4; ++r) {
-      out[D64_TB + (0 * 64 + lane) * 4 + r] = Pm(freq(0, 4 * g + r), i0);
-      out[D64_TB + (1 * 64 + lane) * 4 + r] = Pm(freq(1, 4 * g + r), i0);
-      out[D64_TB + (2 * 64 + lane) * 4 + r] = Pm(freq(2, 4 * g + r), i0);        // odd rows, output i0
-      out[D64_TB + (3 * 64 + lane) * 4 + r] = Pm(freq(3, 4 * g + r), i0);
-      out[D64_TB + (4 * 64 + lane) * 4 + r] = Pm(freq(2, 4 * g + r), 31 - i0);   // odd rows, output 31 - i0
-      out[D64_TB + (5 * 64 + lane) * 4 + r] = Pm(freq(3, 4 * g + r), 31 - i0);
+      const int u4 = 4 * (4 * g + r);
+      out[D64_G + (0 * 64 + lane) * 4 + r] = Pm(u4 + 0, kap);
+      out[D64_G + (1 * 64 + lane) * 4 + r] = Pm(u4 + 2, kap);
+      out[D64_G + (2 * 64 + lane) * 4 + r] = Pm(u4 + 1, kap);
+      out[D64_G + (3 * 64 + lane) * 4 + r] = Pm(u4 + 3, kap);
+      out[D64_G + (4 * 64 + lane) * 4 + r] = Pm(u4 + 1, 31 - kap);
+      out[D64_G + (5 * 64 + lane) * 4 + r] = Pm(u4 + 3, 31 - kap);
     }
   }
+}
+
+// 16-bit raw buffer accesses
+__device__ __forceinline__ uint32_t bload_u16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
+}
+__device__ __forceinline__ void bstore_u16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, uint32_t v) {
+  __builtin_amdgcn_raw_buffer_store_b16((unsigned short)v, r, (int)voff, (int)soff, 0);
+}
+__device__ __forceinline__ float bload_f1(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ void bstore_f1(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, float v) {
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r, (int)voff, (int)soff, 0);
 }
 
 // PBF16: parameter dtype of every tensor in the table.  FULL: k == 32 and W == 64, so the payload
@@ -66,17 +97,16 @@ template <bool PBF16, bool FULL>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   extern __shared__ float lds[];
-  const float* sPcol = lds + D64_PCOL;
-  const float* sTb = lds + D64_TB;
+  const float* sG = lds;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
-  float* tile = lds + D64_TABLE_FLOATS + wave * D64_TILE_FLOATS;
+  float* tile = lds + D64_G_FLOATS + wave * D64_TILE_FLOATS;
   int* itile = reinterpret_cast<int*>(tile);
   const int k = FULL ? 32 : args.k, W = args.W;
 
-  for (int e = tid; e < D64_TABLE_FLOATS / 4; e += D64_THREADS)
-    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
+  for (int e = tid; e < D64_G_FLOATS / 4; e += D64_THREADS)
+    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + D64_G)[e];
   __syncthreads();
 
   const int nwaves = gridDim.x * D64_WAVES;
@@ -134,6 +164,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   // payload (exact), rounded to integers of `vbits` bits and added with ds_add_u32; W such values
   // cannot overflow 31 bits.  Only sgn(IDCT(S)) is used, so the scale is never undone.  Lanes with
   // nothing to add (inactive pair, index out of range) add zero-weight garbage into their pad slot.
+  // Coefficient (u, v) lives at tile[(16 (u%4) + u/4) * LDT + 16 (v%4) + v/4].
   const uint32_t dummy = (uint32_t)(lane * D64_LDT + 64);
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                // 30 - ceil(log2 W)
@@ -154,16 +185,19 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
       const uint32_t u = (uint32_t)pi[j];
-      const uint32_t a = u < 4096u ? u + ((u >> 6) << 2) : dummy;   // (u / 64) * 68 + u % 64
+      // 12-bit index [u5..u0 v5..v0] -> [u1 u0 u5..u2 | v1 v0 v5..v2], then row stride 64 -> LDT
+      const uint32_t x = ((u & 0xC3u) << 4) | ((u >> 2) & 0x3CFu);
+      const uint32_t a = u < 4096u ? x + ((x >> 6) << 2) : dummy;
       atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
     }
   };
 
-  int t = find_tensor(tv.prefix, tv.n, chunk);
-  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
-  TensorDev d = tv.descs[t];
+  int t = find_tensor_uniform(tv, chunk);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
   load_payload(d, chunk - t_first);
-  const int col4 = 4 * chi(c);
+  const int kap = kappa(c);
+  constexpr uint32_t ES = PBF16 ? 2 : 4;                 // parameter element size
   DEMO_PHASE_DECL
 
   for (; chunk < chunk_end; ++chunk) {
@@ -171,10 +205,28 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
     const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
     const uint32_t ucols = (uint32_t)d.cols;
-    const uint32_t vo_up = (uint32_t)g * ucols + (uint32_t)col4;           // elements
-    const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
+    // per-lane byte offsets: row part g or 3 - g (members w even / odd), column kappa or 31 - kappa
+    // (members w' even / odd; w' >= 2 adds 32 columns)
+    uint32_t vo[2][2];
+    vo[0][0] = ((uint32_t)g * ucols + (uint32_t)kap) * ES;
+    vo[0][1] = ((uint32_t)g * ucols + (uint32_t)(31 - kap)) * ES;
+    vo[1][0] = ((uint32_t)(3 - g) * ucols + (uint32_t)kap) * ES;
+    vo[1][1] = ((uint32_t)(3 - g) * ucols + (uint32_t)(31 - kap)) * ES;
     const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
                                               : make_rsrc(static_cast<const float*>(d.param) + origin);
+    // element (s, w, w'): row rho(4s + w, g) = rho_base(4s + w) + (g | 3 - g), column member(w', kappa)
+    auto x_voff = [&](int w, int wp) { return vo[w & 1][wp & 1] + (wp >= 2 ? 32u * ES : 0u); };
+    auto x_soff = [&](int s, int w) { return (uint32_t)rho_base(4 * s + w) * ucols * ES; };
+    // bf16 parameters of this chunk: requested before the scatter, packed two per register after it
+    uint32_t Xr[PBF16 ? 64 : 1];
+    if (PBF16) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) Xr[(4 * s + w) * 4 + e] = bload_u16(xres, x_voff(w, e), x_soff(s, w));
+    }
     DEMO_PHASE(0);
 
     // ---- S = sum over workers ---------------------------------------------------------------------------
@@ -182,6 +234,13 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
     scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
+    uint32_t Xp[PBF16 ? 32 : 1];
+    if (PBF16) {
+#pragma unroll
+      for (int i = 0; i < 32; ++i) Xp[i] = Xr[2 * i] | (Xr[2 * i + 1] << 16);
+#pragma unroll
+      for (int i = 0; i < 32; ++i) asm volatile("" : "+v"(Xp[i]));   // pack here, not at the point of use
+    }
     DEMO_PHASE(1);
     // ---- payload of the next chunk, in flight during the products (after the last chunk the same
     //      chunk is requested again: an unconditional fetch keeps the old registers dead) -----------------
@@ -189,24 +248,22 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       while (chunk + 1 >= t_next) {
         ++t;
         t_first = t_next;
-        t_next = tv.prefix[t + 1];
-        d = tv.descs[t];
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
       }
       load_payload(d, chunk + 1 - t_first);
     } else {
       load_payload(d, cc);
     }
     wave_lds_sync();
-
     DEMO_PHASE(2);
-    // ---- products a and b, interleaved by coefficient-tile pair so that only half of the product-a
-    //      accumulators is alive at a time:
-    //        Ya[mh][e] rows u = freq(2*half + mh, 4g+r), cols j = 4 chi(c) + e      (product a, dense)
-    //        half 0 feeds Cee, Ceo; half 1 feeds Co0, Co1 [e], component s = quadruple base i0 = 4s + g
-    // Product a: k-step 4kg + kr contracts v = 16kg + 4g + kr, four k-steps per 16-byte LDS read of S;
-    // operands of the next k-step are read while the MFMAs of the current one run.
-    f32x4 Cee[4], Ceo[4], Co0[4], Co1[4];
-    u32x2 Xh[16];   // bf16 parameters, raw
+
+    // ---- products ---------------------------------------------------------------------------------------
+    float4 G[6];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) G[i] = *reinterpret_cast<const float4*>(&sG[(i * 64 + lane) * 4]);
+    auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
+    f32x4 Cee[4], Ceo[4], Co0[4], Co1[4];   // [w'], component s: quadruple base i0 = 4s + g
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       Cee[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -214,123 +271,92 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       Co0[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
       Co1[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
-    auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      f32x4 Ya[2][4];
+    for (int rt = 0; rt < 4; ++rt) {
+      // product a for rows u = 4 m + rt (physical rows 16 rt + m); column class of k-block kg is kg
+      const float* arow = &tile[(16 * rt + c) * D64_LDT + 4 * g];
+      float4 a[4];
 #pragma unroll
-      for (int mh = 0; mh < 2; ++mh)
+      for (int kg = 0; kg < 4; ++kg) a[kg] = *reinterpret_cast<const float4*>(arow + 16 * kg);
+      f32x4 ee = {0.f, 0.f, 0.f, 0.f}, eo = ee, o0 = ee, o1 = ee;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) Ya[mh][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      {
-        int srow[2];   // tile row of A row c of tile 2*half + mh
+      for (int kr = 0; kr < 4; ++kr) {
+        // the tile holds fixed-point sums
+        const float a0 = (float)__float_as_int(comp(a[0], kr)), a1 = (float)__float_as_int(comp(a[1], kr));
+        const float a2 = (float)__float_as_int(comp(a[2], kr)), a3 = (float)__float_as_int(comp(a[3], kr));
+        ee = mfma4(a0, comp(G[0], kr), ee);
+        o0 = mfma4(a1, comp(G[2], kr), o0);
+        o1 = mfma4(a1, comp(G[4], kr), o1);
+        eo = mfma4(a2, comp(G[1], kr), eo);
+        o0 = mfma4(a3, comp(G[3], kr), o0);
+        o1 = mfma4(a3, comp(G[5], kr), o1);
+      }
+      // columns member(w', kappa(c)) of Y, rows u = 4 (4g + r) + rt
+      const f32x4 t1 = ee + eo, t2 = ee - eo;
+      const f32x4 Y[4] = {t1 + o0, t2 + o1, t2 - o1, t1 - o0};
+      // product b: this row tile feeds the accumulators of its class
 #pragma unroll
-        for (int mh = 0; mh < 2; ++mh) srow[mh] = freq(2 * half + mh, c) * D64_LDT + 4 * g;
-        float4 sa[2], sn[2];
+      for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int mh = 0; mh < 2; ++mh) sn[mh] = *reinterpret_cast<const float4*>(&tile[srow[mh]]);
-        float4 pn = *reinterpret_cast<const float4*>(&sPcol[(4 * g) * 64 + 4 * c]);
-#pragma unroll
-        for (int ks = 0; ks < 16; ++ks) {
-          const int kg = ks >> 2, kr = ks & 3;
-          if (kr == 0) {
-#pragma unroll
-            for (int mh = 0; mh < 2; ++mh) sa[mh] = sn[mh];
-            if (kg + 1 < 4) {
-#pragma unroll
-              for (int mh = 0; mh < 2; ++mh) sn[mh] = *reinterpret_cast<const float4*>(&tile[srow[mh] + 16 * (kg + 1)]);
-            }
+        for (int e = 0; e < 4; ++e) {
+          if (rt == 0) Cee[e] = mfma4(comp(G[0], r), Y[e][r], Cee[e]);
+          if (rt == 2) Ceo[e] = mfma4(comp(G[1], r), Y[e][r], Ceo[e]);
+          if (rt == 1) {
+            Co0[e] = mfma4(comp(G[2], r), Y[e][r], Co0[e]);
+            Co1[e] = mfma4(comp(G[4], r), Y[e][r], Co1[e]);
           }
-          const float bf[4] = {pn.x, pn.y, pn.z, pn.w};
-          if (ks + 1 < 16) {
-            const int kg2 = (ks + 1) >> 2, kr2 = (ks + 1) & 3;
-            pn = *reinterpret_cast<const float4*>(&sPcol[(16 * kg2 + 4 * g + kr2) * 64 + 4 * c]);
+          if (rt == 3) {
+            Co0[e] = mfma4(comp(G[3], r), Y[e][r], Co0[e]);
+            Co1[e] = mfma4(comp(G[5], r), Y[e][r], Co1[e]);
           }
-#pragma unroll
-          for (int mh = 0; mh < 2; ++mh) {
-            const float a = (float)__float_as_int(comp(sa[mh], kr));   // the tile holds fixed-point sums
-#pragma unroll
-            for (int e = 0; e < 4; ++e) Ya[mh][e] = mfma4(a, bf[e], Ya[mh][e]);
-          }
-          if (PBF16 && half == 1) {
-            // parameters: requested during the second half, one row per k-step
-            Xh[ks] = bload_u2(xres, ((ks & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(ks) * ucols * 2);
-          }
-          __builtin_amdgcn_sched_barrier(0);
         }
-      }
-      // product b for this pair of tiles (3/8 dense over both halves)
-      if (half == 0) {
-        const float4 tee = *reinterpret_cast<const float4*>(&sTb[(0 * 64 + lane) * 4]);
-        const float4 teo = *reinterpret_cast<const float4*>(&sTb[(1 * 64 + lane) * 4]);
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            Cee[e] = mfma4(comp(tee, r), Ya[0][e][r], Cee[e]);
-            Ceo[e] = mfma4(comp(teo, r), Ya[1][e][r], Ceo[e]);
-          }
-      } else {
-        float4 tb[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) tb[i] = *reinterpret_cast<const float4*>(&sTb[((2 + i) * 64 + lane) * 4]);
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            Co0[e] = mfma4(comp(tb[0], r), Ya[0][e][r], Co0[e]);
-            Co1[e] = mfma4(comp(tb[2], r), Ya[0][e][r], Co1[e]);
-            Co0[e] = mfma4(comp(tb[1], r), Ya[1][e][r], Co0[e]);
-            Co1[e] = mfma4(comp(tb[3], r), Ya[1][e][r], Co1[e]);
-          }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      if (half == 0) { DEMO_PHASE(3); }
     }
+    DEMO_PHASE(3);
 
-    DEMO_PHASE(4);
     // ---- x <- x - lr*(sgn(R) + wd*x), R from the quadruple identities ------------------------------------------
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      f32x4 xin[4];   // fp32 parameters of the four rows of this quadruple
+      float xf[4][4];   // fp32 parameters [w][w'] of this quadruple of rows
       if (!PBF16) {
 #pragma unroll
         for (int w = 0; w < 4; ++w)
-          xin[w] = bload_f4(xres, ((w & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(4 * s + w) * ucols * 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) xf[w][e] = bload_f1(xres, x_voff(w, e), x_soff(s, w));
       }
-      float o[4][4];   // [w][e]
+      float o[4][4];   // [w][w']
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float t1 = Cee[e][s] + Ceo[e][s], t2 = Cee[e][s] - Ceo[e][s];
         const float rr[4] = {t1 + Co0[e][s], t2 + Co1[e][s], t2 - Co1[e][s], t1 - Co0[e][s]};
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          const int q = 4 * s + w;
           float x;
           if (PBF16) {
-            const uint32_t raw = Xh[q][e >> 1];
+            const uint32_t raw = Xp[(4 * s + w) * 2 + (e >> 1)];
             x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
           } else {
-            x = xin[w][e];
+            x = xf[w][e];
           }
           o[w][e] = sign_update(x, sgnf(rr[w]), args.lr, args.weight_decay);
         }
       }
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const int q = 4 * s + w;
-        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
         if (PBF16) {
-          const u32x2 pk = {pack_bf16x2(o[w][0], o[w][1]), pack_bf16x2(o[w][2], o[w][3])};
-          bstore_u2(xres, vo * 2, so * 2, pk);
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            const uint32_t pk = pack_bf16x2(o[w][2 * h], o[w][2 * h + 1]);
+            bstore_u16(xres, x_voff(w, 2 * h), x_soff(s, w), pk);
+            bstore_u16(xres, x_voff(w, 2 * h + 1), x_soff(s, w), pk >> 16);
+          }
         } else {
-          const f32x4 ov = {o[w][0], o[w][1], o[w][2], o[w][3]};
-          bstore_f4(xres, vo * 4, so * 4, ov);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bstore_f1(xres, x_voff(w, e), x_soff(s, w), o[w][e]);
         }
       }
     }
     wave_lds_sync();
-    DEMO_PHASE(5);
+    DEMO_PHASE(4);
   }
   DEMO_PHASE_FLUSH(8);
 }
@@ -384,9 +410,9 @@ __global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, 
     pv = lane < npairs ? as_global(dd.val)[off] : 0.f;
   };
 
-  int t = find_tensor(tv.prefix, tv.n, chunk);
-  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
-  TensorDev d = tv.descs[t];
+  int t = find_tensor_uniform(tv, chunk);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
   load_pair(d, chunk - t_first);
   const int col4 = 4 * chi(c);
 
@@ -418,8 +444,8 @@ __global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, 
       while (chunk + 1 >= t_next) {
         ++t;
         t_first = t_next;
-        t_next = tv.prefix[t + 1];
-        d = tv.descs[t];
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
       }
       load_pair(d, chunk + 1 - t_first);
     } else {

@@ -32,6 +32,28 @@ __device__ __forceinline__ int find_tensor(const int32_t* __restrict__ prefix, i
   return lo;
 }
 
+// The wavefront-per-chunk kernels walk the descriptor table with wavefront-uniform indices.  Reading
+// the entries through the first active lane keeps them (and every address derived from them, e.g. a
+// buffer resource descriptor) in scalar registers; without it the compiler must assume a divergent
+// descriptor and wraps each buffer access in a loop over the distinct values.
+__device__ __forceinline__ int uniform_i32(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int uniform_prefix(const TableView& tv, int t) {
+  return __builtin_amdgcn_readfirstlane(as_global(tv.prefix)[t]);
+}
+__device__ __forceinline__ int find_tensor_uniform(const TableView& tv, int chunk) {
+  return __builtin_amdgcn_readfirstlane(find_tensor(tv.prefix, tv.n, chunk));
+}
+__device__ __forceinline__ TensorDev load_desc_uniform(const TableView& tv, int t) {
+  static_assert(sizeof(TensorDev) % 4 == 0, "descriptor is a whole number of dwords");
+  constexpr int NW = sizeof(TensorDev) / 4;
+  struct Words { uint32_t w[NW]; };
+  const DEMO_GLOBAL uint32_t* p = reinterpret_cast<const DEMO_GLOBAL uint32_t*>(as_global(tv.descs) + t);
+  Words u;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) u.w[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)p[i]);
+  return __builtin_bit_cast(TensorDev, u);
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {

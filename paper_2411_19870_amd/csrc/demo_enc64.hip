@@ -113,9 +113,9 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   int chunk = wid * per + (wid < rem ? wid : rem);
   const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
   if (chunk >= chunk_end) return;
-  int t = find_tensor(tv.prefix, tv.n, chunk);
-  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
-  TensorDev d = tv.descs[t];
+  int t = find_tensor_uniform(tv, chunk);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
 
   // lane constants: column offset, and flat-index bases u(t,c)*64 + v(vt,4g) of the coefficient tiles
   const int col4 = 4 * chi(c);
@@ -184,8 +184,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       while (chunk + 1 >= t_next) {
         ++t;
         t_first = t_next;
-        t_next = tv.prefix[t + 1];
-        d = tv.descs[t];
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
       }
       nxt = place(d, chunk + 1 - t_first);
     }

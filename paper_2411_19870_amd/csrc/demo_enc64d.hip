@@ -78,9 +78,9 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   int tileno = wid * per + (wid < rem ? wid : rem);
   const int tile_end = tileno + per + (wid < rem ? 1 : 0);
   if (tileno >= tile_end) return;
-  int t = find_tensor(tv.prefix, tv.n, tileno);
-  int t_first = tv.prefix[t], t_next = tv.prefix[t + 1];
-  TensorDev d = tv.descs[t];
+  int t = find_tensor_uniform(tv, tileno);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
 
   const int col4 = 4 * chi(c);
   // flat index inside a chunk of coefficient C2[mt][nt][r]: (16(nt&1) + c)*32 + 16(mt&1) + 4g + r
@@ -143,8 +143,8 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
       while (tileno + 1 >= t_next) {
         ++t;
         t_first = t_next;
-        t_next = tv.prefix[t + 1];
-        d = tv.descs[t];
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
       }
       nxt = place(d, tileno + 1 - t_first);
     }
