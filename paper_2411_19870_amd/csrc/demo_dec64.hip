@@ -11,10 +11,12 @@
 // The same holds for the columns.  Both products therefore keep the four members of a quadruple
 // in one lane: lane l = 16 g + c ends up with the elements
 //   rows    member(w, 4 s + g)        s, w  = 0..3   (16 rows)
-//   columns member(w', kappa(c))      w'    = 0..3   ( 4 columns)
-// and reads / writes the parameters in exactly that layout.  One access instruction (fixed s, w,
-// w') then covers four rows x sixteen adjacent columns, i.e. whole 32-byte (bf16) or 64-byte (fp32)
-// sectors, and the four w' of a row fill its 128 / 256 bytes.
+//   columns member(w', kappa(c))      w'    = 0..3   ( 4 columns).
+// Accessing the parameters in that layout would take 2- or 4-byte accesses, and the address path of
+// the CU (one wavefront instruction per 16 cycles whatever its width) then limits the kernel, so R
+// is passed once through the LDS tile of S (dead by then) into the layout of the encode kernel
+// (demo_device.h: rows rho(q, g), columns 4 chi(c) .. +3), where every load and store instruction
+// covers whole 128- or 256-byte rows, and the sign update is fused there.
 //
 // S is accumulated in a private LDS tile in block fixed point with integer atomics (see `scatter`
 // below); its rows and columns are stored grouped by residue mod 4 (physical index
@@ -75,20 +77,6 @@ void build_dec64_tables(const double* P, float* out) {
       out[D64_G + (5 * 64 + lane) * 4 + r] = Pm(u4 + 3, 31 - kap);
     }
   }
-}
-
-// 16-bit raw buffer accesses
-__device__ __forceinline__ uint32_t bload_u16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-  return (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0);
-}
-__device__ __forceinline__ void bstore_u16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, uint32_t v) {
-  __builtin_amdgcn_raw_buffer_store_b16((unsigned short)v, r, (int)voff, (int)soff, 0);
-}
-__device__ __forceinline__ float bload_f1(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
-}
-__device__ __forceinline__ void bstore_f1(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, float v) {
-  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r, (int)voff, (int)soff, 0);
 }
 
 // PBF16: parameter dtype of every tensor in the table.  FULL: k == 32 and W == 64, so the payload
@@ -196,8 +184,11 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
   load_payload(d, chunk - t_first);
-  const int kap = kappa(c);
-  constexpr uint32_t ES = PBF16 ? 2 : 4;                 // parameter element size
+  const int kap = kappa(c), col4 = 4 * chi(c);
+  // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
+  // for members w' even / odd (w' >= 2 adds 32 columns)
+  const int row_up = 4 * g * D64_LDT, row_dn = 4 * (3 - g) * D64_LDT;
+  const int wr_col_up = kap, wr_col_dn = 31 - kap;
   DEMO_PHASE_DECL
 
   for (; chunk < chunk_end; ++chunk) {
@@ -205,27 +196,15 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
     const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
     const uint32_t ucols = (uint32_t)d.cols;
-    // per-lane byte offsets: row part g or 3 - g (members w even / odd), column kappa or 31 - kappa
-    // (members w' even / odd; w' >= 2 adds 32 columns)
-    uint32_t vo[2][2];
-    vo[0][0] = ((uint32_t)g * ucols + (uint32_t)kap) * ES;
-    vo[0][1] = ((uint32_t)g * ucols + (uint32_t)(31 - kap)) * ES;
-    vo[1][0] = ((uint32_t)(3 - g) * ucols + (uint32_t)kap) * ES;
-    vo[1][1] = ((uint32_t)(3 - g) * ucols + (uint32_t)(31 - kap)) * ES;
+    // parameters: lane (g, c) reads / writes rows rho(q, g), columns 4 chi(c) .. +3 (whole rows per instruction)
+    const uint32_t vo_up = (uint32_t)g * ucols + (uint32_t)col4;           // elements
+    const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
     const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
                                               : make_rsrc(static_cast<const float*>(d.param) + origin);
-    // element (s, w, w'): row rho(4s + w, g) = rho_base(4s + w) + (g | 3 - g), column member(w', kappa)
-    auto x_voff = [&](int w, int wp) { return vo[w & 1][wp & 1] + (wp >= 2 ? 32u * ES : 0u); };
-    auto x_soff = [&](int s, int w) { return (uint32_t)rho_base(4 * s + w) * ucols * ES; };
-    // bf16 parameters of this chunk: requested before the scatter, packed two per register after it
-    uint32_t Xr[PBF16 ? 64 : 1];
+    u32x2 Xh[16];   // bf16 parameters, raw: requested before the scatter, used after the products
     if (PBF16) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) Xr[(4 * s + w) * 4 + e] = bload_u16(xres, x_voff(w, e), x_soff(s, w));
+      for (int q = 0; q < 16; ++q) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
     }
     DEMO_PHASE(0);
 
@@ -234,13 +213,6 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
     scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
-    uint32_t Xp[PBF16 ? 32 : 1];
-    if (PBF16) {
-#pragma unroll
-      for (int i = 0; i < 32; ++i) Xp[i] = Xr[2 * i] | (Xr[2 * i + 1] << 16);
-#pragma unroll
-      for (int i = 0; i < 32; ++i) asm volatile("" : "+v"(Xp[i]));   // pack here, not at the point of use
-    }
     DEMO_PHASE(1);
     // ---- payload of the next chunk, in flight during the products (after the last chunk the same
     //      chunk is requested again: an unconditional fetch keeps the old registers dead) -----------------
@@ -313,50 +285,64 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     }
     DEMO_PHASE(3);
 
-    // ---- x <- x - lr*(sgn(R) + wd*x), R from the quadruple identities ------------------------------------------
+    // ---- R (quadruple identities) goes through the tile, which is dead by now, into the layout of the
+    //      parameters.  Row i is kept at tile row rperm(i) = 16 (i / 16) + 4 (i % 4) + (i / 4) % 4: the four
+    //      rows written by one instruction are then 16 banks apart and the sixteen columns fill the gaps.
+    //      For i = member(w, 4s + g):  rperm = 16 w + 4 g + s (w even),  16 w + 4 (3 - g) + (3 - s) (w odd).
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      float xf[4][4];   // fp32 parameters [w][w'] of this quadruple of rows
-      if (!PBF16) {
+    for (int e = 0; e < 4; ++e) {
+      float* wcol = tile + ((e & 1) ? wr_col_dn : wr_col_up) + (e >= 2 ? 32 : 0);
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) xf[w][e] = bload_f1(xres, x_voff(w, e), x_soff(s, w));
-      }
-      float o[4][4];   // [w][w']
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      for (int s = 0; s < 4; ++s) {
         const float t1 = Cee[e][s] + Ceo[e][s], t2 = Cee[e][s] - Ceo[e][s];
         const float rr[4] = {t1 + Co0[e][s], t2 + Co1[e][s], t2 - Co1[e][s], t1 - Co0[e][s]};
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float x;
-          if (PBF16) {
-            const uint32_t raw = Xp[(4 * s + w) * 2 + (e >> 1)];
-            x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
-          } else {
-            x = xf[w][e];
-          }
-          o[w][e] = sign_update(x, sgnf(rr[w]), args.lr, args.weight_decay);
-        }
-      }
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        if (PBF16) {
-#pragma unroll
-          for (int h = 0; h < 2; ++h) {
-            const uint32_t pk = pack_bf16x2(o[w][2 * h], o[w][2 * h + 1]);
-            bstore_u16(xres, x_voff(w, 2 * h), x_soff(s, w), pk);
-            bstore_u16(xres, x_voff(w, 2 * h + 1), x_soff(s, w), pk >> 16);
-          }
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) bstore_f1(xres, x_voff(w, e), x_soff(s, w), o[w][e]);
-        }
+        for (int w = 0; w < 4; ++w)
+          wcol[((w & 1) ? row_dn : row_up) + (16 * w + ((w & 1) ? 3 - s : s)) * D64_LDT] = rr[w];
       }
     }
     wave_lds_sync();
     DEMO_PHASE(4);
+
+    // ---- x <- x - lr*(sgn(R) + wd*x) ------------------------------------------------------------------------
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      f32x4 xin[4];   // fp32 parameters of the four rows of this quadruple
+      if (!PBF16) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          xin[w] = bload_f4(xres, ((w & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(4 * s + w) * ucols * 4);
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int q = 4 * s + w;
+        const float4 rv = *reinterpret_cast<const float4*>(
+            &tile[((w & 1) ? row_dn : row_up) + (16 * w + ((w & 1) ? 3 - s : s)) * D64_LDT + col4]);
+        const float rr[4] = {rv.x, rv.y, rv.z, rv.w};
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float x;
+          if (PBF16) {
+            const uint32_t raw = Xh[q][e >> 1];
+            x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+          } else {
+            x = xin[w][e];
+          }
+          o[e] = sign_update(x, sgnf(rr[e]), args.lr, args.weight_decay);
+        }
+        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
+        if (PBF16) {
+          const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+          bstore_u2(xres, vo * 2, so * 2, pk);
+        } else {
+          const f32x4 ov = {o[0], o[1], o[2], o[3]};
+          bstore_f4(xres, vo * 4, so * 4, ov);
+        }
+      }
+    }
+    wave_lds_sync();
+    DEMO_PHASE(5);
   }
   DEMO_PHASE_FLUSH(8);
 }
