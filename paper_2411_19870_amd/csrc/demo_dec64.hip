@@ -100,10 +100,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   const int nwaves = gridDim.x * D64_WAVES;
   const int wid = blockIdx.x * D64_WAVES + wave;
   const int total = tv.total_chunks;
-  const int per = total / nwaves, rem = total - per * nwaves;
-  int chunk = wid * per + (wid < rem ? wid : rem);
-  const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
-  if (chunk >= chunk_end) return;
+  int chunk = wid;   // wavefront w takes chunks w, w + nwaves, ... (see the encode kernel)
+  if (chunk >= total) return;
 
   // ---- payload access ---------------------------------------------------------------------------------
   // 32 (index, value) pairs per lane hold the whole payload of a chunk (W * k <= 2048 pairs).
@@ -191,7 +189,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   const int wr_col_up = kap, wr_col_dn = 31 - kap;
   DEMO_PHASE_DECL
 
-  for (; chunk < chunk_end; ++chunk) {
+  for (; chunk < total; chunk += nwaves) {
     const int cc = chunk - t_first;
     const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
     const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
@@ -216,14 +214,14 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     DEMO_PHASE(1);
     // ---- payload of the next chunk, in flight during the products (after the last chunk the same
     //      chunk is requested again: an unconditional fetch keeps the old registers dead) -----------------
-    if (chunk + 1 < chunk_end) {
-      while (chunk + 1 >= t_next) {
+    if (chunk + nwaves < total) {
+      while (chunk + nwaves >= t_next) {
         ++t;
         t_first = t_next;
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, chunk + 1 - t_first);
+      load_payload(d, chunk + nwaves - t_first);
     } else {
       load_payload(d, cc);
     }
@@ -381,10 +379,8 @@ __global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, 
   const int nwaves = gridDim.x * D64S_WAVES;
   const int wid = blockIdx.x * D64S_WAVES + wave;
   const int total = tv.total_chunks;
-  const int per = total / nwaves, rem = total - per * nwaves;
-  int chunk = wid * per + (wid < rem ? wid : rem);
-  const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
-  if (chunk >= chunk_end) return;
+  int chunk = wid;   // wavefront w takes chunks w, w + nwaves, ... (see the encode kernel)
+  if (chunk >= total) return;
 
   // pair `lane` of a chunk: worker lane / k, position lane % k
   const int pw = lane / k, pt = lane - pw * k;
@@ -402,7 +398,7 @@ __global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, 
   load_pair(d, chunk - t_first);
   const int col4 = 4 * chi(c);
 
-  for (; chunk < chunk_end; ++chunk) {
+  for (; chunk < total; chunk += nwaves) {
     const int cc = chunk - t_first;
     const int k0 = cc / d.cchunks, k1 = cc - k0 * d.cchunks;
     const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
@@ -426,14 +422,14 @@ __global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, 
     }
     wave_lds_sync();
     // pair of the next chunk (after the last chunk the same one again: keeps the old registers dead)
-    if (chunk + 1 < chunk_end) {
-      while (chunk + 1 >= t_next) {
+    if (chunk + nwaves < total) {
+      while (chunk + nwaves >= t_next) {
         ++t;
         t_first = t_next;
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_pair(d, chunk + 1 - t_first);
+      load_pair(d, chunk + nwaves - t_first);
     } else {
       load_pair(d, cc);
     }

@@ -105,14 +105,13 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
   __syncthreads();
 
-  // contiguous range of chunks for this wavefront
+  // wavefront w takes chunks w, w + nwaves, ...: at any time the wavefronts of the grid work on one
+  // narrow band of memory, which the HBM channels serve faster than a far-apart range per wavefront
   const int nwaves = gridDim.x * E64_WAVES;
   const int wid = blockIdx.x * E64_WAVES + wave;
   const int total = tv.total_chunks;
-  const int per = total / nwaves, rem = total - per * nwaves;
-  int chunk = wid * per + (wid < rem ? wid : rem);
-  const int chunk_end = chunk + per + (wid < rem ? 1 : 0);
-  if (chunk >= chunk_end) return;
+  int chunk = wid;
+  if (chunk >= total) return;
   int t = find_tensor_uniform(tv, chunk);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
@@ -173,21 +172,21 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   fetch_g(cur);
 
   DEMO_PHASE_DECL
-  for (; chunk < chunk_end; ++chunk) {
+  for (; chunk < total; chunk += nwaves) {
     const int cc = cur.cc;
     const uint32_t ucols = cur.ucols, vo_up = cur.vo_up, vo_dn = cur.vo_dn;
     const __amdgpu_buffer_rsrc_t mres = cur.mres;
     // the chunk after this one (if any)
-    const bool has_next = chunk + 1 < chunk_end;
+    const bool has_next = chunk + nwaves < total;
     Place nxt = cur;
     if (has_next) {
-      while (chunk + 1 >= t_next) {
+      while (chunk + nwaves >= t_next) {
         ++t;
         t_first = t_next;
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      nxt = place(d, chunk + 1 - t_first);
+      nxt = place(d, chunk + nwaves - t_first);
     }
 
     // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ------------------

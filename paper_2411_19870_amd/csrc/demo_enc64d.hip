@@ -74,10 +74,8 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   const int nwaves = gridDim.x * ED_WAVES;
   const int wid = blockIdx.x * ED_WAVES + wave;
   const int total = tv.total_chunks;
-  const int per = total / nwaves, rem = total - per * nwaves;
-  int tileno = wid * per + (wid < rem ? wid : rem);
-  const int tile_end = tileno + per + (wid < rem ? 1 : 0);
-  if (tileno >= tile_end) return;
+  int tileno = wid;   // wavefront w takes tiles w, w + nwaves, ...
+  if (tileno >= total) return;
   int t = find_tensor_uniform(tv, tileno);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
@@ -135,18 +133,18 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   fetch_m(cur);
   fetch_g(cur);
 
-  for (; tileno < tile_end; ++tileno) {
+  for (; tileno < total; tileno += nwaves) {
     const uint32_t ucols = cur.ucols, vo_up = cur.vo_up, vo_dn = cur.vo_dn;
     const __amdgpu_buffer_rsrc_t mres = cur.mres;
     Place nxt = cur;
-    if (tileno + 1 < tile_end) {
-      while (tileno + 1 >= t_next) {
+    if (tileno + nwaves < total) {
+      while (tileno + nwaves >= t_next) {
         ++t;
         t_first = t_next;
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      nxt = place(d, tileno + 1 - t_first);
+      nxt = place(d, tileno + nwaves - t_first);
     }
 
     // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ------------------
