@@ -504,17 +504,37 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
   const TensorDev d = tv.descs[t];
   const int c = chunk - tv.prefix[t];
   const int64_t base = (int64_t)c * S;
-  for (int n = lane; n < S; n += 64) s_acc[n] = 0.f;
-  __syncthreads();
+  int* i_acc = reinterpret_cast<int*>(s_acc);
+  for (int n = lane; n < S; n += 64) i_acc[n] = 0;
+  // sum of the W payloads in block fixed point (as in the order-2 kernels): pass 1 finds the largest
+  // magnitude of the chunk's W*k values, pass 2 adds them as integers, independent of the order
   const int64_t wstride = (int64_t)d.nchunks * k;
-  for (int w = 0; w < W; ++w) {
-    for (int tt = lane; tt < k; tt += 64) {
-      const int64_t po = (int64_t)w * wstride + (int64_t)c * k + tt;
-      const int fi = d.idx[po];
-      const float fv = d.val[po];
-      if (fi >= 0 && fi < S) atomicAdd(&s_acc[fi], fv);
-    }
+  const DEMO_GLOBAL int32_t* ip = as_global(d.idx) + (int64_t)c * k;
+  const DEMO_GLOBAL float* vp = as_global(d.val) + (int64_t)c * k;
+  const int npairs = W * k;
+  float mx = 0.f;
+#pragma unroll 4
+  for (int p = lane; p < npairs; p += 64) {
+    const int w = p / k, tt = p - w * k;
+    mx = fmaxf(mx, fabsf(vp[(int64_t)w * wstride + tt]));
   }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  int ex = (int)(__float_as_uint(mx) >> 23);
+  ex = ex < 1 ? 1 : ex;
+  int vbits = 30;
+  for (int w = 1; w < W; w <<= 1) --vbits;
+  const int sh = vbits + 126 - ex;
+  __syncthreads();
+#pragma unroll 4
+  for (int p = lane; p < npairs; p += 64) {
+    const int w = p / k, tt = p - w * k;
+    const int fi = ip[(int64_t)w * wstride + tt];
+    const float fv = vp[(int64_t)w * wstride + tt];
+    if (fi >= 0 && fi < S) atomicAdd(&i_acc[fi], __float2int_rn(ldexpf(fv, sh)));
+  }
+  __syncthreads();
+  for (int n = lane; n < S; n += 64) s_acc[n] = (float)i_acc[n];
   __syncthreads();
 #pragma unroll
   for (int e = 0; e < EPL; ++e) {
