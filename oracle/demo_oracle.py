@@ -36,12 +36,30 @@ with reasons is kept in the design document):
     paper does not fix this precision; where a rounding decides the stored code
     both sides must round the same way, so the oracle mimics float32 here.
 
+Variants of the method's scalars and of the server-side aggregate, all off by
+default (the defaults are the readings above):
+
+  * grad_scale: coefficient of g in the momentum update; 1 - beta gives the
+    weighted form of the first display equation of Sec. 2.1;
+  * alpha: coefficient of the subtracted reconstruction (display equation of
+    "Momentum Subtraction as Error Feedback"; ablation "Impact of Momentum
+    Subtraction", alpha in [0, 1]); the payload still carries the coefficients
+    themselves;
+  * phi: "sign" (Signum) or "identity" (SGD) in the update rule of "Momentum
+    Reconstruction and Parameter Update"; Muon's phi is not covered;
+  * aggregate mode: "sum" (algorithm boxes), "mean" (sum / W, the AvgAllGather
+    of "Top-k Sparsification") or "count" (appendix algorithm "Sparse Top-k
+    Averaging": S (/) n with 0/0 = 0, n = how many workers sent the coefficient).
+
 Parity pins (tests/test_oracle_pins.py): DCT against scipy's orthonormal DCT-II,
 orthonormality, Parseval, closed forms (constant and single-cosine chunks),
 hand-worked 4-point and 4x4 examples, brute-force top-k, k = M exact recovery,
 the l1/l2 residual bounds of the appendix lemma and remarks, linearity of the
-aggregate, the 128x512 -> 16x32 blocking example, and bfloat16 rounding against
-torch's conversion.  No function here is "parity unpinned".
+aggregate, the 128x512 -> 16x32 blocking example, bfloat16 rounding against
+torch's conversion, and for the variants: k = M with alpha (residual (1-alpha) m),
+alpha = 0, a hand-worked weighted momentum, W identical full payloads under the
+mean, the identity update in closed form, and a hand-worked two-worker example of
+the count-normalised average.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -49,7 +67,7 @@ import numpy as np
 
 __all__ = [
     "dct_basis", "chunk", "unchunk", "momentum_update", "dct_chunks",
-    "idct_chunks", "topk_indices", "encode", "aggregate", "decode", "step",
+    "idct_chunks", "topk_indices", "encode", "aggregate", "aggregate_counts", "decode", "step",
     "round_to_bf16", "sgn",
 ]
 
@@ -109,8 +127,9 @@ def unchunk(b: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Step 1: local momentum  (Algorithm 1, "update local momentum buffer")
 # --------------------------------------------------------------------------
-def momentum_update(m_prev: np.ndarray, g: np.ndarray, beta: float) -> np.ndarray:
-    return np.float64(beta) * np.asarray(m_prev, np.float64) + np.asarray(g, np.float64)
+def momentum_update(m_prev: np.ndarray, g: np.ndarray, beta: float, grad_scale: float = 1.0) -> np.ndarray:
+    return (np.float64(beta) * np.asarray(m_prev, np.float64)
+            + np.float64(grad_scale) * np.asarray(g, np.float64))
 
 
 # --------------------------------------------------------------------------
@@ -147,7 +166,7 @@ def topk_indices(q_flat: np.ndarray, k: int) -> np.ndarray:
 # Worker side, one tensor
 # --------------------------------------------------------------------------
 def encode(m_prev: np.ndarray, g: np.ndarray, beta: float, s: int, k: int,
-           forced_idx: np.ndarray | None = None):
+           forced_idx: np.ndarray | None = None, alpha: float = 1.0, grad_scale: float = 1.0):
     """One worker's encode of one tensor.
 
     m_prev, g : float arrays of identical shape ([n] or [n0, n1]); their values
@@ -155,15 +174,17 @@ def encode(m_prev: np.ndarray, g: np.ndarray, beta: float, s: int, k: int,
     forced_idx: optional [nchunks, k] index sets to use instead of the oracle's
                 own top-k (the parity tests use it to evaluate values and the
                 residual on a selection that differs only inside a near-tie).
+    alpha     : coefficient of the subtracted reconstruction (1 = algorithm boxes).
+    grad_scale: coefficient of g in the momentum update (1 = algorithm boxes).
     Returns dict with
       m_new  : residual momentum, same shape as m_prev
       idx    : int32 [nchunks, k]   (chunk order row-major over (k0, k1))
       val    : float64 [nchunks, k] (the coefficients at idx)
       Q      : all coefficients, float64 [nchunks, M]
-      m_mid  : beta*m + g before the subtraction
+      m_mid  : beta*m + grad_scale*g before the subtraction
     """
     P = dct_basis(s)
-    m_mid = momentum_update(m_prev, g, beta)
+    m_mid = momentum_update(m_prev, g, beta, grad_scale)
     b = chunk(m_mid, s)                                     # ChunkExtract
     Q = dct_chunks(b, P)                                    # DCT
     M = s if m_mid.ndim == 1 else s * s
@@ -177,7 +198,7 @@ def encode(m_prev: np.ndarray, g: np.ndarray, beta: float, s: int, k: int,
         idx[c] = sel
         val[c] = Qf[c, sel]
         Qhat[c, sel] = Qf[c, sel]
-    resid = b - idct_chunks(Qhat.reshape(Q.shape), P)       # B <- B - IDCT(q_sp)
+    resid = b - np.float64(alpha) * idct_chunks(Qhat.reshape(Q.shape), P)   # B <- B - alpha IDCT(q_sp)
     m_new = unchunk(resid).reshape(m_mid.shape)             # ChunkInsert
     return {"m_new": m_new, "idx": idx, "val": val, "Q": Qf, "m_mid": m_mid}
 
@@ -197,6 +218,19 @@ def aggregate(idx: np.ndarray, val: np.ndarray, M: int) -> np.ndarray:
         ok = (iw >= 0) & (iw < M)
         np.add.at(S, (rows[ok], iw[ok]), np.asarray(val[w], np.float64)[ok])
     return S
+
+
+def aggregate_counts(idx: np.ndarray, M: int) -> np.ndarray:
+    """n of the appendix algorithm "Sparse Top-k Averaging": how many workers sent
+    each coefficient.  idx: [W, nchunks, k]; returns int64 [nchunks, M]."""
+    W, nch, k = idx.shape
+    n = np.zeros((nch, M), np.int64)
+    rows = np.repeat(np.arange(nch), k).reshape(nch, k)
+    for w in range(W):                                      # n_I <- n_I + 1
+        iw = np.asarray(idx[w], np.int64)
+        ok = (iw >= 0) & (iw < M)
+        np.add.at(n, (rows[ok], iw[ok]), 1)
+    return n
 
 
 def sgn(x: np.ndarray) -> np.ndarray:
@@ -219,12 +253,13 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
 
 
 def decode(x: np.ndarray, idx: np.ndarray, val: np.ndarray, lr: float, weight_decay: float,
-           s: int, param_dtype: str = "f32"):
+           s: int, param_dtype: str = "f32", phi: str = "sign", aggregate_mode: str = "sum"):
     """Server side for one tensor: aggregate W payloads, inverse transform,
     sign, parameter update.
 
     x   : parameters ([n] or [n0, n1]), values used exactly
     idx : int [W, nchunks, k];  val: float [W, nchunks, k]
+    phi : "sign" or "identity";  aggregate_mode: "sum", "mean" or "count"
     Returns dict with x_new (float32 values, representable in `param_dtype`),
     R (the reconstructed momentum, float64, same shape as x).
     """
@@ -232,13 +267,25 @@ def decode(x: np.ndarray, idx: np.ndarray, val: np.ndarray, lr: float, weight_de
     x64 = np.asarray(x, np.float64)
     M = s if x64.ndim == 1 else s * s
     S = aggregate(np.asarray(idx), np.asarray(val, np.float64), M)
+    if aggregate_mode == "mean":
+        S = S / np.float64(np.asarray(idx).shape[0])
+    elif aggregate_mode == "count":
+        n = aggregate_counts(np.asarray(idx), M)
+        S = np.divide(S, n, out=np.zeros_like(S), where=n > 0)   # S (/) n, 0/0 = 0
+    elif aggregate_mode != "sum":
+        raise ValueError("aggregate_mode must be 'sum', 'mean' or 'count'")
     if x64.ndim == 1:
         R = unchunk(idct_chunks(S.reshape(-1, s), P))
     else:
         c0, c1 = x64.shape[0] // s, x64.shape[1] // s
         R = unchunk(idct_chunks(S.reshape(c0, c1, s, s), P))
     R = R.reshape(x64.shape)
-    x_new = _sign_update_f32(x64, sgn(R), lr, weight_decay)
+    if phi == "sign":
+        x_new = _sign_update_f32(x64, sgn(R), lr, weight_decay)
+    elif phi == "identity":
+        x_new = _sign_update_f32(x64, R, lr, weight_decay)   # same two FMAs with phi(m) = m
+    else:
+        raise ValueError("phi must be 'sign' or 'identity'")
     if param_dtype == "bf16":
         x_new = round_to_bf16(x_new)
     elif param_dtype != "f32":
@@ -255,7 +302,7 @@ def _fma_f32(a: np.ndarray, b: np.ndarray, c: np.ndarray) -> np.ndarray:
 
 
 def _sign_update_f32(x64: np.ndarray, sg: np.ndarray, lr: float, wd: float) -> np.ndarray:
-    """x' = x - eta (sgn(m) + lambda x)   (Algorithm 1, parameter update line)."""
+    """x' = x - eta (phi(m) + lambda x)   (Algorithm 1, parameter update line; `sg` is phi(m))."""
     lr32 = np.float32(lr)
     wd32 = np.float32(wd)
     x32 = x64.astype(np.float32)
@@ -263,10 +310,11 @@ def _sign_update_f32(x64: np.ndarray, sg: np.ndarray, lr: float, wd: float) -> n
     return _fma_f32(-lr32, t, x32)
 
 
-def step(m_prev, g, x, beta, lr, weight_decay, s, k, param_dtype="f32"):
+def step(m_prev, g, x, beta, lr, weight_decay, s, k, param_dtype="f32", alpha=1.0, grad_scale=1.0,
+         phi="sign", aggregate_mode="sum"):
     """encode followed by decode of the worker's own payload (W = 1).  The
     payload carries float32 values, so the decode side sees them rounded."""
-    e = encode(m_prev, g, beta, s, k)
+    e = encode(m_prev, g, beta, s, k, alpha=alpha, grad_scale=grad_scale)
     payload_val = e["val"].astype(np.float32)
-    d = decode(x, e["idx"][None], payload_val[None], lr, weight_decay, s, param_dtype)
+    d = decode(x, e["idx"][None], payload_val[None], lr, weight_decay, s, param_dtype, phi, aggregate_mode)
     return {**e, **d}

@@ -283,3 +283,89 @@ def test_step_is_encode_then_decode():
     e = O.encode(m, g, 0.999, 32, 8)
     d = O.decode(x, e["idx"][None], e["val"].astype(np.float32)[None], 1e-3, 0.1, 32)
     assert np.array_equal(st["m_new"], e["m_new"]) and np.array_equal(st["x_new"], d["x_new"])
+
+
+# ---------------------------------------------------------------------------
+# Variants of the scalars and of the aggregate (off by default)
+# ---------------------------------------------------------------------------
+def test_alpha_full_selection_leaves_one_minus_alpha():
+    # k = M: the reconstruction is the momentum itself, so the momentum-subtraction equation
+    # (Sec. 2.1, "Momentum Subtraction as Error Feedback") leaves (1 - alpha) * (beta m + g)
+    rng = np.random.default_rng(21)
+    m, g = rng.standard_normal((16, 24)), rng.standard_normal((16, 24))
+    for alpha in (0.0, 0.2, 0.5, 1.0):
+        e = O.encode(m, g, 0.9, 8, 64, alpha=alpha)
+        assert np.allclose(e["m_new"], (1.0 - alpha) * (0.9 * m + g), atol=1e-12)
+    v, gv = rng.standard_normal(32), rng.standard_normal(32)
+    e = O.encode(v, gv, 0.5, 8, 8, alpha=0.2)
+    assert np.allclose(e["m_new"], 0.8 * (0.5 * v + gv), atol=1e-12)
+
+
+def test_alpha_zero_subtracts_nothing_and_payload_is_unscaled():
+    rng = np.random.default_rng(22)
+    m, g = rng.standard_normal((16, 16)), rng.standard_normal((16, 16))
+    e0 = O.encode(m, g, 0.9, 8, 3, alpha=0.0)
+    e1 = O.encode(m, g, 0.9, 8, 3)
+    e2 = O.encode(m, g, 0.9, 8, 3, alpha=0.2)
+    assert np.array_equal(e0["m_new"], 0.9 * m + g)
+    # the transmitted coefficients do not depend on alpha; the residual interpolates linearly
+    assert np.array_equal(e0["idx"], e1["idx"]) and np.array_equal(e0["val"], e1["val"])
+    assert np.array_equal(e2["val"], e1["val"])
+    assert np.allclose(e2["m_new"], 0.8 * e1["m_mid"] + 0.2 * e1["m_new"], atol=1e-12)
+
+
+def test_weighted_momentum_hand_example():
+    # first display equation of Sec. 2.1: M = beta M + (1 - beta) G, worked by hand with beta = 1/2
+    m = np.array([2.0, 4.0, 6.0, 8.0])
+    g = np.array([4.0, 0.0, -2.0, 2.0])
+    e = O.encode(m, g, 0.5, 4, 4, grad_scale=0.5)
+    assert np.array_equal(e["m_mid"], np.array([3.0, 2.0, 2.0, 5.0]))
+    # k = M = 4 and alpha = 1: everything is sent, nothing is left
+    assert np.allclose(e["m_new"], 0.0, atol=1e-14)
+    # the DC coefficient of the orthonormal DCT-II of [3, 2, 2, 5] is 12 / sqrt(4) = 6
+    dc = e["val"][0][list(e["idx"][0]).index(0)]
+    assert abs(dc - 6.0) < 1e-12
+
+
+def test_identity_phi_and_mean_closed_form():
+    # W workers all send every coefficient of the same momentum m: the mean is m's transform, the
+    # reconstruction is m, and the SGD form of the update rule gives x - lr (m + wd x) (Sec. 2.1,
+    # "Momentum Reconstruction and Parameter Update" with phi = identity)
+    rng = np.random.default_rng(23)
+    m = rng.standard_normal((16, 16))
+    x = rng.standard_normal((16, 16)).astype(np.float32).astype(np.float64)
+    e = O.encode(np.zeros_like(m), m, 0.0, 8, 64)
+    W = 5
+    idx = np.repeat(e["idx"][None], W, 0)
+    val = np.repeat(e["val"][None], W, 0)
+    d = O.decode(x, idx, val, 0.25, 0.5, 8, phi="identity", aggregate_mode="mean")
+    assert np.allclose(d["R"], m, atol=1e-12)
+    assert np.allclose(d["x_new"], x - 0.25 * (m + 0.5 * x), rtol=0, atol=2e-6)
+    dsum = O.decode(x, idx, val, 0.25, 0.5, 8, phi="identity", aggregate_mode="sum")
+    assert np.allclose(dsum["R"], W * m, atol=1e-11)
+    # every worker sent every coefficient: the count-normalised average equals the mean
+    dcnt = O.decode(x, idx, val, 0.25, 0.5, 8, phi="identity", aggregate_mode="count")
+    assert np.allclose(dcnt["R"], m, atol=1e-12)
+    # sign descent does not see a positive rescaling of the aggregate
+    a = O.decode(x, idx, val, 0.25, 0.5, 8, aggregate_mode="mean")["x_new"]
+    b = O.decode(x, idx, val, 0.25, 0.5, 8, aggregate_mode="sum")["x_new"]
+    assert np.array_equal(a, b)
+
+
+def test_count_normalised_average_hand_example():
+    # appendix algorithm "Sparse Top-k Averaging", N = 2, d = 4, k = 2, worked by hand:
+    #   X1 = [3, -1, 0.5, 2] sends {0: 3, 3: 2};  X2 = [1, 4, -0.2, 3] sends {1: 4, 3: 3}
+    #   S = [3, 4, 0, 5], n = [1, 1, 0, 2]  ->  S (/) n = [3, 4, 0, 2.5]  (0/0 = 0)
+    X1, X2 = np.array([3.0, -1.0, 0.5, 2.0]), np.array([1.0, 4.0, -0.2, 3.0])
+    i1, i2 = O.topk_indices(X1, 2), O.topk_indices(X2, 2)
+    assert sorted(i1) == [0, 3] and sorted(i2) == [1, 3]
+    idx = np.stack([i1, i2])[:, None, :]
+    val = np.stack([X1[i1], X2[i2]])[:, None, :]
+    assert np.array_equal(O.aggregate(idx, val, 4), np.array([[3.0, 4.0, 0.0, 5.0]]))
+    assert np.array_equal(O.aggregate_counts(idx, 4), np.array([[1, 1, 0, 2]]))
+    d = O.decode(np.zeros(4), idx, val, 1.0, 0.0, 4, phi="identity", aggregate_mode="count")
+    # the reconstruction's transform (scipy's orthonormal DCT-II, an independent routine) is the average
+    assert np.allclose(scipy.fft.dct(d["R"], norm="ortho"), np.array([3.0, 4.0, 0.0, 2.5]), atol=1e-12)
+    # not sign-equivalent to the plain sum in general: here coefficient 3 halves
+    dsum = O.decode(np.zeros(4), idx, val, 1.0, 0.0, 4, phi="identity", aggregate_mode="sum")
+    assert np.allclose(scipy.fft.dct(dsum["R"], norm="ortho"), np.array([3.0, 4.0, 0.0, 5.0]), atol=1e-12)
