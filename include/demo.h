@@ -106,6 +106,45 @@ int demo_decode(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, float l
 int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, float lr,
               float weight_decay, int s, int k, void* hip_stream);
 
+/* The paper's other operating points (all scalar or per-element changes of the two
+ * calls above).  demo_hparams_default fills in the algorithm boxes' values, with
+ * which the _ex calls below are identical to demo_encode / demo_decode / demo_step.
+ *   grad_scale    coefficient of g in the momentum update m <- beta*m + grad_scale*g; 1 in the
+ *                 algorithm boxes, 1 - beta in the first display equation of Sec. 2.1.
+ *   alpha         coefficient of the subtracted reconstruction, m <- m - alpha*IDCT(kept)
+ *                 (display equation of "Momentum Subtraction as Error Feedback"; the ablation
+ *                 "Impact of Momentum Subtraction" varies it in [0, 1], 0.2 being its best).  The
+ *                 payload carries the kept coefficients themselves whatever alpha is.
+ *   phi           DEMO_PHI_SIGN: x <- x - lr*(sgn(m_t) + weight_decay*x) (Signum);
+ *                 DEMO_PHI_IDENTITY: x <- x - lr*(m_t + weight_decay*x) (SGD), same two float32
+ *                 fused multiply-adds (update rule of "Momentum Reconstruction and Parameter
+ *                 Update").  Muon's phi is not provided.
+ *   aggregate     DEMO_AGG_SUM: plain sum over the W payloads (algorithm boxes);
+ *                 DEMO_AGG_MEAN: sum / W (the AvgAllGather of "Top-k Sparsification");
+ *                 DEMO_AGG_COUNT: each coefficient's sum divided by the number of workers that
+ *                 sent it, 0/0 = 0 (appendix algorithm "Sparse Top-k Averaging"); needs W <= 255.
+ * beta, lr, weight_decay as in the calls above.  DEMO_ERR_ARG for an unknown phi / aggregate, a
+ * non-finite scalar, or DEMO_AGG_COUNT with W > 255.  32 bytes, no implicit padding.  */
+typedef enum demo_phi { DEMO_PHI_SIGN = 0, DEMO_PHI_IDENTITY = 1 } demo_phi;
+typedef enum demo_aggregate { DEMO_AGG_SUM = 0, DEMO_AGG_MEAN = 1, DEMO_AGG_COUNT = 2 } demo_aggregate;
+typedef struct demo_hparams {
+  float   beta;
+  float   grad_scale;
+  float   alpha;
+  float   lr;
+  float   weight_decay;
+  int32_t phi;         /* demo_phi */
+  int32_t aggregate;   /* demo_aggregate */
+  int32_t reserved;    /* must be 0 */
+} demo_hparams;
+int demo_hparams_default(demo_hparams* hp, float beta, float lr, float weight_decay);
+int demo_encode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_hparams* hp, int s, int k,
+                   void* hip_stream);   /* uses beta, grad_scale, alpha */
+int demo_decode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, const demo_hparams* hp, int s,
+                   int k, void* hip_stream);   /* uses lr, weight_decay, phi, aggregate */
+int demo_step_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_hparams* hp, int s, int k,
+                 void* hip_stream);
+
 /* Kernel timing with HIP events recorded on the call's own stream around each
  * kernel launch.  demo_set_timing(ctx, 1) opens a measurement window (and clears
  * the previous one); every encode / decode / step call then records one event

@@ -20,9 +20,12 @@ LIB_PATH = os.environ.get("DEMO_LIBRARY_PATH") or os.path.join(_HERE, "libdemo.s
 DEMO_OK, DEMO_ERR_ARG, DEMO_ERR_SHAPE, DEMO_ERR_UNSUPPORTED, DEMO_ERR_HIP, DEMO_ERR_NOMEM = 0, -1, -2, -3, -4, -5
 DEMO_F32, DEMO_BF16 = 0, 1
 DEMO_MAX_K = 256
+DEMO_PHI_SIGN, DEMO_PHI_IDENTITY = 0, 1
+DEMO_AGG_SUM, DEMO_AGG_MEAN, DEMO_AGG_COUNT = 0, 1, 2
 
 EXPORTS = [
     "demo_create", "demo_destroy", "demo_payload_elems", "demo_encode", "demo_decode", "demo_step",
+    "demo_hparams_default", "demo_encode_ex", "demo_decode_ex", "demo_step_ex",
     "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_copy_probe", "demo_strerror", "demo_last_hip_error",
 ]
 
@@ -33,6 +36,14 @@ class DemoTensor(ctypes.Structure):
         ("idx", ctypes.c_void_p), ("val", ctypes.c_void_p),
         ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
         ("grad_dtype", ctypes.c_int32), ("param_dtype", ctypes.c_int32),
+    ]
+
+
+class DemoHParams(ctypes.Structure):
+    _fields_ = [
+        ("beta", ctypes.c_float), ("grad_scale", ctypes.c_float), ("alpha", ctypes.c_float),
+        ("lr", ctypes.c_float), ("weight_decay", ctypes.c_float),
+        ("phi", ctypes.c_int32), ("aggregate", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -62,6 +73,11 @@ def load_library() -> ctypes.CDLL:
     lib.demo_encode.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, cf, ci, ci, vp]
     lib.demo_decode.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, ci, cf, cf, ci, ci, vp]
     lib.demo_step.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, cf, cf, cf, ci, ci, vp]
+    hpp = ctypes.POINTER(DemoHParams)
+    lib.demo_hparams_default.argtypes = [hpp, cf, cf, cf]
+    lib.demo_encode_ex.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, hpp, ci, ci, vp]
+    lib.demo_decode_ex.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, ci, hpp, ci, ci, vp]
+    lib.demo_step_ex.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, hpp, ci, ci, vp]
     lib.demo_set_timing.argtypes = [vp, ci]
     lib.demo_last_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(cf)]
     lib.demo_set_variant.argtypes = [vp, ci]
@@ -79,6 +95,19 @@ def load_library() -> ctypes.CDLL:
 
 def demo_strerror(status: int) -> str:
     return load_library().demo_strerror(status).decode()
+
+
+def demo_hparams_default(beta: float = 0.0, lr: float = 0.0, weight_decay: float = 0.0, **fields) -> DemoHParams:
+    """demo_hparams with the algorithm boxes' values; keyword arguments overwrite single fields."""
+    hp = DemoHParams()
+    rc = load_library().demo_hparams_default(ctypes.byref(hp), beta, lr, weight_decay)
+    if rc != DEMO_OK:
+        raise DemoError(rc, demo_strerror(rc))
+    for name, value in fields.items():
+        if name not in dict(DemoHParams._fields_):
+            raise TypeError(f"demo_hparams has no field {name!r}")
+        setattr(hp, name, value)
+    return hp
 
 
 def demo_payload_elems(rows: int, cols: int, s: int, k: int) -> int:
@@ -193,6 +222,18 @@ class Context:
                   stream=None):
         tl = _as_list(tensors)
         self._check(self._lib.demo_step(self._h, tl.arr, tl.n, beta, lr, weight_decay, s, k, _stream_ptr(stream)))
+
+    def demo_encode_ex(self, tensors: Sequence[TensorArgs], hp: DemoHParams, s: int, k: int, stream=None):
+        tl = _as_list(tensors)
+        self._check(self._lib.demo_encode_ex(self._h, tl.arr, tl.n, ctypes.byref(hp), s, k, _stream_ptr(stream)))
+
+    def demo_decode_ex(self, tensors: Sequence[TensorArgs], W: int, hp: DemoHParams, s: int, k: int, stream=None):
+        tl = _as_list(tensors)
+        self._check(self._lib.demo_decode_ex(self._h, tl.arr, tl.n, W, ctypes.byref(hp), s, k, _stream_ptr(stream)))
+
+    def demo_step_ex(self, tensors: Sequence[TensorArgs], hp: DemoHParams, s: int, k: int, stream=None):
+        tl = _as_list(tensors)
+        self._check(self._lib.demo_step_ex(self._h, tl.arr, tl.n, ctypes.byref(hp), s, k, _stream_ptr(stream)))
 
     def demo_set_timing(self, enabled: bool):
         self._check(self._lib.demo_set_timing(self._h, int(enabled)))

@@ -307,8 +307,9 @@ int timer_end(demo_ctx* ctx, int which, hipStream_t st) {
   return DEMO_OK;
 }
 
-int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, float beta, int s, int k, hipStream_t st) {
-  demo::EncodeArgs a{beta, k};
+int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, const demo_hparams& hp, int s, int k,
+               hipStream_t st) {
+  demo::EncodeArgs a{hp.beta, hp.grad_scale, hp.alpha, k};
   int rc;
   if (tc->tv2.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 0, st)) != DEMO_OK) return rc;
@@ -325,9 +326,10 @@ int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, fl
   return DEMO_OK;
 }
 
-int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, int W, float lr, float wd, int s, int k,
-               hipStream_t st) {
-  demo::DecodeArgs a{lr, wd, k, W};
+int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, int W, const demo_hparams& hp, int s,
+               int k, hipStream_t st) {
+  const float scale = hp.aggregate == DEMO_AGG_MEAN ? 1.0f / (float)W : 1.0f;
+  demo::DecodeArgs a{hp.lr, hp.weight_decay, scale, k, W, hp.phi, hp.aggregate};
   int rc;
   if (tc->tv2.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 2, st)) != DEMO_OK) return rc;
@@ -340,6 +342,22 @@ int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, in
     hipError_t e = demo::launch_decode1d(tc->tv1, basis.basis, s, a, st);
     if (e != hipSuccess) return fail_hip(ctx, e);
     if ((rc = timer_end(ctx, 3, st)) != DEMO_OK) return rc;
+  }
+  return DEMO_OK;
+}
+
+// Scalars and modes of the _ex calls; `need` says which side's fields are used.
+int check_hparams(const demo_hparams* hp, int need, int W) {
+  if (hp == nullptr || hp->reserved != 0) return DEMO_ERR_ARG;
+  if (need & NEED_ENCODE) {
+    if (!std::isfinite(hp->beta) || !std::isfinite(hp->grad_scale) || !std::isfinite(hp->alpha)) return DEMO_ERR_ARG;
+  }
+  if (need & NEED_DECODE) {
+    if (!std::isfinite(hp->lr) || !std::isfinite(hp->weight_decay)) return DEMO_ERR_ARG;
+    if (hp->phi != DEMO_PHI_SIGN && hp->phi != DEMO_PHI_IDENTITY) return DEMO_ERR_ARG;
+    if (hp->aggregate != DEMO_AGG_SUM && hp->aggregate != DEMO_AGG_MEAN && hp->aggregate != DEMO_AGG_COUNT)
+      return DEMO_ERR_ARG;
+    if (hp->aggregate == DEMO_AGG_COUNT && W > 255) return DEMO_ERR_ARG;
   }
   return DEMO_OK;
 }
@@ -392,37 +410,73 @@ int demo_payload_elems(int64_t rows, int64_t cols, int s, int k, int64_t* out) {
   return DEMO_OK;
 }
 
-int demo_encode(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k, void* hip_stream) {
+int demo_hparams_default(demo_hparams* hp, float beta, float lr, float weight_decay) {
+  if (hp == nullptr) return DEMO_ERR_ARG;
+  hp->beta = beta;
+  hp->grad_scale = 1.0f;
+  hp->alpha = 1.0f;
+  hp->lr = lr;
+  hp->weight_decay = weight_decay;
+  hp->phi = DEMO_PHI_SIGN;
+  hp->aggregate = DEMO_AGG_SUM;
+  hp->reserved = 0;
+  return DEMO_OK;
+}
+
+int demo_encode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_hparams* hp, int s, int k,
+                   void* hip_stream) {
   int rc = validate(ctx, tensors, n, s, k, NEED_ENCODE);
-  if (rc != DEMO_OK || n == 0) return rc;
+  if (rc != DEMO_OK) return rc;
+  if ((rc = check_hparams(hp, NEED_ENCODE, 1)) != DEMO_OK || n == 0) return rc;
   demo::BasisTables basis{};
   TableCache* tc = nullptr;
   if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
-  return run_encode(ctx, tc, basis, beta, s, k, static_cast<hipStream_t>(hip_stream));
+  return run_encode(ctx, tc, basis, *hp, s, k, static_cast<hipStream_t>(hip_stream));
 }
 
-int demo_decode(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, float lr, float weight_decay, int s,
-                int k, void* hip_stream) {
+int demo_decode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, const demo_hparams* hp, int s, int k,
+                   void* hip_stream) {
   int rc = validate(ctx, tensors, n, s, k, NEED_DECODE);
   if (rc != DEMO_OK) return rc;
   if (W < 1) return DEMO_ERR_ARG;
-  if (n == 0) return DEMO_OK;
+  if ((rc = check_hparams(hp, NEED_DECODE, W)) != DEMO_OK || n == 0) return rc;
   demo::BasisTables basis{};
   TableCache* tc = nullptr;
   if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
-  return run_decode(ctx, tc, basis, W, lr, weight_decay, s, k, static_cast<hipStream_t>(hip_stream));
+  return run_decode(ctx, tc, basis, W, *hp, s, k, static_cast<hipStream_t>(hip_stream));
 }
 
-int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, float lr, float weight_decay, int s,
-              int k, void* hip_stream) {
+int demo_step_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_hparams* hp, int s, int k,
+                 void* hip_stream) {
   int rc = validate(ctx, tensors, n, s, k, NEED_ENCODE | NEED_DECODE);
-  if (rc != DEMO_OK || n == 0) return rc;
+  if (rc != DEMO_OK) return rc;
+  if ((rc = check_hparams(hp, NEED_ENCODE | NEED_DECODE, 1)) != DEMO_OK || n == 0) return rc;
   demo::BasisTables basis{};
   TableCache* tc = nullptr;
   if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if ((rc = run_encode(ctx, tc, basis, beta, s, k, st)) != DEMO_OK) return rc;
-  return run_decode(ctx, tc, basis, 1, lr, weight_decay, s, k, st);
+  if ((rc = run_encode(ctx, tc, basis, *hp, s, k, st)) != DEMO_OK) return rc;
+  return run_decode(ctx, tc, basis, 1, *hp, s, k, st);
+}
+
+int demo_encode(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k, void* hip_stream) {
+  demo_hparams hp;
+  demo_hparams_default(&hp, beta, 0.0f, 0.0f);
+  return demo_encode_ex(ctx, tensors, n, &hp, s, k, hip_stream);
+}
+
+int demo_decode(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, float lr, float weight_decay, int s,
+                int k, void* hip_stream) {
+  demo_hparams hp;
+  demo_hparams_default(&hp, 0.0f, lr, weight_decay);
+  return demo_decode_ex(ctx, tensors, n, W, &hp, s, k, hip_stream);
+}
+
+int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, float lr, float weight_decay, int s,
+              int k, void* hip_stream) {
+  demo_hparams hp;
+  demo_hparams_default(&hp, beta, lr, weight_decay);
+  return demo_step_ex(ctx, tensors, n, &hp, s, k, hip_stream);
 }
 
 int demo_set_timing(demo_ctx* ctx, int enabled) {

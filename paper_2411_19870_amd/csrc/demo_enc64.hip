@@ -194,16 +194,16 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     if (GBF16) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
-        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], __uint_as_float(ng[q][0] << 16));
-        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], __uint_as_float(ng[q][0] & 0xffff0000u));
-        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], __uint_as_float(ng[q][1] << 16));
-        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], __uint_as_float(ng[q][1] & 0xffff0000u));
+        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], args.grad_scale * __uint_as_float(ng[q][0] << 16));
+        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], args.grad_scale * __uint_as_float(ng[q][0] & 0xffff0000u));
+        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], args.grad_scale * __uint_as_float(ng[q][1] << 16));
+        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], args.grad_scale * __uint_as_float(ng[q][1] & 0xffff0000u));
       }
     } else {
 #pragma unroll
       for (int q = 0; q < 16; ++q)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], ngf[q][e]);
+        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], args.grad_scale * ngf[q][e]);
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -386,7 +386,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     for (int ks = 0; ks < (skip ? 0 : kpad / 4); ++ks) {
       const uint2 sv = sel[4 * ks + g];
       const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
-      const float nv = -__uint_as_float(sv.y);
+      const float nv = -(args.alpha * __uint_as_float(sv.y));
       const float4 pa = *reinterpret_cast<const float4*>(&sProw[u * 64 + 4 * c]);
       const float4 pb = *reinterpret_cast<const float4*>(&sPcol[v * 64 + 4 * c]);
       const float af[4] = {nv * pa.x, nv * pa.y, nv * pa.z, nv * pa.w};

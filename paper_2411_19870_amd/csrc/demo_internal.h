@@ -44,15 +44,23 @@ struct Worklist {
 
 struct EncodeArgs {
   float beta;
+  float grad_scale;   // m <- beta*m + grad_scale*g
+  float alpha;        // m <- m - alpha*IDCT(kept)
   int k;
 };
 
 struct DecodeArgs {
   float lr;
   float weight_decay;
+  float scale;        // factor on the aggregate when phi is the identity: 1 (sum, count) or 1/W (mean)
   int k;
   int W;
+  int phi;            // demo_phi
+  int agg;            // demo_aggregate
 };
+// The wavefront-per-chunk decode kernels implement sign descent on the plain sum (which the mean
+// is sign-equivalent to); the other operating points run on the generic kernels.
+inline bool decode_is_sign_of_sum(const DecodeArgs& a) { return a.phi == 0 && a.agg != 2; }
 
 // Device tables of one chunk size.
 struct BasisTables {

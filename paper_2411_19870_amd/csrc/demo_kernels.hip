@@ -138,10 +138,10 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
       float4 g = load4(d.grad, off, d.grad_bf16);
       float4 m = *reinterpret_cast<const float4*>(d.mom + off);
       float4 v;
-      v.x = __fmaf_rn(args.beta, m.x, g.x);
-      v.y = __fmaf_rn(args.beta, m.y, g.y);
-      v.z = __fmaf_rn(args.beta, m.z, g.z);
-      v.w = __fmaf_rn(args.beta, m.w, g.w);
+      v.x = __fmaf_rn(args.beta, m.x, args.grad_scale * g.x);
+      v.y = __fmaf_rn(args.beta, m.y, args.grad_scale * g.y);
+      v.z = __fmaf_rn(args.beta, m.z, args.grad_scale * g.z);
+      v.w = __fmaf_rn(args.beta, m.w, args.grad_scale * g.w);
       mid[p] = v;
       *reinterpret_cast<float4*>(&sX[row * G::LD + lcol]) = v;
     }
@@ -294,10 +294,10 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
       const int64_t off = base + (int64_t)row * d.cols + lcol;
       const float4 r = *reinterpret_cast<const float4*>(&sX[row * G::LD + lcol]);
       float4 o;
-      o.x = mid[p].x - r.x;
-      o.y = mid[p].y - r.y;
-      o.z = mid[p].z - r.z;
-      o.w = mid[p].w - r.w;
+      o.x = __fmaf_rn(-args.alpha, r.x, mid[p].x);
+      o.y = __fmaf_rn(-args.alpha, r.y, mid[p].y);
+      o.z = __fmaf_rn(-args.alpha, r.z, mid[p].z);
+      o.w = __fmaf_rn(-args.alpha, r.w, mid[p].w);
       *reinterpret_cast<float4*>(d.mom + off) = o;
     }
   }
@@ -325,8 +325,10 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
   float* sX = sP + G::TILE_FLOATS;                     // coefficient sums / first product / signs
   float* sT = G::INPLACE ? sX : sX + G::TILE_FLOATS;
   uint32_t* s_red = reinterpret_cast<uint32_t*>(sX + G::TILE_FLOATS * (G::INPLACE ? 1 : 2));   // [4]
+  uint32_t* s_cnt = s_red + 4;   // [TILE_FLOATS / 4] senders per coefficient, one byte each (count aggregate)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int k = args.k, W = args.W;
+  const bool by_count = args.agg == 2, plain_sign = args.phi == 0 && !by_count;
 
   for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
 
@@ -340,6 +342,8 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
 
     __syncthreads();
     for (int e = tid; e < S * G::LD; e += G::NT) sX[e] = 0.f;
+    if (by_count)
+      for (int e = tid; e < G::TILE_FLOATS / 4; e += G::NT) s_cnt[e] = 0u;
     __syncthreads();
 
     // ---- S[idx] += val in block fixed point: the values are scaled by a power of two taken from
@@ -373,11 +377,25 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
         const int fi = d.idx[po];
         if (fi >= 0 && fi < G::M) {
           const int u = fi / S, v = fi - u * S;
-          atomicAdd(&iX[u * G::LD + v], __float2int_rn(ldexpf(d.val[po], sh)));
+          const int a = u * G::LD + v;
+          atomicAdd(&iX[a], __float2int_rn(ldexpf(d.val[po], sh)));
+          if (by_count) atomicAdd(&s_cnt[a >> 2], 1u << (8 * (a & 3)));   // W <= 255: no carry between bytes
         }
       }
       __syncthreads();
-      for (int e = tid; e < S * G::LD; e += G::NT) sX[e] = (float)iX[e];
+      if (plain_sign) {
+        // only sgn(IDCT(S)) is used: the scale is never undone
+        for (int e = tid; e < S * G::LD; e += G::NT) sX[e] = (float)iX[e];
+      } else {
+        for (int e = tid; e < S * G::LD; e += G::NT) {
+          float v = ldexpf((float)iX[e], -sh) * args.scale;
+          if (by_count) {
+            const uint32_t n = (s_cnt[e >> 2] >> (8 * (e & 3))) & 255u;
+            v = n != 0u ? v / (float)n : 0.f;                              // S (/) n, 0/0 = 0
+          }
+          sX[e] = v;
+        }
+      }
     }
     __syncthreads();
 
@@ -396,12 +414,12 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
 #pragma unroll
     for (int i = 0; i < G::TPW; ++i)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) acc[i][r] = sgnf(acc[i][r]);
+      for (int r = 0; r < 4; ++r) acc[i][r] = args.phi == 0 ? sgnf(acc[i][r]) : acc[i][r];   // phi(m)
     __syncthreads();                       // all reads of Y are done
     store_acc<S>(acc, wave, lane, sX);
     __syncthreads();
 
-    // ---- x <- x - lr*(sgn + wd*x) -----------------------------------------------------------
+    // ---- x <- x - lr*(phi(m) + wd*x) --------------------------------------------------------
 #pragma unroll
     for (int p = 0; p < G::PASSES; ++p) {
       const int row = p * G::ROWS_PER_PASS + lrow;
@@ -444,7 +462,7 @@ __global__ __launch_bounds__(64) void encode1d_wave(TableView tv, const float* _
     if (n < S) {
       const float g = d.grad_bf16 ? bf16_to_f32(static_cast<const uint16_t*>(d.grad)[base + n])
                                   : static_cast<const float*>(d.grad)[base + n];
-      b[e] = __fmaf_rn(args.beta, d.mom[base + n], g);
+      b[e] = __fmaf_rn(args.beta, d.mom[base + n], args.grad_scale * g);
       s_b[n] = b[e];
     }
   }
@@ -487,7 +505,7 @@ __global__ __launch_bounds__(64) void encode1d_wave(TableView tv, const float* _
     if (n < S) {
       float r = 0.f;
       for (int j = 0; j < k; ++j) r = __fmaf_rn(s_sel_val[j], basis[s_sel_idx[j] * S + n], r);   // P^T q^
-      d.mom[base + n] = b[e] - r;
+      d.mom[base + n] = __fmaf_rn(-args.alpha, r, b[e]);
     }
   }
 }
@@ -504,8 +522,13 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
   const TensorDev d = tv.descs[t];
   const int c = chunk - tv.prefix[t];
   const int64_t base = (int64_t)c * S;
+  __shared__ int s_cnt1[S];
   int* i_acc = reinterpret_cast<int*>(s_acc);
-  for (int n = lane; n < S; n += 64) i_acc[n] = 0;
+  const bool by_count = args.agg == 2, plain_sign = args.phi == 0 && !by_count;
+  for (int n = lane; n < S; n += 64) {
+    i_acc[n] = 0;
+    s_cnt1[n] = 0;
+  }
   // sum of the W payloads in block fixed point (as in the order-2 kernels): pass 1 finds the largest
   // magnitude of the chunk's W*k values, pass 2 adds them as integers, independent of the order
   const int64_t wstride = (int64_t)d.nchunks * k;
@@ -531,10 +554,20 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
     const int w = p / k, tt = p - w * k;
     const int fi = ip[(int64_t)w * wstride + tt];
     const float fv = vp[(int64_t)w * wstride + tt];
-    if (fi >= 0 && fi < S) atomicAdd(&i_acc[fi], __float2int_rn(ldexpf(fv, sh)));
+    if (fi >= 0 && fi < S) {
+      atomicAdd(&i_acc[fi], __float2int_rn(ldexpf(fv, sh)));
+      if (by_count) atomicAdd(&s_cnt1[fi], 1);
+    }
   }
   __syncthreads();
-  for (int n = lane; n < S; n += 64) s_acc[n] = (float)i_acc[n];
+  for (int n = lane; n < S; n += 64) {
+    float v = (float)i_acc[n];
+    if (!plain_sign) {
+      v = ldexpf(v, -sh) * args.scale;
+      if (by_count) v = s_cnt1[n] != 0 ? v / (float)s_cnt1[n] : 0.f;
+    }
+    s_acc[n] = v;
+  }
   __syncthreads();
 #pragma unroll
   for (int e = 0; e < EPL; ++e) {
@@ -542,7 +575,7 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
     if (n < S) {
       float r = 0.f;
       for (int u = 0; u < S; ++u) r = __fmaf_rn(s_acc[u], basis[u * S + n], r);   // P^T s
-      const float sg = sgnf(r);
+      const float sg = args.phi == 0 ? sgnf(r) : r;   // phi(m)
       if (d.param_bf16) {
         uint16_t* xp = static_cast<uint16_t*>(d.param) + base + n;
         *xp = (uint16_t)f32_to_bf16_rne(sign_update(bf16_to_f32(*xp), sg, args.lr, args.weight_decay));
@@ -596,7 +629,7 @@ template <int S>
 static hipError_t launch_dec2d_generic(const TableView& tv, const float* basis, const DecodeArgs& a, int num_cus,
                                        hipStream_t stream) {
   using G = Geo<S>;
-  const size_t lds_bytes = sizeof(float) * (G::TILE_FLOATS * (G::INPLACE ? 2 : 3) + 4);
+  const size_t lds_bytes = sizeof(float) * (G::TILE_FLOATS * (G::INPLACE ? 2 : 3) + 4 + G::TILE_FLOATS / 4);
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_generic<S>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
@@ -639,7 +672,8 @@ hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, co
                            int variant, hipStream_t stream) {
   if (tv.total_chunks == 0) return hipSuccess;
   const uint32_t pmix = (tv.dtypes >> 2) & 3u;   // parameter dtypes present: the wavefront kernel wants one
-  if (variant >= 1 && s == 64 && fast64_decode_supports(a.W, a.k) && bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
+  if (variant >= 1 && s == 64 && decode_is_sign_of_sum(a) && fast64_decode_supports(a.W, a.k) && bt.dec64 != nullptr &&
+      (pmix == 1u || pmix == 2u))
     return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {

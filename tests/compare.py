@@ -29,12 +29,13 @@ def chunk_rows(x: np.ndarray, s: int) -> np.ndarray:
     return b.reshape(-1, s) if x.ndim == 1 else b.reshape(b.shape[0] * b.shape[1], s * s)
 
 
-def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_REL):
+def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_REL, alpha32=1.0, grad_scale32=1.0):
     """All arrays numpy; m_prev/g exact input values; gpu_* the HIP outputs.
     Returns a dict of statistics; raises AssertionError on a violation."""
     m_prev = np.asarray(m_prev, np.float64)
     g = np.asarray(g, np.float64)
-    ref = O.encode(m_prev, g, float(np.float32(beta32)), s, k)
+    var = dict(alpha=float(np.float32(alpha32)), grad_scale=float(np.float32(grad_scale32)))
+    ref = O.encode(m_prev, g, float(np.float32(beta32)), s, k, **var)
     Q = ref["Q"]
     nch, M = Q.shape
     gpu_idx = np.asarray(gpu_idx).reshape(nch, k).astype(np.int64)
@@ -58,7 +59,7 @@ def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_R
     eq = gm[:, :-1] == gm[:, 1:]
     assert np.all(gpu_idx[:, :-1][eq] < gpu_idx[:, 1:][eq]), "equal magnitudes not in ascending index order"
     # ---- stage 2: values and residual on the GPU's own selection
-    forced = O.encode(m_prev, g, float(np.float32(beta32)), s, k, forced_idx=gpu_idx)
+    forced = O.encode(m_prev, g, float(np.float32(beta32)), s, k, forced_idx=gpu_idx, **var)
     scale_q = absQ.max(axis=1)
     err_val = np.abs(gpu_val - forced["val"]).max(axis=1)
     ok = err_val <= val_rel * scale_q
@@ -77,13 +78,24 @@ def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_R
     }
 
 
-def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x):
-    """x_prev exact parameter values before the call; idx/val the W payloads the GPU consumed."""
+def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x, phi="sign", aggregate_mode="sum"):
+    """x_prev exact parameter values before the call; idx/val the W payloads the GPU consumed.
+    phi = "identity": the update is a real number, so the parameters are compared numerically:
+    within lr * 1e-5 * (largest |R| of the chunk) plus one unit in the last place of the storage type."""
     x_prev = np.asarray(x_prev, np.float64)
     ref = O.decode(x_prev, np.asarray(idx), np.asarray(val), float(np.float32(lr32)), float(np.float32(wd32)),
-                   s, param_dtype)
+                   s, param_dtype, phi, aggregate_mode)
     got = np.asarray(gpu_x, np.float32)
     want = ref["x_new"]
+    if phi == "identity":
+        R = chunk_rows(ref["R"], s)
+        tolR = float(np.float32(lr32)) * VAL_REL * np.abs(R).max(axis=1, keepdims=True)
+        w = chunk_rows(want.astype(np.float64), s)
+        ulp = np.abs(w) * (2.0 ** -8 if param_dtype == "bf16" else 2.0 ** -23) + 1e-45
+        err = np.abs(chunk_rows(got.astype(np.float64), s) - w)
+        assert np.all(err <= tolR + ulp), f"parameters off: worst excess {np.max(err - tolR - ulp):.3e}"
+        return {"elements": int(got.size), "mismatch": int((got != want).sum()), "in_band": 0,
+                "max_err_over_lr_Rmax": float(np.max(err / np.maximum(tolR / VAL_REL, 1e-300)))}
     bad = got != want
     stats = {"elements": int(got.size), "mismatch": int(bad.sum()), "in_band": 0}
     if bad.any():

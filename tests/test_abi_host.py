@@ -105,6 +105,32 @@ def test_validation_happens_before_any_launch():
     assert lib.demo_strerror(B.DEMO_ERR_SHAPE) and lib.demo_strerror(12345)
 
 
+def test_hparams_struct_and_validation():
+    lib = B.load_library()
+    assert ctypes.sizeof(B.DemoHParams) == 32
+    hp = B.demo_hparams_default(0.999, 1e-3, 0.1)
+    assert (hp.beta, hp.grad_scale, hp.alpha) == (ctypes.c_float(0.999).value, 1.0, 1.0)
+    assert (hp.phi, hp.aggregate, hp.reserved) == (B.DEMO_PHI_SIGN, B.DEMO_AGG_SUM, 0)
+    assert lib.demo_hparams_default(None, 0.9, 0.0, 0.0) == B.DEMO_ERR_ARG
+    h = ctypes.c_void_p()
+    assert lib.demo_create(ctypes.byref(h)) == B.DEMO_OK
+    arr1 = (B.DemoTensor * 1)
+    t = _tensor()
+    assert lib.demo_decode_ex(h, arr1(t), 1, 1, None, 64, 32, None) == B.DEMO_ERR_ARG
+    for bad in (dict(phi=2), dict(aggregate=3), dict(reserved=5), dict(weight_decay=float("inf"))):
+        hpb = B.demo_hparams_default(**{**dict(beta=0.9, lr=1e-3, weight_decay=0.0), **bad})
+        assert lib.demo_decode_ex(h, arr1(t), 1, 1, ctypes.byref(hpb), 64, 32, None) == B.DEMO_ERR_ARG
+    cnt = B.demo_hparams_default(0.9, 1e-3, 0.0, aggregate=B.DEMO_AGG_COUNT)
+    assert lib.demo_decode_ex(h, arr1(t), 1, 256, ctypes.byref(cnt), 64, 32, None) == B.DEMO_ERR_ARG
+    nanb = B.demo_hparams_default(float("nan"), 1e-3, 0.0)
+    assert lib.demo_encode_ex(h, arr1(t), 1, ctypes.byref(nanb), 64, 32, None) == B.DEMO_ERR_ARG
+    assert lib.demo_step_ex(h, arr1(t), 1, ctypes.byref(nanb), 64, 32, None) == B.DEMO_ERR_ARG
+    # shape errors are still reported first, and an empty list is fine
+    assert lib.demo_encode_ex(h, arr1(_tensor(rows=100)), 1, ctypes.byref(hp), 64, 32, None) == B.DEMO_ERR_SHAPE
+    assert lib.demo_encode_ex(h, arr1(t), 0, ctypes.byref(hp), 64, 32, None) == B.DEMO_OK
+    assert lib.demo_destroy(h) == B.DEMO_OK
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libdemo.so"))
