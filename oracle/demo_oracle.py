@@ -49,7 +49,11 @@ default (the defaults are the readings above):
     Reconstruction and Parameter Update"; Muon's phi is not covered;
   * aggregate mode: "sum" (algorithm boxes), "mean" (sum / W, the AvgAllGather
     of "Top-k Sparsification") or "count" (appendix algorithm "Sparse Top-k
-    Averaging": S (/) n with 0/0 = 0, n = how many workers sent the coefficient).
+    Averaging": S (/) n with 0/0 = 0, n = how many workers sent the coefficient);
+  * P: any orthonormal s x s matrix in place of the DCT (ablation "Choice of
+    Linear Projections": the identity, or Gaussian entries orthonormalised by
+    Gram-Schmidt -- `gram_schmidt`, rows in order; drawing the entries is the
+    caller's business).
 
 Parity pins (tests/test_oracle_pins.py): DCT against scipy's orthonormal DCT-II,
 orthonormality, Parseval, closed forms (constant and single-cosine chunks),
@@ -59,14 +63,16 @@ aggregate, the 128x512 -> 16x32 blocking example, bfloat16 rounding against
 torch's conversion, and for the variants: k = M with alpha (residual (1-alpha) m),
 alpha = 0, a hand-worked weighted momentum, W identical full payloads under the
 mean, the identity update in closed form, and a hand-worked two-worker example of
-the count-normalised average.  No function here is "parity unpinned".
+the count-normalised average; Gram-Schmidt against numpy's QR and a hand-worked
+2 x 2 case, the identity basis as plain top-k of the momentum entries.  No
+function here is "parity unpinned".
 """
 from __future__ import annotations
 
 import numpy as np
 
 __all__ = [
-    "dct_basis", "chunk", "unchunk", "momentum_update", "dct_chunks",
+    "dct_basis", "gram_schmidt", "chunk", "unchunk", "momentum_update", "dct_chunks",
     "idct_chunks", "topk_indices", "encode", "aggregate", "aggregate_counts", "decode", "step",
     "round_to_bf16", "sgn",
 ]
@@ -124,6 +130,21 @@ def unchunk(b: np.ndarray) -> np.ndarray:
     return x
 
 
+def gram_schmidt(A: np.ndarray) -> np.ndarray:
+    """Rows of the square matrix A orthonormalised in order by the Gram-Schmidt process (ablation
+    "Choice of Linear Projections": Gaussian entries, then Gram-Schmidt; the paper does not say
+    rows or columns -- rows are taken, row 0 keeps its direction).  Each row has its projections on
+    the rows already finished removed one after the other, then is normalised."""
+    A = np.asarray(A, np.float64)
+    P = np.zeros_like(A)
+    for i in range(A.shape[0]):
+        v = A[i].copy()
+        for j in range(i):
+            v -= np.dot(P[j], v) * P[j]
+        P[i] = v / np.sqrt(np.dot(v, v))
+    return P
+
+
 # --------------------------------------------------------------------------
 # Step 1: local momentum  (Algorithm 1, "update local momentum buffer")
 # --------------------------------------------------------------------------
@@ -166,7 +187,8 @@ def topk_indices(q_flat: np.ndarray, k: int) -> np.ndarray:
 # Worker side, one tensor
 # --------------------------------------------------------------------------
 def encode(m_prev: np.ndarray, g: np.ndarray, beta: float, s: int, k: int,
-           forced_idx: np.ndarray | None = None, alpha: float = 1.0, grad_scale: float = 1.0):
+           forced_idx: np.ndarray | None = None, alpha: float = 1.0, grad_scale: float = 1.0,
+           P: np.ndarray | None = None):
     """One worker's encode of one tensor.
 
     m_prev, g : float arrays of identical shape ([n] or [n0, n1]); their values
@@ -176,6 +198,7 @@ def encode(m_prev: np.ndarray, g: np.ndarray, beta: float, s: int, k: int,
                 residual on a selection that differs only inside a near-tie).
     alpha     : coefficient of the subtracted reconstruction (1 = algorithm boxes).
     grad_scale: coefficient of g in the momentum update (1 = algorithm boxes).
+    P         : s x s orthonormal projection matrix used for every dimension; default the DCT.
     Returns dict with
       m_new  : residual momentum, same shape as m_prev
       idx    : int32 [nchunks, k]   (chunk order row-major over (k0, k1))
@@ -183,7 +206,7 @@ def encode(m_prev: np.ndarray, g: np.ndarray, beta: float, s: int, k: int,
       Q      : all coefficients, float64 [nchunks, M]
       m_mid  : beta*m + grad_scale*g before the subtraction
     """
-    P = dct_basis(s)
+    P = dct_basis(s) if P is None else np.asarray(P, np.float64)
     m_mid = momentum_update(m_prev, g, beta, grad_scale)
     b = chunk(m_mid, s)                                     # ChunkExtract
     Q = dct_chunks(b, P)                                    # DCT
@@ -253,7 +276,8 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
 
 
 def decode(x: np.ndarray, idx: np.ndarray, val: np.ndarray, lr: float, weight_decay: float,
-           s: int, param_dtype: str = "f32", phi: str = "sign", aggregate_mode: str = "sum"):
+           s: int, param_dtype: str = "f32", phi: str = "sign", aggregate_mode: str = "sum",
+           P: np.ndarray | None = None):
     """Server side for one tensor: aggregate W payloads, inverse transform,
     sign, parameter update.
 
@@ -263,7 +287,7 @@ def decode(x: np.ndarray, idx: np.ndarray, val: np.ndarray, lr: float, weight_de
     Returns dict with x_new (float32 values, representable in `param_dtype`),
     R (the reconstructed momentum, float64, same shape as x).
     """
-    P = dct_basis(s)
+    P = dct_basis(s) if P is None else np.asarray(P, np.float64)
     x64 = np.asarray(x, np.float64)
     M = s if x64.ndim == 1 else s * s
     S = aggregate(np.asarray(idx), np.asarray(val, np.float64), M)

@@ -369,3 +369,60 @@ def test_count_normalised_average_hand_example():
     # not sign-equivalent to the plain sum in general: here coefficient 3 halves
     dsum = O.decode(np.zeros(4), idx, val, 1.0, 0.0, 4, phi="identity", aggregate_mode="sum")
     assert np.allclose(scipy.fft.dct(dsum["R"], norm="ortho"), np.array([3.0, 4.0, 0.0, 5.0]), atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# Other projection matrices (ablation "Choice of Linear Projections")
+# ---------------------------------------------------------------------------
+def test_gram_schmidt_hand_and_qr():
+    # hand-worked: rows (3, 4) and (1, 0): first row / 5; second minus its projection 0.6 * (0.6, 0.8)
+    # = (0.64, -0.48), of norm 0.8 -> (0.8, -0.6)
+    P = O.gram_schmidt(np.array([[3.0, 4.0], [1.0, 0.0]]))
+    assert np.allclose(P, np.array([[0.6, 0.8], [0.8, -0.6]]), atol=1e-15)
+    rng = np.random.default_rng(40)
+    for s in (4, 32, 64, 128):
+        A = rng.standard_normal((s, s))
+        P = O.gram_schmidt(A)
+        assert np.allclose(P @ P.T, np.eye(s), atol=1e-10)
+        # Gram-Schmidt on the rows of A is the QR factorisation of A^T with positive diagonal of R
+        Qm, Rm = np.linalg.qr(A.T)
+        Qm = Qm * np.sign(np.diag(Rm))[None, :]
+        assert np.allclose(P, Qm.T, atol=1e-9)
+        # row i stays inside the span of the first i + 1 rows of A, along +A[i] modulo earlier rows
+        assert np.all(np.diag(P @ A.T) > 0)
+
+
+def test_identity_basis_is_plain_topk_of_entries():
+    rng = np.random.default_rng(41)
+    m, g = rng.standard_normal((8, 12)), rng.standard_normal((8, 12))
+    e = O.encode(m, g, 0.5, 4, 3, P=np.eye(4))
+    mid = 0.5 * m + g
+    blocks = O.chunk(mid, 4).reshape(-1, 16)
+    for c in range(blocks.shape[0]):
+        order = sorted(range(16), key=lambda i: (-abs(blocks[c, i]), i))[:3]
+        assert list(e["idx"][c]) == order
+        assert np.array_equal(e["val"][c], blocks[c, order])
+    # the kept entries are removed, everything else stays
+    left = O.chunk(e["m_new"], 4).reshape(-1, 16)
+    for c in range(blocks.shape[0]):
+        keep = np.ones(16, bool)
+        keep[e["idx"][c]] = False
+        assert np.array_equal(left[c, keep], blocks[c, keep]) and np.all(left[c, ~keep] == 0.0)
+
+
+def test_random_orthonormal_basis_exact_recovery_and_parseval():
+    rng = np.random.default_rng(42)
+    s = 8
+    P = O.gram_schmidt(rng.standard_normal((s, s)))
+    m = rng.standard_normal((16, 24))
+    e = O.encode(np.zeros_like(m), m, 0.0, s, s * s, P=P)
+    assert np.allclose(e["m_new"], 0.0, atol=1e-12)
+    assert np.allclose((e["Q"] ** 2).sum(), (m ** 2).sum(), rtol=1e-12)
+    x = rng.standard_normal((16, 24))
+    d = O.decode(x, e["idx"][None], e["val"][None], 0.5, 0.0, s, phi="identity", P=P)
+    assert np.allclose(d["R"], m, atol=1e-12)
+    # 1-D
+    v = rng.standard_normal(32)
+    e1 = O.encode(np.zeros(32), v, 0.0, s, s, P=P)
+    d1 = O.decode(np.zeros(32), e1["idx"][None], e1["val"][None], 1.0, 0.0, s, phi="identity", P=P)
+    assert np.allclose(d1["R"], v, atol=1e-12) and np.allclose(e1["m_new"], 0.0, atol=1e-12)
