@@ -145,6 +145,21 @@ int demo_decode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, cons
 int demo_step_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_hparams* hp, int s, int k,
                  void* hip_stream);
 
+/* Projection matrix used by later calls for chunk size s (ablation "Choice of Linear Projections"):
+ *   DEMO_BASIS_DCT           the orthonormal DCT-II (default; a_host ignored);
+ *   DEMO_BASIS_IDENTITY      P = I, no transformation (a_host ignored);
+ *   DEMO_BASIS_GRAM_SCHMIDT  a_host points to s*s float32 values in HOST memory, row-major (the
+ *                            paper draws them from N(0, 1) with the step number as seed, the same on
+ *                            every worker; drawing them is the caller's business).  The rows are
+ *                            orthonormalised in order by the Gram-Schmidt process in double precision
+ *                            and rounded once to float32.  DEMO_ERR_ARG if they are linearly dependent.
+ * The same matrix serves every dimension and both directions (inverse = transpose).  With a matrix
+ * other than the DCT the calls run on the kernels that read the matrix from memory; the s = 64 / 32
+ * wavefront kernels are specific to the DCT.  The call synchronises the device (kernels enqueued
+ * earlier may still read the matrix it replaces) and copies s*s floats to it.  */
+typedef enum demo_basis { DEMO_BASIS_DCT = 0, DEMO_BASIS_IDENTITY = 1, DEMO_BASIS_GRAM_SCHMIDT = 2 } demo_basis;
+int demo_set_basis(demo_ctx* ctx, int s, int kind, const float* a_host);
+
 /* Kernel timing with HIP events recorded on the call's own stream around each
  * kernel launch.  demo_set_timing(ctx, 1) opens a measurement window (and clears
  * the previous one); every encode / decode / step call then records one event

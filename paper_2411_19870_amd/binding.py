@@ -22,10 +22,11 @@ DEMO_F32, DEMO_BF16 = 0, 1
 DEMO_MAX_K = 256
 DEMO_PHI_SIGN, DEMO_PHI_IDENTITY = 0, 1
 DEMO_AGG_SUM, DEMO_AGG_MEAN, DEMO_AGG_COUNT = 0, 1, 2
+DEMO_BASIS_DCT, DEMO_BASIS_IDENTITY, DEMO_BASIS_GRAM_SCHMIDT = 0, 1, 2
 
 EXPORTS = [
     "demo_create", "demo_destroy", "demo_payload_elems", "demo_encode", "demo_decode", "demo_step",
-    "demo_hparams_default", "demo_encode_ex", "demo_decode_ex", "demo_step_ex",
+    "demo_hparams_default", "demo_encode_ex", "demo_decode_ex", "demo_step_ex", "demo_set_basis",
     "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_copy_probe", "demo_strerror", "demo_last_hip_error",
 ]
 
@@ -78,6 +79,7 @@ def load_library() -> ctypes.CDLL:
     lib.demo_encode_ex.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, hpp, ci, ci, vp]
     lib.demo_decode_ex.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, ci, hpp, ci, ci, vp]
     lib.demo_step_ex.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, hpp, ci, ci, vp]
+    lib.demo_set_basis.argtypes = [vp, ci, ci, vp]
     lib.demo_set_timing.argtypes = [vp, ci]
     lib.demo_last_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(cf)]
     lib.demo_set_variant.argtypes = [vp, ci]
@@ -234,6 +236,15 @@ class Context:
     def demo_step_ex(self, tensors: Sequence[TensorArgs], hp: DemoHParams, s: int, k: int, stream=None):
         tl = _as_list(tensors)
         self._check(self._lib.demo_step_ex(self._h, tl.arr, tl.n, ctypes.byref(hp), s, k, _stream_ptr(stream)))
+
+    def demo_set_basis(self, s: int, kind: int, a: Optional[torch.Tensor] = None):
+        """a: CPU float32 tensor of s*s values (DEMO_BASIS_GRAM_SCHMIDT), else None."""
+        ptr = None
+        if a is not None:
+            if a.device.type != "cpu" or a.dtype != torch.float32 or not a.is_contiguous() or a.numel() != s * s:
+                raise ValueError("demo_set_basis wants a contiguous CPU float32 tensor of s*s values")
+            ptr = a.data_ptr()
+        self._check(self._lib.demo_set_basis(self._h, s, kind, ptr))
 
     def demo_set_timing(self, enabled: bool):
         self._check(self._lib.demo_set_timing(self._h, int(enabled)))

@@ -23,6 +23,8 @@ struct BasisTable {
   float* enc64 = nullptr;    // tables of the s = 64 wavefront-per-chunk kernels
   float* dec64 = nullptr;
   float* enc32 = nullptr;    // dense-basis tile tables for s = 32
+  float* custom = nullptr;   // s x s matrix set with demo_set_basis (identity / Gram-Schmidt), allocated on first use
+  bool use_custom = false;   // later calls project with `custom` on the generic kernels
 };
 
 // One cached descriptor upload: the host bytes it was built from and the device copy.
@@ -135,7 +137,13 @@ int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
 
 int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   for (const BasisTable& b : ctx->bases)
-    if (b.s == s) { *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32}; return DEMO_OK; }
+    if (b.s == s) {
+      // the wavefront kernels are built on the symmetries of the DCT: any other matrix runs on the
+      // kernels that read the matrix itself
+      *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr}
+                          : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32};
+      return DEMO_OK;
+    }
   std::vector<double> P((size_t)s * s);
   const double pi = 3.14159265358979323846;
   for (int u = 0; u < s; ++u) {
@@ -390,6 +398,7 @@ int demo_destroy(demo_ctx* ctx) {
       if (b.enc64) (void)hipFree(b.enc64);
       if (b.dec64) (void)hipFree(b.dec64);
       if (b.enc32) (void)hipFree(b.enc32);
+      if (b.custom) (void)hipFree(b.custom);
     }
     for (TableCache& tc : ctx->tables)
       if (tc.dev) (void)hipFree(tc.dev);
@@ -515,6 +524,63 @@ int demo_copy_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes, v
   hipError_t e = demo::launch_copy_probe(src, dst, (size_t)nbytes, ctx->num_cus, st);
   if (e != hipSuccess) return fail_hip(ctx, e);
   return timer_end(ctx, 1, st);
+}
+
+int demo_set_basis(demo_ctx* ctx, int s, int kind, const float* a_host) {
+  if (ctx == nullptr) return DEMO_ERR_ARG;
+  if (s != 32 && s != 64 && s != 128) return DEMO_ERR_UNSUPPORTED;
+  if (kind != DEMO_BASIS_DCT && kind != DEMO_BASIS_IDENTITY && kind != DEMO_BASIS_GRAM_SCHMIDT) return DEMO_ERR_ARG;
+  if (kind == DEMO_BASIS_GRAM_SCHMIDT && a_host == nullptr) return DEMO_ERR_ARG;
+  std::vector<double> P;
+  if (kind == DEMO_BASIS_IDENTITY) {
+    P.assign((size_t)s * s, 0.0);
+    for (int i = 0; i < s; ++i) P[(size_t)i * s + i] = 1.0;
+  } else if (kind == DEMO_BASIS_GRAM_SCHMIDT) {
+    // rows orthonormalised in order, in double: each row loses its components along the finished
+    // rows one after the other, then is normalised
+    P.assign(a_host, a_host + (size_t)s * s);
+    for (int i = 0; i < s; ++i) {
+      double* v = &P[(size_t)i * s];
+      double n0 = 0.0;
+      for (int c = 0; c < s; ++c) n0 += v[c] * v[c];
+      if (!std::isfinite(n0)) return DEMO_ERR_ARG;
+      for (int j = 0; j < i; ++j) {
+        const double* q = &P[(size_t)j * s];
+        double dot = 0.0;
+        for (int c = 0; c < s; ++c) dot += q[c] * v[c];
+        for (int c = 0; c < s; ++c) v[c] -= dot * q[c];
+      }
+      double n1 = 0.0;
+      for (int c = 0; c < s; ++c) n1 += v[c] * v[c];
+      if (!(n1 > 1e-20 * n0) || n0 == 0.0) return DEMO_ERR_ARG;   // rows (numerically) dependent
+      const double inv = 1.0 / std::sqrt(n1);
+      for (int c = 0; c < s; ++c) v[c] *= inv;
+    }
+  }
+  int rc = bind_device(ctx);
+  if (rc != DEMO_OK) return rc;
+  demo::BasisTables unused{};
+  if ((rc = get_basis(ctx, s, &unused)) != DEMO_OK) return rc;   // makes sure the entry of this s exists
+  for (BasisTable& b : ctx->bases) {
+    if (b.s != s) continue;
+    if (kind == DEMO_BASIS_DCT) {
+      b.use_custom = false;
+      return DEMO_OK;
+    }
+    // kernels enqueued earlier may still read the matrix this call replaces
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    const std::vector<float> host(P.begin(), P.end());   // one rounding to float32
+    if (b.custom == nullptr) {
+      if ((rc = upload(ctx, host, &b.custom)) != DEMO_OK) return rc;
+    } else {
+      e = hipMemcpy(b.custom, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice);
+      if (e != hipSuccess) return fail_hip(ctx, e);
+    }
+    b.use_custom = true;
+    return DEMO_OK;
+  }
+  return DEMO_ERR_ARG;
 }
 
 int demo_set_variant(demo_ctx* ctx, int variant) {

@@ -88,6 +88,15 @@ def gaussian(spec: TensorSpec, std: float, seed: int, tensor_index: int, step: i
     return t.to(dtype)
 
 
+def projection_draws(s: int, step: int) -> torch.Tensor:
+    """s x s float32 draws from N(0, 1) seeded with the step number: the raw material of the random
+    projection matrix of the paper's ablation (every worker draws the same matrix at a given step).
+    Orthonormalising them is the method's business, not this module's."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(step))
+    return torch.randn((s, s), generator=g, dtype=torch.float32)
+
+
 def student_t3(spec: TensorSpec, scale: float, seed: int, tensor_index: int, step: int, role: str,
                dtype=torch.float32, device="cpu") -> torch.Tensor:
     """Student-t with 3 degrees of freedom, times `scale` (heavy tails; rounding

@@ -29,12 +29,13 @@ def chunk_rows(x: np.ndarray, s: int) -> np.ndarray:
     return b.reshape(-1, s) if x.ndim == 1 else b.reshape(b.shape[0] * b.shape[1], s * s)
 
 
-def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_REL, alpha32=1.0, grad_scale32=1.0):
+def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_REL, alpha32=1.0, grad_scale32=1.0,
+                 P=None):
     """All arrays numpy; m_prev/g exact input values; gpu_* the HIP outputs.
     Returns a dict of statistics; raises AssertionError on a violation."""
     m_prev = np.asarray(m_prev, np.float64)
     g = np.asarray(g, np.float64)
-    var = dict(alpha=float(np.float32(alpha32)), grad_scale=float(np.float32(grad_scale32)))
+    var = dict(alpha=float(np.float32(alpha32)), grad_scale=float(np.float32(grad_scale32)), P=P)
     ref = O.encode(m_prev, g, float(np.float32(beta32)), s, k, **var)
     Q = ref["Q"]
     nch, M = Q.shape
@@ -78,13 +79,13 @@ def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_R
     }
 
 
-def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x, phi="sign", aggregate_mode="sum"):
+def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x, phi="sign", aggregate_mode="sum", P=None):
     """x_prev exact parameter values before the call; idx/val the W payloads the GPU consumed.
     phi = "identity": the update is a real number, so the parameters are compared numerically:
     within lr * 1e-5 * (largest |R| of the chunk) plus one unit in the last place of the storage type."""
     x_prev = np.asarray(x_prev, np.float64)
     ref = O.decode(x_prev, np.asarray(idx), np.asarray(val), float(np.float32(lr32)), float(np.float32(wd32)),
-                   s, param_dtype, phi, aggregate_mode)
+                   s, param_dtype, phi, aggregate_mode, P)
     got = np.asarray(gpu_x, np.float32)
     want = ref["x_new"]
     if phi == "identity":

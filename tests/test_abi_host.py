@@ -131,6 +131,20 @@ def test_hparams_struct_and_validation():
     assert lib.demo_destroy(h) == B.DEMO_OK
 
 
+def test_set_basis_validation_on_host():
+    lib = B.load_library()
+    h = ctypes.c_void_p()
+    assert lib.demo_create(ctypes.byref(h)) == B.DEMO_OK
+    assert lib.demo_set_basis(None, 64, B.DEMO_BASIS_DCT, None) == B.DEMO_ERR_ARG
+    assert lib.demo_set_basis(h, 48, B.DEMO_BASIS_IDENTITY, None) == B.DEMO_ERR_UNSUPPORTED
+    assert lib.demo_set_basis(h, 64, 9, None) == B.DEMO_ERR_ARG
+    assert lib.demo_set_basis(h, 64, B.DEMO_BASIS_GRAM_SCHMIDT, None) == B.DEMO_ERR_ARG
+    # linearly dependent rows are refused before anything touches a device
+    a = (ctypes.c_float * (32 * 32))(*([1.0] * (32 * 32)))
+    assert lib.demo_set_basis(h, 32, B.DEMO_BASIS_GRAM_SCHMIDT, ctypes.cast(a, ctypes.c_void_p)) == B.DEMO_ERR_ARG
+    assert lib.demo_destroy(h) == B.DEMO_OK
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libdemo.so"))

@@ -119,3 +119,84 @@ def test_hparams_are_validated(ctx):
         assert e.value.status == B.DEMO_ERR_ARG
     with pytest.raises(B.DemoError):
         ctx.demo_encode_ex(case.args, B.demo_hparams_default(beta=0.9, alpha=float("inf")), 64, 8)
+
+
+# ---- other projection matrices (ablation "Choice of Linear Projections") ---------------------------------
+def _projection(s, kind, step):
+    """(argument for demo_set_basis, the oracle's matrix)"""
+    from oracle import demo_oracle as O
+    if kind == "identity":
+        return None, np.eye(s)
+    a = synth.projection_draws(s, step)
+    return a, O.gram_schmidt(a.double().numpy())
+
+
+@pytest.mark.parametrize("s,k", [(32, 8), (64, 32), (128, 8)])
+@pytest.mark.parametrize("kind", ["identity", "gram_schmidt"])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_other_projection_matrices(ctx, s, k, kind, dt):
+    W = 3
+    case = Case(synth.tensor_set("tiny"), s, k, W=W, grad_dtype=dt, param_dtype=dt, seed=37)
+    a, P = _projection(s, kind, step=5)
+    code = B.DEMO_BASIS_IDENTITY if kind == "identity" else B.DEMO_BASIS_GRAM_SCHMIDT
+    try:
+        ctx.demo_set_basis(s, code, a)
+        before = case.snapshot()
+        ctx.demo_encode(case.args, 0.9, s, k)
+        torch.cuda.synchronize()
+        after = case.snapshot()
+        for ti in range(len(case.specs)):
+            C.check_encode(before["m"][ti], before["g"][ti], 0.9, s, k, after["idx"][ti][0], after["val"][ti][0],
+                           after["m"][ti], P=P)
+        case.fill_payloads()
+        before = case.snapshot()
+        ctx.demo_decode(case.args, W, LR, 0.0, s, k)
+        torch.cuda.synchronize()
+        after = case.snapshot()
+        pd = "bf16" if dt == torch.bfloat16 else "f32"
+        for ti in range(len(case.specs)):
+            C.check_decode(before["x"][ti], before["idx"][ti], before["val"][ti], LR, 0.0, s, pd, after["x"][ti], P=P)
+    finally:
+        ctx.demo_set_basis(s, B.DEMO_BASIS_DCT)
+
+
+def test_new_matrix_every_step_then_back_to_dct(ctx):
+    # the paper's random projection: a fresh matrix per step, seeded with the step number
+    s, k = 64, 16
+    case = Case(synth.tensor_set("tiny"), s, k, seed=38)
+    ref = Case(synth.tensor_set("tiny"), s, k, seed=38)
+    try:
+        for step in range(3):
+            a, P = _projection(s, "gram_schmidt", step)
+            ctx.demo_set_basis(s, B.DEMO_BASIS_GRAM_SCHMIDT, a)
+            case.new_grads(step)
+            before = case.snapshot()
+            ctx.demo_encode(case.args, 0.9, s, k)
+            torch.cuda.synchronize()
+            after = case.snapshot()
+            for ti in range(len(case.specs)):
+                C.check_encode(before["m"][ti], before["g"][ti], 0.9, s, k, after["idx"][ti][0],
+                               after["val"][ti][0], after["m"][ti], P=P)
+    finally:
+        ctx.demo_set_basis(s, B.DEMO_BASIS_DCT)
+    # back on the DCT the wavefront kernels are in use again and give what a fresh context gives
+    fresh = B.Context()
+    a2 = Case(synth.tensor_set("tiny"), s, k, seed=39)
+    ctx.demo_encode(a2.args, 0.9, s, k)
+    fresh.demo_encode(ref.args, 0.9, s, k)   # `ref` holds seed 38: only its own consistency matters below
+    b2 = Case(synth.tensor_set("tiny"), s, k, seed=39)
+    fresh.demo_encode(b2.args, 0.9, s, k)
+    torch.cuda.synchronize()
+    sa, sb = a2.snapshot(), b2.snapshot()
+    for key in ("m", "idx", "val"):
+        for ta, tb in zip(sa[key], sb[key]):
+            assert np.array_equal(ta, tb)
+    fresh.close()
+
+
+def test_set_basis_rejects_dependent_rows(ctx):
+    a = synth.projection_draws(32, 0)
+    a[7] = a[3] * 2.0
+    with pytest.raises(B.DemoError) as e:
+        ctx.demo_set_basis(32, B.DEMO_BASIS_GRAM_SCHMIDT, a)
+    assert e.value.status == B.DEMO_ERR_ARG
