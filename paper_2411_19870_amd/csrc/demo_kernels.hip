@@ -16,6 +16,8 @@ namespace demo {
 // ---------------------------------------------------------------------------
 // Geometry of the generic order-2 kernels
 // ---------------------------------------------------------------------------
+constexpr int GEN_CAND_CAP = 512;   // candidate list of the generic encode kernel's top-k
+
 template <int S>
 struct Geo {
   static constexpr int NT = 256;                     // threads per workgroup (4 wavefronts)
@@ -30,7 +32,7 @@ struct Geo {
   static constexpr int M = S * S;
   static constexpr int TILE_FLOATS = S * LD;
   // LDS: basis, data tile, (second tile when not in place), selection scratch
-  static constexpr int LDS_FLOATS = TILE_FLOATS * (INPLACE ? 2 : 3) + 3 * DEMO_MAXK_INTERNAL + 32;
+  static constexpr int LDS_FLOATS = TILE_FLOATS * (INPLACE ? 2 : 3) + 3 * DEMO_MAXK_INTERNAL + 32 + 3 * GEN_CAND_CAP;
 };
 
 // tile i of wavefront w -> (mt, nt)
@@ -83,6 +85,27 @@ __device__ __forceinline__ void store_acc(const f32x4* acc, int wave, int lane, 
   }
 }
 
+// Tensor of a chunk for a workgroup that walks the chunks in ascending order: a step from the tensor
+// of the previous chunk instead of a binary search (a chain of dependent loads) per chunk.  `st` holds
+// {tensor, its first chunk, the next tensor's first chunk}; st.t < 0 before the first call.
+struct TensorCursor {
+  int t = -1, first = 0, next = 0;
+};
+__device__ __forceinline__ int tensor_of_chunk(const TableView& tv, int chunk, TensorCursor& st) {
+  if (st.t < 0 || chunk < st.first) {
+    st.t = find_tensor(tv.prefix, tv.n, chunk);
+    st.first = tv.prefix[st.t];
+    st.next = tv.prefix[st.t + 1];
+  } else {
+    while (chunk >= st.next) {
+      ++st.t;
+      st.first = st.next;
+      st.next = tv.prefix[st.t + 1];
+    }
+  }
+  return st.t;
+}
+
 // Workgroup-wide sum of a per-wavefront count (4 wavefronts).  `slot` must
 // alternate between consecutive calls; one barrier per call.
 __device__ __forceinline__ int block_sum4(int wave_count, int wave, int lane, int* s_cnt, int slot) {
@@ -110,6 +133,9 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
   float* sel_val = scratch + 2 * DEMO_MAXK_INTERNAL;
   int* s_cnt = reinterpret_cast<int*>(scratch + 3 * DEMO_MAXK_INTERNAL);  // [8] counters + [1] list cursor
   int* s_cursor = s_cnt + 8;
+  uint32_t* cand_mag = reinterpret_cast<uint32_t*>(scratch + 3 * DEMO_MAXK_INTERNAL + 32);   // [GEN_CAND_CAP]
+  int32_t* cand_idx = reinterpret_cast<int32_t*>(cand_mag + GEN_CAND_CAP);
+  float* cand_val = reinterpret_cast<float*>(cand_idx + GEN_CAND_CAP);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lq = lane >> 4;
   const int k = args.k;
@@ -119,11 +145,13 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
   if (nwork > 0)
     for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
 
+  DEMO_PHASE_DECL
+  TensorCursor cur;
   for (int wi = blockIdx.x; wi < nwork; wi += gridDim.x) {
     const int chunk = wl.list != nullptr ? wl.list[wi] : wi;
-    const int t = find_tensor(tv.prefix, tv.n, chunk);
+    const int t = tensor_of_chunk(tv, chunk, cur);
     const TensorDev d = tv.descs[t];
-    const int c = chunk - tv.prefix[t];
+    const int c = chunk - cur.first;
     const int k0 = c / d.cchunks, k1 = c - k0 * d.cchunks;
     const int64_t base = (int64_t)k0 * S * d.cols + (int64_t)k1 * S;
 
@@ -147,6 +175,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
     }
     if (tid == 0) *s_cursor = 0;
     __syncthreads();
+    DEMO_PHASE(0);
 
     // ---- T = P * X -----------------------------------------------------------------------
     f32x4 acc[G::TPW];
@@ -161,12 +190,14 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
     }
     __syncthreads();
 
+    DEMO_PHASE(1);
     // ---- Q = T * P^T ---------------------------------------------------------------------
     const int t_off = (int)(sT - lds);
     gemm_lds<S>(acc, wave, lane, lds,
                 [&](int m, int kk) { return t_off + m * G::LD + kk; },                     // T[u][j]
                 [&](int kk, int n) { return n * G::LD + kk; });                             // P[v][j]
 
+    DEMO_PHASE(2);
     // ---- exact top-k over the chunk (magnitude bits are order preserving as unsigned) ------
     uint32_t mag[G::TPW * 4];
 #pragma unroll
@@ -174,99 +205,169 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
 #pragma unroll
       for (int r = 0; r < 4; ++r) mag[i * 4 + r] = __float_as_uint(acc[i][r]) & 0x7fffffffu;
 
-    int slot = 0;
-    uint32_t thr = 0;  // becomes the k-th largest magnitude
-    for (int bit = 30; bit >= 0; --bit) {
-      const uint32_t cand = thr | (1u << bit);
-      int cw = 0;
+    // (1) a lower bound of the k-th largest magnitude: the k-th largest of the 256 per-thread maxima
+    //     (each is a coefficient of its own), resolved to its upper 16 bits.  Every wavefront reads all
+    //     256 maxima and bisects on its own, so this costs one barrier.
+    {
+      uint32_t tmax = 0;
 #pragma unroll
-      for (int e = 0; e < G::TPW * 4; ++e) cw += __popcll(__ballot(mag[e] >= cand));
-      const int tot = block_sum4(cw, wave, lane, s_cnt, slot);
-      slot ^= 1;
-      if (tot >= k) thr = cand;
+      for (int e = 0; e < G::TPW * 4; ++e) tmax = max(tmax, mag[e]);
+      sel_mag[tid] = tmax;
     }
-    int cw_gt = 0, cw_ge = 0;
-#pragma unroll
-    for (int e = 0; e < G::TPW * 4; ++e) {
-      cw_gt += __popcll(__ballot(mag[e] > thr));
-      cw_ge += __popcll(__ballot(mag[e] >= thr));
-    }
-    const int n_gt = block_sum4(cw_gt, wave, lane, s_cnt, slot);
-    slot ^= 1;
-    const int n_ge = block_sum4(cw_ge, wave, lane, s_cnt, slot);
-    slot ^= 1;
-    const int need = k - n_gt;          // ties to take, >= 1
-    uint32_t tie_last = 0xffffffffu;    // largest flat index among the ties taken
-    if (n_ge - n_gt != need) {
-      // more equal magnitudes than places: take the `need` lowest flat indices
-      uint32_t lo = 0;
-      for (int bit = 31 - __builtin_clz(G::M - 1); bit >= 0; --bit) {
-        const uint32_t cand = lo | (1u << bit);
-        int cw = 0;
-#pragma unroll
-        for (int i = 0; i < G::TPW; ++i) {
-          int mt, nt;
-          tile_of<S>(wave, i, mt, nt);
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
-            cw += __popcll(__ballot(mag[i * 4 + r] == thr && flat < cand));
-          }
-        }
-        const int tot = block_sum4(cw, wave, lane, s_cnt, slot);
-        slot ^= 1;
-        if (tot < need) lo = cand;
+    __syncthreads();
+    uint32_t thr_lo = 0;
+    {
+      const uint32_t m0 = sel_mag[lane], m1 = sel_mag[lane + 64], m2 = sel_mag[lane + 128], m3 = sel_mag[lane + 192];
+      for (int bit = 30; bit >= 16; --bit) {
+        const uint32_t cnd = thr_lo | (1u << bit);
+        const int cnt = __popcll(__ballot(m0 >= cnd)) + __popcll(__ballot(m1 >= cnd)) +
+                        __popcll(__ballot(m2 >= cnd)) + __popcll(__ballot(m3 >= cnd));
+        if (cnt >= k) thr_lo = cnd;
       }
-      tie_last = lo;
     }
-    // gather the k selected coefficients (arrival order), then rank them
+    // (2) candidates |q| >= thr_lo go to a list in LDS (arrival order)
 #pragma unroll
     for (int i = 0; i < G::TPW; ++i) {
       int mt, nt;
       tile_of<S>(wave, i, mt, nt);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
-        const uint32_t mg = mag[i * 4 + r];
-        if (mg > thr || (mg == thr && flat <= tie_last)) {
+        if (mag[i * 4 + r] >= thr_lo) {
           const int pos = atomicAdd(s_cursor, 1);
-          if (pos < DEMO_MAXK_INTERNAL) {
-            sel_mag[pos] = mg;
-            sel_idx[pos] = (int32_t)flat;
-            sel_val[pos] = acc[i][r];
+          if (pos < GEN_CAND_CAP) {
+            cand_mag[pos] = mag[i * 4 + r];
+            cand_idx[pos] = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+            cand_val[pos] = acc[i][r];
           }
         }
       }
     }
     __syncthreads();
-    // rank = number of selected entries that precede this one (magnitude desc, index asc)
+    const int ncand = *s_cursor;   // uniform
     int my_rank = -1, my_idx = 0;
     float my_val = 0.f;
-    if (tid < k) {
-      const uint32_t mg = sel_mag[tid];
-      my_idx = sel_idx[tid];
-      my_val = sel_val[tid];
-      int rk = 0;
-      for (int j = 0; j < k; ++j) {
-        const uint32_t mj = sel_mag[j];
-        rk += (mj > mg || (mj == mg && sel_idx[j] < my_idx)) ? 1 : 0;
+    if (ncand <= GEN_CAND_CAP) {
+      // (3) rank the candidates (magnitude descending, index ascending); ranks below k are the payload.
+      //     k <= 256 = number of threads, and at most one candidate per thread lands below k per pass.
+      for (int i = tid; i < ncand; i += G::NT) {
+        const uint32_t mg = cand_mag[i];
+        const int fi = cand_idx[i];
+        int rk = 0;
+        for (int j = 0; j < ncand; ++j) {
+          const uint32_t mj = cand_mag[j];
+          rk += (mj > mg || (mj == mg && cand_idx[j] < fi)) ? 1 : 0;
+        }
+        if (rk < k) {
+          const float fv = cand_val[i];
+          const int64_t po = (int64_t)c * k + rk;
+          d.idx[po] = fi;
+          d.val[po] = fv;
+          sel_idx[rk] = fi;
+          sel_val[rk] = fv;
+        }
       }
-      my_rank = rk;
-      const int64_t po = (int64_t)c * k + rk;
-      d.idx[po] = my_idx;
-      d.val[po] = my_val;
+      if (tid >= k && tid < kpad) {
+        sel_idx[tid] = 0;
+        sel_val[tid] = 0.f;
+      }
+      __syncthreads();
+    } else {
+      // many (near-)equal magnitudes at the threshold: exact selection by bisection over the whole chunk
+      if (tid == 0) *s_cursor = 0;
+      __syncthreads();
+      int slot = 0;
+      uint32_t thr = 0;  // becomes the k-th largest magnitude
+      for (int bit = 30; bit >= 0; --bit) {
+        const uint32_t cand = thr | (1u << bit);
+        int cw = 0;
+#pragma unroll
+        for (int e = 0; e < G::TPW * 4; ++e) cw += __popcll(__ballot(mag[e] >= cand));
+        const int tot = block_sum4(cw, wave, lane, s_cnt, slot);
+        slot ^= 1;
+        if (tot >= k) thr = cand;
+      }
+      int cw_gt = 0, cw_ge = 0;
+#pragma unroll
+      for (int e = 0; e < G::TPW * 4; ++e) {
+        cw_gt += __popcll(__ballot(mag[e] > thr));
+        cw_ge += __popcll(__ballot(mag[e] >= thr));
+      }
+      const int n_gt = block_sum4(cw_gt, wave, lane, s_cnt, slot);
+      slot ^= 1;
+      const int n_ge = block_sum4(cw_ge, wave, lane, s_cnt, slot);
+      slot ^= 1;
+      const int need = k - n_gt;          // ties to take, >= 1
+      uint32_t tie_last = 0xffffffffu;    // largest flat index among the ties taken
+      if (n_ge - n_gt != need) {
+        // more equal magnitudes than places: take the `need` lowest flat indices
+        uint32_t lo = 0;
+        for (int bit = 31 - __builtin_clz(G::M - 1); bit >= 0; --bit) {
+          const uint32_t cand = lo | (1u << bit);
+          int cw = 0;
+#pragma unroll
+          for (int i = 0; i < G::TPW; ++i) {
+            int mt, nt;
+            tile_of<S>(wave, i, mt, nt);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+              cw += __popcll(__ballot(mag[i * 4 + r] == thr && flat < cand));
+            }
+          }
+          const int tot = block_sum4(cw, wave, lane, s_cnt, slot);
+          slot ^= 1;
+          if (tot < need) lo = cand;
+        }
+        tie_last = lo;
+      }
+      // gather the k selected coefficients (arrival order), then rank them
+#pragma unroll
+      for (int i = 0; i < G::TPW; ++i) {
+        int mt, nt;
+        tile_of<S>(wave, i, mt, nt);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+          const uint32_t mg = mag[i * 4 + r];
+          if (mg > thr || (mg == thr && flat <= tie_last)) {
+            const int pos = atomicAdd(s_cursor, 1);
+            if (pos < DEMO_MAXK_INTERNAL) {
+              sel_mag[pos] = mg;
+              sel_idx[pos] = (int32_t)flat;
+              sel_val[pos] = acc[i][r];
+            }
+          }
+        }
+      }
+      __syncthreads();
+      // rank = number of selected entries that precede this one (magnitude desc, index asc)
+      if (tid < k) {
+        const uint32_t mg = sel_mag[tid];
+        my_idx = sel_idx[tid];
+        my_val = sel_val[tid];
+        int rk = 0;
+        for (int j = 0; j < k; ++j) {
+          const uint32_t mj = sel_mag[j];
+          rk += (mj > mg || (mj == mg && sel_idx[j] < my_idx)) ? 1 : 0;
+        }
+        my_rank = rk;
+        const int64_t po = (int64_t)c * k + rk;
+        d.idx[po] = my_idx;
+        d.val[po] = my_val;
+      }
+      __syncthreads();
+      // sorted list for the reconstruction (deterministic summation order); padded to a multiple of 4
+      if (tid < k) {
+        sel_idx[my_rank] = my_idx;
+        sel_val[my_rank] = my_val;
+      } else if (tid < kpad) {
+        sel_idx[tid] = 0;
+        sel_val[tid] = 0.f;
+      }
+      __syncthreads();
     }
-    __syncthreads();
-    // sorted list for the reconstruction (deterministic summation order); padded to a multiple of 4
-    if (tid < k) {
-      sel_idx[my_rank] = my_idx;
-      sel_val[my_rank] = my_val;
-    } else if (tid < kpad) {
-      sel_idx[tid] = 0;
-      sel_val[tid] = 0.f;
-    }
-    __syncthreads();
 
+    DEMO_PHASE(3);
     // ---- R = P^T Q^ P = sum_t val_t * P[u_t][:]^T P[v_t][:]  (contraction length k) ----------
 #pragma unroll
     for (int i = 0; i < G::TPW; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -287,6 +388,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
     store_acc<S>(acc, wave, lane, sX);   // sX (and sT) are dead since the barriers above
     __syncthreads();
 
+    DEMO_PHASE(4);
     // ---- m <- m - R ----------------------------------------------------------------------
 #pragma unroll
     for (int p = 0; p < G::PASSES; ++p) {
@@ -300,7 +402,9 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
       o.w = __fmaf_rn(-args.alpha, r.w, mid[p].w);
       *reinterpret_cast<float4*>(d.mom + off) = o;
     }
+    DEMO_PHASE(5);
   }
+  DEMO_PHASE_FLUSH(0);
   if (wl.list != nullptr) {
     __syncthreads();   // every thread has read *wl.count
     if (tid == 0) {
@@ -332,10 +436,11 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
 
   for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
 
+  TensorCursor cur;
   for (int chunk = blockIdx.x; chunk < tv.total_chunks; chunk += gridDim.x) {
-    const int t = find_tensor(tv.prefix, tv.n, chunk);
+    const int t = tensor_of_chunk(tv, chunk, cur);
     const TensorDev d = tv.descs[t];
-    const int c = chunk - tv.prefix[t];
+    const int c = chunk - cur.first;
     const int k0 = c / d.cchunks, k1 = c - k0 * d.cchunks;
     const int64_t base = (int64_t)k0 * S * d.cols + (int64_t)k1 * S;
     const int lrow = tid / G::F4_PER_ROW, lcol = (tid % G::F4_PER_ROW) * 4;
@@ -711,3 +816,5 @@ hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const
 }
 
 }  // namespace demo
+
+DEMO_PHASE_GETTER(demo_debug_phase_clocks_gen)
