@@ -32,7 +32,7 @@ struct Geo {
   static constexpr int M = S * S;
   static constexpr int TILE_FLOATS = S * LD;
   // LDS: basis, data tile, (second tile when not in place), selection scratch
-  static constexpr int LDS_FLOATS = TILE_FLOATS * (INPLACE ? 2 : 3) + 3 * DEMO_MAXK_INTERNAL + 32 + 3 * GEN_CAND_CAP;
+  static constexpr int LDS_FLOATS = TILE_FLOATS * (INPLACE ? 2 : 3) + 3 * DEMO_MAXK_INTERNAL + 32 + 3 * GEN_CAND_CAP + 16;
 };
 
 // tile i of wavefront w -> (mt, nt)
@@ -133,9 +133,8 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
   float* sel_val = scratch + 2 * DEMO_MAXK_INTERNAL;
   int* s_cnt = reinterpret_cast<int*>(scratch + 3 * DEMO_MAXK_INTERNAL);  // [8] counters + [1] list cursor
   int* s_cursor = s_cnt + 8;
-  uint32_t* cand_mag = reinterpret_cast<uint32_t*>(scratch + 3 * DEMO_MAXK_INTERNAL + 32);   // [GEN_CAND_CAP]
-  int32_t* cand_idx = reinterpret_cast<int32_t*>(cand_mag + GEN_CAND_CAP);
-  float* cand_val = reinterpret_cast<float*>(cand_idx + GEN_CAND_CAP);
+  uint2* cand_key = reinterpret_cast<uint2*>(scratch + 3 * DEMO_MAXK_INTERNAL + 32);   // [GEN_CAND_CAP + 8], 16-byte aligned
+  float* cand_val = reinterpret_cast<float*>(cand_key + GEN_CAND_CAP + 8);              // [GEN_CAND_CAP]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, lq = lane >> 4;
   const int k = args.k;
@@ -159,19 +158,39 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
     float4 mid[G::PASSES];
     const int lrow = tid / G::F4_PER_ROW, lcol = (tid % G::F4_PER_ROW) * 4;
     __syncthreads();  // previous chunk's readers of sX are done
+    // all loads of the chunk are issued before the first use (one dtype branch per chunk, not per load)
+    {
+      float4 mv[G::PASSES], gv[G::PASSES];
 #pragma unroll
-    for (int p = 0; p < G::PASSES; ++p) {
-      const int row = p * G::ROWS_PER_PASS + lrow;
-      const int64_t off = base + (int64_t)row * d.cols + lcol;
-      float4 g = load4(d.grad, off, d.grad_bf16);
-      float4 m = *reinterpret_cast<const float4*>(d.mom + off);
-      float4 v;
-      v.x = __fmaf_rn(args.beta, m.x, args.grad_scale * g.x);
-      v.y = __fmaf_rn(args.beta, m.y, args.grad_scale * g.y);
-      v.z = __fmaf_rn(args.beta, m.z, args.grad_scale * g.z);
-      v.w = __fmaf_rn(args.beta, m.w, args.grad_scale * g.w);
-      mid[p] = v;
-      *reinterpret_cast<float4*>(&sX[row * G::LD + lcol]) = v;
+      for (int p = 0; p < G::PASSES; ++p)
+        mv[p] = *reinterpret_cast<const float4*>(d.mom + base + (int64_t)(p * G::ROWS_PER_PASS + lrow) * d.cols + lcol);
+      if (d.grad_bf16) {
+        uint2 gh[G::PASSES];
+#pragma unroll
+        for (int p = 0; p < G::PASSES; ++p)
+          gh[p] = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(d.grad) + base +
+                                                  (int64_t)(p * G::ROWS_PER_PASS + lrow) * d.cols + lcol);
+#pragma unroll
+        for (int p = 0; p < G::PASSES; ++p)
+          gv[p] = make_float4(bf16_to_f32(gh[p].x & 0xffffu), bf16_to_f32(gh[p].x >> 16), bf16_to_f32(gh[p].y & 0xffffu),
+                              bf16_to_f32(gh[p].y >> 16));
+      } else {
+#pragma unroll
+        for (int p = 0; p < G::PASSES; ++p)
+          gv[p] = *reinterpret_cast<const float4*>(static_cast<const float*>(d.grad) + base +
+                                                   (int64_t)(p * G::ROWS_PER_PASS + lrow) * d.cols + lcol);
+      }
+#pragma unroll
+      for (int p = 0; p < G::PASSES; ++p) {
+        const int row = p * G::ROWS_PER_PASS + lrow;
+        float4 v;
+        v.x = __fmaf_rn(args.beta, mv[p].x, args.grad_scale * gv[p].x);
+        v.y = __fmaf_rn(args.beta, mv[p].y, args.grad_scale * gv[p].y);
+        v.z = __fmaf_rn(args.beta, mv[p].z, args.grad_scale * gv[p].z);
+        v.w = __fmaf_rn(args.beta, mv[p].w, args.grad_scale * gv[p].w);
+        mid[p] = v;
+        *reinterpret_cast<float4*>(&sX[row * G::LD + lcol]) = v;
+      }
     }
     if (tid == 0) *s_cursor = 0;
     __syncthreads();
@@ -225,7 +244,8 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
         if (cnt >= k) thr_lo = cnd;
       }
     }
-    // (2) candidates |q| >= thr_lo go to a list in LDS (arrival order)
+    // (2) candidates |q| >= thr_lo go to a list in LDS (arrival order); key = {~flat index, magnitude} so
+    //     that a larger 64-bit key precedes (magnitude descending, then index ascending)
 #pragma unroll
     for (int i = 0; i < G::TPW; ++i) {
       int mt, nt;
@@ -235,8 +255,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
         if (mag[i * 4 + r] >= thr_lo) {
           const int pos = atomicAdd(s_cursor, 1);
           if (pos < GEN_CAND_CAP) {
-            cand_mag[pos] = mag[i * 4 + r];
-            cand_idx[pos] = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+            cand_key[pos] = make_uint2(~(uint32_t)((16 * mt + 4 * lq + r) * S + 16 * nt + l16), mag[i * 4 + r]);
             cand_val[pos] = acc[i][r];
           }
         }
@@ -247,18 +266,28 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
     int my_rank = -1, my_idx = 0;
     float my_val = 0.f;
     if (ncand <= GEN_CAND_CAP) {
-      // (3) rank the candidates (magnitude descending, index ascending); ranks below k are the payload.
-      //     k <= 256 = number of threads, and at most one candidate per thread lands below k per pass.
+      // (3) rank the candidates; ranks below k are the payload.  The list is padded with zero keys (which
+      //     precede nothing) to a multiple of 8 so that the reads of a trip are issued together.
+      const int npad = (ncand + 7) & ~7;
+      if (tid < npad - ncand) cand_key[ncand + tid] = make_uint2(0u, 0u);
+      __syncthreads();
       for (int i = tid; i < ncand; i += G::NT) {
-        const uint32_t mg = cand_mag[i];
-        const int fi = cand_idx[i];
+        const uint2 me = cand_key[i];
+        const uint64_t key = ((uint64_t)me.y << 32) | me.x;
         int rk = 0;
-        for (int j = 0; j < ncand; ++j) {
-          const uint32_t mj = cand_mag[j];
-          rk += (mj > mg || (mj == mg && cand_idx[j] < fi)) ? 1 : 0;
+        for (int j = 0; j < npad; j += 8) {
+          uint4 o[4];
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) o[jj] = *reinterpret_cast<const uint4*>(&cand_key[j + 2 * jj]);
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            rk += ((((uint64_t)o[jj].y << 32) | o[jj].x) > key) ? 1 : 0;
+            rk += ((((uint64_t)o[jj].w << 32) | o[jj].z) > key) ? 1 : 0;
+          }
         }
         if (rk < k) {
           const float fv = cand_val[i];
+          const int fi = (int)~me.x;
           const int64_t po = (int64_t)c * k + rk;
           d.idx[po] = fi;
           d.val[po] = fv;
@@ -445,6 +474,24 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
     const int64_t base = (int64_t)k0 * S * d.cols + (int64_t)k1 * S;
     const int lrow = tid / G::F4_PER_ROW, lcol = (tid % G::F4_PER_ROW) * 4;
 
+    // parameters of the chunk: requested now, used after the products (one dtype branch per chunk)
+    float4 xv[G::PASSES];
+    if (d.param_bf16) {
+      uint2 xh[G::PASSES];
+#pragma unroll
+      for (int p = 0; p < G::PASSES; ++p)
+        xh[p] = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(d.param) + base +
+                                                (int64_t)(p * G::ROWS_PER_PASS + lrow) * d.cols + lcol);
+#pragma unroll
+      for (int p = 0; p < G::PASSES; ++p)
+        xv[p] = make_float4(bf16_to_f32(xh[p].x & 0xffffu), bf16_to_f32(xh[p].x >> 16), bf16_to_f32(xh[p].y & 0xffffu),
+                            bf16_to_f32(xh[p].y >> 16));
+    } else {
+#pragma unroll
+      for (int p = 0; p < G::PASSES; ++p)
+        xv[p] = *reinterpret_cast<const float4*>(static_cast<const float*>(d.param) + base +
+                                                 (int64_t)(p * G::ROWS_PER_PASS + lrow) * d.cols + lcol);
+    }
     __syncthreads();
     for (int e = tid; e < S * G::LD; e += G::NT) sX[e] = 0.f;
     if (by_count)
@@ -528,14 +575,20 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
 #pragma unroll
     for (int p = 0; p < G::PASSES; ++p) {
       const int row = p * G::ROWS_PER_PASS + lrow;
-      const int64_t off = base + (int64_t)row * d.cols + lcol;
       const float4 sg = *reinterpret_cast<const float4*>(&sX[row * G::LD + lcol]);
-      float4 x = load4(d.param, off, d.param_bf16);
-      x.x = sign_update(x.x, sg.x, args.lr, args.weight_decay);
-      x.y = sign_update(x.y, sg.y, args.lr, args.weight_decay);
-      x.z = sign_update(x.z, sg.z, args.lr, args.weight_decay);
-      x.w = sign_update(x.w, sg.w, args.lr, args.weight_decay);
-      store4(d.param, off, d.param_bf16, x);
+      xv[p].x = sign_update(xv[p].x, sg.x, args.lr, args.weight_decay);
+      xv[p].y = sign_update(xv[p].y, sg.y, args.lr, args.weight_decay);
+      xv[p].z = sign_update(xv[p].z, sg.z, args.lr, args.weight_decay);
+      xv[p].w = sign_update(xv[p].w, sg.w, args.lr, args.weight_decay);
+    }
+    if (d.param_bf16) {
+#pragma unroll
+      for (int p = 0; p < G::PASSES; ++p)
+        store4(d.param, base + (int64_t)(p * G::ROWS_PER_PASS + lrow) * d.cols + lcol, 1, xv[p]);
+    } else {
+#pragma unroll
+      for (int p = 0; p < G::PASSES; ++p)
+        store4(d.param, base + (int64_t)(p * G::ROWS_PER_PASS + lrow) * d.cols + lcol, 0, xv[p]);
     }
   }
 }
