@@ -23,6 +23,7 @@ struct BasisTable {
   float* enc64 = nullptr;    // tables of the s = 64 wavefront-per-chunk kernels
   float* dec64 = nullptr;
   float* enc32 = nullptr;    // dense-basis tile tables for s = 32
+  float* dec32 = nullptr;    // fragment table of the s = 32 tile decode kernel
   float* custom = nullptr;   // s x s matrix set with demo_set_basis (identity / Gram-Schmidt), allocated on first use
   bool use_custom = false;   // later calls project with `custom` on the generic kernels
 };
@@ -140,8 +141,8 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     if (b.s == s) {
       // the wavefront kernels are built on the symmetries of the DCT: any other matrix runs on the
       // kernels that read the matrix itself
-      *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr}
-                          : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32};
+      *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr}
+                          : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32};
       return DEMO_OK;
     }
   std::vector<double> P((size_t)s * s);
@@ -171,9 +172,12 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     std::vector<float> et(demo::kEnc64dTableFloats);
     demo::build_enc64d_tables(B2.data(), et.data());
     if ((rc = upload(ctx, et, &b.enc32)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
+    std::vector<float> dt(demo::kDec32TableFloats);
+    demo::build_dec32_tables(P.data(), dt.data());
+    if ((rc = upload(ctx, dt, &b.dec32)) != DEMO_OK) { (void)hipFree(b.dev); (void)hipFree(b.enc32); return rc; }
   }
   ctx->bases.push_back(b);
-  *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32};
+  *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32};
   return DEMO_OK;
 }
 
@@ -341,7 +345,8 @@ int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, in
   int rc;
   if (tc->tv2.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 2, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_decode2d(tc->tv2, basis, s, a, ctx->num_cus, ctx->variant, st);
+    hipError_t e = demo::launch_decode2d(tc->tv2, tc->tv2t.n > 0 ? &tc->tv2t : nullptr, basis, s, a, ctx->num_cus,
+                                         ctx->variant, st);
     if (e != hipSuccess) return fail_hip(ctx, e);
     if ((rc = timer_end(ctx, 2, st)) != DEMO_OK) return rc;
   }
@@ -398,6 +403,7 @@ int demo_destroy(demo_ctx* ctx) {
       if (b.enc64) (void)hipFree(b.enc64);
       if (b.dec64) (void)hipFree(b.dec64);
       if (b.enc32) (void)hipFree(b.enc32);
+      if (b.dec32) (void)hipFree(b.dec32);
       if (b.custom) (void)hipFree(b.custom);
     }
     for (TableCache& tc : ctx->tables)

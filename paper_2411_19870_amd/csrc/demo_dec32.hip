@@ -1,0 +1,308 @@
+// s = 32 decode kernel: one wavefront per 64 x 64 tile = 2 x 2 chunks.
+//
+// The tile is transformed with the block-diagonal matrix diag(P32, P32), so chunk (a, b) of the tile is
+// R_ab = P32^T S_ab P32 and the four chunks never mix.  The structure is that of the s = 64 kernel
+// (demo_dec64.hip) with the mirror symmetry of the 32-point DCT in place of the two nested ones of the
+// 64-point DCT: even rows of P32 are even under i -> 31-i, odd rows odd, so for the quadruple
+// {i0, 31-i0, 32+i0, 63-i0} (i0 < 16: one mirror pair in each block) four partial sums
+//   E_a = sum over even u of block a,  O_a = sum over odd u of block a      (16 frequencies each)
+// give  out[i0] = E_0+O_0, out[31-i0] = E_0-O_0, out[32+i0] = E_1+O_1, out[63-i0] = E_1-O_1.
+// Both products therefore cost 64 MFMAs per tile (a quarter of the dense 64 x 64 products), the tile of
+// coefficient sums is stored with rows and columns grouped by class (block, parity), lane l = 16 g + c ends
+// up with rows member(w, 4s + g) and columns member(w', kappa(c)), and R goes once through the LDS tile
+// into the row layout in which the parameters are read and written (see demo_dec64.hip).
+//
+// Payload: the W*k <= 512 pairs of each of the four chunks sit in 8 registers per lane and chunk (pair
+// p = 64 j + lane of the chunk belongs to worker p / k, position p % k) and are fetched for the next tile
+// while the products of this one run.  Each chunk has its own fixed-point scale.
+#include "demo_device.h"
+
+namespace demo {
+
+namespace {
+constexpr int D32_WAVES = 8;
+constexpr int D32_THREADS = D32_WAVES * 64;
+constexpr int D32_LDT = 68;                        // tile row stride (floats); columns 64..67 are pad slots
+constexpr int D32_TILE_FLOATS = 64 * D32_LDT;
+constexpr int D32_G_FLOATS = 512;                  // fragment table: 2 parities x 64 lanes x 4
+constexpr int D32_LDS_BYTES = 4 * (D32_G_FLOATS + D32_WAVES * D32_TILE_FLOATS);
+constexpr int D32_SLOTS = 8;                       // payload registers per lane and chunk
+static_assert(D32_G_FLOATS == kDec32TableFloats, "table size");
+static_assert(D32_LDS_BYTES <= 160 * 1024, "LDS budget");
+static_assert(kFast32MaxPairs == 64 * D32_SLOTS, "pairs per chunk held in registers");
+
+__host__ __device__ constexpr int kappa32(int c) { return 4 * (c & 3) + (c >> 2); }
+}  // namespace
+
+// Host: fragment table from the 32 x 32 basis P32 (double, row-major).  Lane (g, c), component r of
+// group p holds P32[2 (4g + r) + p][kappa(c)]: the contraction index of k-slot g at step r is the
+// (4g + r)-th frequency of parity p, the other index the quadruple base kappa(c).
+void build_dec32_tables(const double* P32, float* out) {
+  for (int p = 0; p < 2; ++p)
+    for (int lane = 0; lane < 64; ++lane) {
+      const int g = lane >> 4, c = lane & 15;
+      for (int r = 0; r < 4; ++r) out[(p * 64 + lane) * 4 + r] = (float)P32[(2 * (4 * g + r) + p) * 32 + kappa32(c)];
+    }
+}
+
+// The table `tv` lists the order-2 tensors in units of 64 x 64 tiles (cchunks = cols / 64, nchunks =
+// tiles); payload arrays are addressed per 32 x 32 chunk (4 * nchunks chunks per tensor).
+template <bool PBF16>
+__global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, const float* __restrict__ tables,
+                                                               DecodeArgs args) {
+  extern __shared__ float lds[];
+  const float* sG = lds;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4, c = lane & 15;
+  float* tile = lds + D32_G_FLOATS + wave * D32_TILE_FLOATS;
+  int* itile = reinterpret_cast<int*>(tile);
+  const int k = args.k, W = args.W;
+  const int npairs = W * k;                                   // per chunk, <= 512
+  const int nslots = (npairs + 63) >> 6;                      // payload registers in use per chunk (uniform)
+
+  for (int e = tid; e < D32_G_FLOATS / 4; e += D32_THREADS)
+    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
+  __syncthreads();
+
+  const int nwaves = gridDim.x * D32_WAVES;
+  const int total = tv.total_chunks;
+  int tileno = blockIdx.x * D32_WAVES + wave;                 // wavefront w takes tiles w, w + nwaves, ...
+  if (tileno >= total) return;
+
+  // ---- payload: slot 8 q + j holds pair 64 j + lane of chunk q = 2 bu + bv of the tile -------------------
+  int32_t pi[4 * D32_SLOTS];
+  float pv[4 * D32_SLOTS];
+#pragma unroll
+  for (int j = 0; j < 4 * D32_SLOTS; ++j) {
+    pi[j] = -1;
+    pv[j] = 0.f;
+  }
+  const float rk = 1.0f / (float)k;
+  auto load_payload = [&](const TensorDev& dd, int tt) {
+    const int K0 = tt / dd.cchunks, K1 = tt - K0 * dd.cchunks;
+    const int cch32 = 2 * dd.cchunks;
+    const int64_t wstride = (int64_t)dd.nchunks * 4 * k;      // pairs of one worker for this tensor
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int c32 = (2 * K0 + (q >> 1)) * cch32 + 2 * K1 + (q & 1);
+      const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)c32 * k;
+      const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)c32 * k;
+#pragma unroll
+      for (int j = 0; j < D32_SLOTS; ++j) {
+        if (j < nslots) {                                     // uniform
+          const int p = 64 * j + lane;
+          // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far
+          // more than the rounding error of the float product for p < 512
+          const int w = (int)(((float)p + 0.5f) * rk);
+          const int pos = p - w * k;
+          const bool ok = p < npairs;
+          const uint32_t off = (uint32_t)(w * (int)wstride + pos);
+          pi[D32_SLOTS * q + j] = ok ? ip[off] : -1;
+          pv[D32_SLOTS * q + j] = ok ? vp[off] : 0.f;
+        }
+      }
+    }
+  };
+
+  // S[idx] += val in block fixed point with integer LDS atomics, one scale per chunk (see demo_dec64.hip).
+  // Coefficient (u, v) of chunk (a, b) lives at tile row 32 a + 16 (u % 2) + u / 2, column
+  // 32 b + 16 (v % 2) + v / 2.  Lanes with nothing to add put a zero-weight value into their pad slot.
+  const uint32_t dummy = (uint32_t)(lane * D32_LDT + 64);
+  int vbits = 30;
+  for (int w = 1; w < W; w <<= 1) --vbits;                    // 30 - ceil(log2 W)
+  auto scatter = [&]() {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float mx = 0.f;
+#pragma unroll
+      for (int j = 0; j < D32_SLOTS; ++j)
+        if (j < nslots) mx = fmaxf(mx, fabsf(pv[D32_SLOTS * q + j]));
+      uint32_t mb = __float_as_uint(mx);
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x141, 0xf, 0xf, false));  // row_half_mirror
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
+      const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
+      const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
+      int ex = (int)(max(m01, m23) >> 23);                    // biased exponent of the chunk's largest magnitude
+      ex = ex < 1 ? 1 : ex;
+      const int sh = vbits + 126 - ex;                        // max |val| * 2^sh < 2^vbits
+      const uint32_t quad = (uint32_t)(((q >> 1) << 11) | ((q & 1) << 5));
+#pragma unroll
+      for (int j = 0; j < D32_SLOTS; ++j) {
+        if (j < nslots) {
+          const uint32_t u = (uint32_t)pi[D32_SLOTS * q + j];
+          // 10-bit index [u4..u0 v4..v0] -> 12-bit [a u0 u4..u1 | b v0 v4..v1], then row stride 64 -> LDT
+          const uint32_t x = quad | (u & 0x3C0u) | ((u & 0x20u) << 5) | ((u & 1u) << 4) | ((u >> 1) & 0xFu);
+          const uint32_t a = u < 1024u ? x + ((x >> 6) << 2) : dummy;
+          atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[D32_SLOTS * q + j], sh)));
+        }
+      }
+    }
+  };
+
+  int t = find_tensor_uniform(tv, tileno);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
+  load_payload(d, tileno - t_first);
+  const int kap = kappa32(c), col4 = 4 * chi(c);
+  // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
+  // for members w' even / odd (w' >= 2 adds 32 columns)
+  const int row_up = 4 * g * D32_LDT, row_dn = 4 * (3 - g) * D32_LDT;
+  const int wr_col_up = kap, wr_col_dn = 31 - kap;
+
+  for (; tileno < total; tileno += nwaves) {
+    const int tt = tileno - t_first;
+    const int k0 = tt / d.cchunks, k1 = tt - k0 * d.cchunks;
+    const int64_t origin = (int64_t)k0 * 64 * d.cols + (int64_t)k1 * 64;   // uniform
+    const uint32_t ucols = (uint32_t)d.cols;
+    // parameters: lane (g, c) reads / writes rows rho(q, g), columns 4 chi(c) .. +3 (whole rows per instruction)
+    const uint32_t vo_up = (uint32_t)g * ucols + (uint32_t)col4;           // elements
+    const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
+    const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
+                                              : make_rsrc(static_cast<const float*>(d.param) + origin);
+    u32x2 Xh[16];   // bf16 parameters, raw: requested before the scatter, used after the products
+    if (PBF16) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
+    }
+
+    // ---- S = sum over workers, four chunks ----------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
+    wave_lds_sync();
+    scatter();
+    // ---- payload of the next tile, in flight during the products (after the last tile the same tile is
+    //      requested again: an unconditional fetch keeps the old registers dead) -----------------------------
+    if (tileno + nwaves < total) {
+      while (tileno + nwaves >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
+      }
+      load_payload(d, tileno + nwaves - t_first);
+    } else {
+      load_payload(d, tt);
+    }
+    wave_lds_sync();
+
+    // ---- products -----------------------------------------------------------------------------------------
+    float4 G[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) G[i] = *reinterpret_cast<const float4*>(&sG[(i * 64 + lane) * 4]);
+    auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
+    f32x4 C[4][4];   // [row class 2a + parity][w'], component s: quadruple base i0 = 4s + g
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) C[rt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+      // product a for the 16 rows of class rt (physical rows 16 rt + m); k-block kg is column class kg
+      const float* arow = &tile[(16 * rt + c) * D32_LDT + 4 * g];
+      float4 a[4];
+#pragma unroll
+      for (int kg = 0; kg < 4; ++kg) a[kg] = *reinterpret_cast<const float4*>(arow + 16 * kg);
+      f32x4 P[4];   // E_0, O_0, E_1, O_1
+#pragma unroll
+      for (int kg = 0; kg < 4; ++kg) P[kg] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kr = 0; kr < 4; ++kr)
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg)   // the tile holds fixed-point sums
+          P[kg] = mfma4((float)__float_as_int(comp(a[kg], kr)), comp(G[kg & 1], kr), P[kg]);
+      // columns member(w', kappa(c)) of Y
+      const f32x4 Y[4] = {P[0] + P[1], P[0] - P[1], P[2] + P[3], P[2] - P[3]};
+      // product b: this row class feeds its own partial sum
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) C[rt][e] = mfma4(comp(G[rt & 1], r), Y[e][r], C[rt][e]);
+    }
+
+    // ---- R (pair identities) goes through the tile, which is dead by now, into the layout of the
+    //      parameters.  Row i is kept at tile row rperm(i) = 16 (i / 16) + 4 (i % 4) + (i / 4) % 4.
+    //      For i = member(w, 4s + g):  rperm = 16 w + 4 g + s (w even),  16 w + 4 (3 - g) + (3 - s) (w odd).
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float* wcol = tile + ((e & 1) ? wr_col_dn : wr_col_up) + (e >= 2 ? 32 : 0);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const float rr[4] = {C[0][e][s] + C[1][e][s], C[0][e][s] - C[1][e][s], C[2][e][s] + C[3][e][s],
+                             C[2][e][s] - C[3][e][s]};
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          wcol[((w & 1) ? row_dn : row_up) + (16 * w + ((w & 1) ? 3 - s : s)) * D32_LDT] = rr[w];
+      }
+    }
+    wave_lds_sync();
+
+    // ---- x <- x - lr*(sgn(R) + wd*x) ------------------------------------------------------------------------
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      f32x4 xin[4];   // fp32 parameters of the four rows of this quadruple
+      if (!PBF16) {
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          xin[w] = bload_f4(xres, ((w & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(4 * s + w) * ucols * 4);
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int q = 4 * s + w;
+        const float4 rv = *reinterpret_cast<const float4*>(
+            &tile[((w & 1) ? row_dn : row_up) + (16 * w + ((w & 1) ? 3 - s : s)) * D32_LDT + col4]);
+        const float rr[4] = {rv.x, rv.y, rv.z, rv.w};
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float x;
+          if (PBF16) {
+            const uint32_t raw = Xh[q][e >> 1];
+            x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+          } else {
+            x = xin[w][e];
+          }
+          o[e] = sign_update(x, sgnf(rr[e]), args.lr, args.weight_decay);
+        }
+        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
+        if (PBF16) {
+          const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+          bstore_u2(xres, vo * 2, so * 2, pk);
+        } else {
+          const f32x4 ov = {o[0], o[1], o[2], o[3]};
+          bstore_f4(xres, vo * 4, so * 4, ov);
+        }
+      }
+    }
+    wave_lds_sync();
+  }
+}
+
+template <bool PBF16>
+static hipError_t launch_dec_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
+                                    hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, D32_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(decode2d_tile32<PBF16>, dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES, stream, tiles,
+                     tables, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,
+                                  int num_cus, hipStream_t stream) {
+  if (a.W * a.k > kFast32MaxPairs || a.W < 1) return hipErrorInvalidValue;   // the registers hold 512 pairs per chunk
+  int64_t grid = num_cus;
+  const int64_t max_grid = ((int64_t)tiles.total_chunks + D32_WAVES - 1) / D32_WAVES;
+  if (grid > max_grid) grid = max_grid;
+  return param_bf16 ? launch_dec_tile32<true>(tiles, tables, a, grid, stream)
+                    : launch_dec_tile32<false>(tiles, tables, a, grid, stream);
+}
+
+}  // namespace demo

@@ -68,6 +68,7 @@ struct BasisTables {
   const float* enc64;    // fragment tables of the wavefront-per-chunk encode kernel (s = 64 only, else null)
   const float* dec64;    // tables of the wavefront-per-chunk decode kernel (s = 64 only, else null)
   const float* enc32;    // dense-basis tile tables for diag(P32, P32) (s = 32 only, else null)
+  const float* dec32;    // fragment table of the wavefront-per-tile decode kernel (s = 32 only, else null)
 };
 
 // Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:
@@ -78,8 +79,8 @@ hipError_t launch_encode2d(const TableView& tv, const TableView* tiles, const Ba
                            const EncodeArgs& a, const Worklist& wl, int num_cus, int variant, hipStream_t stream);
 hipError_t launch_encode1d(const TableView& tv, const float* basis, int s, const EncodeArgs& a,
                            hipStream_t stream);
-hipError_t launch_decode2d(const TableView& tv, const BasisTables& bt, int s, const DecodeArgs& a,
-                           int num_cus, int variant, hipStream_t stream);
+hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const BasisTables& bt, int s,
+                           const DecodeArgs& a, int num_cus, int variant, hipStream_t stream);
 hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
                            hipStream_t stream);
 
@@ -100,6 +101,13 @@ hipError_t launch_encode2d_tile32(const TableView& tiles, const int32_t* prefix3
                                   const EncodeArgs& a, const Worklist& wl, bool grad_bf16, int num_cus,
                                   hipStream_t stream);
 // The decode kernel keeps all W workers' pairs of a chunk in registers: W <= 64 when k <= 32, W <= 32 above.
+// s = 32 decode, one wavefront per 64 x 64 tile (2 x 2 chunks): the registers hold W*k <= 512 pairs per chunk
+constexpr int kDec32TableFloats = 512;
+constexpr int kFast32MaxPairs = 512;
+void build_dec32_tables(const double* P32, float* out /* kDec32TableFloats */);
+hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,
+                                  int num_cus, hipStream_t stream);
+
 inline bool fast64_decode_supports(int W, int k) { return k <= kFast64MaxK && W <= (k <= 32 ? 64 : 32); }
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream);

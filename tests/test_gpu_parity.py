@@ -254,3 +254,36 @@ def test_timing_hooks(ctx):
     for which in range(4):
         assert ctx.demo_last_kernel_ms(which) > 0
     ctx.demo_set_timing(False)
+
+
+# ---- s = 32 decode: wavefront-per-tile kernel (tile-aligned shapes, W*k <= 512) and the fallback ---------------
+@pytest.mark.parametrize("W,k", [(16, 32), (1, 32), (5, 7), (64, 8), (3, 1), (8, 32), (17, 32)])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+def test_s32_decode_tile_kernel(ctx, W, k, pdt):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 192, 320), synth.TensorSpec("b", 64, 64), synth.TensorSpec("v", 96, 0),
+             synth.TensorSpec("c", 128, 1088)]
+    case = Case(specs, 32, k, W=W, param_dtype=pdt, seed=100 + W)
+    case.fill_payloads()
+    st = run_decode_check(ctx, case, W=W, wd=0.01)
+    assert sum(x["elements"] for x in st) == sum(sp.numel for sp in specs)
+
+
+def test_s32_decode_chunks_with_very_different_scales(ctx):
+    # the four chunks of a tile keep separate fixed-point scales: one chunk's payload is 1e12 times larger
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 128, 128)]
+    W, k = 4, 16
+    case = Case(specs, 32, k, W=W, seed=7)
+    case.fill_payloads()
+    case.val[0][:, 5, :] *= 1e12        # chunk 5 = tile (0, 0)... of the 4 x 4 chunk grid: row 1, column 1
+    case.val[0][:, 6, :] *= 1e-12
+    run_decode_check(ctx, case, W=W)
+
+
+def test_s32_decode_unaligned_shape_takes_the_generic_kernel(ctx):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 96, 160)]
+    case = Case(specs, 32, 8, W=4, seed=9)
+    case.fill_payloads()
+    run_decode_check(ctx, case, W=4)
