@@ -90,3 +90,50 @@ def test_full_size_encode_then_decode(big):
         st = C.check_decode(pre_x[(ti, c)], idx, val, LR, 0.0, S, "bf16", block(tensors[ti].param, sp, c).astype(np.float32))
         in_band += st["in_band"]
     print(f"decode: {len(picks)} sampled chunks, parameters inside the sign-noise band: {in_band}")
+
+
+# ---- stress sweep at full size: heavy-tailed bf16 gradients (exact magnitude ties), momentum carried over
+#      10 steps of encode + decode of the worker's own payload, sampled chunks checked every step ---------------
+def _block(t: torch.Tensor, sp, c: int, s: int) -> np.ndarray:
+    if sp.cols == 0:
+        return t[c * s:(c + 1) * s].to("cpu", torch.float64).numpy()
+    k0, k1 = divmod(c, sp.cols // s)
+    return t[k0 * s:(k0 + 1) * s, k1 * s:(k1 + 1) * s].to("cpu", torch.float64).numpy()
+
+
+@pytest.mark.parametrize("s,k", [(32, 8), (128, 32), (64, 1)])
+def test_full_size_ten_carried_steps(s, k):
+    specs = synth.tensor_set("1b")
+    tensors = []
+    for ti, sp in enumerate(specs):
+        g = torch.empty(sp.shape, dtype=torch.bfloat16, device=DEV)
+        m = torch.zeros(sp.shape, dtype=torch.float32, device=DEV)
+        x = synth.gaussian(sp, 0.02, 1, ti, 0, "param", dtype=torch.bfloat16, device=DEV)
+        nch = sp.nchunks(s)
+        tensors.append(B.TensorArgs(g, m, x, torch.zeros((1, nch, k), dtype=torch.int32, device=DEV),
+                                    torch.zeros((1, nch, k), dtype=torch.float32, device=DEV)))
+    tl = B.TensorList(tensors)
+    ctx = B.Context()
+    rng = np.random.default_rng(s)
+    swaps = in_band = checked = 0
+    for step in range(10):
+        for ti, sp in enumerate(specs):
+            tensors[ti].grad.copy_(synth.student_t3(sp, 1e-2, 1, ti, step, "grad", dtype=torch.bfloat16, device=DEV))
+        picks = [(ti, int(c)) for ti, sp in enumerate(specs) if (ti + step) % 5 == 0
+                 for c in {0, sp.nchunks(s) - 1, int(rng.integers(0, sp.nchunks(s)))}]
+        pre = {(ti, c): (_block(tensors[ti].mom, specs[ti], c, s), _block(tensors[ti].grad, specs[ti], c, s),
+                         _block(tensors[ti].param, specs[ti], c, s)) for ti, c in picks}
+        ctx.demo_step(tl, BETA, LR, 0.0, s, k)
+        torch.cuda.synchronize()
+        for ti, c in picks:
+            m0, g0, x0 = pre[(ti, c)]
+            idx = tensors[ti].idx[0, c].cpu().numpy()
+            val = tensors[ti].val[0, c].cpu().numpy()
+            st = C.check_encode(m0, g0, BETA, s, k, idx, val, _block(tensors[ti].mom, specs[ti], c, s))
+            swaps += st["tie_swaps"]
+            sd = C.check_decode(x0, idx[None, None], val[None, None], LR, 0.0, s, "bf16",
+                                _block(tensors[ti].param, specs[ti], c, s).astype(np.float32))
+            in_band += sd["in_band"]
+            checked += 1
+    ctx.close()
+    print(f"s={s} k={k}: {checked} chunk-steps checked, tie swaps {swaps}, parameters inside the sign-noise band {in_band}")
