@@ -141,8 +141,8 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     if (b.s == s) {
       // the wavefront kernels are built on the symmetries of the DCT: any other matrix runs on the
       // kernels that read the matrix itself
-      *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr}
-                          : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32};
+      *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr, false}
+                          : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
       return DEMO_OK;
     }
   std::vector<double> P((size_t)s * s);
@@ -177,7 +177,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     if ((rc = upload(ctx, dt, &b.dec32)) != DEMO_OK) { (void)hipFree(b.dev); (void)hipFree(b.enc32); return rc; }
   }
   ctx->bases.push_back(b);
-  *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32};
+  *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
   return DEMO_OK;
 }
 
@@ -321,7 +321,7 @@ int timer_end(demo_ctx* ctx, int which, hipStream_t st) {
 
 int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, const demo_hparams& hp, int s, int k,
                hipStream_t st) {
-  demo::EncodeArgs a{hp.beta, hp.grad_scale, hp.alpha, k};
+  demo::EncodeArgs a{hp.beta, hp.grad_scale, hp.alpha, k, basis.dct ? 1 : 0};
   int rc;
   if (tc->tv2.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 0, st)) != DEMO_OK) return rc;
@@ -341,7 +341,7 @@ int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, co
 int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, int W, const demo_hparams& hp, int s,
                int k, hipStream_t st) {
   const float scale = hp.aggregate == DEMO_AGG_MEAN ? 1.0f / (float)W : 1.0f;
-  demo::DecodeArgs a{hp.lr, hp.weight_decay, scale, k, W, hp.phi, hp.aggregate};
+  demo::DecodeArgs a{hp.lr, hp.weight_decay, scale, k, W, hp.phi, hp.aggregate, basis.dct ? 1 : 0};
   int rc;
   if (tc->tv2.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 2, st)) != DEMO_OK) return rc;

@@ -47,6 +47,7 @@ struct EncodeArgs {
   float grad_scale;   // m <- beta*m + grad_scale*g
   float alpha;        // m <- m - alpha*IDCT(kept)
   int k;
+  int mirror;         // the projection matrix is the DCT (mirror-folded products allowed); set by the launch wrappers
 };
 
 struct DecodeArgs {
@@ -57,6 +58,7 @@ struct DecodeArgs {
   int W;
   int phi;            // demo_phi
   int agg;            // demo_aggregate
+  int mirror;         // as in EncodeArgs
 };
 // The wavefront-per-chunk decode kernels implement sign descent on the plain sum (which the mean
 // is sign-equivalent to); the other operating points run on the generic kernels.
@@ -69,6 +71,7 @@ struct BasisTables {
   const float* dec64;    // tables of the wavefront-per-chunk decode kernel (s = 64 only, else null)
   const float* enc32;    // dense-basis tile tables for diag(P32, P32) (s = 32 only, else null)
   const float* dec32;    // fragment table of the wavefront-per-tile decode kernel (s = 32 only, else null)
+  bool dct;              // `basis` is the orthonormal DCT-II (false: a matrix set by the caller)
 };
 
 // Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:

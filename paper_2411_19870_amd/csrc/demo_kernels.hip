@@ -85,6 +85,172 @@ __device__ __forceinline__ void store_acc(const f32x4* acc, int wave, int lane, 
   }
 }
 
+// ---------------------------------------------------------------------------
+// Mirror-folded products for the DCT (S >= 64).  Row u of the orthonormal DCT-II matrix is even (u even)
+// or odd (u odd) under i -> S-1-i, so a product that contracts over i needs only i < S/2 on the folded
+// operand x[i] +- x[S-1-i], and a product whose output index is i needs only i < S/2 of two partial
+// sums (even u, odd u), the mirror outputs being their sum and difference: half the MFMAs either way.
+// In these paths the basis tile in LDS holds the rows of P class-major: row u at position
+// prow(u) = (u % 2) * S/2 + u / 2, so that the 16 rows of an operand tile are adjacent.
+// ---------------------------------------------------------------------------
+template <int S>
+__device__ __forceinline__ int fold_pos(int u) { return (u & 1) * (S / 2) + (u >> 1); }   // row u -> class-major position
+template <int S>
+__device__ __forceinline__ int fold_idx(int p) { return 2 * (p & (S / 2 - 1)) + (p >= S / 2 ? 1 : 0); }   // inverse
+
+// encode, first product: T[u][j] = sum_{i < S/2} P[u][i] (X[i][j] +- X[S-1-i][j]); tile (mt, nt) of the
+// wavefront holds rows u = fold_idx(16 mt + m) (m-tiles below TN/2 are the even rows), columns 16 nt + n.
+template <int S>
+__device__ __forceinline__ void gemm_fold_enc1(f32x4* acc, int wave, int lane, const float* sP, const float* sX) {
+  using G = Geo<S>;
+  static_assert(G::TN >= 4, "folded products need S >= 64");
+  const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < G::TPW; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int ks = 0; ks < S / 8; ++ks) {
+    const int kk = 4 * ks + lq;
+    float be[G::CW], bo[G::CW];
+#pragma unroll
+    for (int j = 0; j < G::CW; ++j) {
+      const int col = 16 * (wave * G::CW + j) + l16;
+      const float x0 = sX[kk * G::LD + col], x1 = sX[(S - 1 - kk) * G::LD + col];
+      be[j] = x0 + x1;
+      bo[j] = x0 - x1;
+    }
+#pragma unroll
+    for (int mt = 0; mt < G::TN; ++mt) {
+      const float a = sP[(16 * mt + l16) * G::LD + kk];
+#pragma unroll
+      for (int j = 0; j < G::CW; ++j)
+        acc[mt * G::CW + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, mt >= G::TN / 2 ? bo[j] : be[j], acc[mt * G::CW + j], 0, 0, 0);
+    }
+  }
+}
+// rows of the accumulators above go to their natural places
+template <int S>
+__device__ __forceinline__ void store_fold_rows(const f32x4* acc, int wave, int lane, float* tile) {
+  using G = Geo<S>;
+  const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < G::TPW; ++i) {
+    int mt, nt;
+    tile_of<S>(wave, i, mt, nt);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) tile[fold_idx<S>(16 * mt + 4 * lq + r) * G::LD + 16 * nt + l16] = acc[i][r];
+  }
+}
+// encode, second product: Q[u][v] = sum_{j < S/2} (T[u][j] +- T[u][S-1-j]) P[v][j]; tile (mt, nt) holds rows
+// 16 mt + m and columns v = fold_idx(16 nt + n) (all n-tiles of a wavefront are of one class).
+template <int S>
+__device__ __forceinline__ void gemm_fold_enc2(f32x4* acc, int wave, int lane, const float* sP, const float* sT) {
+  using G = Geo<S>;
+  static_assert(G::TN >= 4, "folded products need S >= 64");
+  const int l16 = lane & 15, lq = lane >> 4;
+  const bool odd = wave * G::CW >= G::TN / 2;   // class of this wavefront's column tiles (uniform)
+#pragma unroll
+  for (int i = 0; i < G::TPW; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int ks = 0; ks < S / 8; ++ks) {
+    const int kk = 4 * ks + lq;
+    float b[G::CW];
+#pragma unroll
+    for (int j = 0; j < G::CW; ++j) b[j] = sP[(16 * (wave * G::CW + j) + l16) * G::LD + kk];
+#pragma unroll
+    for (int mt = 0; mt < G::TN; ++mt) {
+      const float t0 = sT[(16 * mt + l16) * G::LD + kk], t1 = sT[(16 * mt + l16) * G::LD + S - 1 - kk];
+      const float a = odd ? t0 - t1 : t0 + t1;
+#pragma unroll
+      for (int j = 0; j < G::CW; ++j)
+        acc[mt * G::CW + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[j], acc[mt * G::CW + j], 0, 0, 0);
+    }
+  }
+}
+
+// decode, first product: Y[i][v] for i < S/2 as two partial sums over even / odd u; the wavefront owns the
+// column tiles of its strip (as tile_of), accumulator (2 mh + cls) * CW + j is rows 16 mh + m, class cls.
+// Writes Y[i] = e + o and Y[S-1-i] = e - o (in place is safe: a wavefront reads only its own columns).
+template <int S>
+__device__ __forceinline__ void gemm_fold_dec1(f32x4* acc, int wave, int lane, const float* sP, const float* sS, float* sY) {
+  using G = Geo<S>;
+  static_assert(G::TN >= 4, "folded decode products need S >= 64");
+  const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < G::TPW; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int ks = 0; ks < S / 8; ++ks) {
+    const int kk = 4 * ks + lq;
+#pragma unroll
+    for (int mh = 0; mh < G::TN / 2; ++mh)
+#pragma unroll
+      for (int cls = 0; cls < 2; ++cls)
+#pragma unroll
+        for (int j = 0; j < G::CW; ++j) {
+          const int nt = wave * G::CW + j;
+          const float a = sP[(cls * (S / 2) + kk) * G::LD + 16 * mh + l16];
+          const float b = sS[(2 * kk + cls) * G::LD + 16 * nt + l16];
+          f32x4& c = acc[(2 * mh + cls) * G::CW + j];
+          c = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+        }
+  }
+#pragma unroll
+  for (int mh = 0; mh < G::TN / 2; ++mh)
+#pragma unroll
+    for (int j = 0; j < G::CW; ++j) {
+      const int nt = wave * G::CW + j;
+      const f32x4 e = acc[(2 * mh) * G::CW + j], o = acc[(2 * mh + 1) * G::CW + j];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = 16 * mh + 4 * lq + r;
+        sY[i * G::LD + 16 * nt + l16] = e[r] + o[r];
+        sY[(S - 1 - i) * G::LD + 16 * nt + l16] = e[r] - o[r];
+      }
+    }
+}
+// decode, second product: R[i][j] for j < S/2 as two partial sums over even / odd v.  Folded column tile nh
+// and the m-tiles of a wavefront: S = 128: nh = wave, all 8 m-tiles; S = 64: nh = wave % 2, m-tiles
+// 2 (wave / 2) + {0, 1}.  Accumulator 2 ml + cls.  emit_fold_dec2 hands R[i][j] and R[i][S-1-j] to
+// `emit(row, col, value)` (called after the barrier that ends the reads of Y).
+template <int S>
+__device__ __forceinline__ void gemm_fold_dec2(f32x4* acc, int wave, int lane, const float* sP, const float* sY) {
+  using G = Geo<S>;
+  static_assert(G::TN >= 4, "folded decode products need S >= 64");
+  constexpr int NM = G::TPW / 2;                         // m-tiles per wavefront
+  const int nh = S == 128 ? wave : (wave & 1);
+  const int m0 = S == 128 ? 0 : 2 * (wave >> 1);
+  const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < G::TPW; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+  for (int ks = 0; ks < S / 8; ++ks) {
+    const int kk = 4 * ks + lq;
+#pragma unroll
+    for (int ml = 0; ml < NM; ++ml)
+#pragma unroll
+      for (int cls = 0; cls < 2; ++cls) {
+        const float a = sY[(16 * (m0 + ml) + l16) * G::LD + 2 * kk + cls];
+        const float b = sP[(cls * (S / 2) + kk) * G::LD + 16 * nh + l16];
+        acc[2 * ml + cls] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[2 * ml + cls], 0, 0, 0);
+      }
+  }
+}
+template <int S, class F>
+__device__ __forceinline__ void emit_fold_dec2(const f32x4* acc, int wave, int lane, F emit) {
+  using G = Geo<S>;
+  constexpr int NM = G::TPW / 2;
+  const int nh = S == 128 ? wave : (wave & 1);
+  const int m0 = S == 128 ? 0 : 2 * (wave >> 1);
+  const int l16 = lane & 15, lq = lane >> 4;
+#pragma unroll
+  for (int ml = 0; ml < NM; ++ml)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = 16 * (m0 + ml) + 4 * lq + r, j = 16 * nh + l16;
+      emit(i, j, acc[2 * ml][r] + acc[2 * ml + 1][r]);
+      emit(i, S - 1 - j, acc[2 * ml][r] - acc[2 * ml + 1][r]);
+    }
+}
+
 // Tensor of a chunk for a workgroup that walks the chunks in ascending order: a step from the tensor
 // of the previous chunk instead of a binary search (a chain of dependent loads) per chunk.  `st` holds
 // {tensor, its first chunk, the next tensor's first chunk}; st.t < 0 before the first call.
@@ -119,7 +285,9 @@ __device__ __forceinline__ int block_sum4(int wave_count, int wave, int lane, in
 // ---------------------------------------------------------------------------
 // With a worklist (wl.list != nullptr) only the chunks queued there are processed, and the
 // last workgroup to finish clears the queue for the next call.
-template <int S>
+// MIR: the projection matrix is the DCT and the two products are mirror-folded (instantiated for S = 128, where
+// dense fp32 MFMA work is the bound; at S = 64 the extra registers cost more than the saved MFMAs).
+template <int S, bool MIR>
 __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const float* __restrict__ basis,
                                                         EncodeArgs args, Worklist wl) {
   using G = Geo<S>;
@@ -140,9 +308,10 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
   const int k = args.k;
   const int kpad = (k + 3) & ~3;
 
+  constexpr bool mir = MIR;
   const int nwork = wl.list != nullptr ? *wl.count : tv.total_chunks;
   if (nwork > 0)
-    for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
+    for (int e = tid; e < S * S; e += G::NT) sP[(mir ? fold_pos<S>(e / S) : e / S) * G::LD + (e % S)] = basis[e];
 
   DEMO_PHASE_DECL
   TensorCursor cur;
@@ -198,23 +367,30 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
 
     // ---- T = P * X -----------------------------------------------------------------------
     f32x4 acc[G::TPW];
-    gemm_lds<S>(acc, wave, lane, lds,
-                [&](int m, int kk) { return m * G::LD + kk; },                              // P[u][i]
-                [&](int kk, int n) { return G::TILE_FLOATS + kk * G::LD + n; });           // X[i][j]
-    if (!G::INPLACE) {
-      store_acc<S>(acc, wave, lane, sT);
+    if constexpr (MIR) {
+      gemm_fold_enc1<S>(acc, wave, lane, sP, sX);
+      store_fold_rows<S>(acc, wave, lane, sX);   // own column strip only: in place is safe
     } else {
-      // every read of this wavefront's column strip is its own: overwrite in place
-      store_acc<S>(acc, wave, lane, sX);
+      gemm_lds<S>(acc, wave, lane, lds,
+                  [&](int m, int kk) { return m * G::LD + kk; },                              // P[u][i]
+                  [&](int kk, int n) { return G::TILE_FLOATS + kk * G::LD + n; });           // X[i][j]
+      // every read of this wavefront's column strip is its own: overwrite in place (S >= 64)
+      store_acc<S>(acc, wave, lane, G::INPLACE ? sX : sT);
     }
     __syncthreads();
 
     DEMO_PHASE(1);
     // ---- Q = T * P^T ---------------------------------------------------------------------
     const int t_off = (int)(sT - lds);
-    gemm_lds<S>(acc, wave, lane, lds,
-                [&](int m, int kk) { return t_off + m * G::LD + kk; },                     // T[u][j]
-                [&](int kk, int n) { return n * G::LD + kk; });                             // P[v][j]
+    if constexpr (MIR) {
+      gemm_fold_enc2<S>(acc, wave, lane, sP, sT);
+    } else {
+      gemm_lds<S>(acc, wave, lane, lds,
+                  [&](int m, int kk) { return t_off + m * G::LD + kk; },                     // T[u][j]
+                  [&](int kk, int n) { return n * G::LD + kk; });                             // P[v][j]
+    }
+    // column of coefficient tile nt held by this lane
+    auto qcol = [&](int nt) { return mir ? fold_idx<S>(16 * nt + l16) : 16 * nt + l16; };
 
     DEMO_PHASE(2);
     // ---- exact top-k over the chunk (magnitude bits are order preserving as unsigned) ------
@@ -255,7 +431,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
         if (mag[i * 4 + r] >= thr_lo) {
           const int pos = atomicAdd(s_cursor, 1);
           if (pos < GEN_CAND_CAP) {
-            cand_key[pos] = make_uint2(~(uint32_t)((16 * mt + 4 * lq + r) * S + 16 * nt + l16), mag[i * 4 + r]);
+            cand_key[pos] = make_uint2(~(uint32_t)((16 * mt + 4 * lq + r) * S + qcol(nt)), mag[i * 4 + r]);
             cand_val[pos] = acc[i][r];
           }
         }
@@ -339,7 +515,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
             tile_of<S>(wave, i, mt, nt);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-              const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+              const uint32_t flat = (16 * mt + 4 * lq + r) * S + qcol(nt);
               cw += __popcll(__ballot(mag[i * 4 + r] == thr && flat < cand));
             }
           }
@@ -356,7 +532,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
         tile_of<S>(wave, i, mt, nt);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const uint32_t flat = (16 * mt + 4 * lq + r) * S + 16 * nt + l16;
+          const uint32_t flat = (16 * mt + 4 * lq + r) * S + qcol(nt);
           const uint32_t mg = mag[i * 4 + r];
           if (mg > thr || (mg == thr && flat <= tie_last)) {
             const int pos = atomicAdd(s_cursor, 1);
@@ -405,12 +581,13 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
       const int fi = sel_idx[tt];
       const float fv = sel_val[tt];
       const int u = fi / S, v = fi - u * S;
+      const int pu = mir ? fold_pos<S>(u) : u, pv = mir ? fold_pos<S>(v) : v;   // rows of P in the LDS tile
 #pragma unroll
       for (int i = 0; i < G::TPW; ++i) {
         int mt, nt;
         tile_of<S>(wave, i, mt, nt);
-        const float a = fv * sP[u * G::LD + 16 * mt + l16];
-        const float b = sP[v * G::LD + 16 * nt + l16];
+        const float a = fv * sP[pu * G::LD + 16 * mt + l16];
+        const float b = sP[pv * G::LD + 16 * nt + l16];
         acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
       }
     }
@@ -449,7 +626,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
 // ---------------------------------------------------------------------------
 // decode, order-2 tensors, generic
 // ---------------------------------------------------------------------------
-template <int S>
+template <int S, bool MIR>
 __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const float* __restrict__ basis,
                                                         DecodeArgs args) {
   using G = Geo<S>;
@@ -463,7 +640,8 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
   const int k = args.k, W = args.W;
   const bool by_count = args.agg == 2, plain_sign = args.phi == 0 && !by_count;
 
-  for (int e = tid; e < S * S; e += G::NT) sP[(e / S) * G::LD + (e % S)] = basis[e];
+  constexpr bool mir = MIR;
+  for (int e = tid; e < S * S; e += G::NT) sP[(mir ? fold_pos<S>(e / S) : e / S) * G::LD + (e % S)] = basis[e];
 
   TensorCursor cur;
   for (int chunk = blockIdx.x; chunk < tv.total_chunks; chunk += gridDim.x) {
@@ -551,25 +729,35 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
     }
     __syncthreads();
 
-    // ---- Y = P^T * S ------------------------------------------------------------------------
+    // ---- Y = P^T * S, R = Y * P, phi(R) into sX ---------------------------------------------
     f32x4 acc[G::TPW];
-    gemm_lds<S>(acc, wave, lane, lds,
-                [&](int m, int kk) { return kk * G::LD + m; },                              // P[u][i]
-                [&](int kk, int n) { return G::TILE_FLOATS + kk * G::LD + n; });           // S[u][v]
-    store_acc<S>(acc, wave, lane, sT);
-    __syncthreads();
-    // ---- R = Y * P --------------------------------------------------------------------------
-    const int t_off = (int)(sT - lds);
-    gemm_lds<S>(acc, wave, lane, lds,
-                [&](int m, int kk) { return t_off + m * G::LD + kk; },                     // Y[i][v]
-                [&](int kk, int n) { return kk * G::LD + n; });                             // P[v][j]
+    if constexpr (MIR) {
+      gemm_fold_dec1<S>(acc, wave, lane, sP, sX, sT);   // in place: a wavefront touches only its own columns
+      __syncthreads();
+      gemm_fold_dec2<S>(acc, wave, lane, sP, sT);
+      __syncthreads();                                   // all reads of Y are done
+      emit_fold_dec2<S>(acc, wave, lane, [&](int i, int j, float r) {
+        sX[i * G::LD + j] = args.phi == 0 ? sgnf(r) : r;                                     // phi(m)
+      });
+      __syncthreads();
+    } else {
+      gemm_lds<S>(acc, wave, lane, lds,
+                  [&](int m, int kk) { return kk * G::LD + m; },                              // P[u][i]
+                  [&](int kk, int n) { return G::TILE_FLOATS + kk * G::LD + n; });           // S[u][v]
+      store_acc<S>(acc, wave, lane, sT);
+      __syncthreads();
+      const int t_off = (int)(sT - lds);
+      gemm_lds<S>(acc, wave, lane, lds,
+                  [&](int m, int kk) { return t_off + m * G::LD + kk; },                     // Y[i][v]
+                  [&](int kk, int n) { return kk * G::LD + n; });                             // P[v][j]
 #pragma unroll
-    for (int i = 0; i < G::TPW; ++i)
+      for (int i = 0; i < G::TPW; ++i)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) acc[i][r] = args.phi == 0 ? sgnf(acc[i][r]) : acc[i][r];   // phi(m)
-    __syncthreads();                       // all reads of Y are done
-    store_acc<S>(acc, wave, lane, sX);
-    __syncthreads();
+        for (int r = 0; r < 4; ++r) acc[i][r] = args.phi == 0 ? sgnf(acc[i][r]) : acc[i][r];   // phi(m)
+      __syncthreads();                       // all reads of Y are done
+      store_acc<S>(acc, wave, lane, sX);
+      __syncthreads();
+    }
 
     // ---- x <- x - lr*(phi(m) + wd*x) --------------------------------------------------------
 #pragma unroll
@@ -772,14 +960,20 @@ static hipError_t launch_enc2d_generic(const TableView& tv, const float* basis, 
                                        const Worklist& wl, int num_cus, hipStream_t stream) {
   using G = Geo<S>;
   const size_t lds_bytes = sizeof(float) * G::LDS_FLOATS;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_generic<S>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  constexpr bool CAN_FOLD = S == 128;
+  const bool fold = CAN_FOLD && a.mirror != 0;
+  const void* kern = fold ? reinterpret_cast<const void*>(&encode2d_generic<S, CAN_FOLD>)
+                          : reinterpret_cast<const void*>(&encode2d_generic<S, false>);
+  hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   const int per_cu = (int)((160 * 1024) / lds_bytes) < 1 ? 1 : (int)((160 * 1024) / lds_bytes);
   int64_t grid = (int64_t)num_cus * (per_cu > 8 ? 8 : per_cu);
   if (grid > tv.total_chunks) grid = tv.total_chunks;
   if (wl.list != nullptr && grid > 64) grid = 64;   // the queue is short; an empty one costs one launch
-  hipLaunchKernelGGL(encode2d_generic<S>, dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a, wl);
+  if (fold)
+    hipLaunchKernelGGL((encode2d_generic<S, CAN_FOLD>), dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a, wl);
+  else
+    hipLaunchKernelGGL((encode2d_generic<S, false>), dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a, wl);
   return hipGetLastError();
 }
 
@@ -788,13 +982,19 @@ static hipError_t launch_dec2d_generic(const TableView& tv, const float* basis, 
                                        hipStream_t stream) {
   using G = Geo<S>;
   const size_t lds_bytes = sizeof(float) * (G::TILE_FLOATS * (G::INPLACE ? 2 : 3) + 4 + G::TILE_FLOATS / 4);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_generic<S>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  constexpr bool CAN_FOLD = S == 128;
+  const bool fold = CAN_FOLD && a.mirror != 0;
+  const void* kern = fold ? reinterpret_cast<const void*>(&decode2d_generic<S, CAN_FOLD>)
+                          : reinterpret_cast<const void*>(&decode2d_generic<S, false>);
+  hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
   if (e != hipSuccess) return e;
   const int per_cu = (int)((160 * 1024) / lds_bytes) < 1 ? 1 : (int)((160 * 1024) / lds_bytes);
   int64_t grid = (int64_t)num_cus * (per_cu > 8 ? 8 : per_cu);
   if (grid > tv.total_chunks) grid = tv.total_chunks;
-  hipLaunchKernelGGL(decode2d_generic<S>, dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a);
+  if (fold)
+    hipLaunchKernelGGL((decode2d_generic<S, CAN_FOLD>), dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a);
+  else
+    hipLaunchKernelGGL((decode2d_generic<S, false>), dim3((unsigned)grid), dim3(256), lds_bytes, stream, tv, basis, a);
   return hipGetLastError();
 }
 
