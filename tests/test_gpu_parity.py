@@ -287,3 +287,54 @@ def test_s32_decode_unaligned_shape_takes_the_generic_kernel(ctx):
     case = Case(specs, 32, 8, W=4, seed=9)
     case.fill_payloads()
     run_decode_check(ctx, case, W=4)
+
+
+# ---- large sparsity budgets and many workers (generic kernels; k = 64 is the last budget of the s = 64 wavefront kernel)
+@pytest.mark.parametrize("s,k", [(64, 64), (64, 65), (64, 256), (32, 200), (128, 256)])
+def test_large_k(ctx, s, k):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 2 * s, 3 * s), synth.TensorSpec("v", 8 * s, 0)]
+    kk = [k, min(k, s)]
+    for sp, kq in zip(specs, kk):     # the order-1 tensor allows k <= s only: one call per tensor
+        case = Case([sp], s, kq, W=2, seed=k)
+        run_encode_check(ctx, case)
+        case.fill_payloads()
+        run_decode_check(ctx, case, W=2)
+
+
+@pytest.mark.parametrize("s,W,k", [(64, 200, 8), (64, 33, 64), (32, 255, 4), (128, 100, 32)])
+def test_many_workers_beyond_the_register_payload(ctx, s, W, k):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 2 * s, 2 * s), synth.TensorSpec("v", 2 * s, 0)]
+    case = Case(specs, s, k, W=W, param_dtype=torch.bfloat16, seed=W)
+    case.fill_payloads()
+    run_decode_check(ctx, case, W=W)
+
+
+# ---- the calls are plain kernel launches once a tensor list has been seen: they can be captured in a HIP graph
+def test_step_can_be_captured_and_replayed(ctx):
+    ctx.demo_set_variant(1)
+    s, k = 64, 32
+    a = Case(synth.tensor_set("tiny"), s, k, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, seed=50)
+    b = Case(synth.tensor_set("tiny"), s, k, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, seed=50)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx.demo_step(a.args, BETA, LR, 0.01, s, k, side)      # first sight of the list: descriptor upload
+        side.synchronize()
+    for t_a, t_b in zip(a.m + a.x, b.m + b.x):                   # back to the common start
+        t_a.copy_(t_b)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ctx.demo_step(a.args, BETA, LR, 0.01, s, k, torch.cuda.current_stream())
+    for step in range(3):
+        a.new_grads(step + 1)
+        b.new_grads(step + 1)
+        torch.cuda.synchronize()
+        graph.replay()
+        ctx.demo_step(b.args, BETA, LR, 0.01, s, k)            # eager, between the replays
+        torch.cuda.synchronize()
+        sa, sb = a.snapshot(), b.snapshot()
+        for key in ("m", "x", "idx", "val"):
+            for ta, tb in zip(sa[key], sb[key]):
+                assert np.array_equal(ta, tb), (step, key)
