@@ -122,8 +122,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     if (FULL) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const u32x4 a = *reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + lane_off);
-        const f32x4 b = *reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + lane_off);
+        const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + lane_off));
+        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + lane_off));
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
           pi[4 * j + x] = (int32_t)a[x];
