@@ -67,7 +67,7 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
 
   const int nwaves = gridDim.x * D32_WAVES;
   const int total = tv.total_chunks;
-  int tileno = blockIdx.x * D32_WAVES + wave;                 // wavefront w takes tiles w, w + nwaves, ...
+  int tileno = first_work_item<DEMO_RUN>(wave);                         // then tiles + nwaves, ...
   if (tileno >= total) return;
 
   // ---- payload: slot 8 q + j holds pair 64 j + lane of chunk q = 2 bu + bv of the tile -------------------

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   __syncthreads();
 
   const int nwaves = gridDim.x * D64_WAVES;
-  const int wid = blockIdx.x * D64_WAVES + wave;
+  const int wid = first_work_item<DEMO_RUN>(wave);
   const int total = tv.total_chunks;
   int chunk = wid;   // wavefront w takes chunks w, w + nwaves, ... (see the encode kernel)
   if (chunk >= total) return;

@@ -108,7 +108,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   // wavefront w takes chunks w, w + nwaves, ...: at any time the wavefronts of the grid work on one
   // narrow band of memory, which the HBM channels serve faster than a far-apart range per wavefront
   const int nwaves = gridDim.x * E64_WAVES;
-  const int wid = blockIdx.x * E64_WAVES + wave;
+  const int wid = first_work_item<DEMO_RUN>(wave);
   const int total = tv.total_chunks;
   int chunk = wid;
   if (chunk >= total) return;

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   __syncthreads();
 
   const int nwaves = gridDim.x * ED_WAVES;
-  const int wid = blockIdx.x * ED_WAVES + wave;
+  const int wid = first_work_item<DEMO_RUN>(wave);
   const int total = tv.total_chunks;
   int tileno = wid;   // wavefront w takes tiles w, w + nwaves, ...
   if (tileno >= total) return;
