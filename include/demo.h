@@ -12,6 +12,8 @@
  *   - All tensor and payload pointers are DEVICE pointers owned by the caller; the
  *     library never frees or keeps them after the call returns.  `demo_tensor`
  *     arrays themselves are HOST memory and are copied during the call.
+ *   - grad, mom and param must be 16-byte aligned (the kernels move rows with 16-byte accesses); idx and val
+ *     need only 4-byte alignment (16-byte aligned payload arrays get the widest loads).  DEMO_ERR_ARG otherwise.
  *   - Tensors are dense row-major.  cols == 0 marks an order-1 tensor of `rows`
  *     elements, chunked into pieces of s; otherwise the tensor is rows x cols and
  *     is chunked into s x s blocks (appendix "Multilinear Transforms and

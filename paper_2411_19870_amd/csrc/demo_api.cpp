@@ -98,6 +98,11 @@ int validate(const demo_ctx* ctx, const demo_tensor* t, int n, int s, int k, int
     if (t[i].idx == nullptr || t[i].val == nullptr) return DEMO_ERR_ARG;
     if ((need & NEED_ENCODE) && (t[i].grad == nullptr || t[i].mom == nullptr)) return DEMO_ERR_ARG;
     if ((need & NEED_DECODE) && t[i].param == nullptr) return DEMO_ERR_ARG;
+    // the kernels move tensor rows with 16-byte accesses; payload arrays only need their natural alignment
+    auto misaligned = [](const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; };
+    if ((need & NEED_ENCODE) && (misaligned(t[i].grad, 16) || misaligned(t[i].mom, 16))) return DEMO_ERR_ARG;
+    if ((need & NEED_DECODE) && misaligned(t[i].param, 16)) return DEMO_ERR_ARG;
+    if (misaligned(t[i].idx, 4) || misaligned(t[i].val, 4)) return DEMO_ERR_ARG;
     if (t[i].cols == 0) total1 += t[i].rows / s;
     else total2 += (t[i].rows / s) * (t[i].cols / s);
     if (total1 > INT32_MAX || total2 > INT32_MAX) return DEMO_ERR_UNSUPPORTED;

@@ -95,6 +95,11 @@ def test_validation_happens_before_any_launch():
     assert dec(_tensor(param_dtype=5)) == B.DEMO_ERR_UNSUPPORTED
     assert dec(_tensor(), W=0) == B.DEMO_ERR_ARG
     assert dec(_tensor(rows=64, cols=96)) == B.DEMO_ERR_SHAPE
+    assert enc(_tensor(grad=0x1004)) == B.DEMO_ERR_ARG            # tensor pointers: 16-byte aligned
+    assert enc(_tensor(mom=0x2008)) == B.DEMO_ERR_ARG
+    assert dec(_tensor(param=0x3002)) == B.DEMO_ERR_ARG
+    assert enc(_tensor(idx=0x4002)) == B.DEMO_ERR_ARG             # payload arrays: 4-byte aligned
+    assert enc(_tensor(idx=0x4004, val=0x5004), n=0) == B.DEMO_OK
     assert step(_tensor(param=None)) == B.DEMO_ERR_ARG
     assert step(_tensor(grad=None)) == B.DEMO_ERR_ARG
     assert lib.demo_set_variant(h, 5) == B.DEMO_ERR_ARG

@@ -338,3 +338,51 @@ def test_step_can_be_captured_and_replayed(ctx):
         for key in ("m", "x", "idx", "val"):
             for ta, tb in zip(sa[key], sb[key]):
                 assert np.array_equal(ta, tb), (step, key)
+
+
+# ---- payload arrays that are only 4-byte aligned (views into a larger buffer) take the narrower loads -----------
+@pytest.mark.parametrize("s,W,k", [(64, 64, 32), (64, 8, 32), (32, 16, 32)])
+def test_payload_arrays_with_4_byte_alignment(ctx, s, W, k):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 192, 128), synth.TensorSpec("v", 256, 0)]
+    base = Case(specs, s, k, W=W, param_dtype=torch.bfloat16, grad_dtype=torch.bfloat16, seed=60)
+    # rebuild the argument list with idx / val as views that start one element into a padded buffer
+    idx2, val2 = [], []
+    for i, v in zip(base.idx, base.val):
+        bi = torch.zeros(i.numel() + 4, dtype=torch.int32, device=i.device)
+        bv = torch.zeros(v.numel() + 4, dtype=torch.float32, device=v.device)
+        idx2.append(bi[1:1 + i.numel()].view(i.shape))
+        val2.append(bv[1:1 + v.numel()].view(v.shape))
+        assert idx2[-1].data_ptr() % 16 == 4
+    base.idx, base.val = idx2, val2
+    base.args = B.TensorList([B.TensorArgs(g, m, x, i, v) for g, m, x, i, v in zip(base.g, base.m, base.x, base.idx, base.val)])
+    run_encode_check(ctx, base)
+    base.fill_payloads()
+    run_decode_check(ctx, base, W=W)
+
+
+# ---- tensors of different dtypes in one call (the wavefront kernels want one dtype per call: generic path) ---------
+@pytest.mark.parametrize("s", [32, 64])
+def test_mixed_dtypes_in_one_list(ctx, s):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 128, 192), synth.TensorSpec("b", 192, 64), synth.TensorSpec("v", 128, 0)]
+    k, W = 8, 3
+    case = Case(specs, s, k, W=W, seed=61)
+    # tensor 1 gets bf16 gradients and parameters, the others stay float32
+    case.g[1] = case.g[1].to(torch.bfloat16)
+    case.x[1] = case.x[1].to(torch.bfloat16)
+    case.args = B.TensorList([B.TensorArgs(g, m, x, i, v) for g, m, x, i, v in zip(case.g, case.m, case.x, case.idx, case.val)])
+    before = case.snapshot()
+    ctx.demo_encode(case.args, BETA, s, k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    for ti in range(len(specs)):
+        C.check_encode(before["m"][ti], before["g"][ti], BETA, s, k, after["idx"][ti][0], after["val"][ti][0], after["m"][ti])
+    case.fill_payloads()
+    before = case.snapshot()
+    ctx.demo_decode(case.args, W, LR, 0.0, s, k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    for ti in range(len(specs)):
+        pd = "bf16" if case.x[ti].dtype == torch.bfloat16 else "f32"
+        C.check_decode(before["x"][ti], before["idx"][ti], before["val"][ti], LR, 0.0, s, pd, after["x"][ti])
