@@ -358,7 +358,7 @@ constexpr int D64S_LDS_BYTES = 4 * (2 * 4096 + D64S_WAVES * 2 * 64);
 }  // namespace
 
 template <bool PBF16>
-__global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, const float* __restrict__ tables,
+__global__ __launch_bounds__(D64S_THREADS, 3) void decode2d_sparse64(TableView tv, const float* __restrict__ tables,
                                                                   DecodeArgs args) {
   extern __shared__ float lds[];
   const float* sPcol = lds;
@@ -439,14 +439,20 @@ __global__ __launch_bounds__(D64S_THREADS) void decode2d_sparse64(TableView tv, 
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
       for (int e = 0; e < 4; ++e) R[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < npad / 4; ++ks) {
-      const uint2 sv = sel[4 * ks + g];
-      const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
+    // operands of step ks + 1 (pair, then the two rows of P it names) are read while the MFMAs of step ks run
+    const int nks = npad / 4;
+    uint2 sv = sel[g];
+    float4 pa = *reinterpret_cast<const float4*>(&sProw[((sv.x >> 6) & 63u) * 64 + 4 * c]);
+    float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+    for (int ks = 0; ks < nks; ++ks) {
       const float val = __uint_as_float(sv.y);
-      const float4 pa = *reinterpret_cast<const float4*>(&sProw[u * 64 + 4 * c]);
-      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[v * 64 + 4 * c]);
       const float af[4] = {val * pa.x, val * pa.y, val * pa.z, val * pa.w};
       const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+      if (ks + 1 < nks) {
+        sv = sel[4 * (ks + 1) + g];
+        pa = *reinterpret_cast<const float4*>(&sProw[((sv.x >> 6) & 63u) * 64 + 4 * c]);
+        pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+      }
 #pragma unroll
       for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
