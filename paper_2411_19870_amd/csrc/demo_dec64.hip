@@ -79,9 +79,11 @@ void build_dec64_tables(const double* P, float* out) {
   }
 }
 
-// PBF16: parameter dtype of every tensor in the table.  FULL: k == 32 and W == 64, so the payload
-// of a chunk is read with eight fully populated 16-byte loads per array (eight workers each).
-template <bool PBF16, bool FULL>
+// PBF16: parameter dtype of every tensor in the table.  MODE 1: k == 32 and W == 64, the payload of a chunk is
+// read with eight fully populated 16-byte loads per array (eight workers each).  MODE 2: k == 32 and W a smaller
+// multiple of 8: the first W / 8 of those loads.  MODE 0: any k <= 64, W * k <= 2048, one pair per load.  Modes
+// 1 and 2 need 16-byte aligned payload arrays.
+template <bool PBF16, int MODE>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   extern __shared__ float lds[];
@@ -91,7 +93,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   const int g = lane >> 4, c = lane & 15;
   float* tile = lds + D64_G_FLOATS + wave * D64_TILE_FLOATS;
   int* itile = reinterpret_cast<int*>(tile);
-  const int k = FULL ? 32 : args.k, W = args.W;
+  constexpr bool FULL = MODE == 1;          // every payload register is in use
+  constexpr bool WIDE = MODE != 0;          // 16-byte payload loads
+  const int k = WIDE ? 32 : args.k, W = args.W;
 
   for (int e = tid; e < D64_G_FLOATS / 4; e += D64_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + D64_G)[e];
@@ -105,41 +109,51 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 
   // ---- payload access ---------------------------------------------------------------------------------
   // 32 (index, value) pairs per lane hold the whole payload of a chunk (W * k <= 2048 pairs).
-  //   FULL:  load j (0..7) fetches pairs 4(l%8) .. +3 of worker 8j + l/8 as one 16-byte load;
+  //   WIDE:  load j (0..7) fetches pairs 4(l%8) .. +3 of worker 8j + l/8 as one 16-byte load;
   //   else:  load j (0..31) fetches one pair: with k <= 32 of worker 2j + l/32, else of worker j.
   constexpr int NP = 32;
   int32_t pi[NP];
   float pv[NP];
+#pragma unroll
+  for (int j = 0; j < NP; ++j) {   // registers past the W workers are never loaded and stay empty
+    pi[j] = -1;
+    pv[j] = 0.f;
+  }
   const int wpi = k <= 32 ? 2 : 1;
-  const int sub = FULL ? (lane >> 3) : (wpi == 2 ? (lane >> 5) : 0);
-  const int pt = FULL ? 4 * (lane & 7) : (wpi == 2 ? (lane & 31) : lane);
-  const bool pact = FULL || pt < k;
+  const int nact = FULL ? NP : WIDE ? W / 2 : (W + wpi - 1) / wpi;   // payload registers in use (uniform)
+  const int sub = WIDE ? (lane >> 3) : (wpi == 2 ? (lane >> 5) : 0);
+  const int pt = WIDE ? 4 * (lane & 7) : (wpi == 2 ? (lane & 31) : lane);
+  const bool pact = WIDE || pt < k;
   auto load_payload = [&](const TensorDev& dd, int ccc) {
     const int64_t wstride = (int64_t)dd.nchunks * k;
     const uint32_t lane_off = (uint32_t)(sub * (int)wstride + pt);
     const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)ccc * k;
     const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)ccc * k;
-    if (FULL) {
+    if (WIDE) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + lane_off));
-        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + lane_off));
+        if (FULL || 4 * j < nact) {
+          const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + lane_off));
+          const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + lane_off));
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
-          pi[4 * j + x] = (int32_t)a[x];
-          pv[4 * j + x] = b[x];
+          for (int x = 0; x < 4; ++x) {
+            pi[4 * j + x] = (int32_t)a[x];
+            pv[4 * j + x] = b[x];
+          }
+          ip += 8 * wstride;
+          vp += 8 * wstride;
         }
-        ip += 8 * wstride;
-        vp += 8 * wstride;
       }
     } else {
 #pragma unroll
       for (int j = 0; j < NP; ++j) {
-        const bool ok = pact && j * wpi + sub < W;
-        pi[j] = ok ? ip[lane_off] : -1;
-        pv[j] = ok ? vp[lane_off] : 0.f;
-        ip += wpi * wstride;
-        vp += wpi * wstride;
+        if (j < nact) {
+          const bool ok = pact && j * wpi + sub < W;
+          pi[j] = ok ? ip[lane_off] : -1;
+          pv[j] = ok ? vp[lane_off] : 0.f;
+          ip += wpi * wstride;
+          vp += wpi * wstride;
+        }
       }
     }
   };
@@ -157,7 +171,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   auto scatter = [&]() {
     float mx = 0.f;
 #pragma unroll
-    for (int j = 0; j < NP; ++j) mx = fmaxf(mx, fabsf(pv[j]));
+    for (int j = 0; j < NP; ++j)
+      if (FULL || j < nact) mx = fmaxf(mx, fabsf(pv[j]));
     uint32_t mb = __float_as_uint(mx);
     mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
     mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
@@ -170,11 +185,13 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     const int sh = vbits + 126 - ex;                      // max |val| * 2^sh < 2^vbits
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
-      const uint32_t u = (uint32_t)pi[j];
-      // 12-bit index [u5..u0 v5..v0] -> [u1 u0 u5..u2 | v1 v0 v5..v2], then row stride 64 -> LDT
-      const uint32_t x = ((u & 0xC3u) << 4) | ((u >> 2) & 0x3CFu);
-      const uint32_t a = u < 4096u ? x + ((x >> 6) << 2) : dummy;
-      atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
+      if (FULL || j < nact) {
+        const uint32_t u = (uint32_t)pi[j];
+        // 12-bit index [u5..u0 v5..v0] -> [u1 u0 u5..u2 | v1 v0 v5..v2], then row stride 64 -> LDT
+        const uint32_t x = ((u & 0xC3u) << 4) | ((u >> 2) & 0x3CFu);
+        const uint32_t a = u < 4096u ? x + ((x >> 6) << 2) : dummy;
+        atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
+      }
     }
   };
 
@@ -505,17 +522,17 @@ static hipError_t launch_dec_sparse64(const TableView& tv, const float* tables, 
   return hipGetLastError();
 }
 
-template <bool PBF16, bool FULL>
+template <bool PBF16, int MODE>
 static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, FULL>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D64_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wave64<PBF16, FULL>), dim3((unsigned)grid), dim3(D64_THREADS), D64_LDS_BYTES, stream,
+  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE>), dim3((unsigned)grid), dim3(D64_THREADS), D64_LDS_BYTES, stream,
                      tv, tables, a);
   return hipGetLastError();
 }
@@ -528,12 +545,19 @@ hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, cons
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tv.total_chunks + D64_WAVES - 1) / D64_WAVES;
   if (grid > max_grid) grid = max_grid;
-  const bool full = a.k == 32 && a.W == 64 && payload_aligned16;
-  if (param_bf16)
-    return full ? launch_dec_wave64<true, true>(tv, tables, a, grid, stream)
-                : launch_dec_wave64<true, false>(tv, tables, a, grid, stream);
-  return full ? launch_dec_wave64<false, true>(tv, tables, a, grid, stream)
-              : launch_dec_wave64<false, false>(tv, tables, a, grid, stream);
+  const int mode = (a.k == 32 && payload_aligned16 && a.W % 8 == 0 && a.W <= 64) ? (a.W == 64 ? 1 : 2) : 0;
+  if (param_bf16) {
+    switch (mode) {
+      case 1: return launch_dec_wave64<true, 1>(tv, tables, a, grid, stream);
+      case 2: return launch_dec_wave64<true, 2>(tv, tables, a, grid, stream);
+      default: return launch_dec_wave64<true, 0>(tv, tables, a, grid, stream);
+    }
+  }
+  switch (mode) {
+    case 1: return launch_dec_wave64<false, 1>(tv, tables, a, grid, stream);
+    case 2: return launch_dec_wave64<false, 2>(tv, tables, a, grid, stream);
+    default: return launch_dec_wave64<false, 0>(tv, tables, a, grid, stream);
+  }
 }
 
 }  // namespace demo

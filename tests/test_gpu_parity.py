@@ -386,3 +386,14 @@ def test_mixed_dtypes_in_one_list(ctx, s):
     for ti in range(len(specs)):
         pd = "bf16" if case.x[ti].dtype == torch.bfloat16 else "f32"
         C.check_decode(before["x"][ti], before["idx"][ti], before["val"][ti], LR, 0.0, s, pd, after["x"][ti])
+
+
+# ---- s = 64, k = 32: worker counts that are multiples of 8 read the payload with 16-byte loads ------------------
+@pytest.mark.parametrize("W", [8, 16, 24, 40, 56, 12, 63])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+def test_s64_decode_worker_counts(ctx, W, pdt):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 192, 320), synth.TensorSpec("b", 64, 64), synth.TensorSpec("v", 128, 0)]
+    case = Case(specs, 64, 32, W=W, param_dtype=pdt, seed=200 + W)
+    case.fill_payloads()
+    run_decode_check(ctx, case, W=W, wd=0.01)
