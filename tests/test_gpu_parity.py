@@ -397,3 +397,16 @@ def test_s64_decode_worker_counts(ctx, W, pdt):
     case = Case(specs, 64, 32, W=W, param_dtype=pdt, seed=200 + W)
     case.fill_payloads()
     run_decode_check(ctx, case, W=W, wd=0.01)
+
+
+# ---- the context caches a few descriptor tables: more distinct tensor lists than that still work, and a list
+#      that was evicted is simply uploaded again ------------------------------------------------------------------
+def test_many_distinct_tensor_lists(ctx):
+    ctx.demo_set_variant(1)
+    s, k = 64, 8
+    cases = [Case([synth.TensorSpec("a", 64 * (1 + i % 3), 128), synth.TensorSpec("v", 64 * (1 + i % 2), 0)], s, k, seed=300 + i)
+             for i in range(12)]
+    for rnd in range(2):
+        for case in cases:
+            case.new_grads(rnd)
+            run_encode_check(ctx, case)
