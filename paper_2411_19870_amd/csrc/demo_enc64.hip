@@ -24,6 +24,8 @@
 // m - P^T Q^ P is one more MFMA chain of contraction length k that accumulates straight into D,
 // which is then stored with the load pattern.  LDS holds the basis fragment tables and a small
 // candidate list per wavefront.
+#include <type_traits>
+
 #include "demo_device.h"
 
 namespace demo {
@@ -37,10 +39,12 @@ constexpr int E64_CAP = 128;                      // candidate list capacity per
 constexpr int E64_T1 = 0;                         // product-1 fragments: 6 groups x 64 lanes x 4
 constexpr int E64_T2 = 1536;                      // product-2 fragments
 constexpr int E64_PCOL = 3072;                    // pcol[v*64 + 4c + e]  = P[v][4 chi(c) + e]
-constexpr int E64_PROW = 3072 + 4096;             // prow[u*64 + 4c + m]  = P[u][rho(4m + c%4, c/4)]
-constexpr int E64_TABLE_FLOATS = 3072 + 2 * 4096;
-// per-wavefront scratch: candidates {value bits, flat index} [CAP + 2], selected {flat, value bits} [64]
-constexpr int E64_SCRATCH_WORDS = 2 * (E64_CAP + 2) + 2 * 64;
+constexpr int E64_PK = 3072 + 4096;               // pk[u*16 + c]  = P[u][kappa(c)]       (reconstruction, quadruple bases)
+constexpr int E64_PK2 = 3072 + 4096 + 1024;       // pk2[u*16 + c] = P[u][31 - kappa(c)]  (odd u: the second member)
+constexpr int E64_TABLE_FLOATS = 3072 + 4096 + 2048;
+// per-wavefront scratch: candidates {value bits, flat index} [CAP + 2], selected {flat, value bits} by class [3][64]
+constexpr int E64_SCRATCH_WORDS = 2 * (E64_CAP + 2) + 3 * 2 * 64;
+__host__ __device__ constexpr int kappa64(int c) { return 4 * (c & 3) + (c >> 2); }
 constexpr int E64_LDS_BYTES = 4 * (E64_TABLE_FLOATS + E64_WAVES * E64_SCRATCH_WORDS);
 static_assert(E64_TABLE_FLOATS == kEnc64TableFloats, "table size");
 
@@ -68,11 +72,11 @@ void build_enc64_tables(const double* P, float* out) {
     }
   }
   for (int u = 0; u < 64; ++u)
-    for (int cc = 0; cc < 16; ++cc)
-      for (int x = 0; x < 4; ++x) {
-        out[E64_PCOL + u * 64 + 4 * cc + x] = Pm(u, 4 * chi(cc) + x);
-        out[E64_PROW + u * 64 + 4 * cc + x] = Pm(u, rho(4 * x + (cc & 3), cc >> 2));
-      }
+    for (int cc = 0; cc < 16; ++cc) {
+      for (int x = 0; x < 4; ++x) out[E64_PCOL + u * 64 + 4 * cc + x] = Pm(u, 4 * chi(cc) + x);
+      out[E64_PK + u * 16 + cc] = Pm(u, kappa64(cc));
+      out[E64_PK2 + u * 16 + cc] = Pm(u, 31 - kappa64(cc));
+    }
 }
 
 // the six values two butterfly levels make of a mirror quadruple (x[i], x[31-i], x[32+i], x[63-i])
@@ -91,15 +95,15 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   const float* sT1 = lds + E64_T1;
   const float* sT2 = lds + E64_T2;
   const float* sPcol = lds + E64_PCOL;
-  const float* sProw = lds + E64_PROW;
+  const float* sPk = lds + E64_PK;
+  const float* sPk2 = lds + E64_PK2;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
   uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + E64_TABLE_FLOATS) + wave * E64_SCRATCH_WORDS;
   uint2* cand = reinterpret_cast<uint2*>(scratch);                       // {value bits, flat index}
-  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (E64_CAP + 2));    // {flat index, value bits}, rank order
+  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (E64_CAP + 2));    // [3][64] {flat index, value bits} by class of u
   const int k = args.k;
-  const int kpad = (k + 3) & ~3;
 
   for (int e = tid; e < E64_TABLE_FLOATS / 4; e += E64_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
@@ -191,20 +195,28 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
 
     // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ------------------
     f32x4 D[4][4];
-    if (GBF16) {
+    // gs: coefficient of g; the multiplication is left out when it is 1 (the algorithm boxes' form)
+    auto momentum = [&](auto unit_scale) {
+      constexpr bool UNIT = decltype(unit_scale)::value;
+      const float gs = args.grad_scale;
+      if (GBF16) {
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], args.grad_scale * __uint_as_float(ng[q][0] << 16));
-        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], args.grad_scale * __uint_as_float(ng[q][0] & 0xffff0000u));
-        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], args.grad_scale * __uint_as_float(ng[q][1] << 16));
-        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], args.grad_scale * __uint_as_float(ng[q][1] & 0xffff0000u));
+        for (int q = 0; q < 16; ++q) {
+          const float g0 = __uint_as_float(ng[q][0] << 16), g1 = __uint_as_float(ng[q][0] & 0xffff0000u);
+          const float g2 = __uint_as_float(ng[q][1] << 16), g3 = __uint_as_float(ng[q][1] & 0xffff0000u);
+          D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], UNIT ? g0 : gs * g0);
+          D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], UNIT ? g1 : gs * g1);
+          D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], UNIT ? g2 : gs * g2);
+          D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], UNIT ? g3 : gs * g3);
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], UNIT ? ngf[q][e] : gs * ngf[q][e]);
       }
-    } else {
-#pragma unroll
-      for (int q = 0; q < 16; ++q)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], args.grad_scale * ngf[q][e]);
-    }
+    };
+    if (args.grad_scale == 1.0f) momentum(std::true_type{}); else momentum(std::false_type{});
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(0);
@@ -327,12 +339,24 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
         as_global(cur.idx)[po] = lane;
         as_global(cur.val)[po] = 0.f;
       }
-      if (lane < kpad) sel[lane] = make_uint2(0u, 0u);
       ncand = 0;
     }
     DEMO_PHASE(4);
     wave_lds_sync();
-    // (3) rank candidates (magnitude descending, flat index ascending); ranks < k are the payload
+    // (3) rank candidates (magnitude descending, flat index ascending); ranks < k are the payload.  The selected
+    //     coefficients are also listed by the class of their row frequency u (0: u = 0 mod 4, 1: u = 2 mod 4,
+    //     2: u odd) for the reconstruction; ncls[] counts them (uniform).
+    int ncls[3] = {0, 0, 0};
+    auto file_selected = [&](bool selected, uint32_t flat, uint32_t vbits) {
+      const uint32_t u = flat >> 6;
+      const int cls = (u & 1u) ? 2 : (int)((u >> 1) & 1u);
+#pragma unroll
+      for (int q = 0; q < 3; ++q) {
+        const uint64_t m = __ballot(selected && cls == q);
+        if (selected && cls == q) sel[q * 64 + ncls[q] + lanes_below(m)] = make_uint2(flat, vbits);
+        ncls[q] += __popcll(m);
+      }
+    };
     if (all_zero || skip) {
     } else if (ncand <= 64) {
       // one candidate per lane; the others' keys come through v_readlane, four per trip (lanes past
@@ -349,17 +373,20 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
           rank += kj > key ? 1 : 0;
         }
       }
-      if (lane < ncand && rank < k) {
+      const bool selected = lane < ncand && rank < k;
+      if (selected) {
         const int64_t po = (int64_t)cc * k + rank;
         as_global(cur.idx)[po] = (int32_t)me.y;
         as_global(cur.val)[po] = __uint_as_float(me.x);
-        sel[rank] = make_uint2(me.y, me.x);
       }
+      file_selected(selected, me.y, me.x);
     } else {
       if (lane == 0 && (ncand & 1)) cand[ncand] = make_uint2(0u, 0xffffffffu);
       wave_lds_sync();
-      for (int i = lane; i < ncand; i += 64) {
-        const uint2 me = cand[i];
+      for (int base = 0; base < ncand; base += 64) {   // uniform trip count: the ballots below need every lane
+        const int i = base + lane;
+        const bool valid = i < ncand;
+        const uint2 me = cand[valid ? i : 0];
         const uint32_t mag = me.x & 0x7fffffffu;
         int rank = 0;
         for (int j = 0; j < ncand; j += 2) {
@@ -368,35 +395,108 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
           rank += (m0 > mag || (m0 == mag && o.y < me.y)) ? 1 : 0;
           rank += (m1 > mag || (m1 == mag && o.w < me.y)) ? 1 : 0;
         }
-        if (rank < k) {
+        const bool selected = valid && rank < k;
+        if (selected) {
           const int64_t po = (int64_t)cc * k + rank;
           as_global(cur.idx)[po] = (int32_t)me.y;
           as_global(cur.val)[po] = __uint_as_float(me.x);
-          sel[rank] = make_uint2(me.y, me.x);
         }
+        file_selected(selected, me.y, me.x);
       }
     }
-    if (lane >= k && lane < kpad) sel[lane] = make_uint2(0u, 0u);
+    // each class list is padded with zero-valued entries to a multiple of four (one MFMA step holds four)
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+      if (lane < ((4 - (ncls[q] & 3)) & 3)) sel[q * 64 + ncls[q] + lane] = make_uint2(0u, 0u);
     wave_lds_sync();
-    fetch_g(nxt);   // the coefficient registers are dead now
+    if (GBF16) fetch_g(nxt);   // the coefficient registers are dead now (fp32 gradients: twice the registers, see below)
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(5);
-    // ---- reconstruction accumulated into D: D -= sum_t val_t P[u_t][i] P[v_t][j] ----------------
-    for (int ks = 0; ks < (skip ? 0 : kpad / 4); ++ks) {
-      const uint2 sv = sel[4 * ks + g];
-      const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
-      const float nv = -(args.alpha * __uint_as_float(sv.y));
-      const float4 pa = *reinterpret_cast<const float4*>(&sProw[u * 64 + 4 * c]);
-      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[v * 64 + 4 * c]);
-      const float af[4] = {nv * pa.x, nv * pa.y, nv * pa.z, nv * pa.w};
-      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+    // ---- reconstruction  D -= alpha * sum_t val_t P[u_t][i] P[v_t][j]  on the quadruple bases only: by the
+    //      mirror symmetries of the rows of P (see demo_dec64.hip) the four rows {i0, 31-i0, 32+i0, 63-i0} of a
+    //      term differ by signs fixed by the class of u_t, so each class accumulates one 16-row tile per column
+    //      tile (two for odd u: i0 and 31-i0) instead of four, and the members follow from in-lane adds:
+    //        D[i0] += ee+eo+o0, D[31-i0] += ee-eo+o1, D[32+i0] += ee-eo-o1, D[63-i0] += ee+eo-o0.
+    //      MFMA row m = 4g + r of a compact tile is the base i0 = kappa(m) = 4r + g, i.e. component s = r of D.
+    //      The classes are done one after the other so that at most two compact accumulators are alive.
+    if (!skip) {
+      {
+        f32x4 Ree[4];
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+        for (int e = 0; e < 4; ++e) Ree[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < (ncls[0] + 3) / 4; ++ks) {
+          const uint2 sv = sel[0 * 64 + 4 * ks + g];
+          const float nv = -(args.alpha * __uint_as_float(sv.y));
+          const float a = nv * sPk[((sv.x >> 6) & 63u) * 16 + c];
+          const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+          const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) D[mt][e] = mfma4(af[mt], bf[e], D[mt][e]);
+          for (int e = 0; e < 4; ++e) Ree[e] = mfma4(a, bf[e], Ree[e]);
+        }
+#pragma unroll
+        for (int sq = 0; sq < 4; ++sq)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) D[sq][e][w] += Ree[e][sq];
+      }
+      {
+        f32x4 Reo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Reo[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < (ncls[1] + 3) / 4; ++ks) {
+          const uint2 sv = sel[1 * 64 + 4 * ks + g];
+          const float nv = -(args.alpha * __uint_as_float(sv.y));
+          const float a = nv * sPk[((sv.x >> 6) & 63u) * 16 + c];
+          const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+          const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) Reo[e] = mfma4(a, bf[e], Reo[e]);
+        }
+#pragma unroll
+        for (int sq = 0; sq < 4; ++sq)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            D[sq][e][0] += Reo[e][sq];
+            D[sq][e][1] -= Reo[e][sq];
+            D[sq][e][2] -= Reo[e][sq];
+            D[sq][e][3] += Reo[e][sq];
+          }
+      }
+      {
+        f32x4 Ro0[4], Ro1[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          Ro0[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          Ro1[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+        for (int ks = 0; ks < (ncls[2] + 3) / 4; ++ks) {
+          const uint2 sv = sel[2 * 64 + 4 * ks + g];
+          const float nv = -(args.alpha * __uint_as_float(sv.y));
+          const uint32_t ur = ((sv.x >> 6) & 63u) * 16 + c;
+          const float a0 = nv * sPk[ur], a1 = nv * sPk2[ur];
+          const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+          const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            Ro0[e] = mfma4(a0, bf[e], Ro0[e]);
+            Ro1[e] = mfma4(a1, bf[e], Ro1[e]);
+          }
+        }
+#pragma unroll
+        for (int sq = 0; sq < 4; ++sq)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            D[sq][e][0] += Ro0[e][sq];
+            D[sq][e][1] += Ro1[e][sq];
+            D[sq][e][2] -= Ro1[e][sq];
+            D[sq][e][3] -= Ro0[e][sq];
+          }
+      }
     }
 
+    if (!GBF16) fetch_g(nxt);   // 64 registers: requested once the compact accumulators are dead
     DEMO_PHASE(6);
     // ---- store the residual momentum -------------------------------------------------------------
     if (!skip) {

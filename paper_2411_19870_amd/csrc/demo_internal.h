@@ -90,7 +90,7 @@ hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const
 hipError_t launch_copy_probe(const void* src, void* dst, size_t nbytes, int num_cus, hipStream_t stream);
 
 // s = 64 wavefront-per-chunk kernels (demo_enc64.hip, demo_dec64.hip).
-constexpr int kEnc64TableFloats = 3072 + 2 * 4096;
+constexpr int kEnc64TableFloats = 3072 + 4096 + 2048;
 constexpr int kDec64TableFloats = 4096 + 1536 + 4096;
 constexpr int kFast64MaxK = 64;
 void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
