@@ -18,9 +18,10 @@ constexpr int ED_CAP = 128;                       // candidate list capacity per
 constexpr int ED_T1 = 0;                          // t1[(q*64 + lane)*4 + nt]      = B[16nt + c][rho(q, g)]
 constexpr int ED_T2 = 4096;                       // t2[((4e+r)*64 + lane)*4 + mt] = B[16mt + c][4 chi(4g+r) + e]
 constexpr int ED_PCOL = 2 * 4096;                 // pcol[v*64 + 4c + e] = B[v][4 chi(c) + e]
-constexpr int ED_PROW = 3 * 4096;                 // prow[u*64 + 4c + m] = B[u][rho(4m + c%4, c/4)]
-constexpr int ED_TABLE_FLOATS = 4 * 4096;
-constexpr int ED_SELMAX = 4 * 64;                 // selected coefficients of a tile (4 chunks x k <= 64)
+constexpr int ED_PK = 3 * 4096;                   // pk[u*16 + c] = B[u][kappa(c)], u < 32 (= P32[u][kappa(c)]: reconstruction)
+constexpr int ED_TABLE_FLOATS = 3 * 4096 + 512;
+constexpr int ED_SELCLS = 2 * 64;                 // selected coefficients per class (row block, parity of u): 2 chunks x k <= 64
+constexpr int ED_SELMAX = 4 * ED_SELCLS;
 // per-wavefront scratch: candidates {value bits, flat} [CAP + 2], selected {position in tile, value bits} [SELMAX]
 constexpr int ED_SCRATCH_WORDS = 2 * (ED_CAP + 2) + 2 * ED_SELMAX;
 constexpr int ED_LDS_BYTES = 4 * (ED_TABLE_FLOATS + ED_WAVES * ED_SCRATCH_WORDS);
@@ -41,10 +42,9 @@ void build_enc64d_tables(const double* Bm, float* out) {
   }
   for (int u = 0; u < 64; ++u)
     for (int cc = 0; cc < 16; ++cc)
-      for (int x = 0; x < 4; ++x) {
-        out[ED_PCOL + u * 64 + 4 * cc + x] = Bf(u, 4 * chi(cc) + x);
-        out[ED_PROW + u * 64 + 4 * cc + x] = Bf(u, rho(4 * x + (cc & 3), cc >> 2));
-      }
+      for (int x = 0; x < 4; ++x) out[ED_PCOL + u * 64 + 4 * cc + x] = Bf(u, 4 * chi(cc) + x);
+  for (int u = 0; u < 32; ++u)
+    for (int cc = 0; cc < 16; ++cc) out[ED_PK + u * 16 + cc] = Bf(u, 4 * (cc & 3) + (cc >> 2));
 }
 
 // The table `tv` lists the order-2 tensors in units of 64 x 64 tiles (cchunks = cols / 64,
@@ -57,15 +57,14 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   const float* sT1 = lds + ED_T1;
   const float* sT2 = lds + ED_T2;
   const float* sPcol = lds + ED_PCOL;
-  const float* sProw = lds + ED_PROW;
+  const float* sPk = lds + ED_PK;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
   uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + ED_TABLE_FLOATS) + wave * ED_SCRATCH_WORDS;
   uint2* cand = reinterpret_cast<uint2*>(scratch);                      // {value bits, flat index in the chunk}
-  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (ED_CAP + 2));    // {row*64 + col in the tile's coefficient plane, value bits}
+  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (ED_CAP + 2));    // [4][SELCLS] {u*64 + tile column frequency, value bits} by class
   const int k = args.k;
-  const int kpad = (k + 3) & ~3;
 
   for (int e = tid; e < ED_TABLE_FLOATS / 4; e += ED_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
@@ -221,7 +220,7 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
     // ---- top-k, once per chunk (bu, bv): coefficients C2[2bv + mh][2bu + nh][r] ---------------------------
     asm volatile("" : "+v"(fb));
     bool skip = false;
-    int nsel = 0;   // entries written to `sel` so far (kpad per chunk)
+    int ncls[4] = {0, 0, 0, 0};   // selected coefficients per class 2 bu + (u % 2) (uniform)
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
       const int bu = sub >> 1, bv = sub & 1;
@@ -270,7 +269,6 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
           as_global(cur.idx)[po] = lane;
           as_global(cur.val)[po] = 0.f;
         }
-        if (lane < kpad) sel[nsel + lane] = make_uint2(0u, 0u);
       } else if (!overflow) {
         // rank the candidates (magnitude descending, flat index ascending); ranks < k are the payload
         for (int i0 = 0; i0 < ncand; i0 += 64) {
@@ -296,18 +294,24 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
               rank += (mo > mag || (mo == mag && o.y < me.y)) ? 1 : 0;
             }
           }
-          if (i < ncand && rank < k) {
+          const bool selected = i < ncand && rank < k;
+          if (selected) {
             const int64_t po = (int64_t)c32 * k + rank;
             as_global(cur.idx)[po] = (int32_t)me.y;
             as_global(cur.val)[po] = __uint_as_float(me.x);
-            // position in the tile's coefficient plane: (32bu + u)*64 + 32bv + v
-            const uint32_t u = me.y >> 5, v = me.y & 31u;
-            sel[nsel + rank] = make_uint2((32 * bu + u) * 64 + 32 * bv + v, me.x);
+          }
+          // filed for the reconstruction by class: {local row frequency u, column frequency 32 bv + v of the tile}
+          const uint32_t u = me.y >> 5, v = me.y & 31u;
+#pragma unroll
+          for (int par = 0; par < 2; ++par) {
+            const int q = 2 * bu + par;
+            const uint64_t m = __ballot(selected && (int)(u & 1u) == par);
+            if (selected && (int)(u & 1u) == par)
+              sel[q * ED_SELCLS + ncls[q] + lanes_below(m)] = make_uint2(u * 64 + 32 * bv + v, me.x);
+            ncls[q] += __popcll(m);
           }
         }
-        if (lane >= k && lane < kpad) sel[nsel + lane] = make_uint2(0u, 0u);
       }
-      nsel += kpad;
       wave_lds_sync();
     }
     if (skip) {
@@ -317,23 +321,45 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
         wl.list[atomicAdd(wl.count, 1)] = prefix32[cur.tix] + c32;   // chunk number in the 32-grid table
       }
     }
-    fetch_g(nxt);   // the coefficient registers are dead now
+    if (GBF16) fetch_g(nxt);   // the coefficient registers are dead now (fp32 gradients: after the reconstruction)
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- reconstruction accumulated into D over all selected coefficients of the tile ----------------
-    for (int ks = 0; ks < (skip ? 0 : nsel / 4); ++ks) {
-      const uint2 sv = sel[4 * ks + g];
-      const int u = (int)((sv.x >> 6) & 63u), v = (int)(sv.x & 63u);
-      const float nv = -(args.alpha * __uint_as_float(sv.y));
-      const float4 pa = *reinterpret_cast<const float4*>(&sProw[u * 64 + 4 * c]);
-      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[v * 64 + 4 * c]);
-      const float af[4] = {nv * pa.x, nv * pa.y, nv * pa.z, nv * pa.w};
-      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+    // ---- reconstruction on the quadruple bases: a term of chunk (bu, bv) with local row frequency u touches the
+    //      rows of block bu only, and P32[u][31-i0] = +-P32[u][i0] by the parity of u, so each class (bu, parity)
+    //      accumulates one 16-row tile per column tile (rows i0 = kappa(m)) and the two members of block bu follow:
+    //        D[32 bu + i0] += R,  D[32 bu + 31 - i0] += R (u even) or -= R (u odd).
+    //      The column side is the block-diagonal matrix as before (rows of B vanish outside their block).
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+    for (int q = 0; q < 4; ++q)   // pad every class list with zero-valued entries to a multiple of four
+      if (lane < ((4 - (ncls[q] & 3)) & 3)) sel[q * ED_SELCLS + ncls[q] + lane] = make_uint2(0u, 0u);
+    wave_lds_sync();
+    if (!skip) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) D[mt][e] = mfma4(af[mt], bf[e], D[mt][e]);
+      for (int q = 0; q < 4; ++q) {
+        f32x4 R[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) R[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < (ncls[q] + 3) / 4; ++ks) {
+          const uint2 sv = sel[q * ED_SELCLS + 4 * ks + g];
+          const float nv = -(args.alpha * __uint_as_float(sv.y));
+          const float a = nv * sPk[(sv.x >> 6) * 16 + c];
+          const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+          const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) R[e] = mfma4(a, bf[e], R[e]);
+        }
+        const int w0 = 2 * (q >> 1);
+#pragma unroll
+        for (int sq = 0; sq < 4; ++sq)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            D[sq][e][w0] += R[e][sq];
+            if (q & 1) D[sq][e][w0 + 1] -= R[e][sq];
+            else D[sq][e][w0 + 1] += R[e][sq];
+          }
+      }
     }
+    if (!GBF16) fetch_g(nxt);
     if (!skip) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
