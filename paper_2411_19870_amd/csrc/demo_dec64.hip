@@ -40,8 +40,9 @@ constexpr int D64_TILE_FLOATS = 64 * D64_LDT;
 constexpr int D64_PCOL = 0;                        // pcol[v*64 + 4c + e] = P[v][4 chi(c) + e]       (sparse kernel)
 constexpr int D64_G = 4096;                        // fragment table G of the dense kernel
 constexpr int D64_G_FLOATS = 1536;
-constexpr int D64_PROW = 4096 + 1536;              // prow[u*64 + 4c + m] = P[u][rho(4m + c%4, c/4)] (sparse kernel)
-constexpr int D64_ALL_TABLE_FLOATS = 4096 + 1536 + 4096;
+constexpr int D64_PK = 4096 + 1536;                // pk[u*16 + c]  = P[u][kappa(c)]       (sparse kernel: quadruple bases)
+constexpr int D64_PK2 = 4096 + 1536 + 1024;        // pk2[u*16 + c] = P[u][31 - kappa(c)]  (odd u: the second member)
+constexpr int D64_ALL_TABLE_FLOATS = 4096 + 1536 + 2048;
 constexpr int D64_LDS_BYTES = 4 * (D64_G_FLOATS + D64_WAVES * D64_TILE_FLOATS);
 static_assert(D64_ALL_TABLE_FLOATS == kDec64TableFloats, "table size");
 static_assert(D64_LDS_BYTES <= 160 * 1024, "LDS budget");
@@ -59,10 +60,12 @@ void build_dec64_tables(const double* P, float* out) {
   auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
   for (int v = 0; v < 64; ++v)
     for (int cc = 0; cc < 16; ++cc)
-      for (int e = 0; e < 4; ++e) {
-        out[D64_PCOL + v * 64 + 4 * cc + e] = Pm(v, 4 * chi(cc) + e);
-        out[D64_PROW + v * 64 + 4 * cc + e] = Pm(v, rho(4 * e + (cc & 3), cc >> 2));
-      }
+      for (int e = 0; e < 4; ++e) out[D64_PCOL + v * 64 + 4 * cc + e] = Pm(v, 4 * chi(cc) + e);
+  for (int u = 0; u < 64; ++u)
+    for (int cc = 0; cc < 16; ++cc) {
+      out[D64_PK + u * 16 + cc] = Pm(u, kappa(cc));
+      out[D64_PK2 + u * 16 + cc] = Pm(u, 31 - kappa(cc));
+    }
   // G: lane (g, c), component r.  The contraction index of k-slot g at step r is 4 (4 g + r) + class,
   // the other index is kappa(c) (groups 0..3) or 31 - kappa(c) (groups 4, 5: odd classes only).
   for (int lane = 0; lane < 64; ++lane) {
@@ -364,33 +367,36 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 
 // ---------------------------------------------------------------------------
 // Few pairs per chunk (W * k <= 64, e.g. a worker decoding its own payload): no coefficient tile.
-// R = sum_p val_p P[u_p]^T P[v_p] is one MFMA chain of contraction length W*k whose operands are
-// gathered rows of P, exactly like the reconstruction of the encode kernel; pairs of different
-// workers that hit the same coefficient simply add up inside the chain.
+// R = sum_p val_p P[u_p]^T P[v_p] is accumulated by MFMA chains whose operands are gathered rows of P, as in the
+// reconstruction of the encode kernel: the pairs are filed by the class of u (0 mod 4, 2 mod 4, odd), each class
+// accumulates one 16-row tile per column tile on the quadruple bases (two for odd u), and the four members of a
+// quadruple follow from in-lane adds.  Pairs of different workers that hit the same coefficient simply add up.
 // ---------------------------------------------------------------------------
 namespace {
-constexpr int D64S_WAVES = 4;                     // three workgroups per CU (registers allow 3 wavefronts per SIMD)
+constexpr int D64S_WAVES = 4;                     // three workgroups per CU (3 wavefronts per SIMD)
 constexpr int D64S_THREADS = D64S_WAVES * 64;
-constexpr int D64S_LDS_BYTES = 4 * (2 * 4096 + D64S_WAVES * 2 * 64);
+constexpr int D64S_TABLE_FLOATS = 4096 + 2048;    // pcol, pk, pk2
+constexpr int D64S_LDS_BYTES = 4 * (D64S_TABLE_FLOATS + D64S_WAVES * 3 * 2 * 64);   // + three class lists per wavefront
 }  // namespace
 
 template <bool PBF16>
 __global__ __launch_bounds__(D64S_THREADS, 3) void decode2d_sparse64(TableView tv, const float* __restrict__ tables,
-                                                                  DecodeArgs args) {
+                                                                     DecodeArgs args) {
   extern __shared__ float lds[];
   const float* sPcol = lds;
-  const float* sProw = lds + 4096;
+  const float* sPk = lds + 4096;
+  const float* sPk2 = lds + 4096 + 1024;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
-  uint2* sel = reinterpret_cast<uint2*>(lds + 2 * 4096) + wave * 64;   // {flat index, value bits}
+  uint2* sel = reinterpret_cast<uint2*>(lds + D64S_TABLE_FLOATS) + wave * 3 * 64;   // [3][64] {flat index, value bits}
   const int k = args.k, W = args.W;
-  const int npairs = W * k, npad = (npairs + 3) & ~3;
+  const int npairs = W * k;
 
-  for (int e = tid; e < 4096 / 4; e += D64S_THREADS) {
+  for (int e = tid; e < 4096 / 4; e += D64S_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + D64_PCOL)[e];
-    reinterpret_cast<float4*>(lds + 4096)[e] = reinterpret_cast<const float4*>(tables + D64_PROW)[e];
-  }
+  for (int e = tid; e < 2048 / 4; e += D64S_THREADS)
+    reinterpret_cast<float4*>(lds + 4096)[e] = reinterpret_cast<const float4*>(tables + D64_PK)[e];
   __syncthreads();
 
   const int nwaves = gridDim.x * D64S_WAVES;
@@ -432,10 +438,20 @@ __global__ __launch_bounds__(D64S_THREADS, 3) void decode2d_sparse64(TableView t
       if (PBF16) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
       else Xf[q] = bload_f4(xres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(q) * ucols * 4);
     }
-    // pairs of this chunk -> LDS (out-of-range indices contribute nothing)
+    // pairs of this chunk -> class lists in LDS (out-of-range indices contribute nothing), padded with zero-valued
+    // entries to a multiple of four
+    int ncls[3];
     {
       const bool ok = (uint32_t)pi < 4096u;
-      sel[lane] = make_uint2(ok ? (uint32_t)pi : 0u, ok ? __float_as_uint(pv) : 0u);
+      const uint32_t u = ((uint32_t)pi >> 6) & 63u;
+      const int cls = (u & 1u) ? 2 : (int)((u >> 1) & 1u);
+#pragma unroll
+      for (int q = 0; q < 3; ++q) {
+        const uint64_t m = __ballot(ok && cls == q);
+        ncls[q] = __popcll(m);
+        if (ok && cls == q) sel[q * 64 + lanes_below(m)] = make_uint2((uint32_t)pi, __float_as_uint(pv));
+        if (lane < ((4 - (ncls[q] & 3)) & 3)) sel[q * 64 + ncls[q] + lane] = make_uint2(0u, 0u);
+      }
     }
     wave_lds_sync();
     // pair of the next chunk (after the last chunk the same one again: keeps the old registers dead)
@@ -451,53 +467,76 @@ __global__ __launch_bounds__(D64S_THREADS, 3) void decode2d_sparse64(TableView t
       load_pair(d, cc);
     }
 
-    f32x4 R[4][4];
+    // compact accumulators: component s of tile e is the quadruple base i0 = 4s + g, column 4 chi(c) + e
+    f32x4 Ree[4], Reo[4], Ro0[4], Ro1[4];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) R[mt][e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    // operands of step ks + 1 (pair, then the two rows of P it names) are read while the MFMAs of step ks run
-    const int nks = npad / 4;
-    uint2 sv = sel[g];
-    float4 pa = *reinterpret_cast<const float4*>(&sProw[((sv.x >> 6) & 63u) * 64 + 4 * c]);
-    float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
-    for (int ks = 0; ks < nks; ++ks) {
-      const float val = __uint_as_float(sv.y);
-      const float af[4] = {val * pa.x, val * pa.y, val * pa.z, val * pa.w};
-      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
-      if (ks + 1 < nks) {
-        sv = sel[4 * (ks + 1) + g];
-        pa = *reinterpret_cast<const float4*>(&sProw[((sv.x >> 6) & 63u) * 64 + 4 * c]);
-        pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
-      }
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) R[mt][e] = mfma4(af[mt], bf[e], R[mt][e]);
+    for (int e = 0; e < 4; ++e) {
+      Ree[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      Reo[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      Ro0[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      Ro1[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
-
-    // x <- x - lr*(sgn(R) + wd*x); R[mt][e][r] is the element (row rho(4mt + r, g), col 4 chi(c) + e)
+    for (int ks = 0; ks < (ncls[0] + 3) / 4; ++ks) {
+      const uint2 sv = sel[0 * 64 + 4 * ks + g];
+      const float a = __uint_as_float(sv.y) * sPk[((sv.x >> 6) & 63u) * 16 + c];
+      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      float o[4];
+      for (int e = 0; e < 4; ++e) Ree[e] = mfma4(a, bf[e], Ree[e]);
+    }
+    for (int ks = 0; ks < (ncls[1] + 3) / 4; ++ks) {
+      const uint2 sv = sel[1 * 64 + 4 * ks + g];
+      const float a = __uint_as_float(sv.y) * sPk[((sv.x >> 6) & 63u) * 16 + c];
+      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) Reo[e] = mfma4(a, bf[e], Reo[e]);
+    }
+    for (int ks = 0; ks < (ncls[2] + 3) / 4; ++ks) {
+      const uint2 sv = sel[2 * 64 + 4 * ks + g];
+      const uint32_t ur = ((sv.x >> 6) & 63u) * 16 + c;
+      const float a0 = __uint_as_float(sv.y) * sPk[ur], a1 = __uint_as_float(sv.y) * sPk2[ur];
+      const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+      const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float x;
-        if (PBF16) {
-          const uint32_t raw = Xh[q][e >> 1];
-          x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
-        } else {
-          x = Xf[q][e];
-        }
-        o[e] = sign_update(x, sgnf(R[q >> 2][e][q & 3]), args.lr, args.weight_decay);
+        Ro0[e] = mfma4(a0, bf[e], Ro0[e]);
+        Ro1[e] = mfma4(a1, bf[e], Ro1[e]);
       }
-      const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
-      if (PBF16) {
-        const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-        bstore_u2(xres, vo * 2, so * 2, pk);
-      } else {
-        const f32x4 ov = {o[0], o[1], o[2], o[3]};
-        bstore_f4(xres, vo * 4, so * 4, ov);
+    }
+
+    // x <- x - lr*(sgn(R) + wd*x); members of the quadruple with base 4s + g: rows rho(4s + w, g)
+#pragma unroll
+    for (int sq = 0; sq < 4; ++sq) {
+      float o[4][4];   // [w][e]
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float t1 = Ree[e][sq] + Reo[e][sq], t2 = Ree[e][sq] - Reo[e][sq];
+        const float rr[4] = {t1 + Ro0[e][sq], t2 + Ro1[e][sq], t2 - Ro1[e][sq], t1 - Ro0[e][sq]};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const int q = 4 * sq + w;
+          float x;
+          if (PBF16) {
+            const uint32_t raw = Xh[q][e >> 1];
+            x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+          } else {
+            x = Xf[q][e];
+          }
+          o[w][e] = sign_update(x, sgnf(rr[w]), args.lr, args.weight_decay);
+        }
+      }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int q = 4 * sq + w;
+        const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
+        if (PBF16) {
+          const u32x2 pk = {pack_bf16x2(o[w][0], o[w][1]), pack_bf16x2(o[w][2], o[w][3])};
+          bstore_u2(xres, vo * 2, so * 2, pk);
+        } else {
+          const f32x4 ov = {o[w][0], o[w][1], o[w][2], o[w][3]};
+          bstore_f4(xres, vo * 4, so * 4, ov);
+        }
       }
     }
     wave_lds_sync();
@@ -514,7 +553,7 @@ static hipError_t launch_dec_sparse64(const TableView& tv, const float* tables, 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  int64_t grid = (int64_t)num_cus * 3;
+  int64_t grid = (int64_t)num_cus * (PBF16 ? 4 : 3);   // workgroups per CU the registers allow
   const int64_t max_grid = ((int64_t)tv.total_chunks + D64S_WAVES - 1) / D64S_WAVES;
   if (grid > max_grid) grid = max_grid;
   hipLaunchKernelGGL(decode2d_sparse64<PBF16>, dim3((unsigned)grid), dim3(D64S_THREADS), D64S_LDS_BYTES, stream, tv,

@@ -91,7 +91,7 @@ hipError_t launch_copy_probe(const void* src, void* dst, size_t nbytes, int num_
 
 // s = 64 wavefront-per-chunk kernels (demo_enc64.hip, demo_dec64.hip).
 constexpr int kEnc64TableFloats = 3072 + 4096 + 2048;
-constexpr int kDec64TableFloats = 4096 + 1536 + 4096;
+constexpr int kDec64TableFloats = 4096 + 1536 + 2048;
 constexpr int kFast64MaxK = 64;
 void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
 void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
