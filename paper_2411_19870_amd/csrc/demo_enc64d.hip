@@ -1,12 +1,12 @@
-// Dense-basis variant of the wavefront-per-tile encode kernel.
+// s = 32 encode kernel: one wavefront per 64 x 64 tile = 2 x 2 chunks.
 //
-// Same ownership, register layout, prefetch and in-wavefront top-k as demo_enc64.hip, but the two
-// products are plain dense MFMA chains against an arbitrary 64 x 64 basis B (fragments in LDS), so the
-// kernel does not depend on the symmetries of the 64-point DCT.  It is used for chunk size s = 32:
-// a wavefront owns a 64 x 64 tile = 2 x 2 chunks and B = diag(P32, P32); products with the zero
-// blocks are skipped at compile time (128 MFMAs per product), top-k runs once per chunk on the 16
-// coefficients each lane holds of it, and the reconstruction contracts over all 4k selected
-// coefficients at once (rows of B vanish outside their own chunk, so no masking is needed).
+// Same ownership, register layout, prefetch and in-wavefront top-k as demo_enc64.hip.  The tile is transformed
+// with the block-diagonal matrix diag(P32, P32), and the mirror symmetry of the 32-point DCT (even rows even,
+// odd rows odd under i -> 31-i) halves both products once more: a mirror quadruple {i0, 31-i0, 32+i0, 63-i0}
+// holds one pair of each block, the in-lane sums and differences of the pairs feed four MFMA chains -- one per
+// class (block, parity) of 16 frequencies -- of contraction length 16 (64 MFMAs per product).  Top-k runs once
+// per chunk on the 16 coefficients each lane holds of it, and the reconstruction accumulates, per class of the
+// row frequency, the rows of the quadruple bases only (see demo_enc64.hip).
 #include "demo_device.h"
 
 namespace demo {
@@ -15,11 +15,11 @@ namespace {
 constexpr int ED_WAVES = 8;
 constexpr int ED_THREADS = ED_WAVES * 64;
 constexpr int ED_CAP = 128;                       // candidate list capacity per wavefront
-constexpr int ED_T1 = 0;                          // t1[(q*64 + lane)*4 + nt]      = B[16nt + c][rho(q, g)]
-constexpr int ED_T2 = 4096;                       // t2[((4e+r)*64 + lane)*4 + mt] = B[16mt + c][4 chi(4g+r) + e]
-constexpr int ED_PCOL = 2 * 4096;                 // pcol[v*64 + 4c + e] = B[v][4 chi(c) + e]
-constexpr int ED_PK = 3 * 4096;                   // pk[u*16 + c] = B[u][kappa(c)], u < 32 (= P32[u][kappa(c)]: reconstruction)
-constexpr int ED_TABLE_FLOATS = 3 * 4096 + 512;
+constexpr int ED_T1 = 0;                          // t1[(par*64 + lane)*4 + s] = P32[2c + par][4s + g]  (product 1, B operand)
+constexpr int ED_T2 = 512;                        // t2[(par*64 + lane)*4 + s] = P32[2c + par][4g + s]  (product 2, A operand)
+constexpr int ED_PCOL = 1024;                     // pcol[v*64 + 4c + e] = B[v][4 chi(c) + e]
+constexpr int ED_PK = 1024 + 4096;                // pk[u*16 + c] = B[u][kappa(c)], u < 32 (= P32[u][kappa(c)]: reconstruction)
+constexpr int ED_TABLE_FLOATS = 1024 + 4096 + 512;
 constexpr int ED_SELCLS = 2 * 64;                 // selected coefficients per class (row block, parity of u): 2 chunks x k <= 64
 constexpr int ED_SELMAX = 4 * ED_SELCLS;
 // per-wavefront scratch: candidates {value bits, flat} [CAP + 2], selected {position in tile, value bits} [SELMAX]
@@ -31,15 +31,14 @@ static_assert(ED_TABLE_FLOATS == kEnc64dTableFloats, "table size");
 // Host: fragment tables from a 64 x 64 basis B (double, row-major, rows = frequencies).
 void build_enc64d_tables(const double* Bm, float* out) {
   auto Bf = [&](int u, int i) { return (float)Bm[u * 64 + i]; };
-  for (int lane = 0; lane < 64; ++lane) {
-    const int g = lane >> 4, c = lane & 15;
-    for (int q = 0; q < 16; ++q)
-      for (int nt = 0; nt < 4; ++nt) out[ED_T1 + (q * 64 + lane) * 4 + nt] = Bf(16 * nt + c, rho(q, g));
-    for (int e = 0; e < 4; ++e)
-      for (int r = 0; r < 4; ++r)
-        for (int mt = 0; mt < 4; ++mt)
-          out[ED_T2 + ((4 * e + r) * 64 + lane) * 4 + mt] = Bf(16 * mt + c, 4 * chi(4 * g + r) + e);
-  }
+  for (int par = 0; par < 2; ++par)
+    for (int lane = 0; lane < 64; ++lane) {
+      const int g = lane >> 4, c = lane & 15;
+      for (int s = 0; s < 4; ++s) {
+        out[ED_T1 + (par * 64 + lane) * 4 + s] = Bf(2 * c + par, 4 * s + g);
+        out[ED_T2 + (par * 64 + lane) * 4 + s] = Bf(2 * c + par, 4 * g + s);
+      }
+    }
   for (int u = 0; u < 64; ++u)
     for (int cc = 0; cc < 16; ++cc)
       for (int x = 0; x < 4; ++x) out[ED_PCOL + u * 64 + 4 * cc + x] = Bf(u, 4 * chi(cc) + x);
@@ -80,8 +79,8 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   TensorDev d = load_desc_uniform(tv, t);
 
   const int col4 = 4 * chi(c);
-  // flat index inside a chunk of coefficient C2[mt][nt][r]: (16(nt&1) + c)*32 + 16(mt&1) + 4g + r
-  uint32_t fb = (uint32_t)(32 * c + 4 * g);
+  // flat index inside a chunk of coefficient C2[vt][tt][r]: u*32 + v with u = 2c + tt%2, v = 2(4g + r) + vt%2
+  uint32_t fb = (uint32_t)(64 * c + 8 * g);
 
   struct Place {
     __amdgpu_buffer_rsrc_t mres, gres;
@@ -162,54 +161,52 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- product 1: C1[e][nt] rows j = 4 chi(4g+r) + e, cols U = 16nt + c.  Rows rho(q, g) with
-    //      q%4 < 2 lie in the upper chunks, the others in the lower ones: only the matching half of
-    //      the frequency tiles is non-zero.
+    // ---- product 1: C1[e][tt] rows j = 4 chi(4g+r) + e, cols: frequency u = 2c + tt%2 of row block tt/2.
+    //      k-slot g of step s contracts the pair base i0 = 4s + g: sums feed the even, differences the odd class.
     f32x4 C1[4][4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) C1[e][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int tt = 0; tt < 4; ++tt) C1[e][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     {
-      float4 pn = *reinterpret_cast<const float4*>(&sT1[lane * 4]);
+      const float4 pe4 = *reinterpret_cast<const float4*>(&sT1[(0 * 64 + lane) * 4]);
+      const float4 po4 = *reinterpret_cast<const float4*>(&sT1[(1 * 64 + lane) * 4]);
+      const float pe[4] = {pe4.x, pe4.y, pe4.z, pe4.w}, po[4] = {po4.x, po4.y, po4.z, po4.w};
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const float pf[4] = {pn.x, pn.y, pn.z, pn.w};
-        if (q + 1 < 16) pn = *reinterpret_cast<const float4*>(&sT1[((q + 1) * 64 + lane) * 4]);
-        const int br = (q & 3) >> 1;
+      for (int s = 0; s < 4; ++s) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int nh = 0; nh < 2; ++nh) {
-            const int nt = 2 * br + nh;
-            C1[e][nt] = mfma4(D[q >> 2][e][q & 3], pf[nt], C1[e][nt]);
-          }
+        for (int e = 0; e < 4; ++e) {
+          const float x0 = D[s][e][0], x1 = D[s][e][1], x2 = D[s][e][2], x3 = D[s][e][3];
+          C1[e][0] = mfma4(x0 + x1, pe[s], C1[e][0]);
+          C1[e][1] = mfma4(x0 - x1, po[s], C1[e][1]);
+          C1[e][2] = mfma4(x2 + x3, pe[s], C1[e][2]);
+          C1[e][3] = mfma4(x2 - x3, po[s], C1[e][3]);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
 
-    // ---- product 2: C2[mt][nt] rows V = 16mt + 4g + r, cols U = 16nt + c.  k-step (e, r) contracts
-    //      j = 4 chi(4g+r) + e, which lies in the left chunks for r < 2 and in the right ones otherwise.
+    // ---- product 2: C2[vt][tt] rows: frequency v = 2(4g + r) + vt%2 of column block vt/2, cols as above.
+    //      The pair base j0 = 4g + s of the columns sits in registers (e, r) = (s,0), (3-s,1) | (s,2), (3-s,3).
     f32x4 C2[4][4];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int vt = 0; vt < 4; ++vt)
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) C2[mt][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     {
-      float4 pn = *reinterpret_cast<const float4*>(&sT2[lane * 4]);
+      const float4 pe4 = *reinterpret_cast<const float4*>(&sT2[(0 * 64 + lane) * 4]);
+      const float4 po4 = *reinterpret_cast<const float4*>(&sT2[(1 * 64 + lane) * 4]);
+      const float pe[4] = {pe4.x, pe4.y, pe4.z, pe4.w}, po[4] = {po4.x, po4.y, po4.z, po4.w};
 #pragma unroll
-      for (int er = 0; er < 16; ++er) {
-        const int e = er >> 2, r = er & 3;
-        const float pf[4] = {pn.x, pn.y, pn.z, pn.w};
-        if (er + 1 < 16) pn = *reinterpret_cast<const float4*>(&sT2[((er + 1) * 64 + lane) * 4]);
-        const int bc = r >> 1;
+      for (int s = 0; s < 4; ++s) {
 #pragma unroll
-        for (int mh = 0; mh < 2; ++mh)
-#pragma unroll
-          for (int nt = 0; nt < 4; ++nt) {
-            const int mt = 2 * bc + mh;
-            C2[mt][nt] = mfma4(pf[mt], C1[e][nt][r], C2[mt][nt]);
-          }
+        for (int tt = 0; tt < 4; ++tt) {
+          const float y0 = C1[s][tt][0], y1 = C1[3 - s][tt][1], y2 = C1[s][tt][2], y3 = C1[3 - s][tt][3];
+          C2[0][tt] = mfma4(pe[s], y0 + y1, C2[0][tt]);
+          C2[1][tt] = mfma4(po[s], y0 - y1, C2[1][tt]);
+          C2[2][tt] = mfma4(pe[s], y2 + y3, C2[2][tt]);
+          C2[3][tt] = mfma4(po[s], y2 - y3, C2[3][tt]);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -252,7 +249,7 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
               if (mask != 0) {
                 if (is) {
                   const int pos = min((int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)ncand)), ED_CAP);
-                  cand[pos] = make_uint2(__float_as_uint(q), fb + (uint32_t)(512 * nh + 16 * mh + r));
+                  cand[pos] = make_uint2(__float_as_uint(q), fb + (uint32_t)(32 * nh + mh + 2 * r));
                 }
                 ncand += __popcll(mask);
               }

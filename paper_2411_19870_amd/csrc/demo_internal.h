@@ -98,7 +98,7 @@ void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                   bool grad_bf16, int num_cus, hipStream_t stream);
 // dense-basis tile kernel (demo_enc64d.hip)
-constexpr int kEnc64dTableFloats = 3 * 4096 + 512;
+constexpr int kEnc64dTableFloats = 1024 + 4096 + 512;
 void build_enc64d_tables(const double* B64, float* out /* kEnc64dTableFloats */);
 hipError_t launch_encode2d_tile32(const TableView& tiles, const int32_t* prefix32, const float* tables,
                                   const EncodeArgs& a, const Worklist& wl, bool grad_bf16, int num_cus,
