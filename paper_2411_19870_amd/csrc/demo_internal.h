@@ -111,6 +111,16 @@ void build_dec32_tables(const double* P32, float* out /* kDec32TableFloats */);
 hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   int num_cus, hipStream_t stream);
 
+// s = 128 kernels, one 1024-thread workgroup per chunk (demo_wg128.hip); they need the DCT (mirror-folded products)
+// and read the plain 128 x 128 basis.
+constexpr int kFast128MaxK = 64;
+hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const EncodeArgs& a, const Worklist& wl,
+                                 bool grad_bf16, int num_cus, hipStream_t stream);
+// decode keeps the W*k pairs of a chunk in four registers per lane of its 1024 threads
+constexpr int kFast128MaxPairs = 4096;
+hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
+                                 int num_cus, hipStream_t stream);
+
 inline bool fast64_decode_supports(int W, int k) { return k <= kFast64MaxK && W <= (k <= 32 ? 64 : 32); }
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream);

@@ -1017,6 +1017,13 @@ hipError_t launch_encode2d(const TableView& tv, const TableView* tiles, const Ba
     if (e != hipSuccess) return e;
     return launch_enc2d_generic<64>(tv, basis, a, wl, num_cus, stream);
   }
+  if (variant >= 1 && s == 128 && a.mirror != 0 && a.k <= kFast128MaxK && wl.list != nullptr &&
+      (gmix == 1u || gmix == 2u)) {
+    // workgroup-per-chunk kernel with the next chunk in flight, then the exact generic kernel over its queue
+    hipError_t e = launch_encode2d_wg128(tv, basis, a, wl, gmix == 1u, num_cus, stream);
+    if (e != hipSuccess) return e;
+    return launch_enc2d_generic<128>(tv, basis, a, wl, num_cus, stream);
+  }
   const Worklist none{nullptr, nullptr, nullptr};
   switch (s) {
     case 32: return launch_enc2d_generic<32>(tv, basis, a, none, num_cus, stream);
@@ -1038,6 +1045,9 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
   if (variant >= 1 && s == 64 && decode_is_sign_of_sum(a) && fast64_decode_supports(a.W, a.k) && payload_fits32 &&
       bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
+  if (variant >= 1 && s == 128 && a.mirror != 0 && decode_is_sign_of_sum(a) && (int64_t)a.W * a.k <= kFast128MaxPairs &&
+      payload_fits32 && (pmix == 1u || pmix == 2u))
+    return launch_decode2d_wg128(tv, bt.basis, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {
     case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);

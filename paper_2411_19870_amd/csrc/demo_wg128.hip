@@ -1,0 +1,695 @@
+// s = 128 kernels: one 1024-thread workgroup (16 wavefronts) per 128 x 128 chunk, one workgroup per CU.
+//
+// A chunk is too large for one wavefront's registers, so it lives in an LDS tile and the products read their
+// operands from LDS; sixteen wavefronts (four per SIMD) hide the operand reads behind one another's MFMAs, and
+// the rows of the next chunk are fetched into registers (24 - 32 per lane) while this one is transformed.
+//
+// Mirror fold: row u of the 128-point orthonormal DCT-II is even (u even) or odd (u odd) under i -> 127-i.  A
+// product that contracts over i needs i < 64 of the folded operand x[i] +- x[127-i]; a product whose output
+// index is i needs i < 64 of two partial sums (even u, odd u), the mirror outputs being their sum and
+// difference.  Either way 1024 instead of 2048 MFMAs (16x16x4) per product.  The basis sits in LDS as
+// P[u][i], i < 64, rows grouped by class: row u at position pos(u) = 64 (u % 2) + u / 2; coefficient rows and
+// columns are held in the same class-major order and translated when the payload is written.
+//
+// The contraction index of k-slot g at step s of group kg is 16 kg + 4 g + s, so that operands whose
+// contraction index runs along an LDS row come in one 16-byte read per four MFMAs.
+#include <type_traits>
+
+#include "demo_device.h"
+
+namespace demo {
+
+namespace {
+constexpr int W128_WAVES = 16;
+constexpr int W128_THREADS = 64 * W128_WAVES;
+constexpr int W128_LDX = 132;                          // data tile row stride (floats)
+constexpr int W128_LDP = 68;                           // folded basis row stride
+constexpr int W128_P_FLOATS = 128 * W128_LDP;
+constexpr int W128_X_FLOATS = 128 * W128_LDX;
+constexpr int W128_CAP = 512;                          // candidate list of the top-k
+constexpr int W128_SEL = 68;                           // entries per class list of selected coefficients (k <= 64, padded)
+constexpr int W128_ENC_LDS_BYTES = 4 * (W128_P_FLOATS + W128_X_FLOATS + 128 + 16 + W128_CAP) + 8 * (W128_CAP + 2 + 4 * W128_SEL);
+static_assert(W128_ENC_LDS_BYTES <= 160 * 1024, "LDS budget");
+
+// Workgroup barrier that orders LDS accesses only: global loads and stores stay in flight across it.
+__device__ __forceinline__ void wg_lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ int pos128(uint32_t u) { return (int)(((u & 1u) << 6) | (u >> 1)); }
+
+// folded basis into LDS: P[u][i], i < 64, at row pos(u)
+__device__ __forceinline__ void stage_folded_basis(float* sP, const float* __restrict__ basis, int tid) {
+  for (int e = tid; e < 128 * 16; e += W128_THREADS) {
+    const int u = e >> 4, c4 = (e & 15) * 4;
+    *reinterpret_cast<f32x4*>(&sP[pos128((uint32_t)u) * W128_LDP + c4]) = gload_f4(basis + u * 128 + c4);
+  }
+}
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// encode:  m <- beta m + g ;  Q = P B P^T ;  k largest |Q| ;  m <- m - alpha P^T Q^ P      (Algorithm 1, worker side)
+// ---------------------------------------------------------------------------
+// Thread t owns elements (rows t/32 + 32 p, columns 4 (t%32) .. +3), p < 4, of the chunk: loads, momentum
+// update and the final store happen in this layout (a wavefront touches two 512-byte row segments per access).
+// A chunk whose candidate list overflows (many equal magnitudes at the threshold) is left untouched and queued
+// for the exact generic kernel that runs next.
+template <bool GBF16>
+__global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, const float* __restrict__ basis,
+                                                                EncodeArgs args, Worklist wl) {
+  extern __shared__ float lds[];
+  float* sP = lds;
+  float* sX = sP + W128_P_FLOATS;
+  uint32_t* gmax = reinterpret_cast<uint32_t*>(sX + W128_X_FLOATS);   // [128] maxima of groups of 8 lanes
+  int* ctl = reinterpret_cast<int*>(gmax + 128);                      // [0] candidate cursor, [1] threshold, [2] all-zero flag, [4..7] class counts
+  uint32_t* rk = reinterpret_cast<uint32_t*>(ctl + 16);               // [CAP] rank | class rank << 16 of a candidate
+  uint2* cand = reinterpret_cast<uint2*>(rk + W128_CAP);              // [CAP + 2] {coefficient bits, flat index}
+  uint2* sel = cand + W128_CAP + 2;                                   // [4][SEL]  {basis row offsets, coefficient bits}
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int k = args.k;
+  const int total = tv.total_chunks;
+  int chunk = blockIdx.x;
+  if (chunk >= total) return;
+
+  stage_folded_basis(sP, basis, tid);
+
+  using GT = typename std::conditional<GBF16, u32x2, f32x4>::type;
+  const int lrow = tid >> 5, lcol = (tid & 31) * 4;
+  f32x4 mv[4];
+  GT gv[4];
+  auto issue_loads = [&](const TensorDev& dd, int cc) {
+    const int k0 = cc / dd.cchunks, k1 = cc - k0 * dd.cchunks;
+    const int64_t origin = (int64_t)k0 * 128 * dd.cols + (int64_t)k1 * 128;
+    const uint32_t ucols = (uint32_t)dd.cols;
+    const uint32_t vo = (uint32_t)lrow * ucols + (uint32_t)lcol;
+    const __amdgpu_buffer_rsrc_t mres = make_rsrc(dd.mom + origin);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) mv[p] = bload_f4(mres, vo * 4, 32u * p * ucols * 4);
+    if constexpr (GBF16) {
+      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const uint16_t*>(dd.grad) + origin);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) gv[p] = bload_u2(gres, vo * 2, 32u * p * ucols * 2);
+    } else {
+      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const float*>(dd.grad) + origin);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) gv[p] = bload_f4(gres, vo * 4, 32u * p * ucols * 4);
+    }
+  };
+
+  int t = find_tensor_uniform(tv, chunk);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
+  issue_loads(d, chunk - t_first);
+
+  // flat index 128 u + v of coefficient acc[i][r] of the second product: u = 2 (16 i + 4 lq + r) + mh,
+  // v = 2 ((16 nt + l16) % 64) + nt / 4   (mh = wave / 8, nt = wave % 8)
+  const uint32_t fb = (uint32_t)(1024 * lq + 128 * (wave >> 3) + 2 * ((16 * (wave & 7) + l16) & 63) + ((wave & 7) >> 2));
+
+  // momentum update of the chunk whose rows are in the registers, staged into the tile
+  f32x4 D[4];
+  auto update_and_stage = [&]() {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      f32x4 gf;
+      if constexpr (GBF16) {
+        gf = (f32x4){bf16_to_f32(gv[p][0] & 0xffffu), bf16_to_f32(gv[p][0] >> 16), bf16_to_f32(gv[p][1] & 0xffffu),
+                     bf16_to_f32(gv[p][1] >> 16)};
+      } else {
+        gf = gv[p];
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) D[p][e] = __fmaf_rn(args.beta, mv[p][e], args.grad_scale * gf[e]);
+      *reinterpret_cast<f32x4*>(&sX[(lrow + 32 * p) * W128_LDX + lcol]) = D[p];
+    }
+  };
+  update_and_stage();
+
+  DEMO_PHASE_DECL
+  for (;;) {
+    // ---- the tile holds D = beta m + g of this chunk; the registers take the rows of the next one -----------
+    int tidv = tid;
+    asm volatile("" : "+v"(tidv));   // addresses below are recomputed per chunk rather than kept (and spilled) across it
+    if (tidv < 4 * W128_SEL) sel[tidv] = make_uint2(0u, 0u);                 // zero-valued padding of the class lists
+    if (tidv < W128_CAP + 2) cand[tidv] = make_uint2(0u, 0xffffffffu);        // entries that precede nothing
+    if (tidv < W128_CAP) rk[tidv] = 0u;
+    if (tidv < 8) ctl[tidv] = 0;
+    // where this chunk's results go
+    const int cc = chunk - t_first;
+    const uint32_t ucols = (uint32_t)d.cols;
+    const __amdgpu_buffer_rsrc_t mres_out =
+        make_rsrc(d.mom + ((int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128));
+    DEMO_GLOBAL int32_t* const out_idx = as_global(d.idx) + (int64_t)cc * k;
+    DEMO_GLOBAL float* const out_val = as_global(d.val) + (int64_t)cc * k;
+    const int nxt = chunk + (int)gridDim.x;
+    wg_lds_barrier();
+    if (nxt < total) {
+      while (nxt >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
+      }
+      issue_loads(d, nxt - t_first);
+    }
+    DEMO_PHASE(0);
+
+    // ---- product 1: T[u][j] = sum_{i<64} P[u][i] (X[i][j] +- X[127-i][j]); the wavefront owns column tile
+    //      nt = wave % 8 and the four row tiles of class wave / 8 -----------------------------------------------
+    f32x4 acc[4];
+    {
+      const int nt = wave & 7, cls = wave >> 3;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const float* pa = sP + (64 * cls + l16) * W128_LDP + 4 * lq;
+      const float* xb = sX + 16 * nt + l16;
+#pragma unroll
+      for (int kg = 0; kg < 4; ++kg) {
+        float b[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int i = 16 * kg + 4 * lq + s;
+          const float x0 = xb[i * W128_LDX], x1 = xb[(127 - i) * W128_LDX];
+          b[s] = cls ? x0 - x1 : x0 + x1;
+        }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 16 * mt * W128_LDP + 16 * kg);
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc[mt] = mfma4(a[s], b[s], acc[mt]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      wg_lds_barrier();   // every read of X is done: T replaces it, rows in class-major order
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sX[(64 * cls + 16 * mt + 4 * lq + r) * W128_LDX + 16 * nt + l16] = acc[mt][r];
+    }
+    wg_lds_barrier();
+    DEMO_PHASE(1);
+
+    // ---- product 2: Q[u][v] = sum_{j<64} (T[u][j] +- T[u][127-j]) P[v][j]; column tile nt = wave % 8 (positions
+    //      16 nt .., class nt / 4), row tiles 4 (wave / 8) + i ------------------------------------------------------
+    {
+      const int nt = wave & 7, mh = wave >> 3;
+      const bool oddv = nt >= 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const float* pb = sP + (16 * nt + l16) * W128_LDP + 4 * lq;
+      const float* ta = sX + (64 * mh + l16) * W128_LDX + 4 * lq;
+      const float* tm = sX + (64 * mh + l16) * W128_LDX + 124 - 4 * lq;
+#pragma unroll
+      for (int kg = 0; kg < 4; ++kg) {
+        const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 16 * kg);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const f32x4 t0 = *reinterpret_cast<const f32x4*>(ta + 16 * i * W128_LDX + 16 * kg);
+          const f32x4 t1 = *reinterpret_cast<const f32x4*>(tm + 16 * i * W128_LDX - 16 * kg);
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc[i] = mfma4(oddv ? t0[s] - t1[3 - s] : t0[s] + t1[3 - s], b[s], acc[i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    DEMO_PHASE(2);
+
+    // ---- top-k over the 16384 coefficients -----------------------------------------------------------------
+    // (1) lower bound of the k-th largest magnitude: the k-th largest of the 128 maxima of groups of 8 lanes
+    //     (each a coefficient of its own), resolved to its upper 16 bits
+    float gm[4];   // largest magnitude of each accumulator
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      gm[i] = fmaxf(fmaxf(fabsf(acc[i][0]), fabsf(acc[i][1])), fmaxf(fabsf(acc[i][2]), fabsf(acc[i][3])));
+    uint32_t lm = __float_as_uint(fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3])));
+    lm = max(lm, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lm, 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    lm = max(lm, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lm, 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    lm = max(lm, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lm, 0x141, 0xf, 0xf, false));   // row_half_mirror
+    const int lanev = tidv & 63;
+    if ((lanev & 7) == 0) gmax[8 * wave + (lanev >> 3)] = lm;
+    wg_lds_barrier();
+    if (wave == 0) {
+      // one wavefront bisects (sixteen doing the same would only queue at the scalar unit)
+      const uint32_t g0 = gmax[lanev], g1 = gmax[lanev + 64];
+      uint32_t t0 = 0;
+      for (int bit = 30; bit >= 16; --bit) {
+        const uint32_t cnd = t0 | (1u << bit);
+        if (__popcll(__ballot(g0 >= cnd)) + __popcll(__ballot(g1 >= cnd)) >= k) t0 = cnd;
+      }
+      const bool none = __ballot((g0 | g1) != 0u) == 0;
+      if (lane == 0) {
+        ctl[1] = (int)t0;
+        ctl[2] = none ? 1 : 0;
+      }
+    }
+    wg_lds_barrier();
+    const float thr_f = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane(ctl[1]));
+    // (2) candidates |q| >= thr: a wavefront reserves its range of the list with one atomic.  Accumulators whose
+    //     largest magnitude is below the threshold in every lane are passed over as a whole.
+    {
+      uint32_t fbv = fb;
+      asm volatile("" : "+v"(fbv));   // keeps the 16 per-register flat indices from being precomputed outside the chunk loop
+      int cnt = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (__ballot(gm[i] >= thr_f) != 0) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cnt += __popcll(__ballot(fabsf(acc[i][r]) >= thr_f));
+        }
+      int base = 0;
+      if (lane == 0 && cnt != 0) base = atomicAdd(&ctl[0], cnt);
+      base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (__ballot(gm[i] >= thr_f) != 0) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const bool is = fabsf(acc[i][r]) >= thr_f;
+            const uint64_t mask = __ballot(is);
+            if (mask != 0) {
+              const int pos = base + lanes_below(mask);
+              if (is && pos < W128_CAP) cand[pos] = make_uint2(__float_as_uint(acc[i][r]), fbv + (uint32_t)(4096 * i + 256 * r));
+              base += __popcll(mask);
+            }
+          }
+        }
+    }
+    wg_lds_barrier();
+    DEMO_PHASE(3);
+    const int ncand = __builtin_amdgcn_readfirstlane(ctl[0]);
+    const bool overflow = ncand > W128_CAP;
+    const bool all_zero = overflow && __builtin_amdgcn_readfirstlane(ctl[2]) != 0;
+    const bool skip = overflow && !all_zero;
+    if (skip && tid == 0) wl.list[atomicAdd(wl.count, 1)] = chunk;
+    if (all_zero && tid < k) {
+      // every coefficient is zero: the k lowest flat indices with zero values; m = D is stored below
+      out_idx[tid] = tid;
+      out_val[tid] = 0.f;
+    }
+    // (3) rank the candidates (magnitude descending, flat index ascending).  Wavefront w counts, for every
+    //     candidate, the entries of its slice of the list that precede it, and those among them of the same class
+    //     2 (u % 2) + v % 2; the sixteen partial counts meet in rk[].
+    if (!overflow) {
+      const int slice = 2 * ((ncand + 31) >> 5);
+      const int j0 = wave * slice;
+      if (j0 < ncand) {
+        for (int ib = 0; 64 * ib < ncand; ++ib) {
+          const int i = 64 * ib + lane;
+          const uint2 me = cand[i < ncand ? i : W128_CAP];
+          const uint32_t mag = me.x & 0x7fffffffu;
+          uint32_t part = 0;
+          for (int j = j0; j < j0 + slice; j += 2) {
+            const uint4 o = *reinterpret_cast<const uint4*>(&cand[j]);
+            const uint32_t m0 = o.x & 0x7fffffffu, m1 = o.z & 0x7fffffffu;
+            const bool p0 = m0 > mag || (m0 == mag && o.y < me.y), p1 = m1 > mag || (m1 == mag && o.w < me.y);
+            part += (p0 ? (((o.y ^ me.y) & 0x81u) == 0 ? 0x10001u : 1u) : 0u) +
+                    (p1 ? (((o.w ^ me.y) & 0x81u) == 0 ? 0x10001u : 1u) : 0u);
+          }
+          if (i < ncand && part != 0) atomicAdd(&rk[i], part);
+        }
+      }
+    }
+    wg_lds_barrier();
+    // ranks < k are the payload; a selected coefficient also goes to the list of its class, at the number of
+    // class members ahead of it (a deterministic order of summation for the reconstruction)
+    if (!overflow && tidv < ncand) {
+      const uint2 me = cand[tidv];
+      const uint32_t r2 = rk[tidv];
+      const int rank = (int)(r2 & 0xffffu), rcls = (int)(r2 >> 16);
+      if (rank < k) {
+        out_idx[rank] = (int32_t)me.y;
+        out_val[rank] = __uint_as_float(me.x);
+        const int cls = (int)(((me.y >> 6) & 2u) | (me.y & 1u));
+        // byte offsets of rows pos(u) and pos(v) of the basis tile, and the value
+        const uint32_t offs = (uint32_t)(pos128(me.y >> 7) * (W128_LDP * 4)) | ((uint32_t)(pos128(me.y & 127u) * (W128_LDP * 4)) << 16);
+        sel[cls * W128_SEL + rcls] = make_uint2(offs, me.x);
+        atomicAdd(&ctl[4 + cls], 1);
+      }
+    }
+    wg_lds_barrier();
+    DEMO_PHASE(4);
+
+    // ---- reconstruction on the quadrant i, j < 64, one partial sum per class (a, b) = (u % 2, v % 2):
+    //      R[i][j] = sum s_ab,  R[127-i][j] = sum (-1)^a s_ab,  R[i][127-j] = sum (-1)^b s_ab ---------------------
+    {
+      const int mt = wave >> 2, nt = wave & 3;
+      f32x4 rc[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) rc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      // the lists are zero-padded, so every class runs to the length of the longest
+      const int4 nc = *reinterpret_cast<const int4*>(&ctl[4]);
+      const int nmax = __builtin_amdgcn_readfirstlane(max(max(nc.x, nc.y), max(nc.z, nc.w)));
+      const float* pa = sP + 16 * mt + l16;
+      const float* pb = sP + 16 * nt + l16;
+      for (int st = 0; 4 * st < nmax; ++st) {
+        uint2 e[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) e[c] = sel[c * W128_SEL + 4 * st + lq];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float a = __uint_as_float(e[c].y) * *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pa) + (e[c].x & 0xffffu));
+          const float b = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pb) + (e[c].x >> 16));
+          rc[c] = mfma4(a, b, rc[c]);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i0 = 16 * mt + 4 * lq + r, j0 = 16 * nt + l16;
+        const float pe = rc[0][r] + rc[1][r], po = rc[2][r] + rc[3][r];
+        const float me = rc[0][r] - rc[1][r], mo = rc[2][r] - rc[3][r];
+        sX[i0 * W128_LDX + j0] = pe + po;
+        sX[i0 * W128_LDX + 127 - j0] = me + mo;
+        sX[(127 - i0) * W128_LDX + j0] = pe - po;
+        sX[(127 - i0) * W128_LDX + 127 - j0] = me - mo;
+      }
+    }
+    wg_lds_barrier();
+    DEMO_PHASE(5);
+
+    // ---- m <- D - alpha R.  The rows of the next chunk are consumed (into D and the tile) before the stores are
+    //      issued, so that waiting for those rows never waits for these stores ---------------------------------
+    {
+      f32x4 o[4];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const f32x4 rv = *reinterpret_cast<const f32x4*>(&sX[(lrow + 32 * p) * W128_LDX + lcol]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[p][e] = __fmaf_rn(-args.alpha, rv[e], D[p][e]);
+      }
+      if (nxt < total) update_and_stage();
+      if (!skip) {
+        const uint32_t vo = (uint32_t)lrow * ucols + (uint32_t)lcol;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) bstore_f4(mres_out, vo * 4, 32u * p * ucols * 4, o[p]);
+      }
+    }
+    DEMO_PHASE(6);
+    if (nxt >= total) break;
+    chunk = nxt;
+  }
+  DEMO_PHASE_FLUSH(0);
+}
+
+template <bool GBF16>
+static hipError_t launch_enc_wg128(const TableView& tv, const float* basis, const EncodeArgs& a, const Worklist& wl,
+                                   int64_t grid, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_wg128<GBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, W128_ENC_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(encode2d_wg128<GBF16>, dim3((unsigned)grid), dim3(W128_THREADS), W128_ENC_LDS_BYTES, stream, tv,
+                     basis, a, wl);
+  return hipGetLastError();
+}
+
+hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const EncodeArgs& a, const Worklist& wl,
+                                 bool grad_bf16, int num_cus, hipStream_t stream) {
+  if (a.k < 1 || a.k > kFast128MaxK || wl.list == nullptr) return hipErrorInvalidValue;
+  int64_t grid = num_cus;
+  if (grid > tv.total_chunks) grid = tv.total_chunks;
+  return grad_bf16 ? launch_enc_wg128<true>(tv, basis, a, wl, grid, stream)
+                   : launch_enc_wg128<false>(tv, basis, a, wl, grid, stream);
+}
+
+// ---------------------------------------------------------------------------
+// decode:  S = sum over workers of the payloads ;  R = P^T S P ;  x <- x - lr (sgn(R) + wd x)     (Algorithm 1, update)
+// ---------------------------------------------------------------------------
+// Sign descent on the plain sum only (the other operating points run on the generic kernel).  The W k <= 4096
+// pairs of a chunk sit in at most four registers per lane (pair 1024 j + tid belongs to worker p / k, position
+// p % k) and are fetched for the next chunk while the products of this one run.  S is accumulated in block
+// fixed point with integer LDS atomics (one scale per chunk: the sum is exact and independent of the order of
+// arrival), rows and columns in class-major order.  Basis in LDS: PT[i][pos(u)] = P[u][i], i < 64, so that both
+// products read it along the contraction index.
+namespace {
+constexpr int W128_DEC_SLOTS = 4;
+constexpr int W128_PT_FLOATS = 64 * W128_LDX;
+constexpr int W128_DEC_LDS_BYTES = 4 * (W128_PT_FLOATS + W128_X_FLOATS + 16);
+static_assert(kFast128MaxPairs == W128_DEC_SLOTS * W128_THREADS, "pairs per chunk held in registers");
+}  // namespace
+
+template <bool PBF16>
+__global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, const float* __restrict__ basis,
+                                                                DecodeArgs args) {
+  extern __shared__ float lds[];
+  float* sPT = lds;
+  float* tile = sPT + W128_PT_FLOATS;
+  int* itile = reinterpret_cast<int*>(tile);
+  uint32_t* wmax = reinterpret_cast<uint32_t*>(tile + W128_X_FLOATS);   // [16] per-wavefront largest |val|
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, lq = lane >> 4;
+  const int k = args.k, W = args.W;
+  const int npairs = W * k;
+  const int nslots = (npairs + W128_THREADS - 1) / W128_THREADS;   // payload registers in use (uniform)
+  const int total = tv.total_chunks;
+  int chunk = blockIdx.x;
+  if (chunk >= total) return;
+
+  // PT[i][pos(u)] = P[u][i]: thread reads P[u][4c..4c+3] and writes four rows of the transposed tile
+  for (int e = tid; e < 128 * 16; e += W128_THREADS) {
+    const int u = e >> 4, c4 = (e & 15) * 4;
+    const f32x4 v = gload_f4(basis + u * 128 + c4);
+#pragma unroll
+    for (int x = 0; x < 4; ++x) sPT[(c4 + x) * W128_LDX + pos128((uint32_t)u)] = v[x];
+  }
+
+  int32_t pi[W128_DEC_SLOTS];
+  float pv[W128_DEC_SLOTS];
+#pragma unroll
+  for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+    pi[j] = -1;
+    pv[j] = 0.f;
+  }
+  const float rk = 1.0f / (float)k;
+  auto load_payload = [&](const TensorDev& dd, int cc) {
+    const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)cc * k;
+    const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)cc * k;
+    const int wstride = dd.nchunks * k;                        // pairs of one worker for this tensor
+#pragma unroll
+    for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+      if (j < nslots) {                                        // uniform
+        const int p = W128_THREADS * j + tid;
+        // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
+        // the rounding error of the float product for p < 4096
+        const int w = (int)(((float)p + 0.5f) * rk);
+        const int pos = p - w * k;
+        const bool ok = p < npairs;
+        const uint32_t off = (uint32_t)(w * wstride + pos);
+        pi[j] = ok ? __builtin_nontemporal_load(ip + off) : -1;
+        pv[j] = ok ? __builtin_nontemporal_load(vp + off) : 0.f;
+      }
+    }
+  };
+
+  int t = find_tensor_uniform(tv, chunk);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
+  load_payload(d, chunk - t_first);
+
+  int vbits = 30;
+  for (int w = 1; w < W; w <<= 1) --vbits;                     // 30 - ceil(log2 W)
+  const int lrow = tid >> 5, lcol = (tid & 31) * 4;
+  const uint32_t dummy = (uint32_t)((tid & 127) * W128_LDX + 128 + ((tid >> 7) & 3));   // pad slot of this thread
+
+  for (;;) {
+    const int cc = chunk - t_first;
+    const uint32_t ucols = (uint32_t)d.cols;
+    const int64_t origin = (int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128;
+    const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
+                                              : make_rsrc(static_cast<const float*>(d.param) + origin);
+    const uint32_t vo = (uint32_t)lrow * ucols + (uint32_t)lcol;
+
+    // ---- largest |val| of the chunk, zero tile --------------------------------------------------------------
+    {
+      float mx = 0.f;
+#pragma unroll
+      for (int j = 0; j < W128_DEC_SLOTS; ++j)
+        if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
+      uint32_t mb = __float_as_uint(mx);
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x141, 0xf, 0xf, false));  // row_half_mirror
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
+      const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
+      const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
+      if (lane == 0) wmax[wave] = max(m01, m23);
+    }
+    for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS)
+      *reinterpret_cast<f32x4*>(&tile[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
+    wg_lds_barrier();
+
+    // ---- S[idx] += val in fixed point ------------------------------------------------------------------------
+    {
+      uint32_t mall = wmax[lane & 15];
+      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0xB1, 0xf, 0xf, false));
+      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x4E, 0xf, 0xf, false));
+      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x141, 0xf, 0xf, false));
+      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x140, 0xf, 0xf, false));
+      int ex = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)mall) >> 23);   // biased exponent of the largest magnitude
+      ex = ex < 1 ? 1 : ex;
+      const int sh = vbits + 126 - ex;                         // max |val| * 2^sh < 2^vbits
+#pragma unroll
+      for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+        if (j < nslots) {
+          const uint32_t fi = (uint32_t)pi[j];
+          const uint32_t a = fi < 16384u ? (uint32_t)(pos128(fi >> 7) * W128_LDX + pos128(fi & 127u)) : dummy;
+          atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
+        }
+      }
+    }
+    // ---- payload of the next chunk, in flight during the products ----------------------------------------------
+    const int nxt = chunk + (int)gridDim.x;
+    if (nxt < total) {
+      while (nxt >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
+      }
+      load_payload(d, nxt - t_first);
+    }
+    wg_lds_barrier();
+
+    // ---- product a: Y[i][v] = sum_u P[u][i] S[u][v] for i < 64 as partial sums over even / odd u; column tile
+    //      nt = wave % 8, row tiles 2 (wave / 8) + {0, 1}; accumulator 2 il + cls ------------------------------------
+    f32x4 acc[4];
+    {
+      const int nt = wave & 7, ih = wave >> 3;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const float* pa = sPT + (32 * ih + l16) * W128_LDX + 4 * lq;
+      const int* sb = itile + 4 * lq * W128_LDX + 16 * nt + l16;
+#pragma unroll
+      for (int cls = 0; cls < 2; ++cls) {
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg) {
+          float b[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) b[s] = (float)sb[(64 * cls + 16 * kg + s) * W128_LDX];
+#pragma unroll
+          for (int il = 0; il < 2; ++il) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 16 * il * W128_LDX + 64 * cls + 16 * kg);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[2 * il + cls] = mfma4(a[s], b[s], acc[2 * il + cls]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      wg_lds_barrier();   // every read of S is done: Y replaces it (rows in natural order)
+#pragma unroll
+      for (int il = 0; il < 2; ++il)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int i = 16 * (2 * ih + il) + 4 * lq + r;
+          tile[i * W128_LDX + 16 * nt + l16] = acc[2 * il][r] + acc[2 * il + 1][r];
+          tile[(127 - i) * W128_LDX + 16 * nt + l16] = acc[2 * il][r] - acc[2 * il + 1][r];
+        }
+    }
+    wg_lds_barrier();
+
+    // ---- the parameters of this chunk: requested now, used after product b -----------------------------------
+    using XT = typename std::conditional<PBF16, u32x2, f32x4>::type;
+    XT xin[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      if constexpr (PBF16) xin[p] = bload_u2(xres, vo * 2, 32u * p * ucols * 2);
+      else xin[p] = bload_f4(xres, vo * 4, 32u * p * ucols * 4);
+    }
+
+    // ---- product b: R[i][j] = sum_v Y[i][v] P[v][j] for j < 64 as partial sums over even / odd v; column tile
+    //      jt = wave % 4, row tiles 2 (wave / 4) + {0, 1} ---------------------------------------------------------
+    {
+      const int jt = wave & 3, ih = wave >> 2;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const float* ya = tile + (32 * ih + l16) * W128_LDX + 4 * lq;
+      const float* pb = sPT + (16 * jt + l16) * W128_LDX + 4 * lq;
+#pragma unroll
+      for (int cls = 0; cls < 2; ++cls) {
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg) {
+          const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 64 * cls + 16 * kg);
+#pragma unroll
+          for (int il = 0; il < 2; ++il) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(ya + 16 * il * W128_LDX + 64 * cls + 16 * kg);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[2 * il + cls] = mfma4(a[s], b[s], acc[2 * il + cls]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      wg_lds_barrier();   // every read of Y is done: R replaces it
+#pragma unroll
+      for (int il = 0; il < 2; ++il)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int i = 16 * (2 * ih + il) + 4 * lq + r, j = 16 * jt + l16;
+          tile[i * W128_LDX + j] = acc[2 * il][r] + acc[2 * il + 1][r];
+          tile[i * W128_LDX + 127 - j] = acc[2 * il][r] - acc[2 * il + 1][r];
+        }
+    }
+    wg_lds_barrier();
+
+    // ---- x <- x - lr (sgn(R) + wd x) ------------------------------------------------------------------------------
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const f32x4 rv = *reinterpret_cast<const f32x4*>(&tile[(lrow + 32 * p) * W128_LDX + lcol]);
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float x;
+        if constexpr (PBF16) {
+          const uint32_t raw = xin[p][e >> 1];
+          x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+        } else {
+          x = xin[p][e];
+        }
+        o[e] = sign_update(x, sgnf(rv[e]), args.lr, args.weight_decay);
+      }
+      if constexpr (PBF16) {
+        const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+        bstore_u2(xres, vo * 2, 32u * p * ucols * 2, pk);
+      } else {
+        const f32x4 ov = {o[0], o[1], o[2], o[3]};
+        bstore_f4(xres, vo * 4, 32u * p * ucols * 4, ov);
+      }
+    }
+    if (nxt >= total) break;
+    chunk = nxt;
+    wg_lds_barrier();   // the tile is zeroed next
+  }
+}
+
+template <bool PBF16>
+static hipError_t launch_dec_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
+                                   hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, W128_DEC_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(decode2d_wg128<PBF16>, dim3((unsigned)grid), dim3(W128_THREADS), W128_DEC_LDS_BYTES, stream, tv,
+                     basis, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
+                                 int num_cus, hipStream_t stream) {
+  if (a.W < 1 || a.k < 1 || (int64_t)a.W * a.k > kFast128MaxPairs) return hipErrorInvalidValue;
+  int64_t grid = num_cus;
+  if (grid > tv.total_chunks) grid = tv.total_chunks;
+  return param_bf16 ? launch_dec_wg128<true>(tv, basis, a, grid, stream)
+                    : launch_dec_wg128<false>(tv, basis, a, grid, stream);
+}
+
+}  // namespace demo
+
+DEMO_PHASE_GETTER(demo_debug_phase_clocks_wg128)
