@@ -81,29 +81,30 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
   const int lrow = tid >> 5, lcol = (tid & 31) * 4;
   f32x4 mv[4];
   GT gv[4];
-  auto issue_loads = [&](const TensorDev& dd, int cc) {
+  // rows 32 p + lrow of the chunk `cc` of tensor `dd`: one quarter of the chunk per call (p < 4)
+  __amdgpu_buffer_rsrc_t mres_in, gres_in;
+  uint32_t ucols_in = 0;
+  auto set_source = [&](const TensorDev& dd, int cc) {
     const int k0 = cc / dd.cchunks, k1 = cc - k0 * dd.cchunks;
     const int64_t origin = (int64_t)k0 * 128 * dd.cols + (int64_t)k1 * 128;
-    const uint32_t ucols = (uint32_t)dd.cols;
-    const uint32_t vo = (uint32_t)lrow * ucols + (uint32_t)lcol;
-    const __amdgpu_buffer_rsrc_t mres = make_rsrc(dd.mom + origin);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) mv[p] = bload_f4(mres, vo * 4, 32u * p * ucols * 4);
-    if constexpr (GBF16) {
-      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const uint16_t*>(dd.grad) + origin);
-#pragma unroll
-      for (int p = 0; p < 4; ++p) gv[p] = bload_u2(gres, vo * 2, 32u * p * ucols * 2);
-    } else {
-      const __amdgpu_buffer_rsrc_t gres = make_rsrc(static_cast<const float*>(dd.grad) + origin);
-#pragma unroll
-      for (int p = 0; p < 4; ++p) gv[p] = bload_f4(gres, vo * 4, 32u * p * ucols * 4);
-    }
+    ucols_in = (uint32_t)dd.cols;
+    mres_in = make_rsrc(dd.mom + origin);
+    gres_in = GBF16 ? make_rsrc(static_cast<const uint16_t*>(dd.grad) + origin)
+                    : make_rsrc(static_cast<const float*>(dd.grad) + origin);
+  };
+  auto issue_quarter = [&](int p) {
+    const uint32_t vo = (uint32_t)lrow * ucols_in + (uint32_t)lcol;
+    mv[p] = bload_f4(mres_in, vo * 4, 32u * p * ucols_in * 4);
+    if constexpr (GBF16) gv[p] = bload_u2(gres_in, vo * 2, 32u * p * ucols_in * 2);
+    else gv[p] = bload_f4(gres_in, vo * 4, 32u * p * ucols_in * 4);
   };
 
   int t = find_tensor_uniform(tv, chunk);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
-  issue_loads(d, chunk - t_first);
+  set_source(d, chunk - t_first);
+#pragma unroll
+  for (int p = 0; p < 4; ++p) issue_quarter(p);
 
   // flat index 128 u + v of coefficient acc[i][r] of the second product: u = 2 (16 i + 4 lq + r) + mh,
   // v = 2 ((16 nt + l16) % 64) + nt / 4   (mh = wave / 8, nt = wave % 8)
@@ -133,10 +134,11 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     // ---- the tile holds D = beta m + g of this chunk; the registers take the rows of the next one -----------
     int tidv = tid;
     asm volatile("" : "+v"(tidv));   // addresses below are recomputed per chunk rather than kept (and spilled) across it
-    if (tidv < 4 * W128_SEL) sel[tidv] = make_uint2(0u, 0u);                 // zero-valued padding of the class lists
-    if (tidv < W128_CAP + 2) cand[tidv] = make_uint2(0u, 0xffffffffu);        // entries that precede nothing
-    if (tidv < W128_CAP) rk[tidv] = 0u;
-    if (tidv < 8) ctl[tidv] = 0;
+    const uint32_t zero = (uint32_t)(tidv >> 31);                            // 0, formed per chunk like the addresses
+    if (tidv < 4 * W128_SEL) sel[tidv] = make_uint2(zero, zero);             // zero-valued padding of the class lists
+    if (tidv < W128_CAP + 2) cand[tidv] = make_uint2(zero, ~zero);            // entries that precede nothing
+    if (tidv < W128_CAP) rk[tidv] = zero;
+    if (tidv < 8) ctl[tidv] = (int)zero;
     // where this chunk's results go
     const int cc = chunk - t_first;
     const uint32_t ucols = (uint32_t)d.cols;
@@ -145,16 +147,17 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     DEMO_GLOBAL int32_t* const out_idx = as_global(d.idx) + (int64_t)cc * k;
     DEMO_GLOBAL float* const out_val = as_global(d.val) + (int64_t)cc * k;
     const int nxt = chunk + (int)gridDim.x;
-    wg_lds_barrier();
-    if (nxt < total) {
+    const bool has_next = nxt < total;
+    if (has_next) {
       while (nxt >= t_next) {
         ++t;
         t_first = t_next;
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      issue_loads(d, nxt - t_first);
+      set_source(d, nxt - t_first);
     }
+    wg_lds_barrier();
     DEMO_PHASE(0);
 
     // ---- product 1: T[u][j] = sum_{i<64} P[u][i] (X[i][j] +- X[127-i][j]); the wavefront owns column tile
@@ -181,6 +184,9 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
 #pragma unroll
           for (int s = 0; s < 4; ++s) acc[mt] = mfma4(a[s], b[s], acc[mt]);
         }
+        // a quarter of the next chunk's rows per step: the requests of the sixteen wavefronts trickle into the
+        // memory pipeline instead of queueing at the barrier
+        if (has_next) issue_quarter(kg);
         __builtin_amdgcn_sched_barrier(0);
       }
       wg_lds_barrier();   // every read of X is done: T replaces it, rows in class-major order
@@ -344,16 +350,24 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
       const int nmax = __builtin_amdgcn_readfirstlane(max(max(nc.x, nc.y), max(nc.z, nc.w)));
       const float* pa = sP + 16 * mt + l16;
       const float* pb = sP + 16 * nt + l16;
+      uint2 en[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + lq];
       for (int st = 0; 4 * st < nmax; ++st) {
         uint2 e[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) e[c] = sel[c * W128_SEL + 4 * st + lq];
+        for (int c = 0; c < 4; ++c) e[c] = en[c];
+        float a[4], b[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-          const float a = __uint_as_float(e[c].y) * *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pa) + (e[c].x & 0xffffu));
-          const float b = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pb) + (e[c].x >> 16));
-          rc[c] = mfma4(a, b, rc[c]);
+          a[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pa) + (e[c].x & 0xffffu));
+          b[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pb) + (e[c].x >> 16));
         }
+        // entries of the next step (the lists are 68 long and zero past their ends: step 16 reads padding)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + 4 * (st + 1) + lq];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) rc[c] = mfma4(__uint_as_float(e[c].y) * a[c], b[c], rc[c]);
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -379,15 +393,17 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[p][e] = __fmaf_rn(-args.alpha, rv[e], D[p][e]);
       }
-      if (nxt < total) update_and_stage();
+      DEMO_PHASE(6);
+      if (has_next) update_and_stage();
+      DEMO_PHASE(7);
       if (!skip) {
         const uint32_t vo = (uint32_t)lrow * ucols + (uint32_t)lcol;
 #pragma unroll
         for (int p = 0; p < 4; ++p) bstore_f4(mres_out, vo * 4, 32u * p * ucols * 4, o[p]);
       }
     }
-    DEMO_PHASE(6);
-    if (nxt >= total) break;
+    DEMO_PHASE(0);
+    if (!has_next) break;
     chunk = nxt;
   }
   DEMO_PHASE_FLUSH(0);
@@ -424,9 +440,16 @@ hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const 
 // pairs of a chunk sit in at most four registers per lane (pair 1024 j + tid belongs to worker p / k, position
 // p % k) and are fetched for the next chunk while the products of this one run.  S is accumulated in block
 // fixed point with integer LDS atomics (one scale per chunk: the sum is exact and independent of the order of
-// arrival), rows and columns in class-major order.  Basis in LDS: PT[i][pos(u)] = P[u][i], i < 64, so that both
-// products read it along the contraction index.
+// arrival).  Two mirror folds: rows u = 0 mod 4 of P are even under i -> 63-i and i -> 127-i, rows u = 2 mod 4
+// odd / even, odd rows odd under i -> 127-i.  For the quadruple {i, 63-i, 64+i, 127-i}, i < 32, four partial sums
+//   E0 = sum over u = 0 mod 4,  E2 = sum over u = 2 mod 4  (32 frequencies each),
+//   Oa = sum over odd u of P[u][i] ..,  Ob = sum over odd u of P[u][63-i] ..  (64 frequencies each)
+// give out[i] = E0+E2+Oa, out[127-i] = E0+E2-Oa, out[63-i] = E0-E2+Ob, out[64+i] = E0-E2-Ob: 768 MFMAs per
+// product instead of 2048.  S is held with rows and columns in class-major order pos3(); basis in LDS:
+// PT[i][pos3(u)] = P[u][i], i < 64, so that both products read it along the contraction index.
 namespace {
+// class-major position of frequency u in the decode kernel: u = 0 mod 4 first, then u = 2 mod 4, then odd u
+__device__ __forceinline__ int pos3(uint32_t u) { return (int)((u & 1u) ? 64u + (u >> 1) : ((u & 2u) << 4) + (u >> 2)); }
 constexpr int W128_DEC_SLOTS = 4;
 constexpr int W128_PT_FLOATS = 64 * W128_LDX;
 constexpr int W128_DEC_LDS_BYTES = 4 * (W128_PT_FLOATS + W128_X_FLOATS + 16);
@@ -451,12 +474,12 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   int chunk = blockIdx.x;
   if (chunk >= total) return;
 
-  // PT[i][pos(u)] = P[u][i]: thread reads P[u][4c..4c+3] and writes four rows of the transposed tile
+  // PT[i][pos3(u)] = P[u][i]: thread reads P[u][4c..4c+3] and writes four rows of the transposed tile
   for (int e = tid; e < 128 * 16; e += W128_THREADS) {
     const int u = e >> 4, c4 = (e & 15) * 4;
     const f32x4 v = gload_f4(basis + u * 128 + c4);
 #pragma unroll
-    for (int x = 0; x < 4; ++x) sPT[(c4 + x) * W128_LDX + pos128((uint32_t)u)] = v[x];
+    for (int x = 0; x < 4; ++x) sPT[(c4 + x) * W128_LDX + pos3((uint32_t)u)] = v[x];
   }
 
   int32_t pi[W128_DEC_SLOTS];
@@ -538,7 +561,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       for (int j = 0; j < W128_DEC_SLOTS; ++j) {
         if (j < nslots) {
           const uint32_t fi = (uint32_t)pi[j];
-          const uint32_t a = fi < 16384u ? (uint32_t)(pos128(fi >> 7) * W128_LDX + pos128(fi & 127u)) : dummy;
+          const uint32_t a = fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
           atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
         }
       }
@@ -556,40 +579,51 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     }
     wg_lds_barrier();
 
-    // ---- product a: Y[i][v] = sum_u P[u][i] S[u][v] for i < 64 as partial sums over even / odd u; column tile
-    //      nt = wave % 8, row tiles 2 (wave / 8) + {0, 1}; accumulator 2 il + cls ------------------------------------
+    // ---- product a: Y[i][v] = sum_u P[u][i] S[u][v]; the wavefront owns column tile nt = wave % 8 and the
+    //      quadruple bases i = 16 h + m, h = wave / 8; accumulators E0, E2, Oa, Ob ---------------------------------
     f32x4 acc[4];
     {
-      const int nt = wave & 7, ih = wave >> 3;
+      const int nt = wave & 7, h = wave >> 3;
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const float* pa = sPT + (32 * ih + l16) * W128_LDX + 4 * lq;
+      const float* pa = sPT + (16 * h + l16) * W128_LDX + 4 * lq;           // P[u][i]
+      const float* pm = sPT + (63 - 16 * h - l16) * W128_LDX + 4 * lq;      // P[u][63 - i]
       const int* sb = itile + 4 * lq * W128_LDX + 16 * nt + l16;
 #pragma unroll
-      for (int cls = 0; cls < 2; ++cls) {
+      for (int kg = 0; kg < 4; ++kg) {   // kg = 0, 1: u = 0 mod 4;  kg = 2, 3: u = 2 mod 4
+        float b[4];
 #pragma unroll
-        for (int kg = 0; kg < 4; ++kg) {
-          float b[4];
+        for (int s = 0; s < 4; ++s) b[s] = (float)sb[(16 * kg + s) * W128_LDX];
+        const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 16 * kg);
 #pragma unroll
-          for (int s = 0; s < 4; ++s) b[s] = (float)sb[(64 * cls + 16 * kg + s) * W128_LDX];
-#pragma unroll
-          for (int il = 0; il < 2; ++il) {
-            const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 16 * il * W128_LDX + 64 * cls + 16 * kg);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) acc[2 * il + cls] = mfma4(a[s], b[s], acc[2 * il + cls]);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
+        for (int s = 0; s < 4; ++s) acc[kg >> 1] = mfma4(a[s], b[s], acc[kg >> 1]);
       }
-      wg_lds_barrier();   // every read of S is done: Y replaces it (rows in natural order)
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int il = 0; il < 2; ++il)
+      for (int kg = 0; kg < 4; ++kg) {   // odd u
+        float b[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int i = 16 * (2 * ih + il) + 4 * lq + r;
-          tile[i * W128_LDX + 16 * nt + l16] = acc[2 * il][r] + acc[2 * il + 1][r];
-          tile[(127 - i) * W128_LDX + 16 * nt + l16] = acc[2 * il][r] - acc[2 * il + 1][r];
+        for (int s = 0; s < 4; ++s) b[s] = (float)sb[(64 + 16 * kg + s) * W128_LDX];
+        const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 64 + 16 * kg);
+        const f32x4 am = *reinterpret_cast<const f32x4*>(pm + 64 + 16 * kg);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          acc[2] = mfma4(a[s], b[s], acc[2]);
+          acc[3] = mfma4(am[s], b[s], acc[3]);
         }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      wg_lds_barrier();   // every read of S is done: Y replaces it (rows in natural order, columns as they were)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = 16 * h + 4 * lq + r;
+        const float ep = acc[0][r] + acc[1][r], em = acc[0][r] - acc[1][r];
+        float* col = tile + 16 * nt + l16;
+        col[i * W128_LDX] = ep + acc[2][r];
+        col[(127 - i) * W128_LDX] = ep - acc[2][r];
+        col[(63 - i) * W128_LDX] = em + acc[3][r];
+        col[(64 + i) * W128_LDX] = em - acc[3][r];
+      }
     }
     wg_lds_barrier();
 
@@ -602,37 +636,46 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       else xin[p] = bload_f4(xres, vo * 4, 32u * p * ucols * 4);
     }
 
-    // ---- product b: R[i][j] = sum_v Y[i][v] P[v][j] for j < 64 as partial sums over even / odd v; column tile
-    //      jt = wave % 4, row tiles 2 (wave / 4) + {0, 1} ---------------------------------------------------------
+    // ---- product b: R[i][j] = sum_v Y[i][v] P[v][j]; the wavefront owns row tile it = wave / 2 and the quadruple
+    //      bases j = 16 h + n, h = wave % 2; accumulators E0, E2, Oa, Ob ----------------------------------------------
     {
-      const int jt = wave & 3, ih = wave >> 2;
+      const int it = wave >> 1, h = wave & 1;
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const float* ya = tile + (32 * ih + l16) * W128_LDX + 4 * lq;
-      const float* pb = sPT + (16 * jt + l16) * W128_LDX + 4 * lq;
+      const float* ya = tile + (16 * it + l16) * W128_LDX + 4 * lq;
+      const float* pb = sPT + (16 * h + l16) * W128_LDX + 4 * lq;            // P[v][j]
+      const float* pm = sPT + (63 - 16 * h - l16) * W128_LDX + 4 * lq;       // P[v][63 - j]
 #pragma unroll
-      for (int cls = 0; cls < 2; ++cls) {
+      for (int kg = 0; kg < 4; ++kg) {   // kg = 0, 1: v = 0 mod 4;  kg = 2, 3: v = 2 mod 4
+        const f32x4 a = *reinterpret_cast<const f32x4*>(ya + 16 * kg);
+        const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 16 * kg);
 #pragma unroll
-        for (int kg = 0; kg < 4; ++kg) {
-          const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 64 * cls + 16 * kg);
+        for (int s = 0; s < 4; ++s) acc[kg >> 1] = mfma4(a[s], b[s], acc[kg >> 1]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int il = 0; il < 2; ++il) {
-            const f32x4 a = *reinterpret_cast<const f32x4*>(ya + 16 * il * W128_LDX + 64 * cls + 16 * kg);
+      for (int kg = 0; kg < 4; ++kg) {   // odd v
+        const f32x4 a = *reinterpret_cast<const f32x4*>(ya + 64 + 16 * kg);
+        const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 64 + 16 * kg);
+        const f32x4 bm = *reinterpret_cast<const f32x4*>(pm + 64 + 16 * kg);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) acc[2 * il + cls] = mfma4(a[s], b[s], acc[2 * il + cls]);
-          }
-          __builtin_amdgcn_sched_barrier(0);
+        for (int s = 0; s < 4; ++s) {
+          acc[2] = mfma4(a[s], b[s], acc[2]);
+          acc[3] = mfma4(a[s], bm[s], acc[3]);
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
       wg_lds_barrier();   // every read of Y is done: R replaces it
 #pragma unroll
-      for (int il = 0; il < 2; ++il)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int i = 16 * (2 * ih + il) + 4 * lq + r, j = 16 * jt + l16;
-          tile[i * W128_LDX + j] = acc[2 * il][r] + acc[2 * il + 1][r];
-          tile[i * W128_LDX + 127 - j] = acc[2 * il][r] - acc[2 * il + 1][r];
-        }
+      for (int r = 0; r < 4; ++r) {
+        const int j = 16 * h + l16;
+        float* row = tile + (16 * it + 4 * lq + r) * W128_LDX;
+        const float ep = acc[0][r] + acc[1][r], em = acc[0][r] - acc[1][r];
+        row[j] = ep + acc[2][r];
+        row[127 - j] = ep - acc[2][r];
+        row[63 - j] = em + acc[3][r];
+        row[64 + j] = em - acc[3][r];
+      }
     }
     wg_lds_barrier();
 
