@@ -4,12 +4,14 @@
 // operands from LDS; sixteen wavefronts (four per SIMD) hide the operand reads behind one another's MFMAs, and
 // the rows of the next chunk are fetched into registers (24 - 32 per lane) while this one is transformed.
 //
-// Mirror fold: row u of the 128-point orthonormal DCT-II is even (u even) or odd (u odd) under i -> 127-i.  A
-// product that contracts over i needs i < 64 of the folded operand x[i] +- x[127-i]; a product whose output
-// index is i needs i < 64 of two partial sums (even u, odd u), the mirror outputs being their sum and
-// difference.  Either way 1024 instead of 2048 MFMAs (16x16x4) per product.  The basis sits in LDS as
-// P[u][i], i < 64, rows grouped by class: row u at position pos(u) = 64 (u % 2) + u / 2; coefficient rows and
-// columns are held in the same class-major order and translated when the payload is written.
+// Mirror folds: row u of the 128-point orthonormal DCT-II is even (u even) or odd (u odd) under i -> 127-i, and
+// the even rows are in turn even (u = 0 mod 4) or odd (u = 2 mod 4) under i -> 63-i.  A product that contracts
+// over i needs i < 64 of x[i] - x[127-i] for the odd rows and i < 32 of (x[i] + x[127-i]) +- (x[63-i] + x[64+i])
+// for the two even classes; a product whose output index is i needs the matching partial sums, the mirror
+// outputs being their sums and differences.  Either way 768 instead of 2048 MFMAs (16x16x4) per product.  The
+// basis sits in LDS as P[u][i], i < 64, rows grouped by class: row u at position pos3(u) (u = 0 mod 4, then
+// u = 2 mod 4, then odd); coefficient rows and columns are held in the same class-major order and translated
+// when the payload is written.
 //
 // The contraction index of k-slot g at step s of group kg is 16 kg + 4 g + s, so that operands whose
 // contraction index runs along an LDS row come in one 16-byte read per four MFMAs.
@@ -38,13 +40,14 @@ __device__ __forceinline__ void wg_lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-__device__ __forceinline__ int pos128(uint32_t u) { return (int)(((u & 1u) << 6) | (u >> 1)); }
+// class-major position of frequency u: u = 0 mod 4 first, then u = 2 mod 4, then odd u; and its inverse
+__device__ __forceinline__ int pos3(uint32_t u) { return (int)((u & 1u) ? 64u + (u >> 1) : ((u & 2u) << 4) + (u >> 2)); }
 
 // folded basis into LDS: P[u][i], i < 64, at row pos(u)
 __device__ __forceinline__ void stage_folded_basis(float* sP, const float* __restrict__ basis, int tid) {
   for (int e = tid; e < 128 * 16; e += W128_THREADS) {
     const int u = e >> 4, c4 = (e & 15) * 4;
-    *reinterpret_cast<f32x4*>(&sP[pos128((uint32_t)u) * W128_LDP + c4]) = gload_f4(basis + u * 128 + c4);
+    *reinterpret_cast<f32x4*>(&sP[pos3((uint32_t)u) * W128_LDP + c4]) = gload_f4(basis + u * 128 + c4);
   }
 }
 }  // namespace
@@ -106,9 +109,16 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
 #pragma unroll
   for (int p = 0; p < 4; ++p) issue_quarter(p);
 
-  // flat index 128 u + v of coefficient acc[i][r] of the second product: u = 2 (16 i + 4 lq + r) + mh,
-  // v = 2 ((16 nt + l16) % 64) + nt / 4   (mh = wave / 8, nt = wave % 8)
-  const uint32_t fb = (uint32_t)(1024 * lq + 128 * (wave >> 3) + 2 * ((16 * (wave & 7) + l16) & 63) + ((wave & 7) >> 2));
+  // flat index 128 u + v of coefficient acc[a][r] of the second product (row tile mt = wave / 2, half h = wave % 2):
+  // row position 16 mt + 4 lq + r, i.e. u = ub + su (4 lq + r) with su = 4 (even classes) or 2 (odd rows);
+  // column position 32 h + 16 a + l16 of an even class (a < 2): v = 64 a + 4 l16 + 2 h, or 64 + 32 h + 16 (a - 2) + l16
+  // of the odd class: v = 64 h + 32 (a - 2) + 2 l16 + 1
+  const int q_mt = wave >> 1, q_h = wave & 1;
+  const int q_su = q_mt < 4 ? 4 : 2;
+  const int q_ub = q_mt < 2 ? 64 * q_mt : q_mt < 4 ? 64 * (q_mt - 2) + 2 : 32 * (q_mt - 4) + 1;
+  const uint32_t fb_u = (uint32_t)(128 * (q_ub + 4 * q_su * lq));
+  const uint32_t fb_c = (uint32_t)(4 * l16 + 2 * q_h), fb_o = (uint32_t)(64 * q_h + 2 * l16 + 1);
+  const uint32_t fb_rstep = (uint32_t)(128 * q_su);
 
   // momentum update of the chunk whose rows are in the registers, staged into the tile
   f32x4 D[4];
@@ -160,29 +170,43 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     wg_lds_barrier();
     DEMO_PHASE(0);
 
-    // ---- product 1: T[u][j] = sum_{i<64} P[u][i] (X[i][j] +- X[127-i][j]); the wavefront owns column tile
-    //      nt = wave % 8 and the four row tiles of class wave / 8 -----------------------------------------------
+    // ---- product 1: T[u][j] = sum_i P[u][i] X[i][j] on the folded rows of X; the wavefront owns column tile
+    //      nt = wave % 8, two row tiles of the even class h = wave / 8 (u = 0 / 2 mod 4) and the odd row tiles
+    //      2 h, 2 h + 1 -----------------------------------------------------------------------------------------
     f32x4 acc[4];
     {
-      const int nt = wave & 7, cls = wave >> 3;
+      const int nt = wave & 7, h = wave >> 3;
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const float* pa = sP + (64 * cls + l16) * W128_LDP + 4 * lq;
+      const float* pc = sP + (32 * h + l16) * W128_LDP + 4 * lq;
+      const float* po = sP + (64 + 32 * h + l16) * W128_LDP + 4 * lq;
       const float* xb = sX + 16 * nt + l16;
 #pragma unroll
       for (int kg = 0; kg < 4; ++kg) {
-        float b[4];
+        float bo[4], bc[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           const int i = 16 * kg + 4 * lq + s;
           const float x0 = xb[i * W128_LDX], x1 = xb[(127 - i) * W128_LDX];
-          b[s] = cls ? x0 - x1 : x0 + x1;
+          bo[s] = x0 - x1;
+          if (kg < 2) {
+            const float e0 = x0 + x1, e1 = xb[(63 - i) * W128_LDX] + xb[(64 + i) * W128_LDX];
+            bc[s] = h ? e0 - e1 : e0 + e1;
+          }
+        }
+        if (kg < 2) {
+#pragma unroll
+          for (int t2 = 0; t2 < 2; ++t2) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(pc + 16 * t2 * W128_LDP + 16 * kg);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[t2] = mfma4(a[s], bc[s], acc[t2]);
+          }
         }
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 16 * mt * W128_LDP + 16 * kg);
+        for (int t2 = 0; t2 < 2; ++t2) {
+          const f32x4 a = *reinterpret_cast<const f32x4*>(po + 16 * t2 * W128_LDP + 16 * kg);
 #pragma unroll
-          for (int s = 0; s < 4; ++s) acc[mt] = mfma4(a[s], b[s], acc[mt]);
+          for (int s = 0; s < 4; ++s) acc[2 + t2] = mfma4(a[s], bo[s], acc[2 + t2]);
         }
         // a quarter of the next chunk's rows per step: the requests of the sixteen wavefronts trickle into the
         // memory pipeline instead of queueing at the barrier
@@ -191,32 +215,53 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
       }
       wg_lds_barrier();   // every read of X is done: T replaces it, rows in class-major order
 #pragma unroll
-      for (int mt = 0; mt < 4; ++mt)
+      for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sX[(64 * cls + 16 * mt + 4 * lq + r) * W128_LDX + 16 * nt + l16] = acc[mt][r];
+        for (int r = 0; r < 4; ++r) {
+          sX[(32 * h + 16 * t2 + 4 * lq + r) * W128_LDX + 16 * nt + l16] = acc[t2][r];
+          sX[(64 + 32 * h + 16 * t2 + 4 * lq + r) * W128_LDX + 16 * nt + l16] = acc[2 + t2][r];
+        }
     }
     wg_lds_barrier();
     DEMO_PHASE(1);
 
-    // ---- product 2: Q[u][v] = sum_{j<64} (T[u][j] +- T[u][127-j]) P[v][j]; column tile nt = wave % 8 (positions
-    //      16 nt .., class nt / 4), row tiles 4 (wave / 8) + i ------------------------------------------------------
+    // ---- product 2: Q[u][v] = sum_j T[u][j] P[v][j] on the folded columns of T; the wavefront owns row tile
+    //      mt = wave / 2 (positions 16 mt ..), two column tiles of the even class h = wave % 2 and the odd column
+    //      tiles 2 h, 2 h + 1 --------------------------------------------------------------------------------------
     {
-      const int nt = wave & 7, mh = wave >> 3;
-      const bool oddv = nt >= 4;
+      const int mt = wave >> 1, h = wave & 1;
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const float* pb = sP + (16 * nt + l16) * W128_LDP + 4 * lq;
-      const float* ta = sX + (64 * mh + l16) * W128_LDX + 4 * lq;
-      const float* tm = sX + (64 * mh + l16) * W128_LDX + 124 - 4 * lq;
+      const float* pc = sP + (32 * h + l16) * W128_LDP + 4 * lq;
+      const float* po = sP + (64 + 32 * h + l16) * W128_LDP + 4 * lq;
+      const float* tr = sX + (16 * mt + l16) * W128_LDX;
 #pragma unroll
       for (int kg = 0; kg < 4; ++kg) {
-        const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 16 * kg);
+        // columns j = 16 kg + 4 lq + s and 127 - j
+        const f32x4 t0 = *reinterpret_cast<const f32x4*>(tr + 16 * kg + 4 * lq);
+        const f32x4 t1 = *reinterpret_cast<const f32x4*>(tr + 124 - 16 * kg - 4 * lq);
+        if (kg < 2) {
+          // and 63 - j, 64 + j
+          const f32x4 t2 = *reinterpret_cast<const f32x4*>(tr + 60 - 16 * kg - 4 * lq);
+          const f32x4 t3 = *reinterpret_cast<const f32x4*>(tr + 64 + 16 * kg + 4 * lq);
+          float ac[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const f32x4 t0 = *reinterpret_cast<const f32x4*>(ta + 16 * i * W128_LDX + 16 * kg);
-          const f32x4 t1 = *reinterpret_cast<const f32x4*>(tm + 16 * i * W128_LDX - 16 * kg);
+          for (int s = 0; s < 4; ++s) {
+            const float e0 = t0[s] + t1[3 - s], e1 = t2[3 - s] + t3[s];
+            ac[s] = h ? e0 - e1 : e0 + e1;
+          }
 #pragma unroll
-          for (int s = 0; s < 4; ++s) acc[i] = mfma4(oddv ? t0[s] - t1[3 - s] : t0[s] + t1[3 - s], b[s], acc[i]);
+          for (int c2 = 0; c2 < 2; ++c2) {
+            const f32x4 b = *reinterpret_cast<const f32x4*>(pc + 16 * c2 * W128_LDP + 16 * kg);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[c2] = mfma4(ac[s], b[s], acc[c2]);
+          }
+        }
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2) {
+          const f32x4 b = *reinterpret_cast<const f32x4*>(po + 16 * c2 * W128_LDP + 16 * kg);
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc[2 + c2] = mfma4(t0[s] - t1[3 - s], b[s], acc[2 + c2]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -256,8 +301,8 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     // (2) candidates |q| >= thr: a wavefront reserves its range of the list with one atomic.  Accumulators whose
     //     largest magnitude is below the threshold in every lane are passed over as a whole.
     {
-      uint32_t fbv = fb;
-      asm volatile("" : "+v"(fbv));   // keeps the 16 per-register flat indices from being precomputed outside the chunk loop
+      uint32_t fu = fb_u, fc = fb_c, fo = fb_o;
+      asm volatile("" : "+v"(fu), "+v"(fc), "+v"(fo));   // keeps the 16 per-register flat indices from being precomputed outside the chunk loop
       int cnt = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -277,7 +322,7 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
             const uint64_t mask = __ballot(is);
             if (mask != 0) {
               const int pos = base + lanes_below(mask);
-              if (is && pos < W128_CAP) cand[pos] = make_uint2(__float_as_uint(acc[i][r]), fbv + (uint32_t)(4096 * i + 256 * r));
+              if (is && pos < W128_CAP) cand[pos] = make_uint2(__float_as_uint(acc[i][r]), fu + (uint32_t)r * fb_rstep + (i < 2 ? fc + 64u * i : fo + 32u * (i - 2)));
               base += __popcll(mask);
             }
           }
@@ -330,7 +375,7 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
         out_val[rank] = __uint_as_float(me.x);
         const int cls = (int)(((me.y >> 6) & 2u) | (me.y & 1u));
         // byte offsets of rows pos(u) and pos(v) of the basis tile, and the value
-        const uint32_t offs = (uint32_t)(pos128(me.y >> 7) * (W128_LDP * 4)) | ((uint32_t)(pos128(me.y & 127u) * (W128_LDP * 4)) << 16);
+        const uint32_t offs = (uint32_t)(pos3(me.y >> 7) * (W128_LDP * 4)) | ((uint32_t)(pos3(me.y & 127u) * (W128_LDP * 4)) << 16);
         sel[cls * W128_SEL + rcls] = make_uint2(offs, me.x);
         atomicAdd(&ctl[4 + cls], 1);
       }
@@ -369,15 +414,20 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
 #pragma unroll
         for (int c = 0; c < 4; ++c) rc[c] = mfma4(__uint_as_float(e[c].y) * a[c], b[c], rc[c]);
       }
+      // four base addresses formed per chunk (kept across the chunk they would be spilled), rows at immediate offsets
+      const int lqv = lanev >> 4, l16v = lanev & 15;
+      float* w00 = sX + (16 * mt + 4 * lqv) * W128_LDX + 16 * nt + l16v;            // (i0, j0), r = 0
+      float* w01 = sX + (16 * mt + 4 * lqv) * W128_LDX + 127 - 16 * nt - l16v;      // (i0, 127 - j0)
+      float* w10 = sX + (124 - 16 * mt - 4 * lqv) * W128_LDX + 16 * nt + l16v;      // (127 - i0, j0), r = 3
+      float* w11 = sX + (124 - 16 * mt - 4 * lqv) * W128_LDX + 127 - 16 * nt - l16v;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int i0 = 16 * mt + 4 * lq + r, j0 = 16 * nt + l16;
         const float pe = rc[0][r] + rc[1][r], po = rc[2][r] + rc[3][r];
         const float me = rc[0][r] - rc[1][r], mo = rc[2][r] - rc[3][r];
-        sX[i0 * W128_LDX + j0] = pe + po;
-        sX[i0 * W128_LDX + 127 - j0] = me + mo;
-        sX[(127 - i0) * W128_LDX + j0] = pe - po;
-        sX[(127 - i0) * W128_LDX + 127 - j0] = me - mo;
+        w00[r * W128_LDX] = pe + po;
+        w01[r * W128_LDX] = me + mo;
+        w10[(3 - r) * W128_LDX] = pe - po;
+        w11[(3 - r) * W128_LDX] = me - mo;
       }
     }
     wg_lds_barrier();
@@ -448,8 +498,6 @@ hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const 
 // product instead of 2048.  S is held with rows and columns in class-major order pos3(); basis in LDS:
 // PT[i][pos3(u)] = P[u][i], i < 64, so that both products read it along the contraction index.
 namespace {
-// class-major position of frequency u in the decode kernel: u = 0 mod 4 first, then u = 2 mod 4, then odd u
-__device__ __forceinline__ int pos3(uint32_t u) { return (int)((u & 1u) ? 64u + (u >> 1) : ((u & 2u) << 4) + (u >> 2)); }
 constexpr int W128_DEC_SLOTS = 4;
 constexpr int W128_PT_FLOATS = 64 * W128_LDX;
 constexpr int W128_DEC_LDS_BYTES = 4 * (W128_PT_FLOATS + W128_X_FLOATS + 16);
