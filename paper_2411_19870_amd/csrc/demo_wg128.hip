@@ -116,8 +116,6 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
   const int q_mt = wave >> 1, q_h = wave & 1;
   const int q_su = q_mt < 4 ? 4 : 2;
   const int q_ub = q_mt < 2 ? 64 * q_mt : q_mt < 4 ? 64 * (q_mt - 2) + 2 : 32 * (q_mt - 4) + 1;
-  const uint32_t fb_u = (uint32_t)(128 * (q_ub + 4 * q_su * lq));
-  const uint32_t fb_c = (uint32_t)(4 * l16 + 2 * q_h), fb_o = (uint32_t)(64 * q_h + 2 * l16 + 1);
   const uint32_t fb_rstep = (uint32_t)(128 * q_su);
 
   // momentum update of the chunk whose rows are in the registers, staged into the tile
@@ -301,8 +299,10 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     // (2) candidates |q| >= thr: a wavefront reserves its range of the list with one atomic.  Accumulators whose
     //     largest magnitude is below the threshold in every lane are passed over as a whole.
     {
-      uint32_t fu = fb_u, fc = fb_c, fo = fb_o;
-      asm volatile("" : "+v"(fu), "+v"(fc), "+v"(fo));   // keeps the 16 per-register flat indices from being precomputed outside the chunk loop
+      // lane parts of the flat indices, formed per chunk from the opaque lane id (kept across the chunk, these
+      // and the 16 per-register indices derived from them would be spilled)
+      const uint32_t fu = (uint32_t)(128 * (q_ub + 4 * q_su * (lanev >> 4)));
+      const uint32_t fc = (uint32_t)(4 * (lanev & 15) + 2 * q_h), fo = (uint32_t)(64 * q_h + 2 * (lanev & 15) + 1);
       int cnt = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
       const float* pb = sP + 16 * nt + l16;
       uint2 en[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + lq];
+      for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + (lanev >> 4)];
       for (int st = 0; 4 * st < nmax; ++st) {
         uint2 e[4];
 #pragma unroll
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
         }
         // entries of the next step (the lists are 68 long and zero past their ends: step 16 reads padding)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + 4 * (st + 1) + lq];
+        for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + 4 * (st + 1) + (lanev >> 4)];
 #pragma unroll
         for (int c = 0; c < 4; ++c) rc[c] = mfma4(__uint_as_float(e[c].y) * a[c], b[c], rc[c]);
       }
