@@ -85,6 +85,7 @@ def cpu_baseline(specs, seed):
 
 
 def main():
+    global S, K, W
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -93,7 +94,13 @@ def main():
     ap.add_argument("--variant", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    # other operating points of the same path (the headline configuration is the default)
+    ap.add_argument("--s", type=int, default=S, choices=[32, 64, 128], help="chunk size")
+    ap.add_argument("--k", type=int, default=K, help="coefficients kept per chunk")
+    ap.add_argument("--workers", type=int, default=W, help="payloads decoded per step")
     a = ap.parse_args()
+    headline = (a.s, a.k, a.workers) == (S, K, W)
+    S, K, W = a.s, a.k, a.workers
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the W workers' payloads are synthesised on-device); "
               "--gpus must be 1", file=sys.stderr)
@@ -167,7 +174,8 @@ def main():
     dom = "enc2d" if (kms["enc2d"] or 0) >= (kms["dec2d"] or 0) else "dec2d"
     achieved = ab[dom] / (kms[dom] * 1e-3) / 1e9
     out = {
-        "metric": "DeMo encode+decode throughput at 1B shape" if a.workload == "1b" else f"DeMo encode+decode throughput ({a.workload})",
+        "metric": "DeMo encode+decode throughput at 1B shape" if a.workload == "1b" and headline
+                  else f"DeMo encode+decode throughput ({a.workload}, s={S}, k={K}, W={W})",
         "value": step_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s",
         "params_per_s": nparams / (ms_step * 1e-3),
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
@@ -193,7 +201,7 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             rec = json.load(f)
-        if rec.get("variant") == a.variant and dom in rec.get("kernels", {}):
+        if headline and rec.get("variant") == a.variant and dom in rec.get("kernels", {}):
             out["roofline"]["traffic"] = rec["kernels"][dom]["hbm_bytes_per_launch"]
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(specs, a.seed)
