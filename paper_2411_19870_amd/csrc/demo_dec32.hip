@@ -47,7 +47,9 @@ void build_dec32_tables(const double* P32, float* out) {
 
 // The table `tv` lists the order-2 tensors in units of 64 x 64 tiles (cchunks = cols / 64, nchunks =
 // tiles); payload arrays are addressed per 32 x 32 chunk (4 * nchunks chunks per tensor).
-template <bool PBF16>
+// VEC4: k is a multiple of four and every payload pointer is 16-byte aligned; a lane then fetches four consecutive
+// pairs of one worker with one 16-byte load per array (slot 8 q + 4 jj + e holds pair 4 (64 jj + lane) + e of chunk q).
+template <bool PBF16, bool VEC4>
 __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   extern __shared__ float lds[];
@@ -59,7 +61,9 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   int* itile = reinterpret_cast<int*>(tile);
   const int k = args.k, W = args.W;
   const int npairs = W * k;                                   // per chunk, <= 512
-  const int nslots = (npairs + 63) >> 6;                      // payload registers in use per chunk (uniform)
+  const int nunits = VEC4 ? (npairs >> 2) : npairs;           // loads per array and chunk
+  const int nloads = (nunits + 63) >> 6;                      // ... per lane (uniform)
+  const int nslots = VEC4 ? 4 * nloads : nloads;              // payload registers in use per chunk (uniform)
 
   for (int e = tid; e < D32_G_FLOATS / 4; e += D32_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
@@ -83,15 +87,40 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
     const int K0 = tt / dd.cchunks, K1 = tt - K0 * dd.cchunks;
     const int cch32 = 2 * dd.cchunks;
     const int64_t wstride = (int64_t)dd.nchunks * 4 * k;      // pairs of one worker for this tensor
+    // the per-slot (worker, position) are formed anew at every call: kept across the tile loop as 64-bit offsets
+    // they are spilled, and every reload of a spilled value waits for all loads in flight
+    int lanev = lane;
+    asm volatile("" : "+v"(lanev));
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int c32 = (2 * K0 + (q >> 1)) * cch32 + 2 * K1 + (q & 1);
       const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)c32 * k;
       const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)c32 * k;
+      if constexpr (VEC4) {
+#pragma unroll
+        for (int jj = 0; jj < D32_SLOTS / 4; ++jj) {
+          if (jj < nloads) {                                  // uniform
+            const int unit = 64 * jj + lanev;
+            const int p = 4 * unit;
+            const int w = (int)(((float)p + 0.5f) * rk);      // as below
+            const int pos = p - w * k;
+            const bool ok = unit < nunits;
+            const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
+            const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+            const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
+              pv[D32_SLOTS * q + 4 * jj + e] = ok ? vv[e] : 0.f;
+            }
+          }
+        }
+        continue;
+      }
 #pragma unroll
       for (int j = 0; j < D32_SLOTS; ++j) {
         if (j < nslots) {                                     // uniform
-          const int p = 64 * j + lane;
+          const int p = 64 * j + lanev;
           // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far
           // more than the rounding error of the float product for p < 512
           const int w = (int)(((float)p + 0.5f) * rk);
@@ -162,11 +191,14 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
     const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
     const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
                                               : make_rsrc(static_cast<const float*>(d.param) + origin);
-    u32x2 Xh[16];   // bf16 parameters, raw: requested before the scatter, used after the products
-    if (PBF16) {
+    // bf16 parameters, raw: requested before the scatter (with 16-byte payload loads; the 4-byte path has too many
+    // addresses live for that and requests them after the payload of the next tile), used after the products
+    u32x2 Xh[16];
+    auto request_x = [&]() {
 #pragma unroll
       for (int q = 0; q < 16; ++q) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
-    }
+    };
+    if (PBF16 && VEC4) request_x();
 
     // ---- S = sum over workers, four chunks ----------------------------------------------------------------
 #pragma unroll
@@ -186,6 +218,7 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
     } else {
       load_payload(d, tt);
     }
+    if (PBF16 && !VEC4) request_x();
     wave_lds_sync();
 
     // ---- products -----------------------------------------------------------------------------------------
@@ -280,18 +313,18 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   }
 }
 
-template <bool PBF16>
+template <bool PBF16, bool VEC4>
 static hipError_t launch_dec_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, VEC4>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D32_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(decode2d_tile32<PBF16>, dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES, stream, tiles,
-                     tables, a);
+  hipLaunchKernelGGL((decode2d_tile32<PBF16, VEC4>), dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES, stream,
+                     tiles, tables, a);
   return hipGetLastError();
 }
 
@@ -301,8 +334,12 @@ hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, c
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tiles.total_chunks + D32_WAVES - 1) / D32_WAVES;
   if (grid > max_grid) grid = max_grid;
-  return param_bf16 ? launch_dec_tile32<true>(tiles, tables, a, grid, stream)
-                    : launch_dec_tile32<false>(tiles, tables, a, grid, stream);
+  const bool vec4 = (a.k & 3) == 0 && (tiles.dtypes & 16u) == 0;   // 16-byte payload loads
+  if (vec4)
+    return param_bf16 ? launch_dec_tile32<true, true>(tiles, tables, a, grid, stream)
+                      : launch_dec_tile32<false, true>(tiles, tables, a, grid, stream);
+  return param_bf16 ? launch_dec_tile32<true, false>(tiles, tables, a, grid, stream)
+                    : launch_dec_tile32<false, false>(tiles, tables, a, grid, stream);
 }
 
 }  // namespace demo
