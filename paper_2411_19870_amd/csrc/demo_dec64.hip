@@ -84,8 +84,9 @@ void build_dec64_tables(const double* P, float* out) {
 
 // PBF16: parameter dtype of every tensor in the table.  MODE 1: k == 32 and W == 64, the payload of a chunk is
 // read with eight fully populated 16-byte loads per array (eight workers each).  MODE 2: k == 32 and W a smaller
-// multiple of 8: the first W / 8 of those loads.  MODE 0: any k <= 64, W * k <= 2048, one pair per load.  Modes
-// 1 and 2 need 16-byte aligned payload arrays.
+// multiple of 8: the first W / 8 of those loads.  MODE 3 / 4: k a multiple of 4 / 2, any W: a lane fetches 4 / 2
+// consecutive pairs of one worker per load (unit 64 j + lane of the chunk's W k pairs in worker-major order).
+// MODE 0: any k <= 64, W * k <= 2048, one pair per load.  Modes 1 to 4 need 16-byte aligned payload arrays.
 template <bool PBF16, int MODE>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
@@ -97,7 +98,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   float* tile = lds + D64_G_FLOATS + wave * D64_TILE_FLOATS;
   int* itile = reinterpret_cast<int*>(tile);
   constexpr bool FULL = MODE == 1;          // every payload register is in use
-  constexpr bool WIDE = MODE != 0;          // 16-byte payload loads
+  constexpr bool WIDE = MODE == 1 || MODE == 2;   // 16-byte payload loads, eight workers per load
+  constexpr int VW = MODE == 3 ? 4 : MODE == 4 ? 2 : 1;   // pairs per load of the unit-wise modes
+  constexpr bool UNITS = MODE >= 3;
   const int k = WIDE ? 32 : args.k, W = args.W;
 
   for (int e = tid; e < D64_G_FLOATS / 4; e += D64_THREADS)
@@ -123,7 +126,10 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     pv[j] = 0.f;
   }
   const int wpi = k <= 32 ? 2 : 1;
-  const int nact = FULL ? NP : WIDE ? W / 2 : (W + wpi - 1) / wpi;   // payload registers in use (uniform)
+  const int nunits = (W * k) / VW;                                   // UNITS: loads per array and chunk
+  const int nloads = (nunits + 63) >> 6;                             // ... per lane
+  const float rk = 1.0f / (float)k;
+  const int nact = FULL ? NP : WIDE ? W / 2 : UNITS ? VW * nloads : (W + wpi - 1) / wpi;   // payload registers in use (uniform)
   const int sub = WIDE ? (lane >> 3) : (wpi == 2 ? (lane >> 5) : 0);
   const int pt = WIDE ? 4 * (lane & 7) : (wpi == 2 ? (lane & 31) : lane);
   const bool pact = WIDE || pt < k;
@@ -132,7 +138,42 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     const uint32_t lane_off = (uint32_t)(sub * (int)wstride + pt);
     const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)ccc * k;
     const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)ccc * k;
-    if (WIDE) {
+    if constexpr (UNITS) {
+      // worker and position of a unit are formed anew at every call (kept across the chunk loop they would be
+      // spilled, and the reload of a spilled value waits for every load in flight)
+      int lanev = lane;
+      asm volatile("" : "+v"(lanev));
+#pragma unroll
+      for (int j = 0; j < NP / VW; ++j) {
+        if (j < nloads) {   // uniform
+          const int unit = 64 * j + lanev;
+          const int p = VW * unit;
+          // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
+          // the rounding error of the float product for p < 2048
+          const int w = (int)(((float)p + 0.5f) * rk);
+          const int pos = p - w * k;
+          const bool ok = unit < nunits;
+          const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
+          if constexpr (VW == 4) {
+            const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+            const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
+              pv[4 * j + x] = ok ? b[x] : 0.f;
+            }
+          } else {
+            const u32x2 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x2*>(ip + off));
+            const f32x2 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x2*>(vp + off));
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+              pi[2 * j + x] = ok ? (int32_t)a[x] : -1;
+              pv[2 * j + x] = ok ? b[x] : 0.f;
+            }
+          }
+        }
+      }
+    } else if (WIDE) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         if (FULL || 4 * j < nact) {
@@ -584,17 +625,23 @@ hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, cons
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tv.total_chunks + D64_WAVES - 1) / D64_WAVES;
   if (grid > max_grid) grid = max_grid;
-  const int mode = (a.k == 32 && payload_aligned16 && a.W % 8 == 0 && a.W <= 64) ? (a.W == 64 ? 1 : 2) : 0;
+  const int mode = !payload_aligned16 ? 0
+                   : (a.k == 32 && a.W % 8 == 0 && a.W <= 64) ? (a.W == 64 ? 1 : 2)
+                   : a.k % 4 == 0 ? 3 : a.k % 2 == 0 ? 4 : 0;
   if (param_bf16) {
     switch (mode) {
       case 1: return launch_dec_wave64<true, 1>(tv, tables, a, grid, stream);
       case 2: return launch_dec_wave64<true, 2>(tv, tables, a, grid, stream);
+      case 3: return launch_dec_wave64<true, 3>(tv, tables, a, grid, stream);
+      case 4: return launch_dec_wave64<true, 4>(tv, tables, a, grid, stream);
       default: return launch_dec_wave64<true, 0>(tv, tables, a, grid, stream);
     }
   }
   switch (mode) {
     case 1: return launch_dec_wave64<false, 1>(tv, tables, a, grid, stream);
     case 2: return launch_dec_wave64<false, 2>(tv, tables, a, grid, stream);
+    case 3: return launch_dec_wave64<false, 3>(tv, tables, a, grid, stream);
+    case 4: return launch_dec_wave64<false, 4>(tv, tables, a, grid, stream);
     default: return launch_dec_wave64<false, 0>(tv, tables, a, grid, stream);
   }
 }

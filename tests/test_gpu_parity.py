@@ -399,6 +399,19 @@ def test_s64_decode_worker_counts(ctx, W, pdt):
     run_decode_check(ctx, case, W=W, wd=0.01)
 
 
+# ---- s = 64, other budgets: k a multiple of 4 (16-byte loads of four pairs), of 2 (8-byte loads), odd (one pair) ----
+@pytest.mark.parametrize("W,k", [(64, 16), (64, 8), (64, 4), (64, 2), (37, 12), (100, 6), (32, 64), (5, 32), (21, 20),
+                                 (64, 3), (33, 2), (128, 16), (17, 4)])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+def test_s64_decode_budgets(ctx, W, k, pdt):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 192, 320), synth.TensorSpec("b", 64, 64), synth.TensorSpec("v", 128, 0)]
+    case = Case(specs, 64, k, W=W, param_dtype=pdt, seed=300 + W + k)
+    case.fill_payloads()
+    st = run_decode_check(ctx, case, W=W, wd=0.01)
+    assert sum(x["elements"] for x in st) == sum(sp.numel for sp in specs)
+
+
 # ---- the context caches a few descriptor tables: more distinct tensor lists than that still work, and a list
 #      that was evicted is simply uploaded again ------------------------------------------------------------------
 def test_many_distinct_tensor_lists(ctx):
