@@ -684,10 +684,35 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
     {
       const int64_t wstride = (int64_t)d.nchunks * k;
       const int npairs = W * k;
+      // pair p = tid, tid + 256, ...: worker p / k, position p % k, advanced without dividing; loads in batches
+      // of four so that several are in flight per thread (S = 32 runs many workgroups per CU instead and keeps
+      // its registers: batches of one)
+      constexpr int NB = S == 32 ? 1 : 4;
+      const int dq = G::NT / k, dr = G::NT - dq * k;
+      const int w0 = tid / k, t0 = tid - w0 * k;
+      const float* vbase = d.val + (int64_t)c * k;
+      const int32_t* ibase = d.idx + (int64_t)c * k;
+      auto advance = [&](int& w, int& tt) {
+        w += dq;
+        tt += dr;
+        if (tt >= k) {
+          tt -= k;
+          ++w;
+        }
+      };
       float mx = 0.f;
-      for (int p = tid; p < npairs; p += G::NT) {
-        const int w = p / k, tt = p - w * k;
-        mx = fmaxf(mx, fabsf(d.val[(int64_t)w * wstride + (int64_t)c * k + tt]));
+      {
+        int w = w0, tt = t0;
+        for (int p = tid; p < npairs; p += NB * G::NT) {
+          float v[NB];
+#pragma unroll
+          for (int q = 0; q < NB; ++q) {
+            v[q] = p + q * G::NT < npairs ? vbase[(int64_t)w * wstride + tt] : 0.f;
+            advance(w, tt);
+          }
+#pragma unroll
+          for (int q = 0; q < NB; ++q) mx = fmaxf(mx, fabsf(v[q]));
+        }
       }
       uint32_t mb = __float_as_uint(mx);
 #pragma unroll
@@ -701,15 +726,28 @@ __global__ __launch_bounds__(256) void decode2d_generic(TableView tv, const floa
       for (int w = 1; w < W; w <<= 1) --vbits;
       const int sh = vbits + 126 - ex;
       int* iX = reinterpret_cast<int*>(sX);
-      for (int p = tid; p < npairs; p += G::NT) {
-        const int w = p / k, tt = p - w * k;
-        const int64_t po = (int64_t)w * wstride + (int64_t)c * k + tt;
-        const int fi = d.idx[po];
-        if (fi >= 0 && fi < G::M) {
-          const int u = fi / S, v = fi - u * S;
-          const int a = u * G::LD + v;
-          atomicAdd(&iX[a], __float2int_rn(ldexpf(d.val[po], sh)));
-          if (by_count) atomicAdd(&s_cnt[a >> 2], 1u << (8 * (a & 3)));   // W <= 255: no carry between bytes
+      {
+        int w = w0, tt = t0;
+        for (int p = tid; p < npairs; p += NB * G::NT) {
+          int fi[NB];
+          float fv[NB];
+#pragma unroll
+          for (int q = 0; q < NB; ++q) {
+            const bool ok = p + q * G::NT < npairs;
+            const int64_t po = (int64_t)w * wstride + tt;
+            fi[q] = ok ? ibase[po] : -1;
+            fv[q] = ok ? vbase[po] : 0.f;
+            advance(w, tt);
+          }
+#pragma unroll
+          for (int q = 0; q < NB; ++q) {
+            if (fi[q] >= 0 && fi[q] < G::M) {
+              const int u = fi[q] / S, v = fi[q] - u * S;
+              const int a = u * G::LD + v;
+              atomicAdd(&iX[a], __float2int_rn(ldexpf(fv[q], sh)));
+              if (by_count) atomicAdd(&s_cnt[a >> 2], 1u << (8 * (a & 3)));   // W <= 255: no carry between bytes
+            }
+          }
         }
       }
       __syncthreads();
