@@ -86,7 +86,10 @@ void build_dec64_tables(const double* P, float* out) {
 // read with eight fully populated 16-byte loads per array (eight workers each).  MODE 2: k == 32 and W a smaller
 // multiple of 8: the first W / 8 of those loads.  MODE 3 / 4: k a multiple of 4 / 2, any W: a lane fetches 4 / 2
 // consecutive pairs of one worker per load (unit 64 j + lane of the chunk's W k pairs in worker-major order).
-// MODE 0: any k <= 64, W * k <= 2048, one pair per load.  Modes 1 to 4 need 16-byte aligned payload arrays.
+// MODE 0: any k <= 64, W * k <= 2048, one pair per load.  MODE 5: k a multiple of 4 and more than 2048 pairs per
+// chunk (up to 65536): the payload is streamed in rounds of 2048 pairs, once for the largest magnitude (values only)
+// and once for the sums; the values of the first round of the next chunk are fetched during the products.
+// Modes 1 to 5 need 16-byte aligned payload arrays.
 template <bool PBF16, int MODE>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
@@ -99,8 +102,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   int* itile = reinterpret_cast<int*>(tile);
   constexpr bool FULL = MODE == 1;          // every payload register is in use
   constexpr bool WIDE = MODE == 1 || MODE == 2;   // 16-byte payload loads, eight workers per load
-  constexpr int VW = MODE == 3 ? 4 : MODE == 4 ? 2 : 1;   // pairs per load of the unit-wise modes
+  constexpr int VW = (MODE == 3 || MODE == 5) ? 4 : MODE == 4 ? 2 : 1;   // pairs per load of the unit-wise modes
   constexpr bool UNITS = MODE >= 3;
+  constexpr bool STREAM = MODE == 5;        // more pairs than the registers hold: rounds of 2048
   const int k = WIDE ? 32 : args.k, W = args.W;
 
   for (int e = tid; e < D64_G_FLOATS / 4; e += D64_THREADS)
@@ -127,13 +131,15 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   }
   const int wpi = k <= 32 ? 2 : 1;
   const int nunits = (W * k) / VW;                                   // UNITS: loads per array and chunk
-  const int nloads = (nunits + 63) >> 6;                             // ... per lane
+  const int nloads = STREAM ? NP / VW : (nunits + 63) >> 6;          // ... per lane (STREAM: per round)
+  const int nrounds = (nunits + 64 * (NP / VW) - 1) / (64 * (NP / VW));
   const float rk = 1.0f / (float)k;
   const int nact = FULL ? NP : WIDE ? W / 2 : UNITS ? VW * nloads : (W + wpi - 1) / wpi;   // payload registers in use (uniform)
   const int sub = WIDE ? (lane >> 3) : (wpi == 2 ? (lane >> 5) : 0);
   const int pt = WIDE ? 4 * (lane & 7) : (wpi == 2 ? (lane & 31) : lane);
   const bool pact = WIDE || pt < k;
-  auto load_payload = [&](const TensorDev& dd, int ccc) {
+  // `round` and `with_idx` matter in STREAM mode only: units 512 round + 64 j + lane, values alone or both arrays
+  auto load_payload = [&](const TensorDev& dd, int ccc, int round = 0, bool with_idx = true) {
     const int64_t wstride = (int64_t)dd.nchunks * k;
     const uint32_t lane_off = (uint32_t)(sub * (int)wstride + pt);
     const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)ccc * k;
@@ -146,21 +152,22 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 #pragma unroll
       for (int j = 0; j < NP / VW; ++j) {
         if (j < nloads) {   // uniform
-          const int unit = 64 * j + lanev;
+          const int unit = (STREAM ? 64 * (NP / VW) * round : 0) + 64 * j + lanev;
           const int p = VW * unit;
           // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
-          // the rounding error of the float product for p < 2048
+          // the rounding error of the float product for p < 65536
           const int w = (int)(((float)p + 0.5f) * rk);
           const int pos = p - w * k;
           const bool ok = unit < nunits;
           const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
           if constexpr (VW == 4) {
-            const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
             const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-              pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
-              pv[4 * j + x] = ok ? b[x] : 0.f;
+            for (int x = 0; x < 4; ++x) pv[4 * j + x] = ok ? b[x] : 0.f;
+            if (!STREAM || with_idx) {   // uniform
+              const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+#pragma unroll
+              for (int x = 0; x < 4; ++x) pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
             }
           } else {
             const u32x2 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x2*>(ip + off));
@@ -212,11 +219,14 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   const uint32_t dummy = (uint32_t)(lane * D64_LDT + 64);
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                // 30 - ceil(log2 W)
-  auto scatter = [&]() {
-    float mx = 0.f;
+  auto lane_max = [&](float mx) {
 #pragma unroll
     for (int j = 0; j < NP; ++j)
       if (FULL || j < nact) mx = fmaxf(mx, fabsf(pv[j]));
+    return mx;
+  };
+  // shift of the block fixed point from the lanes' largest magnitudes
+  auto shift_of = [&](float mx) {
     uint32_t mb = __float_as_uint(mx);
     mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
     mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
@@ -226,7 +236,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
     int ex = (int)(max(m01, m23) >> 23);                  // biased exponent of the largest magnitude
     ex = ex < 1 ? 1 : ex;
-    const int sh = vbits + 126 - ex;                      // max |val| * 2^sh < 2^vbits
+    return vbits + 126 - ex;                              // max |val| * 2^sh < 2^vbits
+  };
+  auto add_pairs = [&](int sh) {
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
       if (FULL || j < nact) {
@@ -238,11 +250,12 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       }
     }
   };
+  auto scatter = [&]() { add_pairs(shift_of(lane_max(0.f))); };
 
   int t = find_tensor_uniform(tv, chunk);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
-  load_payload(d, chunk - t_first);
+  load_payload(d, chunk - t_first, 0, false);
   const int kap = kappa(c), col4 = 4 * chi(c);
   // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
   // for members w' even / odd (w' >= 2 adds 32 columns)
@@ -271,7 +284,21 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 #pragma unroll
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
+    if constexpr (STREAM) {
+      // the registers hold the values of round 0; the other rounds' values, then both arrays round by round
+      float mx = lane_max(0.f);
+      for (int r = 1; r < nrounds; ++r) {
+        load_payload(d, cc, r, false);
+        mx = lane_max(mx);
+      }
+      const int sh = shift_of(mx);
+      for (int r = 0; r < nrounds; ++r) {
+        load_payload(d, cc, r, true);
+        add_pairs(sh);
+      }
+    } else {
+      scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
+    }
     DEMO_PHASE(1);
     // ---- payload of the next chunk, in flight during the products (after the last chunk the same
     //      chunk is requested again: an unconditional fetch keeps the old registers dead) -----------------
@@ -282,9 +309,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, chunk + nwaves - t_first);
+      load_payload(d, chunk + nwaves - t_first, 0, false);
     } else {
-      load_payload(d, cc);
+      load_payload(d, cc, 0, false);
     }
     wave_lds_sync();
     DEMO_PHASE(2);
@@ -619,6 +646,7 @@ static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, co
 
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream) {
+  if (!fast64_decode_supports(a.W, a.k, payload_aligned16)) return hipErrorInvalidValue;
   if (a.W * a.k <= 64)
     return param_bf16 ? launch_dec_sparse64<true>(tv, tables, a, num_cus, stream)
                       : launch_dec_sparse64<false>(tv, tables, a, num_cus, stream);
@@ -626,6 +654,7 @@ hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, cons
   const int64_t max_grid = ((int64_t)tv.total_chunks + D64_WAVES - 1) / D64_WAVES;
   if (grid > max_grid) grid = max_grid;
   const int mode = !payload_aligned16 ? 0
+                   : a.W * a.k > 2048 ? 5
                    : (a.k == 32 && a.W % 8 == 0 && a.W <= 64) ? (a.W == 64 ? 1 : 2)
                    : a.k % 4 == 0 ? 3 : a.k % 2 == 0 ? 4 : 0;
   if (param_bf16) {
@@ -634,6 +663,7 @@ hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, cons
       case 2: return launch_dec_wave64<true, 2>(tv, tables, a, grid, stream);
       case 3: return launch_dec_wave64<true, 3>(tv, tables, a, grid, stream);
       case 4: return launch_dec_wave64<true, 4>(tv, tables, a, grid, stream);
+      case 5: return launch_dec_wave64<true, 5>(tv, tables, a, grid, stream);
       default: return launch_dec_wave64<true, 0>(tv, tables, a, grid, stream);
     }
   }
@@ -642,6 +672,7 @@ hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, cons
     case 2: return launch_dec_wave64<false, 2>(tv, tables, a, grid, stream);
     case 3: return launch_dec_wave64<false, 3>(tv, tables, a, grid, stream);
     case 4: return launch_dec_wave64<false, 4>(tv, tables, a, grid, stream);
+    case 5: return launch_dec_wave64<false, 5>(tv, tables, a, grid, stream);
     default: return launch_dec_wave64<false, 0>(tv, tables, a, grid, stream);
   }
 }

@@ -121,7 +121,12 @@ constexpr int kFast128MaxPairs = 4096;
 hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
                                  int num_cus, hipStream_t stream);
 
-inline bool fast64_decode_supports(int W, int k) { return k <= kFast64MaxK && W <= (k <= 32 ? 64 : 32); }
+// ... and streams larger payloads (k a multiple of 4, 16-byte aligned arrays, at most 65536 pairs per chunk).
+inline bool fast64_decode_supports(int W, int k, bool payload_aligned16) {
+  if (k > kFast64MaxK) return false;
+  if ((int64_t)W * k <= 2048) return true;
+  return payload_aligned16 && k % 4 == 0 && (int64_t)W * k <= 65536;
+}
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream);
 

@@ -401,7 +401,9 @@ def test_s64_decode_worker_counts(ctx, W, pdt):
 
 # ---- s = 64, other budgets: k a multiple of 4 (16-byte loads of four pairs), of 2 (8-byte loads), odd (one pair) ----
 @pytest.mark.parametrize("W,k", [(64, 16), (64, 8), (64, 4), (64, 2), (37, 12), (100, 6), (32, 64), (5, 32), (21, 20),
-                                 (64, 3), (33, 2), (128, 16), (17, 4)])
+                                 (64, 3), (33, 2), (128, 16), (17, 4),
+                                 # more than 2048 pairs per chunk: streamed in rounds (k a multiple of 4), else generic
+                                 (128, 32), (255, 32), (100, 24), (70, 36), (130, 16), (513, 4), (90, 30)])
 @pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
 def test_s64_decode_budgets(ctx, W, k, pdt):
     ctx.demo_set_variant(1)
