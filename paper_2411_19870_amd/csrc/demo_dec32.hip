@@ -29,7 +29,7 @@ constexpr int D32_LDS_BYTES = 4 * (D32_G_FLOATS + D32_WAVES * D32_TILE_FLOATS);
 constexpr int D32_SLOTS = 8;                       // payload registers per lane and chunk
 static_assert(D32_G_FLOATS == kDec32TableFloats, "table size");
 static_assert(D32_LDS_BYTES <= 160 * 1024, "LDS budget");
-static_assert(kFast32MaxPairs == 64 * D32_SLOTS, "pairs per chunk held in registers");
+static_assert(kFast32MaxPairs == 64 * D32_SLOTS, "pairs per chunk held in registers (per round when streaming)");
 
 __host__ __device__ constexpr int kappa32(int c) { return 4 * (c & 3) + (c >> 2); }
 }  // namespace
@@ -47,11 +47,14 @@ void build_dec32_tables(const double* P32, float* out) {
 
 // The table `tv` lists the order-2 tensors in units of 64 x 64 tiles (cchunks = cols / 64, nchunks =
 // tiles); payload arrays are addressed per 32 x 32 chunk (4 * nchunks chunks per tensor).
-// VEC4: k is a multiple of four and every payload pointer is 16-byte aligned; a lane then fetches four consecutive
-// pairs of one worker with one 16-byte load per array (slot 8 q + 4 jj + e holds pair 4 (64 jj + lane) + e of chunk q).
-template <bool PBF16, bool VEC4>
+// MODE 1, 2 (VEC4): k is a multiple of four and every payload pointer is 16-byte aligned; a lane then fetches four
+// consecutive pairs of one worker with one 16-byte load per array (slot 8 q + 4 jj + e holds pair 4 (64 jj + lane) + e
+// of chunk q).  MODE 2 (STREAM): more than 512 pairs per chunk (up to 65536), streamed in rounds of 512 per chunk,
+// once for the largest magnitudes (values only) and once for the sums.  MODE 0: one pair per load.
+template <bool PBF16, int MODE>
 __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
+  constexpr bool VEC4 = MODE >= 1, STREAM = MODE == 2;
   extern __shared__ float lds[];
   const float* sG = lds;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -60,10 +63,11 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   float* tile = lds + D32_G_FLOATS + wave * D32_TILE_FLOATS;
   int* itile = reinterpret_cast<int*>(tile);
   const int k = args.k, W = args.W;
-  const int npairs = W * k;                                   // per chunk, <= 512
+  const int npairs = W * k;                                   // per chunk (<= 512 unless STREAM)
   const int nunits = VEC4 ? (npairs >> 2) : npairs;           // loads per array and chunk
-  const int nloads = (nunits + 63) >> 6;                      // ... per lane (uniform)
+  const int nloads = STREAM ? D32_SLOTS / 4 : (nunits + 63) >> 6;   // ... per lane (uniform; STREAM: per round)
   const int nslots = VEC4 ? 4 * nloads : nloads;              // payload registers in use per chunk (uniform)
+  const int nrounds = (nunits + 16 * D32_SLOTS - 1) / (16 * D32_SLOTS);   // STREAM: rounds of 64 * SLOTS / 4 units
 
   for (int e = tid; e < D32_G_FLOATS / 4; e += D32_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
@@ -83,7 +87,8 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
     pv[j] = 0.f;
   }
   const float rk = 1.0f / (float)k;
-  auto load_payload = [&](const TensorDev& dd, int tt) {
+  // `round` and `with_idx` matter in STREAM mode only: units 128 round + 64 jj + lane, values alone or both arrays
+  auto load_payload = [&](const TensorDev& dd, int tt, int round = 0, bool with_idx = true) {
     const int K0 = tt / dd.cchunks, K1 = tt - K0 * dd.cchunks;
     const int cch32 = 2 * dd.cchunks;
     const int64_t wstride = (int64_t)dd.nchunks * 4 * k;      // pairs of one worker for this tensor
@@ -100,18 +105,19 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
 #pragma unroll
         for (int jj = 0; jj < D32_SLOTS / 4; ++jj) {
           if (jj < nloads) {                                  // uniform
-            const int unit = 64 * jj + lanev;
+            const int unit = (STREAM ? 16 * D32_SLOTS * round : 0) + 64 * jj + lanev;
             const int p = 4 * unit;
-            const int w = (int)(((float)p + 0.5f) * rk);      // as below
+            const int w = (int)(((float)p + 0.5f) * rk);      // as below (p < 65536)
             const int pos = p - w * k;
             const bool ok = unit < nunits;
             const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
-            const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
             const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
-              pv[D32_SLOTS * q + 4 * jj + e] = ok ? vv[e] : 0.f;
+            for (int e = 0; e < 4; ++e) pv[D32_SLOTS * q + 4 * jj + e] = ok ? vv[e] : 0.f;
+            if (!STREAM || with_idx) {   // uniform
+              const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+#pragma unroll
+              for (int e = 0; e < 4; ++e) pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
             }
           }
         }
@@ -140,13 +146,14 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   const uint32_t dummy = (uint32_t)(lane * D32_LDT + 64);
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                    // 30 - ceil(log2 W)
-  auto scatter = [&]() {
+  auto lane_max = [&](int q, float mx) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float mx = 0.f;
-#pragma unroll
-      for (int j = 0; j < D32_SLOTS; ++j)
-        if (j < nslots) mx = fmaxf(mx, fabsf(pv[D32_SLOTS * q + j]));
+    for (int j = 0; j < D32_SLOTS; ++j)
+      if (j < nslots) mx = fmaxf(mx, fabsf(pv[D32_SLOTS * q + j]));
+    return mx;
+  };
+  // shift of a chunk's block fixed point from the lanes' largest magnitudes
+  auto shift_of = [&](float mx) {
       uint32_t mb = __float_as_uint(mx);
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
@@ -156,7 +163,9 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
       const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
       int ex = (int)(max(m01, m23) >> 23);                    // biased exponent of the chunk's largest magnitude
       ex = ex < 1 ? 1 : ex;
-      const int sh = vbits + 126 - ex;                        // max |val| * 2^sh < 2^vbits
+      return vbits + 126 - ex;                                // max |val| * 2^sh < 2^vbits
+  };
+  auto add_pairs = [&](int q, int sh) {
       const uint32_t quad = (uint32_t)(((q >> 1) << 11) | ((q & 1) << 5));
 #pragma unroll
       for (int j = 0; j < D32_SLOTS; ++j) {
@@ -168,13 +177,16 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
           atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[D32_SLOTS * q + j], sh)));
         }
       }
-    }
+  };
+  auto scatter = [&]() {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) add_pairs(q, shift_of(lane_max(q, 0.f)));
   };
 
   int t = find_tensor_uniform(tv, tileno);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
-  load_payload(d, tileno - t_first);
+  load_payload(d, tileno - t_first, 0, false);
   const int kap = kappa32(c), col4 = 4 * chi(c);
   // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
   // for members w' even / odd (w' >= 2 adds 32 columns)
@@ -204,7 +216,27 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
 #pragma unroll
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    scatter();
+    if constexpr (STREAM) {
+      // the registers hold the values of round 0; the other rounds' values, then both arrays round by round
+      float mx[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) mx[q] = lane_max(q, 0.f);
+      for (int r = 1; r < nrounds; ++r) {
+        load_payload(d, tt, r, false);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) mx[q] = lane_max(q, mx[q]);
+      }
+      int sh[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) sh[q] = shift_of(mx[q]);
+      for (int r = 0; r < nrounds; ++r) {
+        load_payload(d, tt, r, true);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) add_pairs(q, sh[q]);
+      }
+    } else {
+      scatter();
+    }
     // ---- payload of the next tile, in flight during the products (after the last tile the same tile is
     //      requested again: an unconditional fetch keeps the old registers dead) -----------------------------
     if (tileno + nwaves < total) {
@@ -214,9 +246,9 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, tileno + nwaves - t_first);
+      load_payload(d, tileno + nwaves - t_first, 0, false);
     } else {
-      load_payload(d, tt);
+      load_payload(d, tt, 0, false);
     }
     if (PBF16 && !VEC4) request_x();
     wave_lds_sync();
@@ -313,33 +345,41 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   }
 }
 
-template <bool PBF16, bool VEC4>
+template <bool PBF16, int MODE>
 static hipError_t launch_dec_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, VEC4>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, MODE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D32_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_tile32<PBF16, VEC4>), dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES, stream,
+  hipLaunchKernelGGL((decode2d_tile32<PBF16, MODE>), dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES, stream,
                      tiles, tables, a);
   return hipGetLastError();
 }
 
 hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   int num_cus, hipStream_t stream) {
-  if (a.W * a.k > kFast32MaxPairs || a.W < 1) return hipErrorInvalidValue;   // the registers hold 512 pairs per chunk
+  const bool aligned16 = (tiles.dtypes & 16u) == 0;
+  if (!fast32_decode_supports(a.W, a.k, aligned16)) return hipErrorInvalidValue;
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tiles.total_chunks + D32_WAVES - 1) / D32_WAVES;
   if (grid > max_grid) grid = max_grid;
-  const bool vec4 = (a.k & 3) == 0 && (tiles.dtypes & 16u) == 0;   // 16-byte payload loads
-  if (vec4)
-    return param_bf16 ? launch_dec_tile32<true, true>(tiles, tables, a, grid, stream)
-                      : launch_dec_tile32<false, true>(tiles, tables, a, grid, stream);
-  return param_bf16 ? launch_dec_tile32<true, false>(tiles, tables, a, grid, stream)
-                    : launch_dec_tile32<false, false>(tiles, tables, a, grid, stream);
+  const int mode = (int64_t)a.W * a.k > kFast32MaxPairs ? 2 : ((a.k & 3) == 0 && aligned16) ? 1 : 0;
+  if (param_bf16) {
+    switch (mode) {
+      case 2: return launch_dec_tile32<true, 2>(tiles, tables, a, grid, stream);
+      case 1: return launch_dec_tile32<true, 1>(tiles, tables, a, grid, stream);
+      default: return launch_dec_tile32<true, 0>(tiles, tables, a, grid, stream);
+    }
+  }
+  switch (mode) {
+    case 2: return launch_dec_tile32<false, 2>(tiles, tables, a, grid, stream);
+    case 1: return launch_dec_tile32<false, 1>(tiles, tables, a, grid, stream);
+    default: return launch_dec_tile32<false, 0>(tiles, tables, a, grid, stream);
+  }
 }
 
 }  // namespace demo

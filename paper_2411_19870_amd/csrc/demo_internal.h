@@ -107,6 +107,12 @@ hipError_t launch_encode2d_tile32(const TableView& tiles, const int32_t* prefix3
 // s = 32 decode, one wavefront per 64 x 64 tile (2 x 2 chunks): the registers hold W*k <= 512 pairs per chunk
 constexpr int kDec32TableFloats = 512;
 constexpr int kFast32MaxPairs = 512;
+// ... and streams larger payloads (k a multiple of 4, 16-byte aligned arrays, at most 65536 pairs per chunk)
+inline bool fast32_decode_supports(int W, int k, bool payload_aligned16) {
+  if (W < 1 || k < 1) return false;
+  if ((int64_t)W * k <= kFast32MaxPairs) return true;
+  return payload_aligned16 && k % 4 == 0 && (int64_t)W * k <= 65536;
+}
 void build_dec32_tables(const double* P32, float* out /* kDec32TableFloats */);
 hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   int num_cus, hipStream_t stream);

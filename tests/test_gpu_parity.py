@@ -257,7 +257,9 @@ def test_timing_hooks(ctx):
 
 
 # ---- s = 32 decode: wavefront-per-tile kernel (tile-aligned shapes, W*k <= 512) and the fallback ---------------
-@pytest.mark.parametrize("W,k", [(16, 32), (1, 32), (5, 7), (64, 8), (3, 1), (8, 32), (17, 32)])
+@pytest.mark.parametrize("W,k", [(16, 32), (1, 32), (5, 7), (64, 8), (3, 1), (8, 32), (17, 32),
+                                 # more than 512 pairs per chunk: streamed in rounds (k a multiple of 4), else generic
+                                 (64, 32), (255, 8), (40, 20), (33, 16), (100, 7), (200, 32)])
 @pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
 def test_s32_decode_tile_kernel(ctx, W, k, pdt):
     ctx.demo_set_variant(1)
