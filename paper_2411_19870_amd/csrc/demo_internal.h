@@ -124,6 +124,12 @@ hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const 
                                  bool grad_bf16, int num_cus, hipStream_t stream);
 // decode keeps the W*k pairs of a chunk in four registers per lane of its 1024 threads
 constexpr int kFast128MaxPairs = 4096;
+// ... and streams larger payloads (k a multiple of 4, 16-byte aligned arrays, at most 65536 pairs per chunk)
+inline bool fast128_decode_supports(int W, int k, bool payload_aligned16) {
+  if (W < 1 || k < 1) return false;
+  if ((int64_t)W * k <= kFast128MaxPairs) return true;
+  return payload_aligned16 && k % 4 == 0 && (int64_t)W * k <= 65536;
+}
 hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
                                  int num_cus, hipStream_t stream);
 

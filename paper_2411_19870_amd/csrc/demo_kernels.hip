@@ -1084,8 +1084,8 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
   if (variant >= 1 && s == 64 && decode_is_sign_of_sum(a) && fast64_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 &&
       bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
-  if (variant >= 1 && s == 128 && a.mirror != 0 && decode_is_sign_of_sum(a) && (int64_t)a.W * a.k <= kFast128MaxPairs &&
-      payload_fits32 && (pmix == 1u || pmix == 2u))
+  if (variant >= 1 && s == 128 && a.mirror != 0 && decode_is_sign_of_sum(a) &&
+      fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wg128(tv, bt.basis, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {

@@ -504,9 +504,15 @@ constexpr int W128_DEC_LDS_BYTES = 4 * (W128_PT_FLOATS + W128_X_FLOATS + 16);
 static_assert(kFast128MaxPairs == W128_DEC_SLOTS * W128_THREADS, "pairs per chunk held in registers");
 }  // namespace
 
-template <bool PBF16>
+// STREAM false: W k <= 4096, one pair per load (consecutive threads read consecutive pairs, and the pairs are spread
+// evenly over the sixteen wavefronts; 16-byte loads would leave half of them without work at W k = 2048 and measured
+// slower).  STREAM true: more than 4096 pairs per chunk (up to 65536), k a multiple of four and 16-byte aligned payload
+// arrays: rounds of 4096 pairs, a thread fetching four consecutive pairs of one worker per load, once for the largest
+// magnitude (values only) and once for the sums.
+template <bool PBF16, bool STREAM>
 __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, const float* __restrict__ basis,
                                                                 DecodeArgs args) {
+  constexpr bool VEC4 = STREAM;
   extern __shared__ float lds[];
   float* sPT = lds;
   float* tile = sPT + W128_PT_FLOATS;
@@ -517,7 +523,9 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   const int l16 = lane & 15, lq = lane >> 4;
   const int k = args.k, W = args.W;
   const int npairs = W * k;
-  const int nslots = (npairs + W128_THREADS - 1) / W128_THREADS;   // payload registers in use (uniform)
+  const int nunits = npairs >> 2;                                  // VEC4: 16-byte units per chunk
+  const int nslots = VEC4 ? W128_DEC_SLOTS : (npairs + W128_THREADS - 1) / W128_THREADS;   // payload registers in use (uniform)
+  const int nrounds = STREAM ? (nunits + W128_THREADS - 1) / W128_THREADS : 1;
   const int total = tv.total_chunks;
   int chunk = blockIdx.x;
   if (chunk >= total) return;
@@ -538,10 +546,29 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     pv[j] = 0.f;
   }
   const float rk = 1.0f / (float)k;
-  auto load_payload = [&](const TensorDev& dd, int cc) {
+  // `round` and `with_idx` matter in STREAM mode only: units 1024 round + tid, values alone or both arrays
+  auto load_payload = [&](const TensorDev& dd, int cc, int round = 0, bool with_idx = true) {
     const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)cc * k;
     const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)cc * k;
     const int wstride = dd.nchunks * k;                        // pairs of one worker for this tensor
+    if constexpr (VEC4) {
+      static_assert(W128_DEC_SLOTS == 4, "one 16-byte load per array fills the payload registers");
+      const int unit = (STREAM ? W128_THREADS * round : 0) + tid;
+      const int p = 4 * unit;
+      const int w = (int)(((float)p + 0.5f) * rk);             // as below (p < 65536)
+      const int pos = p - w * k;
+      const bool ok = unit < nunits;
+      const uint32_t off = ok ? (uint32_t)(w * wstride + pos) : 0u;
+      const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pv[e] = ok ? vv[e] : 0.f;
+      if (!STREAM || with_idx) {   // uniform
+        const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pi[e] = ok ? (int32_t)iv[e] : -1;
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < W128_DEC_SLOTS; ++j) {
       if (j < nslots) {                                        // uniform
@@ -561,7 +588,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   int t = find_tensor_uniform(tv, chunk);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
-  load_payload(d, chunk - t_first);
+  load_payload(d, chunk - t_first, 0, false);
 
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                     // 30 - ceil(log2 W)
@@ -579,9 +606,13 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     // ---- largest |val| of the chunk, zero tile --------------------------------------------------------------
     {
       float mx = 0.f;
+      // (STREAM: the registers hold the values of round 0; then the other rounds' values)
+      for (int r = 0; r < nrounds; ++r) {
+        if (r > 0) load_payload(d, cc, r, false);
 #pragma unroll
-      for (int j = 0; j < W128_DEC_SLOTS; ++j)
-        if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
+        for (int j = 0; j < W128_DEC_SLOTS; ++j)
+          if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
+      }
       uint32_t mb = __float_as_uint(mx);
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
@@ -605,12 +636,15 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       int ex = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)mall) >> 23);   // biased exponent of the largest magnitude
       ex = ex < 1 ? 1 : ex;
       const int sh = vbits + 126 - ex;                         // max |val| * 2^sh < 2^vbits
+      for (int r = 0; r < nrounds; ++r) {
+        if (STREAM) load_payload(d, cc, r, true);
 #pragma unroll
-      for (int j = 0; j < W128_DEC_SLOTS; ++j) {
-        if (j < nslots) {
-          const uint32_t fi = (uint32_t)pi[j];
-          const uint32_t a = fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
-          atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
+        for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+          if (j < nslots) {
+            const uint32_t fi = (uint32_t)pi[j];
+            const uint32_t a = fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
+            atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
+          }
         }
       }
     }
@@ -623,7 +657,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, nxt - t_first);
+      load_payload(d, nxt - t_first, 0, false);
     }
     wg_lds_barrier();
 
@@ -757,28 +791,31 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   }
 }
 
-template <bool PBF16>
+template <bool PBF16, bool STREAM>
 static hipError_t launch_dec_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
                                    hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16, STREAM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, W128_DEC_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(decode2d_wg128<PBF16>, dim3((unsigned)grid), dim3(W128_THREADS), W128_DEC_LDS_BYTES, stream, tv,
-                     basis, a);
+  hipLaunchKernelGGL((decode2d_wg128<PBF16, STREAM>), dim3((unsigned)grid), dim3(W128_THREADS), W128_DEC_LDS_BYTES,
+                     stream, tv, basis, a);
   return hipGetLastError();
 }
 
 hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
                                  int num_cus, hipStream_t stream) {
-  if (a.W < 1 || a.k < 1 || (int64_t)a.W * a.k > kFast128MaxPairs) return hipErrorInvalidValue;
+  if (!fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0)) return hipErrorInvalidValue;
   int64_t grid = num_cus;
   if (grid > tv.total_chunks) grid = tv.total_chunks;
-  return param_bf16 ? launch_dec_wg128<true>(tv, basis, a, grid, stream)
-                    : launch_dec_wg128<false>(tv, basis, a, grid, stream);
+  if ((int64_t)a.W * a.k > kFast128MaxPairs)
+    return param_bf16 ? launch_dec_wg128<true, true>(tv, basis, a, grid, stream)
+                      : launch_dec_wg128<false, true>(tv, basis, a, grid, stream);
+  return param_bf16 ? launch_dec_wg128<true, false>(tv, basis, a, grid, stream)
+                    : launch_dec_wg128<false, false>(tv, basis, a, grid, stream);
 }
 
 }  // namespace demo

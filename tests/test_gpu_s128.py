@@ -88,10 +88,11 @@ def test_all_zero_and_constant_chunks(ctx):
     run_encode_check(ctx, case2)
 
 
-@pytest.mark.parametrize("W,k", [(128, 32), (129, 32), (64, 64), (255, 16), (1, 1), (33, 7)])
+@pytest.mark.parametrize("W,k", [(128, 32), (129, 32), (64, 64), (255, 16), (1, 1), (33, 7), (255, 32), (200, 30), (90, 6)])
 @pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
 def test_decode_payload_sizes(ctx, W, k, pdt):
-    # W k = 4096 is the register capacity of the workgroup kernel; past it the generic kernel runs
+    # W k = 4096 is the register capacity of the workgroup kernel; past it the payload is streamed in rounds
+    # (k a multiple of 4) or the generic kernel runs
     specs = [synth.TensorSpec("a", 256, 384), synth.TensorSpec("v", 256, 0)]
     case = Case(specs, S, k, W=W, param_dtype=pdt, seed=200 + W)
     case.fill_payloads()
