@@ -40,10 +40,10 @@ __device__ __forceinline__ void wg_lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// class-major position of frequency u: u = 0 mod 4 first, then u = 2 mod 4, then odd u; and its inverse
+// class-major position of frequency u: u = 0 mod 4 first, then u = 2 mod 4, then odd u
 __device__ __forceinline__ int pos3(uint32_t u) { return (int)((u & 1u) ? 64u + (u >> 1) : ((u & 2u) << 4) + (u >> 2)); }
 
-// folded basis into LDS: P[u][i], i < 64, at row pos(u)
+// folded basis into LDS: P[u][i], i < 64, at row pos3(u)
 __device__ __forceinline__ void stage_folded_basis(float* sP, const float* __restrict__ basis, int tid) {
   for (int e = tid; e < 128 * 16; e += W128_THREADS) {
     const int u = e >> 4, c4 = (e & 15) * 4;
@@ -374,7 +374,7 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
         out_idx[rank] = (int32_t)me.y;
         out_val[rank] = __uint_as_float(me.x);
         const int cls = (int)(((me.y >> 6) & 2u) | (me.y & 1u));
-        // byte offsets of rows pos(u) and pos(v) of the basis tile, and the value
+        // byte offsets of rows pos3(u) and pos3(v) of the basis tile, and the value
         const uint32_t offs = (uint32_t)(pos3(me.y >> 7) * (W128_LDP * 4)) | ((uint32_t)(pos3(me.y & 127u) * (W128_LDP * 4)) << 16);
         sel[cls * W128_SEL + rcls] = make_uint2(offs, me.x);
         atomicAdd(&ctl[4 + cls], 1);
