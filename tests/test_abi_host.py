@@ -1,6 +1,7 @@
 """Host-side checks that need no GPU: the shared library loads, exports every
 function include/demo.h declares, and rejects bad arguments before any launch."""
 import ctypes
+import numpy as np
 import os
 import re
 
@@ -155,3 +156,14 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libdemo.so"))
     with pytest.raises(FileNotFoundError):
         B.load_library()
+
+
+def test_worker_and_position_of_a_pair_from_a_float_product():
+    """The decode kernels split pair number p of a chunk into worker p // k and position p % k with one float32
+    multiply, w = int((p + 0.5) * (1 / k)), for p < 65536 (the streamed payload limit) and every budget k the
+    ABI accepts: emulated here in float32, it must agree with the integer division for all of them."""
+    p = np.arange(0, 65536, dtype=np.int64)
+    for k in range(1, 257):
+        rk = np.float32(1.0) / np.float32(k)
+        w = ((p.astype(np.float32) + np.float32(0.5)) * rk).astype(np.int32)
+        assert np.array_equal(w, p // k), k
