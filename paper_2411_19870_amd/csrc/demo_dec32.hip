@@ -15,6 +15,8 @@
 // Payload: the W*k <= 512 pairs of each of the four chunks sit in 8 registers per lane and chunk (pair
 // p = 64 j + lane of the chunk belongs to worker p / k, position p % k) and are fetched for the next tile
 // while the products of this one run.  Each chunk has its own fixed-point scale.
+#include <type_traits>
+
 #include "demo_device.h"
 
 namespace demo {
@@ -51,7 +53,9 @@ void build_dec32_tables(const double* P32, float* out) {
 // consecutive pairs of one worker with one 16-byte load per array (slot 8 q + 4 jj + e holds pair 4 (64 jj + lane) + e
 // of chunk q).  MODE 2 (STREAM): more than 512 pairs per chunk (up to 65536), streamed in rounds of 512 per chunk,
 // once for the largest magnitudes (values only) and once for the sums.  MODE 0: one pair per load.
-template <bool PBF16, int MODE>
+// IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
+// nothing for it).
+template <bool PBF16, int MODE, bool IDENT>
 __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   constexpr bool VEC4 = MODE >= 1, STREAM = MODE == 2;
@@ -178,9 +182,13 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
         }
       }
   };
+  int sh[4];   // shifts of the four chunks' fixed points (undone when phi is the identity)
   auto scatter = [&]() {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) add_pairs(q, shift_of(lane_max(q, 0.f)));
+    for (int q = 0; q < 4; ++q) {
+      sh[q] = shift_of(lane_max(q, 0.f));
+      add_pairs(q, sh[q]);
+    }
   };
 
   int t = find_tensor_uniform(tv, tileno);
@@ -226,7 +234,6 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
 #pragma unroll
         for (int q = 0; q < 4; ++q) mx[q] = lane_max(q, mx[q]);
       }
-      int sh[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) sh[q] = shift_of(mx[q]);
       for (int r = 0; r < nrounds; ++r) {
@@ -304,7 +311,12 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
     }
     wave_lds_sync();
 
-    // ---- x <- x - lr*(sgn(R) + wd*x) ------------------------------------------------------------------------
+    // ---- x <- x - lr*(phi(R) + wd*x): phi = sgn, or the identity on the aggregate (the sums of chunk q carry the
+    //      factor 2^sh[q]; rows of members w < 2 lie in the upper chunks, this lane's columns in the left or right
+    //      ones) ---------------------------------------------------------------------------------------------------
+    const bool right = (c & 3) >= 2;
+    const float f_up = IDENT ? ldexpf(args.scale, -(right ? sh[1] : sh[0])) : 0.f;
+    const float f_dn = IDENT ? ldexpf(args.scale, -(right ? sh[3] : sh[2])) : 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       f32x4 xin[4];   // fp32 parameters of the four rows of this quadruple
@@ -329,7 +341,7 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
           } else {
             x = xin[w][e];
           }
-          o[e] = sign_update(x, sgnf(rr[e]), args.lr, args.weight_decay);
+          o[e] = sign_update(x, IDENT ? rr[e] * (w < 2 ? f_up : f_dn) : sgnf(rr[e]), args.lr, args.weight_decay);
         }
         const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
         if (PBF16) {
@@ -345,19 +357,25 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   }
 }
 
-template <bool PBF16, int MODE>
-static hipError_t launch_dec_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
-                                    hipStream_t stream) {
+template <bool PBF16, int MODE, bool IDENT>
+static hipError_t launch_dec_tile32_phi(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
+                                        hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, MODE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, MODE, IDENT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D32_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_tile32<PBF16, MODE>), dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES, stream,
-                     tiles, tables, a);
+  hipLaunchKernelGGL((decode2d_tile32<PBF16, MODE, IDENT>), dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES,
+                     stream, tiles, tables, a);
   return hipGetLastError();
+}
+template <bool PBF16, int MODE>
+static hipError_t launch_dec_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
+                                    hipStream_t stream) {
+  return a.phi != 0 ? launch_dec_tile32_phi<PBF16, MODE, true>(tiles, tables, a, grid, stream)
+                    : launch_dec_tile32_phi<PBF16, MODE, false>(tiles, tables, a, grid, stream);
 }
 
 hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,

@@ -28,6 +28,8 @@
 //   product b   per w':  Cee/Ceo/Co0/Co1[i0][j] += G (as A) * Y tile (accumulators as B operand),
 //               row tile t feeding the class t belongs to; the four row members by in-lane adds.
 // Both products use the same fragment table G (6 groups x 64 lanes x 4 floats).
+#include <type_traits>
+
 #include "demo_device.h"
 
 namespace demo {
@@ -90,7 +92,9 @@ void build_dec64_tables(const double* P, float* out) {
 // chunk (up to 65536): the payload is streamed in rounds of 2048 pairs, once for the largest magnitude (values only)
 // and once for the sums; the values of the first round of the next chunk are fetched during the products.
 // Modes 1 to 5 need 16-byte aligned payload arrays.
-template <bool PBF16, int MODE>
+// IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
+// nothing for it).
+template <bool PBF16, int MODE, bool IDENT>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   extern __shared__ float lds[];
@@ -250,7 +254,11 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       }
     }
   };
-  auto scatter = [&]() { add_pairs(shift_of(lane_max(0.f))); };
+  auto scatter = [&]() {
+    const int sh = shift_of(lane_max(0.f));
+    add_pairs(sh);
+    return sh;
+  };
 
   int t = find_tensor_uniform(tv, chunk);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
@@ -284,6 +292,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 #pragma unroll
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
+    int sh_chunk;   // shift of this chunk's fixed point (undone when phi is the identity)
     if constexpr (STREAM) {
       // the registers hold the values of round 0; the other rounds' values, then both arrays round by round
       float mx = lane_max(0.f);
@@ -291,13 +300,13 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
         load_payload(d, cc, r, false);
         mx = lane_max(mx);
       }
-      const int sh = shift_of(mx);
+      sh_chunk = shift_of(mx);
       for (int r = 0; r < nrounds; ++r) {
         load_payload(d, cc, r, true);
-        add_pairs(sh);
+        add_pairs(sh_chunk);
       }
     } else {
-      scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
+      sh_chunk = scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
     }
     DEMO_PHASE(1);
     // ---- payload of the next chunk, in flight during the products (after the last chunk the same
@@ -390,7 +399,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     wave_lds_sync();
     DEMO_PHASE(4);
 
-    // ---- x <- x - lr*(sgn(R) + wd*x) ------------------------------------------------------------------------
+    // ---- x <- x - lr*(phi(R) + wd*x): phi = sgn (the scale of the fixed point does not matter), or the identity
+    //      on the aggregate itself (the sum of the tile is R * 2^sh; `scale` is 1 or 1/W) ------------------------------
+    const float factor = IDENT ? ldexpf(args.scale, -sh_chunk) : 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       f32x4 xin[4];   // fp32 parameters of the four rows of this quadruple
@@ -415,7 +426,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
           } else {
             x = xin[w][e];
           }
-          o[e] = sign_update(x, sgnf(rr[e]), args.lr, args.weight_decay);
+          o[e] = sign_update(x, IDENT ? rr[e] * factor : sgnf(rr[e]), args.lr, args.weight_decay);
         }
         const uint32_t vo = (q & 1) ? vo_dn : vo_up, so = (uint32_t)rho_base(q) * ucols;
         if (PBF16) {
@@ -573,7 +584,10 @@ __global__ __launch_bounds__(D64S_THREADS, 3) void decode2d_sparse64(TableView t
       }
     }
 
-    // x <- x - lr*(sgn(R) + wd*x); members of the quadruple with base 4s + g: rows rho(4s + w, g)
+    // x <- x - lr*(phi(R) + wd*x); members of the quadruple with base 4s + g: rows rho(4s + w, g).  phi = sgn, or the
+    // identity on the aggregate (times `scale`: 1 or 1/W), chosen per element: this kernel has registers for one copy
+    // of the loop only
+    const bool ident = args.phi != 0;
 #pragma unroll
     for (int sq = 0; sq < 4; ++sq) {
       float o[4][4];   // [w][e]
@@ -591,7 +605,7 @@ __global__ __launch_bounds__(D64S_THREADS, 3) void decode2d_sparse64(TableView t
           } else {
             x = Xf[q][e];
           }
-          o[w][e] = sign_update(x, sgnf(rr[w]), args.lr, args.weight_decay);
+          o[w][e] = sign_update(x, ident ? rr[w] * args.scale : sgnf(rr[w]), args.lr, args.weight_decay);
         }
       }
 #pragma unroll
@@ -629,19 +643,25 @@ static hipError_t launch_dec_sparse64(const TableView& tv, const float* tables, 
   return hipGetLastError();
 }
 
-template <bool PBF16, int MODE>
-static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
-                                    hipStream_t stream) {
+template <bool PBF16, int MODE, bool IDENT>
+static hipError_t launch_dec_wave64_phi(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
+                                        hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE, IDENT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D64_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE>), dim3((unsigned)grid), dim3(D64_THREADS), D64_LDS_BYTES, stream,
-                     tv, tables, a);
+  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE, IDENT>), dim3((unsigned)grid), dim3(D64_THREADS), D64_LDS_BYTES,
+                     stream, tv, tables, a);
   return hipGetLastError();
+}
+template <bool PBF16, int MODE>
+static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
+                                    hipStream_t stream) {
+  return a.phi != 0 ? launch_dec_wave64_phi<PBF16, MODE, true>(tv, tables, a, grid, stream)
+                    : launch_dec_wave64_phi<PBF16, MODE, false>(tv, tables, a, grid, stream);
 }
 
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,

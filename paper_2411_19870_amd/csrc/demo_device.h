@@ -17,8 +17,23 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ f32x4 gload_f4(const float* p) { return *(const DEMO_GLOBAL f32x4*)(p); }
 __device__ __forceinline__ u32x2 gload_u2(const void* p) { return *(const DEMO_GLOBAL u32x2*)(p); }
-__device__ __forceinline__ void gstore_f4(float* p, f32x4 v) { *(DEMO_GLOBAL f32x4*)(p) = v; }
-__device__ __forceinline__ void gstore_u2(void* p, u32x2 v) { *(DEMO_GLOBAL u32x2*)(p) = v; }
+// Stores whose data registers stay untouched for two wait states behind them (see bstore_f4 below for why).
+template <class T>
+__device__ __forceinline__ void store_guarded(DEMO_GLOBAL T* p, T v) {
+  *p = v;
+#ifndef DEMO_NO_STORE_GUARD
+  asm volatile("s_nop 1" ::"v"(v));
+#endif
+}
+template <class T>
+__device__ __forceinline__ void store_guarded(T* p, T v) {
+  *p = v;
+#ifndef DEMO_NO_STORE_GUARD
+  asm volatile("s_nop 1" ::"v"(v));
+#endif
+}
+__device__ __forceinline__ void gstore_f4(float* p, f32x4 v) { store_guarded((DEMO_GLOBAL f32x4*)(p), v); }
+__device__ __forceinline__ void gstore_u2(void* p, u32x2 v) { store_guarded((DEMO_GLOBAL u32x2*)(p), v); }
 
 // ---------------------------------------------------------------------------
 // small helpers
@@ -85,12 +100,12 @@ __device__ __forceinline__ float4 load4(const void* __restrict__ base, int64_t o
 
 __device__ __forceinline__ void store4(void* __restrict__ base, int64_t off, int is_bf16, float4 v) {
   if (is_bf16) {
-    uint2 r;
-    r.x = f32_to_bf16_rne(v.x) | (f32_to_bf16_rne(v.y) << 16);
-    r.y = f32_to_bf16_rne(v.z) | (f32_to_bf16_rne(v.w) << 16);
-    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + off) = r;
+    u32x2 r;
+    r[0] = f32_to_bf16_rne(v.x) | (f32_to_bf16_rne(v.y) << 16);
+    r[1] = f32_to_bf16_rne(v.z) | (f32_to_bf16_rne(v.w) << 16);
+    store_guarded(reinterpret_cast<u32x2*>(static_cast<uint16_t*>(base) + off), r);
   } else {
-    *reinterpret_cast<float4*>(static_cast<float*>(base) + off) = v;
+    store_guarded(reinterpret_cast<f32x4*>(static_cast<float*>(base) + off), (f32x4){v.x, v.y, v.z, v.w});
   }
 }
 
@@ -157,11 +172,22 @@ __device__ __forceinline__ f32x4 bload_f4(__amdgpu_buffer_rsrc_t r, uint32_t vof
 __device__ __forceinline__ u32x2 bload_u2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
   return __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(r, (int)voff, (int)soff, DEMO_LOAD_AUX));
 }
+// The data registers of a buffer store have to survive the instructions right behind it.  The compiler knows of
+// no hazard there when the store has a scalar offset, yet on this part a VALU write to the first data register in
+// the slot after the store has been seen to reach memory in its place (lanes 12-15 of every row of 16, now and
+// then, in the first launches of a process).  The empty-operand asm keeps the registers live past two wait states.
 __device__ __forceinline__ void bstore_f4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, f32x4 v) {
-  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)voff, (int)soff, DEMO_STORE_AUX);
+  const u32x4 u = __builtin_bit_cast(u32x4, v);
+  __builtin_amdgcn_raw_buffer_store_b128(u, r, (int)voff, (int)soff, DEMO_STORE_AUX);
+#ifndef DEMO_NO_STORE_GUARD
+  asm volatile("s_nop 1" ::"v"(u));
+#endif
 }
 __device__ __forceinline__ void bstore_u2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, u32x2 v) {
   __builtin_amdgcn_raw_buffer_store_b64(v, r, (int)voff, (int)soff, DEMO_STORE_AUX);
+#ifndef DEMO_NO_STORE_GUARD
+  asm volatile("s_nop 1" ::"v"(v));
+#endif
 }
 
 __device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) {

@@ -336,8 +336,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       // every coefficient is zero: the k lowest flat indices with zero values; D (all zero) is stored below
       if (lane < k) {
         const int64_t po = (int64_t)cc * k + lane;
-        as_global(cur.idx)[po] = lane;
-        as_global(cur.val)[po] = 0.f;
+        store_guarded(as_global(cur.idx) + po, (int32_t)lane);
+        store_guarded(as_global(cur.val) + po, 0.f);
       }
       ncand = 0;
     }
@@ -376,8 +376,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       const bool selected = lane < ncand && rank < k;
       if (selected) {
         const int64_t po = (int64_t)cc * k + rank;
-        as_global(cur.idx)[po] = (int32_t)me.y;
-        as_global(cur.val)[po] = __uint_as_float(me.x);
+        store_guarded(as_global(cur.idx) + po, (int32_t)me.y);
+        store_guarded(as_global(cur.val) + po, __uint_as_float(me.x));
       }
       file_selected(selected, me.y, me.x);
     } else {
@@ -398,8 +398,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
         const bool selected = valid && rank < k;
         if (selected) {
           const int64_t po = (int64_t)cc * k + rank;
-          as_global(cur.idx)[po] = (int32_t)me.y;
-          as_global(cur.val)[po] = __uint_as_float(me.x);
+          store_guarded(as_global(cur.idx) + po, (int32_t)me.y);
+          store_guarded(as_global(cur.val) + po, __uint_as_float(me.x));
         }
         file_selected(selected, me.y, me.x);
       }

@@ -263,8 +263,8 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
       if (all_zero) {
         if (lane < k) {
           const int64_t po = (int64_t)c32 * k + lane;
-          as_global(cur.idx)[po] = lane;
-          as_global(cur.val)[po] = 0.f;
+          store_guarded(as_global(cur.idx) + po, (int32_t)lane);
+          store_guarded(as_global(cur.val) + po, 0.f);
         }
       } else if (!overflow) {
         // rank the candidates (magnitude descending, flat index ascending); ranks < k are the payload
@@ -294,8 +294,8 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
           const bool selected = i < ncand && rank < k;
           if (selected) {
             const int64_t po = (int64_t)c32 * k + rank;
-            as_global(cur.idx)[po] = (int32_t)me.y;
-            as_global(cur.val)[po] = __uint_as_float(me.x);
+            store_guarded(as_global(cur.idx) + po, (int32_t)me.y);
+            store_guarded(as_global(cur.val) + po, __uint_as_float(me.x));
           }
           // filed for the reconstruction by class: {local row frequency u, column frequency 32 bv + v of the tile}
           const uint32_t u = me.y >> 5, v = me.y & 31u;

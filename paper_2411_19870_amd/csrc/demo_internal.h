@@ -60,9 +60,9 @@ struct DecodeArgs {
   int agg;            // demo_aggregate
   int mirror;         // as in EncodeArgs
 };
-// The wavefront-per-chunk decode kernels implement sign descent on the plain sum (which the mean
-// is sign-equivalent to); the other operating points run on the generic kernels.
-inline bool decode_is_sign_of_sum(const DecodeArgs& a) { return a.phi == 0 && a.agg != 2; }
+// The fast decode kernels aggregate by the plain sum (the mean is the sum times `scale`) and apply phi = sgn or
+// the identity in their epilogues; the count-normalised aggregate runs on the generic kernels.
+inline bool decode_is_sign_of_sum(const DecodeArgs& a) { return a.agg != 2; }
 
 // Device tables of one chunk size.
 struct BasisTables {

@@ -465,8 +465,8 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
           const float fv = cand_val[i];
           const int fi = (int)~me.x;
           const int64_t po = (int64_t)c * k + rk;
-          d.idx[po] = fi;
-          d.val[po] = fv;
+          store_guarded(d.idx + po, (int32_t)fi);
+          store_guarded(d.val + po, fv);
           sel_idx[rk] = fi;
           sel_val[rk] = fv;
         }
@@ -557,8 +557,8 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
         }
         my_rank = rk;
         const int64_t po = (int64_t)c * k + rk;
-        d.idx[po] = my_idx;
-        d.val[po] = my_val;
+        store_guarded(d.idx + po, (int32_t)my_idx);
+        store_guarded(d.val + po, my_val);
       }
       __syncthreads();
       // sorted list for the reconstruction (deterministic summation order); padded to a multiple of 4
@@ -606,7 +606,7 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
       o.y = __fmaf_rn(-args.alpha, r.y, mid[p].y);
       o.z = __fmaf_rn(-args.alpha, r.z, mid[p].z);
       o.w = __fmaf_rn(-args.alpha, r.w, mid[p].w);
-      *reinterpret_cast<float4*>(d.mom + off) = o;
+      store_guarded(reinterpret_cast<f32x4*>(d.mom + off), (f32x4){o.x, o.y, o.z, o.w});
     }
     DEMO_PHASE(5);
   }
@@ -875,8 +875,8 @@ __global__ __launch_bounds__(64) void encode1d_wave(TableView tv, const float* _
         rk += (mj > mg || (mj == mg && j < u)) ? 1 : 0;
       }
       if (rk < k) {
-        d.idx[(int64_t)c * k + rk] = u;
-        d.val[(int64_t)c * k + rk] = q[e];
+        store_guarded(d.idx + ((int64_t)c * k + rk), (int32_t)u);
+        store_guarded(d.val + ((int64_t)c * k + rk), q[e]);
         s_sel_idx[rk] = u;
         s_sel_val[rk] = q[e];
       }
@@ -889,7 +889,7 @@ __global__ __launch_bounds__(64) void encode1d_wave(TableView tv, const float* _
     if (n < S) {
       float r = 0.f;
       for (int j = 0; j < k; ++j) r = __fmaf_rn(s_sel_val[j], basis[s_sel_idx[j] * S + n], r);   // P^T q^
-      d.mom[base + n] = __fmaf_rn(-args.alpha, r, b[e]);
+      store_guarded(d.mom + (base + n), __fmaf_rn(-args.alpha, r, b[e]));
     }
   }
 }
@@ -965,7 +965,7 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
         *xp = (uint16_t)f32_to_bf16_rne(sign_update(bf16_to_f32(*xp), sg, args.lr, args.weight_decay));
       } else {
         float* xp = static_cast<float*>(d.param) + base + n;
-        *xp = sign_update(*xp, sg, args.lr, args.weight_decay);
+        store_guarded(xp, sign_update(*xp, sg, args.lr, args.weight_decay));
       }
     }
   }

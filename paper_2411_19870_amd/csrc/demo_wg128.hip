@@ -337,8 +337,8 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     if (skip && tid == 0) wl.list[atomicAdd(wl.count, 1)] = chunk;
     if (all_zero && tid < k) {
       // every coefficient is zero: the k lowest flat indices with zero values; m = D is stored below
-      out_idx[tid] = tid;
-      out_val[tid] = 0.f;
+      store_guarded(out_idx + tid, (int32_t)tid);
+      store_guarded(out_val + tid, 0.f);
     }
     // (3) rank the candidates (magnitude descending, flat index ascending).  Wavefront w counts, for every
     //     candidate, the entries of its slice of the list that precede it, and those among them of the same class
@@ -371,8 +371,8 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
       const uint32_t r2 = rk[tidv];
       const int rank = (int)(r2 & 0xffffu), rcls = (int)(r2 >> 16);
       if (rank < k) {
-        out_idx[rank] = (int32_t)me.y;
-        out_val[rank] = __uint_as_float(me.x);
+        store_guarded(out_idx + rank, (int32_t)me.y);
+        store_guarded(out_val + rank, __uint_as_float(me.x));
         const int cls = (int)(((me.y >> 6) & 2u) | (me.y & 1u));
         // byte offsets of rows pos3(u) and pos3(v) of the basis tile, and the value
         const uint32_t offs = (uint32_t)(pos3(me.y >> 7) * (W128_LDP * 4)) | ((uint32_t)(pos3(me.y & 127u) * (W128_LDP * 4)) << 16);
@@ -509,7 +509,8 @@ static_assert(kFast128MaxPairs == W128_DEC_SLOTS * W128_THREADS, "pairs per chun
 // slower).  STREAM true: more than 4096 pairs per chunk (up to 65536), k a multiple of four and 16-byte aligned payload
 // arrays: rounds of 4096 pairs, a thread fetching four consecutive pairs of one worker per load, once for the largest
 // magnitude (values only) and once for the sums.
-template <bool PBF16, bool STREAM>
+// IDENT: phi is the identity on the aggregate instead of sgn (its own instance).
+template <bool PBF16, bool STREAM, bool IDENT>
 __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, const float* __restrict__ basis,
                                                                 DecodeArgs args) {
   constexpr bool VEC4 = STREAM;
@@ -627,6 +628,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     wg_lds_barrier();
 
     // ---- S[idx] += val in fixed point ------------------------------------------------------------------------
+    int sh_chunk;   // shift of this chunk's fixed point (undone when phi is the identity)
     {
       uint32_t mall = wmax[lane & 15];
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0xB1, 0xf, 0xf, false));
@@ -636,6 +638,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       int ex = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)mall) >> 23);   // biased exponent of the largest magnitude
       ex = ex < 1 ? 1 : ex;
       const int sh = vbits + 126 - ex;                         // max |val| * 2^sh < 2^vbits
+      sh_chunk = sh;
       for (int r = 0; r < nrounds; ++r) {
         if (STREAM) load_payload(d, cc, r, true);
 #pragma unroll
@@ -761,7 +764,9 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     }
     wg_lds_barrier();
 
-    // ---- x <- x - lr (sgn(R) + wd x) ------------------------------------------------------------------------------
+    // ---- x <- x - lr (phi(R) + wd x): phi = sgn, or the identity on the aggregate (the tile holds R * 2^sh; `scale`
+    //      is 1 or 1/W) -----------------------------------------------------------------------------------------------
+    const float factor = IDENT ? ldexpf(args.scale, -sh_chunk) : 0.f;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const f32x4 rv = *reinterpret_cast<const f32x4*>(&tile[(lrow + 32 * p) * W128_LDX + lcol]);
@@ -775,7 +780,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
         } else {
           x = xin[p][e];
         }
-        o[e] = sign_update(x, sgnf(rv[e]), args.lr, args.weight_decay);
+        o[e] = sign_update(x, IDENT ? rv[e] * factor : sgnf(rv[e]), args.lr, args.weight_decay);
       }
       if constexpr (PBF16) {
         const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
@@ -791,19 +796,25 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   }
 }
 
-template <bool PBF16, bool STREAM>
-static hipError_t launch_dec_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
-                                   hipStream_t stream) {
+template <bool PBF16, bool STREAM, bool IDENT>
+static hipError_t launch_dec_wg128_phi(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
+                                       hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16, STREAM>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16, STREAM, IDENT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, W128_DEC_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wg128<PBF16, STREAM>), dim3((unsigned)grid), dim3(W128_THREADS), W128_DEC_LDS_BYTES,
+  hipLaunchKernelGGL((decode2d_wg128<PBF16, STREAM, IDENT>), dim3((unsigned)grid), dim3(W128_THREADS), W128_DEC_LDS_BYTES,
                      stream, tv, basis, a);
   return hipGetLastError();
+}
+template <bool PBF16, bool STREAM>
+static hipError_t launch_dec_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
+                                   hipStream_t stream) {
+  return a.phi != 0 ? launch_dec_wg128_phi<PBF16, STREAM, true>(tv, basis, a, grid, stream)
+                    : launch_dec_wg128_phi<PBF16, STREAM, false>(tv, basis, a, grid, stream);
 }
 
 hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,

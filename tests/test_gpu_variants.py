@@ -200,3 +200,22 @@ def test_set_basis_rejects_dependent_rows(ctx):
     with pytest.raises(B.DemoError) as e:
         ctx.demo_set_basis(32, B.DEMO_BASIS_GRAM_SCHMIDT, a)
     assert e.value.status == B.DEMO_ERR_ARG
+
+
+@pytest.mark.parametrize("s,k,W", [(64, 32, 8), (32, 8, 4), (128, 32, 3)])
+def test_identity_phi_with_zero_step_leaves_parameters_untouched(ctx, s, k, W):
+    # lr = 0 with phi = identity: x' = x - 0 * (R + wd x) must give x back bit for bit, on freshly allocated float32
+    # tensors and in the first launches of a context.  (Regression: the data registers of a 16-byte buffer store
+    # were overwritten by the instruction right behind it; a few elements per launch then held R instead of x.)
+    for rep in range(4):
+        c = B.Context()
+        c.demo_set_variant(1)
+        case = Case(synth.tensor_set("tiny"), s, k, W=W, param_dtype=torch.float32, seed=40 + rep)
+        case.fill_payloads()
+        before = [x.clone() for x in case.x]
+        hp = B.demo_hparams_default(lr=0.0, weight_decay=0.0, phi=PHI["identity"], aggregate=AGG["sum"])
+        c.demo_decode_ex(case.args, W, hp, s, k)
+        torch.cuda.synchronize()
+        for b, a in zip(before, case.x):
+            assert torch.equal(a, b)
+        c.close()
