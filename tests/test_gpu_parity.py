@@ -427,3 +427,45 @@ def test_many_distinct_tensor_lists(ctx):
         for case in cases:
             case.new_grads(rnd)
             run_encode_check(ctx, case)
+
+
+# ---- non-finite inputs: the result for the chunks that hold them is undefined, but the call returns and every other
+#      chunk comes out as it does without them (no loop of any kernel depends on the data for its end) --------------------
+@pytest.mark.parametrize("s", [32, 64, 128])
+def test_non_finite_inputs_stay_in_their_chunks(ctx, s):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 256, 384), synth.TensorSpec("v", 4 * s, 0)]
+    k, W = 8, 4
+    clean = Case(specs, s, k, W=W, seed=77)
+    dirty = Case(specs, s, k, W=W, seed=77)
+    for c in (clean, dirty):
+        c.fill_payloads()
+    # one chunk of the matrix (its top-left one) and the first chunk of the vector get NaN / Inf / -Inf
+    dirty.g[0][0, 0] = float("nan")
+    dirty.g[0][1, 2] = float("inf")
+    dirty.m[0][2, 1] = float("-inf")
+    dirty.g[1][0] = float("nan")
+    dirty.val[0][1, 0, 0] = float("nan")
+    dirty.val[0][2, 0, 1] = float("inf")
+    dirty.val[1][0, 0, 0] = float("nan")
+    for c in (clean, dirty):
+        ctx.demo_encode(c.args, BETA, s, k)
+    torch.cuda.synchronize()
+    nch_cols = 384 // s
+
+    def other_chunks(t):            # everything but chunk (0, 0)
+        keep = torch.ones_like(t, dtype=torch.bool)
+        keep[:s, :s] = False
+        return t[keep]
+    assert torch.equal(other_chunks(dirty.m[0]), other_chunks(clean.m[0]))
+    assert torch.equal(dirty.idx[0][0, 1:], clean.idx[0][0, 1:]) and torch.equal(dirty.val[0][0, 1:], clean.val[0][0, 1:])
+    assert torch.equal(dirty.m[1][s:], clean.m[1][s:])
+    # decode with the payloads as filled (worker slot 0 was overwritten by the encode above: make it equal again)
+    dirty.idx[0][0].copy_(clean.idx[0][0]); dirty.val[0][0].copy_(clean.val[0][0])
+    dirty.idx[1][0].copy_(clean.idx[1][0]); dirty.val[1][0].copy_(clean.val[1][0])
+    for c in (clean, dirty):
+        ctx.demo_decode(c.args, W, LR, 0.0, s, k)
+    torch.cuda.synchronize()
+    assert torch.equal(other_chunks(dirty.x[0]), other_chunks(clean.x[0]))
+    assert torch.equal(dirty.x[1][s:], clean.x[1][s:])
+    assert nch_cols >= 3
