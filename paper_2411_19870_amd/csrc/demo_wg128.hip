@@ -14,7 +14,10 @@
 // when the payload is written.
 //
 // The contraction index of k-slot g at step s of group kg is 16 kg + 4 g + s, so that operands whose
-// contraction index runs along an LDS row come in one 16-byte read per four MFMAs.
+// contraction index runs along an LDS row come in one 16-byte read per four MFMAs.  The encode kernel contracts the
+// columns first (Z = X P^T, rows of X read along j) and writes Z transposed, four consecutive i per 16-byte store
+// as they lie in an accumulator, so that the second product (Q = P Z) reads Z along i as well: no operand is read
+// across rows.
 #include <type_traits>
 
 #include "demo_device.h"
@@ -109,14 +112,13 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
 #pragma unroll
   for (int p = 0; p < 4; ++p) issue_quarter(p);
 
-  // flat index 128 u + v of coefficient acc[a][r] of the second product (row tile mt = wave / 2, half h = wave % 2):
-  // row position 16 mt + 4 lq + r, i.e. u = ub + su (4 lq + r) with su = 4 (even classes) or 2 (odd rows);
-  // column position 32 h + 16 a + l16 of an even class (a < 2): v = 64 a + 4 l16 + 2 h, or 64 + 32 h + 16 (a - 2) + l16
-  // of the odd class: v = 64 h + 32 (a - 2) + 2 l16 + 1
-  const int q_mt = wave >> 1, q_h = wave & 1;
-  const int q_su = q_mt < 4 ? 4 : 2;
-  const int q_ub = q_mt < 2 ? 64 * q_mt : q_mt < 4 ? 64 * (q_mt - 2) + 2 : 32 * (q_mt - 4) + 1;
-  const uint32_t fb_rstep = (uint32_t)(128 * q_su);
+  // flat index 128 u + v of coefficient acc[a][r] of the second product (column tile vt = wave / 2, half h = wave % 2):
+  // column position 16 vt + l16, i.e. v = vb + sv l16 with sv = 4 (even classes) or 2 (odd columns); row position
+  // 32 h + 16 a + 4 lq + r of an even class (a < 2): u = 4 (16 a + 4 lq + r) + 2 h, or 64 + 32 h + 16 (a - 2) + 4 lq + r
+  // of the odd class: u = 2 (32 h + 16 (a - 2) + 4 lq + r) + 1
+  const int q_vt = wave >> 1, q_h = wave & 1;
+  const int q_sv = q_vt < 4 ? 4 : 2;
+  const int q_vb = q_vt < 2 ? 64 * q_vt : q_vt < 4 ? 64 * (q_vt - 2) + 2 : 32 * (q_vt - 4) + 1;
 
   // momentum update of the chunk whose rows are in the registers, staged into the tile
   f32x4 D[4];
@@ -168,80 +170,26 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     wg_lds_barrier();
     DEMO_PHASE(0);
 
-    // ---- product 1: T[u][j] = sum_i P[u][i] X[i][j] on the folded rows of X; the wavefront owns column tile
-    //      nt = wave % 8, two row tiles of the even class h = wave / 8 (u = 0 / 2 mod 4) and the odd row tiles
-    //      2 h, 2 h + 1 -----------------------------------------------------------------------------------------
+    // ---- product 1: Z[i][v] = sum_j X[i][j] P[v][j] on the folded columns of X; the wavefront owns row tile
+    //      it = wave / 2, two column tiles of the even class h = wave % 2 (v = 0 / 2 mod 4) and the odd column
+    //      tiles 2 h, 2 h + 1 -------------------------------------------------------------------------------------
     f32x4 acc[4];
     {
-      const int nt = wave & 7, h = wave >> 3;
+      const int it = wave >> 1, h = wave & 1;
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
       const float* pc = sP + (32 * h + l16) * W128_LDP + 4 * lq;
       const float* po = sP + (64 + 32 * h + l16) * W128_LDP + 4 * lq;
-      const float* xb = sX + 16 * nt + l16;
-#pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {
-        float bo[4], bc[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const int i = 16 * kg + 4 * lq + s;
-          const float x0 = xb[i * W128_LDX], x1 = xb[(127 - i) * W128_LDX];
-          bo[s] = x0 - x1;
-          if (kg < 2) {
-            const float e0 = x0 + x1, e1 = xb[(63 - i) * W128_LDX] + xb[(64 + i) * W128_LDX];
-            bc[s] = h ? e0 - e1 : e0 + e1;
-          }
-        }
-        if (kg < 2) {
-#pragma unroll
-          for (int t2 = 0; t2 < 2; ++t2) {
-            const f32x4 a = *reinterpret_cast<const f32x4*>(pc + 16 * t2 * W128_LDP + 16 * kg);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) acc[t2] = mfma4(a[s], bc[s], acc[t2]);
-          }
-        }
-#pragma unroll
-        for (int t2 = 0; t2 < 2; ++t2) {
-          const f32x4 a = *reinterpret_cast<const f32x4*>(po + 16 * t2 * W128_LDP + 16 * kg);
-#pragma unroll
-          for (int s = 0; s < 4; ++s) acc[2 + t2] = mfma4(a[s], bo[s], acc[2 + t2]);
-        }
-        // a quarter of the next chunk's rows per step: the requests of the sixteen wavefronts trickle into the
-        // memory pipeline instead of queueing at the barrier
-        if (has_next) issue_quarter(kg);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      wg_lds_barrier();   // every read of X is done: T replaces it, rows in class-major order
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          sX[(32 * h + 16 * t2 + 4 * lq + r) * W128_LDX + 16 * nt + l16] = acc[t2][r];
-          sX[(64 + 32 * h + 16 * t2 + 4 * lq + r) * W128_LDX + 16 * nt + l16] = acc[2 + t2][r];
-        }
-    }
-    wg_lds_barrier();
-    DEMO_PHASE(1);
-
-    // ---- product 2: Q[u][v] = sum_j T[u][j] P[v][j] on the folded columns of T; the wavefront owns row tile
-    //      mt = wave / 2 (positions 16 mt ..), two column tiles of the even class h = wave % 2 and the odd column
-    //      tiles 2 h, 2 h + 1 --------------------------------------------------------------------------------------
-    {
-      const int mt = wave >> 1, h = wave & 1;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const float* pc = sP + (32 * h + l16) * W128_LDP + 4 * lq;
-      const float* po = sP + (64 + 32 * h + l16) * W128_LDP + 4 * lq;
-      const float* tr = sX + (16 * mt + l16) * W128_LDX;
+      const float* xr = sX + (16 * it + l16) * W128_LDX;
 #pragma unroll
       for (int kg = 0; kg < 4; ++kg) {
         // columns j = 16 kg + 4 lq + s and 127 - j
-        const f32x4 t0 = *reinterpret_cast<const f32x4*>(tr + 16 * kg + 4 * lq);
-        const f32x4 t1 = *reinterpret_cast<const f32x4*>(tr + 124 - 16 * kg - 4 * lq);
+        const f32x4 t0 = *reinterpret_cast<const f32x4*>(xr + 16 * kg + 4 * lq);
+        const f32x4 t1 = *reinterpret_cast<const f32x4*>(xr + 124 - 16 * kg - 4 * lq);
         if (kg < 2) {
           // and 63 - j, 64 + j
-          const f32x4 t2 = *reinterpret_cast<const f32x4*>(tr + 60 - 16 * kg - 4 * lq);
-          const f32x4 t3 = *reinterpret_cast<const f32x4*>(tr + 64 + 16 * kg + 4 * lq);
+          const f32x4 t2 = *reinterpret_cast<const f32x4*>(xr + 60 - 16 * kg - 4 * lq);
+          const f32x4 t3 = *reinterpret_cast<const f32x4*>(xr + 64 + 16 * kg + 4 * lq);
           float ac[4];
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
@@ -261,6 +209,60 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
 #pragma unroll
           for (int s = 0; s < 4; ++s) acc[2 + c2] = mfma4(t0[s] - t1[3 - s], b[s], acc[2 + c2]);
         }
+        // the next chunk's rows, a quarter per other step of the two products: the requests of the sixteen
+        // wavefronts trickle into the memory pipeline instead of queueing at a barrier
+        if (has_next && (kg & 1) == 0) issue_quarter(kg >> 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      wg_lds_barrier();   // every read of X is done: Z^T replaces it, row = column position of v, four i per store
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2) {
+        *reinterpret_cast<f32x4*>(&sX[(32 * h + 16 * c2 + l16) * W128_LDX + 16 * it + 4 * lq]) = acc[c2];
+        *reinterpret_cast<f32x4*>(&sX[(64 + 32 * h + 16 * c2 + l16) * W128_LDX + 16 * it + 4 * lq]) = acc[2 + c2];
+      }
+    }
+    wg_lds_barrier();
+    DEMO_PHASE(1);
+
+    // ---- product 2: Q[u][v] = sum_i P[u][i] Z[i][v] on the folded rows of Z (read along i from Z^T); the wavefront
+    //      owns column tile vt = wave / 2 (positions 16 vt ..), two row tiles of the even class h = wave % 2 and the odd
+    //      row tiles 2 h, 2 h + 1 -------------------------------------------------------------------------------------
+    {
+      const int vt = wave >> 1, h = wave & 1;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const float* pc = sP + (32 * h + l16) * W128_LDP + 4 * lq;
+      const float* po = sP + (64 + 32 * h + l16) * W128_LDP + 4 * lq;
+      const float* zr = sX + (16 * vt + l16) * W128_LDX;
+#pragma unroll
+      for (int kg = 0; kg < 4; ++kg) {
+        // rows i = 16 kg + 4 lq + s and 127 - i
+        const f32x4 t0 = *reinterpret_cast<const f32x4*>(zr + 16 * kg + 4 * lq);
+        const f32x4 t1 = *reinterpret_cast<const f32x4*>(zr + 124 - 16 * kg - 4 * lq);
+        if (kg < 2) {
+          // and 63 - i, 64 + i
+          const f32x4 t2 = *reinterpret_cast<const f32x4*>(zr + 60 - 16 * kg - 4 * lq);
+          const f32x4 t3 = *reinterpret_cast<const f32x4*>(zr + 64 + 16 * kg + 4 * lq);
+          float bc[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const float e0 = t0[s] + t1[3 - s], e1 = t2[3 - s] + t3[s];
+            bc[s] = h ? e0 - e1 : e0 + e1;
+          }
+#pragma unroll
+          for (int c2 = 0; c2 < 2; ++c2) {
+            const f32x4 a = *reinterpret_cast<const f32x4*>(pc + 16 * c2 * W128_LDP + 16 * kg);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc[c2] = mfma4(a[s], bc[s], acc[c2]);
+          }
+        }
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2) {
+          const f32x4 a = *reinterpret_cast<const f32x4*>(po + 16 * c2 * W128_LDP + 16 * kg);
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc[2 + c2] = mfma4(a[s], t0[s] - t1[3 - s], acc[2 + c2]);
+        }
+        if (has_next && (kg & 1) == 0) issue_quarter(2 + (kg >> 1));
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -301,8 +303,9 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     {
       // lane parts of the flat indices, formed per chunk from the opaque lane id (kept across the chunk, these
       // and the 16 per-register indices derived from them would be spilled)
-      const uint32_t fu = (uint32_t)(128 * (q_ub + 4 * q_su * (lanev >> 4)));
-      const uint32_t fc = (uint32_t)(4 * (lanev & 15) + 2 * q_h), fo = (uint32_t)(64 * q_h + 2 * (lanev & 15) + 1);
+      const uint32_t fv = (uint32_t)(q_vb + q_sv * (lanev & 15));
+      const uint32_t fc = (uint32_t)(2048 * (lanev >> 4) + 256 * q_h) + fv;
+      const uint32_t fo = (uint32_t)(8192 * q_h + 1024 * (lanev >> 4) + 128) + fv;
       int cnt = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
             const uint64_t mask = __ballot(is);
             if (mask != 0) {
               const int pos = base + lanes_below(mask);
-              if (is && pos < W128_CAP) cand[pos] = make_uint2(__float_as_uint(acc[i][r]), fu + (uint32_t)r * fb_rstep + (i < 2 ? fc + 64u * i : fo + 32u * (i - 2)));
+              if (is && pos < W128_CAP) cand[pos] = make_uint2(__float_as_uint(acc[i][r]), i < 2 ? fc + (uint32_t)(8192 * i + 512 * r) : fo + (uint32_t)(4096 * (i - 2) + 256 * r));
               base += __popcll(mask);
             }
           }
