@@ -894,7 +894,10 @@ __global__ __launch_bounds__(64) void encode1d_wave(TableView tv, const float* _
   }
 }
 
-template <int S>
+// VEC: k a multiple of four, 16-byte aligned payload arrays and at most 2048 pairs per chunk: the pairs are fetched
+// once, four consecutive pairs of one worker per 16-byte load (unit 64 j + lane of the W k pairs in worker-major
+// order), and kept in registers for both the maximum and the sums.
+template <int S, bool VEC>
 __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* __restrict__ basis,
                                                     DecodeArgs args) {
   constexpr int EPL = (S + 63) / 64;
@@ -920,10 +923,37 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
   const DEMO_GLOBAL float* vp = as_global(d.val) + (int64_t)c * k;
   const int npairs = W * k;
   float mx = 0.f;
+  constexpr int NPV = 32;   // VEC: payload registers per lane
+  int32_t pi[NPV];
+  float pv[NPV];
+  const int nunits = npairs >> 2, nloads = (nunits + 63) >> 6;
+  if constexpr (VEC) {
+    const float rk = 1.0f / (float)k;
+#pragma unroll
+    for (int j = 0; j < NPV / 4; ++j) {
+      if (j < nloads) {   // uniform
+        const int unit = 64 * j + lane;
+        const int p = 4 * unit;
+        const int w = (int)(((float)p + 0.5f) * rk);   // p / k, exact for p < 65536 (see the order-2 kernels)
+        const int tt = p - w * k;
+        const bool ok = unit < nunits;
+        const int64_t off = ok ? (int64_t)w * wstride + tt : 0;
+        const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
+          pv[4 * j + x] = ok ? b[x] : 0.f;
+          mx = fmaxf(mx, fabsf(pv[4 * j + x]));
+        }
+      }
+    }
+  } else {
 #pragma unroll 4
-  for (int p = lane; p < npairs; p += 64) {
-    const int w = p / k, tt = p - w * k;
-    mx = fmaxf(mx, fabsf(vp[(int64_t)w * wstride + tt]));
+    for (int p = lane; p < npairs; p += 64) {
+      const int w = p / k, tt = p - w * k;
+      mx = fmaxf(mx, fabsf(vp[(int64_t)w * wstride + tt]));
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
@@ -933,14 +963,27 @@ __global__ __launch_bounds__(64) void decode1d_wave(TableView tv, const float* _
   for (int w = 1; w < W; w <<= 1) --vbits;
   const int sh = vbits + 126 - ex;
   __syncthreads();
+  if constexpr (VEC) {
+#pragma unroll
+    for (int j = 0; j < NPV; ++j) {
+      if (j < 4 * nloads) {   // uniform
+        const int fi = pi[j];
+        if (fi >= 0 && fi < S) {
+          atomicAdd(&i_acc[fi], __float2int_rn(ldexpf(pv[j], sh)));
+          if (by_count) atomicAdd(&s_cnt1[fi], 1);
+        }
+      }
+    }
+  } else {
 #pragma unroll 4
-  for (int p = lane; p < npairs; p += 64) {
-    const int w = p / k, tt = p - w * k;
-    const int fi = ip[(int64_t)w * wstride + tt];
-    const float fv = vp[(int64_t)w * wstride + tt];
-    if (fi >= 0 && fi < S) {
-      atomicAdd(&i_acc[fi], __float2int_rn(ldexpf(fv, sh)));
-      if (by_count) atomicAdd(&s_cnt1[fi], 1);
+    for (int p = lane; p < npairs; p += 64) {
+      const int w = p / k, tt = p - w * k;
+      const int fi = ip[(int64_t)w * wstride + tt];
+      const float fv = vp[(int64_t)w * wstride + tt];
+      if (fi >= 0 && fi < S) {
+        atomicAdd(&i_acc[fi], __float2int_rn(ldexpf(fv, sh)));
+        if (by_count) atomicAdd(&s_cnt1[fi], 1);
+      }
     }
   }
   __syncthreads();
@@ -1113,10 +1156,20 @@ hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const
                            hipStream_t stream) {
   if (tv.total_chunks == 0) return hipSuccess;
   const dim3 grid((unsigned)tv.total_chunks), block(64);
+  const bool vec = (tv.dtypes & 16u) == 0 && (a.k & 3) == 0 && (int64_t)a.W * a.k <= 2048;
   switch (s) {
-    case 32: hipLaunchKernelGGL(decode1d_wave<32>, grid, block, 0, stream, tv, basis, a); break;
-    case 64: hipLaunchKernelGGL(decode1d_wave<64>, grid, block, 0, stream, tv, basis, a); break;
-    case 128: hipLaunchKernelGGL(decode1d_wave<128>, grid, block, 0, stream, tv, basis, a); break;
+    case 32:
+      if (vec) hipLaunchKernelGGL((decode1d_wave<32, true>), grid, block, 0, stream, tv, basis, a);
+      else hipLaunchKernelGGL((decode1d_wave<32, false>), grid, block, 0, stream, tv, basis, a);
+      break;
+    case 64:
+      if (vec) hipLaunchKernelGGL((decode1d_wave<64, true>), grid, block, 0, stream, tv, basis, a);
+      else hipLaunchKernelGGL((decode1d_wave<64, false>), grid, block, 0, stream, tv, basis, a);
+      break;
+    case 128:
+      if (vec) hipLaunchKernelGGL((decode1d_wave<128, true>), grid, block, 0, stream, tv, basis, a);
+      else hipLaunchKernelGGL((decode1d_wave<128, false>), grid, block, 0, stream, tv, basis, a);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
