@@ -89,7 +89,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="1b", choices=["1b", "300m", "single"])
     ap.add_argument("--variant", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
