@@ -54,8 +54,9 @@ void build_dec32_tables(const double* P32, float* out) {
 // of chunk q).  MODE 2 (STREAM): more than 512 pairs per chunk (up to 65536), streamed in rounds of 512 per chunk,
 // once for the largest magnitudes (values only) and once for the sums.  MODE 0: one pair per load.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
-// nothing for it).
-template <bool PBF16, int MODE, bool IDENT>
+// nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
+// coefficient's sum divided by the number of pairs that name it), modes 0 and 1 only.
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
 __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   constexpr bool VEC4 = MODE >= 1, STREAM = MODE == 2;
@@ -169,21 +170,43 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
       ex = ex < 1 ? 1 : ex;
       return vbits + 126 - ex;                                // max |val| * 2^sh < 2^vbits
   };
-  auto add_pairs = [&](int q, int sh) {
+  auto slot_of = [&](int q, int j) {
       const uint32_t quad = (uint32_t)(((q >> 1) << 11) | ((q & 1) << 5));
+      const uint32_t u = (uint32_t)pi[D32_SLOTS * q + j];
+      // 10-bit index [u4..u0 v4..v0] -> 12-bit [a u0 u4..u1 | b v0 v4..v1], then row stride 64 -> LDT
+      const uint32_t x = quad | (u & 0x3C0u) | ((u & 0x20u) << 5) | ((u & 1u) << 4) | ((u >> 1) & 0xFu);
+      return u < 1024u ? x + ((x >> 6) << 2) : dummy;
+  };
+  auto add_pairs = [&](int q, int sh) {
 #pragma unroll
-      for (int j = 0; j < D32_SLOTS; ++j) {
-        if (j < nslots) {
-          const uint32_t u = (uint32_t)pi[D32_SLOTS * q + j];
-          // 10-bit index [u4..u0 v4..v0] -> 12-bit [a u0 u4..u1 | b v0 v4..v1], then row stride 64 -> LDT
-          const uint32_t x = quad | (u & 0x3C0u) | ((u & 0x20u) << 5) | ((u & 1u) << 4) | ((u >> 1) & 0xFu);
-          const uint32_t a = u < 1024u ? x + ((x >> 6) << 2) : dummy;
-          atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[D32_SLOTS * q + j], sh)));
-        }
-      }
+      for (int j = 0; j < D32_SLOTS; ++j)
+        if (j < nslots) atomicAdd(&itile[slot_of(q, j)], __float2int_rn(ldexpf(pv[D32_SLOTS * q + j], sh)));
   };
   int sh[4];   // shifts of the four chunks' fixed points (undone when phi is the identity)
   auto scatter = [&]() {
+    if constexpr (COUNT) {
+      static_assert(!COUNT || !STREAM, "the count pass needs the whole payload in registers");
+      // every pair adds one to its coefficient's slot, reads the total back and is divided by it; the slots are
+      // cleared again before the sums go in.  Sum of val/n over the n pairs of a slot = (sum of val) / n.
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < D32_SLOTS; ++j)
+          if (j < nslots) atomicAdd(&itile[slot_of(q, j)], 1);
+      wave_lds_sync();
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < D32_SLOTS; ++j)
+          if (j < nslots) pv[D32_SLOTS * q + j] = pv[D32_SLOTS * q + j] / (float)itile[slot_of(q, j)];
+      wave_lds_sync();
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < D32_SLOTS; ++j)
+          if (j < nslots) itile[slot_of(q, j)] = 0;
+      wave_lds_sync();
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       sh[q] = shift_of(lane_max(q, 0.f));
@@ -357,23 +380,28 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   }
 }
 
-template <bool PBF16, int MODE, bool IDENT>
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
 static hipError_t launch_dec_tile32_phi(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
                                         hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, MODE, IDENT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, MODE, IDENT, COUNT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D32_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_tile32<PBF16, MODE, IDENT>), dim3((unsigned)grid), dim3(D32_THREADS), D32_LDS_BYTES,
-                     stream, tiles, tables, a);
+  hipLaunchKernelGGL((decode2d_tile32<PBF16, MODE, IDENT, COUNT>), dim3((unsigned)grid), dim3(D32_THREADS),
+                     D32_LDS_BYTES, stream, tiles, tables, a);
   return hipGetLastError();
 }
 template <bool PBF16, int MODE>
 static hipError_t launch_dec_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
+  if constexpr (MODE != 2) {
+    if (a.agg == 2)
+      return a.phi != 0 ? launch_dec_tile32_phi<PBF16, MODE, true, true>(tiles, tables, a, grid, stream)
+                        : launch_dec_tile32_phi<PBF16, MODE, false, true>(tiles, tables, a, grid, stream);
+  }
   return a.phi != 0 ? launch_dec_tile32_phi<PBF16, MODE, true>(tiles, tables, a, grid, stream)
                     : launch_dec_tile32_phi<PBF16, MODE, false>(tiles, tables, a, grid, stream);
 }
@@ -382,6 +410,7 @@ hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, c
                                   int num_cus, hipStream_t stream) {
   const bool aligned16 = (tiles.dtypes & 16u) == 0;
   if (!fast32_decode_supports(a.W, a.k, aligned16)) return hipErrorInvalidValue;
+  if (a.agg == 2 && (int64_t)a.W * a.k > kFast32MaxPairs) return hipErrorInvalidValue;   // counted from registers
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tiles.total_chunks + D32_WAVES - 1) / D32_WAVES;
   if (grid > max_grid) grid = max_grid;

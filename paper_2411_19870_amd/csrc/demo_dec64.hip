@@ -93,8 +93,9 @@ void build_dec64_tables(const double* P, float* out) {
 // and once for the sums; the values of the first round of the next chunk are fetched during the products.
 // Modes 1 to 5 need 16-byte aligned payload arrays.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
-// nothing for it).
-template <bool PBF16, int MODE, bool IDENT>
+// nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
+// coefficient's sum divided by the number of pairs that name it), modes 0, 3 and 4 only.
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   extern __shared__ float lds[];
@@ -242,19 +243,35 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     ex = ex < 1 ? 1 : ex;
     return vbits + 126 - ex;                              // max |val| * 2^sh < 2^vbits
   };
+  auto slot_of = [&](int j) {
+    const uint32_t u = (uint32_t)pi[j];
+    // 12-bit index [u5..u0 v5..v0] -> [u1 u0 u5..u2 | v1 v0 v5..v2], then row stride 64 -> LDT
+    const uint32_t x = ((u & 0xC3u) << 4) | ((u >> 2) & 0x3CFu);
+    return u < 4096u ? x + ((x >> 6) << 2) : dummy;
+  };
   auto add_pairs = [&](int sh) {
 #pragma unroll
-    for (int j = 0; j < NP; ++j) {
-      if (FULL || j < nact) {
-        const uint32_t u = (uint32_t)pi[j];
-        // 12-bit index [u5..u0 v5..v0] -> [u1 u0 u5..u2 | v1 v0 v5..v2], then row stride 64 -> LDT
-        const uint32_t x = ((u & 0xC3u) << 4) | ((u >> 2) & 0x3CFu);
-        const uint32_t a = u < 4096u ? x + ((x >> 6) << 2) : dummy;
-        atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
-      }
-    }
+    for (int j = 0; j < NP; ++j)
+      if (FULL || j < nact) atomicAdd(&itile[slot_of(j)], __float2int_rn(ldexpf(pv[j], sh)));
   };
   auto scatter = [&]() {
+    if constexpr (COUNT) {
+      static_assert(!COUNT || !STREAM, "the count pass needs the whole payload in registers");
+      // every pair adds one to its coefficient's slot, reads the total back and is divided by it; the slots are
+      // cleared again before the sums go in.  Sum of val/n over the n pairs of a slot = (sum of val) / n.
+#pragma unroll
+      for (int j = 0; j < NP; ++j)
+        if (j < nact) atomicAdd(&itile[slot_of(j)], 1);
+      wave_lds_sync();
+#pragma unroll
+      for (int j = 0; j < NP; ++j)
+        if (j < nact) pv[j] = pv[j] / (float)itile[slot_of(j)];
+      wave_lds_sync();
+#pragma unroll
+      for (int j = 0; j < NP; ++j)
+        if (j < nact) itile[slot_of(j)] = 0;
+      wave_lds_sync();
+    }
     const int sh = shift_of(lane_max(0.f));
     add_pairs(sh);
     return sh;
@@ -643,23 +660,28 @@ static hipError_t launch_dec_sparse64(const TableView& tv, const float* tables, 
   return hipGetLastError();
 }
 
-template <bool PBF16, int MODE, bool IDENT>
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
 static hipError_t launch_dec_wave64_phi(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
                                         hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE, IDENT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE, IDENT, COUNT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D64_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE, IDENT>), dim3((unsigned)grid), dim3(D64_THREADS), D64_LDS_BYTES,
-                     stream, tv, tables, a);
+  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE, IDENT, COUNT>), dim3((unsigned)grid), dim3(D64_THREADS),
+                     D64_LDS_BYTES, stream, tv, tables, a);
   return hipGetLastError();
 }
 template <bool PBF16, int MODE>
 static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
+  if constexpr (MODE == 0 || MODE == 3 || MODE == 4) {
+    if (a.agg == 2)
+      return a.phi != 0 ? launch_dec_wave64_phi<PBF16, MODE, true, true>(tv, tables, a, grid, stream)
+                        : launch_dec_wave64_phi<PBF16, MODE, false, true>(tv, tables, a, grid, stream);
+  }
   return a.phi != 0 ? launch_dec_wave64_phi<PBF16, MODE, true>(tv, tables, a, grid, stream)
                     : launch_dec_wave64_phi<PBF16, MODE, false>(tv, tables, a, grid, stream);
 }
@@ -667,7 +689,9 @@ static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, co
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream) {
   if (!fast64_decode_supports(a.W, a.k, payload_aligned16)) return hipErrorInvalidValue;
-  if (a.W * a.k <= 64)
+  const bool by_count = a.agg == 2;   // needs the coefficient tile and the whole payload in registers
+  if (by_count && a.W * a.k > 2048) return hipErrorInvalidValue;
+  if (a.W * a.k <= 64 && !by_count)
     return param_bf16 ? launch_dec_sparse64<true>(tv, tables, a, num_cus, stream)
                       : launch_dec_sparse64<false>(tv, tables, a, num_cus, stream);
   int64_t grid = num_cus;
@@ -675,7 +699,7 @@ hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, cons
   if (grid > max_grid) grid = max_grid;
   const int mode = !payload_aligned16 ? 0
                    : a.W * a.k > 2048 ? 5
-                   : (a.k == 32 && a.W % 8 == 0 && a.W <= 64) ? (a.W == 64 ? 1 : 2)
+                   : (a.k == 32 && a.W % 8 == 0 && a.W <= 64 && !by_count) ? (a.W == 64 ? 1 : 2)
                    : a.k % 4 == 0 ? 3 : a.k % 2 == 0 ? 4 : 0;
   if (param_bf16) {
     switch (mode) {

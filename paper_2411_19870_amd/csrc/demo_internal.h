@@ -61,8 +61,10 @@ struct DecodeArgs {
   int mirror;         // as in EncodeArgs
 };
 // The fast decode kernels aggregate by the plain sum (the mean is the sum times `scale`) and apply phi = sgn or
-// the identity in their epilogues; the count-normalised aggregate runs on the generic kernels.
+// the identity in their epilogues.  The count-normalised aggregate runs in them while a chunk's whole payload
+// fits their registers (it is counted before it is summed), else on the generic kernels.
 inline bool decode_is_sign_of_sum(const DecodeArgs& a) { return a.agg != 2; }
+constexpr int kFast64CountMaxPairs = 2048;
 
 // Device tables of one chunk size.
 struct BasisTables {

@@ -1120,14 +1120,15 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
   const uint32_t pmix = (tv.dtypes >> 2) & 3u;   // parameter dtypes present: the wavefront kernel wants one
   // the wavefront kernels address a tensor's payload with 32-bit offsets (worker * pairs-per-worker + position)
   const bool payload_fits32 = (int64_t)tv.total_chunks * a.k * a.W < (int64_t)1 << 31;
-  if (variant >= 1 && s == 32 && decode_is_sign_of_sum(a) && tiles != nullptr &&
+  if (variant >= 1 && s == 32 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast32MaxPairs) && tiles != nullptr &&
       fast32_decode_supports(a.W, a.k, (tiles->dtypes & 16u) == 0) && payload_fits32 && bt.dec32 != nullptr &&
       (pmix == 1u || pmix == 2u))
     return launch_decode2d_tile32(*tiles, bt.dec32, a, pmix == 1u, num_cus, stream);
-  if (variant >= 1 && s == 64 && decode_is_sign_of_sum(a) && fast64_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 &&
+  if (variant >= 1 && s == 64 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast64CountMaxPairs) &&
+      fast64_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 &&
       bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
-  if (variant >= 1 && s == 128 && a.mirror != 0 && decode_is_sign_of_sum(a) &&
+  if (variant >= 1 && s == 128 && a.mirror != 0 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast128MaxPairs) &&
       fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wg128(tv, bt.basis, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;

@@ -512,8 +512,10 @@ static_assert(kFast128MaxPairs == W128_DEC_SLOTS * W128_THREADS, "pairs per chun
 // slower).  STREAM true: more than 4096 pairs per chunk (up to 65536), k a multiple of four and 16-byte aligned payload
 // arrays: rounds of 4096 pairs, a thread fetching four consecutive pairs of one worker per load, once for the largest
 // magnitude (values only) and once for the sums.
-// IDENT: phi is the identity on the aggregate instead of sgn (its own instance).
-template <bool PBF16, bool STREAM, bool IDENT>
+// IDENT: phi is the identity on the aggregate instead of sgn (its own instance).  COUNT: the count-normalised
+// aggregate of the appendix algorithm Decompress&Aggregate (every coefficient's sum divided by the number of pairs
+// that name it), without STREAM only.
+template <bool PBF16, bool STREAM, bool IDENT, bool COUNT = false>
 __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, const float* __restrict__ basis,
                                                                 DecodeArgs args) {
   constexpr bool VEC4 = STREAM;
@@ -607,6 +609,26 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
                                               : make_rsrc(static_cast<const float*>(d.param) + origin);
     const uint32_t vo = (uint32_t)lrow * ucols + (uint32_t)lcol;
 
+    if constexpr (COUNT) {
+      static_assert(!COUNT || !STREAM, "the count pass needs the whole payload in registers");
+      // every pair adds one to its coefficient's slot, reads the total back and is divided by it (sum of val/n over
+      // the n pairs of a slot = (sum of val) / n); the tile is zeroed again below before the sums go in
+      auto slot_of = [&](int j) {
+        const uint32_t fi = (uint32_t)pi[j];
+        return fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
+      };
+      for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS)
+        *reinterpret_cast<f32x4*>(&tile[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
+      wg_lds_barrier();
+#pragma unroll
+      for (int j = 0; j < W128_DEC_SLOTS; ++j)
+        if (j < nslots) atomicAdd(&itile[slot_of(j)], 1);
+      wg_lds_barrier();
+#pragma unroll
+      for (int j = 0; j < W128_DEC_SLOTS; ++j)
+        if (j < nslots) pv[j] = pv[j] / (float)itile[slot_of(j)];
+      wg_lds_barrier();
+    }
     // ---- largest |val| of the chunk, zero tile --------------------------------------------------------------
     {
       float mx = 0.f;
@@ -799,23 +821,28 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   }
 }
 
-template <bool PBF16, bool STREAM, bool IDENT>
+template <bool PBF16, bool STREAM, bool IDENT, bool COUNT = false>
 static hipError_t launch_dec_wg128_phi(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
                                        hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16, STREAM, IDENT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16, STREAM, IDENT, COUNT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, W128_DEC_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wg128<PBF16, STREAM, IDENT>), dim3((unsigned)grid), dim3(W128_THREADS), W128_DEC_LDS_BYTES,
-                     stream, tv, basis, a);
+  hipLaunchKernelGGL((decode2d_wg128<PBF16, STREAM, IDENT, COUNT>), dim3((unsigned)grid), dim3(W128_THREADS),
+                     W128_DEC_LDS_BYTES, stream, tv, basis, a);
   return hipGetLastError();
 }
 template <bool PBF16, bool STREAM>
 static hipError_t launch_dec_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
                                    hipStream_t stream) {
+  if constexpr (!STREAM) {
+    if (a.agg == 2)
+      return a.phi != 0 ? launch_dec_wg128_phi<PBF16, STREAM, true, true>(tv, basis, a, grid, stream)
+                        : launch_dec_wg128_phi<PBF16, STREAM, false, true>(tv, basis, a, grid, stream);
+  }
   return a.phi != 0 ? launch_dec_wg128_phi<PBF16, STREAM, true>(tv, basis, a, grid, stream)
                     : launch_dec_wg128_phi<PBF16, STREAM, false>(tv, basis, a, grid, stream);
 }
@@ -823,6 +850,7 @@ static hipError_t launch_dec_wg128(const TableView& tv, const float* basis, cons
 hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
                                  int num_cus, hipStream_t stream) {
   if (!fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0)) return hipErrorInvalidValue;
+  if (a.agg == 2 && (int64_t)a.W * a.k > kFast128MaxPairs) return hipErrorInvalidValue;   // counted from registers
   int64_t grid = num_cus;
   if (grid > tv.total_chunks) grid = tv.total_chunks;
   if ((int64_t)a.W * a.k > kFast128MaxPairs)

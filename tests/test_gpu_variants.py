@@ -81,6 +81,36 @@ def test_count_aggregate_with_repeated_senders(ctx):
                        phi="identity", aggregate_mode="count")
 
 
+@pytest.mark.parametrize("s,k,W", [(64, 32, 64), (64, 6, 20), (64, 7, 9), (64, 8, 4), (64, 32, 255), (64, 64, 32),
+                                   (32, 32, 16), (32, 5, 30), (32, 8, 3), (32, 32, 17),
+                                   (128, 32, 128), (128, 7, 40), (128, 1, 255), (128, 32, 129)])
+@pytest.mark.parametrize("phi", ["sign", "identity"])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+def test_count_aggregate_with_many_collisions(ctx, s, k, W, phi, pdt):
+    # every worker draws its k distinct indices from the same 2k positions of the chunk: each of them is named by
+    # about W/2 workers.  Covers every payload access mode of the fast kernels and the sizes they hand on.
+    ctx.demo_set_variant(1)
+    case = Case(synth.tensor_set("tiny"), s, k, W=W, param_dtype=pdt, seed=36)
+    case.fill_payloads()
+    gen = torch.Generator(device="cpu").manual_seed(36)
+    for ti, sp in enumerate(case.specs):
+        M = s if sp.cols == 0 else s * s
+        R = min(2 * k, M)
+        stride = M // R
+        nch = sp.nchunks(s)
+        pick = torch.rand(W, nch, R, generator=gen).argsort(dim=-1)[..., :k] * stride
+        case.idx[ti][:W].copy_(pick.to(torch.int32))
+    hp = B.demo_hparams_default(lr=LR, weight_decay=0.05, phi=PHI[phi], aggregate=B.DEMO_AGG_COUNT)
+    before = case.snapshot()
+    ctx.demo_decode_ex(case.args, W, hp, s, k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    pd = "bf16" if pdt == torch.bfloat16 else "f32"
+    for ti in range(len(case.specs)):
+        C.check_decode(before["x"][ti], before["idx"][ti][:W], before["val"][ti][:W], LR, 0.05, s, pd, after["x"][ti],
+                       phi=phi, aggregate_mode="count")
+
+
 @pytest.mark.parametrize("variant", [0, 1])
 def test_default_hparams_match_plain_calls_bit_for_bit(ctx, variant):
     ctx.demo_set_variant(variant)
