@@ -330,7 +330,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     const bool skip = overflow && !all_zero;
     if (skip) {
       // leave the chunk untouched and queue it for the exact workgroup kernel that runs next
-      if (lane == 0) wl.list[atomicAdd(wl.count, 1)] = chunk;
+      if (lane == 0) store_guarded(&wl.list[atomicAdd(wl.count, 1)], chunk);
     }
     if (all_zero) {
       // every coefficient is zero: the k lowest flat indices with zero values; D (all zero) is stored below

@@ -315,7 +315,7 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
       // leave the tile untouched (its payload entries are overwritten too) and queue its four chunks
       if (lane < 4) {
         const int c32 = (2 * cur.K0 + (lane >> 1)) * cur.cch32 + 2 * cur.K1 + (lane & 1);
-        wl.list[atomicAdd(wl.count, 1)] = prefix32[cur.tix] + c32;   // chunk number in the 32-grid table
+        store_guarded(&wl.list[atomicAdd(wl.count, 1)], prefix32[cur.tix] + c32);   // chunk number in the 32-grid table
       }
     }
     if (GBF16) fetch_g(nxt);   // the coefficient registers are dead now (fp32 gradients: after the reconstruction)

@@ -616,8 +616,8 @@ __global__ __launch_bounds__(256) void encode2d_generic(TableView tv, const floa
     if (tid == 0) {
       __threadfence();
       if (atomicAdd(wl.ticket, 1) == (int)gridDim.x - 1) {
-        *wl.count = 0;
-        *wl.ticket = 0;
+        store_guarded(wl.count, 0);
+        store_guarded(wl.ticket, 0);
       }
     }
   }

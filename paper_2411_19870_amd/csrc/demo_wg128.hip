@@ -337,7 +337,7 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
     const bool overflow = ncand > W128_CAP;
     const bool all_zero = overflow && __builtin_amdgcn_readfirstlane(ctl[2]) != 0;
     const bool skip = overflow && !all_zero;
-    if (skip && tid == 0) wl.list[atomicAdd(wl.count, 1)] = chunk;
+    if (skip && tid == 0) store_guarded(&wl.list[atomicAdd(wl.count, 1)], chunk);
     if (all_zero && tid < k) {
       // every coefficient is zero: the k lowest flat indices with zero values; m = D is stored below
       store_guarded(out_idx + tid, (int32_t)tid);
