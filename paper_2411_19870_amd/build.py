@@ -12,18 +12,35 @@ SOURCES = [os.path.join(PKG, "csrc", f) for f in ("demo_kernels.hip", "demo_enc6
 
 
 def build(verbose: bool = True, out: str = LIB, defines=()) -> str:
+    """Compile every source to an object (in parallel, one hipcc per file) and link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [
-        hipcc, "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
+    objdir = os.path.join(PKG, "_build", os.path.splitext(os.path.basename(out))[0])
+    os.makedirs(objdir, exist_ok=True)
+    flags = [
+        "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
         # packed-fp32 VALU forms are kept out of the generated code on this target
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
-        "-o", out,
-    ] + [f"-D{d}" for d in defines] + SOURCES
+    ] + [f"-D{d}" for d in defines]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, os.path.basename(src) + ".o")
+        cmd = [hipcc, "-c"] + flags + ["-o", obj, src]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    jobs = max(1, min(len(SOURCES), os.cpu_count() or 1, 8))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    link = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out] + objs
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return out
 
 
