@@ -52,7 +52,8 @@ typedef enum demo_status {
   DEMO_OK = 0,
   DEMO_ERR_ARG = -1,         /* null pointer, n < 0, W < 1, k < 1, k > M (M = s or s*s)   */
   DEMO_ERR_SHAPE = -2,       /* rows or cols not a positive multiple of s                 */
-  DEMO_ERR_UNSUPPORTED = -3, /* s not in {32,64,128}, unknown dtype, k > DEMO_MAX_K       */
+  DEMO_ERR_UNSUPPORTED = -3, /* s not in {32,64,128}, unknown dtype, k > DEMO_MAX_K,
+                                more than 2^31 - 1 chunks in a tensor or in a call        */
   DEMO_ERR_HIP = -4,         /* a HIP runtime call failed (see demo_last_hip_error)       */
   DEMO_ERR_NOMEM = -5        /* host or device allocation for the context's tables failed */
 } demo_status;

@@ -11,8 +11,9 @@ LIB = os.path.join(PKG, "libdemo.so")
 SOURCES = [os.path.join(PKG, "csrc", f) for f in ("demo_kernels.hip", "demo_enc64.hip", "demo_enc64d.hip", "demo_dec64.hip", "demo_dec32.hip", "demo_wg128.hip", "demo_api.cpp")]
 
 
-def build(verbose: bool = True, out: str = LIB, defines=()) -> str:
-    """Compile every source to an object (in parallel, one hipcc per file) and link the shared library."""
+def build(verbose: bool = True, out: str = LIB, defines=(), extra_flags=()) -> str:
+    """Compile every source to an object (in parallel, one hipcc per file) and link the shared library.
+    `extra_flags` go to every compile and to the link (e.g. host-side sanitizers)."""
     from concurrent.futures import ThreadPoolExecutor
 
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -24,7 +25,7 @@ def build(verbose: bool = True, out: str = LIB, defines=()) -> str:
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
-    ] + [f"-D{d}" for d in defines]
+    ] + [f"-D{d}" for d in defines] + list(extra_flags)
 
     def compile_one(src: str) -> str:
         obj = os.path.join(objdir, os.path.basename(src) + ".o")
@@ -37,7 +38,7 @@ def build(verbose: bool = True, out: str = LIB, defines=()) -> str:
     jobs = max(1, min(len(SOURCES), os.cpu_count() or 1, 8))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(compile_one, SOURCES))
-    link = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out] + objs
+    link = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950"] + list(extra_flags) + ["-o", out] + objs
     if verbose:
         print(" ".join(link), flush=True)
     subprocess.run(link, check=True)

@@ -78,6 +78,9 @@ int check_shape(int64_t rows, int64_t cols, int s, int k) {
   const int64_t M = cols == 0 ? (int64_t)s : (int64_t)s * s;
   if (k > M) return DEMO_ERR_ARG;
   if (k > DEMO_MAX_K) return DEMO_ERR_UNSUPPORTED;
+  // chunks are numbered with 32 bits (and the products below must not overflow)
+  const int64_t r = rows / s, c = cols / s;
+  if (r > INT32_MAX || (c > 0 && r > INT32_MAX / c)) return DEMO_ERR_UNSUPPORTED;
   return DEMO_OK;
 }
 

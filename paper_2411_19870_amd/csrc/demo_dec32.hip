@@ -412,7 +412,7 @@ hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, c
   if (!fast32_decode_supports(a.W, a.k, aligned16)) return hipErrorInvalidValue;
   if (a.agg == 2 && (int64_t)a.W * a.k > kFast32MaxPairs) return hipErrorInvalidValue;   // counted from registers
   int64_t grid = num_cus;
-  const int64_t max_grid = ((int64_t)tiles.total_chunks + D32_WAVES - 1) / D32_WAVES;
+  const int64_t max_grid = ((int64_t)tiles.total_chunks + DEMO_RUN - 1) / DEMO_RUN;   // few items: one run per workgroup, spread over the CUs
   if (grid > max_grid) grid = max_grid;
   const int mode = (int64_t)a.W * a.k > kFast32MaxPairs ? 2 : ((a.k & 3) == 0 && aligned16) ? 1 : 0;
   if (param_bf16) {

@@ -695,7 +695,7 @@ hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, cons
     return param_bf16 ? launch_dec_sparse64<true>(tv, tables, a, num_cus, stream)
                       : launch_dec_sparse64<false>(tv, tables, a, num_cus, stream);
   int64_t grid = num_cus;
-  const int64_t max_grid = ((int64_t)tv.total_chunks + D64_WAVES - 1) / D64_WAVES;
+  const int64_t max_grid = ((int64_t)tv.total_chunks + DEMO_RUN - 1) / DEMO_RUN;   // few items: one run per workgroup, spread over the CUs
   if (grid > max_grid) grid = max_grid;
   const int mode = !payload_aligned16 ? 0
                    : a.W * a.k > 2048 ? 5

@@ -531,7 +531,7 @@ static hipError_t launch_enc_wave64(const TableView& tv, const float* tables, co
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                   bool grad_bf16, int num_cus, hipStream_t stream) {
   int64_t grid = num_cus;
-  const int64_t max_grid = ((int64_t)tv.total_chunks + E64_WAVES - 1) / E64_WAVES;
+  const int64_t max_grid = ((int64_t)tv.total_chunks + DEMO_RUN - 1) / DEMO_RUN;   // few items: one run per workgroup, spread over the CUs
   if (grid > max_grid) grid = max_grid;
   return grad_bf16 ? launch_enc_wave64<true>(tv, tables, a, wl, grid, stream)
                    : launch_enc_wave64<false>(tv, tables, a, wl, grid, stream);

@@ -388,7 +388,7 @@ hipError_t launch_encode2d_tile32(const TableView& tiles, const int32_t* prefix3
                                   const EncodeArgs& a, const Worklist& wl, bool grad_bf16, int num_cus,
                                   hipStream_t stream) {
   int64_t grid = num_cus;
-  const int64_t max_grid = ((int64_t)tiles.total_chunks + ED_WAVES - 1) / ED_WAVES;
+  const int64_t max_grid = ((int64_t)tiles.total_chunks + DEMO_RUN - 1) / DEMO_RUN;   // few items: one run per workgroup, spread over the CUs
   if (grid > max_grid) grid = max_grid;
   return grad_bf16 ? launch_tile32<true>(tiles, prefix32, tables, a, wl, grid, stream)
                    : launch_tile32<false>(tiles, prefix32, tables, a, wl, grid, stream);

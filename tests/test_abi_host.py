@@ -47,6 +47,8 @@ def test_payload_elems_and_shape_errors():
         ((1024, 0, 64, 65), B.DEMO_ERR_ARG),           # k > M = s
         ((1024, 1024, 32, 1025), B.DEMO_ERR_ARG),      # k > M = s*s
         ((1024, 1024, 64, 257), B.DEMO_ERR_UNSUPPORTED),
+        ((1 << 40, 1 << 40, 64, 1), B.DEMO_ERR_UNSUPPORTED),    # more chunks than 32 bits number
+        ((1 << 40, 0, 32, 1), B.DEMO_ERR_UNSUPPORTED),
     ]:
         with pytest.raises(B.DemoError) as e:
             B.demo_payload_elems(*args)
@@ -167,3 +169,25 @@ def test_worker_and_position_of_a_pair_from_a_float_product():
         rk = np.float32(1.0) / np.float32(k)
         w = ((p.astype(np.float32) + np.float32(0.5)) * rk).astype(np.int32)
         assert np.array_equal(w, p // k), k
+
+
+def test_host_code_under_sanitizers(tmp_path):
+    """The library's host code (validation of every entry point, Gram-Schmidt, fragment-table
+    builders) built with AddressSanitizer + UndefinedBehaviorSanitizer on the host side only and
+    driven by tests/host_check/host_check.cpp; no GPU call is reached."""
+    import subprocess
+    from paper_2411_19870_amd import build
+
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    build.build(verbose=False, out=str(tmp_path / "libdemo_san.so"), extra_flags=san)
+    exe = str(tmp_path / "host_check")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O1", "-g", "-std=c++17"] + san + [
+        "-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2411_19870_amd", "csrc"),
+        os.path.join(ROOT, "tests", "host_check", "host_check.cpp"), "-L", str(tmp_path), "-ldemo_san",
+        f"-Wl,-rpath,{tmp_path}", "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0 and "host_check OK" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
