@@ -51,8 +51,8 @@ void build_dec32_tables(const double* P32, float* out) {
 // tiles); payload arrays are addressed per 32 x 32 chunk (4 * nchunks chunks per tensor).
 // MODE 1, 2 (VEC4): k is a multiple of four and every payload pointer is 16-byte aligned; a lane then fetches four
 // consecutive pairs of one worker with one 16-byte load per array (slot 8 q + 4 jj + e holds pair 4 (64 jj + lane) + e
-// of chunk q).  MODE 2 (STREAM): more than 512 pairs per chunk (up to 65536), streamed in rounds of 512 per chunk,
-// once for the largest magnitudes (values only) and once for the sums.  MODE 0: one pair per load.
+// of chunk q).  MODE 2 (STREAM): more than 512 pairs per chunk (up to 65536), streamed once in rounds of 512 per
+// chunk, a chunk's sums being shifted down whenever a round raises its block exponent.  MODE 0: one pair per load.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
 // nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
 // coefficient's sum divided by the number of pairs that name it), modes 0 and 1 only.
@@ -92,8 +92,8 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
     pv[j] = 0.f;
   }
   const float rk = 1.0f / (float)k;
-  // `round` and `with_idx` matter in STREAM mode only: units 128 round + 64 jj + lane, values alone or both arrays
-  auto load_payload = [&](const TensorDev& dd, int tt, int round = 0, bool with_idx = true) {
+  // `round` matters in STREAM mode only: units 128 round + 64 jj + lane
+  auto load_payload = [&](const TensorDev& dd, int tt, int round = 0) {
     const int K0 = tt / dd.cchunks, K1 = tt - K0 * dd.cchunks;
     const int cch32 = 2 * dd.cchunks;
     const int64_t wstride = (int64_t)dd.nchunks * 4 * k;      // pairs of one worker for this tensor
@@ -119,11 +119,9 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
             const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
             for (int e = 0; e < 4; ++e) pv[D32_SLOTS * q + 4 * jj + e] = ok ? vv[e] : 0.f;
-            if (!STREAM || with_idx) {   // uniform
-              const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+            const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-              for (int e = 0; e < 4; ++e) pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
-            }
+            for (int e = 0; e < 4; ++e) pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
           }
         }
         continue;
@@ -217,7 +215,7 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   int t = find_tensor_uniform(tv, tileno);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
-  load_payload(d, tileno - t_first, 0, false);
+  load_payload(d, tileno - t_first, 0);
   const int kap = kappa32(c), col4 = 4 * chi(c);
   // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
   // for members w' even / odd (w' >= 2 adds 32 columns)
@@ -248,21 +246,40 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
     if constexpr (STREAM) {
-      // the registers hold the values of round 0; the other rounds' values, then both arrays round by round
-      float mx[4];
+      // one pass: the registers hold round 0; every round is added with the block exponents of the largest
+      // magnitudes seen so far, and when a round raises a chunk's exponent that chunk's sums are first shifted
+      // down to the new scale (round to nearest, ties to even; every later shift at least halves the error of an earlier one,
+      // so the shifts together cost at most one unit of the final scale per coefficient)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) mx[q] = lane_max(q, 0.f);
-      for (int r = 1; r < nrounds; ++r) {
-        load_payload(d, tt, r, false);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) mx[q] = lane_max(q, mx[q]);
+      for (int q = 0; q < 4; ++q) {
+        sh[q] = shift_of(lane_max(q, 0.f));
+        add_pairs(q, sh[q]);
       }
+      for (int r = 1; r < nrounds; ++r) {
+        load_payload(d, tt, r);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) sh[q] = shift_of(mx[q]);
-      for (int r = 0; r < nrounds; ++r) {
-        load_payload(d, tt, r, true);
+        for (int q = 0; q < 4; ++q) {
+          const int sh_r = shift_of(lane_max(q, 0.f));
+          if (sh_r < sh[q]) {   // uniform
+            const int dsh = min(sh[q] - sh_r, 31);
+            const int half = (1 << (dsh - 1)) - 1;   // + the kept part's lowest bit: ties go to even (a bias would add up over the slots)
+            wave_lds_sync();
+            // quadrant q of the tile: rows 32 (q / 2) .. +31, columns 32 (q % 2) .. +31
+            int* quad = itile + (32 * (q >> 1) + (lane >> 3)) * D32_LDT + 32 * (q & 1) + 4 * (lane & 7);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) add_pairs(q, sh[q]);
+            for (int i = 0; i < 4; ++i) {
+              int4 v = *reinterpret_cast<int4*>(quad + 8 * i * D32_LDT);
+              v.x = (v.x + half + ((v.x >> dsh) & 1)) >> dsh;
+              v.y = (v.y + half + ((v.y >> dsh) & 1)) >> dsh;
+              v.z = (v.z + half + ((v.z >> dsh) & 1)) >> dsh;
+              v.w = (v.w + half + ((v.w >> dsh) & 1)) >> dsh;
+              *reinterpret_cast<int4*>(quad + 8 * i * D32_LDT) = v;
+            }
+            wave_lds_sync();
+            sh[q] = sh_r;
+          }
+          add_pairs(q, sh[q]);
+        }
       }
     } else {
       scatter();
@@ -276,9 +293,9 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, tileno + nwaves - t_first, 0, false);
+      load_payload(d, tileno + nwaves - t_first, 0);
     } else {
-      load_payload(d, tt, 0, false);
+      load_payload(d, tt, 0);
     }
     if (PBF16 && !VEC4) request_x();
     wave_lds_sync();

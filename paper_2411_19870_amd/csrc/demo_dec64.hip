@@ -89,8 +89,8 @@ void build_dec64_tables(const double* P, float* out) {
 // multiple of 8: the first W / 8 of those loads.  MODE 3 / 4: k a multiple of 4 / 2, any W: a lane fetches 4 / 2
 // consecutive pairs of one worker per load (unit 64 j + lane of the chunk's W k pairs in worker-major order).
 // MODE 0: any k <= 64, W * k <= 2048, one pair per load.  MODE 5: k a multiple of 4 and more than 2048 pairs per
-// chunk (up to 65536): the payload is streamed in rounds of 2048 pairs, once for the largest magnitude (values only)
-// and once for the sums; the values of the first round of the next chunk are fetched during the products.
+// chunk (up to 65536): the payload is streamed once, in rounds of 2048 pairs, the sums being shifted down whenever a
+// round raises the block exponent; the first round of the next chunk is fetched during the products.
 // Modes 1 to 5 need 16-byte aligned payload arrays.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
 // nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
@@ -143,8 +143,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   const int sub = WIDE ? (lane >> 3) : (wpi == 2 ? (lane >> 5) : 0);
   const int pt = WIDE ? 4 * (lane & 7) : (wpi == 2 ? (lane & 31) : lane);
   const bool pact = WIDE || pt < k;
-  // `round` and `with_idx` matter in STREAM mode only: units 512 round + 64 j + lane, values alone or both arrays
-  auto load_payload = [&](const TensorDev& dd, int ccc, int round = 0, bool with_idx = true) {
+  // `round` matters in STREAM mode only: units 512 round + 64 j + lane
+  auto load_payload = [&](const TensorDev& dd, int ccc, int round = 0) {
     const int64_t wstride = (int64_t)dd.nchunks * k;
     const uint32_t lane_off = (uint32_t)(sub * (int)wstride + pt);
     const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)ccc * k;
@@ -169,11 +169,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
             const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
             for (int x = 0; x < 4; ++x) pv[4 * j + x] = ok ? b[x] : 0.f;
-            if (!STREAM || with_idx) {   // uniform
-              const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+            const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-              for (int x = 0; x < 4; ++x) pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
-            }
+            for (int x = 0; x < 4; ++x) pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
           } else {
             const u32x2 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x2*>(ip + off));
             const f32x2 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x2*>(vp + off));
@@ -280,7 +278,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   int t = find_tensor_uniform(tv, chunk);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
-  load_payload(d, chunk - t_first, 0, false);
+  load_payload(d, chunk - t_first, 0);
   const int kap = kappa(c), col4 = 4 * chi(c);
   // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
   // for members w' even / odd (w' >= 2 adds 32 columns)
@@ -311,15 +309,31 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     wave_lds_sync();
     int sh_chunk;   // shift of this chunk's fixed point (undone when phi is the identity)
     if constexpr (STREAM) {
-      // the registers hold the values of round 0; the other rounds' values, then both arrays round by round
-      float mx = lane_max(0.f);
+      // one pass: the registers hold round 0; every round is added with the block exponent of the largest
+      // magnitude seen so far, and when a round raises that exponent the sums in the tile are first shifted
+      // down to the new scale (round to nearest, ties to even; every later shift at least halves the error of an earlier one,
+      // so the shifts together cost at most one unit of the final scale per coefficient)
+      sh_chunk = shift_of(lane_max(0.f));
+      add_pairs(sh_chunk);
       for (int r = 1; r < nrounds; ++r) {
-        load_payload(d, cc, r, false);
-        mx = lane_max(mx);
-      }
-      sh_chunk = shift_of(mx);
-      for (int r = 0; r < nrounds; ++r) {
-        load_payload(d, cc, r, true);
+        load_payload(d, cc, r);
+        const int sh_r = shift_of(lane_max(0.f));
+        if (sh_r < sh_chunk) {   // uniform
+          const int dsh = min(sh_chunk - sh_r, 31);
+          const int half = (1 << (dsh - 1)) - 1;   // + the kept part's lowest bit: ties go to even (a bias would add up over the slots)
+          wave_lds_sync();
+#pragma unroll
+          for (int i = 0; i < 17; ++i) {
+            int4 v = *reinterpret_cast<int4*>(&itile[(i * 64 + lane) * 4]);
+            v.x = (v.x + half + ((v.x >> dsh) & 1)) >> dsh;
+            v.y = (v.y + half + ((v.y >> dsh) & 1)) >> dsh;
+            v.z = (v.z + half + ((v.z >> dsh) & 1)) >> dsh;
+            v.w = (v.w + half + ((v.w >> dsh) & 1)) >> dsh;
+            *reinterpret_cast<int4*>(&itile[(i * 64 + lane) * 4]) = v;
+          }
+          wave_lds_sync();
+          sh_chunk = sh_r;
+        }
         add_pairs(sh_chunk);
       }
     } else {
@@ -335,9 +349,9 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, chunk + nwaves - t_first, 0, false);
+      load_payload(d, chunk + nwaves - t_first, 0);
     } else {
-      load_payload(d, cc, 0, false);
+      load_payload(d, cc, 0);
     }
     wave_lds_sync();
     DEMO_PHASE(2);

@@ -503,15 +503,15 @@ hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const 
 namespace {
 constexpr int W128_DEC_SLOTS = 4;
 constexpr int W128_PT_FLOATS = 64 * W128_LDX;
-constexpr int W128_DEC_LDS_BYTES = 4 * (W128_PT_FLOATS + W128_X_FLOATS + 16);
+constexpr int W128_DEC_LDS_BYTES = 4 * (W128_PT_FLOATS + W128_X_FLOATS + 32);
 static_assert(kFast128MaxPairs == W128_DEC_SLOTS * W128_THREADS, "pairs per chunk held in registers");
 }  // namespace
 
 // STREAM false: W k <= 4096, one pair per load (consecutive threads read consecutive pairs, and the pairs are spread
 // evenly over the sixteen wavefronts; 16-byte loads would leave half of them without work at W k = 2048 and measured
 // slower).  STREAM true: more than 4096 pairs per chunk (up to 65536), k a multiple of four and 16-byte aligned payload
-// arrays: rounds of 4096 pairs, a thread fetching four consecutive pairs of one worker per load, once for the largest
-// magnitude (values only) and once for the sums.
+// arrays: one pass in rounds of 4096 pairs, a thread fetching four consecutive pairs of one worker per load; the sums
+// are shifted down whenever a round raises the block exponent.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance).  COUNT: the count-normalised
 // aggregate of the appendix algorithm Decompress&Aggregate (every coefficient's sum divided by the number of pairs
 // that name it), without STREAM only.
@@ -523,7 +523,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   float* sPT = lds;
   float* tile = sPT + W128_PT_FLOATS;
   int* itile = reinterpret_cast<int*>(tile);
-  uint32_t* wmax = reinterpret_cast<uint32_t*>(tile + W128_X_FLOATS);   // [16] per-wavefront largest |val|
+  uint32_t* wmax = reinterpret_cast<uint32_t*>(tile + W128_X_FLOATS);   // [2][16] per-wavefront largest |val| (two buffers: consecutive rounds of a streamed payload alternate)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, lq = lane >> 4;
@@ -552,8 +552,8 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     pv[j] = 0.f;
   }
   const float rk = 1.0f / (float)k;
-  // `round` and `with_idx` matter in STREAM mode only: units 1024 round + tid, values alone or both arrays
-  auto load_payload = [&](const TensorDev& dd, int cc, int round = 0, bool with_idx = true) {
+  // `round` matters in STREAM mode only: units 1024 round + tid
+  auto load_payload = [&](const TensorDev& dd, int cc, int round = 0) {
     const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)cc * k;
     const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)cc * k;
     const int wstride = dd.nchunks * k;                        // pairs of one worker for this tensor
@@ -568,11 +568,9 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
       for (int e = 0; e < 4; ++e) pv[e] = ok ? vv[e] : 0.f;
-      if (!STREAM || with_idx) {   // uniform
-        const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+      const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pi[e] = ok ? (int32_t)iv[e] : -1;
-      }
+      for (int e = 0; e < 4; ++e) pi[e] = ok ? (int32_t)iv[e] : -1;
       return;
     }
 #pragma unroll
@@ -594,7 +592,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   int t = find_tensor_uniform(tv, chunk);
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
-  load_payload(d, chunk - t_first, 0, false);
+  load_payload(d, chunk - t_first, 0);
 
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                     // 30 - ceil(log2 W)
@@ -629,16 +627,13 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
         if (j < nslots) pv[j] = pv[j] / (float)itile[slot_of(j)];
       wg_lds_barrier();
     }
-    // ---- largest |val| of the chunk, zero tile --------------------------------------------------------------
-    {
+    // ---- largest |val| of the payload registers, zero tile ----------------------------------------------------
+    // per-wavefront largest magnitude (as bits) of the payload registers into wmax buffer `buf`
+    auto post_wave_max = [&](int buf) {
       float mx = 0.f;
-      // (STREAM: the registers hold the values of round 0; then the other rounds' values)
-      for (int r = 0; r < nrounds; ++r) {
-        if (r > 0) load_payload(d, cc, r, false);
 #pragma unroll
-        for (int j = 0; j < W128_DEC_SLOTS; ++j)
-          if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
-      }
+      for (int j = 0; j < W128_DEC_SLOTS; ++j)
+        if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
       uint32_t mb = __float_as_uint(mx);
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
@@ -646,34 +641,62 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
       const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
       const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
-      if (lane == 0) wmax[wave] = max(m01, m23);
-    }
-    for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS)
-      *reinterpret_cast<f32x4*>(&tile[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
-    wg_lds_barrier();
-
-    // ---- S[idx] += val in fixed point ------------------------------------------------------------------------
-    int sh_chunk;   // shift of this chunk's fixed point (undone when phi is the identity)
-    {
-      uint32_t mall = wmax[lane & 15];
+      if (lane == 0) wmax[16 * buf + wave] = max(m01, m23);
+    };
+    // shift of the block fixed point from the sixteen posted maxima (after a barrier)
+    auto shift_from = [&](int buf) {
+      uint32_t mall = wmax[16 * buf + (lane & 15)];
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0xB1, 0xf, 0xf, false));
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x4E, 0xf, 0xf, false));
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x141, 0xf, 0xf, false));
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x140, 0xf, 0xf, false));
       int ex = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)mall) >> 23);   // biased exponent of the largest magnitude
       ex = ex < 1 ? 1 : ex;
-      const int sh = vbits + 126 - ex;                         // max |val| * 2^sh < 2^vbits
-      sh_chunk = sh;
-      for (int r = 0; r < nrounds; ++r) {
-        if (STREAM) load_payload(d, cc, r, true);
+      return vbits + 126 - ex;                                 // max |val| * 2^sh < 2^vbits
+    };
+    auto add_pairs = [&](int sh) {
 #pragma unroll
-        for (int j = 0; j < W128_DEC_SLOTS; ++j) {
-          if (j < nslots) {
-            const uint32_t fi = (uint32_t)pi[j];
-            const uint32_t a = fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
-            atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
-          }
+      for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+        if (j < nslots) {
+          const uint32_t fi = (uint32_t)pi[j];
+          const uint32_t a = fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
+          atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
         }
+      }
+    };
+    post_wave_max(0);
+    for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS)
+      *reinterpret_cast<f32x4*>(&tile[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
+    wg_lds_barrier();
+
+    // ---- S[idx] += val in fixed point ------------------------------------------------------------------------
+    int sh_chunk = shift_from(0);   // shift of this chunk's fixed point (undone when phi is the identity)
+    add_pairs(sh_chunk);
+    if constexpr (STREAM) {
+      // one pass over the payload: the registers held round 0; every further round is added with the block
+      // exponent of the largest magnitude seen so far, and when a round raises that exponent the sums in the tile
+      // are first shifted down to the new scale (round to nearest, ties to even; every later shift at least halves the error of
+      // an earlier one, so the shifts together cost at most one unit of the final scale per coefficient)
+      for (int r = 1; r < nrounds; ++r) {
+        load_payload(d, cc, r);
+        post_wave_max(r & 1);
+        wg_lds_barrier();   // maxima posted; the previous round's additions have landed
+        const int sh_r = shift_from(r & 1);
+        if (sh_r < sh_chunk) {   // uniform over the workgroup
+          const int dsh = min(sh_chunk - sh_r, 31);
+          const int half = (1 << (dsh - 1)) - 1;   // + the kept part's lowest bit: ties go to even (a bias would add up over the slots)
+          for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS) {
+            int4 v = *reinterpret_cast<int4*>(&itile[4 * e]);
+            v.x = (v.x + half + ((v.x >> dsh) & 1)) >> dsh;
+            v.y = (v.y + half + ((v.y >> dsh) & 1)) >> dsh;
+            v.z = (v.z + half + ((v.z >> dsh) & 1)) >> dsh;
+            v.w = (v.w + half + ((v.w >> dsh) & 1)) >> dsh;
+            *reinterpret_cast<int4*>(&itile[4 * e]) = v;
+          }
+          wg_lds_barrier();
+          sh_chunk = sh_r;
+        }
+        add_pairs(sh_chunk);
       }
     }
     // ---- payload of the next chunk, in flight during the products ----------------------------------------------
@@ -685,7 +708,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, nxt - t_first, 0, false);
+      load_payload(d, nxt - t_first, 0);
     }
     wg_lds_barrier();
 

@@ -92,7 +92,8 @@ def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x, phi="sign"
         R = chunk_rows(ref["R"], s)
         tolR = float(np.float32(lr32)) * VAL_REL * np.abs(R).max(axis=1, keepdims=True)
         w = chunk_rows(want.astype(np.float64), s)
-        ulp = np.abs(w) * (2.0 ** -8 if param_dtype == "bf16" else 2.0 ** -23) + 1e-45
+        # one unit in the last place: the spacing of the storage type at |w| (8 significant bits for bf16, 24 for f32)
+        ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(w), 1e-300))) - (7 if param_dtype == "bf16" else 23)) + 1e-45
         err = np.abs(chunk_rows(got.astype(np.float64), s) - w)
         assert np.all(err <= tolR + ulp), f"parameters off: worst excess {np.max(err - tolR - ulp):.3e}"
         return {"elements": int(got.size), "mismatch": int((got != want).sum()), "in_band": 0,

@@ -111,6 +111,32 @@ def test_count_aggregate_with_many_collisions(ctx, s, k, W, phi, pdt):
                        phi=phi, aggregate_mode="count")
 
 
+@pytest.mark.parametrize("s,k,W", [(64, 32, 200), (64, 8, 300), (32, 32, 64), (32, 8, 255), (128, 32, 255), (128, 64, 200)])
+@pytest.mark.parametrize("grow", [1.0, -1.0])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+def test_streamed_payload_with_changing_magnitudes(ctx, s, k, W, grow, pdt):
+    # more pairs per chunk than the decode kernels hold in registers: the payload is streamed in rounds, and
+    # the magnitudes grow (or shrink) by a factor 2^12 from the first worker to the last, so that round after
+    # round the block exponent of the running sums rises (or never does).  phi = identity: the values count.
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 2 * s, 3 * s), synth.TensorSpec("v", 2 * s, 0)]
+    case = Case(specs, s, k, W=W, param_dtype=pdt, seed=37)
+    case.fill_payloads()
+    w = torch.arange(W, dtype=torch.float32, device=case.val[0].device)
+    factor = torch.exp2(grow * 12.0 * w / (W - 1)).reshape(W, 1, 1)
+    for ti in range(len(case.specs)):
+        case.val[ti][:W] *= factor
+    hp = B.demo_hparams_default(lr=LR, weight_decay=0.0, phi=B.DEMO_PHI_IDENTITY)
+    before = case.snapshot()
+    ctx.demo_decode_ex(case.args, W, hp, s, k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    pd = "bf16" if pdt == torch.bfloat16 else "f32"
+    for ti in range(len(case.specs)):
+        C.check_decode(before["x"][ti], before["idx"][ti][:W], before["val"][ti][:W], LR, 0.0, s, pd, after["x"][ti],
+                       phi="identity")
+
+
 @pytest.mark.parametrize("variant", [0, 1])
 def test_default_hparams_match_plain_calls_bit_for_bit(ctx, variant):
     ctx.demo_set_variant(variant)
