@@ -15,8 +15,6 @@
 // Payload: the W*k <= 512 pairs of each of the four chunks sit in 8 registers per lane and chunk (pair
 // p = 64 j + lane of the chunk belongs to worker p / k, position p % k) and are fetched for the next tile
 // while the products of this one run.  Each chunk has its own fixed-point scale.
-#include <type_traits>
-
 #include "demo_device.h"
 
 namespace demo {
@@ -55,8 +53,10 @@ void build_dec32_tables(const double* P32, float* out) {
 // chunk, a chunk's sums being shifted down whenever a round raises its block exponent.  MODE 0: one pair per load.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
 // nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
-// coefficient's sum divided by the number of pairs that name it), modes 0 and 1 only.
-template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
+// coefficient's sum divided by the number of pairs that name it), modes 0 and 1 only.  NT: the 16-byte payload loads
+// are non-temporal (asked for when a row of k pairs fills a 128-byte line; shorter rows share lines with the
+// neighbouring chunks and stay cached).
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true>
 __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   constexpr bool VEC4 = MODE >= 1, STREAM = MODE == 2;
@@ -107,21 +107,23 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
       const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)c32 * k;
       const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)c32 * k;
       if constexpr (VEC4) {
+        {
 #pragma unroll
-        for (int jj = 0; jj < D32_SLOTS / 4; ++jj) {
-          if (jj < nloads) {                                  // uniform
-            const int unit = (STREAM ? 16 * D32_SLOTS * round : 0) + 64 * jj + lanev;
-            const int p = 4 * unit;
-            const int w = (int)(((float)p + 0.5f) * rk);      // as below (p < 65536)
-            const int pos = p - w * k;
-            const bool ok = unit < nunits;
-            const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
-            const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+          for (int jj = 0; jj < D32_SLOTS / 4; ++jj) {
+            if (jj < nloads) {                                  // uniform
+              const int unit = (STREAM ? 16 * D32_SLOTS * round : 0) + 64 * jj + lanev;
+              const int p = 4 * unit;
+              const int w = (int)(((float)p + 0.5f) * rk);      // as below (p < 65536)
+              const int pos = p - w * k;
+              const bool ok = unit < nunits;
+              const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
+              const f32x4 vv = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) pv[D32_SLOTS * q + 4 * jj + e] = ok ? vv[e] : 0.f;
-            const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+              for (int e = 0; e < 4; ++e) pv[D32_SLOTS * q + 4 * jj + e] = ok ? vv[e] : 0.f;
+              const u32x4 iv = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-            for (int e = 0; e < 4; ++e) pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
+              for (int e = 0; e < 4; ++e) pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
+            }
           }
         }
         continue;
@@ -397,30 +399,38 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   }
 }
 
-template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true>
 static hipError_t launch_dec_tile32_phi(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
                                         hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, MODE, IDENT, COUNT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_tile32<PBF16, MODE, IDENT, COUNT, NT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D32_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_tile32<PBF16, MODE, IDENT, COUNT>), dim3((unsigned)grid), dim3(D32_THREADS),
+  hipLaunchKernelGGL((decode2d_tile32<PBF16, MODE, IDENT, COUNT, NT>), dim3((unsigned)grid), dim3(D32_THREADS),
                      D32_LDS_BYTES, stream, tiles, tables, a);
   return hipGetLastError();
+}
+template <bool PBF16, int MODE, bool NT>
+static hipError_t launch_dec_tile32_nt(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
+                                       hipStream_t stream) {
+  if constexpr (MODE != 2) {
+    if (a.agg == 2)
+      return a.phi != 0 ? launch_dec_tile32_phi<PBF16, MODE, true, true, NT>(tiles, tables, a, grid, stream)
+                        : launch_dec_tile32_phi<PBF16, MODE, false, true, NT>(tiles, tables, a, grid, stream);
+  }
+  return a.phi != 0 ? launch_dec_tile32_phi<PBF16, MODE, true, false, NT>(tiles, tables, a, grid, stream)
+                    : launch_dec_tile32_phi<PBF16, MODE, false, false, NT>(tiles, tables, a, grid, stream);
 }
 template <bool PBF16, int MODE>
 static hipError_t launch_dec_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
-  if constexpr (MODE != 2) {
-    if (a.agg == 2)
-      return a.phi != 0 ? launch_dec_tile32_phi<PBF16, MODE, true, true>(tiles, tables, a, grid, stream)
-                        : launch_dec_tile32_phi<PBF16, MODE, false, true>(tiles, tables, a, grid, stream);
+  if constexpr (MODE != 0) {   // rows of k pairs shorter than a 128-byte line: plain loads
+    if (a.k < 32) return launch_dec_tile32_nt<PBF16, MODE, false>(tiles, tables, a, grid, stream);
   }
-  return a.phi != 0 ? launch_dec_tile32_phi<PBF16, MODE, true>(tiles, tables, a, grid, stream)
-                    : launch_dec_tile32_phi<PBF16, MODE, false>(tiles, tables, a, grid, stream);
+  return launch_dec_tile32_nt<PBF16, MODE, true>(tiles, tables, a, grid, stream);
 }
 
 hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,

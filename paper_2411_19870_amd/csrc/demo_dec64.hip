@@ -28,8 +28,6 @@
 //   product b   per w':  Cee/Ceo/Co0/Co1[i0][j] += G (as A) * Y tile (accumulators as B operand),
 //               row tile t feeding the class t belongs to; the four row members by in-lane adds.
 // Both products use the same fragment table G (6 groups x 64 lanes x 4 floats).
-#include <type_traits>
-
 #include "demo_device.h"
 
 namespace demo {
@@ -94,8 +92,10 @@ void build_dec64_tables(const double* P, float* out) {
 // Modes 1 to 5 need 16-byte aligned payload arrays.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
 // nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
-// coefficient's sum divided by the number of pairs that name it), modes 0, 3 and 4 only.
-template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
+// coefficient's sum divided by the number of pairs that name it), modes 0, 3 and 4 only.  NT: the 16- and 8-byte
+// payload loads of modes 3 to 5 are non-temporal (the launch wrapper asks for that when a row of k pairs fills a
+// 128-byte line; shorter rows share lines with neighbouring chunks and stay cached).
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   extern __shared__ float lds[];
@@ -154,31 +154,33 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       // spilled, and the reload of a spilled value waits for every load in flight)
       int lanev = lane;
       asm volatile("" : "+v"(lanev));
+      {
 #pragma unroll
-      for (int j = 0; j < NP / VW; ++j) {
-        if (j < nloads) {   // uniform
-          const int unit = (STREAM ? 64 * (NP / VW) * round : 0) + 64 * j + lanev;
-          const int p = VW * unit;
-          // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
-          // the rounding error of the float product for p < 65536
-          const int w = (int)(((float)p + 0.5f) * rk);
-          const int pos = p - w * k;
-          const bool ok = unit < nunits;
-          const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
-          if constexpr (VW == 4) {
-            const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+        for (int j = 0; j < NP / VW; ++j) {
+          if (j < nloads) {   // uniform
+            const int unit = (STREAM ? 64 * (NP / VW) * round : 0) + 64 * j + lanev;
+            const int p = VW * unit;
+            // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
+            // the rounding error of the float product for p < 65536
+            const int w = (int)(((float)p + 0.5f) * rk);
+            const int pos = p - w * k;
+            const bool ok = unit < nunits;
+            const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
+            if constexpr (VW == 4) {
+              const f32x4 b = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
-            for (int x = 0; x < 4; ++x) pv[4 * j + x] = ok ? b[x] : 0.f;
-            const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+              for (int x = 0; x < 4; ++x) pv[4 * j + x] = ok ? b[x] : 0.f;
+              const u32x4 a = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-            for (int x = 0; x < 4; ++x) pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
-          } else {
-            const u32x2 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x2*>(ip + off));
-            const f32x2 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x2*>(vp + off));
+              for (int x = 0; x < 4; ++x) pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
+            } else {
+              const u32x2 a = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x2*>(ip + off));
+              const f32x2 b = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL f32x2*>(vp + off));
 #pragma unroll
-            for (int x = 0; x < 2; ++x) {
-              pi[2 * j + x] = ok ? (int32_t)a[x] : -1;
-              pv[2 * j + x] = ok ? b[x] : 0.f;
+              for (int x = 0; x < 2; ++x) {
+                pi[2 * j + x] = ok ? (int32_t)a[x] : -1;
+                pv[2 * j + x] = ok ? b[x] : 0.f;
+              }
             }
           }
         }
@@ -187,8 +189,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         if (FULL || 4 * j < nact) {
-          const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + lane_off));
-          const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + lane_off));
+          const u32x4 a = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + lane_off));
+          const f32x4 b = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + lane_off));
 #pragma unroll
           for (int x = 0; x < 4; ++x) {
             pi[4 * j + x] = (int32_t)a[x];
@@ -674,30 +676,40 @@ static hipError_t launch_dec_sparse64(const TableView& tv, const float* tables, 
   return hipGetLastError();
 }
 
-template <bool PBF16, int MODE, bool IDENT, bool COUNT = false>
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true>
 static hipError_t launch_dec_wave64_phi(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
                                         hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE, IDENT, COUNT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE, IDENT, COUNT, NT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, D64_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE, IDENT, COUNT>), dim3((unsigned)grid), dim3(D64_THREADS),
+  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE, IDENT, COUNT, NT>), dim3((unsigned)grid), dim3(D64_THREADS),
                      D64_LDS_BYTES, stream, tv, tables, a);
   return hipGetLastError();
+}
+template <bool PBF16, int MODE, bool NT>
+static hipError_t launch_dec_wave64_nt(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
+                                       hipStream_t stream) {
+  if constexpr (MODE == 0 || MODE == 3 || MODE == 4) {
+    if (a.agg == 2)
+      return a.phi != 0 ? launch_dec_wave64_phi<PBF16, MODE, true, true, NT>(tv, tables, a, grid, stream)
+                        : launch_dec_wave64_phi<PBF16, MODE, false, true, NT>(tv, tables, a, grid, stream);
+  }
+  return a.phi != 0 ? launch_dec_wave64_phi<PBF16, MODE, true, false, NT>(tv, tables, a, grid, stream)
+                    : launch_dec_wave64_phi<PBF16, MODE, false, false, NT>(tv, tables, a, grid, stream);
 }
 template <bool PBF16, int MODE>
 static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
                                     hipStream_t stream) {
-  if constexpr (MODE == 0 || MODE == 3 || MODE == 4) {
-    if (a.agg == 2)
-      return a.phi != 0 ? launch_dec_wave64_phi<PBF16, MODE, true, true>(tv, tables, a, grid, stream)
-                        : launch_dec_wave64_phi<PBF16, MODE, false, true>(tv, tables, a, grid, stream);
+  // rows of k pairs shorter than a 128-byte line: plain loads (mode 4 has such rows but for k = 34 ... 62)
+  if constexpr (MODE == 3 || MODE == 5) {
+    if (a.k < 32) return launch_dec_wave64_nt<PBF16, MODE, false>(tv, tables, a, grid, stream);
   }
-  return a.phi != 0 ? launch_dec_wave64_phi<PBF16, MODE, true>(tv, tables, a, grid, stream)
-                    : launch_dec_wave64_phi<PBF16, MODE, false>(tv, tables, a, grid, stream);
+  if constexpr (MODE == 4) return launch_dec_wave64_nt<PBF16, MODE, false>(tv, tables, a, grid, stream);
+  return launch_dec_wave64_nt<PBF16, MODE, true>(tv, tables, a, grid, stream);
 }
 
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,

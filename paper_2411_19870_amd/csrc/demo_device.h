@@ -17,6 +17,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ f32x4 gload_f4(const float* p) { return *(const DEMO_GLOBAL f32x4*)(p); }
 __device__ __forceinline__ u32x2 gload_u2(const void* p) { return *(const DEMO_GLOBAL u32x2*)(p); }
+// Payload loads of the decode kernels.  The payload is read once, so rows of a full 128-byte line or more
+// (k >= 32) are fetched non-temporally; shorter rows share their lines with the neighbouring chunks that other
+// wavefronts read at about the same time, and must stay in the cache for them (measured on the 1B-like set, W = 64:
+// s = 32, k = 8 2.96 -> 2.05 ms and s = 64, k = 2 1.41 -> 1.22 ms with plain loads; k = 32 1 to 3 % the other way).
+template <bool NT, class T>
+__device__ __forceinline__ T payload_load(const DEMO_GLOBAL T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
 // Stores whose data registers stay untouched for two wait states behind them (see bstore_f4 below for why).
 template <class T>
 __device__ __forceinline__ void store_guarded(DEMO_GLOBAL T* p, T v) {

@@ -565,10 +565,10 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       const int pos = p - w * k;
       const bool ok = unit < nunits;
       const uint32_t off = ok ? (uint32_t)(w * wstride + pos) : 0u;
-      const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+      const f32x4 vv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
       for (int e = 0; e < 4; ++e) pv[e] = ok ? vv[e] : 0.f;
-      const u32x4 iv = __builtin_nontemporal_load(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+      const u32x4 iv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
       for (int e = 0; e < 4; ++e) pi[e] = ok ? (int32_t)iv[e] : -1;
       return;
@@ -583,8 +583,8 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
         const int pos = p - w * k;
         const bool ok = p < npairs;
         const uint32_t off = (uint32_t)(w * wstride + pos);
-        pi[j] = ok ? __builtin_nontemporal_load(ip + off) : -1;
-        pv[j] = ok ? __builtin_nontemporal_load(vp + off) : 0.f;
+        pi[j] = ok ? payload_load<true>(ip + off) : -1;
+        pv[j] = ok ? payload_load<true>(vp + off) : 0.f;
       }
     }
   };
