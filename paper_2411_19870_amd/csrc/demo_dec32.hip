@@ -52,7 +52,7 @@ void build_dec32_tables(const double* P32, float* out) {
 // of chunk q).  MODE 2 (STREAM): more than 512 pairs per chunk (up to 65536), streamed once in rounds of 512 per
 // chunk, a chunk's sums being shifted down whenever a round raises its block exponent.  MODE 0: one pair per load.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
-// nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
+// nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm "Sparse Top-k Averaging" (every
 // coefficient's sum divided by the number of pairs that name it), modes 0 and 1 only.  NT: the 16-byte payload loads
 // are non-temporal (asked for when a row of k pairs fills a 128-byte line; shorter rows share lines with the
 // neighbouring chunks and stay cached).

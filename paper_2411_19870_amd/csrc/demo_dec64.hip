@@ -91,7 +91,7 @@ void build_dec64_tables(const double* P, float* out) {
 // round raises the block exponent; the first round of the next chunk is fetched during the products.
 // Modes 1 to 5 need 16-byte aligned payload arrays.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance, so that the sign kernels carry
-// nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm Decompress&Aggregate (every
+// nothing for it).  COUNT: the count-normalised aggregate of the appendix algorithm "Sparse Top-k Averaging" (every
 // coefficient's sum divided by the number of pairs that name it), modes 0, 3 and 4 only.  NT: the 16- and 8-byte
 // payload loads of modes 3 to 5 are non-temporal (the launch wrapper asks for that when a row of k pairs fills a
 // 128-byte line; shorter rows share lines with neighbouring chunks and stay cached).

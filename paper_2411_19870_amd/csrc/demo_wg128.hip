@@ -513,7 +513,7 @@ static_assert(kFast128MaxPairs == W128_DEC_SLOTS * W128_THREADS, "pairs per chun
 // arrays: one pass in rounds of 4096 pairs, a thread fetching four consecutive pairs of one worker per load; the sums
 // are shifted down whenever a round raises the block exponent.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance).  COUNT: the count-normalised
-// aggregate of the appendix algorithm Decompress&Aggregate (every coefficient's sum divided by the number of pairs
+// aggregate of the appendix algorithm "Sparse Top-k Averaging" (every coefficient's sum divided by the number of pairs
 // that name it), without STREAM only.
 template <bool PBF16, bool STREAM, bool IDENT, bool COUNT = false>
 __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, const float* __restrict__ basis,
