@@ -28,14 +28,22 @@ struct BasisTable {
   bool use_custom = false;   // later calls project with `custom` on the generic kernels
 };
 
+// The order-2 tensors of a list that share gradient and parameter dtype: they go out in one launch per
+// side (the wavefront kernels are instances per dtype; a list of mixed dtypes takes one launch per group
+// instead of falling back to the kernels that read the dtype per tensor).
+struct TableGroup {
+  TableView tv2{};
+  TableView tv2t{};           // the same tensors counted in 64 x 64 tiles (s = 32, all dimensions multiples of 64), else n = 0
+  demo::Worklist wl{};        // queue of this group's chunks for the exact fallback kernel
+};
+
 // One cached descriptor upload: the host bytes it was built from and the device copy.
 struct TableCache {
   std::vector<char> key;      // raw demo_tensor bytes + s
-  void* dev = nullptr;        // [TensorDev x n2][int32 x (n2+1)] [TensorDev x n1][int32 x (n1+1)]
+  void* dev = nullptr;        // per group [TensorDev x n][int32 x (n+1)][queue][tile tables], then the order-1 tables
   size_t dev_bytes = 0;
-  TableView tv2{}, tv1{};
-  TableView tv2t{};           // order-2 tensors counted in 64 x 64 tiles (s = 32, all dimensions multiples of 64), else n = 0
-  demo::Worklist wl{};        // queue of order-2 chunks for the exact fallback kernel
+  std::vector<TableGroup> groups;   // order-2 tensors by (gradient dtype, parameter dtype), at most four
+  TableView tv1{};
   uint64_t last_use = 0;
 };
 
@@ -202,14 +210,21 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
       return DEMO_OK;
     }
   }
-  std::vector<TensorDev> d2, d1, d2t;
-  std::vector<int32_t> p2(1, 0), p1(1, 0), p2t(1, 0);
-  bool tiles_ok = s == 32;
-  uint32_t mix2 = 0, mix1 = 0;
+  struct HostGroup {
+    uint32_t dt = 0;   // (gradient is bf16) | (parameter is bf16) << 1
+    std::vector<TensorDev> d2, d2t;
+    std::vector<int32_t> p2{0}, p2t{0};
+    bool tiles_ok = true;
+    uint32_t mix = 0;
+    size_t o_d2 = 0, o_p2 = 0, o_wl = 0, o_d2t = 0, o_p2t = 0;
+  };
+  std::vector<HostGroup> hg;
+  std::vector<TensorDev> d1;
+  std::vector<int32_t> p1(1, 0);
+  uint32_t mix1 = 0;
   for (int i = 0; i < n; ++i) {
     const bool al16 = ((reinterpret_cast<uintptr_t>(t[i].idx) | reinterpret_cast<uintptr_t>(t[i].val)) & 15u) == 0;
     const uint32_t mix = (t[i].grad_dtype == DEMO_BF16 ? 1u : 2u) | (t[i].param_dtype == DEMO_BF16 ? 4u : 8u) | (al16 ? 0u : 16u);
-    (t[i].cols == 0 ? mix1 : mix2) |= mix;
     TensorDev d{};
     d.grad = t[i].grad;
     d.mom = t[i].mom;
@@ -221,40 +236,58 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
     d.grad_bf16 = t[i].grad_dtype == DEMO_BF16;
     d.param_bf16 = t[i].param_dtype == DEMO_BF16;
     if (t[i].cols == 0) {
+      mix1 |= mix;
       d.cchunks = 1;
       d.nchunks = (int32_t)(t[i].rows / s);
       d1.push_back(d);
       p1.push_back(p1.back() + d.nchunks);
     } else {
+      const uint32_t dt = (d.grad_bf16 ? 1u : 0u) | (d.param_bf16 ? 2u : 0u);
+      HostGroup* g = nullptr;
+      for (HostGroup& x : hg)
+        if (x.dt == dt) g = &x;
+      if (g == nullptr) {
+        hg.emplace_back();
+        g = &hg.back();
+        g->dt = dt;
+        g->tiles_ok = s == 32;
+      }
+      g->mix |= mix;
       d.cchunks = (int32_t)(t[i].cols / s);
       d.nchunks = (int32_t)((t[i].rows / s) * (t[i].cols / s));
-      d2.push_back(d);
-      p2.push_back(p2.back() + d.nchunks);
-      if (t[i].rows % 64 != 0 || t[i].cols % 64 != 0) tiles_ok = false;
-      TensorDev dt = d;
-      dt.cchunks = (int32_t)(t[i].cols / 64);
-      dt.nchunks = (int32_t)((t[i].rows / 64) * (t[i].cols / 64));
-      d2t.push_back(dt);
-      p2t.push_back(p2t.back() + dt.nchunks);
+      g->d2.push_back(d);
+      g->p2.push_back(g->p2.back() + d.nchunks);
+      if (t[i].rows % 64 != 0 || t[i].cols % 64 != 0) g->tiles_ok = false;
+      TensorDev dt64 = d;
+      dt64.cchunks = (int32_t)(t[i].cols / 64);
+      dt64.nchunks = (int32_t)((t[i].rows / 64) * (t[i].cols / 64));
+      g->d2t.push_back(dt64);
+      g->p2t.push_back(g->p2t.back() + dt64.nchunks);
     }
   }
   auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
-  const size_t o_d2 = 0;
-  const size_t o_p2 = align16(o_d2 + d2.size() * sizeof(TensorDev));
-  const size_t o_d1 = align16(o_p2 + p2.size() * sizeof(int32_t));
+  size_t off = 0;
+  for (HostGroup& g : hg) {
+    if (!g.tiles_ok) { g.d2t.clear(); g.p2t.assign(1, 0); }
+    g.o_d2 = off;
+    g.o_p2 = align16(g.o_d2 + g.d2.size() * sizeof(TensorDev));
+    g.o_wl = align16(g.o_p2 + g.p2.size() * sizeof(int32_t));   // count, ticket, pad, pad, list[]
+    g.o_d2t = align16(g.o_wl + (4 + (size_t)g.p2.back()) * sizeof(int32_t));
+    g.o_p2t = align16(g.o_d2t + g.d2t.size() * sizeof(TensorDev));
+    off = align16(g.o_p2t + g.p2t.size() * sizeof(int32_t));
+  }
+  const size_t o_d1 = off;
   const size_t o_p1 = align16(o_d1 + d1.size() * sizeof(TensorDev));
-  const size_t o_wl = align16(o_p1 + p1.size() * sizeof(int32_t));   // count, ticket, pad, pad, list[]
-  const size_t o_d2t = align16(o_wl + (4 + (size_t)p2.back()) * sizeof(int32_t));
-  if (!tiles_ok) { d2t.clear(); p2t.assign(1, 0); }
-  const size_t o_p2t = align16(o_d2t + d2t.size() * sizeof(TensorDev));
-  const size_t total = align16(o_p2t + p2t.size() * sizeof(int32_t));
-  std::vector<char> host(total, 0);
-  if (!d2.empty()) std::memcpy(host.data() + o_d2, d2.data(), d2.size() * sizeof(TensorDev));
-  std::memcpy(host.data() + o_p2, p2.data(), p2.size() * sizeof(int32_t));
+  const size_t total = align16(o_p1 + p1.size() * sizeof(int32_t));
+  std::vector<char> host(total, 0);   // the queues start out zero-filled
+  for (const HostGroup& g : hg) {
+    std::memcpy(host.data() + g.o_d2, g.d2.data(), g.d2.size() * sizeof(TensorDev));
+    std::memcpy(host.data() + g.o_p2, g.p2.data(), g.p2.size() * sizeof(int32_t));
+    if (!g.d2t.empty()) std::memcpy(host.data() + g.o_d2t, g.d2t.data(), g.d2t.size() * sizeof(TensorDev));
+    std::memcpy(host.data() + g.o_p2t, g.p2t.data(), g.p2t.size() * sizeof(int32_t));
+  }
   if (!d1.empty()) std::memcpy(host.data() + o_d1, d1.data(), d1.size() * sizeof(TensorDev));
   std::memcpy(host.data() + o_p1, p1.data(), p1.size() * sizeof(int32_t));
-  if (!d2t.empty()) std::memcpy(host.data() + o_d2t, d2t.data(), d2t.size() * sizeof(TensorDev));
-  std::memcpy(host.data() + o_p2t, p2t.data(), p2t.size() * sizeof(int32_t));
 
   TableCache* slot = nullptr;
   if ((int)ctx->tables.size() < kMaxCachedTables) {
@@ -280,23 +313,28 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
   hipError_t e = hipMemcpy(slot->dev, host.data(), total, hipMemcpyHostToDevice);
   if (e != hipSuccess) { slot->key.clear(); return fail_hip(ctx, e); }
   char* base = static_cast<char*>(slot->dev);
-  slot->tv2.descs = reinterpret_cast<const TensorDev*>(base + o_d2);
-  slot->tv2.prefix = reinterpret_cast<const int32_t*>(base + o_p2);
-  slot->tv2.n = (int32_t)d2.size();
-  slot->tv2.total_chunks = p2.back();
-  slot->tv2.dtypes = mix2;
+  slot->groups.clear();
+  for (const HostGroup& g : hg) {
+    TableGroup tg;
+    tg.tv2.descs = reinterpret_cast<const TensorDev*>(base + g.o_d2);
+    tg.tv2.prefix = reinterpret_cast<const int32_t*>(base + g.o_p2);
+    tg.tv2.n = (int32_t)g.d2.size();
+    tg.tv2.total_chunks = g.p2.back();
+    tg.tv2.dtypes = g.mix;
+    tg.tv2t.descs = reinterpret_cast<const TensorDev*>(base + g.o_d2t);
+    tg.tv2t.prefix = reinterpret_cast<const int32_t*>(base + g.o_p2t);
+    tg.tv2t.n = (int32_t)g.d2t.size();
+    tg.tv2t.total_chunks = g.p2t.back();
+    tg.tv2t.dtypes = g.mix;
+    int32_t* wl = reinterpret_cast<int32_t*>(base + g.o_wl);
+    tg.wl = demo::Worklist{wl, wl + 1, wl + 4};
+    slot->groups.push_back(tg);
+  }
   slot->tv1.descs = reinterpret_cast<const TensorDev*>(base + o_d1);
   slot->tv1.prefix = reinterpret_cast<const int32_t*>(base + o_p1);
   slot->tv1.n = (int32_t)d1.size();
   slot->tv1.total_chunks = p1.back();
   slot->tv1.dtypes = mix1;
-  slot->tv2t.descs = reinterpret_cast<const TensorDev*>(base + o_d2t);
-  slot->tv2t.prefix = reinterpret_cast<const int32_t*>(base + o_p2t);
-  slot->tv2t.n = (int32_t)d2t.size();
-  slot->tv2t.total_chunks = p2t.back();
-  slot->tv2t.dtypes = mix2;
-  int32_t* wl = reinterpret_cast<int32_t*>(base + o_wl);   // zero-filled by the copy above
-  slot->wl = demo::Worklist{wl, wl + 1, wl + 4};
   slot->key.swap(key);
   slot->last_use = ++ctx->use_counter;
   *out = slot;
@@ -331,10 +369,13 @@ int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, co
                hipStream_t st) {
   demo::EncodeArgs a{hp.beta, hp.grad_scale, hp.alpha, k, basis.dct ? 1 : 0};
   int rc;
-  if (tc->tv2.total_chunks > 0) {
+  if (!tc->groups.empty()) {   // the timer brackets the launches of all groups
     if ((rc = timer_begin(ctx, 0, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_encode2d(tc->tv2, tc->tv2t.n > 0 ? &tc->tv2t : nullptr, basis, s, a, tc->wl, ctx->num_cus, ctx->variant, st);
-    if (e != hipSuccess) return fail_hip(ctx, e);
+    for (const TableGroup& g : tc->groups) {
+      hipError_t e = demo::launch_encode2d(g.tv2, g.tv2t.n > 0 ? &g.tv2t : nullptr, basis, s, a, g.wl, ctx->num_cus,
+                                           ctx->variant, st);
+      if (e != hipSuccess) return fail_hip(ctx, e);
+    }
     if ((rc = timer_end(ctx, 0, st)) != DEMO_OK) return rc;
   }
   if (tc->tv1.total_chunks > 0) {
@@ -351,11 +392,13 @@ int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, in
   const float scale = hp.aggregate == DEMO_AGG_MEAN ? 1.0f / (float)W : 1.0f;
   demo::DecodeArgs a{hp.lr, hp.weight_decay, scale, k, W, hp.phi, hp.aggregate, basis.dct ? 1 : 0};
   int rc;
-  if (tc->tv2.total_chunks > 0) {
+  if (!tc->groups.empty()) {
     if ((rc = timer_begin(ctx, 2, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_decode2d(tc->tv2, tc->tv2t.n > 0 ? &tc->tv2t : nullptr, basis, s, a, ctx->num_cus,
-                                         ctx->variant, st);
-    if (e != hipSuccess) return fail_hip(ctx, e);
+    for (const TableGroup& g : tc->groups) {
+      hipError_t e = demo::launch_decode2d(g.tv2, g.tv2t.n > 0 ? &g.tv2t : nullptr, basis, s, a, ctx->num_cus,
+                                           ctx->variant, st);
+      if (e != hipSuccess) return fail_hip(ctx, e);
+    }
     if ((rc = timer_end(ctx, 2, st)) != DEMO_OK) return rc;
   }
   if (tc->tv1.total_chunks > 0) {

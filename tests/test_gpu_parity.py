@@ -364,16 +364,21 @@ def test_payload_arrays_with_4_byte_alignment(ctx, s, W, k):
     run_decode_check(ctx, base, W=W)
 
 
-# ---- tensors of different dtypes in one call (the wavefront kernels want one dtype per call: generic path) ---------
-@pytest.mark.parametrize("s", [32, 64])
-def test_mixed_dtypes_in_one_list(ctx, s):
-    ctx.demo_set_variant(1)
-    specs = [synth.TensorSpec("a", 128, 192), synth.TensorSpec("b", 192, 64), synth.TensorSpec("v", 128, 0)]
+# ---- tensors of different dtypes in one call: one launch per (gradient dtype, parameter dtype) group --------------
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("s", [32, 64, 128])
+def test_mixed_dtypes_in_one_list(ctx, s, variant):
+    ctx.demo_set_variant(variant)
+    specs = [synth.TensorSpec("a", 256, 384), synth.TensorSpec("b", 384, 128), synth.TensorSpec("v", 256, 0),
+             synth.TensorSpec("c", 128, 256), synth.TensorSpec("d", 256, 256), synth.TensorSpec("w", 128, 0)]
     k, W = 8, 3
     case = Case(specs, s, k, W=W, seed=61)
-    # tensor 1 gets bf16 gradients and parameters, the others stay float32
-    case.g[1] = case.g[1].to(torch.bfloat16)
-    case.x[1] = case.x[1].to(torch.bfloat16)
+    # four dtype combinations among the order-2 tensors, interleaved in the list; one bf16 vector
+    for ti, (gb, xb) in {1: (True, True), 3: (True, False), 4: (False, True), 5: (True, True)}.items():
+        if gb:
+            case.g[ti] = case.g[ti].to(torch.bfloat16)
+        if xb:
+            case.x[ti] = case.x[ti].to(torch.bfloat16)
     case.args = B.TensorList([B.TensorArgs(g, m, x, i, v) for g, m, x, i, v in zip(case.g, case.m, case.x, case.idx, case.val)])
     before = case.snapshot()
     ctx.demo_encode(case.args, BETA, s, k)
@@ -389,6 +394,7 @@ def test_mixed_dtypes_in_one_list(ctx, s):
     for ti in range(len(specs)):
         pd = "bf16" if case.x[ti].dtype == torch.bfloat16 else "f32"
         C.check_decode(before["x"][ti], before["idx"][ti], before["val"][ti], LR, 0.0, s, pd, after["x"][ti])
+    ctx.demo_set_variant(1)
 
 
 # ---- s = 64, k = 32: worker counts that are multiples of 8 read the payload with 16-byte loads ------------------
