@@ -42,7 +42,7 @@ struct TableCache {
   std::vector<char> key;      // raw demo_tensor bytes + s
   void* dev = nullptr;        // per group [TensorDev x n][int32 x (n+1)][queue][tile tables], then the order-1 tables
   size_t dev_bytes = 0;
-  std::vector<TableGroup> groups;   // order-2 tensors by (gradient dtype, parameter dtype), at most four
+  std::vector<TableGroup> groups;   // order-2 tensors by (gradient dtype, parameter dtype, tileable at s = 32)
   TableView tv1{};
   uint64_t last_use = 0;
 };
@@ -211,7 +211,7 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
     }
   }
   struct HostGroup {
-    uint32_t dt = 0;   // (gradient is bf16) | (parameter is bf16) << 1
+    uint32_t dt = 0;   // (gradient is bf16) | (parameter is bf16) << 1 | (s = 32 and not made of 64 x 64 tiles) << 2
     std::vector<TensorDev> d2, d2t;
     std::vector<int32_t> p2{0}, p2t{0};
     bool tiles_ok = true;
@@ -242,7 +242,10 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
       d1.push_back(d);
       p1.push_back(p1.back() + d.nchunks);
     } else {
-      const uint32_t dt = (d.grad_bf16 ? 1u : 0u) | (d.param_bf16 ? 2u : 0u);
+      // s = 32: tensors that the 64 x 64 tile kernels cannot take (a dimension not a multiple of 64) form groups
+      // of their own, so that they do not pull the others onto the generic kernels
+      const bool odd_tiles = s == 32 && (t[i].rows % 64 != 0 || t[i].cols % 64 != 0);
+      const uint32_t dt = (d.grad_bf16 ? 1u : 0u) | (d.param_bf16 ? 2u : 0u) | (odd_tiles ? 4u : 0u);
       HostGroup* g = nullptr;
       for (HostGroup& x : hg)
         if (x.dt == dt) g = &x;

@@ -292,6 +292,18 @@ def test_s32_decode_unaligned_shape_takes_the_generic_kernel(ctx):
     run_decode_check(ctx, case, W=4)
 
 
+def test_s32_list_with_and_without_64_multiples(ctx):
+    # 96 x 160 cannot be cut into 64 x 64 tiles: it runs apart from the tensors that can
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 128, 192), synth.TensorSpec("b", 96, 160), synth.TensorSpec("c", 64, 256),
+             synth.TensorSpec("d", 32, 32), synth.TensorSpec("v", 96, 0)]
+    case = Case(specs, 32, 8, W=4, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, seed=10)
+    run_encode_check(ctx, case)
+    run_decode_check(ctx, case, W=1)
+    case.fill_payloads()
+    run_decode_check(ctx, case, W=4, wd=0.1)
+
+
 # ---- large sparsity budgets and many workers (generic kernels; k = 64 is the last budget of the s = 64 wavefront kernel)
 @pytest.mark.parametrize("s,k", [(64, 64), (64, 65), (64, 256), (32, 200), (128, 256)])
 def test_large_k(ctx, s, k):
