@@ -86,7 +86,7 @@ void build_dec64_tables(const double* P, float* out) {
 // read with eight fully populated 16-byte loads per array (eight workers each).  MODE 2: k == 32 and W a smaller
 // multiple of 8: the first W / 8 of those loads.  MODE 3 / 4: k a multiple of 4 / 2, any W: a lane fetches 4 / 2
 // consecutive pairs of one worker per load (unit 64 j + lane of the chunk's W k pairs in worker-major order).
-// MODE 0: any k <= 64, W * k <= 2048, one pair per load.  MODE 5: k a multiple of 4 and more than 2048 pairs per
+// MODE 0: any k <= 64, W * k <= 2048, one pair per load (unit-wise like modes 3 and 4).  MODE 5: k a multiple of 4 and more than 2048 pairs per
 // chunk (up to 65536): the payload is streamed once, in rounds of 2048 pairs, the sums being shifted down whenever a
 // round raises the block exponent; the first round of the next chunk is fetched during the products.
 // Modes 1 to 5 need 16-byte aligned payload arrays.
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   constexpr bool FULL = MODE == 1;          // every payload register is in use
   constexpr bool WIDE = MODE == 1 || MODE == 2;   // 16-byte payload loads, eight workers per load
   constexpr int VW = (MODE == 3 || MODE == 5) ? 4 : MODE == 4 ? 2 : 1;   // pairs per load of the unit-wise modes
-  constexpr bool UNITS = MODE >= 3;
+  constexpr bool UNITS = MODE >= 3 || MODE == 0;   // unit 64 j + lane of the chunk's pairs, VW pairs per unit
   constexpr bool STREAM = MODE == 5;        // more pairs than the registers hold: rounds of 2048
   const int k = WIDE ? 32 : args.k, W = args.W;
 
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   // ---- payload access ---------------------------------------------------------------------------------
   // 32 (index, value) pairs per lane hold the whole payload of a chunk (W * k <= 2048 pairs).
   //   WIDE:  load j (0..7) fetches pairs 4(l%8) .. +3 of worker 8j + l/8 as one 16-byte load;
-  //   else:  load j (0..31) fetches one pair: with k <= 32 of worker 2j + l/32, else of worker j.
+  //   else:  load j fetches unit 64 j + l of the chunk's W k / VW units in worker-major order (VW pairs each).
   constexpr int NP = 32;
   int32_t pi[NP];
   float pv[NP];
@@ -134,15 +134,12 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     pi[j] = -1;
     pv[j] = 0.f;
   }
-  const int wpi = k <= 32 ? 2 : 1;
   const int nunits = (W * k) / VW;                                   // UNITS: loads per array and chunk
   const int nloads = STREAM ? NP / VW : (nunits + 63) >> 6;          // ... per lane (STREAM: per round)
   const int nrounds = (nunits + 64 * (NP / VW) - 1) / (64 * (NP / VW));
   const float rk = 1.0f / (float)k;
-  const int nact = FULL ? NP : WIDE ? W / 2 : UNITS ? VW * nloads : (W + wpi - 1) / wpi;   // payload registers in use (uniform)
-  const int sub = WIDE ? (lane >> 3) : (wpi == 2 ? (lane >> 5) : 0);
-  const int pt = WIDE ? 4 * (lane & 7) : (wpi == 2 ? (lane & 31) : lane);
-  const bool pact = WIDE || pt < k;
+  const int nact = FULL ? NP : WIDE ? W / 2 : VW * nloads;   // payload registers in use (uniform)
+  const int sub = lane >> 3, pt = 4 * (lane & 7);              // WIDE: worker within the load, first pair
   // `round` matters in STREAM mode only: units 512 round + 64 j + lane
   auto load_payload = [&](const TensorDev& dd, int ccc, int round = 0) {
     const int64_t wstride = (int64_t)dd.nchunks * k;
@@ -173,7 +170,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
               const u32x4 a = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
               for (int x = 0; x < 4; ++x) pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
-            } else {
+            } else if constexpr (VW == 2) {
               const u32x2 a = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x2*>(ip + off));
               const f32x2 b = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL f32x2*>(vp + off));
 #pragma unroll
@@ -181,6 +178,11 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
                 pi[2 * j + x] = ok ? (int32_t)a[x] : -1;
                 pv[2 * j + x] = ok ? b[x] : 0.f;
               }
+            } else {   // one pair per load: any k, arrays with their natural alignment only
+              pi[j] = ok ? ip[off] : -1;
+              pv[j] = ok ? vp[off] : 0.f;
+              // the 32 offsets are formed eight at a time (all at once they would not fit the registers)
+              if ((j & 7) == 7) __builtin_amdgcn_sched_barrier(0);
             }
           }
         }
@@ -198,17 +200,6 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
           }
           ip += 8 * wstride;
           vp += 8 * wstride;
-        }
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < NP; ++j) {
-        if (j < nact) {
-          const bool ok = pact && j * wpi + sub < W;
-          pi[j] = ok ? ip[lane_off] : -1;
-          pv[j] = ok ? vp[lane_off] : 0.f;
-          ip += wpi * wstride;
-          vp += wpi * wstride;
         }
       }
     }

@@ -356,7 +356,7 @@ def test_step_can_be_captured_and_replayed(ctx):
 
 
 # ---- payload arrays that are only 4-byte aligned (views into a larger buffer) take the narrower loads -----------
-@pytest.mark.parametrize("s,W,k", [(64, 64, 32), (64, 8, 32), (32, 16, 32)])
+@pytest.mark.parametrize("s,W,k", [(64, 64, 32), (64, 8, 32), (32, 16, 32), (64, 100, 8), (64, 130, 12), (32, 100, 4)])
 def test_payload_arrays_with_4_byte_alignment(ctx, s, W, k):
     ctx.demo_set_variant(1)
     specs = [synth.TensorSpec("a", 192, 128), synth.TensorSpec("v", 256, 0)]
@@ -423,6 +423,8 @@ def test_s64_decode_worker_counts(ctx, W, pdt):
 # ---- s = 64, other budgets: k a multiple of 4 (16-byte loads of four pairs), of 2 (8-byte loads), odd (one pair) ----
 @pytest.mark.parametrize("W,k", [(64, 16), (64, 8), (64, 4), (64, 2), (37, 12), (100, 6), (32, 64), (5, 32), (21, 20),
                                  (64, 3), (33, 2), (128, 16), (17, 4),
+                                 # one pair per load with more than 64 workers (odd k)
+                                 (200, 3), (100, 1), (400, 5), (65, 31), (40, 51),
                                  # more than 2048 pairs per chunk: streamed in rounds (k a multiple of 4), else generic
                                  (128, 32), (255, 32), (100, 24), (70, 36), (130, 16), (513, 4), (90, 30)])
 @pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
