@@ -64,7 +64,7 @@ def test_random_operating_point(ctx, seed):
     cfg = draw(seed)
     s, k, W, specs = cfg["s"], cfg["k"], cfg["W"], cfg["specs"]
     print({key: (val if key != "specs" else [sp.shape for sp in val]) for key, val in cfg.items()}, flush=True)
-    ctx.demo_set_variant(1)
+    ctx.demo_set_variant(0 if seed % 3 == 2 else 1)   # every third point on the generic kernels
     case = Case(specs, s, k, W=W, seed=300 + seed, grad=cfg["grad"])
     if cfg["unaligned"]:    # payload arrays as views one element into a padded buffer: 4-byte alignment only
         for ti in range(len(specs)):
@@ -99,3 +99,4 @@ def test_random_operating_point(ctx, seed):
         pd = "bf16" if case.x[ti].dtype == torch.bfloat16 else "f32"
         C.check_decode(before["x"][ti], before["idx"][ti][:W], before["val"][ti][:W], lr, cfg["wd"], s, pd,
                        after["x"][ti], phi=cfg["phi"], aggregate_mode=cfg["agg"])
+    ctx.demo_set_variant(1)
