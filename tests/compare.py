@@ -10,7 +10,10 @@ is compared in two stages:
      within 1e-5 of the chunk's largest magnitude.
 Decode: the updated parameters must equal the oracle's bit for bit wherever the
 reconstructed momentum is not within rounding noise of zero (|R| > 1e-5 * max|R| of
-the chunk); inside that band any of sgn in {-1, 0, +1} is accepted.
+the chunk); inside that band any of sgn in {-1, 0, +1} is accepted.  Outside the band the
+parameters are also held against the update line of Algorithm 1 evaluated in plain float64,
+x - eta (sgn(m) + lambda x), rounded once to the storage type: every element within one unit
+in the last place, and the number of elements that differ at all is reported.
 """
 from __future__ import annotations
 
@@ -27,6 +30,12 @@ def chunk_rows(x: np.ndarray, s: int) -> np.ndarray:
     """[nchunks, M] view of a tensor in chunk order."""
     b = O.chunk(np.asarray(x), s)
     return b.reshape(-1, s) if x.ndim == 1 else b.reshape(b.shape[0] * b.shape[1], s * s)
+
+
+def _unchunk_rows(rows: np.ndarray, shape, s: int) -> np.ndarray:
+    """Inverse of chunk_rows for an order-2 tensor of `shape`."""
+    c0, c1 = shape[0] // s, shape[1] // s
+    return O.unchunk(rows.reshape(c0, c1, s, s))
 
 
 def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_REL, alpha32=1.0, grad_scale32=1.0,
@@ -79,6 +88,19 @@ def check_encode(m_prev, g, beta32, s, k, gpu_idx, gpu_val, gpu_m, val_rel=VAL_R
     }
 
 
+def storage_ulp(w: np.ndarray, param_dtype: str) -> np.ndarray:
+    """Spacing of the storage type at |w| (8 significant bits for bfloat16, 24 for float32)."""
+    return np.exp2(np.floor(np.log2(np.maximum(np.abs(w), 1e-300))) - (7 if param_dtype == "bf16" else 23)) + 1e-45
+
+
+def round_once(w: np.ndarray, param_dtype: str) -> np.ndarray:
+    """float64 values rounded once (nearest, ties to even) to the storage type, returned as float64."""
+    if param_dtype != "bf16":
+        return w.astype(np.float32).astype(np.float64)
+    m, e = np.frexp(w)
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
 def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x, phi="sign", aggregate_mode="sum", P=None):
     """x_prev exact parameter values before the call; idx/val the W payloads the GPU consumed.
     phi = "identity": the update is a real number, so the parameters are compared numerically:
@@ -100,10 +122,18 @@ def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x, phi="sign"
                 "max_err_over_lr_Rmax": float(np.max(err / np.maximum(tolR / VAL_REL, 1e-300)))}
     bad = got != want
     stats = {"elements": int(got.size), "mismatch": int(bad.sum()), "in_band": 0}
+    R = chunk_rows(ref["R"], s)
+    band = SIGN_BAND * np.abs(R).max(axis=1, keepdims=True)
+    in_band = np.abs(R) <= band
+    # the update line of Algorithm 1 in plain float64, one rounding to the storage type
+    lr64, wd64 = float(np.float32(lr32)), float(np.float32(wd32))
+    exact = x_prev - lr64 * (np.sign(ref["R"]) + wd64 * x_prev)
+    off = np.abs(got.astype(np.float64) - exact)
+    sure = ~in_band.reshape(-1) if x_prev.ndim == 1 else ~_unchunk_rows(in_band, x_prev.shape, s)
+    assert np.all(off[sure] <= storage_ulp(exact, param_dtype)[sure]), (
+        f"parameters more than one unit in the last place from the float64 update: worst {np.max(off[sure]):.3e}")
+    stats["differs_from_f64_update"] = int(np.sum((got.astype(np.float64) != round_once(exact, param_dtype)) & sure))
     if bad.any():
-        R = chunk_rows(ref["R"], s)
-        band = SIGN_BAND * np.abs(R).max(axis=1, keepdims=True)
-        in_band = np.abs(R) <= band
         badc = chunk_rows(bad, s)
         assert not np.any(badc & ~in_band), (
             f"{int(np.sum(badc & ~in_band))} parameters differ where the sign is not in doubt")

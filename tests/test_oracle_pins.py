@@ -426,3 +426,55 @@ def test_random_orthonormal_basis_exact_recovery_and_parseval():
     e1 = O.encode(np.zeros(32), v, 0.0, s, s, P=P)
     d1 = O.decode(np.zeros(32), e1["idx"][None], e1["val"][None], 1.0, 0.0, s, phi="identity", P=P)
     assert np.allclose(d1["R"], v, atol=1e-12) and np.allclose(e1["m_new"], 0.0, atol=1e-12)
+
+
+# ---- bit-level pins of the float32 update epilogue  t = fma(lambda, x, phi),  x' = fma(-eta, t, x) ---------------
+def _round_fraction_to_f32(fr):
+    """Exact rational -> nearest float32 (ties to even), by integer arithmetic only."""
+    from fractions import Fraction
+    if fr == 0:
+        return np.float32(0.0)
+    sign = -1 if fr < 0 else 1
+    fr = abs(Fraction(fr))
+    e = 0
+    while fr >= 2:
+        fr /= 2
+        e += 1
+    while fr < 1:
+        fr *= 2
+        e -= 1
+    scaled = fr * (1 << 23)                       # significand in [2^23, 2^24)
+    q, r = divmod(scaled.numerator, scaled.denominator)
+    twice = 2 * r
+    if twice > scaled.denominator or (twice == scaled.denominator and (q & 1)):
+        q += 1
+    return np.float32(sign * float(q) * 2.0 ** (e - 23))
+
+
+def test_update_epilogue_bits_with_weight_decay():
+    upd = lambda x, sg, lr, wd: O._sign_update_f32(np.array([x], np.float64), np.array([sg], np.float64), lr, wd)[0]
+    # exact cases: 1 - 0.25 (1 + 0.5*1) = 0.625 ;  -2 - 0.5 (-1 + 0.25*(-2)) = -1.25
+    assert upd(1.0, 1.0, 0.25, 0.5) == np.float32(0.625)
+    assert upd(-2.0, -1.0, 0.5, 0.25) == np.float32(-1.25)
+    # first product-sum lands half-way between two float32 values: 1 + 2^-24 -> 1 (even), then 1 - 0.5 = 0.5
+    assert upd(1.0, 1.0, 0.5, 2.0 ** -24) == np.float32(0.5)
+    # 1 + 3*2^-24 is half-way between 1 + 2^-23 (odd) and 1 + 2^-22 (even) -> 1 + 2^-22;
+    # then 3 - 0.5 (1 + 2^-22) = 2.5 - 2^-23, half-way between 2.5 - 2^-22 and 2.5 (even) -> 2.5
+    assert upd(3.0, 1.0, 0.5, 2.0 ** -24) == np.float32(2.5)
+    # just above the half-way point the sum rounds up: 1 + 2^-24 + 2^-47 (x = 1 + 2^-23 exactly representable)
+    # -> 1 + 2^-23, and x' = x - t = 0 (rounded down to 1 it would leave 2^-23)
+    assert upd(1.0 + 2.0 ** -23, 1.0, 1.0, 2.0 ** -24) == np.float32(0.0)
+    # the products are not rounded on their own (fused): 1 - fl32(1e-3) * 1, one rounding of the exact difference
+    lr32 = float(np.float32(1e-3))
+    assert upd(1.0, 1.0, 1e-3, 0.0) == _round_fraction_to_f32(1 - __import__("fractions").Fraction(lr32))
+    assert upd(1.0, 1.0, 1e-3, 0.0) == np.float32(16760439.0 * 2.0 ** -24)   # exact difference: 16760438.783... * 2^-24
+    # random float32 inputs against exact rational arithmetic with one rounding per fused operation
+    from fractions import Fraction
+    rng = np.random.default_rng(5)
+    for _ in range(400):
+        x = float(np.float32(rng.standard_normal() * 0.02))
+        sg = float(rng.integers(-1, 2))
+        lr, wd = float(np.float32(10.0 ** rng.uniform(-4, -1))), float(np.float32(10.0 ** rng.uniform(-3, 0)))
+        t = _round_fraction_to_f32(Fraction(wd) * Fraction(x) + Fraction(sg))
+        want = _round_fraction_to_f32(-Fraction(lr) * Fraction(float(t)) + Fraction(x))
+        assert upd(x, sg, lr, wd) == want
