@@ -29,9 +29,16 @@
  *     val[W][nchunks][k]; encode writes worker slot 0 of such a buffer.
  *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t
  *     passed as void*, NULL = default stream) and results are valid after that
- *     stream has been synchronised.  The first call that presents a new tensor
- *     list synchronises once to upload its descriptor table; repeating the same
- *     list does not.
+ *     stream has been synchronised.  The context keeps the descriptor tables of the
+ *     8 most recently used tensor lists (a list = the demo_tensor array's contents,
+ *     buffer addresses included, and s); a call with one of them only launches
+ *     kernels.  The first 8 distinct lists each cost one device allocation and one
+ *     blocking copy; after that a new list reuses the memory of the least recently
+ *     used one and its table is written by a small kernel on `hip_stream`, without
+ *     allocation or host synchronisation (the device is synchronised first only if
+ *     the evicted list was last used on another stream or its memory is too small).
+ *     A list first used under stream capture must have been seen before the capture
+ *     began; lists used under capture are never evicted.
  *   - Every function returns DEMO_OK (0) or a negative demo_status.  Arguments
  *     are validated on the host before anything is enqueued; on error nothing
  *     was launched.  No exceptions cross this boundary.
@@ -53,7 +60,8 @@ typedef enum demo_status {
   DEMO_ERR_ARG = -1,         /* null pointer, n < 0, W < 1, k < 1, k > M (M = s or s*s)   */
   DEMO_ERR_SHAPE = -2,       /* rows or cols not a positive multiple of s                 */
   DEMO_ERR_UNSUPPORTED = -3, /* s not in {32,64,128}, unknown dtype, k > DEMO_MAX_K,
-                                more than 2^31 - 1 chunks in a tensor or in a call        */
+                                more than 2^31 - 1 chunks in a tensor or in a call,
+                                cols >= DEMO_MAX_COLS                                      */
   DEMO_ERR_HIP = -4,         /* a HIP runtime call failed (see demo_last_hip_error)       */
   DEMO_ERR_NOMEM = -5        /* host or device allocation for the context's tables failed */
 } demo_status;
@@ -62,6 +70,9 @@ typedef enum demo_dtype { DEMO_F32 = 0, DEMO_BF16 = 1 } demo_dtype;
 
 /* Largest supported sparsity budget per chunk (the paper uses k <= 32). */
 #define DEMO_MAX_K 256
+/* Order-2 tensors must have fewer columns than this: the kernels address the rows of a chunk with 32-bit byte
+ * offsets from the chunk's origin (128 rows of 4-byte elements stay below 2^31). */
+#define DEMO_MAX_COLS (1 << 22)
 
 /* One tensor of the list.  64 bytes, no implicit padding. */
 typedef struct demo_tensor {
@@ -162,29 +173,6 @@ int demo_step_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_hp
  * earlier may still read the matrix it replaces) and copies s*s floats to it.  */
 typedef enum demo_basis { DEMO_BASIS_DCT = 0, DEMO_BASIS_IDENTITY = 1, DEMO_BASIS_GRAM_SCHMIDT = 2 } demo_basis;
 int demo_set_basis(demo_ctx* ctx, int s, int kind, const float* a_host);
-
-/* Kernel timing with HIP events recorded on the call's own stream around each
- * kernel launch.  demo_set_timing(ctx, 1) opens a measurement window (and clears
- * the previous one); every encode / decode / step call then records one event
- * pair per kernel it launches, without synchronising.  demo_last_kernel_ms blocks
- * until the recorded events have completed and returns the average duration in
- * milliseconds over the launches of the window (the 256 most recent at most).
- * which: 0 = encode order-2 kernel, 1 = encode order-1, 2 = decode order-2,
- * 3 = decode order-1.  DEMO_ERR_ARG if nothing was recorded for `which`.  */
-int demo_set_timing(demo_ctx* ctx, int enabled);
-int demo_last_kernel_ms(demo_ctx* ctx, int which, float* ms);
-
-/* Bandwidth probe: one plain streaming copy kernel of nbytes (a multiple of 16, both pointers
- * 16-byte aligned, device memory) from src to dst.  It is what the HBM traffic counters are
- * calibrated with (a copy of known size) and gives the copy bandwidth this GPU reaches; while
- * timing is enabled its duration is recorded in slot 1 of demo_last_kernel_ms.  Not part of the
- * method.  */
-int demo_copy_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes, void* hip_stream);
-
-/* Kernel family used by later calls: 1 (default) = the fastest kernels available
- * for the chunk size, 0 = the generic LDS-staged kernels only (kept selectable so
- * that the two families can be checked against each other).  */
-int demo_set_variant(demo_ctx* ctx, int variant);
 
 /* Static text for a status code; hipGetErrorString of the last failing HIP call. */
 const char* demo_strerror(int status);

@@ -27,7 +27,10 @@ DEMO_BASIS_DCT, DEMO_BASIS_IDENTITY, DEMO_BASIS_GRAM_SCHMIDT = 0, 1, 2
 EXPORTS = [
     "demo_create", "demo_destroy", "demo_payload_elems", "demo_encode", "demo_decode", "demo_step",
     "demo_hparams_default", "demo_encode_ex", "demo_decode_ex", "demo_step_ex", "demo_set_basis",
-    "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_copy_probe", "demo_strerror", "demo_last_hip_error",
+    "demo_strerror", "demo_last_hip_error",
+    # include/demo_debug.h: measurement and test hooks
+    "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_copy_probe", "demo_stream_probe",
+    "demo_debug_set_encode_stage",
 ]
 
 
@@ -84,6 +87,8 @@ def load_library() -> ctypes.CDLL:
     lib.demo_last_kernel_ms.argtypes = [vp, ci, ctypes.POINTER(cf)]
     lib.demo_set_variant.argtypes = [vp, ci]
     lib.demo_copy_probe.argtypes = [vp, vp, vp, i64, vp]
+    lib.demo_stream_probe.argtypes = [vp, vp, vp, i64, ci, vp]
+    lib.demo_debug_set_encode_stage.argtypes = [vp, ci]
     lib.demo_strerror.argtypes = [ci]
     lib.demo_strerror.restype = ctypes.c_char_p
     lib.demo_last_hip_error.argtypes = [vp]
@@ -256,6 +261,15 @@ class Context:
         nbytes = src.numel() * src.element_size()
         assert dst.numel() * dst.element_size() >= nbytes
         self._check(self._lib.demo_copy_probe(self._h, dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)))
+
+    def demo_stream_probe(self, dst: torch.Tensor, src: torch.Tensor, mode: int, stream=None):
+        nbytes = src.numel() * src.element_size()
+        assert dst.numel() * dst.element_size() >= (nbytes if mode != 2 else 65536)
+        self._check(self._lib.demo_stream_probe(self._h, dst.data_ptr(), src.data_ptr(), nbytes, mode,
+                                                _stream_ptr(stream)))
+
+    def demo_debug_set_encode_stage(self, stage: int):
+        self._check(self._lib.demo_debug_set_encode_stage(self._h, stage))
 
     def demo_last_kernel_ms(self, which: int) -> float:
         ms = ctypes.c_float(0)

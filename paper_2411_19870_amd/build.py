@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libdemo.so")
-SOURCES = [os.path.join(PKG, "csrc", f) for f in ("demo_kernels.hip", "demo_enc64.hip", "demo_enc64d.hip", "demo_dec64.hip", "demo_dec32.hip", "demo_wg128.hip", "demo_api.cpp")]
+SOURCES = [os.path.join(PKG, "csrc", f) for f in ("demo_kernels.hip", "demo_enc64.hip", "demo_enc64d.hip", "demo_dec64.hip", "demo_dec32.hip", "demo_wg128.hip", "demo_noalloc.hip", "demo_api.cpp")]
 
 
 def build(verbose: bool = True, out: str = LIB, defines=(), extra_flags=()) -> str:

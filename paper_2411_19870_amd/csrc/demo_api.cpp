@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/demo.h: argument validation,
 // context (DCT basis tables, cached device descriptor tables), dispatch.
 #include "demo.h"
+#include "demo_debug.h"
 #include "demo_internal.h"
 
 #include <cmath>
@@ -39,7 +40,10 @@ struct TableGroup {
 
 // One cached descriptor upload: the host bytes it was built from and the device copy.
 struct TableCache {
-  std::vector<char> key;      // raw demo_tensor bytes + s
+  std::vector<char> key;      // raw demo_tensor bytes + s (empty: the slot holds nothing valid)
+  hipStream_t last_stream = nullptr;   // stream of the last call that used the tables
+  bool many_streams = false;  // ... and whether calls on several streams have used them
+  bool pinned = false;        // used under stream capture: a graph holds the table's address, never evicted
   void* dev = nullptr;        // per group [TensorDev x n][int32 x (n+1)][queue][tile tables], then the order-1 tables
   size_t dev_bytes = 0;
   std::vector<TableGroup> groups;   // order-2 tensors by (gradient dtype, parameter dtype, tileable at s = 32)
@@ -64,6 +68,7 @@ struct demo_ctx {
   int ev_count[kNumTimers] = {};               // launches recorded since timing was enabled
   hipError_t last_hip = hipSuccess;
   int variant = 1;            // 0 = generic kernels only
+  int enc_stage = 0;          // 1..3: cut-down copies of the s = 64 encode kernel (time attribution)
 };
 
 namespace {
@@ -83,6 +88,7 @@ int check_shape(int64_t rows, int64_t cols, int s, int k) {
   if (k < 1) return DEMO_ERR_ARG;
   if (rows <= 0 || cols < 0) return DEMO_ERR_SHAPE;
   if (rows % s != 0 || cols % s != 0) return DEMO_ERR_SHAPE;
+  if (cols >= DEMO_MAX_COLS) return DEMO_ERR_UNSUPPORTED;   // 32-bit row offsets inside a chunk
   const int64_t M = cols == 0 ? (int64_t)s : (int64_t)s * s;
   if (k > M) return DEMO_ERR_ARG;
   if (k > DEMO_MAX_K) return DEMO_ERR_UNSUPPORTED;
@@ -137,9 +143,8 @@ int bind_device(demo_ctx* ctx) {
   return DEMO_OK;
 }
 
-// Orthonormal DCT-II matrix P[u][n] = c_u cos(pi (2n+1) u / (2s)), evaluated in
-// double precision and rounded once to float32 (Sec. 2.1 "Blockwise Linear
-// Projection": the matrices are precomputed once and shared by all tensors).
+// One device allocation filled from the host (Sec. 2.1 "Blockwise Linear Projection": the matrices are
+// precomputed once and shared by all tensors).
 int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
   hipError_t e = hipMalloc(reinterpret_cast<void**>(dev), host.size() * sizeof(float));
   if (e != hipSuccess) return fail_hip(ctx, e);
@@ -152,6 +157,39 @@ int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
   return DEMO_OK;
 }
 
+// Host copies of the tables of one chunk size: the orthonormal DCT-II matrix P[u][n] = c_u cos(pi (2n+1) u / (2s))
+// evaluated in double precision and rounded once to float32, and the fragment tables the wavefront kernels read.
+struct HostBasis {
+  std::vector<float> P, enc64, dec64, enc32, dec32;
+};
+
+void build_host_basis(int s, HostBasis* hb) {
+  std::vector<double> P((size_t)s * s);
+  const double pi = 3.14159265358979323846;
+  for (int u = 0; u < s; ++u) {
+    const double cu = u == 0 ? std::sqrt(1.0 / s) : std::sqrt(2.0 / s);
+    for (int n = 0; n < s; ++n) P[(size_t)u * s + n] = cu * std::cos(pi * (2.0 * n + 1.0) * u / (2.0 * s));
+  }
+  hb->P.assign(P.begin(), P.end());   // one rounding to float32
+  if (s == 64) {
+    hb->enc64.resize(demo::kEnc64TableFloats);
+    hb->dec64.resize(demo::kDec64TableFloats);
+    demo::build_enc64_tables(P.data(), hb->enc64.data());
+    demo::build_dec64_tables(P.data(), hb->dec64.data());
+  }
+  if (s == 32) {
+    // 64 x 64 block-diagonal basis diag(P32, P32): a wavefront tile holds 2 x 2 chunks
+    std::vector<double> B2(64 * 64, 0.0);
+    for (int blk = 0; blk < 2; ++blk)
+      for (int u = 0; u < 32; ++u)
+        for (int i = 0; i < 32; ++i) B2[(size_t)(32 * blk + u) * 64 + 32 * blk + i] = P[(size_t)u * 32 + i];
+    hb->enc32.resize(demo::kEnc64dTableFloats);
+    demo::build_enc64d_tables(B2.data(), hb->enc32.data());
+    hb->dec32.resize(demo::kDec32TableFloats);
+    demo::build_dec32_tables(P.data(), hb->dec32.data());
+  }
+}
+
 int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   for (const BasisTable& b : ctx->bases)
     if (b.s == s) {
@@ -161,62 +199,54 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
                           : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
       return DEMO_OK;
     }
-  std::vector<double> P((size_t)s * s);
-  const double pi = 3.14159265358979323846;
-  for (int u = 0; u < s; ++u) {
-    const double cu = u == 0 ? std::sqrt(1.0 / s) : std::sqrt(2.0 / s);
-    for (int n = 0; n < s; ++n) P[(size_t)u * s + n] = cu * std::cos(pi * (2.0 * n + 1.0) * u / (2.0 * s));
-  }
-  std::vector<float> host(P.begin(), P.end());   // one rounding to float32
+  HostBasis hb;
+  build_host_basis(s, &hb);
   BasisTable b;
   b.s = s;
-  int rc = upload(ctx, host, &b.dev);
+  int rc = upload(ctx, hb.P, &b.dev);
   if (rc != DEMO_OK) return rc;
-  if (s == 64) {
-    std::vector<float> et(demo::kEnc64TableFloats), dt(demo::kDec64TableFloats);
-    demo::build_enc64_tables(P.data(), et.data());
-    demo::build_dec64_tables(P.data(), dt.data());
-    if ((rc = upload(ctx, et, &b.enc64)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
-    if ((rc = upload(ctx, dt, &b.dec64)) != DEMO_OK) { (void)hipFree(b.dev); (void)hipFree(b.enc64); return rc; }
-  }
-  if (s == 32) {
-    // 64 x 64 block-diagonal basis diag(P32, P32): a wavefront tile holds 2 x 2 chunks
-    std::vector<double> B2(64 * 64, 0.0);
-    for (int blk = 0; blk < 2; ++blk)
-      for (int u = 0; u < 32; ++u)
-        for (int i = 0; i < 32; ++i) B2[(size_t)(32 * blk + u) * 64 + 32 * blk + i] = P[(size_t)u * 32 + i];
-    std::vector<float> et(demo::kEnc64dTableFloats);
-    demo::build_enc64d_tables(B2.data(), et.data());
-    if ((rc = upload(ctx, et, &b.enc32)) != DEMO_OK) { (void)hipFree(b.dev); return rc; }
-    std::vector<float> dt(demo::kDec32TableFloats);
-    demo::build_dec32_tables(P.data(), dt.data());
-    if ((rc = upload(ctx, dt, &b.dec32)) != DEMO_OK) { (void)hipFree(b.dev); (void)hipFree(b.enc32); return rc; }
-  }
+  auto drop = [&]() {
+    (void)hipFree(b.dev);
+    if (b.enc64) (void)hipFree(b.enc64);
+    if (b.dec64) (void)hipFree(b.dec64);
+    if (b.enc32) (void)hipFree(b.enc32);
+    if (b.dec32) (void)hipFree(b.dec32);
+  };
+  if (!hb.enc64.empty() && (rc = upload(ctx, hb.enc64, &b.enc64)) != DEMO_OK) { drop(); return rc; }
+  if (!hb.dec64.empty() && (rc = upload(ctx, hb.dec64, &b.dec64)) != DEMO_OK) { drop(); return rc; }
+  if (!hb.enc32.empty() && (rc = upload(ctx, hb.enc32, &b.enc32)) != DEMO_OK) { drop(); return rc; }
+  if (!hb.dec32.empty() && (rc = upload(ctx, hb.dec32, &b.dec32)) != DEMO_OK) { drop(); return rc; }
   ctx->bases.push_back(b);
   *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
   return DEMO_OK;
 }
 
-// Find or build the device descriptor tables of a tensor list.
-int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** out) {
-  const size_t raw = sizeof(demo_tensor) * (size_t)n;
-  std::vector<char> key(raw + sizeof(int));
-  std::memcpy(key.data(), t, raw);
-  std::memcpy(key.data() + raw, &s, sizeof(int));
-  for (TableCache& tc : ctx->tables) {
-    if (tc.key.size() == key.size() && std::memcmp(tc.key.data(), key.data(), key.size()) == 0) {
-      tc.last_use = ++ctx->use_counter;
-      *out = &tc;
-      return DEMO_OK;
-    }
-  }
+// Host image of the device tables of one tensor list.  `head` holds everything the kernels read before they
+// write: per group of order-2 tensors [TensorDev x n][int32 prefix x (n+1)][queue header: count, ticket, 0, 0]
+// [TensorDev x n in 64 x 64 tiles][int32 prefix], then the order-1 tables.  The queue lists (one int32 per order-2
+// chunk) follow the head on the device and need no initial contents.
+struct TableImage {
+  struct Group {
+    size_t o_d2 = 0, o_p2 = 0, o_wl = 0, o_d2t = 0, o_p2t = 0, o_list = 0;
+    int32_t n = 0, total = 0, n_t = 0, total_t = 0;
+    uint32_t mix = 0;
+  };
+  std::vector<char> head;
+  std::vector<Group> groups;
+  size_t o_d1 = 0, o_p1 = 0;
+  int32_t n1 = 0, total1 = 0;
+  uint32_t mix1 = 0;
+  size_t total_bytes = 0;      // head + queue lists
+  int64_t chunks2 = 0;         // order-2 chunks of the whole list
+};
+
+void build_image(const demo_tensor* t, int n, int s, TableImage* img) {
   struct HostGroup {
     uint32_t dt = 0;   // (gradient is bf16) | (parameter is bf16) << 1 | (s = 32 and not made of 64 x 64 tiles) << 2
     std::vector<TensorDev> d2, d2t;
     std::vector<int32_t> p2{0}, p2t{0};
     bool tiles_ok = true;
     uint32_t mix = 0;
-    size_t o_d2 = 0, o_p2 = 0, o_wl = 0, o_d2t = 0, o_p2t = 0;
   };
   std::vector<HostGroup> hg;
   std::vector<TensorDev> d1;
@@ -269,76 +299,137 @@ int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, TableCache** o
     }
   }
   auto align16 = [](size_t x) { return (x + 15) & ~(size_t)15; };
+  img->groups.clear();
   size_t off = 0;
   for (HostGroup& g : hg) {
     if (!g.tiles_ok) { g.d2t.clear(); g.p2t.assign(1, 0); }
-    g.o_d2 = off;
-    g.o_p2 = align16(g.o_d2 + g.d2.size() * sizeof(TensorDev));
-    g.o_wl = align16(g.o_p2 + g.p2.size() * sizeof(int32_t));   // count, ticket, pad, pad, list[]
-    g.o_d2t = align16(g.o_wl + (4 + (size_t)g.p2.back()) * sizeof(int32_t));
-    g.o_p2t = align16(g.o_d2t + g.d2t.size() * sizeof(TensorDev));
-    off = align16(g.o_p2t + g.p2t.size() * sizeof(int32_t));
+    TableImage::Group ig;
+    ig.o_d2 = off;
+    ig.o_p2 = align16(ig.o_d2 + g.d2.size() * sizeof(TensorDev));
+    ig.o_wl = align16(ig.o_p2 + g.p2.size() * sizeof(int32_t));   // count, ticket, pad, pad
+    ig.o_d2t = align16(ig.o_wl + 4 * sizeof(int32_t));
+    ig.o_p2t = align16(ig.o_d2t + g.d2t.size() * sizeof(TensorDev));
+    off = align16(ig.o_p2t + g.p2t.size() * sizeof(int32_t));
+    ig.n = (int32_t)g.d2.size();
+    ig.total = g.p2.back();
+    ig.n_t = (int32_t)g.d2t.size();
+    ig.total_t = g.p2t.back();
+    ig.mix = g.mix;
+    img->groups.push_back(ig);
   }
-  const size_t o_d1 = off;
-  const size_t o_p1 = align16(o_d1 + d1.size() * sizeof(TensorDev));
-  const size_t total = align16(o_p1 + p1.size() * sizeof(int32_t));
-  std::vector<char> host(total, 0);   // the queues start out zero-filled
-  for (const HostGroup& g : hg) {
-    std::memcpy(host.data() + g.o_d2, g.d2.data(), g.d2.size() * sizeof(TensorDev));
-    std::memcpy(host.data() + g.o_p2, g.p2.data(), g.p2.size() * sizeof(int32_t));
-    if (!g.d2t.empty()) std::memcpy(host.data() + g.o_d2t, g.d2t.data(), g.d2t.size() * sizeof(TensorDev));
-    std::memcpy(host.data() + g.o_p2t, g.p2t.data(), g.p2t.size() * sizeof(int32_t));
+  img->o_d1 = off;
+  img->o_p1 = align16(img->o_d1 + d1.size() * sizeof(TensorDev));
+  const size_t head_bytes = align16(img->o_p1 + p1.size() * sizeof(int32_t));
+  img->n1 = (int32_t)d1.size();
+  img->total1 = p1.back();
+  img->mix1 = mix1;
+  img->head.assign(head_bytes, 0);   // the queue headers start out zero
+  img->chunks2 = 0;
+  off = head_bytes;
+  for (size_t gi = 0; gi < hg.size(); ++gi) {
+    const HostGroup& g = hg[gi];
+    TableImage::Group& ig = img->groups[gi];
+    std::memcpy(img->head.data() + ig.o_d2, g.d2.data(), g.d2.size() * sizeof(TensorDev));
+    std::memcpy(img->head.data() + ig.o_p2, g.p2.data(), g.p2.size() * sizeof(int32_t));
+    if (!g.d2t.empty()) std::memcpy(img->head.data() + ig.o_d2t, g.d2t.data(), g.d2t.size() * sizeof(TensorDev));
+    std::memcpy(img->head.data() + ig.o_p2t, g.p2t.data(), g.p2t.size() * sizeof(int32_t));
+    ig.o_list = off;
+    off = align16(off + (size_t)ig.total * sizeof(int32_t));
+    img->chunks2 += ig.total;
   }
-  if (!d1.empty()) std::memcpy(host.data() + o_d1, d1.data(), d1.size() * sizeof(TensorDev));
-  std::memcpy(host.data() + o_p1, p1.data(), p1.size() * sizeof(int32_t));
+  if (!d1.empty()) std::memcpy(img->head.data() + img->o_d1, d1.data(), d1.size() * sizeof(TensorDev));
+  std::memcpy(img->head.data() + img->o_p1, p1.data(), p1.size() * sizeof(int32_t));
+  img->total_bytes = off;
+}
 
-  TableCache* slot = nullptr;
-  if ((int)ctx->tables.size() < kMaxCachedTables) {
-    ctx->tables.emplace_back();
-    slot = &ctx->tables.back();
-  } else {
-    slot = &ctx->tables[0];
-    for (TableCache& tc : ctx->tables)
-      if (tc.last_use < slot->last_use) slot = &tc;
-    // the evicted table may still be read by kernels in flight
-    hipError_t e = hipDeviceSynchronize();
-    if (e != hipSuccess) return fail_hip(ctx, e);
-  }
-  if (slot->dev_bytes < total) {
-    if (slot->dev) (void)hipFree(slot->dev);
-    slot->dev = nullptr;
-    slot->dev_bytes = 0;
-    hipError_t e = hipMalloc(&slot->dev, total);
-    if (e != hipSuccess) { slot->key.clear(); return fail_hip(ctx, e); }
-    slot->dev_bytes = total;
-  }
-  // blocking copy: the table is complete before any launch on any stream reads it
-  hipError_t e = hipMemcpy(slot->dev, host.data(), total, hipMemcpyHostToDevice);
-  if (e != hipSuccess) { slot->key.clear(); return fail_hip(ctx, e); }
-  char* base = static_cast<char*>(slot->dev);
-  slot->groups.clear();
-  for (const HostGroup& g : hg) {
+// Views of an image that lives at `base` on the device.
+void bind_image(const TableImage& img, char* base, std::vector<TableGroup>* groups, TableView* tv1) {
+  groups->clear();
+  for (const TableImage::Group& g : img.groups) {
     TableGroup tg;
     tg.tv2.descs = reinterpret_cast<const TensorDev*>(base + g.o_d2);
     tg.tv2.prefix = reinterpret_cast<const int32_t*>(base + g.o_p2);
-    tg.tv2.n = (int32_t)g.d2.size();
-    tg.tv2.total_chunks = g.p2.back();
+    tg.tv2.n = g.n;
+    tg.tv2.total_chunks = g.total;
     tg.tv2.dtypes = g.mix;
     tg.tv2t.descs = reinterpret_cast<const TensorDev*>(base + g.o_d2t);
     tg.tv2t.prefix = reinterpret_cast<const int32_t*>(base + g.o_p2t);
-    tg.tv2t.n = (int32_t)g.d2t.size();
-    tg.tv2t.total_chunks = g.p2t.back();
+    tg.tv2t.n = g.n_t;
+    tg.tv2t.total_chunks = g.total_t;
     tg.tv2t.dtypes = g.mix;
     int32_t* wl = reinterpret_cast<int32_t*>(base + g.o_wl);
-    tg.wl = demo::Worklist{wl, wl + 1, wl + 4};
-    slot->groups.push_back(tg);
+    tg.wl = demo::Worklist{wl, wl + 1, reinterpret_cast<int32_t*>(base + g.o_list)};
+    groups->push_back(tg);
   }
-  slot->tv1.descs = reinterpret_cast<const TensorDev*>(base + o_d1);
-  slot->tv1.prefix = reinterpret_cast<const int32_t*>(base + o_p1);
-  slot->tv1.n = (int32_t)d1.size();
-  slot->tv1.total_chunks = p1.back();
-  slot->tv1.dtypes = mix1;
+  tv1->descs = reinterpret_cast<const TensorDev*>(base + img.o_d1);
+  tv1->prefix = reinterpret_cast<const int32_t*>(base + img.o_p1);
+  tv1->n = img.n1;
+  tv1->total_chunks = img.total1;
+  tv1->dtypes = img.mix1;
+}
+
+// Find or build the device descriptor tables of a tensor list.  A table, once written, is never changed while its
+// list stays cached (a captured graph may hold its address): a list seen before costs nothing; a new list takes a
+// free or the least recently used slot.  While slots are free that is one allocation and one blocking copy; once
+// all are in use the evicted slot's memory is reused when it is large enough, and the new table is then written
+// by a small kernel on the call's stream, with no allocation and no host synchronisation (a caller whose buffers
+// move every step ends up here).  Slots used under stream capture are never evicted.
+int get_tables(demo_ctx* ctx, const demo_tensor* t, int n, int s, hipStream_t st, TableCache** out) {
+  const size_t raw = sizeof(demo_tensor) * (size_t)n;
+  std::vector<char> key(raw + sizeof(int));
+  std::memcpy(key.data(), t, raw);
+  std::memcpy(key.data() + raw, &s, sizeof(int));
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cap) != hipSuccess) cap = hipStreamCaptureStatusNone;
+  const bool capturing = cap == hipStreamCaptureStatusActive;
+  for (TableCache& tc : ctx->tables) {
+    if (tc.key.size() == key.size() && std::memcmp(tc.key.data(), key.data(), key.size()) == 0) {
+      tc.last_use = ++ctx->use_counter;
+      tc.many_streams = tc.many_streams || tc.last_stream != st;
+      tc.last_stream = st;
+      tc.pinned = tc.pinned || capturing;
+      *out = &tc;
+      return DEMO_OK;
+    }
+  }
+  TableImage img;
+  build_image(t, n, s, &img);
+  TableCache* slot = nullptr;
+  int unpinned = 0;
+  for (const TableCache& tc : ctx->tables) unpinned += tc.pinned ? 0 : 1;
+  if (unpinned < kMaxCachedTables) {
+    ctx->tables.emplace_back();
+    slot = &ctx->tables.back();
+  } else {
+    for (TableCache& tc : ctx->tables)
+      if (!tc.pinned && (slot == nullptr || tc.last_use < slot->last_use)) slot = &tc;
+    // kernels of the evicted list's last call may still read its table: later work on the same stream is ordered
+    // behind them, any other stream is not
+    if (slot->last_stream != st || slot->many_streams || slot->dev_bytes < img.total_bytes) {
+      hipError_t e = hipDeviceSynchronize();
+      if (e != hipSuccess) return fail_hip(ctx, e);
+    }
+  }
+  slot->key.clear();
+  if (slot->dev_bytes >= img.total_bytes) {
+    hipError_t e = demo::device_write(slot->dev, img.head.data(), img.head.size(), st);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+  } else {
+    if (slot->dev) (void)hipFree(slot->dev);
+    slot->dev = nullptr;
+    slot->dev_bytes = 0;
+    hipError_t e = hipMalloc(&slot->dev, img.total_bytes);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+    slot->dev_bytes = img.total_bytes;
+    // blocking copy: the table is complete before any launch on any stream reads it
+    e = hipMemcpy(slot->dev, img.head.data(), img.head.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(ctx, e);
+  }
+  bind_image(img, static_cast<char*>(slot->dev), &slot->groups, &slot->tv1);
   slot->key.swap(key);
+  slot->last_stream = st;
+  slot->many_streams = false;
+  slot->pinned = capturing;
   slot->last_use = ++ctx->use_counter;
   *out = slot;
   return DEMO_OK;
@@ -368,22 +459,28 @@ int timer_end(demo_ctx* ctx, int which, hipStream_t st) {
   return DEMO_OK;
 }
 
-int run_encode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, const demo_hparams& hp, int s, int k,
-               hipStream_t st) {
-  demo::EncodeArgs a{hp.beta, hp.grad_scale, hp.alpha, k, basis.dct ? 1 : 0};
+int run_encode(demo_ctx* ctx, const std::vector<TableGroup>& groups, const TableView& tv1,
+               const demo::BasisTables& basis, const demo_hparams& hp, int s, int k, hipStream_t st) {
+  demo::EncodeArgs a{hp.beta, hp.grad_scale, hp.alpha, k, basis.dct ? 1 : 0, ctx->enc_stage};
+  if (ctx->enc_stage != 0) {
+    // the cut-down kernels exist for the s = 64 DCT kernel with bfloat16 gradients only
+    if (s != 64 || !basis.dct || ctx->variant != 1 || k > demo::kFast64MaxK) return DEMO_ERR_UNSUPPORTED;
+    for (const TableGroup& g : groups)
+      if (g.tv2.dtypes & 2u) return DEMO_ERR_UNSUPPORTED;
+  }
   int rc;
-  if (!tc->groups.empty()) {   // the timer brackets the launches of all groups
+  if (!groups.empty()) {   // the timer brackets the launches of all groups
     if ((rc = timer_begin(ctx, 0, st)) != DEMO_OK) return rc;
-    for (const TableGroup& g : tc->groups) {
+    for (const TableGroup& g : groups) {
       hipError_t e = demo::launch_encode2d(g.tv2, g.tv2t.n > 0 ? &g.tv2t : nullptr, basis, s, a, g.wl, ctx->num_cus,
                                            ctx->variant, st);
       if (e != hipSuccess) return fail_hip(ctx, e);
     }
     if ((rc = timer_end(ctx, 0, st)) != DEMO_OK) return rc;
   }
-  if (tc->tv1.total_chunks > 0) {
+  if (tv1.total_chunks > 0) {
     if ((rc = timer_begin(ctx, 1, st)) != DEMO_OK) return rc;
-    hipError_t e = demo::launch_encode1d(tc->tv1, basis.basis, s, a, st);
+    hipError_t e = demo::launch_encode1d(tv1, basis.basis, s, a, st);
     if (e != hipSuccess) return fail_hip(ctx, e);
     if ((rc = timer_end(ctx, 1, st)) != DEMO_OK) return rc;
   }
@@ -429,11 +526,12 @@ int check_hparams(const demo_hparams* hp, int need, int W) {
   return DEMO_OK;
 }
 
-int prepare(demo_ctx* ctx, const demo_tensor* t, int n, int s, demo::BasisTables* basis, TableCache** tc) {
+int prepare(demo_ctx* ctx, const demo_tensor* t, int n, int s, hipStream_t st, demo::BasisTables* basis,
+            TableCache** tc) {
   int rc = bind_device(ctx);
   if (rc != DEMO_OK) return rc;
   if ((rc = get_basis(ctx, s, basis)) != DEMO_OK) return rc;
-  return get_tables(ctx, t, n, s, tc);
+  return get_tables(ctx, t, n, s, st, tc);
 }
 
 }  // namespace
@@ -499,8 +597,8 @@ int demo_encode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_
   if ((rc = check_hparams(hp, NEED_ENCODE, 1)) != DEMO_OK || n == 0) return rc;
   demo::BasisTables basis{};
   TableCache* tc = nullptr;
-  if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
-  return run_encode(ctx, tc, basis, *hp, s, k, static_cast<hipStream_t>(hip_stream));
+  if ((rc = prepare(ctx, tensors, n, s, static_cast<hipStream_t>(hip_stream), &basis, &tc)) != DEMO_OK) return rc;
+  return run_encode(ctx, tc->groups, tc->tv1, basis, *hp, s, k, static_cast<hipStream_t>(hip_stream));
 }
 
 int demo_decode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, const demo_hparams* hp, int s, int k,
@@ -511,7 +609,7 @@ int demo_decode_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, int W, cons
   if ((rc = check_hparams(hp, NEED_DECODE, W)) != DEMO_OK || n == 0) return rc;
   demo::BasisTables basis{};
   TableCache* tc = nullptr;
-  if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
+  if ((rc = prepare(ctx, tensors, n, s, static_cast<hipStream_t>(hip_stream), &basis, &tc)) != DEMO_OK) return rc;
   return run_decode(ctx, tc, basis, W, *hp, s, k, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -522,9 +620,9 @@ int demo_step_ex(demo_ctx* ctx, const demo_tensor* tensors, int n, const demo_hp
   if ((rc = check_hparams(hp, NEED_ENCODE | NEED_DECODE, 1)) != DEMO_OK || n == 0) return rc;
   demo::BasisTables basis{};
   TableCache* tc = nullptr;
-  if ((rc = prepare(ctx, tensors, n, s, &basis, &tc)) != DEMO_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if ((rc = run_encode(ctx, tc, basis, *hp, s, k, st)) != DEMO_OK) return rc;
+  if ((rc = prepare(ctx, tensors, n, s, st, &basis, &tc)) != DEMO_OK) return rc;
+  if ((rc = run_encode(ctx, tc->groups, tc->tv1, basis, *hp, s, k, st)) != DEMO_OK) return rc;
   return run_decode(ctx, tc, basis, 1, *hp, s, k, st);
 }
 
@@ -584,6 +682,26 @@ int demo_copy_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes, v
   hipError_t e = demo::launch_copy_probe(src, dst, (size_t)nbytes, ctx->num_cus, st);
   if (e != hipSuccess) return fail_hip(ctx, e);
   return timer_end(ctx, 1, st);
+}
+
+int demo_stream_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes, int mode, void* hip_stream) {
+  if (ctx == nullptr || dst == nullptr || src == nullptr || nbytes < 0 || (nbytes & 15) != 0) return DEMO_ERR_ARG;
+  if (((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) != 0) return DEMO_ERR_ARG;
+  if (mode < 0 || mode > 4) return DEMO_ERR_ARG;
+  if (nbytes == 0) return DEMO_OK;
+  int rc = bind_device(ctx);
+  if (rc != DEMO_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if ((rc = timer_begin(ctx, 1, st)) != DEMO_OK) return rc;
+  hipError_t e = demo::launch_stream_probe(src, dst, (size_t)nbytes, mode, ctx->num_cus, st);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  return timer_end(ctx, 1, st);
+}
+
+int demo_debug_set_encode_stage(demo_ctx* ctx, int stage) {
+  if (ctx == nullptr || stage < 0 || stage > 3) return DEMO_ERR_ARG;
+  ctx->enc_stage = stage;
+  return DEMO_OK;
 }
 
 int demo_set_basis(demo_ctx* ctx, int s, int kind, const float* a_host) {

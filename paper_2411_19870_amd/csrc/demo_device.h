@@ -243,6 +243,13 @@ static __device__ unsigned long long demo_phase_clocks[16];   // one copy per tr
     if ((threadIdx.x & 63) == 0)                                                           \
       for (int ph_i = 0; ph_i < 8; ++ph_i) atomicAdd(&demo_phase_clocks[(off) + ph_i], ph_acc[ph_i]); \
   } while (0)
+#elif defined(DEMO_PHASE_MARKS)
+// -DDEMO_PHASE_MARKS: the phase boundaries only leave a comment in the generated assembly (for counting the
+// instructions of each phase in a -save-temps listing); the code is the ordinary build's up to scheduling
+#define DEMO_PHASE_GETTER(name)
+#define DEMO_PHASE_DECL
+#define DEMO_PHASE(i) asm volatile("; PHASE_MARK " #i)
+#define DEMO_PHASE_FLUSH(off)
 #else
 #define DEMO_PHASE_GETTER(name)
 #define DEMO_PHASE_DECL

@@ -88,7 +88,10 @@ __device__ __forceinline__ Bfly butterfly(float x0, float x1, float x2, float x3
   return Bfly{e0 + e1, e0 - e1, x0 - x3, x1 - x2};
 }
 
-template <bool GBF16>   // gradient dtype of every tensor in the table
+// STAGE 0 is the kernel.  STAGE 1..3 are cut-down copies for time attribution (they do not encode): 1 = the
+// memory stream only (loads of g and m with the prefetch, momentum update, store of m, k payload pairs per chunk),
+// 2 = stage 1 plus the two products, 3 = stage 2 plus top-k and the payload (everything but the reconstruction).
+template <bool GBF16, int STAGE>   // gradient dtype of every tensor in the table
 __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                EncodeArgs args, Worklist wl) {
   extern __shared__ float lds[];
@@ -220,6 +223,16 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(0);
+    bool skip = false;
+    if constexpr (STAGE == 1) {
+      fetch_m(nxt);
+      if (GBF16) fetch_g(nxt);
+      if (lane < k) {
+        const int64_t po = (int64_t)cc * k + lane;
+        store_guarded(as_global(cur.idx) + po, (int32_t)lane);
+        store_guarded(as_global(cur.val) + po, D[0][0][0]);
+      }
+    } else {
     // ---- product 1: C1[e][t] rows j = 4 chi(4g+r) + e, cols u = freq(t, c) ------------------------
     f32x4 C1[4][4];
 #pragma unroll
@@ -282,6 +295,18 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(2);
+    if constexpr (STAGE == 2) {
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) asm volatile("" ::"v"(C2[vt][tt]));
+      if (GBF16) fetch_g(nxt);
+      if (lane < k) {
+        const int64_t po = (int64_t)cc * k + lane;
+        store_guarded(as_global(cur.idx) + po, (int32_t)lane);
+        store_guarded(as_global(cur.val) + po, C2[0][0][0]);
+      }
+    } else {
     // ---- top-k inside the wavefront ------------------------------------------------------------
     // (1) a lower bound of the k-th largest magnitude: the k-th largest of the 64 per-lane maxima,
     //     resolved to its upper 16 bits
@@ -327,7 +352,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     }
     const bool overflow = ncand > E64_CAP;   // many (near-)equal magnitudes at the threshold
     const bool all_zero = overflow && __ballot(lm != 0u) == 0;
-    const bool skip = overflow && !all_zero;
+    skip = overflow && !all_zero;
     if (skip) {
       // leave the chunk untouched and queue it for the exact workgroup kernel that runs next
       if (lane == 0) store_guarded(&wl.list[atomicAdd(wl.count, 1)], chunk);
@@ -420,7 +445,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     //        D[i0] += ee+eo+o0, D[31-i0] += ee-eo+o1, D[32+i0] += ee-eo-o1, D[63-i0] += ee+eo-o0.
     //      MFMA row m = 4g + r of a compact tile is the base i0 = kappa(m) = 4r + g, i.e. component s = r of D.
     //      The classes are done one after the other so that at most two compact accumulators are alive.
-    if (!skip) {
+    if (!skip && STAGE == 0) {
       {
         f32x4 Ree[4];
 #pragma unroll
@@ -496,6 +521,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       }
     }
 
+    }   // STAGE != 2
+    }   // STAGE != 1
     if (!GBF16) fetch_g(nxt);   // 64 registers: requested once the compact accumulators are dead
     DEMO_PHASE(6);
     // ---- store the residual momentum -------------------------------------------------------------
@@ -513,18 +540,18 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   DEMO_PHASE_FLUSH(0);
 }
 
-template <bool GBF16>
+template <bool GBF16, int STAGE>
 static hipError_t launch_enc_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                     int64_t grid, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_wave64<GBF16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_wave64<GBF16, STAGE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, E64_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(encode2d_wave64<GBF16>, dim3((unsigned)grid), dim3(E64_THREADS), E64_LDS_BYTES, stream, tv, tables,
-                     a, wl);
+  hipLaunchKernelGGL((encode2d_wave64<GBF16, STAGE>), dim3((unsigned)grid), dim3(E64_THREADS), E64_LDS_BYTES, stream, tv,
+                     tables, a, wl);
   return hipGetLastError();
 }
 
@@ -533,8 +560,17 @@ hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, cons
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tv.total_chunks + DEMO_RUN - 1) / DEMO_RUN;   // few items: one run per workgroup, spread over the CUs
   if (grid > max_grid) grid = max_grid;
-  return grad_bf16 ? launch_enc_wave64<true>(tv, tables, a, wl, grid, stream)
-                   : launch_enc_wave64<false>(tv, tables, a, wl, grid, stream);
+  if (a.stage != 0) {   // time attribution only (bfloat16 gradients)
+    if (!grad_bf16) return hipErrorInvalidValue;
+    switch (a.stage) {
+      case 1: return launch_enc_wave64<true, 1>(tv, tables, a, wl, grid, stream);
+      case 2: return launch_enc_wave64<true, 2>(tv, tables, a, wl, grid, stream);
+      case 3: return launch_enc_wave64<true, 3>(tv, tables, a, wl, grid, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  return grad_bf16 ? launch_enc_wave64<true, 0>(tv, tables, a, wl, grid, stream)
+                   : launch_enc_wave64<false, 0>(tv, tables, a, wl, grid, stream);
 }
 
 }  // namespace demo

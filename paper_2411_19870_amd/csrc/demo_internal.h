@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 // Largest sparsity budget per chunk the kernels accept (equals DEMO_MAX_K of the public header).
 #define DEMO_MAXK_INTERNAL 256
@@ -48,6 +49,7 @@ struct EncodeArgs {
   float alpha;        // m <- m - alpha*IDCT(kept)
   int k;
   int mirror;         // the projection matrix is the DCT (mirror-folded products allowed); set by the launch wrappers
+  int stage;          // 0 = encode; 1..3 = cut-down copies of the s = 64 kernel for time attribution (debug interface)
 };
 
 struct DecodeArgs {
@@ -89,7 +91,11 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
 hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
                            hipStream_t stream);
 
+// demo_noalloc.hip: stream-ordered host-to-device write through kernel arguments (no runtime copy, no allocation)
+hipError_t device_write(void* dst, const void* host, size_t nbytes, hipStream_t stream);
+
 hipError_t launch_copy_probe(const void* src, void* dst, size_t nbytes, int num_cus, hipStream_t stream);
+hipError_t launch_stream_probe(const void* src, void* dst, size_t nbytes, int mode, int num_cus, hipStream_t stream);
 
 // s = 64 wavefront-per-chunk kernels (demo_enc64.hip, demo_dec64.hip).
 constexpr int kEnc64TableFloats = 3072 + 4096 + 2048;

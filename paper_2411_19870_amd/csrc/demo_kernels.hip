@@ -1033,6 +1033,65 @@ hipError_t launch_copy_probe(const void* src, void* dst, size_t nbytes, int num_
   return hipGetLastError();
 }
 
+// Streaming probe in the launch shape of the wavefront kernels: one 512-thread workgroup per compute unit, every
+// lane moves 16 bytes per access with eight accesses in flight; a workgroup's accesses of one round are contiguous
+// (8 KiB per access slot) and the workgroups advance together through memory.
+// MODE 0: copy, default cache policy; 1: copy, non-temporal; 2: read only, non-temporal; 3: write only,
+// non-temporal; 4: write only, default cache policy.
+template <int MODE>
+__global__ __launch_bounds__(512) void stream_probe_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst, size_t n16) {
+  constexpr int UNROLL = 8;
+  const size_t per_round = (size_t)gridDim.x * 512 * UNROLL;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (size_t base = (size_t)blockIdx.x * 512 * UNROLL; base < n16; base += per_round) {
+    f32x4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const size_t i = base + (size_t)u * 512 + threadIdx.x;
+      if (MODE >= 3) v[u] = (f32x4){(float)i, 1.f, 2.f, 3.f};
+      else if (i < n16) v[u] = MODE == 0 ? as_global(src)[i] : __builtin_nontemporal_load(as_global(src) + i);
+      else v[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const size_t i = base + (size_t)u * 512 + threadIdx.x;
+      if (MODE == 2) {
+        acc += v[u];
+      } else if (i < n16) {
+        if (MODE == 0 || MODE == 4) as_global(dst)[i] = v[u];
+        else __builtin_nontemporal_store(v[u], as_global(dst) + i);
+      }
+    }
+  }
+  if (MODE == 2) {   // one 16-byte store per wavefront keeps the reads alive
+    f32x4 r = acc;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] += __shfl_xor(r[e], off);
+    if ((threadIdx.x & 63) == 0) as_global(dst)[blockIdx.x * 8 + (threadIdx.x >> 6)] = r;
+  }
+}
+
+hipError_t launch_stream_probe(const void* src, void* dst, size_t nbytes, int mode, int num_cus, hipStream_t stream) {
+  const size_t n16 = nbytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t grid = (size_t)num_cus;
+  if (grid > (n16 + 4095) / 4096) grid = (n16 + 4095) / 4096;
+  if (grid > 512) grid = 512;   // mode 2 writes 128 bytes per workgroup into at least 64 KiB
+  const f32x4* s4 = static_cast<const f32x4*>(src);
+  f32x4* d4 = static_cast<f32x4*>(dst);
+  switch (mode) {
+    case 0: hipLaunchKernelGGL(stream_probe_kernel<0>, dim3((unsigned)grid), dim3(512), 0, stream, s4, d4, n16); break;
+    case 1: hipLaunchKernelGGL(stream_probe_kernel<1>, dim3((unsigned)grid), dim3(512), 0, stream, s4, d4, n16); break;
+    case 2: hipLaunchKernelGGL(stream_probe_kernel<2>, dim3((unsigned)grid), dim3(512), 0, stream, s4, d4, n16); break;
+    case 3: hipLaunchKernelGGL(stream_probe_kernel<3>, dim3((unsigned)grid), dim3(512), 0, stream, s4, d4, n16); break;
+    case 4: hipLaunchKernelGGL(stream_probe_kernel<4>, dim3((unsigned)grid), dim3(512), 0, stream, s4, d4, n16); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // launch wrappers
 // ---------------------------------------------------------------------------

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "demo.h"
+#include "demo_debug.h"
 #include "demo_internal.h"
 
 static int failures = 0;

@@ -490,3 +490,64 @@ def test_non_finite_inputs_stay_in_their_chunks(ctx, s):
     assert torch.equal(other_chunks(dirty.x[0]), other_chunks(clean.x[0]))
     assert torch.equal(dirty.x[1][s:], clean.x[1][s:])
     assert nch_cols >= 3
+
+
+# ---- a caller whose buffers move every step presents a new list each time: beyond the cached lists the tables are
+#      rewritten in reused memory by a kernel on the call's stream (also from a second stream) ----------------------
+@pytest.mark.parametrize("s", [32, 64, 128])
+def test_buffers_that_move_every_step(ctx, s):
+    ctx.demo_set_variant(1)
+    k = 8
+    cases = [Case(synth.tensor_set("tiny"), s, k, W=2, grad_dtype=torch.bfloat16, param_dtype=torch.bfloat16, seed=70 + i)
+             for i in range(11)]
+    side = torch.cuda.Stream()
+    for rep in range(2):
+        for i, case in enumerate(cases):                 # same shapes and dtypes, other addresses, every call
+            on_side = (i % 4 == 3)
+            if on_side:
+                side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side if on_side else torch.cuda.current_stream()):
+                before = case.snapshot()
+                ctx.demo_encode(case.args, BETA, s, k, torch.cuda.current_stream())
+                torch.cuda.current_stream().synchronize()
+                after = case.snapshot()
+            torch.cuda.synchronize()
+            for ti in range(len(case.specs)):
+                C.check_encode(before["m"][ti], before["g"][ti], BETA, s, k, after["idx"][ti][0], after["val"][ti][0],
+                               after["m"][ti])
+            case.fill_payloads()
+            run_decode_check(ctx, case, W=2)
+            case.new_grads(rep + 1)
+
+
+# ---- measurement hooks: cut-down copies of the s = 64 encode kernel and the stream probes run and leave the
+#      library in its ordinary state -------------------------------------------------------------------------------
+def test_debug_stages_and_stream_probes(ctx):
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 512, 1024)]
+    case = Case(specs, 64, 32, grad_dtype=torch.bfloat16, seed=3)
+    for stage in (1, 2, 3):
+        ctx.demo_debug_set_encode_stage(stage)
+        ctx.demo_encode(case.args, BETA, 64, 32)
+        f32 = Case(specs, 64, 32, seed=3)
+        with pytest.raises(B.DemoError) as e:
+            ctx.demo_encode(f32.args, BETA, 64, 32)          # the copies exist for bfloat16 gradients only
+        assert e.value.status == B.DEMO_ERR_UNSUPPORTED
+        with pytest.raises(B.DemoError) as e:
+            ctx.demo_encode(case.args, BETA, 128, 32)
+        assert e.value.status == B.DEMO_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    ctx.demo_debug_set_encode_stage(0)
+    with pytest.raises(B.DemoError):
+        ctx.demo_debug_set_encode_stage(4)
+    case = Case(specs, 64, 32, grad_dtype=torch.bfloat16, seed=4)
+    run_encode_check(ctx, case)
+    src = torch.randn(1 << 20, device=DEV)
+    for mode in range(5):
+        dst = torch.zeros(1 << 20, device=DEV)
+        ctx.demo_stream_probe(dst, src, mode)
+        torch.cuda.synchronize()
+        if mode < 2:
+            assert torch.equal(dst, src)
+    with pytest.raises(B.DemoError):
+        ctx.demo_stream_probe(dst, src, 5)
