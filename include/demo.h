@@ -63,7 +63,8 @@ typedef enum demo_status {
                                 more than 2^31 - 1 chunks in a tensor or in a call,
                                 cols >= DEMO_MAX_COLS                                      */
   DEMO_ERR_HIP = -4,         /* a HIP runtime call failed (see demo_last_hip_error)       */
-  DEMO_ERR_NOMEM = -5        /* host or device allocation for the context's tables failed */
+  DEMO_ERR_NOMEM = -5,       /* host or device allocation for the context's tables failed */
+  DEMO_ERR_LIMIT = -6        /* demo_encode_noalloc: the tensor list exceeds the static scratch array */
 } demo_status;
 
 typedef enum demo_dtype { DEMO_F32 = 0, DEMO_BF16 = 1 } demo_dtype;
@@ -105,6 +106,25 @@ int demo_payload_elems(int64_t rows, int64_t cols, int s, int k, int64_t* out);
  * 0), and m <- m - IDCT(kept).  Requires grad, mom, idx, val.  */
 int demo_encode(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k,
                 void* hip_stream);
+
+/* demo_encode for callers that cannot allocate device memory or synchronise: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same results as
+ * demo_encode, but the tables the kernels read beside the tensors (DCT basis tables, tensor descriptors, the
+ * queue of chunks handed to the exact top-k kernel) live in a static device array of DEMO_NOALLOC_SCRATCH_BYTES
+ * that every GPU the library runs on holds until the process ends, and they are written there by small kernels
+ * on `hip_stream`: the call performs no hipMalloc, hipFree, memory copy or synchronisation, whether or not the
+ * list has been seen before.
+ *   Limits: n <= DEMO_NOALLOC_MAX_TENSORS, at most DEMO_NOALLOC_MAX_CHUNKS order-2 chunks in the call, the DCT
+ *   basis only (DEMO_ERR_UNSUPPORTED after demo_set_basis chose another matrix for s).  DEMO_ERR_LIMIT beyond
+ *   them; nothing is launched then.
+ *   All calls on one GPU share the one array (from any context or thread): calls of this entry point that
+ *   overlap in time on one GPU race; issue them on one stream, or order the streams.  It is not used by any
+ *   other entry point.  demo_set_timing does not cover it.  */
+#define DEMO_NOALLOC_MAX_TENSORS 1024
+#define DEMO_NOALLOC_MAX_CHUNKS (1 << 20)
+#define DEMO_NOALLOC_SCRATCH_BYTES (128 * 1024 + 256 * 1024 + 4 * DEMO_NOALLOC_MAX_CHUNKS + 4096)
+int demo_encode_noalloc(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k,
+                        void* hip_stream);
 
 /* Server side of Algorithm 1 (appendix algorithm Decompress&Aggregate followed by
  * the update line):  per chunk sum the coefficients of the W payloads (workers

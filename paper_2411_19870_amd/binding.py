@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("DEMO_LIBRARY_PATH") or os.path.join(_HERE, "libdemo.so")
 
-DEMO_OK, DEMO_ERR_ARG, DEMO_ERR_SHAPE, DEMO_ERR_UNSUPPORTED, DEMO_ERR_HIP, DEMO_ERR_NOMEM = 0, -1, -2, -3, -4, -5
+DEMO_OK, DEMO_ERR_ARG, DEMO_ERR_SHAPE, DEMO_ERR_UNSUPPORTED, DEMO_ERR_HIP, DEMO_ERR_NOMEM, DEMO_ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6
 DEMO_F32, DEMO_BF16 = 0, 1
 DEMO_MAX_K = 256
 DEMO_PHI_SIGN, DEMO_PHI_IDENTITY = 0, 1
@@ -27,7 +27,7 @@ DEMO_BASIS_DCT, DEMO_BASIS_IDENTITY, DEMO_BASIS_GRAM_SCHMIDT = 0, 1, 2
 EXPORTS = [
     "demo_create", "demo_destroy", "demo_payload_elems", "demo_encode", "demo_decode", "demo_step",
     "demo_hparams_default", "demo_encode_ex", "demo_decode_ex", "demo_step_ex", "demo_set_basis",
-    "demo_strerror", "demo_last_hip_error",
+    "demo_encode_noalloc", "demo_strerror", "demo_last_hip_error",
     # include/demo_debug.h: measurement and test hooks
     "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_copy_probe", "demo_stream_probe",
     "demo_debug_set_encode_stage",
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.demo_destroy.argtypes = [vp]
     lib.demo_payload_elems.argtypes = [i64, i64, ci, ci, ctypes.POINTER(i64)]
     lib.demo_encode.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, cf, ci, ci, vp]
+    lib.demo_encode_noalloc.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, cf, ci, ci, vp]
     lib.demo_decode.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, ci, cf, cf, ci, ci, vp]
     lib.demo_step.argtypes = [vp, ctypes.POINTER(DemoTensor), ci, cf, cf, cf, ci, ci, vp]
     hpp = ctypes.POINTER(DemoHParams)
@@ -219,6 +220,10 @@ class Context:
     def demo_encode(self, tensors: Sequence[TensorArgs], beta: float, s: int, k: int, stream=None):
         tl = _as_list(tensors)
         self._check(self._lib.demo_encode(self._h, tl.arr, tl.n, beta, s, k, _stream_ptr(stream)))
+
+    def demo_encode_noalloc(self, tensors: Sequence[TensorArgs], beta: float, s: int, k: int, stream=None):
+        tl = _as_list(tensors)
+        self._check(self._lib.demo_encode_noalloc(self._h, tl.arr, tl.n, beta, s, k, _stream_ptr(stream)))
 
     def demo_decode(self, tensors: Sequence[TensorArgs], W: int, lr: float, weight_decay: float, s: int, k: int,
                     stream=None):

@@ -12,6 +12,10 @@
 
 static_assert(DEMO_MAX_K == DEMO_MAXK_INTERNAL, "public and internal k limits must agree");
 static_assert(sizeof(demo_tensor) == 64, "demo_tensor layout is part of the ABI");
+static_assert(DEMO_NOALLOC_MAX_TENSORS == demo::kNoallocMaxTensors && DEMO_NOALLOC_MAX_CHUNKS == demo::kNoallocMaxChunks &&
+                  DEMO_NOALLOC_SCRATCH_BYTES == demo::kNoallocScratchBytes,
+              "public and internal limits of the allocation-free entry point must agree");
+
 
 namespace {
 
@@ -646,6 +650,63 @@ int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, floa
   return demo_step_ex(ctx, tensors, n, &hp, s, k, hip_stream);
 }
 
+int demo_encode_noalloc(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, int s, int k,
+                        void* hip_stream) {
+  int rc = validate(ctx, tensors, n, s, k, NEED_ENCODE);
+  if (rc != DEMO_OK) return rc;
+  demo_hparams hp;
+  demo_hparams_default(&hp, beta, 0.0f, 0.0f);
+  if ((rc = check_hparams(&hp, NEED_ENCODE, 1)) != DEMO_OK || n == 0) return rc;
+  // capacity of the static scratch array
+  if (n > demo::kNoallocMaxTensors) return DEMO_ERR_LIMIT;
+  int64_t chunks2 = 0;
+  for (int i = 0; i < n; ++i)
+    if (tensors[i].cols != 0) chunks2 += (tensors[i].rows / s) * (tensors[i].cols / s);
+  if (chunks2 > demo::kNoallocMaxChunks) return DEMO_ERR_LIMIT;
+  for (const BasisTable& b : ctx->bases)
+    if (b.s == s && b.use_custom) return DEMO_ERR_UNSUPPORTED;   // the scratch array holds the DCT tables only
+  if ((rc = bind_device(ctx)) != DEMO_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  void* base = nullptr;
+  hipError_t e = demo::noalloc_scratch(ctx->device, &base);
+  if (e != hipSuccess) return fail_hip(ctx, e);
+  char* sc = static_cast<char*>(base);
+
+  // basis tables of this chunk size: written once, kept until a call with another chunk size replaces them
+  auto align256 = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  const size_t o_enc = align256((size_t)s * s * sizeof(float));
+  if (demo::noalloc_basis_resident(ctx->device) != s) {
+    HostBasis hb;
+    build_host_basis(s, &hb);
+    const std::vector<float>& enc = s == 64 ? hb.enc64 : hb.enc32;   // empty at s = 128
+    if (o_enc + enc.size() * sizeof(float) > demo::kNoallocBasisBytes) return DEMO_ERR_LIMIT;
+    demo::noalloc_set_basis_resident(ctx->device, 0);
+    if ((e = demo::device_write(sc, hb.P.data(), hb.P.size() * sizeof(float), st)) != hipSuccess) return fail_hip(ctx, e);
+    if (!enc.empty() && (e = demo::device_write(sc + o_enc, enc.data(), enc.size() * sizeof(float), st)) != hipSuccess)
+      return fail_hip(ctx, e);
+    demo::noalloc_set_basis_resident(ctx->device, s);
+  }
+  const float* P = reinterpret_cast<const float*>(sc);
+  const float* enc = reinterpret_cast<const float*>(sc + o_enc);
+  const demo::BasisTables basis{P, s == 64 ? enc : nullptr, nullptr, s == 32 ? enc : nullptr, nullptr, true};
+
+  // descriptor tables and queue headers of this call (the headers are zero in the image: the queue starts empty
+  // whatever the last call left); the queue lists behind them need no initial contents
+  TableImage img;
+  build_image(tensors, n, s, &img);
+  if (img.total_bytes > demo::kNoallocScratchBytes - demo::kNoallocBasisBytes) return DEMO_ERR_LIMIT;
+  char* tb = sc + demo::kNoallocBasisBytes;
+  if ((e = demo::device_write(tb, img.head.data(), img.head.size(), st)) != hipSuccess) return fail_hip(ctx, e);
+  std::vector<TableGroup> groups;
+  TableView tv1{};
+  bind_image(img, tb, &groups, &tv1);
+  const bool timing = ctx->timing;
+  ctx->timing = false;   // timers create events on first use
+  rc = run_encode(ctx, groups, tv1, basis, hp, s, k, st);
+  ctx->timing = timing;
+  return rc;
+}
+
 int demo_set_timing(demo_ctx* ctx, int enabled) {
   if (ctx == nullptr) return DEMO_ERR_ARG;
   ctx->timing = enabled != 0;
@@ -775,6 +836,7 @@ const char* demo_strerror(int status) {
     case DEMO_ERR_UNSUPPORTED: return "unsupported chunk size, dtype or k above DEMO_MAX_K";
     case DEMO_ERR_HIP: return "HIP runtime error";
     case DEMO_ERR_NOMEM: return "out of memory";
+    case DEMO_ERR_LIMIT: return "tensor list beyond the fixed capacity of the allocation-free entry point";
   }
   return "unknown status";
 }

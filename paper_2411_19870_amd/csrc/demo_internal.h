@@ -91,8 +91,18 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
 hipError_t launch_decode1d(const TableView& tv, const float* basis, int s, const DecodeArgs& a,
                            hipStream_t stream);
 
-// demo_noalloc.hip: stream-ordered host-to-device write through kernel arguments (no runtime copy, no allocation)
+// demo_noalloc.hip: stream-ordered host-to-device write through kernel arguments, and the static scratch array
+// of the entry point that allocates nothing.  Scratch layout: [basis tables of one chunk size][descriptor tables
+// and queue headers][fallback queue, one int32 per order-2 chunk].
+constexpr size_t kNoallocBasisBytes = 128 * 1024;
+constexpr int kNoallocMaxTensors = 1024;
+constexpr int kNoallocMaxChunks = 1 << 20;          // order-2 chunks per call
+constexpr size_t kNoallocHeadBytes = 256 * 1024;    // descriptors of kNoallocMaxTensors tensors fit
+constexpr size_t kNoallocScratchBytes = kNoallocBasisBytes + kNoallocHeadBytes + 4 * (size_t)kNoallocMaxChunks + 4096;
 hipError_t device_write(void* dst, const void* host, size_t nbytes, hipStream_t stream);
+hipError_t noalloc_scratch(int device, void** ptr);
+int noalloc_basis_resident(int device);
+void noalloc_set_basis_resident(int device, int s);
 
 hipError_t launch_copy_probe(const void* src, void* dst, size_t nbytes, int num_cus, hipStream_t stream);
 hipError_t launch_stream_probe(const void* src, void* dst, size_t nbytes, int mode, int num_cus, hipStream_t stream);

@@ -1,9 +1,18 @@
-// Writes to device memory that need no runtime copy: a writer kernel that carries its data in the kernel arguments.
+// Device memory that needs no allocation: a writer kernel that carries its data in the kernel arguments, and the
+// static scratch array behind demo_encode_noalloc (basis tables, descriptor tables and the fallback queue of one
+// call at a time, per GPU).
 #include "demo_device.h"
 
 namespace demo {
 
 namespace {
+
+// Each GPU the library runs on holds its own copy of this array, at its own address, until the process ends.
+static __device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch` on each GPU (hipGetSymbolAddress)
+int g_basis_resident[kMaxDevices] = {};    // chunk size whose basis tables lie in the scratch of each GPU, 0 = none
 
 constexpr int kBatchWords = 960;           // 3840 bytes of data per launch (kernel arguments are limited to 4 KiB)
 struct WordBatch {
@@ -32,6 +41,25 @@ hipError_t device_write(void* dst, const void* host, size_t nbytes, hipStream_t 
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+// Address of the static scratch array on the current device (looked up once per device).
+hipError_t noalloc_scratch(int device, void** ptr) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch_ptr[device] == nullptr) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = p;
+  }
+  *ptr = g_scratch_ptr[device];
+  return hipSuccess;
+}
+
+int noalloc_basis_resident(int device) { return device >= 0 && device < kMaxDevices ? g_basis_resident[device] : 0; }
+void noalloc_set_basis_resident(int device, int s) {
+  if (device >= 0 && device < kMaxDevices) g_basis_resident[device] = s;
 }
 
 }  // namespace demo
