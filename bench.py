@@ -9,14 +9,19 @@ One step = one pass of the whole hot path over the 1B-like tensor set:
 Inputs are synthetic and resident in HBM before the timed region starts.
 
 Prints ONE JSON line: whole-step throughput in GB/s of algorithmic traffic (and
-params/s), the roofline record of the dominant kernel measured with HIP events on
-the launch stream inside the timed region, and the float64 CPU oracle timed on a
-bounded sample of the same workload.
+params/s); the roofline record of the dominant kernel measured with HIP events on
+the launch stream inside the timed region, against the published HBM peak and against
+the issued fp32 MFMA work, the bound being whichever fraction is larger; the ceilings
+this GPU's memory system reaches for the kernels' own traffic (measured after the timed
+region); the payload size; and the float64 CPU oracle timed on all host cores on a stated
+sample of the same workload.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
+import math
 import os
 import sys
 import time
@@ -26,8 +31,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
 S, K, W = 64, 32, 64
 BETA, LR, WD = 0.999, 1e-3, 0.0
+CPU_SAMPLE_FRACTION = 0.10
 
 
 def algorithmic_bytes(specs, s, k, W, grad_bytes, param_bytes):
@@ -45,42 +52,97 @@ def algorithmic_bytes(specs, s, k, W, grad_bytes, param_bytes):
     return {"enc2d": enc2, "enc1d": enc1, "dec2d": dec2, "dec1d": dec1, "params2d": p2, "params1d": p1}
 
 
-def cpu_baseline(specs, seed):
-    """Time the oracle (as it stands) on a bounded sample of the workload: the first
-    transformer layer's attention output matrix (2048 x 2048, 1024 chunks) and one
-    norm vector, encode + W = 64 decode."""
+def source_hash():
+    """Hash of the kernel sources: profiles/ records made with other sources are not quoted."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2411_19870_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        with open(os.path.join(d, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def mfma_flops_per_launch(kernel, s, k, W, nchunks2, idx_tensors):
+    """fp32 MFMA flops one launch of the order-2 kernel issues (v_mfma_f32_16x16x4_f32 = 2048 flop), from the
+    kernels' own instruction counts: products with the mirror folds, and for encode the reconstruction chain,
+    whose length depends on how many selected coefficients fall into each class of row frequency."""
+    import torch
+    if kernel == "dec2d":
+        per_chunk = {64: 192.0, 32: 32.0, 128: 1536.0}[s]                  # both products, 3/8 (s=32: 1/2) of dense
+        if s == 64 and W * k <= 64:
+            per_chunk = None                                               # the few-pairs kernel: data dependent
+        return None if per_chunk is None else per_chunk * 2048.0 * nchunks2
+    products = {64: 192.0, 32: 32.0, 128: 1536.0}[s]
+    recon = 0.0
+    if s == 64:
+        # classes of u: 0 mod 4, 2 mod 4 (4 MFMAs per step of four coefficients), odd (8 per step)
+        for idx in idx_tensors:
+            u = (idx[0].to(torch.int64) >> 6)
+            c0 = ((u & 3) == 0).sum(1)
+            c1 = ((u & 3) == 2).sum(1)
+            c2 = ((u & 1) == 1).sum(1)
+            recon += float((4 * ((c0 + 3) // 4) + 4 * ((c1 + 3) // 4) + 8 * ((c2 + 3) // 4)).sum())
+        return (products * nchunks2 + recon) * 2048.0
+    if s == 32:
+        return (products + 4.0 * math.ceil(k / 4.0)) * 2048.0 * nchunks2   # four MFMAs per step of four coefficients
+    return (products + 16.0 * 12.0) * 2048.0 * nchunks2                    # s = 128: about 12 per wavefront
+
+
+def _cpu_job(job):
+    """One tensor slab of the CPU baseline: oracle encode + W-worker decode (runs in a worker process)."""
     import numpy as np
     import torch
     from oracle import demo_oracle as O
     from paper_2411_19870_amd import synth
+    name, rows, cols, ti, seed, s, k, Wn = job
+    sp = synth.TensorSpec(name, rows, cols)
+    g = synth.gaussian(sp, 1e-2, seed, ti, 0, "grad", dtype=torch.bfloat16).double().numpy()
+    m = synth.gaussian(sp, 1e-3, seed, ti, 0, "mom").double().numpy()
+    x = synth.gaussian(sp, 0.02, seed, ti, 0, "param", dtype=torch.bfloat16).double().numpy()
+    idx, val = synth.payload_fast(sp, s, k, Wn, 1e-3, seed, ti)
+    idx, val = idx.numpy(), val.numpy()
+    t0 = time.perf_counter()
+    e = O.encode(m, g, float(np.float32(BETA)), s, k)
+    idx[0], val[0] = e["idx"], e["val"].astype(np.float32)
+    O.decode(x, idx, val, LR, WD, s, "bf16")
+    return time.perf_counter() - t0
 
-    sample = [next(sp for sp in specs if sp.name.endswith(".wo")), next(sp for sp in specs if sp.cols == 0)]
-    data = []
-    for ti, sp in enumerate(sample):
-        g = synth.gaussian(sp, 1e-2, seed, ti, 0, "grad", dtype=torch.bfloat16).double().numpy()
-        m = synth.gaussian(sp, 1e-3, seed, ti, 0, "mom").double().numpy()
-        x = synth.gaussian(sp, 0.02, seed, ti, 0, "param", dtype=torch.bfloat16).double().numpy()
-        idx, val = synth.payload_fast(sp, S, K, W, 1e-3, seed, ti)
-        data.append((g, m, x, idx.numpy(), val.numpy()))
-    ab = algorithmic_bytes(sample, S, K, W, 2, 2)
-    nbytes = sum(ab[k] for k in ("enc2d", "enc1d", "dec2d", "dec1d"))
-    nparams = ab["params2d"] + ab["params1d"]
-    reps, t_wall, t_cpu = 0, 0.0, 0.0
-    while t_wall < 10.0 and reps < 50:
-        w0, c0 = time.perf_counter(), time.process_time()
-        for g, m, x, idx, val in data:
-            e = O.encode(m, g, float(np.float32(BETA)), S, K)
-            idx[0], val[0] = e["idx"], e["val"].astype(np.float32)
-            O.decode(x, idx, val, LR, WD, S, "bf16")
-        t_wall += time.perf_counter() - w0
-        t_cpu += time.process_time() - c0
-        reps += 1
-    cores = max(1, int(round(t_cpu / t_wall)))
+
+def cpu_baseline(specs, seed, s, k, Wn, ab_step_bytes, nparams):
+    """The oracle as it stands, on every host core this process may use: one encode + W-worker decode pass over a
+    slab of the first CPU_SAMPLE_FRACTION of the rows of every tensor of the workload (rounded up to whole chunks),
+    cut into jobs of about 2^20 parameters for a pool of worker processes.  The rate is that of the timed pass; input generation in the
+    workers is outside the oracle's timers but inside the wall-clock, so the wall-clock rate is the lower one."""
+    import multiprocessing
+    from concurrent.futures import ProcessPoolExecutor
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    jobs, sample_params = [], 0
+    for ti, sp in enumerate(specs):
+        rows = min(sp.rows, max(s, int(math.ceil(sp.rows * CPU_SAMPLE_FRACTION / s)) * s))
+        # pieces of about 2^20 parameters (whole chunk rows), so that the cores finish together
+        piece = max(s, ((1 << 20) // (sp.cols or 1)) // s * s)
+        for r0 in range(0, rows, piece):
+            jobs.append((sp.name, min(piece, rows - r0), sp.cols, ti, seed + r0, s, k, Wn))
+        sample_params += rows * (sp.cols or 1)
+    jobs.sort(key=lambda j: -j[1] * (j[2] or 1))            # largest first
+    frac = sample_params / nparams
+    w0 = time.perf_counter()
+    with ProcessPoolExecutor(max_workers=cores, mp_context=multiprocessing.get_context("spawn")) as pool:
+        list(pool.map(_cpu_job, jobs[-cores:]))             # start the workers (imports) outside the timed pass
+        w1 = time.perf_counter()
+        busy = sum(pool.map(_cpu_job, jobs))
+        w2 = time.perf_counter()
+    wall = w2 - w1
     return {
-        "value": nbytes * reps / t_wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "params_per_s": nparams * reps / t_wall,
-        "sample": f"{reps} passes of encode + W=64 decode over {sample[0].rows}x{sample[0].cols} "
-                  f"({sample[0].nchunks(S)} chunks) and one vector of {sample[1].rows}; {t_wall:.1f} s wall",
+        "value": ab_step_bytes * frac / wall / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "params_per_s": sample_params / wall,
+        "core_seconds_in_oracle": busy, "wall_s": wall, "pool_start_s": w1 - w0,
+        "sample": f"one pass of encode + W={Wn} decode over the first {100 * CPU_SAMPLE_FRACTION:.0f} % of the rows of each "
+                  f"of the {len(specs)} tensors ({sample_params} parameters, {100 * frac:.1f} % of the workload), "
+                  f"one process per core, wall-clock of the pass",
     }
 
 
@@ -93,6 +155,7 @@ def main():
     ap.add_argument("--workload", default="1b", choices=["1b", "300m", "single"])
     ap.add_argument("--variant", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the memory-system probes after the timed region")
     ap.add_argument("--seed", type=int, default=0)
     # other operating points of the same path (the headline configuration is the default)
     ap.add_argument("--s", type=int, default=S, choices=[32, 64, 128], help="chunk size")
@@ -129,6 +192,8 @@ def main():
     ab = algorithmic_bytes(specs, S, K, W, gb, gb)
     step_bytes = ab["enc2d"] + ab["enc1d"] + ab["dec2d"] + ab["dec1d"]
     nparams = ab["params2d"] + ab["params1d"]
+    nchunks2 = sum(sp.nchunks(S) for sp in specs if sp.cols)
+    nchunks = sum(sp.nchunks(S) for sp in specs)
 
     ctx = B.Context()
     ctx.demo_set_variant(a.variant)
@@ -156,23 +221,34 @@ def main():
             kms[name] = None
     ctx.demo_set_timing(False)
 
-    # plain copy of known size (outside the timed region): the copy bandwidth this GPU reaches, and the
-    # kernel the HBM traffic counters are calibrated with
-    probe_src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_()     # 4 GiB
-    probe_dst = torch.empty_like(probe_src)
-    for _ in range(2):
-        ctx.demo_copy_probe(probe_dst, probe_src, stream)
-    torch.cuda.synchronize()
-    ctx.demo_set_timing(True)
-    for _ in range(5):
-        ctx.demo_copy_probe(probe_dst, probe_src, stream)
-    probe_ms = ctx.demo_last_kernel_ms(1)
-    ctx.demo_set_timing(False)
-    probe_bytes = 2 * probe_src.numel() * 4
-    del probe_src, probe_dst
+    def timed(fn, reps, slot):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ctx.demo_set_timing(True)
+        for _ in range(reps):
+            fn()
+        ms = ctx.demo_last_kernel_ms(slot)
+        ctx.demo_set_timing(False)
+        return ms
 
     dom = "enc2d" if (kms["enc2d"] or 0) >= (kms["dec2d"] or 0) else "dec2d"
     achieved = ab[dom] / (kms[dom] * 1e-3) / 1e9
+    hbm_frac = achieved / HBM_PEAK_GBS
+    mfma_flops = mfma_flops_per_launch(dom, S, K, W, nchunks2, [t.idx for t, sp in zip(tensors, specs) if sp.cols]) \
+        if a.variant == 1 else None
+    mfma_tflops = mfma_flops / (kms[dom] * 1e-3) / 1e12 if mfma_flops else None
+    mfma_frac = mfma_tflops / MFMA_F32_PEAK_TFLOPS if mfma_tflops else None
+    bound = "mfma" if (mfma_frac or 0.0) > hbm_frac else "hbm"
+    roof = {"bound": bound, "kernel": dom, "avg_launch_ms": kms[dom],
+            "hbm": {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac,
+                    "algorithmic_bytes_per_launch": ab[dom]},
+            "mfma": {"achieved": mfma_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac,
+                     "issued_fp32_mfma_flops_per_launch": mfma_flops},
+            "traffic": None, "traffic_source": None}
+    roof.update({"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac} if bound == "hbm" else
+                {"achieved": mfma_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac})
+
     out = {
         "metric": "DeMo encode+decode throughput at 1B shape" if a.workload == "1b" and headline
                   else f"DeMo encode+decode throughput ({a.workload}, s={S}, k={K}, W={W})",
@@ -185,27 +261,68 @@ def main():
                                f"+ decode of W={W} payloads (param {'bf16' if gb == 2 else 'f32'})",
                    "tensors": len(specs), "params": nparams, "s": S, "k": K, "W": W, "beta": BETA, "lr": LR,
                    "kernel_variant": a.variant},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "algorithmic_bytes_per_launch": ab[dom], "avg_launch_ms": kms[dom]},
+        "roofline": roof,
         "kernels_ms": kms,
         "kernels_gbs": {k: (ab[k] / (v * 1e-3) / 1e9 if v else None) for k, v in kms.items()},
         "encode_params_per_s": nparams / (((kms["enc2d"] or 0) + (kms["enc1d"] or 0)) * 1e-3),
         "decode_params_per_s": nparams / (((kms["dec2d"] or 0) + (kms["dec1d"] or 0)) * 1e-3),
         "algorithmic_bytes_per_step": step_bytes,
-        "copy_probe": {"bytes_moved": probe_bytes, "ms": probe_ms, "gbs": probe_bytes / (probe_ms * 1e-3) / 1e9},
+        # what one worker sends per step (k pairs of int32 index + float32 value per chunk) and what the decode reads
+        "payload_bytes_per_step": {"sent_per_worker": nchunks * K * 8, "received": W * nchunks * K * 8},
     }
-    # HBM traffic of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs (scaled by the
-    # copy probe), recorded under profiles/ when those runs were made for this workload
+
+    # ---- memory-system ceilings, measured after the timed region -------------------------------------------------
+    if not a.no_ceilings:
+        probe_src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_()     # 4 GiB
+        probe_dst = torch.empty_like(probe_src)
+        nb = probe_src.numel() * 4
+        probe_ms = timed(lambda: ctx.demo_copy_probe(probe_dst, probe_src, stream), 5, 1)
+        out["copy_probe"] = {"bytes_moved": 2 * nb, "ms": probe_ms, "gbs": 2 * nb / (probe_ms * 1e-3) / 1e9}
+        ceil = {"unit": "GB/s", "bytes_per_probe": nb,
+                "note": "stream probes in the launch shape of the wavefront kernels (one 512-thread workgroup per CU, "
+                        "16 B per lane, 8 accesses in flight), 4 GiB each"}
+        for mode, name, moved in ((1, "copy_nontemporal", 2), (0, "copy_default_policy", 2),
+                                  (2, "read_only", 1), (3, "write_only", 1)):
+            ms = timed(lambda: ctx.demo_stream_probe(probe_dst, probe_src, mode, stream), 5, 1)
+            ceil[name] = moved * nb / (ms * 1e-3) / 1e9
+        del probe_src, probe_dst
+        # the dominant kernel's own traffic mix at the rates the probes reach for pure reads and pure writes
+        rd = ab[dom] - (ab["params2d"] * 4 + nchunks2 * K * 8 if dom == "enc2d" else ab["params2d"] * gb)
+        wr = ab[dom] - rd
+        t_mix = rd / ceil["read_only"] + wr / ceil["write_only"]
+        ceil["kernel_mix_serialised"] = ab[dom] / t_mix
+        if dom == "enc2d" and S == 64 and gb == 2 and a.variant == 1 and K <= 64:
+            # the encode kernel's own access pattern with the transform taken out (loads with the cross-chunk
+            # prefetch, momentum update, store of m, k payload pairs per chunk)
+            ctx.demo_debug_set_encode_stage(1)
+            ms = timed(lambda: ctx.demo_encode(tl, BETA, S, K, stream), 5, 0)
+            ctx.demo_debug_set_encode_stage(0)
+            ceil["kernel_access_pattern_only"] = ab[dom] / (ms * 1e-3) / 1e9
+            ceil["kernel_access_pattern_only_ms"] = ms
+        best = ceil.get("kernel_access_pattern_only", ceil["kernel_mix_serialised"])
+        roof["hbm"]["frac_of_peak"] = hbm_frac
+        roof["hbm"]["frac_of_measured"] = achieved / best
+        roof["hbm"]["measured_ceiling"] = best
+        out["hbm_ceiling"] = ceil
+
+    # HBM traffic of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs (scaled by the copy probe)
+    # recorded under profiles/: quoted only when that record was made with these kernel sources
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{a.workload}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             rec = json.load(f)
-        if headline and rec.get("variant") == a.variant and dom in rec.get("kernels", {}):
-            out["roofline"]["traffic"] = rec["kernels"][dom]["hbm_bytes_per_launch"]
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(specs, a.seed)
+        same = rec.get("source_hash") == source_hash()
+        if headline and rec.get("variant") == a.variant and dom in rec.get("kernels", {}) and same:
+            roof["traffic"] = rec["kernels"][dom]["hbm_bytes_per_launch"]
+            roof["traffic_source"] = f"profiles/hbm_traffic_{a.workload}.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs " \
+                                     f"of these kernel sources, hash {rec['source_hash']})"
+        elif not same:
+            roof["traffic_source"] = f"profiles/hbm_traffic_{a.workload}.json is from other kernel sources: not quoted"
     ctx.close()
+    del tensors, tl
+    torch.cuda.empty_cache()
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(specs, a.seed, S, K, W, step_bytes, nparams)
     print(json.dumps(out), flush=True)
 
 
