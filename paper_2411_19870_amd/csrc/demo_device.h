@@ -175,6 +175,10 @@ __host__ __device__ constexpr int freq(int t, int m) {
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
 }
+// A buffer of zero records: every load from it returns zero and every store to it is dropped by the range check.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc_empty(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0, 0x00020000);
+}
 __device__ __forceinline__ f32x4 bload_f4(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
   return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, (int)soff, DEMO_LOAD_AUX));
 }
@@ -209,6 +213,10 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   __builtin_amdgcn_wave_barrier();
 }
+
+// LDS accessed through a 32-bit byte address
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+__device__ __forceinline__ lds_u32* lds_u32_at(uint32_t byte_address) { return (lds_u32*)(uintptr_t)byte_address; }
 
 // number of lanes below this one whose bit is set in mask
 __device__ __forceinline__ int lanes_below(uint64_t mask) {

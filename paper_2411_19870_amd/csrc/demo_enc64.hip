@@ -42,8 +42,11 @@ constexpr int E64_PCOL = 3072;                    // pcol[v*64 + 4c + e]  = P[v]
 constexpr int E64_PK = 3072 + 4096;               // pk[u*16 + c]  = P[u][kappa(c)]       (reconstruction, quadruple bases)
 constexpr int E64_PK2 = 3072 + 4096 + 1024;       // pk2[u*16 + c] = P[u][31 - kappa(c)]  (odd u: the second member)
 constexpr int E64_TABLE_FLOATS = 3072 + 4096 + 2048;
-// per-wavefront scratch: candidates {value bits, flat index} [CAP + 2], selected {flat, value bits} by class [3][64]
-constexpr int E64_SCRATCH_WORDS = 2 * (E64_CAP + 2) + 3 * 2 * 64;
+// per-wavefront scratch: candidate value bits [LIST], candidate flat indices [LIST] (one gather step appends up to
+// 64 entries to a list of at most CAP), 64-bit sort keys [64], selected {flat, value bits} by class [3][64]
+constexpr int E64_LIST = E64_CAP + 64 + 2;
+constexpr int E64_SCRATCH_WORDS = 2 * E64_LIST + 2 * 64 + 3 * 2 * 64;
+static_assert(E64_LIST % 4 == 2 && (2 * E64_LIST) % 4 == 0 && E64_SCRATCH_WORDS % 4 == 0, "16-byte aligned key and list arrays");
 __host__ __device__ constexpr int kappa64(int c) { return 4 * (c & 3) + (c >> 2); }
 constexpr int E64_LDS_BYTES = 4 * (E64_TABLE_FLOATS + E64_WAVES * E64_SCRATCH_WORDS);
 static_assert(E64_TABLE_FLOATS == kEnc64TableFloats, "table size");
@@ -104,9 +107,15 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
   uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + E64_TABLE_FLOATS) + wave * E64_SCRATCH_WORDS;
-  uint2* cand = reinterpret_cast<uint2*>(scratch);                       // {value bits, flat index}
-  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (E64_CAP + 2));    // [3][64] {flat index, value bits} by class of u
+  uint32_t* cand_v = scratch;                                            // value bits of the candidates
+  uint32_t* cand_f = scratch + E64_LIST;                                 // their flat indices
+  uint2* keys = reinterpret_cast<uint2*>(scratch + 2 * E64_LIST);        // {~flat index, magnitude bits}
+  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * E64_LIST + 128);   // [3][64] {flat index, value bits} by class of u
   const int k = args.k;
+  // LDS byte address of cand_v[0] as a scalar the compiler cannot take apart (it would otherwise re-add the
+  // constant part of the address on every access)
+  uint32_t list_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(lds_u32*)cand_v);
+  asm volatile("" : "+s"(list_base));
 
   for (int e = tid; e < E64_TABLE_FLOATS / 4; e += E64_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
@@ -178,8 +187,38 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   fetch_m(cur);
   fetch_g(cur);
 
+  // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e), from the rows fetched last ----
+  f32x4 D[4][4];
+  // gs: coefficient of g; the multiplication is left out when it is 1 (the algorithm boxes' form)
+  auto momentum = [&](auto unit_scale) {
+    constexpr bool UNIT = decltype(unit_scale)::value;
+    const float gs = args.grad_scale;
+    if (GBF16) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float g0 = __uint_as_float(ng[q][0] << 16), g1 = __uint_as_float(ng[q][0] & 0xffff0000u);
+        const float g2 = __uint_as_float(ng[q][1] << 16), g3 = __uint_as_float(ng[q][1] & 0xffff0000u);
+        D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], UNIT ? g0 : gs * g0);
+        D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], UNIT ? g1 : gs * g1);
+        D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], UNIT ? g2 : gs * g2);
+        D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], UNIT ? g3 : gs * g3);
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], UNIT ? ngf[q][e] : gs * ngf[q][e]);
+    }
+  };
+  const bool unit_grad_scale = args.grad_scale == 1.0f;
+  if (unit_grad_scale) momentum(std::true_type{}); else momentum(std::false_type{});
+
+  // The loop carries D: the rows of the next chunk are requested while this chunk is worked on and turned into the
+  // next D at the END of the body, behind this chunk's stores.  With the wait for those rows at the top of the body
+  // instead, the two ways into it (first entry: nothing behind the loads; back edge: the stores behind them) would
+  // leave the compiler only a wait for everything outstanding, i.e. for the stores' acknowledgements as well.
   DEMO_PHASE_DECL
-  for (; chunk < total; chunk += nwaves) {
+  for (;;) {
     const int cc = cur.cc;
     const uint32_t ucols = cur.ucols, vo_up = cur.vo_up, vo_dn = cur.vo_dn;
     const __amdgpu_buffer_rsrc_t mres = cur.mres;
@@ -195,31 +234,6 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       }
       nxt = place(d, chunk + nwaves - t_first);
     }
-
-    // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ------------------
-    f32x4 D[4][4];
-    // gs: coefficient of g; the multiplication is left out when it is 1 (the algorithm boxes' form)
-    auto momentum = [&](auto unit_scale) {
-      constexpr bool UNIT = decltype(unit_scale)::value;
-      const float gs = args.grad_scale;
-      if (GBF16) {
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const float g0 = __uint_as_float(ng[q][0] << 16), g1 = __uint_as_float(ng[q][0] & 0xffff0000u);
-          const float g2 = __uint_as_float(ng[q][1] << 16), g3 = __uint_as_float(ng[q][1] & 0xffff0000u);
-          D[q >> 2][0][q & 3] = __fmaf_rn(args.beta, nm[q][0], UNIT ? g0 : gs * g0);
-          D[q >> 2][1][q & 3] = __fmaf_rn(args.beta, nm[q][1], UNIT ? g1 : gs * g1);
-          D[q >> 2][2][q & 3] = __fmaf_rn(args.beta, nm[q][2], UNIT ? g2 : gs * g2);
-          D[q >> 2][3][q & 3] = __fmaf_rn(args.beta, nm[q][3], UNIT ? g3 : gs * g3);
-        }
-      } else {
-#pragma unroll
-        for (int q = 0; q < 16; ++q)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) D[q >> 2][e][q & 3] = __fmaf_rn(args.beta, nm[q][e], UNIT ? ngf[q][e] : gs * ngf[q][e]);
-      }
-    };
-    if (args.grad_scale == 1.0f) momentum(std::true_type{}); else momentum(std::false_type{});
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(0);
@@ -324,8 +338,10 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
     }
     DEMO_PHASE(3);
-    // (2) gather candidates |q| >= thr: one compare and one scalar branch per coefficient
+    // (2) gather candidates |q| >= thr: one compare and one scalar branch per coefficient.  The LDS byte address of
+    //     the list's end is kept as a scalar, so a lane's slot costs its count of hits below plus one shift-add
     int ncand = 0;
+    uint32_t list_end = list_base;
     // (keeps the 64 per-register flat indices from being precomputed outside the chunk loop)
     asm volatile("" : "+v"(fb_a), "+v"(fb_b), "+v"(fb_c), "+v"(fb_d));
     {
@@ -340,13 +356,16 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
             const bool is = fabsf(q) >= thr_f;
             const uint64_t mask = __ballot(is);
             if (mask != 0) {
-              if (is) {
-                const int pos = min((int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)ncand)), E64_CAP);
+              if (is && ncand <= E64_CAP) {   // a full list takes no more: slot < CAP + 64 without a per-lane clamp
+                lds_u32* slot = lds_u32_at(list_end + 4u * (uint32_t)lanes_below(mask));
                 const uint32_t fbase = tt < 2 ? (vt < 2 ? fb_a : fb_b) : (vt < 2 ? fb_c : fb_d);
                 const uint32_t fconst = (uint32_t)(64 * freq(tt, 0) + freq(vt, r));
-                cand[pos] = make_uint2(__float_as_uint(q), fbase + fconst);
+                slot[0] = __float_as_uint(q);
+                slot[E64_LIST] = fbase + fconst;
               }
-              ncand += __popcll(mask);
+              const int hits = __popcll(mask);
+              ncand += hits;
+              list_end += 4u * (uint32_t)hits;
             }
           }
     }
@@ -384,49 +403,54 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     };
     if (all_zero || skip) {
     } else if (ncand <= 64) {
-      // one candidate per lane; the others' keys come through v_readlane, four per trip (lanes past
+      // one candidate per lane, ordered by the 64-bit key {magnitude, ~flat index}.  The lanes put their keys into
+      // LDS and every lane reads all of them back, two per 16-byte read at a wavefront-uniform address (lanes past
       // the list carry key 0, which precedes nothing)
-      const uint2 me = cand[lane < ncand ? lane : 0];
-      const uint32_t mag = lane < ncand ? (me.x & 0x7fffffffu) : 0u, nfl = lane < ncand ? ~me.y : 0u;
+      const uint32_t me_v = cand_v[lane < ncand ? lane : 0], me_f = cand_f[lane < ncand ? lane : 0];
+      const uint32_t mag = lane < ncand ? (me_v & 0x7fffffffu) : 0u, nfl = lane < ncand ? ~me_f : 0u;
       const uint64_t key = ((uint64_t)mag << 32) | nfl;
+      keys[lane] = make_uint2(nfl, mag);
+      wave_lds_sync();
       int rank = 0;
       for (int j = 0; j < ncand; j += 4) {
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const uint64_t kj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mag, j + jj) << 32) |
-                              (uint32_t)__builtin_amdgcn_readlane((int)nfl, j + jj);
-          rank += kj > key ? 1 : 0;
-        }
+        const uint4 a = *reinterpret_cast<const uint4*>(&keys[j]);
+        const uint4 b = *reinterpret_cast<const uint4*>(&keys[j + 2]);
+        rank += ((((uint64_t)a.y << 32) | a.x) > key ? 1 : 0) + ((((uint64_t)a.w << 32) | a.z) > key ? 1 : 0);
+        rank += ((((uint64_t)b.y << 32) | b.x) > key ? 1 : 0) + ((((uint64_t)b.w << 32) | b.z) > key ? 1 : 0);
       }
       const bool selected = lane < ncand && rank < k;
       if (selected) {
         const int64_t po = (int64_t)cc * k + rank;
-        store_guarded(as_global(cur.idx) + po, (int32_t)me.y);
-        store_guarded(as_global(cur.val) + po, __uint_as_float(me.x));
+        store_guarded(as_global(cur.idx) + po, (int32_t)me_f);
+        store_guarded(as_global(cur.val) + po, __uint_as_float(me_v));
       }
-      file_selected(selected, me.y, me.x);
+      file_selected(selected, me_f, me_v);
     } else {
-      if (lane == 0 && (ncand & 1)) cand[ncand] = make_uint2(0u, 0xffffffffu);
+      if (lane == 0 && (ncand & 1)) {
+        cand_v[ncand] = 0u;
+        cand_f[ncand] = 0xffffffffu;
+      }
       wave_lds_sync();
       for (int base = 0; base < ncand; base += 64) {   // uniform trip count: the ballots below need every lane
         const int i = base + lane;
         const bool valid = i < ncand;
-        const uint2 me = cand[valid ? i : 0];
-        const uint32_t mag = me.x & 0x7fffffffu;
+        const uint32_t me_v = cand_v[valid ? i : 0], me_f = cand_f[valid ? i : 0];
+        const uint32_t mag = me_v & 0x7fffffffu;
         int rank = 0;
         for (int j = 0; j < ncand; j += 2) {
-          const uint4 o = *reinterpret_cast<const uint4*>(&cand[j]);
-          const uint32_t m0 = o.x & 0x7fffffffu, m1 = o.z & 0x7fffffffu;
-          rank += (m0 > mag || (m0 == mag && o.y < me.y)) ? 1 : 0;
-          rank += (m1 > mag || (m1 == mag && o.w < me.y)) ? 1 : 0;
+          const uint2 ov = *reinterpret_cast<const uint2*>(&cand_v[j]);
+          const uint2 of = *reinterpret_cast<const uint2*>(&cand_f[j]);
+          const uint32_t m0 = ov.x & 0x7fffffffu, m1 = ov.y & 0x7fffffffu;
+          rank += (m0 > mag || (m0 == mag && of.x < me_f)) ? 1 : 0;
+          rank += (m1 > mag || (m1 == mag && of.y < me_f)) ? 1 : 0;
         }
         const bool selected = valid && rank < k;
         if (selected) {
           const int64_t po = (int64_t)cc * k + rank;
-          store_guarded(as_global(cur.idx) + po, (int32_t)me.y);
-          store_guarded(as_global(cur.val) + po, __uint_as_float(me.x));
+          store_guarded(as_global(cur.idx) + po, (int32_t)me_f);
+          store_guarded(as_global(cur.val) + po, __uint_as_float(me_v));
         }
-        file_selected(selected, me.y, me.x);
+        file_selected(selected, me_f, me_v);
       }
     }
     // each class list is padded with zero-valued entries to a multiple of four (one MFMA step holds four)
@@ -525,17 +549,22 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     }   // STAGE != 1
     if (!GBF16) fetch_g(nxt);   // 64 registers: requested once the compact accumulators are dead
     DEMO_PHASE(6);
-    // ---- store the residual momentum -------------------------------------------------------------
-    if (!skip) {
+    // ---- store the residual momentum: always issued, so that the number of stores behind the prefetched rows
+    //      is fixed; a chunk left to the exact kernel stores through a buffer of zero records, which drops them
+    {
+      const __amdgpu_buffer_rsrc_t sres = skip ? make_rsrc_empty(nullptr) : mres;
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
-        bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
+        bstore_f4(sres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
       }
     }
     wave_lds_sync();   // the lists are rewritten by the next chunk
-    cur = nxt;
     DEMO_PHASE(7);
+    if (!has_next) break;
+    chunk += nwaves;
+    if (unit_grad_scale) momentum(std::true_type{}); else momentum(std::false_type{});
+    cur = nxt;
   }
   DEMO_PHASE_FLUSH(0);
 }
