@@ -71,6 +71,8 @@ typedef enum demo_dtype { DEMO_F32 = 0, DEMO_BF16 = 1 } demo_dtype;
 
 /* Largest supported sparsity budget per chunk (the paper uses k <= 32). */
 #define DEMO_MAX_K 256
+/* Most workers demo_decode_ex / demo_step_ex accept with phi = DEMO_PHI_IDENTITY (see demo_hparams). */
+#define DEMO_MAX_W_IDENTITY 1024
 /* Order-2 tensors must have fewer columns than this: the kernels address the rows of a chunk with 32-bit byte
  * offsets from the chunk's origin (128 rows of 4-byte elements stay below 2^31). */
 #define DEMO_MAX_COLS (1 << 22)
@@ -152,7 +154,11 @@ int demo_step(demo_ctx* ctx, const demo_tensor* tensors, int n, float beta, floa
  *   phi           DEMO_PHI_SIGN: x <- x - lr*(sgn(m_t) + weight_decay*x) (Signum);
  *                 DEMO_PHI_IDENTITY: x <- x - lr*(m_t + weight_decay*x) (SGD), same two float32
  *                 fused multiply-adds (update rule of "Momentum Reconstruction and Parameter
- *                 Update").  Muon's phi is not provided.
+ *                 Update").  Muon's phi is not provided.  Accuracy of m_t under the identity: the
+ *                 kernels sum a chunk's W payloads exactly, after rounding every value to a multiple
+ *                 of 2^-(30 - ceil(log2 W)) of the chunk's largest payload magnitude (2^-24 of it at
+ *                 W = 64, 2^-20 at W = 1024); the sign update is insensitive to that, the identity is
+ *                 not, so it is limited to W <= DEMO_MAX_W_IDENTITY (DEMO_ERR_UNSUPPORTED beyond).
  *   aggregate     DEMO_AGG_SUM: plain sum over the W payloads (algorithm boxes);
  *                 DEMO_AGG_MEAN: sum / W (the AvgAllGather of "Top-k Sparsification");
  *                 DEMO_AGG_COUNT: each coefficient's sum divided by the number of workers that

@@ -526,6 +526,9 @@ int check_hparams(const demo_hparams* hp, int need, int W) {
     if (hp->aggregate != DEMO_AGG_SUM && hp->aggregate != DEMO_AGG_MEAN && hp->aggregate != DEMO_AGG_COUNT)
       return DEMO_ERR_ARG;
     if (hp->aggregate == DEMO_AGG_COUNT && W > 255) return DEMO_ERR_ARG;
+    // the aggregate is summed in block fixed point with 30 - ceil(log2 W) fractional bits: beyond this many workers
+    // its rounding would show in the real-valued update of phi = identity (the sign update does not see it)
+    if (hp->phi == DEMO_PHI_IDENTITY && W > DEMO_MAX_W_IDENTITY) return DEMO_ERR_UNSUPPORTED;
   }
   return DEMO_OK;
 }

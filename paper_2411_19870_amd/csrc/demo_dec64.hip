@@ -272,6 +272,13 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
   load_payload(d, chunk - t_first, 0);
+  // The first payload is waited for here, outside the loop.  Inside, the wait before the scatter then only has the
+  // back edge to serve, where the next chunk's payload loads have this chunk's stores and parameter loads behind
+  // them: the compiler can let those stay in flight.  With the first payload still pending at the loop's entry it
+  // had to wait for the count of the entry path, and thereby for the acknowledgement of every store of the
+  // chunk before.
+#pragma unroll
+  for (int j = 0; j < NP; ++j) asm volatile("" : "+v"(pi[j]), "+v"(pv[j]));
   const int kap = kappa(c), col4 = 4 * chi(c);
   // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
   // for members w' even / odd (w' >= 2 adds 32 columns)

@@ -135,6 +135,10 @@ def test_hparams_struct_and_validation():
         assert lib.demo_decode_ex(h, arr1(t), 1, 1, ctypes.byref(hpb), 64, 32, None) == B.DEMO_ERR_ARG
     cnt = B.demo_hparams_default(0.9, 1e-3, 0.0, aggregate=B.DEMO_AGG_COUNT)
     assert lib.demo_decode_ex(h, arr1(t), 1, 256, ctypes.byref(cnt), 64, 32, None) == B.DEMO_ERR_ARG
+    # phi = identity beyond the worker limit of the fixed-point aggregate is refused, not computed coarsely
+    ident = B.demo_hparams_default(0.9, 1e-3, 0.0, phi=B.DEMO_PHI_IDENTITY)
+    assert lib.demo_decode_ex(h, arr1(t), 1, B.DEMO_MAX_W_IDENTITY + 1, ctypes.byref(ident), 64, 32, None) == B.DEMO_ERR_UNSUPPORTED
+    assert lib.demo_decode_ex(h, arr1(t), 1, 3000, ctypes.byref(ident), 64, 32, None) == B.DEMO_ERR_UNSUPPORTED
     nanb = B.demo_hparams_default(float("nan"), 1e-3, 0.0)
     assert lib.demo_encode_ex(h, arr1(t), 1, ctypes.byref(nanb), 64, 32, None) == B.DEMO_ERR_ARG
     assert lib.demo_step_ex(h, arr1(t), 1, ctypes.byref(nanb), 64, 32, None) == B.DEMO_ERR_ARG

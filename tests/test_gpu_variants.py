@@ -63,6 +63,36 @@ def test_decode_phi_and_aggregates(ctx, variant, s, k, W, phi, agg, pdt):
                        phi=phi, aggregate_mode=agg)
 
 
+# ---- phi = identity with many workers: the fixed-point aggregate keeps the update within its bound up to the
+#      documented worker limit; beyond it the call is refused instead of returning a coarser update ------------
+@pytest.mark.parametrize("s,k", [(64, 4), (32, 4), (128, 8)])
+@pytest.mark.parametrize("agg", ["sum", "mean"])
+def test_identity_phi_at_the_worker_limit(ctx, s, k, agg):
+    ctx.demo_set_variant(1)
+    W = B.DEMO_MAX_W_IDENTITY
+    specs = [synth.TensorSpec("a", 2 * s, 3 * s), synth.TensorSpec("v", 2 * s, 0)]
+    case = Case(specs, s, k, W=W, param_dtype=torch.float32, seed=34)
+    case.fill_payloads()
+    hp = B.demo_hparams_default(lr=LR, phi=B.DEMO_PHI_IDENTITY, aggregate=AGG[agg])
+    before = case.snapshot()
+    ctx.demo_decode_ex(case.args, W, hp, s, k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    worst = 0.0
+    for ti in range(len(case.specs)):
+        st = C.check_decode(before["x"][ti], before["idx"][ti], before["val"][ti], LR, 0.0, s, "f32", after["x"][ti],
+                            phi="identity", aggregate_mode=agg)
+        worst = max(worst, st["max_err_over_lr_Rmax"])
+    print(f"identity, W = {W}, s = {s}, {agg}: worst error {worst:.2e} of lr * max|R| (bound 1e-5 plus one ulp)")
+    big = Case(specs, s, k, W=W + 1, param_dtype=torch.float32, seed=34)
+    with pytest.raises(B.DemoError) as e:
+        ctx.demo_decode_ex(big.args, W + 1, hp, s, k)
+    assert e.value.status == B.DEMO_ERR_UNSUPPORTED
+    # the sign update takes any number of workers
+    ctx.demo_decode(big.args, W + 1, LR, 0.0, s, k)
+    torch.cuda.synchronize()
+
+
 def test_count_aggregate_with_repeated_senders(ctx):
     # every worker sends the same k indices: the count-normalised average is the mean of the values,
     # and coefficients nobody sent stay zero (0/0 = 0)
