@@ -161,8 +161,10 @@ def main():
     ap.add_argument("--s", type=int, default=S, choices=[32, 64, 128], help="chunk size")
     ap.add_argument("--k", type=int, default=K, help="coefficients kept per chunk")
     ap.add_argument("--workers", type=int, default=W, help="payloads decoded per step")
+    ap.add_argument("--projection", default="dct", choices=["dct", "random", "identity"],
+                    help="projection matrix: the DCT, or the ablation's random orthonormal matrix (seed = step 0) / identity")
     a = ap.parse_args()
-    headline = (a.s, a.k, a.workers) == (S, K, W)
+    headline = (a.s, a.k, a.workers) == (S, K, W) and a.projection == "dct"
     S, K, W = a.s, a.k, a.workers
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (the W workers' payloads are synthesised on-device); "
@@ -197,6 +199,10 @@ def main():
 
     ctx = B.Context()
     ctx.demo_set_variant(a.variant)
+    if a.projection == "random":
+        ctx.demo_set_basis(S, B.DEMO_BASIS_GRAM_SCHMIDT, synth.projection_draws(S, 0))
+    elif a.projection == "identity":
+        ctx.demo_set_basis(S, B.DEMO_BASIS_IDENTITY)
     stream = torch.cuda.current_stream()
 
     def step():
@@ -236,7 +242,10 @@ def main():
     achieved = ab[dom] / (kms[dom] * 1e-3) / 1e9
     hbm_frac = achieved / HBM_PEAK_GBS
     mfma_flops = mfma_flops_per_launch(dom, S, K, W, nchunks2, [t.idx for t, sp in zip(tensors, specs) if sp.cols]) \
-        if a.variant == 1 else None
+        if a.variant == 1 and a.projection == "dct" else None
+    if a.variant == 1 and a.projection != "dct" and S == 64 and K <= 64 and (dom == "enc2d" or W * K <= 2048):
+        # full products: 256 MFMAs each; reconstruction 16 per four kept coefficients
+        mfma_flops = (512.0 + (16.0 * math.ceil(K / 4.0) if dom == "enc2d" else 0.0)) * 2048.0 * nchunks2
     mfma_tflops = mfma_flops / (kms[dom] * 1e-3) / 1e12 if mfma_flops else None
     mfma_frac = mfma_tflops / MFMA_F32_PEAK_TFLOPS if mfma_tflops else None
     bound = "mfma" if (mfma_frac or 0.0) > hbm_frac else "hbm"
@@ -251,7 +260,7 @@ def main():
 
     out = {
         "metric": "DeMo encode+decode throughput at 1B shape" if a.workload == "1b" and headline
-                  else f"DeMo encode+decode throughput ({a.workload}, s={S}, k={K}, W={W})",
+                  else f"DeMo encode+decode throughput ({a.workload}, s={S}, k={K}, W={W}, projection {a.projection})",
         "value": step_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s",
         "params_per_s": nparams / (ms_step * 1e-3),
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
@@ -260,7 +269,7 @@ def main():
         "config": {"workload": f"{a.workload}-like tensor set: encode (grad {'bf16' if gb == 2 else 'f32'}, momentum f32) "
                                f"+ decode of W={W} payloads (param {'bf16' if gb == 2 else 'f32'})",
                    "tensors": len(specs), "params": nparams, "s": S, "k": K, "W": W, "beta": BETA, "lr": LR,
-                   "kernel_variant": a.variant},
+                   "kernel_variant": a.variant, "projection": a.projection},
         "roofline": roof,
         "kernels_ms": kms,
         "kernels_gbs": {k: (ab[k] / (v * 1e-3) / 1e9 if v else None) for k, v in kms.items()},
@@ -291,7 +300,7 @@ def main():
         wr = ab[dom] - rd
         t_mix = rd / ceil["read_only"] + wr / ceil["write_only"]
         ceil["kernel_mix_serialised"] = ab[dom] / t_mix
-        if dom == "enc2d" and S == 64 and gb == 2 and a.variant == 1 and K <= 64:
+        if dom == "enc2d" and S == 64 and gb == 2 and a.variant == 1 and K <= 64 and a.projection == "dct":
             # the encode kernel's own access pattern with the transform taken out (loads with the cross-chunk
             # prefetch, momentum update, store of m, k payload pairs per chunk)
             ctx.demo_debug_set_encode_stage(1)

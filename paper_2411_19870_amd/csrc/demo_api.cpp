@@ -30,7 +30,9 @@ struct BasisTable {
   float* enc32 = nullptr;    // dense-basis tile tables for s = 32
   float* dec32 = nullptr;    // fragment table of the s = 32 tile decode kernel
   float* custom = nullptr;   // s x s matrix set with demo_set_basis (identity / Gram-Schmidt), allocated on first use
-  bool use_custom = false;   // later calls project with `custom` on the generic kernels
+  float* custom_enc64 = nullptr;   // s = 64: tables of the full-product wavefront kernels for `custom`
+  float* custom_dec64 = nullptr;
+  bool use_custom = false;   // later calls project with `custom` (s = 64: full-product wavefront kernels, else generic)
 };
 
 // The order-2 tensors of a list that share gradient and parameter dtype: they go out in one launch per
@@ -199,7 +201,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     if (b.s == s) {
       // the wavefront kernels are built on the symmetries of the DCT: any other matrix runs on the
       // kernels that read the matrix itself
-      *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr, false}
+      *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr, false, b.custom_enc64, b.custom_dec64}
                           : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
       return DEMO_OK;
     }
@@ -564,6 +566,8 @@ int demo_destroy(demo_ctx* ctx) {
       if (b.enc32) (void)hipFree(b.enc32);
       if (b.dec32) (void)hipFree(b.dec32);
       if (b.custom) (void)hipFree(b.custom);
+      if (b.custom_enc64) (void)hipFree(b.custom_enc64);
+      if (b.custom_dec64) (void)hipFree(b.custom_dec64);
     }
     for (TableCache& tc : ctx->tables)
       if (tc.dev) (void)hipFree(tc.dev);
@@ -813,11 +817,21 @@ int demo_set_basis(demo_ctx* ctx, int s, int kind, const float* a_host) {
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) return fail_hip(ctx, e);
     const std::vector<float> host(P.begin(), P.end());   // one rounding to float32
-    if (b.custom == nullptr) {
-      if ((rc = upload(ctx, host, &b.custom)) != DEMO_OK) return rc;
-    } else {
-      e = hipMemcpy(b.custom, host.data(), host.size() * sizeof(float), hipMemcpyHostToDevice);
-      if (e != hipSuccess) return fail_hip(ctx, e);
+    auto put = [&](const std::vector<float>& h, float** dev) -> int {
+      if (*dev == nullptr) return upload(ctx, h, dev);
+      hipError_t ee = hipMemcpy(*dev, h.data(), h.size() * sizeof(float), hipMemcpyHostToDevice);
+      return ee == hipSuccess ? DEMO_OK : fail_hip(ctx, ee);
+    };
+    b.use_custom = false;
+    if ((rc = put(host, &b.custom)) != DEMO_OK) return rc;
+    if (s == 64) {
+      // tables of the wavefront kernels' full-product instances, from the float32 matrix the other kernels read
+      std::vector<double> Pr(host.begin(), host.end());
+      std::vector<float> et(demo::kEnc64DenseTableFloats), dt(demo::kDec64DenseTableFloats);
+      demo::build_enc64_dense_tables(Pr.data(), et.data());
+      demo::build_dec64_dense_tables(Pr.data(), dt.data());
+      if ((rc = put(et, &b.custom_enc64)) != DEMO_OK) return rc;
+      if ((rc = put(dt, &b.custom_dec64)) != DEMO_OK) return rc;
     }
     b.use_custom = true;
     return DEMO_OK;

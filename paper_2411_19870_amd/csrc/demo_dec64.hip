@@ -44,6 +44,17 @@ constexpr int D64_PK = 4096 + 1536;                // pk[u*16 + c]  = P[u][kappa
 constexpr int D64_PK2 = 4096 + 1536 + 1024;        // pk2[u*16 + c] = P[u][31 - kappa(c)]  (odd u: the second member)
 constexpr int D64_ALL_TABLE_FLOATS = 4096 + 1536 + 2048;
 constexpr int D64_LDS_BYTES = 4 * (D64_G_FLOATS + D64_WAVES * D64_TILE_FLOATS);
+// Instances for a projection matrix without mirror symmetry (DENSE): one fragment table serves both products,
+//   gd[((4a + b) * 64 + lane) * 4 + t] = P[16 a + 4 g + b][16 t + c]
+// (product a: B operand of the step that contracts v = 16 a + 4 g + b, output columns j = 16 t + c; product b: A
+// operand of the step that contracts u = 16 a + 4 g + b, output rows i = 16 t + c).
+constexpr int D64G_FLOATS = 4096;
+static_assert(D64G_FLOATS == kDec64DenseTableFloats, "table size");
+template <bool DENSE>
+constexpr int d64_table_floats() { return DENSE ? D64G_FLOATS : D64_G_FLOATS; }
+template <bool DENSE>
+constexpr int d64_lds_bytes() { return 4 * (d64_table_floats<DENSE>() + D64_WAVES * D64_TILE_FLOATS); }
+static_assert(d64_lds_bytes<true>() <= 160 * 1024, "LDS budget");
 static_assert(D64_ALL_TABLE_FLOATS == kDec64TableFloats, "table size");
 static_assert(D64_LDS_BYTES <= 160 * 1024, "LDS budget");
 
@@ -54,6 +65,14 @@ __host__ __device__ constexpr int member(int w, int i0) {
   return w == 0 ? i0 : w == 1 ? 31 - i0 : w == 2 ? 32 + i0 : 63 - i0;
 }
 }  // namespace
+
+void build_dec64_dense_tables(const double* P, float* out) {
+  for (int a = 0; a < 4; ++a)
+    for (int b = 0; b < 4; ++b)
+      for (int lane = 0; lane < 64; ++lane)
+        for (int t = 0; t < 4; ++t)
+          out[((4 * a + b) * 64 + lane) * 4 + t] = (float)P[(16 * a + 4 * (lane >> 4) + b) * 64 + 16 * t + (lane & 15)];
+}
 
 // Host: tables of the decode kernels from the 64 x 64 basis P (double, row-major).
 void build_dec64_tables(const double* P, float* out) {
@@ -95,15 +114,18 @@ void build_dec64_tables(const double* P, float* out) {
 // coefficient's sum divided by the number of pairs that name it), modes 0, 3 and 4 only.  NT: the 16- and 8-byte
 // payload loads of modes 3 to 5 are non-temporal (the launch wrapper asks for that when a row of k pairs fills a
 // 128-byte line; shorter rows share lines with neighbouring chunks and stay cached).
-template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true>
+// DENSE: any orthonormal 64 x 64 matrix (table of build_dec64_dense_tables): the tile holds S in its natural order,
+// both products are full (256 MFMAs each), R goes through the tile in its natural order.
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true, bool DENSE = false>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
   extern __shared__ float lds[];
   const float* sG = lds;
+  constexpr int G_FLOATS = d64_table_floats<DENSE>();
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
-  float* tile = lds + D64_G_FLOATS + wave * D64_TILE_FLOATS;
+  float* tile = lds + G_FLOATS + wave * D64_TILE_FLOATS;
   int* itile = reinterpret_cast<int*>(tile);
   constexpr bool FULL = MODE == 1;          // every payload register is in use
   constexpr bool WIDE = MODE == 1 || MODE == 2;   // 16-byte payload loads, eight workers per load
@@ -112,8 +134,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   constexpr bool STREAM = MODE == 5;        // more pairs than the registers hold: rounds of 2048
   const int k = WIDE ? 32 : args.k, W = args.W;
 
-  for (int e = tid; e < D64_G_FLOATS / 4; e += D64_THREADS)
-    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + D64_G)[e];
+  for (int e = tid; e < G_FLOATS / 4; e += D64_THREADS)
+    reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + (DENSE ? 0 : D64_G))[e];
   __syncthreads();
 
   const int nwaves = gridDim.x * D64_WAVES;
@@ -237,7 +259,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   auto slot_of = [&](int j) {
     const uint32_t u = (uint32_t)pi[j];
     // 12-bit index [u5..u0 v5..v0] -> [u1 u0 u5..u2 | v1 v0 v5..v2], then row stride 64 -> LDT
-    const uint32_t x = ((u & 0xC3u) << 4) | ((u >> 2) & 0x3CFu);
+    const uint32_t x = DENSE ? u : ((u & 0xC3u) << 4) | ((u >> 2) & 0x3CFu);
     return u < 4096u ? x + ((x >> 6) << 2) : dummy;
   };
   auto add_pairs = [&](int sh) {
@@ -296,11 +318,13 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     const uint32_t vo_dn = (uint32_t)(3 - g) * ucols + (uint32_t)col4;
     const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
                                               : make_rsrc(static_cast<const float*>(d.param) + origin);
-    u32x2 Xh[16];   // bf16 parameters, raw: requested before the scatter, used after the products
-    if (PBF16) {
+    u32x2 Xh[16];   // bf16 parameters, raw: requested before the scatter, used after the products (the
+                    // full-product instances have no registers for them until the products are done)
+    auto fetch_x = [&]() __attribute__((always_inline)) {
 #pragma unroll
       for (int q = 0; q < 16; ++q) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
-    }
+    };
+    if (PBF16 && !DENSE) fetch_x();
     DEMO_PHASE(0);
 
     // ---- S = sum over workers ---------------------------------------------------------------------------
@@ -357,10 +381,57 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     DEMO_PHASE(2);
 
     // ---- products ---------------------------------------------------------------------------------------
+    auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
+    if constexpr (DENSE) {
+      // product a per row tile ut: Y[u = 16 ut + 4g + r][j = 16 jt + c] = sum_v S[u][v] P[v][j], A = S from the tile
+      // (row 16 ut + c, four consecutive v per 16-byte read), B = fragments; the accumulators of Y are, as they lie,
+      // B operands of product b, R[i = 16 it + 4g + r'][j] += sum_u P[u][i] Y[u][j], A = the same fragments
+      f32x4 R[4][4];   // [it][jt]
+#pragma unroll
+      for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) R[it][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ut = 0; ut < 4; ++ut) {
+        const float* arow = &tile[(16 * ut + c) * D64_LDT + 4 * g];
+        float4 a[4];
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg) a[kg] = *reinterpret_cast<const float4*>(arow + 16 * kg);
+        f32x4 Y[4];
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt) Y[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kg = 0; kg < 4; ++kg)
+#pragma unroll
+          for (int kr = 0; kr < 4; ++kr) {
+            const float sv = (float)__float_as_int(comp(a[kg], kr));   // the tile holds fixed-point sums
+            const float4 gd = *reinterpret_cast<const float4*>(&sG[((4 * kg + kr) * 64 + lane) * 4]);
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) Y[jt] = mfma4(sv, comp(gd, jt), Y[jt]);
+          }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float4 gd = *reinterpret_cast<const float4*>(&sG[((4 * ut + r) * 64 + lane) * 4]);
+#pragma unroll
+          for (int it = 0; it < 4; ++it)
+#pragma unroll
+            for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma4(comp(gd, it), Y[jt][r], R[it][jt]);
+        }
+      }
+      DEMO_PHASE(3);
+      // R through the tile (dead by now) in its natural order: a store instruction covers four rows 4 * 68 words
+      // apart, i.e. 16 banks apart, and the sixteen columns fill the gaps
+#pragma unroll
+      for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) tile[(16 * it + 4 * g + r) * D64_LDT + 16 * jt + c] = R[it][jt][r];
+      if (PBF16) fetch_x();
+    } else {
     float4 G[6];
 #pragma unroll
     for (int i = 0; i < 6; ++i) G[i] = *reinterpret_cast<const float4*>(&sG[(i * 64 + lane) * 4]);
-    auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
     f32x4 Cee[4], Ceo[4], Co0[4], Co1[4];   // [w'], component s: quadruple base i0 = 4s + g
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -427,6 +498,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
           wcol[((w & 1) ? row_dn : row_up) + (16 * w + ((w & 1) ? 3 - s : s)) * D64_LDT] = rr[w];
       }
     }
+    }   // !DENSE
     wave_lds_sync();
     DEMO_PHASE(4);
 
@@ -445,7 +517,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       for (int w = 0; w < 4; ++w) {
         const int q = 4 * s + w;
         const float4 rv = *reinterpret_cast<const float4*>(
-            &tile[((w & 1) ? row_dn : row_up) + (16 * w + ((w & 1) ? 3 - s : s)) * D64_LDT + col4]);
+            DENSE ? &tile[(rho_base(q) + ((q & 1) ? 3 - g : g)) * D64_LDT + col4]
+                  : &tile[((w & 1) ? row_dn : row_up) + (16 * w + ((w & 1) ? 3 - s : s)) * D64_LDT + col4]);
         const float rr[4] = {rv.x, rv.y, rv.z, rv.w};
         float o[4];
 #pragma unroll
@@ -674,18 +747,19 @@ static hipError_t launch_dec_sparse64(const TableView& tv, const float* tables, 
   return hipGetLastError();
 }
 
-template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true>
+template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true, bool DENSE = false>
 static hipError_t launch_dec_wave64_phi(const TableView& tv, const float* tables, const DecodeArgs& a, int64_t grid,
                                         hipStream_t stream) {
   static bool attr_set = false;
+  constexpr int lds_bytes = d64_lds_bytes<DENSE>();
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE, IDENT, COUNT, NT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, D64_LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wave64<PBF16, MODE, IDENT, COUNT, NT, DENSE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE, IDENT, COUNT, NT>), dim3((unsigned)grid), dim3(D64_THREADS),
-                     D64_LDS_BYTES, stream, tv, tables, a);
+  hipLaunchKernelGGL((decode2d_wave64<PBF16, MODE, IDENT, COUNT, NT, DENSE>), dim3((unsigned)grid), dim3(D64_THREADS),
+                     lds_bytes, stream, tv, tables, a);
   return hipGetLastError();
 }
 template <bool PBF16, int MODE, bool NT>
@@ -708,6 +782,29 @@ static hipError_t launch_dec_wave64(const TableView& tv, const float* tables, co
   }
   if constexpr (MODE == 4) return launch_dec_wave64_nt<PBF16, MODE, false>(tv, tables, a, grid, stream);
   return launch_dec_wave64_nt<PBF16, MODE, true>(tv, tables, a, grid, stream);
+}
+
+// Full-product instances (any orthonormal matrix; `tables` of build_dec64_dense_tables): the whole payload of a chunk in
+// registers (W * k <= 2048), plain sum or mean, four pairs per load when k is a multiple of 4 and the arrays are
+// 16-byte aligned, else one.
+bool dense64_decode_supports(const DecodeArgs& a) { return a.k <= kFast64MaxK && (int64_t)a.W * a.k <= 2048 && a.agg != 2; }
+hipError_t launch_decode2d_dense64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
+                                   bool payload_aligned16, int num_cus, hipStream_t stream) {
+  if (!dense64_decode_supports(a)) return hipErrorInvalidValue;
+  int64_t grid = num_cus;
+  const int64_t max_grid = ((int64_t)tv.total_chunks + DEMO_RUN - 1) / DEMO_RUN;
+  if (grid > max_grid) grid = max_grid;
+  const bool vec = payload_aligned16 && a.k % 4 == 0, ident = a.phi != 0;
+  if (param_bf16) {
+    if (vec) return ident ? launch_dec_wave64_phi<true, 3, true, false, true, true>(tv, tables, a, grid, stream)
+                          : launch_dec_wave64_phi<true, 3, false, false, true, true>(tv, tables, a, grid, stream);
+    return ident ? launch_dec_wave64_phi<true, 0, true, false, true, true>(tv, tables, a, grid, stream)
+                 : launch_dec_wave64_phi<true, 0, false, false, true, true>(tv, tables, a, grid, stream);
+  }
+  if (vec) return ident ? launch_dec_wave64_phi<false, 3, true, false, true, true>(tv, tables, a, grid, stream)
+                        : launch_dec_wave64_phi<false, 3, false, false, true, true>(tv, tables, a, grid, stream);
+  return ident ? launch_dec_wave64_phi<false, 0, true, false, true, true>(tv, tables, a, grid, stream)
+               : launch_dec_wave64_phi<false, 0, false, false, true, true>(tv, tables, a, grid, stream);
 }
 
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,

@@ -48,10 +48,39 @@ constexpr int E64_LIST = E64_CAP + 64 + 2;
 constexpr int E64_SCRATCH_WORDS = 2 * E64_LIST + 2 * 64 + 3 * 2 * 64;
 static_assert(E64_LIST % 4 == 2 && (2 * E64_LIST) % 4 == 0 && E64_SCRATCH_WORDS % 4 == 0, "16-byte aligned key and list arrays");
 __host__ __device__ constexpr int kappa64(int c) { return 4 * (c & 3) + (c >> 2); }
-constexpr int E64_LDS_BYTES = 4 * (E64_TABLE_FLOATS + E64_WAVES * E64_SCRATCH_WORDS);
 static_assert(E64_TABLE_FLOATS == kEnc64TableFloats, "table size");
 
+// Tables of the instances for a projection matrix without mirror symmetry (DENSE): all four 64 x 64 floats.
+constexpr int E64G_T1 = 0;                        // t1[(q*64 + lane)*4 + t]      = P[16 t + c][rho(q, g)]            (product 1, B operand)
+constexpr int E64G_T2 = 4096;                     // t2[((4e+r)*64 + lane)*4 + vt] = P[16 vt + c][4 chi(4g+r) + e]     (product 2, A operand)
+constexpr int E64G_PCOL = 8192;                   // pcol[v*64 + 4c + e]          = P[v][4 chi(c) + e]                (reconstruction, B operand)
+constexpr int E64G_PROW = 12288;                  // prow[u*64 + 16 w + c]        = P[u][rho(4 (c%4) + w, c/4)]       (reconstruction, A operand)
+constexpr int E64G_TABLE_FLOATS = 16384;
+static_assert(E64G_TABLE_FLOATS == kEnc64DenseTableFloats, "table size");
+template <bool DENSE>
+constexpr int e64_table_floats() { return DENSE ? E64G_TABLE_FLOATS : E64_TABLE_FLOATS; }
+template <bool DENSE>
+constexpr int e64_lds_bytes() { return 4 * (e64_table_floats<DENSE>() + E64_WAVES * E64_SCRATCH_WORDS); }
+
 }  // namespace
+
+void build_enc64_dense_tables(const double* P, float* out) {
+  auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
+  for (int lane = 0; lane < 64; ++lane) {
+    const int g = lane >> 4, c = lane & 15;
+    for (int q = 0; q < 16; ++q)
+      for (int t = 0; t < 4; ++t) out[E64G_T1 + (q * 64 + lane) * 4 + t] = Pm(16 * t + c, rho(q, g));
+    for (int e = 0; e < 4; ++e)
+      for (int r = 0; r < 4; ++r)
+        for (int vt = 0; vt < 4; ++vt)
+          out[E64G_T2 + ((4 * e + r) * 64 + lane) * 4 + vt] = Pm(16 * vt + c, 4 * chi(4 * g + r) + e);
+  }
+  for (int u = 0; u < 64; ++u)
+    for (int cc = 0; cc < 16; ++cc) {
+      for (int x = 0; x < 4; ++x) out[E64G_PCOL + u * 64 + 4 * cc + x] = Pm(u, 4 * chi(cc) + x);
+      for (int w = 0; w < 4; ++w) out[E64G_PROW + u * 64 + 16 * w + cc] = Pm(u, rho(4 * (cc & 3) + w, cc >> 2));
+    }
+}
 
 void build_enc64_tables(const double* P, float* out) {
   auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
@@ -94,19 +123,24 @@ __device__ __forceinline__ Bfly butterfly(float x0, float x1, float x2, float x3
 // STAGE 0 is the kernel.  STAGE 1..3 are cut-down copies for time attribution (they do not encode): 1 = the
 // memory stream only (loads of g and m with the prefetch, momentum update, store of m, k payload pairs per chunk),
 // 2 = stage 1 plus the two products, 3 = stage 2 plus top-k and the payload (everything but the reconstruction).
-template <bool GBF16, int STAGE>   // gradient dtype of every tensor in the table
+// DENSE: the projection matrix is any orthonormal 64 x 64 matrix (tables of build_enc64_dense_tables): the same
+// register layout and the same top-k, with the full products (256 MFMAs each instead of 96) and a reconstruction
+// over all 64 rows (16 MFMAs per four selected coefficients); coefficient tiles hold u = 16 t + c, v = 16 vt + 4g + r.
+template <bool GBF16, int STAGE, bool DENSE = false>   // gradient dtype of every tensor in the table
 __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                EncodeArgs args, Worklist wl) {
   extern __shared__ float lds[];
-  const float* sT1 = lds + E64_T1;
-  const float* sT2 = lds + E64_T2;
-  const float* sPcol = lds + E64_PCOL;
+  constexpr int TABLE_FLOATS = e64_table_floats<DENSE>();
+  const float* sT1 = lds + (DENSE ? E64G_T1 : E64_T1);
+  const float* sT2 = lds + (DENSE ? E64G_T2 : E64_T2);
+  const float* sPcol = lds + (DENSE ? E64G_PCOL : E64_PCOL);
   const float* sPk = lds + E64_PK;
   const float* sPk2 = lds + E64_PK2;
+  const float* sProw = lds + E64G_PROW;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
-  uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + E64_TABLE_FLOATS) + wave * E64_SCRATCH_WORDS;
+  uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + TABLE_FLOATS) + wave * E64_SCRATCH_WORDS;
   uint32_t* cand_v = scratch;                                            // value bits of the candidates
   uint32_t* cand_f = scratch + E64_LIST;                                 // their flat indices
   uint2* keys = reinterpret_cast<uint2*>(scratch + 2 * E64_LIST);        // {~flat index, magnitude bits}
@@ -117,7 +151,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   uint32_t list_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(lds_u32*)cand_v);
   asm volatile("" : "+s"(list_base));
 
-  for (int e = tid; e < E64_TABLE_FLOATS / 4; e += E64_THREADS)
+  for (int e = tid; e < TABLE_FLOATS / 4; e += E64_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables)[e];
   __syncthreads();
 
@@ -134,7 +168,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
 
   // lane constants: column offset, and flat-index bases u(t,c)*64 + v(vt,4g) of the coefficient tiles
   const int col4 = 4 * chi(c);
-  uint32_t fb_a = (uint32_t)(256 * c + 16 * g), fb_b = (uint32_t)(256 * c + 8 * g);
+  uint32_t fb_a = DENSE ? (uint32_t)(64 * c + 4 * g) : (uint32_t)(256 * c + 16 * g), fb_b = (uint32_t)(256 * c + 8 * g);
   uint32_t fb_c = (uint32_t)(128 * c + 16 * g), fb_d = (uint32_t)(128 * c + 8 * g);
 
   // Where a chunk lives: row rho(4s+w, g) = rbase(q) + (w even ? g : 3 - g), i.e. a uniform part
@@ -253,7 +287,18 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     for (int e = 0; e < 4; ++e)
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) C1[e][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    {
+    if constexpr (DENSE) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const float4 p4 = *reinterpret_cast<const float4*>(&sT1[(q * 64 + lane) * 4]);
+        const float pt[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) C1[e][tt] = mfma4(D[q >> 2][e][q & 3], pt[tt], C1[e][tt]);
+        if ((q & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
       const float4 pee4 = *reinterpret_cast<const float4*>(&sT1[(0 * 64 + lane) * 4]);
       const float4 peo4 = *reinterpret_cast<const float4*>(&sT1[(1 * 64 + lane) * 4]);
       const float pee[4] = {pee4.x, pee4.y, pee4.z, pee4.w}, peo[4] = {peo4.x, peo4.y, peo4.z, peo4.w};
@@ -281,7 +326,18 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     for (int vt = 0; vt < 4; ++vt)
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    {
+    if constexpr (DENSE) {
+#pragma unroll
+      for (int er = 0; er < 16; ++er) {
+        const float4 p4 = *reinterpret_cast<const float4*>(&sT2[(er * 64 + lane) * 4]);
+        const float pv4[4] = {p4.x, p4.y, p4.z, p4.w};
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int vt = 0; vt < 4; ++vt) C2[vt][tt] = mfma4(pv4[vt], C1[er >> 2][tt][er & 3], C2[vt][tt]);
+        if ((er & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
       const float4 pee4 = *reinterpret_cast<const float4*>(&sT2[(0 * 64 + lane) * 4]);
       const float4 peo4 = *reinterpret_cast<const float4*>(&sT2[(1 * 64 + lane) * 4]);
       const float pee[4] = {pee4.x, pee4.y, pee4.z, pee4.w}, peo[4] = {peo4.x, peo4.y, peo4.z, peo4.w};
@@ -304,8 +360,9 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     }
 
     // lands while top-k, reconstruction and store of this chunk run (after the last chunk the same
-    // chunk is simply requested again: an unconditional fetch keeps the old registers dead)
-    fetch_m(nxt);
+    // chunk is simply requested again: an unconditional fetch keeps the old registers dead).  The full-product
+    // instances are bound by their MFMAs and short of registers: they request the rows behind the reconstruction
+    if (!DENSE) fetch_m(nxt);
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(2);
@@ -358,8 +415,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
             if (mask != 0) {
               if (is && ncand <= E64_CAP) {   // a full list takes no more: slot < CAP + 64 without a per-lane clamp
                 lds_u32* slot = lds_u32_at(list_end + 4u * (uint32_t)lanes_below(mask));
-                const uint32_t fbase = tt < 2 ? (vt < 2 ? fb_a : fb_b) : (vt < 2 ? fb_c : fb_d);
-                const uint32_t fconst = (uint32_t)(64 * freq(tt, 0) + freq(vt, r));
+                const uint32_t fbase = DENSE ? fb_a : tt < 2 ? (vt < 2 ? fb_a : fb_b) : (vt < 2 ? fb_c : fb_d);
+                const uint32_t fconst = DENSE ? (uint32_t)(1024 * tt + 16 * vt + r) : (uint32_t)(64 * freq(tt, 0) + freq(vt, r));
                 slot[0] = __float_as_uint(q);
                 slot[E64_LIST] = fbase + fconst;
               }
@@ -393,7 +450,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     int ncls[3] = {0, 0, 0};
     auto file_selected = [&](bool selected, uint32_t flat, uint32_t vbits) {
       const uint32_t u = flat >> 6;
-      const int cls = (u & 1u) ? 2 : (int)((u >> 1) & 1u);
+      const int cls = DENSE ? 0 : (u & 1u) ? 2 : (int)((u >> 1) & 1u);   // DENSE: one list (at most 64 long, as k <= 64)
 #pragma unroll
       for (int q = 0; q < 3; ++q) {
         const uint64_t m = __ballot(selected && cls == q);
@@ -458,7 +515,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     for (int q = 0; q < 3; ++q)
       if (lane < ((4 - (ncls[q] & 3)) & 3)) sel[q * 64 + ncls[q] + lane] = make_uint2(0u, 0u);
     wave_lds_sync();
-    if (GBF16) fetch_g(nxt);   // the coefficient registers are dead now (fp32 gradients: twice the registers, see below)
+    if (GBF16 && !DENSE) fetch_g(nxt);   // the coefficient registers are dead now (fp32 gradients: twice the registers, see below)
     __builtin_amdgcn_sched_barrier(0);
 
     DEMO_PHASE(5);
@@ -469,7 +526,30 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     //        D[i0] += ee+eo+o0, D[31-i0] += ee-eo+o1, D[32+i0] += ee-eo-o1, D[63-i0] += ee+eo-o0.
     //      MFMA row m = 4g + r of a compact tile is the base i0 = kappa(m) = 4r + g, i.e. component s = r of D.
     //      The classes are done one after the other so that at most two compact accumulators are alive.
-    if (!skip && STAGE == 0) {
+    if constexpr (DENSE) {
+      if (!skip && STAGE == 0) {
+        // D[r][e][w] -= alpha sum_t val_t P[u_t][rho(4r + w, g)] P[v_t][4 chi(c) + e]: MFMA row m = 4g + r of the
+        // tile of member w is row rho(4r + w, g); one member per pass over the list keeps the accumulators at 16 registers
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          f32x4 Ra[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) Ra[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          for (int ks = 0; ks < (ncls[0] + 3) / 4; ++ks) {
+            const uint2 sv = sel[4 * ks + g];
+            const float a0 = -(args.alpha * __uint_as_float(sv.y)) * sProw[((sv.x >> 6) & 63u) * 64 + c + 16 * w];
+            const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
+            const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Ra[e] = mfma4(a0, bf[e], Ra[e]);
+          }
+#pragma unroll
+          for (int sq = 0; sq < 4; ++sq)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) D[sq][e][w] += Ra[e][sq];
+        }
+      }
+    } else if (!skip && STAGE == 0) {
       {
         f32x4 Ree[4];
 #pragma unroll
@@ -547,7 +627,8 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
 
     }   // STAGE != 2
     }   // STAGE != 1
-    if (!GBF16) fetch_g(nxt);   // 64 registers: requested once the compact accumulators are dead
+    if (DENSE) fetch_m(nxt);
+    if (GBF16 ? DENSE : !DENSE) fetch_g(nxt);   // 64 registers: requested once the compact accumulators are dead
     DEMO_PHASE(6);
     // ---- store the residual momentum: always issued, so that the number of stores behind the prefetched rows
     //      is fixed; a chunk left to the exact kernel stores through a buffer of zero records, which drops them
@@ -559,6 +640,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
         bstore_f4(sres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rbase(q) * ucols * 4, o);
       }
     }
+    if (DENSE && !GBF16) fetch_g(nxt);   // float32 gradients of the full-product instances: no registers before the stores
     wave_lds_sync();   // the lists are rewritten by the next chunk
     DEMO_PHASE(7);
     if (!has_next) break;
@@ -569,26 +651,32 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   DEMO_PHASE_FLUSH(0);
 }
 
-template <bool GBF16, int STAGE>
+template <bool GBF16, int STAGE, bool DENSE = false>
 static hipError_t launch_enc_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                     int64_t grid, hipStream_t stream) {
   static bool attr_set = false;
+  constexpr int lds_bytes = e64_lds_bytes<DENSE>();
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_wave64<GBF16, STAGE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, E64_LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_wave64<GBF16, STAGE, DENSE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((encode2d_wave64<GBF16, STAGE>), dim3((unsigned)grid), dim3(E64_THREADS), E64_LDS_BYTES, stream, tv,
+  hipLaunchKernelGGL((encode2d_wave64<GBF16, STAGE, DENSE>), dim3((unsigned)grid), dim3(E64_THREADS), lds_bytes, stream, tv,
                      tables, a, wl);
   return hipGetLastError();
 }
 
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
-                                  bool grad_bf16, int num_cus, hipStream_t stream) {
+                                  bool grad_bf16, bool dense, int num_cus, hipStream_t stream) {
   int64_t grid = num_cus;
   const int64_t max_grid = ((int64_t)tv.total_chunks + DEMO_RUN - 1) / DEMO_RUN;   // few items: one run per workgroup, spread over the CUs
   if (grid > max_grid) grid = max_grid;
+  if (dense) {   // `tables` are those of build_enc64_dense_tables
+    if (a.stage != 0) return hipErrorInvalidValue;
+    return grad_bf16 ? launch_enc_wave64<true, 0, true>(tv, tables, a, wl, grid, stream)
+                     : launch_enc_wave64<false, 0, true>(tv, tables, a, wl, grid, stream);
+  }
   if (a.stage != 0) {   // time attribution only (bfloat16 gradients)
     if (!grad_bf16) return hipErrorInvalidValue;
     switch (a.stage) {

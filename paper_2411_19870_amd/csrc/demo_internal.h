@@ -76,6 +76,8 @@ struct BasisTables {
   const float* enc32;    // dense-basis tile tables for diag(P32, P32) (s = 32 only, else null)
   const float* dec32;    // fragment table of the wavefront-per-tile decode kernel (s = 32 only, else null)
   bool dct;              // `basis` is the orthonormal DCT-II (false: a matrix set by the caller)
+  const float* enc64g = nullptr;   // s = 64, matrix set by the caller: tables of the full-product wavefront kernels
+  const float* dec64g = nullptr;
 };
 
 // Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:
@@ -113,8 +115,11 @@ constexpr int kDec64TableFloats = 4096 + 1536 + 2048;
 constexpr int kFast64MaxK = 64;
 void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
 void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
+// ... and their instances for a projection matrix without mirror symmetry: full products, other tables
+constexpr int kEnc64DenseTableFloats = 4 * 4096;
+void build_enc64_dense_tables(const double* P, float* out /* kEnc64DenseTableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
-                                  bool grad_bf16, int num_cus, hipStream_t stream);
+                                  bool grad_bf16, bool dense, int num_cus, hipStream_t stream);
 // dense-basis tile kernel (demo_enc64d.hip)
 constexpr int kEnc64dTableFloats = 1024 + 4096 + 512;
 void build_enc64d_tables(const double* B64, float* out /* kEnc64dTableFloats */);
@@ -159,5 +164,11 @@ inline bool fast64_decode_supports(int W, int k, bool payload_aligned16) {
 }
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream);
+// ... and its instances for a projection matrix without mirror symmetry
+constexpr int kDec64DenseTableFloats = 4096;
+void build_dec64_dense_tables(const double* P, float* out /* kDec64DenseTableFloats */);
+bool dense64_decode_supports(const DecodeArgs& a);
+hipError_t launch_decode2d_dense64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
+                                   bool payload_aligned16, int num_cus, hipStream_t stream);
 
 }  // namespace demo

@@ -1153,7 +1153,14 @@ hipError_t launch_encode2d(const TableView& tv, const TableView* tiles, const Ba
   if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.enc64 != nullptr && wl.list != nullptr &&
       (gmix == 1u || gmix == 2u)) {
     // wavefront-per-chunk kernel, then the exact generic kernel over whatever it queued
-    hipError_t e = launch_encode2d_wave64(tv, bt.enc64, a, wl, gmix == 1u, num_cus, stream);
+    hipError_t e = launch_encode2d_wave64(tv, bt.enc64, a, wl, gmix == 1u, false, num_cus, stream);
+    if (e != hipSuccess) return e;
+    return launch_enc2d_generic<64>(tv, basis, a, wl, num_cus, stream);
+  }
+  if (variant >= 1 && s == 64 && a.k <= kFast64MaxK && bt.enc64g != nullptr && !bt.dct && a.stage == 0 &&
+      wl.list != nullptr && (gmix == 1u || gmix == 2u)) {
+    // any orthonormal matrix: the same wavefront-per-chunk kernel with the full products
+    hipError_t e = launch_encode2d_wave64(tv, bt.enc64g, a, wl, gmix == 1u, true, num_cus, stream);
     if (e != hipSuccess) return e;
     return launch_enc2d_generic<64>(tv, basis, a, wl, num_cus, stream);
   }
@@ -1187,6 +1194,9 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
       fast64_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 &&
       bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
+  if (variant >= 1 && s == 64 && !bt.dct && bt.dec64g != nullptr && dense64_decode_supports(a) && payload_fits32 &&
+      (pmix == 1u || pmix == 2u))
+    return launch_decode2d_dense64(tv, bt.dec64g, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
   if (variant >= 1 && s == 128 && a.mirror != 0 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast128MaxPairs) &&
       fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wg128(tv, bt.basis, a, pmix == 1u, num_cus, stream);

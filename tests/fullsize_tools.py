@@ -126,17 +126,17 @@ def _stack(blocks: np.ndarray) -> np.ndarray:
 # ---------------------------------------------------------------------------------------------------
 # jobs (run in the worker processes)
 # ---------------------------------------------------------------------------------------------------
-def encode_job(m0, g0, beta, s, k, idx, val, m1, tag):
+def encode_job(m0, g0, beta, s, k, idx, val, m1, tag, P=None):
     try:
-        st = C.check_encode(_stack(m0), _stack(g0), beta, s, k, idx, val, _stack(m1))
+        st = C.check_encode(_stack(m0), _stack(g0), beta, s, k, idx, val, _stack(m1), P=P)
     except AssertionError as e:
         raise AssertionError(f"{tag}: {e}") from None
     return st
 
 
-def decode_job(x0, idx, val, lr, wd, s, pdt, x1, tag):
+def decode_job(x0, idx, val, lr, wd, s, pdt, x1, tag, P=None):
     try:
-        st = C.check_decode(_stack(x0), idx, val, lr, wd, s, pdt, _stack(x1).astype(np.float32))
+        st = C.check_decode(_stack(x0), idx, val, lr, wd, s, pdt, _stack(x1).astype(np.float32), P=P)
     except AssertionError as e:
         raise AssertionError(f"{tag}: {e}") from None
     return st

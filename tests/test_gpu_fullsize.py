@@ -48,7 +48,7 @@ def gather(tensors, specs, s, picks, field):
     return {ti: F.gather_blocks(getattr(tensors[ti], field), specs[ti], s, ch) for ti, ch in picks.items()}
 
 
-def submit_encode(pool, tally, specs, tensors, s, k, picks, m0, g0, tag):
+def submit_encode(pool, tally, specs, tensors, s, k, picks, m0, g0, tag, P=None):
     m1 = gather(tensors, specs, s, picks, "mom")
     for ti, ch in picks.items():
         ci = torch.as_tensor(ch, device=DEV)
@@ -56,10 +56,10 @@ def submit_encode(pool, tally, specs, tensors, s, k, picks, m0, g0, tag):
         val = tensors[ti].val[0][ci].cpu().numpy()
         for a, b in F.split(len(ch), specs[ti].chunk_elems(s)):
             tally.add(pool.submit(F.encode_job, m0[ti][a:b], g0[ti][a:b], BETA, s, k, idx[a:b], val[a:b], m1[ti][a:b],
-                                  f"{tag} encode {specs[ti].name} chunks {ch[a]}..{ch[b - 1]}"))
+                                  f"{tag} encode {specs[ti].name} chunks {ch[a]}..{ch[b - 1]}", P))
 
 
-def submit_decode(pool, tally, specs, tensors, s, k, W, picks, x0, pdt, tag):
+def submit_decode(pool, tally, specs, tensors, s, k, W, picks, x0, pdt, tag, P=None):
     x1 = gather(tensors, specs, s, picks, "param")
     for ti, ch in picks.items():
         ci = torch.as_tensor(ch, device=DEV)
@@ -67,7 +67,7 @@ def submit_decode(pool, tally, specs, tensors, s, k, W, picks, x0, pdt, tag):
         val = tensors[ti].val[:W][:, ci].cpu().numpy()
         for a, b in F.split(len(ch), specs[ti].chunk_elems(s) * max(1, W * k // 1024)):
             tally.add(pool.submit(F.decode_job, x0[ti][a:b], idx[:, a:b], val[:, a:b], LR, 0.0, s, pdt, x1[ti][a:b],
-                                  f"{tag} decode W={W} {specs[ti].name} chunks {ch[a]}..{ch[b - 1]}"))
+                                  f"{tag} decode W={W} {specs[ti].name} chunks {ch[a]}..{ch[b - 1]}", P))
 
 
 def check_any_size_properties(specs, tensors, s, energy_mid):
@@ -94,13 +94,20 @@ def sample_report(specs, s, picks):
     return f"{c2} of {n2} order-2 chunks ({100.0 * c2 / n2:.1f} %), all {c1} order-1 chunks"
 
 
-def encode_then_decodes(pool, name, s, k, Ws, gdt, pdt, seed):
+def encode_then_decodes(pool, name, s, k, Ws, gdt, pdt, seed, projection_step=None):
     """Encode, then one decode per entry of Ws (W = 1 applies the payload just written; larger W the
-    synthetic payloads with the encode output in worker slot 0), each checked on the sample."""
+    synthetic payloads with the encode output in worker slot 0), each checked on the sample.
+    projection_step: use the random orthonormal projection matrix of that step instead of the DCT."""
     Wmax = max(Ws)
     specs, tensors = make_set(name, s, k, Wmax, gdt, pdt, seed)
     tl = B.TensorList(tensors)
     ctx = B.Context()
+    P = None
+    if projection_step is not None:
+        from oracle import demo_oracle as O
+        draws = synth.projection_draws(s, projection_step)
+        ctx.demo_set_basis(s, B.DEMO_BASIS_GRAM_SCHMIDT, draws)
+        P = O.gram_schmidt(draws.double().numpy())
     pd = "bf16" if pdt == torch.bfloat16 else "f32"
     picks = F.pick_chunks(specs, s, FRAC, seed)
     tally_e, tally_d = F.Tally(), F.Tally()
@@ -108,13 +115,13 @@ def encode_then_decodes(pool, name, s, k, Ws, gdt, pdt, seed):
     energy_mid = energy_of_update(tensors)
     ctx.demo_encode(tl, BETA, s, k)
     torch.cuda.synchronize()
-    submit_encode(pool, tally_e, specs, tensors, s, k, picks, m0, g0, f"{name} s={s} k={k}")
+    submit_encode(pool, tally_e, specs, tensors, s, k, picks, m0, g0, f"{name} s={s} k={k}", P)
     check_any_size_properties(specs, tensors, s, energy_mid)
     for W in Ws:
         x0 = gather(tensors, specs, s, picks, "param")
         ctx.demo_decode(tl, W, LR, 0.0, s, k)
         torch.cuda.synchronize()
-        submit_decode(pool, tally_d, specs, tensors, s, k, W, picks, x0, pd, f"{name} s={s} k={k}")
+        submit_decode(pool, tally_d, specs, tensors, s, k, W, picks, x0, pd, f"{name} s={s} k={k}", P)
     se, sd = tally_e.drain(), tally_d.drain()
     ctx.close()
     print(f"{name} s={s} k={k} W={Ws} {gdt} / {pdt}: {sample_report(specs, s, picks)}; encode {se}; decode {sd}")
@@ -137,6 +144,13 @@ def test_full_size_300m_fp32(pool):
 @pytest.mark.parametrize("s,k,W", [(32, 8, 16), (32, 32, 1), (128, 32, 8)])
 def test_full_size_300m_fp32_other_chunk_sizes(pool, s, k, W):
     encode_then_decodes(pool, "300m", s, k, [W], torch.float32, torch.float32, 3)
+
+
+# ---- the ablation's random orthonormal projection (Gaussian entries, Gram-Schmidt, seed = step number) at full size:
+#      the full-product instances of the s = 64 wavefront kernels walk their persistent loops -------------------------
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+def test_full_size_300m_random_projection(pool, gdt):
+    encode_then_decodes(pool, "300m", 64, 32, [1, 16], gdt, gdt, 4, projection_step=7)
 
 
 # ---- stress sweep at full size: heavy-tailed bf16 gradients (exact magnitude ties), momentum carried over 10

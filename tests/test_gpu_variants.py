@@ -246,6 +246,41 @@ def test_other_projection_matrices(ctx, s, k, kind, dt):
         ctx.demo_set_basis(s, B.DEMO_BASIS_DCT)
 
 
+# ---- s = 64 with another matrix runs on the full-product instances of the wavefront kernels: budgets, worker counts,
+#      both payload access modes, the identity update and the other scalars, against the same oracle ---------------
+@pytest.mark.parametrize("W,k", [(1, 32), (8, 32), (64, 32), (5, 7), (3, 1), (16, 64), (100, 20), (2, 33)])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("phi", ["sign", "identity"])
+def test_random_projection_on_the_wavefront_kernels(ctx, W, k, dt, phi):
+    s = 64
+    ctx.demo_set_variant(1)
+    specs = [synth.TensorSpec("a", 384, 640), synth.TensorSpec("v0", 256, 0), synth.TensorSpec("b", 2048, 1536)]
+    case = Case(specs, s, k, W=W, grad_dtype=dt, param_dtype=dt, seed=41)
+    a, P = _projection(s, "gram_schmidt", step=W + k)
+    pd = "bf16" if dt == torch.bfloat16 else "f32"
+    try:
+        ctx.demo_set_basis(s, B.DEMO_BASIS_GRAM_SCHMIDT, a)
+        hp = B.demo_hparams_default(0.9, LR, 0.05, alpha=0.5, grad_scale=0.25, phi=PHI[phi],
+                                    aggregate=B.DEMO_AGG_MEAN if phi == "identity" else B.DEMO_AGG_SUM)
+        before = case.snapshot()
+        ctx.demo_encode_ex(case.args, hp, s, k)
+        torch.cuda.synchronize()
+        after = case.snapshot()
+        for ti in range(len(case.specs)):
+            C.check_encode(before["m"][ti], before["g"][ti], 0.9, s, k, after["idx"][ti][0], after["val"][ti][0],
+                           after["m"][ti], alpha32=0.5, grad_scale32=0.25, P=P)
+        case.fill_payloads(exact=False)
+        before = case.snapshot()
+        ctx.demo_decode_ex(case.args, W, hp, s, k)
+        torch.cuda.synchronize()
+        after = case.snapshot()
+        for ti in range(len(case.specs)):
+            C.check_decode(before["x"][ti], before["idx"][ti], before["val"][ti], LR, 0.05, s, pd, after["x"][ti],
+                           phi=phi, aggregate_mode="mean" if phi == "identity" else "sum", P=P)
+    finally:
+        ctx.demo_set_basis(s, B.DEMO_BASIS_DCT)
+
+
 def test_new_matrix_every_step_then_back_to_dct(ctx):
     # the paper's random projection: a fresh matrix per step, seeded with the step number
     s, k = 64, 16
