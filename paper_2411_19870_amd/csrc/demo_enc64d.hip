@@ -22,8 +22,11 @@ constexpr int ED_PK = 1024 + 4096;                // pk[u*16 + c] = B[u][kappa(c
 constexpr int ED_TABLE_FLOATS = 1024 + 4096 + 512;
 constexpr int ED_SELCLS = 2 * 64;                 // selected coefficients per class (row block, parity of u): 2 chunks x k <= 64
 constexpr int ED_SELMAX = 4 * ED_SELCLS;
-// per-wavefront scratch: candidates {value bits, flat} [CAP + 2], selected {position in tile, value bits} [SELMAX]
-constexpr int ED_SCRATCH_WORDS = 2 * (ED_CAP + 2) + 2 * ED_SELMAX;
+// per-wavefront scratch: candidate value bits [LIST], candidate flat indices [LIST] (one gather step appends up to 64
+// entries to a list of at most CAP), 64-bit sort keys [64], selected {position in tile, value bits} [SELMAX]
+constexpr int ED_LIST = ED_CAP + 64 + 2;
+constexpr int ED_SCRATCH_WORDS = 2 * ED_LIST + 2 * 64 + 2 * ED_SELMAX;
+static_assert((2 * ED_LIST) % 4 == 0 && ED_SCRATCH_WORDS % 4 == 0 && ED_TABLE_FLOATS % 4 == 0, "16-byte aligned key array");
 constexpr int ED_LDS_BYTES = 4 * (ED_TABLE_FLOATS + ED_WAVES * ED_SCRATCH_WORDS);
 static_assert(ED_TABLE_FLOATS == kEnc64dTableFloats, "table size");
 }  // namespace
@@ -61,8 +64,13 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
   uint32_t* scratch = reinterpret_cast<uint32_t*>(lds + ED_TABLE_FLOATS) + wave * ED_SCRATCH_WORDS;
-  uint2* cand = reinterpret_cast<uint2*>(scratch);                      // {value bits, flat index in the chunk}
-  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * (ED_CAP + 2));    // [4][SELCLS] {u*64 + tile column frequency, value bits} by class
+  uint32_t* cand_v = scratch;                                           // value bits of the candidates
+  uint32_t* cand_f = scratch + ED_LIST;                                 // their flat indices in the chunk
+  uint2* keys = reinterpret_cast<uint2*>(scratch + 2 * ED_LIST);        // {~flat index, magnitude bits}
+  uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * ED_LIST + 128);   // [4][SELCLS] {u*64 + tile column frequency, value bits} by class
+  // LDS byte address of cand_v[0] as a scalar the compiler cannot take apart
+  uint32_t list_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(lds_u32*)cand_v);
+  asm volatile("" : "+s"(list_base));
   const int k = args.k;
 
   for (int e = tid; e < ED_TABLE_FLOATS / 4; e += ED_THREADS)
@@ -130,6 +138,15 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   Place cur = place(d, tileno - t_first);
   fetch_m(cur);
   fetch_g(cur);
+  // The first tile's rows are waited for here, outside the loop: the wait at the top of the body then only has
+  // the back edge to serve, where the rows have the stores of the tile before behind them, and the compiler can
+  // leave those stores in flight instead of waiting for their acknowledgement.
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    asm volatile("" : "+v"(nm[q]));
+    if (GBF16) asm volatile("" : "+v"(ng[q]));
+    else asm volatile("" : "+v"(ngf[q]));
+  }
 
   for (; tileno < total; tileno += nwaves) {
     const uint32_t ucols = cur.ucols, vo_up = cur.vo_up, vo_dn = cur.vo_dn;
@@ -235,6 +252,7 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
         if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
       }
       int ncand = 0;
+      uint32_t list_end = list_base;   // scalar LDS byte address of the list's end
       {
         const float thr_f = __uint_as_float(thr);
 #pragma unroll
@@ -247,11 +265,14 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
               const bool is = fabsf(q) >= thr_f;
               const uint64_t mask = __ballot(is);
               if (mask != 0) {
-                if (is) {
-                  const int pos = min((int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, (uint32_t)ncand)), ED_CAP);
-                  cand[pos] = make_uint2(__float_as_uint(q), fb + (uint32_t)(32 * nh + mh + 2 * r));
+                if (is && ncand <= ED_CAP) {   // a full list takes no more: slot < CAP + 64 without a per-lane clamp
+                  lds_u32* slot = lds_u32_at(list_end + 4u * (uint32_t)lanes_below(mask));
+                  slot[0] = __float_as_uint(q);
+                  slot[ED_LIST] = fb + (uint32_t)(32 * nh + mh + 2 * r);
                 }
-                ncand += __popcll(mask);
+                const int hits = __popcll(mask);
+                ncand += hits;
+                list_end += 4u * (uint32_t)hits;
               }
             }
       }
@@ -270,25 +291,27 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
         // rank the candidates (magnitude descending, flat index ascending); ranks < k are the payload
         for (int i0 = 0; i0 < ncand; i0 += 64) {
           const int i = i0 + lane;
-          const uint2 me = cand[i < ncand ? i : 0];
+          const uint2 me = make_uint2(cand_v[i < ncand ? i : 0], cand_f[i < ncand ? i : 0]);
           const uint32_t mag = me.x & 0x7fffffffu;
           int rank = 0;
           if (ncand <= 64) {
+            // the lanes put their 64-bit keys {magnitude, ~flat index} into LDS and every lane reads all of them back,
+            // two per 16-byte read at a wavefront-uniform address (lanes past the list carry key 0, which precedes nothing)
             const uint32_t magl = i < ncand ? mag : 0u, nfl = i < ncand ? ~me.y : 0u;
             const uint64_t key = ((uint64_t)magl << 32) | nfl;
+            keys[lane] = make_uint2(nfl, magl);
+            wave_lds_sync();
             for (int j = 0; j < ncand; j += 4) {
-#pragma unroll
-              for (int jj = 0; jj < 4; ++jj) {
-                const uint64_t kj = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)magl, j + jj) << 32) |
-                                    (uint32_t)__builtin_amdgcn_readlane((int)nfl, j + jj);
-                rank += kj > key ? 1 : 0;
-              }
+              const uint4 a = *reinterpret_cast<const uint4*>(&keys[j]);
+              const uint4 b = *reinterpret_cast<const uint4*>(&keys[j + 2]);
+              rank += ((((uint64_t)a.y << 32) | a.x) > key ? 1 : 0) + ((((uint64_t)a.w << 32) | a.z) > key ? 1 : 0);
+              rank += ((((uint64_t)b.y << 32) | b.x) > key ? 1 : 0) + ((((uint64_t)b.w << 32) | b.z) > key ? 1 : 0);
             }
           } else {
             for (int j = 0; j < ncand; ++j) {
-              const uint2 o = cand[j];
-              const uint32_t mo = o.x & 0x7fffffffu;
-              rank += (mo > mag || (mo == mag && o.y < me.y)) ? 1 : 0;
+              const uint32_t ov = cand_v[j], of = cand_f[j];
+              const uint32_t mo = ov & 0x7fffffffu;
+              rank += (mo > mag || (mo == mag && of < me.y)) ? 1 : 0;
             }
           }
           const bool selected = i < ncand && rank < k;
@@ -357,11 +380,14 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
       }
     }
     if (!GBF16) fetch_g(nxt);
-    if (!skip) {
+    {
+      // always issued, so that the number of stores behind the prefetched rows is fixed; a tile left to the exact
+      // kernel stores through a buffer of zero records, which drops them
+      const __amdgpu_buffer_rsrc_t sres = skip ? make_rsrc_empty(nullptr) : mres;
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const f32x4 o = {D[q >> 2][0][q & 3], D[q >> 2][1][q & 3], D[q >> 2][2][q & 3], D[q >> 2][3][q & 3]};
-        bstore_f4(mres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(q) * ucols * 4, o);
+        bstore_f4(sres, ((q & 1) ? vo_dn : vo_up) * 4, (uint32_t)rho_base(q) * ucols * 4, o);
       }
     }
     wave_lds_sync();
