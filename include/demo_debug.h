@@ -57,6 +57,13 @@ int demo_stream_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes,
  * another projection matrix while a stage is set returns DEMO_ERR_UNSUPPORTED.  */
 int demo_debug_set_encode_stage(demo_ctx* ctx, int stage);
 
+/* The same for the s = 64 decode kernel (64 < W * k <= 2048, sum or mean): stage 1 = the memory stream only
+ * (payload and parameter loads with the cross-chunk prefetch, update of the parameters with whatever the tile
+ * holds, stores); 2 = stage 1 plus the scatter-add into the tile; 0 = the real kernel.  Parameters after a
+ * stage 1 or 2 call are meaningless.  DEMO_ERR_ARG outside 0..2; calls the stages do not cover return
+ * DEMO_ERR_UNSUPPORTED while one is set.  */
+int demo_debug_set_decode_stage(demo_ctx* ctx, int stage);
+
 #ifdef __cplusplus
 }
 #endif

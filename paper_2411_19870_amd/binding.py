@@ -31,7 +31,7 @@ EXPORTS = [
     "demo_encode_noalloc", "demo_strerror", "demo_last_hip_error",
     # include/demo_debug.h: measurement and test hooks
     "demo_set_timing", "demo_last_kernel_ms", "demo_set_variant", "demo_copy_probe", "demo_stream_probe",
-    "demo_debug_set_encode_stage",
+    "demo_debug_set_encode_stage", "demo_debug_set_decode_stage",
 ]
 
 
@@ -91,6 +91,7 @@ def load_library() -> ctypes.CDLL:
     lib.demo_copy_probe.argtypes = [vp, vp, vp, i64, vp]
     lib.demo_stream_probe.argtypes = [vp, vp, vp, i64, ci, vp]
     lib.demo_debug_set_encode_stage.argtypes = [vp, ci]
+    lib.demo_debug_set_decode_stage.argtypes = [vp, ci]
     lib.demo_strerror.argtypes = [ci]
     lib.demo_strerror.restype = ctypes.c_char_p
     lib.demo_last_hip_error.argtypes = [vp]
@@ -276,6 +277,9 @@ class Context:
 
     def demo_debug_set_encode_stage(self, stage: int):
         self._check(self._lib.demo_debug_set_encode_stage(self._h, stage))
+
+    def demo_debug_set_decode_stage(self, stage: int):
+        self._check(self._lib.demo_debug_set_decode_stage(self._h, stage))
 
     def demo_last_kernel_ms(self, which: int) -> float:
         ms = ctypes.c_float(0)

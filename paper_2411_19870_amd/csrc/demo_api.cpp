@@ -75,6 +75,7 @@ struct demo_ctx {
   hipError_t last_hip = hipSuccess;
   int variant = 1;            // 0 = generic kernels only
   int enc_stage = 0;          // 1..3: cut-down copies of the s = 64 encode kernel (time attribution)
+  int dec_stage = 0;          // 1, 2: cut-down runs of the s = 64 decode kernel
 };
 
 namespace {
@@ -496,7 +497,9 @@ int run_encode(demo_ctx* ctx, const std::vector<TableGroup>& groups, const Table
 int run_decode(demo_ctx* ctx, TableCache* tc, const demo::BasisTables& basis, int W, const demo_hparams& hp, int s,
                int k, hipStream_t st) {
   const float scale = hp.aggregate == DEMO_AGG_MEAN ? 1.0f / (float)W : 1.0f;
-  demo::DecodeArgs a{hp.lr, hp.weight_decay, scale, k, W, hp.phi, hp.aggregate, basis.dct ? 1 : 0};
+  demo::DecodeArgs a{hp.lr, hp.weight_decay, scale, k, W, hp.phi, hp.aggregate, basis.dct ? 1 : 0, ctx->dec_stage};
+  if (ctx->dec_stage != 0 && (s != 64 || ctx->variant != 1 || (int64_t)W * k <= 64 || (int64_t)W * k > 2048 || hp.aggregate == DEMO_AGG_COUNT))
+    return DEMO_ERR_UNSUPPORTED;   // the cut-down runs exist in the s = 64 wavefront kernel with the payload in registers
   int rc;
   if (!tc->groups.empty()) {
     if ((rc = timer_begin(ctx, 2, st)) != DEMO_OK) return rc;
@@ -769,6 +772,12 @@ int demo_stream_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes,
 int demo_debug_set_encode_stage(demo_ctx* ctx, int stage) {
   if (ctx == nullptr || stage < 0 || stage > 3) return DEMO_ERR_ARG;
   ctx->enc_stage = stage;
+  return DEMO_OK;
+}
+
+int demo_debug_set_decode_stage(demo_ctx* ctx, int stage) {
+  if (ctx == nullptr || stage < 0 || stage > 2) return DEMO_ERR_ARG;
+  ctx->dec_stage = stage;
   return DEMO_OK;
 }
 

@@ -328,10 +328,15 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     DEMO_PHASE(0);
 
     // ---- S = sum over workers ---------------------------------------------------------------------------
+    int sh_chunk = 0;   // shift of this chunk's fixed point (undone when phi is the identity)
+    if (args.stage == 1) {
+      // time attribution (debug interface): the memory stream only -- the payload registers are merely kept alive
+#pragma unroll
+      for (int j = 0; j < NP; ++j) asm volatile("" ::"v"(pi[j]), "v"(pv[j]));
+    } else {
 #pragma unroll
     for (int i = 0; i < 17; ++i) *reinterpret_cast<float4*>(&tile[(i * 64 + lane) * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);
     wave_lds_sync();
-    int sh_chunk;   // shift of this chunk's fixed point (undone when phi is the identity)
     if constexpr (STREAM) {
       // one pass: the registers hold round 0; every round is added with the block exponent of the largest
       // magnitude seen so far, and when a round raises that exponent the sums in the tile are first shifted
@@ -363,6 +368,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     } else {
       sh_chunk = scatter();   // the launch wrapper guarantees that one set of NP pairs per lane holds all W workers
     }
+    }   // stage != 1
     DEMO_PHASE(1);
     // ---- payload of the next chunk, in flight during the products (after the last chunk the same
     //      chunk is requested again: an unconditional fetch keeps the old registers dead) -----------------
@@ -382,7 +388,12 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 
     // ---- products ---------------------------------------------------------------------------------------
     auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
-    if constexpr (DENSE) {
+    if (args.stage != 0) {
+      // time attribution: no products, the epilogue reads whatever the tile holds
+      if constexpr (DENSE) {
+        if (PBF16) fetch_x();
+      }
+    } else if constexpr (DENSE) {
       // product a per row tile ut: Y[u = 16 ut + 4g + r][j = 16 jt + c] = sum_v S[u][v] P[v][j], A = S from the tile
       // (row 16 ut + c, four consecutive v per 16-byte read), B = fragments; the accumulators of Y are, as they lie,
       // B operands of product b, R[i = 16 it + 4g + r'][j] += sum_u P[u][i] Y[u][j], A = the same fragments

@@ -61,6 +61,7 @@ struct DecodeArgs {
   int phi;            // demo_phi
   int agg;            // demo_aggregate
   int mirror;         // as in EncodeArgs
+  int stage;          // 0 = decode; 1, 2 = cut-down runs of the s = 64 wavefront kernel for time attribution (debug interface)
 };
 // The fast decode kernels aggregate by the plain sum (the mean is the sum times `scale`) and apply phi = sgn or
 // the identity in their epilogues.  The count-normalised aggregate runs in them while a chunk's whole payload

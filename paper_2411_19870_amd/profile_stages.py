@@ -1,10 +1,11 @@
 #!/usr/bin/env python3
-"""Time attribution of the s = 64 encode kernel on the 1B-like tensor set, and the memory-system ceilings
-it is held against: prints a markdown table.
+"""Time attribution of the s = 64 encode and decode kernels on the 1B-like tensor set, and the memory-system
+ceilings they are held against: prints markdown tables.
 
     python -m paper_2411_19870_amd.profile_stages [--k 32] [--reps 10]
 
-Stages are cut-down copies of the kernel selected with demo_debug_set_encode_stage (include/demo_debug.h):
+Stages are cut-down copies of the kernels selected with demo_debug_set_encode_stage / demo_debug_set_decode_stage
+(include/demo_debug.h):
 each is timed with HIP events on the launch stream; consecutive differences are the costs of the phases.
 The stream probes move 4 GiB in the launch shape of the wavefront kernels.
 """
@@ -23,24 +24,26 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--k", type=int, default=32)
     ap.add_argument("--reps", type=int, default=10)
+    ap.add_argument("--workers", type=int, default=64)
     a = ap.parse_args()
     import torch
     from paper_2411_19870_amd import binding as B
     from paper_2411_19870_amd import synth
 
-    dev, S, K = "cuda:0", 64, a.k
+    dev, S, K, W = "cuda:0", 64, a.k, a.workers
     specs = synth.tensor_set("1b")
     ts = []
     for ti, sp in enumerate(specs):
         g = synth.gaussian(sp, 1e-2, 0, ti, 0, "grad", dtype=torch.bfloat16, device=dev)
         m = synth.gaussian(sp, 1e-3, 0, ti, 0, "mom", device=dev)
-        nch = sp.nchunks(S)
-        ts.append(B.TensorArgs(g, m, None, torch.zeros((1, nch, K), dtype=torch.int32, device=dev),
-                               torch.zeros((1, nch, K), dtype=torch.float32, device=dev)))
+        x = synth.gaussian(sp, 0.02, 0, ti, 0, "param", dtype=torch.bfloat16, device=dev)
+        idx, val = synth.payload_fast(sp, S, K, W, 1e-3, 0, ti, device=dev)
+        ts.append(B.TensorArgs(g, m, x, idx, val))
     tl = B.TensorList(ts)
     n2 = sum(sp.numel for sp in specs if sp.cols)
     pairs2 = sum(sp.nchunks(S) for sp in specs if sp.cols) * K
     enc_bytes = n2 * 10 + pairs2 * 8
+    dec_bytes = n2 * 4 + W * pairs2 * 8
     ctx = B.Context()
 
     def time_encode(stage):
@@ -65,6 +68,28 @@ def main():
         prev = ms
     ctx.demo_debug_set_encode_stage(0)
 
+    def time_decode(stage):
+        ctx.demo_debug_set_decode_stage(stage)
+        for _ in range(3):
+            ctx.demo_decode(tl, W, 1e-3, 0.0, S, K)
+        torch.cuda.synchronize()
+        ctx.demo_set_timing(True)
+        for _ in range(a.reps):
+            ctx.demo_decode(tl, W, 1e-3, 0.0, S, K)
+        ms = ctx.demo_last_kernel_ms(2)
+        ctx.demo_set_timing(False)
+        return ms
+
+    drows = []
+    dnames = {1: "memory stream only (payload and parameter loads with prefetch, update, stores)",
+              2: "+ scatter-add of the W k pairs into the LDS tile", 0: "+ the two IDCT products (192 MFMA) = the kernel"}
+    prev = 0.0
+    for stage in (1, 2, 0):
+        ms = time_decode(stage)
+        drows.append((dnames[stage], ms, ms - prev, dec_bytes / ms / 1e6))
+        prev = ms
+    ctx.demo_debug_set_decode_stage(0)
+
     src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_()
     dst = torch.empty_like(src)
     probes = []
@@ -84,6 +109,10 @@ def main():
     print(f"## encode2d_wave64, 1B-like set, bf16 gradients, s = 64, k = {K}: {enc_bytes} algorithmic bytes per launch\n")
     print("| kernel copy | ms | added ms | algorithmic GB/s | of 8 TB/s |\n|---|---|---|---|---|")
     for name, ms, d, gbs in rows:
+        print(f"| {name} | {ms:.3f} | {d:+.3f} | {gbs:.0f} | {gbs / 8000:.3f} |")
+    print(f"\n## decode2d_wave64, 1B-like set, bf16 parameters, s = 64, k = {K}, W = {W}: {dec_bytes} algorithmic bytes per launch\n")
+    print("| kernel copy | ms | added ms | algorithmic GB/s | of 8 TB/s |\n|---|---|---|---|---|")
+    for name, ms, d, gbs in drows:
         print(f"| {name} | {ms:.3f} | {d:+.3f} | {gbs:.0f} | {gbs / 8000:.3f} |")
     print("\n## stream probes over 4 GiB (one 512-thread workgroup per CU, 16 B per lane, 8 accesses in flight)\n")
     print("| probe | ms | GB/s moved | of 8 TB/s |\n|---|---|---|---|")

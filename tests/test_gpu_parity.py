@@ -542,6 +542,22 @@ def test_debug_stages_and_stream_probes(ctx):
         ctx.demo_debug_set_encode_stage(4)
     case = Case(specs, 64, 32, grad_dtype=torch.bfloat16, seed=4)
     run_encode_check(ctx, case)
+    # ... and of the decode kernel
+    dcase = Case(specs, 64, 32, W=8, param_dtype=torch.bfloat16, seed=5)
+    dcase.fill_payloads(exact=False)
+    for stage in (1, 2):
+        ctx.demo_debug_set_decode_stage(stage)
+        ctx.demo_decode(dcase.args, 8, LR, 0.0, 64, 32)
+        with pytest.raises(B.DemoError) as e:
+            ctx.demo_decode(dcase.args, 1, LR, 0.0, 64, 32)      # W k <= 64 runs on another kernel
+        assert e.value.status == B.DEMO_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    ctx.demo_debug_set_decode_stage(0)
+    with pytest.raises(B.DemoError):
+        ctx.demo_debug_set_decode_stage(3)
+    dcase = Case(specs, 64, 32, W=8, param_dtype=torch.bfloat16, seed=6)
+    dcase.fill_payloads(exact=False)
+    run_decode_check(ctx, dcase, W=8)
     src = torch.randn(1 << 20, device=DEV)
     for mode in range(5):
         dst = torch.zeros(1 << 20, device=DEV)
