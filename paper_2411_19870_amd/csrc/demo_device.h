@@ -60,6 +60,9 @@ __device__ __forceinline__ int find_tensor(const int32_t* __restrict__ prefix, i
 // number of wavefronts of the grid.  The workgroup takes 8 / RUN runs of RUN consecutive items that lie
 // gridDim runs apart (RUN = 8: eight consecutive items).  Measured on the 1B-like set (same box, alternating
 // runs): decode 1.60 / 1.49 / 1.41 / 1.44 ms and encode 1.95 / 1.89 / 1.89 / 1.90 ms for RUN = 1 / 2 / 4 / 8.
+// Consecutive workgroups run on different XCDs (the dispatcher hands them out round robin), so neighbouring runs
+// are streamed by different XCDs; giving each XCD a contiguous range of runs instead was measured and is slower
+// (memory-stream-only copies of the kernels: encode 1.65 -> 1.68 ms, decode 1.37 -> 1.43 ms).
 #ifndef DEMO_RUN
 #define DEMO_RUN 4
 #endif
