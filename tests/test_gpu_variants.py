@@ -340,3 +340,23 @@ def test_identity_phi_with_zero_step_leaves_parameters_untouched(ctx, s, k, W):
         for b, a in zip(before, case.x):
             assert torch.equal(a, b)
         c.close()
+
+
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("s,k", [(64, 32), (32, 8), (128, 32)])
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+def test_encode_with_nothing_to_add_or_subtract_leaves_momentum_untouched(variant, s, k, gdt):
+    # beta = 1, g = 0, alpha = 0: m' = 1 m + 0 - 0 R must give the momentum back bit for bit, on freshly allocated
+    # tensors and in the first launches of a context.  The encode kernels' twin of the test above: a momentum store
+    # whose data registers were overwritten by the instruction behind it would leave some other row's value here.
+    for rep in range(3):
+        c = B.Context()
+        c.demo_set_variant(variant)
+        case = Case(synth.tensor_set("tiny"), s, k, grad_dtype=gdt, grad="zero", seed=50 + rep)
+        before = [m.clone() for m in case.m]
+        c.demo_encode_ex(case.args, B.demo_hparams_default(beta=1.0, alpha=0.0), s, k)
+        torch.cuda.synchronize()
+        for ti, (b, a) in enumerate(zip(before, case.m)):
+            assert torch.equal(a, b), case.specs[ti].name
+            assert bool((case.val[ti][0].abs().amax(dim=1) > 0).all())   # the payload is still the top-k of m
+        c.close()
