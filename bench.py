@@ -32,6 +32,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 S, K, W = 64, 32, 64
 BETA, LR, WD = 0.999, 1e-3, 0.0
 CPU_SAMPLE_FRACTION = 0.10
@@ -243,20 +244,33 @@ def main():
     hbm_frac = achieved / HBM_PEAK_GBS
     mfma_flops = mfma_flops_per_launch(dom, S, K, W, nchunks2, [t.idx for t, sp in zip(tensors, specs) if sp.cols]) \
         if a.variant == 1 and a.projection == "dct" else None
+    bf16_flops = None
     if a.variant == 1 and a.projection != "dct" and S == 64 and K <= 64 and (dom == "enc2d" or W * K <= 2048):
-        # full products: 256 MFMAs each; reconstruction 16 per four kept coefficients
-        mfma_flops = (512.0 + (16.0 * math.ceil(K / 4.0) if dom == "enc2d" else 0.0)) * 2048.0 * nchunks2
-    mfma_tflops = mfma_flops / (kms[dom] * 1e-3) / 1e12 if mfma_flops else None
-    mfma_frac = mfma_tflops / MFMA_F32_PEAK_TFLOPS if mfma_tflops else None
+        # full products of float32 operands split into three bfloat16 parts: 6 v_mfma_f32_16x16x32_bf16 (16384 flop)
+        # per 16 x 16 tile and 32 contraction indices, 192 per product; reconstruction in float32, 16 per four kept
+        # coefficients
+        bf16_flops = 2 * 192.0 * 16384.0 * nchunks2
+        mfma_flops = (16.0 * math.ceil(K / 4.0) if dom == "enc2d" else 0.0) * 2048.0 * nchunks2
+    if bf16_flops:
+        # two instruction types: the fraction is the time the matrix pipe needs at each type's peak over the launch time
+        pipe_s = bf16_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) + mfma_flops / (MFMA_F32_PEAK_TFLOPS * 1e12)
+        mfma_frac = pipe_s / (kms[dom] * 1e-3)
+        mfma_tflops = (bf16_flops + mfma_flops) / (kms[dom] * 1e-3) / 1e12
+        mfma_peak = (bf16_flops + mfma_flops) / pipe_s / 1e12
+    else:
+        mfma_tflops = mfma_flops / (kms[dom] * 1e-3) / 1e12 if mfma_flops else None
+        mfma_frac = mfma_tflops / MFMA_F32_PEAK_TFLOPS if mfma_tflops else None
+        mfma_peak = MFMA_F32_PEAK_TFLOPS
     bound = "mfma" if (mfma_frac or 0.0) > hbm_frac else "hbm"
     roof = {"bound": bound, "kernel": dom, "avg_launch_ms": kms[dom],
             "hbm": {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac,
                     "algorithmic_bytes_per_launch": ab[dom]},
-            "mfma": {"achieved": mfma_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac,
-                     "issued_fp32_mfma_flops_per_launch": mfma_flops},
+            "mfma": {"achieved": mfma_tflops, "peak": mfma_peak, "unit": "TFLOP/s", "frac": mfma_frac,
+                     "issued_fp32_mfma_flops_per_launch": mfma_flops, "issued_bf16_mfma_flops_per_launch": bf16_flops,
+                     "peak_fp32": MFMA_F32_PEAK_TFLOPS, "peak_bf16": MFMA_BF16_PEAK_TFLOPS},
             "traffic": None, "traffic_source": None}
     roof.update({"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac} if bound == "hbm" else
-                {"achieved": mfma_tflops, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": mfma_frac})
+                {"achieved": mfma_tflops, "peak": mfma_peak, "unit": "TFLOP/s", "frac": mfma_frac})
 
     out = {
         "metric": "DeMo encode+decode throughput at 1B shape" if a.workload == "1b" and headline
@@ -265,7 +279,8 @@ def main():
         "params_per_s": nparams / (ms_step * 1e-3),
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if not bf16_flops else "f32 (products on the bf16 matrix pipe, operands split exactly into three bf16 parts)",
+        "data": "synthetic",
         "config": {"workload": f"{a.workload}-like tensor set: encode (grad {'bf16' if gb == 2 else 'f32'}, momentum f32) "
                                f"+ decode of W={W} payloads (param {'bf16' if gb == 2 else 'f32'})",
                    "tensors": len(specs), "params": nparams, "s": S, "k": K, "W": W, "beta": BETA, "lr": LR,

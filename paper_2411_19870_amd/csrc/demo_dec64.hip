@@ -44,11 +44,13 @@ constexpr int D64_PK = 4096 + 1536;                // pk[u*16 + c]  = P[u][kappa
 constexpr int D64_PK2 = 4096 + 1536 + 1024;        // pk2[u*16 + c] = P[u][31 - kappa(c)]  (odd u: the second member)
 constexpr int D64_ALL_TABLE_FLOATS = 4096 + 1536 + 2048;
 constexpr int D64_LDS_BYTES = 4 * (D64_G_FLOATS + D64_WAVES * D64_TILE_FLOATS);
-// Instances for a projection matrix without mirror symmetry (DENSE): one fragment table serves both products,
-//   gd[((4a + b) * 64 + lane) * 4 + t] = P[16 a + 4 g + b][16 t + c]
-// (product a: B operand of the step that contracts v = 16 a + 4 g + b, output columns j = 16 t + c; product b: A
-// operand of the step that contracts u = 16 a + 4 g + b, output rows i = 16 t + c).
-constexpr int D64G_FLOATS = 4096;
+// Instances for a projection matrix without mirror symmetry (DENSE).  Both products run on the bfloat16 matrix pipe
+// with every float32 operand split into three parts (demo_device.h), and one table of pre-split basis fragments
+// serves both: block 2 t + h (kSplitFragFloats words), slot j of contraction group g holds
+//   P[16 (2 h + j / 4) + 4 g + j % 4][16 t + c]
+// (product a: B operand, contracts v = 16 a + 4 g + b with (a, b) = (2 h + j / 4, j % 4), output columns
+// j = 16 t + c; product b: A operand, contracts u = 16 a + 4 g + b, output rows i = 16 t + c).
+constexpr int D64G_FLOATS = 8 * kSplitFragFloats;
 static_assert(D64G_FLOATS == kDec64DenseTableFloats, "table size");
 template <bool DENSE>
 constexpr int d64_table_floats() { return DENSE ? D64G_FLOATS : D64_G_FLOATS; }
@@ -67,11 +69,14 @@ __host__ __device__ constexpr int member(int w, int i0) {
 }  // namespace
 
 void build_dec64_dense_tables(const double* P, float* out) {
-  for (int a = 0; a < 4; ++a)
-    for (int b = 0; b < 4; ++b)
-      for (int lane = 0; lane < 64; ++lane)
-        for (int t = 0; t < 4; ++t)
-          out[((4 * a + b) * 64 + lane) * 4 + t] = (float)P[(16 * a + 4 * (lane >> 4) + b) * 64 + 16 * t + (lane & 15)];
+  for (int t = 0; t < 4; ++t)
+    for (int h = 0; h < 2; ++h)
+      for (int lane = 0; lane < 64; ++lane) {
+        float v[8];
+        for (int j = 0; j < 8; ++j)
+          v[j] = (float)P[(16 * (2 * h + (j >> 2)) + 4 * (lane >> 4) + (j & 3)) * 64 + 16 * t + (lane & 15)];
+        host_store_split8(out + (2 * t + h) * kSplitFragFloats, lane, v);
+      }
 }
 
 // Host: tables of the decode kernels from the 64 x 64 basis P (double, row-major).
@@ -115,7 +120,8 @@ void build_dec64_tables(const double* P, float* out) {
 // payload loads of modes 3 to 5 are non-temporal (the launch wrapper asks for that when a row of k pairs fills a
 // 128-byte line; shorter rows share lines with neighbouring chunks and stay cached).
 // DENSE: any orthonormal 64 x 64 matrix (table of build_dec64_dense_tables): the tile holds S in its natural order,
-// both products are full (256 MFMAs each), R goes through the tile in its natural order.
+// both products are full (on the bfloat16 matrix pipe, float32 operands split into three parts: 192
+// v_mfma_f32_16x16x32_bf16 each), R goes through the tile in its natural order.
 template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true, bool DENSE = false>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
@@ -395,38 +401,70 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       }
     } else if constexpr (DENSE) {
       // product a per row tile ut: Y[u = 16 ut + 4g + r][j = 16 jt + c] = sum_v S[u][v] P[v][j], A = S from the tile
-      // (row 16 ut + c, four consecutive v per 16-byte read), B = fragments; the accumulators of Y are, as they lie,
-      // B operands of product b, R[i = 16 it + 4g + r'][j] += sum_u P[u][i] Y[u][j], A = the same fragments
+      // (row 16 ut + c; the eight v of a slot group are two 16-byte reads), B = fragments.  The accumulators of two
+      // row tiles are, as they lie, the eight contraction slots of product b,
+      // R[i = 16 it + 4g + r'][j] += sum_u P[u][i] Y[u][j], A = the same fragments.
       f32x4 R[4][4];   // [it][jt]
 #pragma unroll
       for (int it = 0; it < 4; ++it)
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt) R[it][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ut = 0; ut < 4; ++ut) {
-        const float* arow = &tile[(16 * ut + c) * D64_LDT + 4 * g];
-        float4 a[4];
+      for (int hp = 0; hp < 2; ++hp) {
+        f32x4 Y[2][4];   // [ut - 2 hp][jt]
 #pragma unroll
-        for (int kg = 0; kg < 4; ++kg) a[kg] = *reinterpret_cast<const float4*>(arow + 16 * kg);
-        f32x4 Y[4];
+        for (int uu = 0; uu < 2; ++uu)
 #pragma unroll
-        for (int jt = 0; jt < 4; ++jt) Y[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+          for (int jt = 0; jt < 4; ++jt) Y[uu][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kg = 0; kg < 4; ++kg)
+        for (int h = 0; h < 2; ++h) {
+          Split8 A[2];   // [ut - 2 hp]: S as float32 (the tile holds fixed-point sums), split
 #pragma unroll
-          for (int kr = 0; kr < 4; ++kr) {
-            const float sv = (float)__float_as_int(comp(a[kg], kr));   // the tile holds fixed-point sums
-            const float4 gd = *reinterpret_cast<const float4*>(&sG[((4 * kg + kr) * 64 + lane) * 4]);
-#pragma unroll
-            for (int jt = 0; jt < 4; ++jt) Y[jt] = mfma4(sv, comp(gd, jt), Y[jt]);
+          for (int uu = 0; uu < 2; ++uu) {
+            const float* arow = &tile[(16 * (2 * hp + uu) + c) * D64_LDT + 4 * g + 32 * h];
+            const float4 a0 = *reinterpret_cast<const float4*>(arow);
+            const float4 a1 = *reinterpret_cast<const float4*>(arow + 16);
+            A[uu] = split8((float)__float_as_int(a0.x), (float)__float_as_int(a0.y), (float)__float_as_int(a0.z),
+                           (float)__float_as_int(a0.w), (float)__float_as_int(a1.x), (float)__float_as_int(a1.y),
+                           (float)__float_as_int(a1.z), (float)__float_as_int(a1.w));
           }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float4 gd = *reinterpret_cast<const float4*>(&sG[((4 * ut + r) * 64 + lane) * 4]);
+          for (int jt = 0; jt < 4; ++jt) {
+            const Split8 Bq = load_split8(sG + (2 * jt + h) * kSplitFragFloats, lane);
 #pragma unroll
-          for (int it = 0; it < 4; ++it)
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].lo, Bq.hi, Y[uu][jt]);
 #pragma unroll
-            for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma4(comp(gd, it), Y[jt][r], R[it][jt]);
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].hi, Bq.lo, Y[uu][jt]);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].mid, Bq.mid, Y[uu][jt]);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].mid, Bq.hi, Y[uu][jt]);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].hi, Bq.mid, Y[uu][jt]);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].hi, Bq.hi, Y[uu][jt]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        Split8 Bt[4];
+#pragma unroll
+        for (int jt = 0; jt < 4; ++jt)
+          Bt[jt] = split8(Y[0][jt][0], Y[0][jt][1], Y[0][jt][2], Y[0][jt][3], Y[1][jt][0], Y[1][jt][1], Y[1][jt][2], Y[1][jt][3]);
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const Split8 Ap = load_split8(sG + (2 * it + hp) * kSplitFragFloats, lane);
+#pragma unroll
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.lo, Bt[jt].hi, R[it][jt]);
+#pragma unroll
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.hi, Bt[jt].lo, R[it][jt]);
+#pragma unroll
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.mid, Bt[jt].mid, R[it][jt]);
+#pragma unroll
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.mid, Bt[jt].hi, R[it][jt]);
+#pragma unroll
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.hi, Bt[jt].mid, R[it][jt]);
+#pragma unroll
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.hi, Bt[jt].hi, R[it][jt]);
         }
       }
       DEMO_PHASE(3);

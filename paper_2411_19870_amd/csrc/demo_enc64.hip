@@ -50,12 +50,15 @@ static_assert(E64_LIST % 4 == 2 && (2 * E64_LIST) % 4 == 0 && E64_SCRATCH_WORDS 
 __host__ __device__ constexpr int kappa64(int c) { return 4 * (c & 3) + (c >> 2); }
 static_assert(E64_TABLE_FLOATS == kEnc64TableFloats, "table size");
 
-// Tables of the instances for a projection matrix without mirror symmetry (DENSE): all four 64 x 64 floats.
-constexpr int E64G_T1 = 0;                        // t1[(q*64 + lane)*4 + t]      = P[16 t + c][rho(q, g)]            (product 1, B operand)
-constexpr int E64G_T2 = 4096;                     // t2[((4e+r)*64 + lane)*4 + vt] = P[16 vt + c][4 chi(4g+r) + e]     (product 2, A operand)
-constexpr int E64G_PCOL = 8192;                   // pcol[v*64 + 4c + e]          = P[v][4 chi(c) + e]                (reconstruction, B operand)
-constexpr int E64G_PROW = 12288;                  // prow[u*64 + 16 w + c]        = P[u][rho(4 (c%4) + w, c/4)]       (reconstruction, A operand)
-constexpr int E64G_TABLE_FLOATS = 16384;
+// Tables of the instances for a projection matrix without mirror symmetry (DENSE).  The two products run on the
+// bfloat16 matrix pipe with every float32 operand split into three parts (demo_device.h): their basis fragments
+// are stored pre-split, one block of kSplitFragFloats words per (tile, half h of the contraction range); slot j of
+// contraction group g stands for step 8 h + j of the sixteen steps the float32 instruction form would take.
+constexpr int E64G_T1 = 0;                        // block 2 t + h, slot j:  P[16 t + c][rho(8 h + j, g)]              (product 1, B operand)
+constexpr int E64G_T2 = 8 * kSplitFragFloats;     // block 2 vt + h, slot j: P[16 vt + c][4 chi(4g + r) + e], 4 e + r = 8 h + j  (product 2, A operand)
+constexpr int E64G_PCOL = 16 * kSplitFragFloats;  // pcol[v*64 + 4c + e]          = P[v][4 chi(c) + e]                (reconstruction, B operand)
+constexpr int E64G_PROW = E64G_PCOL + 4096;       // prow[u*64 + 16 w + c]        = P[u][rho(4 (c%4) + w, c/4)]       (reconstruction, A operand)
+constexpr int E64G_TABLE_FLOATS = E64G_PROW + 4096;
 static_assert(E64G_TABLE_FLOATS == kEnc64DenseTableFloats, "table size");
 template <bool DENSE>
 constexpr int e64_table_floats() { return DENSE ? E64G_TABLE_FLOATS : E64_TABLE_FLOATS; }
@@ -68,12 +71,17 @@ void build_enc64_dense_tables(const double* P, float* out) {
   auto Pm = [&](int u, int i) { return (float)P[u * 64 + i]; };
   for (int lane = 0; lane < 64; ++lane) {
     const int g = lane >> 4, c = lane & 15;
-    for (int q = 0; q < 16; ++q)
-      for (int t = 0; t < 4; ++t) out[E64G_T1 + (q * 64 + lane) * 4 + t] = Pm(16 * t + c, rho(q, g));
-    for (int e = 0; e < 4; ++e)
-      for (int r = 0; r < 4; ++r)
-        for (int vt = 0; vt < 4; ++vt)
-          out[E64G_T2 + ((4 * e + r) * 64 + lane) * 4 + vt] = Pm(16 * vt + c, 4 * chi(4 * g + r) + e);
+    for (int t = 0; t < 4; ++t)
+      for (int h = 0; h < 2; ++h) {
+        float v1[8], v2[8];
+        for (int j = 0; j < 8; ++j) {
+          const int q = 8 * h + j;   // product 1: step q; product 2: (e, r) = (q / 4, q % 4)
+          v1[j] = Pm(16 * t + c, rho(q, g));
+          v2[j] = Pm(16 * t + c, 4 * chi(4 * g + (q & 3)) + (q >> 2));
+        }
+        host_store_split8(out + E64G_T1 + (2 * t + h) * kSplitFragFloats, lane, v1);
+        host_store_split8(out + E64G_T2 + (2 * t + h) * kSplitFragFloats, lane, v2);
+      }
   }
   for (int u = 0; u < 64; ++u)
     for (int cc = 0; cc < 16; ++cc) {
@@ -124,7 +132,8 @@ __device__ __forceinline__ Bfly butterfly(float x0, float x1, float x2, float x3
 // memory stream only (loads of g and m with the prefetch, momentum update, store of m, k payload pairs per chunk),
 // 2 = stage 1 plus the two products, 3 = stage 2 plus top-k and the payload (everything but the reconstruction).
 // DENSE: the projection matrix is any orthonormal 64 x 64 matrix (tables of build_enc64_dense_tables): the same
-// register layout and the same top-k, with the full products (256 MFMAs each instead of 96) and a reconstruction
+// register layout and the same top-k, with the full products (on the bfloat16 matrix pipe, float32 operands split
+// into three parts: 192 v_mfma_f32_16x16x32_bf16 each, 3/8 of the time of 256 float32 instructions) and a reconstruction
 // over all 64 rows (16 MFMAs per four selected coefficients); coefficient tiles hold u = 16 t + c, v = 16 vt + 4g + r.
 template <bool GBF16, int STAGE, bool DENSE = false>   // gradient dtype of every tensor in the table
 __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, const float* __restrict__ tables,
@@ -288,15 +297,32 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) C1[e][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     if constexpr (DENSE) {
+      // contraction over the rows in two halves of 32: slot j of group g is row rho(8 h + j, g); the data are split
+      // into bfloat16 triples once per half and serve the four tiles of u
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const float4 p4 = *reinterpret_cast<const float4*>(&sT1[(q * 64 + lane) * 4]);
-        const float pt[4] = {p4.x, p4.y, p4.z, p4.w};
+      for (int h = 0; h < 2; ++h) {
+        Split8 A[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
+          A[e] = split8(D[2 * h][e][0], D[2 * h][e][1], D[2 * h][e][2], D[2 * h][e][3],
+                        D[2 * h + 1][e][0], D[2 * h + 1][e][1], D[2 * h + 1][e][2], D[2 * h + 1][e][3]);
 #pragma unroll
-          for (int tt = 0; tt < 4; ++tt) C1[e][tt] = mfma4(D[q >> 2][e][q & 3], pt[tt], C1[e][tt]);
-        if ((q & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        for (int tt = 0; tt < 4; ++tt) {
+          const Split8 Bq = load_split8(sT1 + (2 * tt + h) * kSplitFragFloats, lane);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].lo, Bq.hi, C1[e][tt]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].hi, Bq.lo, C1[e][tt]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].mid, Bq.mid, C1[e][tt]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].mid, Bq.hi, C1[e][tt]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].hi, Bq.mid, C1[e][tt]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].hi, Bq.hi, C1[e][tt]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
       const float4 pee4 = *reinterpret_cast<const float4*>(&sT1[(0 * 64 + lane) * 4]);
@@ -327,15 +353,32 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     if constexpr (DENSE) {
+      // contraction over the columns j = 4 chi(4g + r) + e in two halves: slot j' of group g is (e, r) with
+      // 4 e + r = 8 h + j'; the accumulators of product 1 are split as they lie and serve the four tiles of v
 #pragma unroll
-      for (int er = 0; er < 16; ++er) {
-        const float4 p4 = *reinterpret_cast<const float4*>(&sT2[(er * 64 + lane) * 4]);
-        const float pv4[4] = {p4.x, p4.y, p4.z, p4.w};
+      for (int h = 0; h < 2; ++h) {
+        Split8 Bt[4];
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt)
+          Bt[tt] = split8(C1[2 * h][tt][0], C1[2 * h][tt][1], C1[2 * h][tt][2], C1[2 * h][tt][3],
+                          C1[2 * h + 1][tt][0], C1[2 * h + 1][tt][1], C1[2 * h + 1][tt][2], C1[2 * h + 1][tt][3]);
 #pragma unroll
-          for (int vt = 0; vt < 4; ++vt) C2[vt][tt] = mfma4(pv4[vt], C1[er >> 2][tt][er & 3], C2[vt][tt]);
-        if ((er & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        for (int vt = 0; vt < 4; ++vt) {
+          const Split8 Ap = load_split8(sT2 + (2 * vt + h) * kSplitFragFloats, lane);
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.lo, Bt[tt].hi, C2[vt][tt]);
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.hi, Bt[tt].lo, C2[vt][tt]);
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.mid, Bt[tt].mid, C2[vt][tt]);
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.mid, Bt[tt].hi, C2[vt][tt]);
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.hi, Bt[tt].mid, C2[vt][tt]);
+#pragma unroll
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.hi, Bt[tt].hi, C2[vt][tt]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     } else {
       const float4 pee4 = *reinterpret_cast<const float4*>(&sT2[(0 * 64 + lane) * 4]);

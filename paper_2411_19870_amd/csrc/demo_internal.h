@@ -117,7 +117,7 @@ constexpr int kFast64MaxK = 64;
 void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
 void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
 // ... and their instances for a projection matrix without mirror symmetry: full products, other tables
-constexpr int kEnc64DenseTableFloats = 4 * 4096;
+constexpr int kEnc64DenseTableFloats = 16 * 768 + 2 * 4096;   // 16 pre-split fragment blocks, two 64 x 64 tables
 void build_enc64_dense_tables(const double* P, float* out /* kEnc64DenseTableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                   bool grad_bf16, bool dense, int num_cus, hipStream_t stream);
@@ -166,7 +166,7 @@ inline bool fast64_decode_supports(int W, int k, bool payload_aligned16) {
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream);
 // ... and its instances for a projection matrix without mirror symmetry
-constexpr int kDec64DenseTableFloats = 4096;
+constexpr int kDec64DenseTableFloats = 8 * 768;   // 8 pre-split fragment blocks
 void build_dec64_dense_tables(const double* P, float* out /* kDec64DenseTableFloats */);
 bool dense64_decode_supports(const DecodeArgs& a);
 hipError_t launch_decode2d_dense64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
