@@ -281,6 +281,45 @@ def test_random_projection_on_the_wavefront_kernels(ctx, W, k, dt, phi):
         ctx.demo_set_basis(s, B.DEMO_BASIS_DCT)
 
 
+@pytest.mark.parametrize("kind", ["dct", "identity", "gram_schmidt"])
+@pytest.mark.parametrize("exp2", [-80, 60])
+def test_encode_is_scale_free_over_the_exponent_range(ctx, kind, exp2):
+    # gradients and momentum scaled by 2^-80 and 2^60: every bound of the comparison is relative to the chunk's largest
+    # magnitude, so nothing may depend on the absolute scale.  With another matrix than the DCT the s = 64 products run
+    # on the bfloat16 matrix pipe, each float32 operand split into three bfloat16 parts whose remainders sit 2^-16 below
+    # the value; with the identity matrix the coefficients are the momentum values themselves, bit for bit.
+    s, k = 64, 32
+    ctx.demo_set_variant(1)
+    scale = 2.0 ** exp2
+    specs = [synth.TensorSpec("a", 256, 384), synth.TensorSpec("v0", 256, 0)]
+    case = Case(specs, s, k, seed=43, grad_std=1e-2 * scale, mom_std=1e-3 * scale)
+    P = None
+    try:
+        if kind == "identity":
+            ctx.demo_set_basis(s, B.DEMO_BASIS_IDENTITY)
+            P = np.eye(s)
+        elif kind == "gram_schmidt":
+            a, P = _projection(s, kind, step=11)
+            ctx.demo_set_basis(s, B.DEMO_BASIS_GRAM_SCHMIDT, a)
+        before = case.snapshot()
+        ctx.demo_encode(case.args, 0.9, s, k)
+        torch.cuda.synchronize()
+        after = case.snapshot()
+        for ti in range(len(case.specs)):
+            st = C.check_encode(before["m"][ti], before["g"][ti], 0.9, s, k, after["idx"][ti][0], after["val"][ti][0],
+                                after["m"][ti], P=P)
+            assert st["chunks"] == case.specs[ti].nchunks(s)
+        if kind == "identity":
+            # Q = momentum after the update: the k payload values of a chunk are elements of beta m + g as float32
+            m0, g0 = before["m"][0].astype(np.float32), before["g"][0].astype(np.float32)
+            upd = (np.float32(0.9) * m0.astype(np.float64) + g0.astype(np.float64)).astype(np.float32)
+            blocks = upd.reshape(256 // s, s, 384 // s, s).transpose(0, 2, 1, 3).reshape(-1, s * s)
+            idx, val = after["idx"][0][0], after["val"][0][0]
+            assert np.array_equal(np.take_along_axis(blocks, idx.astype(np.int64), axis=1), val)
+    finally:
+        ctx.demo_set_basis(s, B.DEMO_BASIS_DCT)
+
+
 def test_new_matrix_every_step_then_back_to_dct(ctx):
     # the paper's random projection: a fresh matrix per step, seeded with the step number
     s, k = 64, 16
