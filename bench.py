@@ -89,6 +89,19 @@ def mfma_flops_per_launch(kernel, s, k, W, nchunks2, idx_tensors):
     return (products + 16.0 * 12.0) * 2048.0 * nchunks2                    # s = 128: about 12 per wavefront
 
 
+def _cpu_worker_init():
+    """One thread per worker process: the pool has one process per core, and numerical libraries that each start
+    a thread per core would oversubscribe the machine sixteen-fold."""
+    import torch
+    torch.set_num_threads(1)
+    try:
+        import threadpoolctl
+        global _cpu_thread_limit
+        _cpu_thread_limit = threadpoolctl.threadpool_limits(1)
+    except ImportError:
+        pass
+
+
 def _cpu_job(job):
     """One tensor slab of the CPU baseline: oracle encode + W-worker decode (runs in a worker process)."""
     import numpy as np
@@ -131,7 +144,8 @@ def cpu_baseline(specs, seed, s, k, Wn, ab_step_bytes, nparams):
     jobs.sort(key=lambda j: -j[1] * (j[2] or 1))            # largest first
     frac = sample_params / nparams
     w0 = time.perf_counter()
-    with ProcessPoolExecutor(max_workers=cores, mp_context=multiprocessing.get_context("spawn")) as pool:
+    with ProcessPoolExecutor(max_workers=cores, mp_context=multiprocessing.get_context("spawn"),
+                             initializer=_cpu_worker_init) as pool:
         list(pool.map(_cpu_job, jobs[-cores:]))             # start the workers (imports) outside the timed pass
         w1 = time.perf_counter()
         busy = sum(pool.map(_cpu_job, jobs))
@@ -143,7 +157,7 @@ def cpu_baseline(specs, seed, s, k, Wn, ab_step_bytes, nparams):
         "core_seconds_in_oracle": busy, "wall_s": wall, "pool_start_s": w1 - w0,
         "sample": f"one pass of encode + W={Wn} decode over the first {100 * CPU_SAMPLE_FRACTION:.0f} % of the rows of each "
                   f"of the {len(specs)} tensors ({sample_params} parameters, {100 * frac:.1f} % of the workload), "
-                  f"one process per core, wall-clock of the pass",
+                  f"one single-threaded process per core, wall-clock of the pass",
     }
 
 
