@@ -117,12 +117,14 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
               const int pos = p - w * k;
               const bool ok = unit < nunits;
               const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
+              // unconditional, and taken as it comes: mask_payload discards the units past the end where the pairs
+              // are consumed (a select right behind a load makes the wavefront wait for it before the next load)
               const f32x4 vv = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
-              for (int e = 0; e < 4; ++e) pv[D32_SLOTS * q + 4 * jj + e] = ok ? vv[e] : 0.f;
+              for (int e = 0; e < 4; ++e) pv[D32_SLOTS * q + 4 * jj + e] = vv[e];
               const u32x4 iv = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-              for (int e = 0; e < 4; ++e) pi[D32_SLOTS * q + 4 * jj + e] = ok ? (int32_t)iv[e] : -1;
+              for (int e = 0; e < 4; ++e) pi[D32_SLOTS * q + 4 * jj + e] = (int32_t)iv[e];
             }
           }
         }
@@ -137,9 +139,25 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
           const int w = (int)(((float)p + 0.5f) * rk);
           const int pos = p - w * k;
           const bool ok = p < npairs;
-          const uint32_t off = (uint32_t)(w * (int)wstride + pos);
-          pi[D32_SLOTS * q + j] = ok ? ip[off] : -1;
-          pv[D32_SLOTS * q + j] = ok ? vp[off] : 0.f;
+          const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
+          pi[D32_SLOTS * q + j] = ip[off];
+          pv[D32_SLOTS * q + j] = vp[off];
+        }
+      }
+    }
+  };
+  // Slots past the end of a chunk's payload become (no index, 0); called where the pairs are consumed.
+  auto mask_payload = [&](int round = 0) {
+    int lanev = lane;
+    asm volatile("" : "+v"(lanev));
+#pragma unroll
+    for (int j = 0; j < D32_SLOTS; ++j) {
+      if (j < nslots) {   // uniform
+        const bool ok = VEC4 ? (STREAM ? 16 * D32_SLOTS * round : 0) + 64 * (j >> 2) + lanev < nunits : 64 * j + lanev < npairs;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          pi[D32_SLOTS * q + j] = ok ? pi[D32_SLOTS * q + j] : -1;
+          pv[D32_SLOTS * q + j] = ok ? pv[D32_SLOTS * q + j] : 0.f;
         }
       }
     }
@@ -218,6 +236,10 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
   load_payload(d, tileno - t_first, 0);
+  // the first tile's pairs are waited for here, outside the loop (see demo_dec64.hip: with loads pending at the
+  // loop's entry its first wait would also be for the acknowledgements of the previous tile's stores)
+#pragma unroll
+  for (int j = 0; j < 4 * D32_SLOTS; ++j) asm volatile("" : "+v"(pi[j]), "+v"(pv[j]));
   const int kap = kappa32(c), col4 = 4 * chi(c);
   // tile offsets (floats) of the transposition of R: row parts for members w even / odd, column parts
   // for members w' even / odd (w' >= 2 adds 32 columns)
@@ -242,6 +264,7 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
       for (int q = 0; q < 16; ++q) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
     };
     if (PBF16 && VEC4) request_x();
+    mask_payload(0);
 
     // ---- S = sum over workers, four chunks ----------------------------------------------------------------
 #pragma unroll
@@ -259,6 +282,7 @@ __global__ __launch_bounds__(D32_THREADS) void decode2d_tile32(TableView tv, con
       }
       for (int r = 1; r < nrounds; ++r) {
         load_payload(d, tt, r);
+        mask_payload(r);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int sh_r = shift_of(lane_max(q, 0.f));

@@ -191,24 +191,27 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
             const int pos = p - w * k;
             const bool ok = unit < nunits;
             const uint32_t off = ok ? (uint32_t)(w * (int)wstride + pos) : 0u;
+            // The loads are unconditional (a unit past the end reads the chunk's first pairs) and what they bring
+            // is taken as it is: mask_payload discards the units past the end where the pairs are consumed.  A
+            // select right behind a load makes the wavefront wait for that load before it issues the next one.
             if constexpr (VW == 4) {
               const f32x4 b = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
-              for (int x = 0; x < 4; ++x) pv[4 * j + x] = ok ? b[x] : 0.f;
+              for (int x = 0; x < 4; ++x) pv[4 * j + x] = b[x];
               const u32x4 a = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-              for (int x = 0; x < 4; ++x) pi[4 * j + x] = ok ? (int32_t)a[x] : -1;
+              for (int x = 0; x < 4; ++x) pi[4 * j + x] = (int32_t)a[x];
             } else if constexpr (VW == 2) {
               const u32x2 a = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL u32x2*>(ip + off));
               const f32x2 b = payload_load<NT>(reinterpret_cast<const DEMO_GLOBAL f32x2*>(vp + off));
 #pragma unroll
               for (int x = 0; x < 2; ++x) {
-                pi[2 * j + x] = ok ? (int32_t)a[x] : -1;
-                pv[2 * j + x] = ok ? b[x] : 0.f;
+                pi[2 * j + x] = (int32_t)a[x];
+                pv[2 * j + x] = b[x];
               }
             } else {   // one pair per load: any k, arrays with their natural alignment only
-              pi[j] = ok ? ip[off] : -1;
-              pv[j] = ok ? vp[off] : 0.f;
+              pi[j] = ip[off];
+              pv[j] = vp[off];
               // the 32 offsets are formed eight at a time (all at once they would not fit the registers)
               if ((j & 7) == 7) __builtin_amdgcn_sched_barrier(0);
             }
@@ -228,6 +231,26 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
           }
           ip += 8 * wstride;
           vp += 8 * wstride;
+        }
+      }
+    }
+  };
+
+  // Units past the end of the chunk's payload (the last load of a lane may reach beyond W k pairs) become
+  // (no index, 0); called where the pairs are consumed.
+  auto mask_payload = [&](int round = 0) {
+    if constexpr (UNITS) {
+      int lanev = lane;
+      asm volatile("" : "+v"(lanev));
+#pragma unroll
+      for (int j = 0; j < NP / VW; ++j) {
+        if (j < nloads) {   // uniform
+          const bool ok = (STREAM ? 64 * (NP / VW) * round : 0) + 64 * j + lanev < nunits;
+#pragma unroll
+          for (int x = 0; x < VW; ++x) {
+            pi[VW * j + x] = ok ? pi[VW * j + x] : -1;
+            pv[VW * j + x] = ok ? pv[VW * j + x] : 0.f;
+          }
         }
       }
     }
@@ -332,6 +355,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     };
     if (PBF16 && !DENSE) fetch_x();
     DEMO_PHASE(0);
+    mask_payload(0);
 
     // ---- S = sum over workers ---------------------------------------------------------------------------
     int sh_chunk = 0;   // shift of this chunk's fixed point (undone when phi is the identity)
@@ -352,6 +376,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
       add_pairs(sh_chunk);
       for (int r = 1; r < nrounds; ++r) {
         load_payload(d, cc, r);
+        mask_payload(r);
         const int sh_r = shift_of(lane_max(0.f));
         if (sh_r < sh_chunk) {   // uniform
           const int dsh = min(sh_chunk - sh_r, 31);

@@ -567,25 +567,42 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       const uint32_t off = ok ? (uint32_t)(w * wstride + pos) : 0u;
       const f32x4 vv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pv[e] = ok ? vv[e] : 0.f;
+      for (int e = 0; e < 4; ++e) pv[e] = vv[e];
       const u32x4 iv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pi[e] = ok ? (int32_t)iv[e] : -1;
+      for (int e = 0; e < 4; ++e) pi[e] = (int32_t)iv[e];
       return;
+    }
+    // every offset before the first load, and the loads unconditional (a slot past the end reads the chunk's first
+    // pair; mask_payload discards it where the pairs are consumed): address arithmetic between the loads picked up a
+    // register of a load in flight as the unused high half of a 64-bit operand, and the wave then waited out that
+    // load before it issued the next (two memory round trips per chunk)
+    uint32_t off[W128_DEC_SLOTS];
+#pragma unroll
+    for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+      const int p = W128_THREADS * j + tid;
+      // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
+      // the rounding error of the float product for p < 4096
+      const int w = (int)(((float)p + 0.5f) * rk);
+      const int pos = p - w * k;
+      off[j] = p < npairs ? (uint32_t)w * (uint32_t)wstride + (uint32_t)pos : 0u;
     }
 #pragma unroll
     for (int j = 0; j < W128_DEC_SLOTS; ++j) {
       if (j < nslots) {                                        // uniform
-        const int p = W128_THREADS * j + tid;
-        // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
-        // the rounding error of the float product for p < 4096
-        const int w = (int)(((float)p + 0.5f) * rk);
-        const int pos = p - w * k;
-        const bool ok = p < npairs;
-        const uint32_t off = (uint32_t)(w * wstride + pos);
-        pi[j] = ok ? payload_load<true>(ip + off) : -1;
-        pv[j] = ok ? payload_load<true>(vp + off) : 0.f;
+        pi[j] = payload_load<true>(ip + off[j]);
+        pv[j] = payload_load<true>(vp + off[j]);
       }
+    }
+  };
+  // Slots past the end of the chunk's payload become (no index, 0).  Applied where the pairs are consumed, not where
+  // they are requested: a select behind the load would make the prefetch wait for its own data.
+  auto mask_payload = [&](int round = 0) {
+#pragma unroll
+    for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+      const bool ok = VEC4 ? (STREAM ? W128_THREADS * round : 0) + tid < nunits : W128_THREADS * j + tid < npairs;
+      pi[j] = ok ? pi[j] : -1;
+      pv[j] = ok ? pv[j] : 0.f;
     }
   };
 
@@ -593,6 +610,11 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
   TensorDev d = load_desc_uniform(tv, t);
   load_payload(d, chunk - t_first, 0);
+  // the first chunk's pairs are waited for here, outside the loop: with loads pending at the loop's entry and
+  // the parameter stores pending on its back edge, the loop's first wait would be for everything outstanding,
+  // i.e. every chunk would begin by waiting for the acknowledgements of the previous chunk's stores
+#pragma unroll
+  for (int j = 0; j < W128_DEC_SLOTS; ++j) asm volatile("" : "+v"(pi[j]), "+v"(pv[j]));
 
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                     // 30 - ceil(log2 W)
@@ -600,6 +622,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   const uint32_t dummy = (uint32_t)((tid & 127) * W128_LDX + 128 + ((tid >> 7) & 3));   // pad slot of this thread
 
   for (;;) {
+    mask_payload(0);
     const int cc = chunk - t_first;
     const uint32_t ucols = (uint32_t)d.cols;
     const int64_t origin = (int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128;
@@ -679,6 +702,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       // an earlier one, so the shifts together cost at most one unit of the final scale per coefficient)
       for (int r = 1; r < nrounds; ++r) {
         load_payload(d, cc, r);
+        mask_payload(r);
         post_wave_max(r & 1);
         wg_lds_barrier();   // maxima posted; the previous round's additions have landed
         const int sh_r = shift_from(r & 1);
