@@ -295,6 +295,15 @@ __device__ __forceinline__ void wave_lds_sync() {
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 __device__ __forceinline__ lds_u32* lds_u32_at(uint32_t byte_address) { return (lds_u32*)(uintptr_t)byte_address; }
 
+// The lane id formed on the spot (two VALU instructions, nothing kept alive for it).  For per-lane constants that are
+// needed late in a long loop body: derived from threadIdx they stay live across the whole body, and where the body
+// is short of registers they are spilled, which costs a wait for every load in flight at each reload.
+__device__ __forceinline__ int fresh_lane_id() {
+  int x;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(x));
+  return x;
+}
+
 // number of lanes below this one whose bit is set in mask
 __device__ __forceinline__ int lanes_below(uint64_t mask) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));

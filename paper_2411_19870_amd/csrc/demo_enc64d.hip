@@ -87,8 +87,6 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
   TensorDev d = load_desc_uniform(tv, t);
 
   const int col4 = 4 * chi(c);
-  // flat index inside a chunk of coefficient C2[vt][tt][r]: u*32 + v with u = 2c + tt%2, v = 2(4g + r) + vt%2
-  uint32_t fb = (uint32_t)(64 * c + 8 * g);
 
   struct Place {
     __amdgpu_buffer_rsrc_t mres, gres;
@@ -98,7 +96,9 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
     int32_t* idx;
     float* val;
   };
-  auto place = [&](const TensorDev& dd, int tt) {
+  // (g, col4: the lane's row within a group of four and first column, passed in so that the tile loop can form them
+  // on the spot instead of keeping them alive across its whole body)
+  auto place = [&](const TensorDev& dd, int tt, int g, int col4) {
     const int k0 = tt / dd.cchunks, k1 = tt - k0 * dd.cchunks;
     const int64_t origin = (int64_t)k0 * 64 * dd.cols + (int64_t)k1 * 64;   // uniform
     Place p;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
     }
   };
 
-  Place cur = place(d, tileno - t_first);
+  Place cur = place(d, tileno - t_first, g, col4);
   fetch_m(cur);
   fetch_g(cur);
   // The first tile's rows are waited for here, outside the loop: the wait at the top of the body then only has
@@ -159,7 +159,8 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      nxt = place(d, tileno + nwaves - t_first);
+      const int ln = fresh_lane_id();
+      nxt = place(d, tileno + nwaves - t_first, ln >> 4, 4 * chi(ln & 15));
     }
 
     // ---- momentum update: D[s][e][w] = element (row rho(4s+w, g), col 4 chi(c) + e) ------------------
@@ -186,8 +187,9 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) C1[e][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     {
-      const float4 pe4 = *reinterpret_cast<const float4*>(&sT1[(0 * 64 + lane) * 4]);
-      const float4 po4 = *reinterpret_cast<const float4*>(&sT1[(1 * 64 + lane) * 4]);
+      const int ln = fresh_lane_id();
+      const float4 pe4 = *reinterpret_cast<const float4*>(&sT1[(0 * 64 + ln) * 4]);
+      const float4 po4 = *reinterpret_cast<const float4*>(&sT1[(1 * 64 + ln) * 4]);
       const float pe[4] = {pe4.x, pe4.y, pe4.z, pe4.w}, po[4] = {po4.x, po4.y, po4.z, po4.w};
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
@@ -211,8 +213,9 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     {
-      const float4 pe4 = *reinterpret_cast<const float4*>(&sT2[(0 * 64 + lane) * 4]);
-      const float4 po4 = *reinterpret_cast<const float4*>(&sT2[(1 * 64 + lane) * 4]);
+      const int ln = fresh_lane_id();
+      const float4 pe4 = *reinterpret_cast<const float4*>(&sT2[(0 * 64 + ln) * 4]);
+      const float4 po4 = *reinterpret_cast<const float4*>(&sT2[(1 * 64 + ln) * 4]);
       const float pe[4] = {pe4.x, pe4.y, pe4.z, pe4.w}, po[4] = {po4.x, po4.y, po4.z, po4.w};
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
@@ -232,7 +235,10 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- top-k, once per chunk (bu, bv): coefficients C2[2bv + mh][2bu + nh][r] ---------------------------
-    asm volatile("" : "+v"(fb));
+    // the lane's number and the flat-index base of its coefficients, formed here for the four selections (flat index
+    // inside a chunk of coefficient C2[vt][tt][r]: u*32 + v with u = 2c + tt%2, v = 2(4g + r) + vt%2)
+    const int lt = fresh_lane_id();
+    const uint32_t fbt = (uint32_t)(64 * (lt & 15) + 8 * (lt >> 4));
     bool skip = false;
     int ncls[4] = {0, 0, 0, 0};   // selected coefficients per class 2 bu + (u % 2) (uniform)
 #pragma unroll
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
                 if (is && ncand <= ED_CAP) {   // a full list takes no more: slot < CAP + 64 without a per-lane clamp
                   lds_u32* slot = lds_u32_at(list_end + 4u * (uint32_t)lanes_below(mask));
                   slot[0] = __float_as_uint(q);
-                  slot[ED_LIST] = fb + (uint32_t)(32 * nh + mh + 2 * r);
+                  slot[ED_LIST] = fbt + (uint32_t)(32 * nh + mh + 2 * r);
                 }
                 const int hits = __popcll(mask);
                 ncand += hits;
@@ -282,15 +288,15 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
       const int c32 = (2 * cur.K0 + bu) * cur.cch32 + 2 * cur.K1 + bv;   // chunk number in the tensor
       wave_lds_sync();
       if (all_zero) {
-        if (lane < k) {
-          const int64_t po = (int64_t)c32 * k + lane;
-          store_guarded(as_global(cur.idx) + po, (int32_t)lane);
+        if (lt < k) {
+          const int64_t po = (int64_t)c32 * k + lt;
+          store_guarded(as_global(cur.idx) + po, (int32_t)lt);
           store_guarded(as_global(cur.val) + po, 0.f);
         }
       } else if (!overflow) {
         // rank the candidates (magnitude descending, flat index ascending); ranks < k are the payload
         for (int i0 = 0; i0 < ncand; i0 += 64) {
-          const int i = i0 + lane;
+          const int i = i0 + lt;
           const uint2 me = make_uint2(cand_v[i < ncand ? i : 0], cand_f[i < ncand ? i : 0]);
           const uint32_t mag = me.x & 0x7fffffffu;
           int rank = 0;
@@ -299,13 +305,18 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
             // two per 16-byte read at a wavefront-uniform address (lanes past the list carry key 0, which precedes nothing)
             const uint32_t magl = i < ncand ? mag : 0u, nfl = i < ncand ? ~me.y : 0u;
             const uint64_t key = ((uint64_t)magl << 32) | nfl;
-            keys[lane] = make_uint2(nfl, magl);
+            keys[lt] = make_uint2(nfl, magl);
             wave_lds_sync();
-            for (int j = 0; j < ncand; j += 4) {
-              const uint4 a = *reinterpret_cast<const uint4*>(&keys[j]);
-              const uint4 b = *reinterpret_cast<const uint4*>(&keys[j + 2]);
-              rank += ((((uint64_t)a.y << 32) | a.x) > key ? 1 : 0) + ((((uint64_t)a.w << 32) | a.z) > key ? 1 : 0);
-              rank += ((((uint64_t)b.y << 32) | b.x) > key ? 1 : 0) + ((((uint64_t)b.w << 32) | b.z) > key ? 1 : 0);
+            // sixteen keys per turn, all eight reads issued before the first comparison: a turn costs one LDS round
+            // trip, and with four selections per tile the round trips of a four-key loop added up to a fifth of the
+            // kernel's time at k = 32 (all 64 keys exist: lanes past the list wrote zeros)
+            for (int j = 0; j < ncand; j += 16) {
+              uint4 kk[8];
+#pragma unroll
+              for (int x = 0; x < 8; ++x) kk[x] = *reinterpret_cast<const uint4*>(&keys[j + 2 * x]);
+#pragma unroll
+              for (int x = 0; x < 8; ++x)
+                rank += ((((uint64_t)kk[x].y << 32) | kk[x].x) > key ? 1 : 0) + ((((uint64_t)kk[x].w << 32) | kk[x].z) > key ? 1 : 0);
             }
           } else {
             for (int j = 0; j < ncand; ++j) {
@@ -336,8 +347,8 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
     }
     if (skip) {
       // leave the tile untouched (its payload entries are overwritten too) and queue its four chunks
-      if (lane < 4) {
-        const int c32 = (2 * cur.K0 + (lane >> 1)) * cur.cch32 + 2 * cur.K1 + (lane & 1);
+      if (lt < 4) {
+        const int c32 = (2 * cur.K0 + (lt >> 1)) * cur.cch32 + 2 * cur.K1 + (lt & 1);
         store_guarded(&wl.list[atomicAdd(wl.count, 1)], prefix32[cur.tix] + c32);   // chunk number in the 32-grid table
       }
     }
@@ -351,22 +362,59 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
     //      The column side is the block-diagonal matrix as before (rows of B vanish outside their block).
 #pragma unroll
     for (int q = 0; q < 4; ++q)   // pad every class list with zero-valued entries to a multiple of four
-      if (lane < ((4 - (ncls[q] & 3)) & 3)) sel[q * ED_SELCLS + ncls[q] + lane] = make_uint2(0u, 0u);
+      if (lt < ((4 - (ncls[q] & 3)) & 3)) sel[q * ED_SELCLS + ncls[q] + lt] = make_uint2(0u, 0u);
     wave_lds_sync();
     if (!skip) {
+      // the lane's place in the class lists is formed anew for every tile: kept across the tile loop the four list
+      // addresses are spilled, and the reload of a spilled value waits for every load in flight, i.e. for the
+      // rows of the next tile
+      const int lane_now = fresh_lane_id();
+      const int gl = lane_now >> 4, cl = lane_now & 15;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         f32x4 R[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) R[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        for (int ks = 0; ks < (ncls[q] + 3) / 4; ++ks) {
-          const uint2 sv = sel[q * ED_SELCLS + 4 * ks + g];
-          const float nv = -(args.alpha * __uint_as_float(sv.y));
-          const float a = nv * sPk[(sv.x >> 6) * 16 + c];
-          const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
-          const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) R[e] = mfma4(a, bf[e], R[e]);
+        // A step's operands hang on two LDS reads in a row (the list entry, then the two basis rows it names).  The
+        // loop runs two steps per turn on alternating registers, with the entry fetched two steps and the rows one
+        // step ahead and scheduling fences around the MFMAs, so that no step waits for its own reads (at k = 32 a tile
+        // has about 32 steps, and this kernel is bound by its own instructions; without the fences the compiler
+        // sinks every read to its use)
+        const int n = (ncls[q] + 3) >> 2;   // uniform
+        if (n > 0) {
+          struct Rows {
+            float val, pk;
+            float4 pb;
+          };
+          auto entry = [&](int step) { return sel[q * ED_SELCLS + 4 * min(step, n - 1) + gl]; };
+          auto rows_of = [&](const uint2& sv) {
+            return Rows{__uint_as_float(sv.y), sPk[((sv.x >> 6) & 31u) * 16 + cl],
+                        *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * cl])};
+          };
+          auto accumulate = [&](const Rows& r) {
+            const float a = -(args.alpha * r.val) * r.pk;
+            R[0] = mfma4(a, r.pb.x, R[0]);
+            R[1] = mfma4(a, r.pb.y, R[1]);
+            R[2] = mfma4(a, r.pb.z, R[2]);
+            R[3] = mfma4(a, r.pb.w, R[3]);
+          };
+          uint2 sv = entry(0);
+          Rows ra = rows_of(sv), rb;
+          sv = entry(1);
+          for (int ks = 0; ks < n; ks += 2) {
+            rb = rows_of(sv);       // step ks + 1 (past the end: the last step again, unused)
+            sv = entry(ks + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            accumulate(ra);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 1 < n) {       // uniform
+              ra = rows_of(sv);     // step ks + 2
+              sv = entry(ks + 3);
+              __builtin_amdgcn_sched_barrier(0);
+              accumulate(rb);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
         }
         const int w0 = 2 * (q >> 1);
 #pragma unroll
