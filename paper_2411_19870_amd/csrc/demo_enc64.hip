@@ -512,11 +512,15 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       keys[lane] = make_uint2(nfl, mag);
       wave_lds_sync();
       int rank = 0;
-      for (int j = 0; j < ncand; j += 4) {
-        const uint4 a = *reinterpret_cast<const uint4*>(&keys[j]);
-        const uint4 b = *reinterpret_cast<const uint4*>(&keys[j + 2]);
-        rank += ((((uint64_t)a.y << 32) | a.x) > key ? 1 : 0) + ((((uint64_t)a.w << 32) | a.z) > key ? 1 : 0);
-        rank += ((((uint64_t)b.y << 32) | b.x) > key ? 1 : 0) + ((((uint64_t)b.w << 32) | b.z) > key ? 1 : 0);
+      // sixteen keys per turn, all eight reads issued before the first comparison: one LDS round trip per turn
+      // (all 64 keys exist: lanes past the list wrote zeros)
+      for (int j = 0; j < ncand; j += 16) {
+        uint4 kk[8];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) kk[x] = *reinterpret_cast<const uint4*>(&keys[j + 2 * x]);
+#pragma unroll
+        for (int x = 0; x < 8; ++x)
+          rank += ((((uint64_t)kk[x].y << 32) | kk[x].x) > key ? 1 : 0) + ((((uint64_t)kk[x].w << 32) | kk[x].z) > key ? 1 : 0);
       }
       const bool selected = lane < ncand && rank < k;
       if (selected) {
