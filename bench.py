@@ -35,7 +35,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 S, K, W = 64, 32, 64
 BETA, LR, WD = 0.999, 1e-3, 0.0
-CPU_SAMPLE_FRACTION = 0.10
+CPU_SAMPLE_FRACTION = 0.30
 
 
 def algorithmic_bytes(specs, s, k, W, grad_bytes, param_bytes):

@@ -75,9 +75,16 @@ __device__ __forceinline__ int first_work_item(int wave) {
 // the entries through the first active lane keeps them (and every address derived from them, e.g. a
 // buffer resource descriptor) in scalar registers; without it the compiler must assume a divergent
 // descriptor and wraps each buffer access in a loop over the distinct values.
+//
+// The walk from one tensor to the next (prefix sums, descriptors; `t` wavefront-uniform) reads the table through
+// the constant address space, i.e. with scalar loads: the table is written before the launch and never during it.
+// Read with vector loads, the walk's waits count in the same counter as the tensor loads and stores, and the
+// point where the walk's rarely taken loop rejoins the chunk loop became a wait for everything outstanding.
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
 __device__ __forceinline__ int uniform_i32(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ int uniform_prefix(const TableView& tv, int t) {
-  return __builtin_amdgcn_readfirstlane(as_global(tv.prefix)[t]);
+  return (int)((const_i32_ptr)(uintptr_t)tv.prefix)[t];
 }
 __device__ __forceinline__ int find_tensor_uniform(const TableView& tv, int chunk) {
   return __builtin_amdgcn_readfirstlane(find_tensor(tv.prefix, tv.n, chunk));
@@ -86,10 +93,10 @@ __device__ __forceinline__ TensorDev load_desc_uniform(const TableView& tv, int 
   static_assert(sizeof(TensorDev) % 4 == 0, "descriptor is a whole number of dwords");
   constexpr int NW = sizeof(TensorDev) / 4;
   struct Words { uint32_t w[NW]; };
-  const DEMO_GLOBAL uint32_t* p = reinterpret_cast<const DEMO_GLOBAL uint32_t*>(as_global(tv.descs) + t);
+  const_u32_ptr p = (const_u32_ptr)(uintptr_t)(tv.descs + t);
   Words u;
 #pragma unroll
-  for (int i = 0; i < NW; ++i) u.w[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)p[i]);
+  for (int i = 0; i < NW; ++i) u.w[i] = p[i];
   return __builtin_bit_cast(TensorDev, u);
 }
 
