@@ -21,6 +21,7 @@ DEMO_OK, DEMO_ERR_ARG, DEMO_ERR_SHAPE, DEMO_ERR_UNSUPPORTED, DEMO_ERR_HIP, DEMO_
 DEMO_F32, DEMO_BF16 = 0, 1
 DEMO_MAX_K = 256
 DEMO_MAX_W_IDENTITY = 1024
+DEMO_MAX_COLS = 1 << 22
 DEMO_PHI_SIGN, DEMO_PHI_IDENTITY = 0, 1
 DEMO_AGG_SUM, DEMO_AGG_MEAN, DEMO_AGG_COUNT = 0, 1, 2
 DEMO_BASIS_DCT, DEMO_BASIS_IDENTITY, DEMO_BASIS_GRAM_SCHMIDT = 0, 1, 2

@@ -26,7 +26,7 @@ def pool():
 
 
 def make_set(name, s, k, W, gdt, pdt, seed, grad=True):
-    specs = synth.tensor_set(name)
+    specs = synth.tensor_set(name) if isinstance(name, str) else list(name)
     tensors = []
     for ti, sp in enumerate(specs):
         g = synth.gaussian(sp, 1e-2, seed, ti, 0, "grad", dtype=gdt, device=DEV) if grad else \
@@ -115,16 +115,18 @@ def encode_then_decodes(pool, name, s, k, Ws, gdt, pdt, seed, projection_step=No
     energy_mid = energy_of_update(tensors)
     ctx.demo_encode(tl, BETA, s, k)
     torch.cuda.synchronize()
-    submit_encode(pool, tally_e, specs, tensors, s, k, picks, m0, g0, f"{name} s={s} k={k}", P)
+    tag = (name if isinstance(name, str) else specs[0].name) + f" s={s} k={k}"
+    submit_encode(pool, tally_e, specs, tensors, s, k, picks, m0, g0, tag, P)
     check_any_size_properties(specs, tensors, s, energy_mid)
     for W in Ws:
         x0 = gather(tensors, specs, s, picks, "param")
         ctx.demo_decode(tl, W, LR, 0.0, s, k)
         torch.cuda.synchronize()
-        submit_decode(pool, tally_d, specs, tensors, s, k, W, picks, x0, pd, f"{name} s={s} k={k}", P)
+        submit_decode(pool, tally_d, specs, tensors, s, k, W, picks, x0, pd, tag, P)
     se, sd = tally_e.drain(), tally_d.drain()
     ctx.close()
-    print(f"{name} s={s} k={k} W={Ws} {gdt} / {pdt}: {sample_report(specs, s, picks)}; encode {se}; decode {sd}")
+    label = name if isinstance(name, str) else "+".join(sp.name for sp in specs)
+    print(f"{label} s={s} k={k} W={Ws} {gdt} / {pdt}: {sample_report(specs, s, picks)}; encode {se}; decode {sd}")
     del tensors, tl
     torch.cuda.empty_cache()
     return se, sd
@@ -151,6 +153,14 @@ def test_full_size_300m_fp32_other_chunk_sizes(pool, s, k, W):
 @pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
 def test_full_size_300m_random_projection(pool, gdt):
     encode_then_decodes(pool, "300m", 64, 32, [1, 16], gdt, gdt, 4, projection_step=7)
+
+
+# ---- the widest tensor the library accepts (cols < 2^22): with float32 elements the last rows of a chunk lie just
+#      below the 2 GiB that a buffer resource addresses -------------------------------------------------------------
+@pytest.mark.parametrize("s", [32, 64, 128])
+def test_widest_tensor_the_kernels_accept(pool, s):
+    specs = [synth.TensorSpec("wide", 128, B.DEMO_MAX_COLS - 128), synth.TensorSpec("v", 4096, 0)]
+    encode_then_decodes(pool, specs, s, 8, [2], torch.float32, torch.float32, 5)
 
 
 # ---- stress sweep at full size: heavy-tailed bf16 gradients (exact magnitude ties), momentum carried over 10
