@@ -163,6 +163,14 @@ def test_widest_tensor_the_kernels_accept(pool, s):
     encode_then_decodes(pool, specs, s, 8, [2], torch.float32, torch.float32, 5)
 
 
+# ---- one tensor of more than 2^31 elements: chunk origins and payload positions need 64-bit arithmetic ------------------
+@pytest.mark.parametrize("s", [64, 128])
+def test_tensor_of_more_than_2_pow_31_elements(pool, s):
+    specs = [synth.TensorSpec("huge", 65536, 32768 + 64 * s)]
+    assert specs[0].numel > 2 ** 31
+    encode_then_decodes(pool, specs, s, 8, [1], torch.bfloat16, torch.bfloat16, 6)
+
+
 # ---- stress sweep at full size: heavy-tailed bf16 gradients (exact magnitude ties), momentum carried over 10
 #      steps of encode + decode of the worker's own payload; the oracle starts every step from the GPU's momentum --
 @pytest.mark.parametrize("s", [32, 64, 128])
