@@ -450,6 +450,23 @@ def test_many_distinct_tensor_lists(ctx):
             run_encode_check(ctx, case)
 
 
+# ---- a list of 1500 small tensors (a model of many small layers): descriptor tables of several upload launches, the
+#      tensor walk of the persistent kernels at nearly every work item ---------------------------------------------------
+@pytest.mark.parametrize("s", [32, 64, 128])
+def test_list_of_1500_small_tensors(ctx, s):
+    ctx.demo_set_variant(1)
+    k = 4
+    specs = []
+    for i in range(1500):
+        if i % 5 == 4:
+            specs.append(synth.TensorSpec(f"v{i}", 128 * (1 + i % 2), 0))
+        else:
+            specs.append(synth.TensorSpec(f"a{i}", 128 * (1 + i % 2), 128 * (1 + (i // 2) % 3)))
+    case = Case(specs, s, k, W=2, seed=77)
+    run_encode_check(ctx, case)
+    run_decode_check(ctx, case, W=2)
+
+
 # ---- non-finite inputs: the result for the chunks that hold them is undefined, but the call returns and every other
 #      chunk comes out as it does without them (no loop of any kernel depends on the data for its end) --------------------
 @pytest.mark.parametrize("s", [32, 64, 128])
