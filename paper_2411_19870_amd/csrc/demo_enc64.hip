@@ -577,18 +577,52 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       if (!skip && STAGE == 0) {
         // D[r][e][w] -= alpha sum_t val_t P[u_t][rho(4r + w, g)] P[v_t][4 chi(c) + e]: MFMA row m = 4g + r of the
         // tile of member w is row rho(4r + w, g); one member per pass over the list keeps the accumulators at 16 registers
+        // A step's operands hang on two LDS reads in a row (the list entry, then the two basis rows it names): the
+        // loop runs two steps per turn on alternating registers, the entry fetched two steps and the rows one step
+        // ahead, with scheduling fences around the MFMAs (without them the compiler sinks every read to its use and a
+        // step of four MFMAs waits out two LDS round trips)
+        const int n = __builtin_amdgcn_readfirstlane((ncls[0] + 3) >> 2);
+        const int lane_now = fresh_lane_id();
+        const int gl = lane_now >> 4, cl = lane_now & 15;
+        struct Rows {
+          float val, pr;
+          float4 pb;
+        };
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           f32x4 Ra[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) Ra[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-          for (int ks = 0; ks < (ncls[0] + 3) / 4; ++ks) {
-            const uint2 sv = sel[4 * ks + g];
-            const float a0 = -(args.alpha * __uint_as_float(sv.y)) * sProw[((sv.x >> 6) & 63u) * 64 + c + 16 * w];
-            const float4 pb = *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * c]);
-            const float bf[4] = {pb.x, pb.y, pb.z, pb.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) Ra[e] = mfma4(a0, bf[e], Ra[e]);
+          if (n > 0) {
+            auto entry = [&](int step) { return sel[4 * min(step, n - 1) + gl]; };
+            auto rows_of = [&](const uint2& sv) {
+              return Rows{__uint_as_float(sv.y), sProw[((sv.x >> 6) & 63u) * 64 + cl + 16 * w],
+                          *reinterpret_cast<const float4*>(&sPcol[(sv.x & 63u) * 64 + 4 * cl])};
+            };
+            auto accumulate = [&](const Rows& r) {
+              const float a0 = -(args.alpha * r.val) * r.pr;
+              Ra[0] = mfma4(a0, r.pb.x, Ra[0]);
+              Ra[1] = mfma4(a0, r.pb.y, Ra[1]);
+              Ra[2] = mfma4(a0, r.pb.z, Ra[2]);
+              Ra[3] = mfma4(a0, r.pb.w, Ra[3]);
+            };
+            uint2 sv = entry(0);
+            Rows ra = rows_of(sv), rb;
+            sv = entry(1);
+            for (int ks = 0; ks < n; ks += 2) {
+              rb = rows_of(sv);       // step ks + 1 (past the end: the last step again, unused)
+              sv = entry(ks + 2);
+              __builtin_amdgcn_sched_barrier(0);
+              accumulate(ra);
+              __builtin_amdgcn_sched_barrier(0);
+              if (ks + 1 < n) {       // uniform
+                ra = rows_of(sv);     // step ks + 2
+                sv = entry(ks + 3);
+                __builtin_amdgcn_sched_barrier(0);
+                accumulate(rb);
+                __builtin_amdgcn_sched_barrier(0);
+              }
+            }
           }
 #pragma unroll
           for (int sq = 0; sq < 4; ++sq)
