@@ -423,19 +423,33 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     } else {
     // ---- top-k inside the wavefront ------------------------------------------------------------
     // (1) a lower bound of the k-th largest magnitude: the k-th largest of the 64 per-lane maxima,
-    //     resolved to its upper 16 bits
-    float lmax = 0.f;
+    //     resolved to its upper 16 bits.  For k > 32 the bound comes from 128 maxima instead, two per lane (of the
+    //     lane's first and second 32 coefficients): among 64 maxima the k-th largest sinks towards the smallest
+    //     one as k approaches 64, the candidate list (about 44 entries at k = 32) then overflows for every chunk,
+    //     and every chunk would go to the exact kernel.  With 128 maxima k = 64 gives about 90 candidates.
+    float lmax0 = 0.f, lmax1 = 0.f;
 #pragma unroll
-    for (int vt = 0; vt < 4; ++vt)
+    for (int vt = 0; vt < 2; ++vt)
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) lmax = fmaxf(lmax, fabsf(C2[vt][tt][r]));
-    const uint32_t lm = __float_as_uint(lmax);
+        for (int r = 0; r < 4; ++r) {
+          lmax0 = fmaxf(lmax0, fabsf(C2[vt][tt][r]));
+          lmax1 = fmaxf(lmax1, fabsf(C2[vt + 2][tt][r]));
+        }
+    const uint32_t lm0 = __float_as_uint(lmax0), lm1 = __float_as_uint(lmax1);
+    const uint32_t lm = max(lm0, lm1);
     uint32_t thr = 0;
-    for (int bit = 30; bit >= 16; --bit) {
-      const uint32_t cnd = thr | (1u << bit);
-      if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
+    if (k <= 32) {
+      for (int bit = 30; bit >= 16; --bit) {
+        const uint32_t cnd = thr | (1u << bit);
+        if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
+      }
+    } else {
+      for (int bit = 30; bit >= 16; --bit) {
+        const uint32_t cnd = thr | (1u << bit);
+        if (__popcll(__ballot(lm0 >= cnd)) + __popcll(__ballot(lm1 >= cnd)) >= k) thr = cnd;
+      }
     }
     DEMO_PHASE(3);
     // (2) gather candidates |q| >= thr: one compare and one scalar branch per coefficient.  The LDS byte address of
@@ -530,9 +544,12 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       }
       file_selected(selected, me_f, me_v);
     } else {
-      if (lane == 0 && (ncand & 1)) {
-        cand_v[ncand] = 0u;
-        cand_f[ncand] = 0xffffffffu;
+      // more candidates than lanes (k > 32, or many magnitudes near the bound): the list is padded to a multiple of
+      // eight with entries that precede nothing, and every lane ranks its candidate of each block of 64 against
+      // the whole list, eight entries per turn with all reads issued before the first comparison
+      if (lane < ((8 - (ncand & 7)) & 7)) {
+        cand_v[ncand + lane] = 0u;
+        cand_f[ncand + lane] = 0xffffffffu;
       }
       wave_lds_sync();
       for (int base = 0; base < ncand; base += 64) {   // uniform trip count: the ballots below need every lane
@@ -541,12 +558,19 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
         const uint32_t me_v = cand_v[valid ? i : 0], me_f = cand_f[valid ? i : 0];
         const uint32_t mag = me_v & 0x7fffffffu;
         int rank = 0;
-        for (int j = 0; j < ncand; j += 2) {
-          const uint2 ov = *reinterpret_cast<const uint2*>(&cand_v[j]);
-          const uint2 of = *reinterpret_cast<const uint2*>(&cand_f[j]);
-          const uint32_t m0 = ov.x & 0x7fffffffu, m1 = ov.y & 0x7fffffffu;
-          rank += (m0 > mag || (m0 == mag && of.x < me_f)) ? 1 : 0;
-          rank += (m1 > mag || (m1 == mag && of.y < me_f)) ? 1 : 0;
+        for (int j = 0; j < ncand; j += 8) {
+          uint2 ov[4], of[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            ov[x] = *reinterpret_cast<const uint2*>(&cand_v[j + 2 * x]);
+            of[x] = *reinterpret_cast<const uint2*>(&cand_f[j + 2 * x]);
+          }
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const uint32_t m0 = ov[x].x & 0x7fffffffu, m1 = ov[x].y & 0x7fffffffu;
+            rank += (m0 > mag || (m0 == mag && of[x].x < me_f)) ? 1 : 0;
+            rank += (m1 > mag || (m1 == mag && of[x].y < me_f)) ? 1 : 0;
+          }
         }
         const bool selected = valid && rank < k;
         if (selected) {

@@ -244,18 +244,30 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
 #pragma unroll
     for (int sub = 0; sub < 4; ++sub) {
       const int bu = sub >> 1, bv = sub & 1;
-      float lmax = 0.f;
+      // lower bound of the chunk's k-th largest magnitude: the k-th largest of the 64 per-lane maxima; for k > 32
+      // of 128 maxima, two per lane (see demo_enc64.hip: with 64 maxima the list overflows for every chunk as k
+      // approaches 64)
+      float lmax0 = 0.f, lmax1 = 0.f;
 #pragma unroll
-      for (int mh = 0; mh < 2; ++mh)
+      for (int nh = 0; nh < 2; ++nh)
 #pragma unroll
-        for (int nh = 0; nh < 2; ++nh)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) lmax = fmaxf(lmax, fabsf(C2[2 * bv + mh][2 * bu + nh][r]));
-      const uint32_t lm = __float_as_uint(lmax);
+        for (int r = 0; r < 4; ++r) {
+          lmax0 = fmaxf(lmax0, fabsf(C2[2 * bv + 0][2 * bu + nh][r]));
+          lmax1 = fmaxf(lmax1, fabsf(C2[2 * bv + 1][2 * bu + nh][r]));
+        }
+      const uint32_t lm0 = __float_as_uint(lmax0), lm1 = __float_as_uint(lmax1);
+      const uint32_t lm = max(lm0, lm1);
       uint32_t thr = 0;
-      for (int bit = 30; bit >= 16; --bit) {
-        const uint32_t cnd = thr | (1u << bit);
-        if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
+      if (k <= 32) {
+        for (int bit = 30; bit >= 16; --bit) {
+          const uint32_t cnd = thr | (1u << bit);
+          if (__popcll(__ballot(lm >= cnd)) >= k) thr = cnd;
+        }
+      } else {
+        for (int bit = 30; bit >= 16; --bit) {
+          const uint32_t cnd = thr | (1u << bit);
+          if (__popcll(__ballot(lm0 >= cnd)) + __popcll(__ballot(lm1 >= cnd)) >= k) thr = cnd;
+        }
       }
       int ncand = 0;
       uint32_t list_end = list_base;   // scalar LDS byte address of the list's end
@@ -294,6 +306,11 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
           store_guarded(as_global(cur.val) + po, 0.f);
         }
       } else if (!overflow) {
+        if (ncand > 64 && lt < ((8 - (ncand & 7)) & 7)) {   // padding for the eight-entry turns below
+          cand_v[ncand + lt] = 0u;
+          cand_f[ncand + lt] = 0xffffffffu;
+        }
+        if (ncand > 64) wave_lds_sync();
         // rank the candidates (magnitude descending, flat index ascending); ranks < k are the payload
         for (int i0 = 0; i0 < ncand; i0 += 64) {
           const int i = i0 + lt;
@@ -319,10 +336,21 @@ __global__ __launch_bounds__(ED_THREADS) void encode2d_tile32(TableView tv, cons
                 rank += ((((uint64_t)kk[x].y << 32) | kk[x].x) > key ? 1 : 0) + ((((uint64_t)kk[x].w << 32) | kk[x].z) > key ? 1 : 0);
             }
           } else {
-            for (int j = 0; j < ncand; ++j) {
-              const uint32_t ov = cand_v[j], of = cand_f[j];
-              const uint32_t mo = ov & 0x7fffffffu;
-              rank += (mo > mag || (mo == mag && of < me.y)) ? 1 : 0;
+            // more candidates than lanes: against the whole list (padded below to a multiple of eight with entries
+            // that precede nothing), eight entries per turn with all reads issued before the first comparison
+            for (int j = 0; j < ncand; j += 8) {
+              uint2 ov[4], of[4];
+#pragma unroll
+              for (int x = 0; x < 4; ++x) {
+                ov[x] = *reinterpret_cast<const uint2*>(&cand_v[j + 2 * x]);
+                of[x] = *reinterpret_cast<const uint2*>(&cand_f[j + 2 * x]);
+              }
+#pragma unroll
+              for (int x = 0; x < 4; ++x) {
+                const uint32_t m0 = ov[x].x & 0x7fffffffu, m1 = ov[x].y & 0x7fffffffu;
+                rank += (m0 > mag || (m0 == mag && of[x].x < me.y)) ? 1 : 0;
+                rank += (m1 > mag || (m1 == mag && of[x].y < me.y)) ? 1 : 0;
+              }
             }
           }
           const bool selected = i < ncand && rank < k;

@@ -304,6 +304,19 @@ def test_s32_list_with_and_without_64_multiples(ctx):
     run_decode_check(ctx, case, W=4, wd=0.1)
 
 
+# ---- budgets between 32 and 64 on the wavefront kernels: the threshold bound comes from two maxima per lane, the
+#      candidate list is longer than the wavefront and is ranked in blocks of 64 -------------------------------------
+@pytest.mark.parametrize("s,k", [(64, 33), (64, 48), (64, 56), (64, 64), (32, 33), (32, 48), (32, 64), (128, 64)])
+@pytest.mark.parametrize("grad", ["gauss", "student"])
+def test_budgets_above_32_on_the_fast_kernels(ctx, s, k, grad):
+    ctx.demo_set_variant(1)
+    case = Case([synth.TensorSpec("a", 512, 768)], s, k, W=1, seed=1000 + k, grad=grad,
+                grad_dtype=torch.bfloat16 if grad == "student" else torch.float32)
+    for st in run_encode_check(ctx, case):
+        assert st["chunks"] == case.specs[0].nchunks(s)
+    run_decode_check(ctx, case, W=1)
+
+
 # ---- large sparsity budgets and many workers (generic kernels; k = 64 is the last budget of the s = 64 wavefront kernel)
 @pytest.mark.parametrize("s,k", [(64, 64), (64, 65), (64, 256), (32, 200), (128, 256)])
 def test_large_k(ctx, s, k):
