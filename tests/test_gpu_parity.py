@@ -195,6 +195,27 @@ def test_many_near_equal_magnitudes(ctx, variant, nequal):
     ctx.demo_set_variant(1)
 
 
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("s", [32, 64, 128])
+def test_spectrum_confined_to_a_few_rows_and_columns(ctx, s, gdt):
+    # every chunk's spectrum lives on a 16 x 16 grid of frequency pairs (low ones and a few odd high
+    # ones), the rest is rounding noise five orders below: whatever way a kernel spreads coefficients
+    # over lanes, the large ones sit in a small part of them, so a threshold taken from per-lane
+    # maxima is far below the k-th magnitude and the candidate list is long
+    import scipy.fft
+    rng = np.random.default_rng(s)
+    u = np.array([0, 1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 14, s // 2 + 1, s // 2 + 3, s // 2 + 5, s // 2 + 7])
+    sp = [synth.TensorSpec("a", 4 * s, 6 * s)]
+    case = Case(sp, s, 32, grad="zero", mom_std=0, grad_dtype=gdt, seed=12)
+    q = np.zeros((4, 6, s, s))
+    q[:, :, u[:, None], u[None, :]] = rng.standard_normal((4, 6, 16, 16))
+    g = 1e-2 * scipy.fft.idctn(q, type=2, norm="ortho", axes=(2, 3)).transpose(0, 2, 1, 3).reshape(4 * s, 6 * s)
+    case.g[0].copy_(torch.from_numpy(g).to(gdt))
+    st = run_encode_check(ctx, case, beta=0.0)[0]
+    print("confined spectrum", s, gdt, st)
+    assert st["sets_identical"] + st["tie_swaps"] == st["chunks"] == 24
+
+
 @pytest.mark.parametrize("s", [32, 64, 128])
 def test_k_equals_M_exact_recovery_1d(ctx, s):
     # k = M on order-1 chunks: the payload is the whole spectrum, the residual momentum vanishes
