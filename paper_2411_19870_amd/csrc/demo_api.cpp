@@ -29,6 +29,7 @@ struct BasisTable {
   float* dec64 = nullptr;
   float* enc32 = nullptr;    // dense-basis tile tables for s = 32
   float* dec32 = nullptr;    // fragment table of the s = 32 tile decode kernel
+  float* dec128 = nullptr;   // fragment tables of the s = 128 decode kernel
   float* custom = nullptr;   // s x s matrix set with demo_set_basis (identity / Gram-Schmidt), allocated on first use
   float* custom_enc64 = nullptr;   // s = 64: tables of the full-product wavefront kernels for `custom`
   float* custom_dec64 = nullptr;
@@ -167,7 +168,7 @@ int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
 // Host copies of the tables of one chunk size: the orthonormal DCT-II matrix P[u][n] = c_u cos(pi (2n+1) u / (2s))
 // evaluated in double precision and rounded once to float32, and the fragment tables the wavefront kernels read.
 struct HostBasis {
-  std::vector<float> P, enc64, dec64, enc32, dec32;
+  std::vector<float> P, enc64, dec64, enc32, dec32, dec128;
 };
 
 void build_host_basis(int s, HostBasis* hb) {
@@ -195,6 +196,10 @@ void build_host_basis(int s, HostBasis* hb) {
     hb->dec32.resize(demo::kDec32TableFloats);
     demo::build_dec32_tables(P.data(), hb->dec32.data());
   }
+  if (s == 128) {
+    hb->dec128.resize(demo::kDec128TableFloats);
+    demo::build_dec128_tables(P.data(), hb->dec128.data());
+  }
 }
 
 int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
@@ -204,6 +209,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
       // kernels that read the matrix itself
       *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr, false, b.custom_enc64, b.custom_dec64}
                           : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
+      if (!b.use_custom) out->dec128 = b.dec128;
       return DEMO_OK;
     }
   HostBasis hb;
@@ -218,13 +224,16 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     if (b.dec64) (void)hipFree(b.dec64);
     if (b.enc32) (void)hipFree(b.enc32);
     if (b.dec32) (void)hipFree(b.dec32);
+    if (b.dec128) (void)hipFree(b.dec128);
   };
   if (!hb.enc64.empty() && (rc = upload(ctx, hb.enc64, &b.enc64)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec64.empty() && (rc = upload(ctx, hb.dec64, &b.dec64)) != DEMO_OK) { drop(); return rc; }
   if (!hb.enc32.empty() && (rc = upload(ctx, hb.enc32, &b.enc32)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec32.empty() && (rc = upload(ctx, hb.dec32, &b.dec32)) != DEMO_OK) { drop(); return rc; }
+  if (!hb.dec128.empty() && (rc = upload(ctx, hb.dec128, &b.dec128)) != DEMO_OK) { drop(); return rc; }
   ctx->bases.push_back(b);
   *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
+  out->dec128 = b.dec128;
   return DEMO_OK;
 }
 
@@ -568,6 +577,7 @@ int demo_destroy(demo_ctx* ctx) {
       if (b.dec64) (void)hipFree(b.dec64);
       if (b.enc32) (void)hipFree(b.enc32);
       if (b.dec32) (void)hipFree(b.dec32);
+      if (b.dec128) (void)hipFree(b.dec128);
       if (b.custom) (void)hipFree(b.custom);
       if (b.custom_enc64) (void)hipFree(b.custom_enc64);
       if (b.custom_dec64) (void)hipFree(b.custom_dec64);

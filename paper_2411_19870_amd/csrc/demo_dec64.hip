@@ -44,13 +44,13 @@ constexpr int D64_PK = 4096 + 1536;                // pk[u*16 + c]  = P[u][kappa
 constexpr int D64_PK2 = 4096 + 1536 + 1024;        // pk2[u*16 + c] = P[u][31 - kappa(c)]  (odd u: the second member)
 constexpr int D64_ALL_TABLE_FLOATS = 4096 + 1536 + 2048;
 constexpr int D64_LDS_BYTES = 4 * (D64_G_FLOATS + D64_WAVES * D64_TILE_FLOATS);
-// Instances for a projection matrix without mirror symmetry (DENSE).  Both products run on the bfloat16 matrix pipe
-// with every float32 operand split into three parts (demo_device.h), and one table of pre-split basis fragments
-// serves both: block 2 t + h (kSplitFragFloats words), slot j of contraction group g holds
+// Instances for a projection matrix without mirror symmetry (DENSE).  Both products run on the float16 matrix pipe
+// with every float32 operand split into two parts (demo_device.h), and one table of pre-split basis fragments (scaled
+// by 2^kSplitHBasisLog2) serves both: block 2 t + h (kSplitHFragFloats words), slot j of contraction group g holds
 //   P[16 (2 h + j / 4) + 4 g + j % 4][16 t + c]
 // (product a: B operand, contracts v = 16 a + 4 g + b with (a, b) = (2 h + j / 4, j % 4), output columns
 // j = 16 t + c; product b: A operand, contracts u = 16 a + 4 g + b, output rows i = 16 t + c).
-constexpr int D64G_FLOATS = 8 * kSplitFragFloats;
+constexpr int D64G_FLOATS = 8 * kSplitHFragFloats;
 static_assert(D64G_FLOATS == kDec64DenseTableFloats, "table size");
 template <bool DENSE>
 constexpr int d64_table_floats() { return DENSE ? D64G_FLOATS : D64_G_FLOATS; }
@@ -74,8 +74,9 @@ void build_dec64_dense_tables(const double* P, float* out) {
       for (int lane = 0; lane < 64; ++lane) {
         float v[8];
         for (int j = 0; j < 8; ++j)
-          v[j] = (float)P[(16 * (2 * h + (j >> 2)) + 4 * (lane >> 4) + (j & 3)) * 64 + 16 * t + (lane & 15)];
-        host_store_split8(out + (2 * t + h) * kSplitFragFloats, lane, v);
+          v[j] = (float)__builtin_ldexp(P[(16 * (2 * h + (j >> 2)) + 4 * (lane >> 4) + (j & 3)) * 64 + 16 * t + (lane & 15)],
+                                        kSplitHBasisLog2);
+        host_store_split8h(out + (2 * t + h) * kSplitHFragFloats, lane, v);
       }
 }
 
@@ -120,8 +121,8 @@ void build_dec64_tables(const double* P, float* out) {
 // payload loads of modes 3 to 5 are non-temporal (the launch wrapper asks for that when a row of k pairs fills a
 // 128-byte line; shorter rows share lines with neighbouring chunks and stay cached).
 // DENSE: any orthonormal 64 x 64 matrix (table of build_dec64_dense_tables): the tile holds S in its natural order,
-// both products are full (on the bfloat16 matrix pipe, float32 operands split into three parts: 192
-// v_mfma_f32_16x16x32_bf16 each), R goes through the tile in its natural order.
+// both products are full (on the float16 matrix pipe, float32 operands split into two parts: 96
+// v_mfma_f32_16x16x32_f16 each), R goes through the tile in its natural order.
 template <bool PBF16, int MODE, bool IDENT, bool COUNT = false, bool NT = true, bool DENSE = false>
 __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, const float* __restrict__ tables,
                                                                DecodeArgs args) {
@@ -443,53 +444,42 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
           for (int jt = 0; jt < 4; ++jt) Y[uu][jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          Split8 A[2];   // [ut - 2 hp]: S as float32 (the tile holds fixed-point sums), split
+          SplitH8 A[2];   // [ut - 2 hp]: S as float32 below 2^8 (the tile holds fixed-point sums below 2^30), split
 #pragma unroll
           for (int uu = 0; uu < 2; ++uu) {
             const float* arow = &tile[(16 * (2 * hp + uu) + c) * D64_LDT + 4 * g + 32 * h];
             const float4 a0 = *reinterpret_cast<const float4*>(arow);
             const float4 a1 = *reinterpret_cast<const float4*>(arow + 16);
-            A[uu] = split8((float)__float_as_int(a0.x), (float)__float_as_int(a0.y), (float)__float_as_int(a0.z),
-                           (float)__float_as_int(a0.w), (float)__float_as_int(a1.x), (float)__float_as_int(a1.y),
-                           (float)__float_as_int(a1.z), (float)__float_as_int(a1.w));
+            constexpr float sc = 0x1p-22f;
+            A[uu] = split8h((float)__float_as_int(a0.x) * sc, (float)__float_as_int(a0.y) * sc, (float)__float_as_int(a0.z) * sc,
+                            (float)__float_as_int(a0.w) * sc, (float)__float_as_int(a1.x) * sc, (float)__float_as_int(a1.y) * sc,
+                            (float)__float_as_int(a1.z) * sc, (float)__float_as_int(a1.w) * sc);
           }
 #pragma unroll
           for (int jt = 0; jt < 4; ++jt) {
-            const Split8 Bq = load_split8(sG + (2 * jt + h) * kSplitFragFloats, lane);
+            const SplitH8 Bq = load_split8h(sG + (2 * jt + h) * kSplitHFragFloats, lane);
 #pragma unroll
-            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].lo, Bq.hi, Y[uu][jt]);
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_f16(A[uu].lo, Bq.hi, Y[uu][jt]);
 #pragma unroll
-            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].hi, Bq.lo, Y[uu][jt]);
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_f16(A[uu].hi, Bq.lo, Y[uu][jt]);
 #pragma unroll
-            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].mid, Bq.mid, Y[uu][jt]);
-#pragma unroll
-            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].mid, Bq.hi, Y[uu][jt]);
-#pragma unroll
-            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].hi, Bq.mid, Y[uu][jt]);
-#pragma unroll
-            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_bf16(A[uu].hi, Bq.hi, Y[uu][jt]);
+            for (int uu = 0; uu < 2; ++uu) Y[uu][jt] = mfma_f16(A[uu].hi, Bq.hi, Y[uu][jt]);
           }
           __builtin_amdgcn_sched_barrier(0);
         }
-        Split8 Bt[4];
+        SplitH8 Bt[4];
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt)
-          Bt[jt] = split8(Y[0][jt][0], Y[0][jt][1], Y[0][jt][2], Y[0][jt][3], Y[1][jt][0], Y[1][jt][1], Y[1][jt][2], Y[1][jt][3]);
+          Bt[jt] = split8h(Y[0][jt][0], Y[0][jt][1], Y[0][jt][2], Y[0][jt][3], Y[1][jt][0], Y[1][jt][1], Y[1][jt][2], Y[1][jt][3]);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-          const Split8 Ap = load_split8(sG + (2 * it + hp) * kSplitFragFloats, lane);
+          const SplitH8 Ap = load_split8h(sG + (2 * it + hp) * kSplitHFragFloats, lane);
 #pragma unroll
-          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.lo, Bt[jt].hi, R[it][jt]);
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_f16(Ap.lo, Bt[jt].hi, R[it][jt]);
 #pragma unroll
-          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.hi, Bt[jt].lo, R[it][jt]);
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_f16(Ap.hi, Bt[jt].lo, R[it][jt]);
 #pragma unroll
-          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.mid, Bt[jt].mid, R[it][jt]);
-#pragma unroll
-          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.mid, Bt[jt].hi, R[it][jt]);
-#pragma unroll
-          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.hi, Bt[jt].mid, R[it][jt]);
-#pragma unroll
-          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_bf16(Ap.hi, Bt[jt].hi, R[it][jt]);
+          for (int jt = 0; jt < 4; ++jt) R[it][jt] = mfma_f16(Ap.hi, Bt[jt].hi, R[it][jt]);
         }
       }
       DEMO_PHASE(3);
@@ -578,7 +568,8 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 
     // ---- x <- x - lr*(phi(R) + wd*x): phi = sgn (the scale of the fixed point does not matter), or the identity
     //      on the aggregate itself (the sum of the tile is R * 2^sh; `scale` is 1 or 1/W) ------------------------------
-    const float factor = IDENT ? ldexpf(args.scale, -sh_chunk) : 0.f;
+    // (full-product instances: the sums went in as 2^-22 of their integers and both products carry 2^kSplitHBasisLog2)
+    const float factor = IDENT ? ldexpf(args.scale, (DENSE ? 22 - 2 * kSplitHBasisLog2 : 0) - sh_chunk) : 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       f32x4 xin[4];   // fp32 parameters of the four rows of this quadruple

@@ -291,6 +291,88 @@ inline void host_store_split8(float* frag, int lane, const float v[8]) {
 }
 constexpr int kSplitFragFloats = 3 * 64 * 4;   // words of one pre-split fragment block
 
+// ---- float32 products on the float16 matrix pipe (decode kernels) ---------------------------------------------
+// With operands whose magnitude is bounded (the decode's block fixed-point sums, basis entries |P| <= 1) two float16
+// parts do: hi = rne16(x), lo = rne16(x - hi) (the remainder is exact in float32), |x - hi - lo| <= 2^-22 |x| as long
+// as x's lowest bit is not below 2^-24, the spacing of the float16 subnormals, which conversion and matrix pipe both
+// keep (checked on the device).  Three products hi hi + hi lo + lo hi on v_mfma_f32_16x16x32_f16 (16 cycles for 32
+// contraction indices) drop lo lo, 2^-22 of the product: float32 accumulation and a relative error of about 2^-21 per
+// term, far inside what a sign (or the 1e-5 bound of the identity rule) needs, at 3/16 of the float32 instructions'
+// time.  The callers scale so that nothing reaches 65504: basis entries by 2^4 (kSplitHBasisScale), the sums to
+// below 2^8, hence |Y| <= 2^4 sqrt(128) 2^8 < 2^15.6; the result then carries 2^8 times the scale of the sums.
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
+struct SplitH8 {
+  u32x4 hi, lo;
+};
+constexpr int kSplitHBasisLog2 = 4;
+__device__ __forceinline__ void split_pair_h(float x0, float x1, uint32_t& h, uint32_t& l) {
+  const h16x2 hh = __builtin_convertvector((f32x2){x0, x1}, h16x2);
+  const float r0 = x0 - (float)hh[0], r1 = x1 - (float)hh[1];
+  const h16x2 ll = __builtin_convertvector((f32x2){r0, r1}, h16x2);
+  h = __builtin_bit_cast(uint32_t, hh);
+  l = __builtin_bit_cast(uint32_t, ll);
+}
+__device__ __forceinline__ SplitH8 split8h(float x0, float x1, float x2, float x3, float x4, float x5, float x6, float x7) {
+  uint32_t h[4], l[4];
+  split_pair_h(x0, x1, h[0], l[0]);
+  split_pair_h(x2, x3, h[1], l[1]);
+  split_pair_h(x4, x5, h[2], l[2]);
+  split_pair_h(x6, x7, h[3], l[3]);
+  return SplitH8{(u32x4){h[0], h[1], h[2], h[3]}, (u32x4){l[0], l[1], l[2], l[3]}};
+}
+__device__ __forceinline__ f32x4 mfma_f16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h16x8, a), __builtin_bit_cast(h16x8, b), c, 0, 0, 0);
+}
+// c += a b from the split operands (smallest terms first)
+__device__ __forceinline__ f32x4 mfma_split_h(const SplitH8& a, const SplitH8& b, f32x4 c) {
+  c = mfma_f16(a.lo, b.hi, c);
+  c = mfma_f16(a.hi, b.lo, c);
+  return mfma_f16(a.hi, b.hi, c);
+}
+// pre-split fragment table: [part (hi, lo)][64 lanes] 16-byte entries
+__device__ __forceinline__ SplitH8 load_split8h(const float* frag, int lane) {
+  SplitH8 s;
+  s.hi = *reinterpret_cast<const u32x4*>(frag + (0 * 64 + lane) * 4);
+  s.lo = *reinterpret_cast<const u32x4*>(frag + (1 * 64 + lane) * 4);
+  return s;
+}
+// Host: float16 code of a float32 (|f| < 65520), round to nearest even, subnormals kept.
+inline uint16_t host_f16_rne(float f) {
+  uint32_t b;
+  __builtin_memcpy(&b, &f, 4);
+  const uint16_t sign = (uint16_t)((b >> 16) & 0x8000u);
+  const uint32_t a = b & 0x7fffffffu;
+  if (a < 0x33000001u) return sign;                      // |f| <= 2^-25: rounds to zero
+  if (a < 0x38800000u) {                                 // below 2^-14: subnormal, units of 2^-24
+    const uint32_t man = (a & 0x7fffffu) | 0x800000u;    // 24-bit significand, value man * 2^(e - 150)
+    const int shift = 126 - (int)(a >> 23);              // man >> shift counts units of 2^-24 (shift 14 .. 24)
+    const uint32_t q = man >> shift, rem = man & ((1u << shift) - 1u), half = 1u << (shift - 1);
+    return (uint16_t)(sign | (q + ((rem > half || (rem == half && (q & 1u))) ? 1u : 0u)));
+  }
+  const uint32_t r = a + 0xfffu + ((a >> 13) & 1u);      // round the 13 dropped bits, ties to even
+  return (uint16_t)(sign | ((r - 0x38000000u) >> 13));
+}
+inline float host_f16_widen(uint16_t h) {
+  const uint32_t e = (h >> 10) & 0x1fu, m = h & 0x3ffu;
+  float mag = e == 0 ? (float)m * 0x1p-24f : __builtin_ldexpf((float)(m | 0x400u), (int)e - 25);
+  return (h & 0x8000u) ? -mag : mag;
+}
+// Host: writes the pre-split fragment of one lane, eight values (already scaled), into a [part][64 lanes][4 words] block.
+inline void host_store_split8h(float* frag, int lane, const float v[8]) {
+  uint32_t* w = reinterpret_cast<uint32_t*>(frag);
+  for (int j = 0; j < 8; ++j) {
+    uint16_t p[2];
+    p[0] = host_f16_rne(v[j]);
+    p[1] = host_f16_rne(v[j] - host_f16_widen(p[0]));
+    for (int part = 0; part < 2; ++part) {
+      uint32_t& word = w[(part * 64 + lane) * 4 + (j >> 1)];
+      word = (j & 1) ? (word & 0x0000ffffu) | ((uint32_t)p[part] << 16) : (word & 0xffff0000u) | p[part];
+    }
+  }
+}
+constexpr int kSplitHFragFloats = 2 * 64 * 4;   // words of one pre-split float16 fragment block
+
 // LDS operations of one wavefront execute in order; this only stops the compiler from moving
 // LDS accesses across the point.
 __device__ __forceinline__ void wave_lds_sync() {

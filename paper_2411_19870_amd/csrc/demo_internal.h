@@ -79,6 +79,7 @@ struct BasisTables {
   bool dct;              // `basis` is the orthonormal DCT-II (false: a matrix set by the caller)
   const float* enc64g = nullptr;   // s = 64, matrix set by the caller: tables of the full-product wavefront kernels
   const float* dec64g = nullptr;
+  const float* dec128 = nullptr;   // tables of the s = 128 decode kernel (DCT only, else null)
 };
 
 // Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:
@@ -141,20 +142,22 @@ void build_dec32_tables(const double* P32, float* out /* kDec32TableFloats */);
 hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   int num_cus, hipStream_t stream);
 
-// s = 128 kernels, one 1024-thread workgroup per chunk (demo_wg128.hip); they need the DCT (mirror-folded products)
-// and read the plain 128 x 128 basis.
+// s = 128 kernels, one workgroup per chunk (demo_wg128.hip); they need the DCT (mirror-folded products).  The encode
+// kernel reads the plain 128 x 128 basis, the decode kernel its own tables.
 constexpr int kFast128MaxK = 64;
 hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const EncodeArgs& a, const Worklist& wl,
                                  bool grad_bf16, int num_cus, hipStream_t stream);
-// decode keeps the W*k pairs of a chunk in four registers per lane of its 1024 threads
+// decode keeps the W*k pairs of a chunk in eight registers per lane of its 512 threads
 constexpr int kFast128MaxPairs = 4096;
+constexpr int kDec128TableFloats = 2 * 8 * 512;   // pre-split float16 fragment blocks of the even and the odd rows of P
+void build_dec128_tables(const double* P128, float* out /* kDec128TableFloats */);
 // ... and streams larger payloads (k a multiple of 4, 16-byte aligned arrays, at most 65536 pairs per chunk)
 inline bool fast128_decode_supports(int W, int k, bool payload_aligned16) {
   if (W < 1 || k < 1) return false;
   if ((int64_t)W * k <= kFast128MaxPairs) return true;
   return payload_aligned16 && k % 4 == 0 && (int64_t)W * k <= 65536;
 }
-hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
+hipError_t launch_decode2d_wg128(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                  int num_cus, hipStream_t stream);
 
 // ... and streams larger payloads (k a multiple of 4, 16-byte aligned arrays, at most 65536 pairs per chunk).
@@ -166,7 +169,7 @@ inline bool fast64_decode_supports(int W, int k, bool payload_aligned16) {
 hipError_t launch_decode2d_wave64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
                                   bool payload_aligned16, int num_cus, hipStream_t stream);
 // ... and its instances for a projection matrix without mirror symmetry
-constexpr int kDec64DenseTableFloats = 8 * 768;   // 8 pre-split fragment blocks
+constexpr int kDec64DenseTableFloats = 8 * 512;   // 8 pre-split float16 fragment blocks
 void build_dec64_dense_tables(const double* P, float* out /* kDec64DenseTableFloats */);
 bool dense64_decode_supports(const DecodeArgs& a);
 hipError_t launch_decode2d_dense64(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,

@@ -1198,8 +1198,9 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
       (pmix == 1u || pmix == 2u))
     return launch_decode2d_dense64(tv, bt.dec64g, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
   if (variant >= 1 && s == 128 && a.mirror != 0 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast128MaxPairs) &&
-      fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 && (pmix == 1u || pmix == 2u))
-    return launch_decode2d_wg128(tv, bt.basis, a, pmix == 1u, num_cus, stream);
+      fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 && bt.dec128 != nullptr &&
+      (pmix == 1u || pmix == 2u))
+    return launch_decode2d_wg128(tv, bt.dec128, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {
     case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);

@@ -489,98 +489,130 @@ hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const 
 // ---------------------------------------------------------------------------
 // decode:  S = sum over workers of the payloads ;  R = P^T S P ;  x <- x - lr (sgn(R) + wd x)     (Algorithm 1, update)
 // ---------------------------------------------------------------------------
-// Sign descent on the plain sum only (the other operating points run on the generic kernel).  The W k <= 4096
-// pairs of a chunk sit in at most four registers per lane (pair 1024 j + tid belongs to worker p / k, position
-// p % k) and are fetched for the next chunk while the products of this one run.  S is accumulated in block
-// fixed point with integer LDS atomics (one scale per chunk: the sum is exact and independent of the order of
-// arrival).  Two mirror folds: rows u = 0 mod 4 of P are even under i -> 63-i and i -> 127-i, rows u = 2 mod 4
-// odd / even, odd rows odd under i -> 127-i.  For the quadruple {i, 63-i, 64+i, 127-i}, i < 32, four partial sums
-//   E0 = sum over u = 0 mod 4,  E2 = sum over u = 2 mod 4  (32 frequencies each),
-//   Oa = sum over odd u of P[u][i] ..,  Ob = sum over odd u of P[u][63-i] ..  (64 frequencies each)
-// give out[i] = E0+E2+Oa, out[127-i] = E0+E2-Oa, out[63-i] = E0-E2+Ob, out[64+i] = E0-E2-Ob: 768 MFMAs per
-// product instead of 2048.  S is held with rows and columns in class-major order pos3(); basis in LDS:
-// PT[i][pos3(u)] = P[u][i], i < 64, so that both products read it along the contraction index.
+// One 512-thread workgroup (8 wavefronts) per chunk.  Row u of the 128-point DCT-II is even (u even) or odd (u odd)
+// under i -> 127 - i, so with A[u'][i] = P[2u'][i], O[u'][i] = P[2u'+1][i] (i < 64) and the coefficients sorted by the
+// parities (a, b) of (u, v) into four 64 x 64 quadrants S_ab[u'][v'] = S[2u'+a][2v'+b], the four two-sided products
+//   R_ab = M_a^T S_ab M_b,   M_0 = A, M_1 = O      (64 x 64 x 64 each)
+// give, for i, j < 64,
+//   R[i][j] = R_00 + R_01 + R_10 + R_11,  R[i][127-j] = R_00 - R_01 + R_10 - R_11,
+//   R[127-i][j] = R_00 + R_01 - R_10 - R_11,  R[127-i][127-j] = R_00 - R_01 - R_10 + R_11:
+// a quarter of the multiplications of the full products.  The quadrant products run on the float16 matrix pipe with
+// both operands split into two parts (demo_device.h; 3 instructions of 16 cycles per 32 contraction indices where the
+// float32 instruction needs 8 of 32 cycles), two wavefronts per quadrant, each with half of the output columns: columns
+// are independent through both products, the accumulators of the first are, as they lie, operands of the second
+// (as in the full-product instance of demo_dec64.hip), and nothing but S and the four R_ab passes through LDS.
+// The W k <= 4096 pairs of a chunk sit in at most eight registers per lane (pair 512 j + tid belongs to worker p / k,
+// position p % k) and are fetched for the next chunk while the products of this one run.  S is accumulated in block
+// fixed point with integer LDS atomics (one scale per chunk: the sum is exact and independent of the order of arrival).
+// Thread t owns, for p < 2, row i = (t + 512 p) / 16 and columns j0 = 4 ((t + 512 p) % 16) .. j0 + 3 of the quadrants,
+// i.e. the parameters (i, j0..), (i, 124 - j0..), (127 - i, j0..), (127 - i, 124 - j0..): sixteen lanes cover a whole
+// 128-element row segment of the chunk with either pair of accesses.
 namespace {
-constexpr int W128_DEC_SLOTS = 4;
-constexpr int W128_PT_FLOATS = 64 * W128_LDX;
-constexpr int W128_DEC_LDS_BYTES = 4 * (W128_PT_FLOATS + W128_X_FLOATS + 32);
-static_assert(kFast128MaxPairs == W128_DEC_SLOTS * W128_THREADS, "pairs per chunk held in registers");
+constexpr int Q128_WAVES = 8;
+constexpr int Q128_THREADS = 64 * Q128_WAVES;
+constexpr int Q128_LDT = 68;                                    // quadrant row stride (floats); columns 64..67 are pad slots
+constexpr int Q128_TILE_FLOATS = 64 * Q128_LDT;
+constexpr int Q128_TILES_FLOATS = 4 * Q128_TILE_FLOATS;
+constexpr int Q128_FRAGS = 8 * kSplitHFragFloats;               // fragment table of one 64 x 64 matrix
+constexpr int Q128_TABLE_FLOATS = 2 * Q128_FRAGS;               // A, then O
+constexpr int Q128_SLOTS = 8;
+constexpr int Q128_LDS_BYTES = 4 * (Q128_TABLE_FLOATS + Q128_TILES_FLOATS + 32);
+static_assert(kFast128MaxPairs == Q128_SLOTS * Q128_THREADS, "pairs per chunk held in registers");
+static_assert(Q128_TABLE_FLOATS == kDec128TableFloats, "table size");
+static_assert(Q128_LDS_BYTES <= 160 * 1024, "LDS budget");
 }  // namespace
 
-// STREAM false: W k <= 4096, one pair per load (consecutive threads read consecutive pairs, and the pairs are spread
-// evenly over the sixteen wavefronts; 16-byte loads would leave half of them without work at W k = 2048 and measured
-// slower).  STREAM true: more than 4096 pairs per chunk (up to 65536), k a multiple of four and 16-byte aligned payload
-// arrays: one pass in rounds of 4096 pairs, a thread fetching four consecutive pairs of one worker per load; the sums
-// are shifted down whenever a round raises the block exponent.
+// Host: pre-split float16 fragment tables of A and O (scaled by 2^kSplitHBasisLog2) from the 128 x 128 DCT matrix P
+// (double, row-major).  Per matrix M the layout of the full-product s = 64 decode kernel: block 2 t + h, slot j of
+// contraction group g holds M[16 (2 h + j / 4) + 4 g + j % 4][16 t + c].
+void build_dec128_tables(const double* P, float* out) {
+  for (int m = 0; m < 2; ++m)
+    for (int t = 0; t < 4; ++t)
+      for (int h = 0; h < 2; ++h)
+        for (int lane = 0; lane < 64; ++lane) {
+          float v[8];
+          for (int j = 0; j < 8; ++j) {
+            const int row = 16 * (2 * h + (j >> 2)) + 4 * (lane >> 4) + (j & 3);
+            v[j] = (float)__builtin_ldexp(P[(2 * row + m) * 128 + 16 * t + (lane & 15)], kSplitHBasisLog2);
+          }
+          host_store_split8h(out + m * Q128_FRAGS + (2 * t + h) * kSplitHFragFloats, lane, v);
+        }
+}
+
+// STREAM false: W k <= 4096, one pair per load (consecutive threads read consecutive pairs).  STREAM true: more than
+// 4096 pairs per chunk (up to 65536), k a multiple of four and 16-byte aligned payload arrays: one pass in rounds of
+// 4096 pairs, a thread fetching four consecutive pairs of one worker per load; the sums are shifted down whenever a
+// round raises the block exponent.
 // IDENT: phi is the identity on the aggregate instead of sgn (its own instance).  COUNT: the count-normalised
 // aggregate of the appendix algorithm "Sparse Top-k Averaging" (every coefficient's sum divided by the number of pairs
 // that name it), without STREAM only.
 template <bool PBF16, bool STREAM, bool IDENT, bool COUNT = false>
-__global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, const float* __restrict__ basis,
-                                                                DecodeArgs args) {
+__global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, const float* __restrict__ tables,
+                                                                  DecodeArgs args) {
   constexpr bool VEC4 = STREAM;
   extern __shared__ float lds[];
-  float* sPT = lds;
-  float* tile = sPT + W128_PT_FLOATS;
-  int* itile = reinterpret_cast<int*>(tile);
-  uint32_t* wmax = reinterpret_cast<uint32_t*>(tile + W128_X_FLOATS);   // [2][16] per-wavefront largest |val| (two buffers: consecutive rounds of a streamed payload alternate)
+  const float* sT = lds;
+  float* tiles = lds + Q128_TABLE_FLOATS;
+  int* itiles = reinterpret_cast<int*>(tiles);
+  uint32_t* wmax = reinterpret_cast<uint32_t*>(tiles + Q128_TILES_FLOATS);   // [2][16] per-wavefront largest |val| (two buffers: consecutive rounds of a streamed payload alternate)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l16 = lane & 15, lq = lane >> 4;
+  const int g = lane >> 4, c = lane & 15;
   const int k = args.k, W = args.W;
   const int npairs = W * k;
   const int nunits = npairs >> 2;                                  // VEC4: 16-byte units per chunk
-  const int nslots = VEC4 ? W128_DEC_SLOTS : (npairs + W128_THREADS - 1) / W128_THREADS;   // payload registers in use (uniform)
-  const int nrounds = STREAM ? (nunits + W128_THREADS - 1) / W128_THREADS : 1;
+  const int nslots = VEC4 ? Q128_SLOTS : (npairs + Q128_THREADS - 1) / Q128_THREADS;   // payload registers in use (uniform)
+  const int nrounds = STREAM ? (nunits + 2 * Q128_THREADS - 1) / (2 * Q128_THREADS) : 1;
   const int total = tv.total_chunks;
   int chunk = blockIdx.x;
   if (chunk >= total) return;
 
-  // PT[i][pos3(u)] = P[u][i]: thread reads P[u][4c..4c+3] and writes four rows of the transposed tile
-  for (int e = tid; e < 128 * 16; e += W128_THREADS) {
-    const int u = e >> 4, c4 = (e & 15) * 4;
-    const f32x4 v = gload_f4(basis + u * 128 + c4);
-#pragma unroll
-    for (int x = 0; x < 4; ++x) sPT[(c4 + x) * W128_LDX + pos3((uint32_t)u)] = v[x];
-  }
+  for (int e = tid; e < Q128_TABLE_FLOATS / 4; e += Q128_THREADS)
+    reinterpret_cast<f32x4*>(lds)[e] = gload_f4(tables + 4 * e);
 
-  int32_t pi[W128_DEC_SLOTS];
-  float pv[W128_DEC_SLOTS];
+  int32_t pi[Q128_SLOTS];
+  float pv[Q128_SLOTS];
 #pragma unroll
-  for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+  for (int j = 0; j < Q128_SLOTS; ++j) {
     pi[j] = -1;
     pv[j] = 0.f;
   }
   const float rk = 1.0f / (float)k;
-  // `round` matters in STREAM mode only: units 1024 round + tid
+  // `round` matters in STREAM mode only: units 1024 round + 512 jj + tid
   auto load_payload = [&](const TensorDev& dd, int cc, int round = 0) {
     const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)cc * k;
     const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)cc * k;
     const int wstride = dd.nchunks * k;                        // pairs of one worker for this tensor
     if constexpr (VEC4) {
-      static_assert(W128_DEC_SLOTS == 4, "one 16-byte load per array fills the payload registers");
-      const int unit = (STREAM ? W128_THREADS * round : 0) + tid;
-      const int p = 4 * unit;
-      const int w = (int)(((float)p + 0.5f) * rk);             // as below (p < 65536)
-      const int pos = p - w * k;
-      const bool ok = unit < nunits;
-      const uint32_t off = ok ? (uint32_t)(w * wstride + pos) : 0u;
-      const f32x4 vv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off));
+      static_assert(Q128_SLOTS == 8, "two 16-byte loads per array fill the payload registers");
+      uint32_t off[2];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pv[e] = vv[e];
-      const u32x4 iv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off));
+      for (int jj = 0; jj < 2; ++jj) {
+        const int unit = (STREAM ? 2 * Q128_THREADS * round : 0) + Q128_THREADS * jj + tid;
+        const int p = 4 * unit;
+        const int w = (int)(((float)p + 0.5f) * rk);           // as below (p < 65536)
+        const int pos = p - w * k;
+        off[jj] = unit < nunits ? (uint32_t)(w * wstride + pos) : 0u;
+      }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) pi[e] = (int32_t)iv[e];
+      for (int jj = 0; jj < 2; ++jj) {
+        const f32x4 vv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off[jj]));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pv[4 * jj + e] = vv[e];
+        const u32x4 iv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off[jj]));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pi[4 * jj + e] = (int32_t)iv[e];
+      }
       return;
     }
     // every offset before the first load, and the loads unconditional (a slot past the end reads the chunk's first
-    // pair; mask_payload discards it where the pairs are consumed): address arithmetic between the loads picked up a
-    // register of a load in flight as the unused high half of a 64-bit operand, and the wave then waited out that
-    // load before it issued the next (two memory round trips per chunk)
-    uint32_t off[W128_DEC_SLOTS];
+    // pair; mask_payload discards it where the pairs are consumed): address arithmetic between the loads can pick up
+    // a register of a load in flight as the unused high half of a 64-bit operand, and the wave then waits out that
+    // load before it issues the next
+    uint32_t off[Q128_SLOTS];
 #pragma unroll
-    for (int j = 0; j < W128_DEC_SLOTS; ++j) {
-      const int p = W128_THREADS * j + tid;
+    for (int j = 0; j < Q128_SLOTS; ++j) {
+      const int p = Q128_THREADS * j + tid;
       // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
       // the rounding error of the float product for p < 4096
       const int w = (int)(((float)p + 0.5f) * rk);
@@ -588,7 +620,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       off[j] = p < npairs ? (uint32_t)w * (uint32_t)wstride + (uint32_t)pos : 0u;
     }
 #pragma unroll
-    for (int j = 0; j < W128_DEC_SLOTS; ++j) {
+    for (int j = 0; j < Q128_SLOTS; ++j) {
       if (j < nslots) {                                        // uniform
         pi[j] = payload_load<true>(ip + off[j]);
         pv[j] = payload_load<true>(vp + off[j]);
@@ -599,11 +631,19 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   // they are requested: a select behind the load would make the prefetch wait for its own data.
   auto mask_payload = [&](int round = 0) {
 #pragma unroll
-    for (int j = 0; j < W128_DEC_SLOTS; ++j) {
-      const bool ok = VEC4 ? (STREAM ? W128_THREADS * round : 0) + tid < nunits : W128_THREADS * j + tid < npairs;
+    for (int j = 0; j < Q128_SLOTS; ++j) {
+      const bool ok = VEC4 ? (STREAM ? 2 * Q128_THREADS * round : 0) + Q128_THREADS * (j >> 2) + tid < nunits
+                           : Q128_THREADS * j + tid < npairs;
       pi[j] = ok ? pi[j] : -1;
       pv[j] = ok ? pv[j] : 0.f;
     }
+  };
+  // coefficient (u, v) lives in quadrant 2 (u % 2) + v % 2 at (u / 2, v / 2); lanes with nothing to add use a pad slot
+  const uint32_t dummy = (uint32_t)((tid & 63) * Q128_LDT + 64 + ((tid >> 6) & 3));
+  auto slot_of = [&](int j) {
+    const uint32_t fi = (uint32_t)pi[j];
+    const uint32_t a = (((fi >> 6) & 2u) | (fi & 1u)) * (uint32_t)Q128_TILE_FLOATS + (fi >> 8) * (uint32_t)Q128_LDT + ((fi & 127u) >> 1);
+    return fi < 16384u ? a : dummy;
   };
 
   int t = find_tensor_uniform(tv, chunk);
@@ -614,12 +654,15 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
   // the parameter stores pending on its back edge, the loop's first wait would be for everything outstanding,
   // i.e. every chunk would begin by waiting for the acknowledgements of the previous chunk's stores
 #pragma unroll
-  for (int j = 0; j < W128_DEC_SLOTS; ++j) asm volatile("" : "+v"(pi[j]), "+v"(pv[j]));
+  for (int j = 0; j < Q128_SLOTS; ++j) asm volatile("" : "+v"(pi[j]), "+v"(pv[j]));
 
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                     // 30 - ceil(log2 W)
-  const int lrow = tid >> 5, lcol = (tid & 31) * 4;
-  const uint32_t dummy = (uint32_t)((tid & 127) * W128_LDX + 128 + ((tid >> 7) & 3));   // pad slot of this thread
+  // products: quadrant of this wavefront, its half of the columns, the two fragment tables
+  const int quad = wave >> 1, jh = wave & 1;
+  const float* tq = tiles + quad * Q128_TILE_FLOATS;
+  const float* TB = sT + (quad & 1) * Q128_FRAGS;              // first product: M_b, the column class
+  const float* TA = sT + (quad >> 1) * Q128_FRAGS;             // second product: M_a, the row class
 
   for (;;) {
     mask_payload(0);
@@ -628,34 +671,29 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     const int64_t origin = (int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128;
     const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
                                               : make_rsrc(static_cast<const float*>(d.param) + origin);
-    const uint32_t vo = (uint32_t)lrow * ucols + (uint32_t)lcol;
 
     if constexpr (COUNT) {
       static_assert(!COUNT || !STREAM, "the count pass needs the whole payload in registers");
       // every pair adds one to its coefficient's slot, reads the total back and is divided by it (sum of val/n over
-      // the n pairs of a slot = (sum of val) / n); the tile is zeroed again below before the sums go in
-      auto slot_of = [&](int j) {
-        const uint32_t fi = (uint32_t)pi[j];
-        return fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
-      };
-      for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS)
-        *reinterpret_cast<f32x4*>(&tile[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
+      // the n pairs of a slot = (sum of val) / n); the tiles are zeroed again below before the sums go in
+      for (int e = tid; e < Q128_TILES_FLOATS / 4; e += Q128_THREADS)
+        *reinterpret_cast<f32x4*>(&tiles[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
       wg_lds_barrier();
 #pragma unroll
-      for (int j = 0; j < W128_DEC_SLOTS; ++j)
-        if (j < nslots) atomicAdd(&itile[slot_of(j)], 1);
+      for (int j = 0; j < Q128_SLOTS; ++j)
+        if (j < nslots) atomicAdd(&itiles[slot_of(j)], 1);
       wg_lds_barrier();
 #pragma unroll
-      for (int j = 0; j < W128_DEC_SLOTS; ++j)
-        if (j < nslots) pv[j] = pv[j] / (float)itile[slot_of(j)];
+      for (int j = 0; j < Q128_SLOTS; ++j)
+        if (j < nslots) pv[j] = pv[j] / (float)itiles[slot_of(j)];
       wg_lds_barrier();
     }
-    // ---- largest |val| of the payload registers, zero tile ----------------------------------------------------
+    // ---- largest |val| of the payload registers, zero tiles ---------------------------------------------------
     // per-wavefront largest magnitude (as bits) of the payload registers into wmax buffer `buf`
     auto post_wave_max = [&](int buf) {
       float mx = 0.f;
 #pragma unroll
-      for (int j = 0; j < W128_DEC_SLOTS; ++j)
+      for (int j = 0; j < Q128_SLOTS; ++j)
         if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
       uint32_t mb = __float_as_uint(mx);
       mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
@@ -666,9 +704,9 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
       if (lane == 0) wmax[16 * buf + wave] = max(m01, m23);
     };
-    // shift of the block fixed point from the sixteen posted maxima (after a barrier)
+    // shift of the block fixed point from the eight posted maxima (after a barrier)
     auto shift_from = [&](int buf) {
-      uint32_t mall = wmax[16 * buf + (lane & 15)];
+      uint32_t mall = wmax[16 * buf + (lane & 7)];
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0xB1, 0xf, 0xf, false));
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x4E, 0xf, 0xf, false));
       mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x141, 0xf, 0xf, false));
@@ -679,17 +717,12 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     };
     auto add_pairs = [&](int sh) {
 #pragma unroll
-      for (int j = 0; j < W128_DEC_SLOTS; ++j) {
-        if (j < nslots) {
-          const uint32_t fi = (uint32_t)pi[j];
-          const uint32_t a = fi < 16384u ? (uint32_t)(pos3(fi >> 7) * W128_LDX + pos3(fi & 127u)) : dummy;
-          atomicAdd(&itile[a], __float2int_rn(ldexpf(pv[j], sh)));
-        }
-      }
+      for (int j = 0; j < Q128_SLOTS; ++j)
+        if (j < nslots) atomicAdd(&itiles[slot_of(j)], __float2int_rn(ldexpf(pv[j], sh)));
     };
     post_wave_max(0);
-    for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS)
-      *reinterpret_cast<f32x4*>(&tile[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int e = tid; e < Q128_TILES_FLOATS / 4; e += Q128_THREADS)
+      *reinterpret_cast<f32x4*>(&tiles[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
     wg_lds_barrier();
 
     // ---- S[idx] += val in fixed point ------------------------------------------------------------------------
@@ -697,7 +730,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
     add_pairs(sh_chunk);
     if constexpr (STREAM) {
       // one pass over the payload: the registers held round 0; every further round is added with the block
-      // exponent of the largest magnitude seen so far, and when a round raises that exponent the sums in the tile
+      // exponent of the largest magnitude seen so far, and when a round raises that exponent the sums in the tiles
       // are first shifted down to the new scale (round to nearest, ties to even; every later shift at least halves the error of
       // an earlier one, so the shifts together cost at most one unit of the final scale per coefficient)
       for (int r = 1; r < nrounds; ++r) {
@@ -709,13 +742,13 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
         if (sh_r < sh_chunk) {   // uniform over the workgroup
           const int dsh = min(sh_chunk - sh_r, 31);
           const int half = (1 << (dsh - 1)) - 1;   // + the kept part's lowest bit: ties go to even (a bias would add up over the slots)
-          for (int e = tid; e < W128_X_FLOATS / 4; e += W128_THREADS) {
-            int4 v = *reinterpret_cast<int4*>(&itile[4 * e]);
+          for (int e = tid; e < Q128_TILES_FLOATS / 4; e += Q128_THREADS) {
+            int4 v = *reinterpret_cast<int4*>(&itiles[4 * e]);
             v.x = (v.x + half + ((v.x >> dsh) & 1)) >> dsh;
             v.y = (v.y + half + ((v.y >> dsh) & 1)) >> dsh;
             v.z = (v.z + half + ((v.z >> dsh) & 1)) >> dsh;
             v.w = (v.w + half + ((v.w >> dsh) & 1)) >> dsh;
-            *reinterpret_cast<int4*>(&itile[4 * e]) = v;
+            *reinterpret_cast<int4*>(&itiles[4 * e]) = v;
           }
           wg_lds_barrier();
           sh_chunk = sh_r;
@@ -723,7 +756,7 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
         add_pairs(sh_chunk);
       }
     }
-    // ---- payload of the next chunk, in flight during the products ----------------------------------------------
+    // ---- payload of the next chunk and the parameters of this one, in flight during the products ---------------
     const int nxt = chunk + (int)gridDim.x;
     if (nxt < total) {
       while (nxt >= t_next) {
@@ -734,137 +767,135 @@ __global__ __launch_bounds__(W128_THREADS) void decode2d_wg128(TableView tv, con
       }
       load_payload(d, nxt - t_first, 0);
     }
-    wg_lds_barrier();
-
-    // ---- product a: Y[i][v] = sum_u P[u][i] S[u][v]; the wavefront owns column tile nt = wave % 8 and the
-    //      quadruple bases i = 16 h + m, h = wave / 8; accumulators E0, E2, Oa, Ob ---------------------------------
-    f32x4 acc[4];
-    {
-      const int nt = wave & 7, h = wave >> 3;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const float* pa = sPT + (16 * h + l16) * W128_LDX + 4 * lq;           // P[u][i]
-      const float* pm = sPT + (63 - 16 * h - l16) * W128_LDX + 4 * lq;      // P[u][63 - i]
-      const int* sb = itile + 4 * lq * W128_LDX + 16 * nt + l16;
-#pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {   // kg = 0, 1: u = 0 mod 4;  kg = 2, 3: u = 2 mod 4
-        float b[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) b[s] = (float)sb[(16 * kg + s) * W128_LDX];
-        const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 16 * kg);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) acc[kg >> 1] = mfma4(a[s], b[s], acc[kg >> 1]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {   // odd u
-        float b[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) b[s] = (float)sb[(64 + 16 * kg + s) * W128_LDX];
-        const f32x4 a = *reinterpret_cast<const f32x4*>(pa + 64 + 16 * kg);
-        const f32x4 am = *reinterpret_cast<const f32x4*>(pm + 64 + 16 * kg);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          acc[2] = mfma4(a[s], b[s], acc[2]);
-          acc[3] = mfma4(am[s], b[s], acc[3]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      wg_lds_barrier();   // every read of S is done: Y replaces it (rows in natural order, columns as they were)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int i = 16 * h + 4 * lq + r;
-        const float ep = acc[0][r] + acc[1][r], em = acc[0][r] - acc[1][r];
-        float* col = tile + 16 * nt + l16;
-        col[i * W128_LDX] = ep + acc[2][r];
-        col[(127 - i) * W128_LDX] = ep - acc[2][r];
-        col[(63 - i) * W128_LDX] = em + acc[3][r];
-        col[(64 + i) * W128_LDX] = em - acc[3][r];
-      }
-    }
-    wg_lds_barrier();
-
-    // ---- the parameters of this chunk: requested now, used after product b -----------------------------------
     using XT = typename std::conditional<PBF16, u32x2, f32x4>::type;
-    XT xin[4];
+    constexpr uint32_t XB = PBF16 ? 2u : 4u;                   // bytes per parameter
+    XT xin[2][4];
+    uint32_t xo[2][4];                                         // byte offsets of the four segments of position block p
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      if constexpr (PBF16) xin[p] = bload_u2(xres, vo * 2, 32u * p * ucols * 2);
-      else xin[p] = bload_f4(xres, vo * 4, 32u * p * ucols * 4);
-    }
-
-    // ---- product b: R[i][j] = sum_v Y[i][v] P[v][j]; the wavefront owns row tile it = wave / 2 and the quadruple
-    //      bases j = 16 h + n, h = wave % 2; accumulators E0, E2, Oa, Ob ----------------------------------------------
-    {
-      const int it = wave >> 1, h = wave & 1;
+    for (int p = 0; p < 2; ++p) {
+      const uint32_t pb = (uint32_t)tid + Q128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
+      xo[p][0] = (ir * ucols + j0) * XB;
+      xo[p][1] = (ir * ucols + 124u - j0) * XB;
+      xo[p][2] = ((127u - ir) * ucols + j0) * XB;
+      xo[p][3] = ((127u - ir) * ucols + 124u - j0) * XB;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const float* ya = tile + (16 * it + l16) * W128_LDX + 4 * lq;
-      const float* pb = sPT + (16 * h + l16) * W128_LDX + 4 * lq;            // P[v][j]
-      const float* pm = sPT + (63 - 16 * h - l16) * W128_LDX + 4 * lq;       // P[v][63 - j]
-#pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {   // kg = 0, 1: v = 0 mod 4;  kg = 2, 3: v = 2 mod 4
-        const f32x4 a = *reinterpret_cast<const f32x4*>(ya + 16 * kg);
-        const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 16 * kg);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) acc[kg >> 1] = mfma4(a[s], b[s], acc[kg >> 1]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int kg = 0; kg < 4; ++kg) {   // odd v
-        const f32x4 a = *reinterpret_cast<const f32x4*>(ya + 64 + 16 * kg);
-        const f32x4 b = *reinterpret_cast<const f32x4*>(pb + 64 + 16 * kg);
-        const f32x4 bm = *reinterpret_cast<const f32x4*>(pm + 64 + 16 * kg);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          acc[2] = mfma4(a[s], b[s], acc[2]);
-          acc[3] = mfma4(a[s], bm[s], acc[3]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      wg_lds_barrier();   // every read of Y is done: R replaces it
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int j = 16 * h + l16;
-        float* row = tile + (16 * it + 4 * lq + r) * W128_LDX;
-        const float ep = acc[0][r] + acc[1][r], em = acc[0][r] - acc[1][r];
-        row[j] = ep + acc[2][r];
-        row[127 - j] = ep - acc[2][r];
-        row[63 - j] = em + acc[3][r];
-        row[64 + j] = em - acc[3][r];
+      for (int sg = 0; sg < 4; ++sg) {
+        if constexpr (PBF16) xin[p][sg] = bload_u2(xres, xo[p][sg], 0u);
+        else xin[p][sg] = bload_f4(xres, xo[p][sg], 0u);
       }
     }
     wg_lds_barrier();
 
-    // ---- x <- x - lr (phi(R) + wd x): phi = sgn, or the identity on the aggregate (the tile holds R * 2^sh; `scale`
-    //      is 1 or 1/W) -----------------------------------------------------------------------------------------------
-    const float factor = IDENT ? ldexpf(args.scale, -sh_chunk) : 0.f;
+    // ---- the two products of this wavefront's quadrant, columns 32 jh .. 32 jh + 31 ------------------------------
+    // first: Y[u][j] = sum_v S_ab[u][v] M_b[v][j], A = S from the tile (row 16 ut + c; the eight v of a slot group
+    // are two 16-byte reads), B = fragments.  The accumulators of two row tiles are, as they lie, the eight
+    // contraction slots of the second, R_ab[i][j] += sum_u M_a[u][i] Y[u][j], A = fragments.
+    f32x4 R[4][2];   // [it][jt - 2 jh]
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const f32x4 rv = *reinterpret_cast<const f32x4*>(&tile[(lrow + 32 * p) * W128_LDX + lcol]);
-      float o[4];
+    for (int it = 0; it < 4; ++it)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float x;
-        if constexpr (PBF16) {
-          const uint32_t raw = xin[p][e >> 1];
-          x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
-        } else {
-          x = xin[p][e];
+      for (int jj = 0; jj < 2; ++jj) R[it][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int hp = 0; hp < 2; ++hp) {
+      f32x4 Y[2][2];   // [ut - 2 hp][jt - 2 jh]
+#pragma unroll
+      for (int uu = 0; uu < 2; ++uu)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) Y[uu][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        SplitH8 A[2];   // the sums as float32 below 2^8 (integers below 2^30 in the tile), split
+#pragma unroll
+        for (int uu = 0; uu < 2; ++uu) {
+          const float* arow = &tq[(16 * (2 * hp + uu) + c) * Q128_LDT + 4 * g + 32 * h];
+          const float4 a0 = *reinterpret_cast<const float4*>(arow);
+          const float4 a1 = *reinterpret_cast<const float4*>(arow + 16);
+          constexpr float sc = 0x1p-22f;
+          A[uu] = split8h((float)__float_as_int(a0.x) * sc, (float)__float_as_int(a0.y) * sc, (float)__float_as_int(a0.z) * sc,
+                          (float)__float_as_int(a0.w) * sc, (float)__float_as_int(a1.x) * sc, (float)__float_as_int(a1.y) * sc,
+                          (float)__float_as_int(a1.z) * sc, (float)__float_as_int(a1.w) * sc);
         }
-        o[e] = sign_update(x, IDENT ? rv[e] * factor : sgnf(rv[e]), args.lr, args.weight_decay);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const SplitH8 Bq = load_split8h(TB + (2 * (2 * jh + jj) + h) * kSplitHFragFloats, lane);
+#pragma unroll
+          for (int uu = 0; uu < 2; ++uu) Y[uu][jj] = mfma_f16(A[uu].lo, Bq.hi, Y[uu][jj]);
+#pragma unroll
+          for (int uu = 0; uu < 2; ++uu) Y[uu][jj] = mfma_f16(A[uu].hi, Bq.lo, Y[uu][jj]);
+#pragma unroll
+          for (int uu = 0; uu < 2; ++uu) Y[uu][jj] = mfma_f16(A[uu].hi, Bq.hi, Y[uu][jj]);
+        }
       }
-      if constexpr (PBF16) {
-        const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
-        bstore_u2(xres, vo * 2, 32u * p * ucols * 2, pk);
-      } else {
-        const f32x4 ov = {o[0], o[1], o[2], o[3]};
-        bstore_f4(xres, vo * 4, 32u * p * ucols * 4, ov);
+      SplitH8 Bt[2];
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+        Bt[jj] = split8h(Y[0][jj][0], Y[0][jj][1], Y[0][jj][2], Y[0][jj][3], Y[1][jj][0], Y[1][jj][1], Y[1][jj][2], Y[1][jj][3]);
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const SplitH8 Ap = load_split8h(TA + (2 * it + hp) * kSplitHFragFloats, lane);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) R[it][jj] = mfma_f16(Ap.lo, Bt[jj].hi, R[it][jj]);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) R[it][jj] = mfma_f16(Ap.hi, Bt[jj].lo, R[it][jj]);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) R[it][jj] = mfma_f16(Ap.hi, Bt[jj].hi, R[it][jj]);
+      }
+    }
+    wg_lds_barrier();   // every read of S is done: the R_ab replace it
+    {
+      float* wq = tiles + quad * Q128_TILE_FLOATS;
+#pragma unroll
+      for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) wq[(16 * it + 4 * g + r) * Q128_LDT + 16 * (2 * jh + jj) + c] = R[it][jj][r];
+    }
+    wg_lds_barrier();
+
+    // ---- x <- x - lr (phi(R) + wd x): phi = sgn, or the identity on the aggregate (the quadrants hold R times
+    //      2^sh 2^-22 2^(2 kSplitHBasisLog2); `scale` is 1 or 1/W) --------------------------------------------------
+    const float factor = IDENT ? ldexpf(args.scale, 22 - 2 * kSplitHBasisLog2 - sh_chunk) : 0.f;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const uint32_t pb = (uint32_t)tid + Q128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
+      const float* rq = tiles + ir * Q128_LDT + j0;
+      const f32x4 q00 = *reinterpret_cast<const f32x4*>(rq), q01 = *reinterpret_cast<const f32x4*>(rq + Q128_TILE_FLOATS);
+      const f32x4 q10 = *reinterpret_cast<const f32x4*>(rq + 2 * Q128_TILE_FLOATS);
+      const f32x4 q11 = *reinterpret_cast<const f32x4*>(rq + 3 * Q128_TILE_FLOATS);
+      const f32x4 ea = q00 + q01, eb = q00 - q01, oa = q10 + q11, ob = q10 - q11;
+      f32x4 rr[4];   // segments (i, j0..), (i, 124 - j0..), (127 - i, j0..), (127 - i, 124 - j0..)
+      rr[0] = ea + oa;
+      rr[2] = ea - oa;
+      const f32x4 m1 = eb + ob, m3 = eb - ob;   // columns 127 - j0 - e: reversed within the segment
+      rr[1] = (f32x4){m1[3], m1[2], m1[1], m1[0]};
+      rr[3] = (f32x4){m3[3], m3[2], m3[1], m3[0]};
+#pragma unroll
+      for (int sg = 0; sg < 4; ++sg) {
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float x;
+          if constexpr (PBF16) {
+            const uint32_t raw = xin[p][sg][e >> 1];
+            x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+          } else {
+            x = xin[p][sg][e];
+          }
+          o[e] = sign_update(x, IDENT ? rr[sg][e] * factor : sgnf(rr[sg][e]), args.lr, args.weight_decay);
+        }
+        if constexpr (PBF16) {
+          const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+          bstore_u2(xres, xo[p][sg], 0u, pk);
+        } else {
+          const f32x4 ov = {o[0], o[1], o[2], o[3]};
+          bstore_f4(xres, xo[p][sg], 0u, ov);
+        }
       }
     }
     if (nxt >= total) break;
     chunk = nxt;
-    wg_lds_barrier();   // the tile is zeroed next
+    wg_lds_barrier();   // the tiles are zeroed next
   }
 }
 
@@ -873,13 +904,13 @@ static hipError_t launch_dec_wg128_phi(const TableView& tv, const float* basis, 
                                        hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_wg128<PBF16, STREAM, IDENT, COUNT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, W128_DEC_LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_quad128<PBF16, STREAM, IDENT, COUNT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Q128_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((decode2d_wg128<PBF16, STREAM, IDENT, COUNT>), dim3((unsigned)grid), dim3(W128_THREADS),
-                     W128_DEC_LDS_BYTES, stream, tv, basis, a);
+  hipLaunchKernelGGL((decode2d_quad128<PBF16, STREAM, IDENT, COUNT>), dim3((unsigned)grid), dim3(Q128_THREADS),
+                     Q128_LDS_BYTES, stream, tv, basis, a);
   return hipGetLastError();
 }
 template <bool PBF16, bool STREAM>
