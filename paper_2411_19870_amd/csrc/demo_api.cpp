@@ -29,7 +29,8 @@ struct BasisTable {
   float* dec64 = nullptr;
   float* enc32 = nullptr;    // dense-basis tile tables for s = 32
   float* dec32 = nullptr;    // fragment table of the s = 32 tile decode kernel
-  float* dec128 = nullptr;   // fragment tables of the s = 128 decode kernel
+  float* dec128 = nullptr;   // fragment tables of the s = 128 kernels
+  float* enc128 = nullptr;
   float* custom = nullptr;   // s x s matrix set with demo_set_basis (identity / Gram-Schmidt), allocated on first use
   float* custom_enc64 = nullptr;   // s = 64: tables of the full-product wavefront kernels for `custom`
   float* custom_dec64 = nullptr;
@@ -168,7 +169,7 @@ int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
 // Host copies of the tables of one chunk size: the orthonormal DCT-II matrix P[u][n] = c_u cos(pi (2n+1) u / (2s))
 // evaluated in double precision and rounded once to float32, and the fragment tables the wavefront kernels read.
 struct HostBasis {
-  std::vector<float> P, enc64, dec64, enc32, dec32, dec128;
+  std::vector<float> P, enc64, dec64, enc32, dec32, dec128, enc128;
 };
 
 void build_host_basis(int s, HostBasis* hb) {
@@ -199,6 +200,8 @@ void build_host_basis(int s, HostBasis* hb) {
   if (s == 128) {
     hb->dec128.resize(demo::kDec128TableFloats);
     demo::build_dec128_tables(P.data(), hb->dec128.data());
+    hb->enc128.resize(demo::kEnc128TableFloats);
+    demo::build_enc128_tables(P.data(), hb->enc128.data());
   }
 }
 
@@ -209,7 +212,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
       // kernels that read the matrix itself
       *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr, false, b.custom_enc64, b.custom_dec64}
                           : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
-      if (!b.use_custom) out->dec128 = b.dec128;
+      if (!b.use_custom) { out->dec128 = b.dec128; out->enc128 = b.enc128; }
       return DEMO_OK;
     }
   HostBasis hb;
@@ -225,15 +228,18 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     if (b.enc32) (void)hipFree(b.enc32);
     if (b.dec32) (void)hipFree(b.dec32);
     if (b.dec128) (void)hipFree(b.dec128);
+    if (b.enc128) (void)hipFree(b.enc128);
   };
   if (!hb.enc64.empty() && (rc = upload(ctx, hb.enc64, &b.enc64)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec64.empty() && (rc = upload(ctx, hb.dec64, &b.dec64)) != DEMO_OK) { drop(); return rc; }
   if (!hb.enc32.empty() && (rc = upload(ctx, hb.enc32, &b.enc32)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec32.empty() && (rc = upload(ctx, hb.dec32, &b.dec32)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec128.empty() && (rc = upload(ctx, hb.dec128, &b.dec128)) != DEMO_OK) { drop(); return rc; }
+  if (!hb.enc128.empty() && (rc = upload(ctx, hb.enc128, &b.enc128)) != DEMO_OK) { drop(); return rc; }
   ctx->bases.push_back(b);
   *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
   out->dec128 = b.dec128;
+  out->enc128 = b.enc128;
   return DEMO_OK;
 }
 
@@ -578,6 +584,7 @@ int demo_destroy(demo_ctx* ctx) {
       if (b.enc32) (void)hipFree(b.enc32);
       if (b.dec32) (void)hipFree(b.dec32);
       if (b.dec128) (void)hipFree(b.dec128);
+      if (b.enc128) (void)hipFree(b.enc128);
       if (b.custom) (void)hipFree(b.custom);
       if (b.custom_enc64) (void)hipFree(b.custom_enc64);
       if (b.custom_dec64) (void)hipFree(b.custom_dec64);
@@ -698,7 +705,7 @@ int demo_encode_noalloc(demo_ctx* ctx, const demo_tensor* tensors, int n, float 
   if (demo::noalloc_basis_resident(ctx->device) != s) {
     HostBasis hb;
     build_host_basis(s, &hb);
-    const std::vector<float>& enc = s == 64 ? hb.enc64 : hb.enc32;   // empty at s = 128
+    const std::vector<float>& enc = s == 64 ? hb.enc64 : s == 32 ? hb.enc32 : hb.enc128;
     if (o_enc + enc.size() * sizeof(float) > demo::kNoallocBasisBytes) return DEMO_ERR_LIMIT;
     demo::noalloc_set_basis_resident(ctx->device, 0);
     if ((e = demo::device_write(sc, hb.P.data(), hb.P.size() * sizeof(float), st)) != hipSuccess) return fail_hip(ctx, e);
@@ -708,7 +715,8 @@ int demo_encode_noalloc(demo_ctx* ctx, const demo_tensor* tensors, int n, float 
   }
   const float* P = reinterpret_cast<const float*>(sc);
   const float* enc = reinterpret_cast<const float*>(sc + o_enc);
-  const demo::BasisTables basis{P, s == 64 ? enc : nullptr, nullptr, s == 32 ? enc : nullptr, nullptr, true};
+  demo::BasisTables basis{P, s == 64 ? enc : nullptr, nullptr, s == 32 ? enc : nullptr, nullptr, true};
+  if (s == 128) basis.enc128 = enc;
 
   // descriptor tables and queue headers of this call (the headers are zero in the image: the queue starts empty
   // whatever the last call left); the queue lists behind them need no initial contents

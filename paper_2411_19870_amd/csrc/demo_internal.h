@@ -80,6 +80,7 @@ struct BasisTables {
   const float* enc64g = nullptr;   // s = 64, matrix set by the caller: tables of the full-product wavefront kernels
   const float* dec64g = nullptr;
   const float* dec128 = nullptr;   // tables of the s = 128 decode kernel (DCT only, else null)
+  const float* enc128 = nullptr;   // tables of the s = 128 encode kernel (DCT only, else null)
 };
 
 // Launch wrappers (demo_kernels.hip).  `variant` selects the kernel family:
@@ -145,8 +146,10 @@ hipError_t launch_decode2d_tile32(const TableView& tiles, const float* tables, c
 // s = 128 kernels, one workgroup per chunk (demo_wg128.hip); they need the DCT (mirror-folded products).  The encode
 // kernel reads the plain 128 x 128 basis, the decode kernel its own tables.
 constexpr int kFast128MaxK = 64;
-hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const EncodeArgs& a, const Worklist& wl,
-                                 bool grad_bf16, int num_cus, hipStream_t stream);
+constexpr int kEnc128TableFloats = 2 * 8 * 512;   // pre-split float16 fragment blocks of the transposed even and odd rows of P
+void build_enc128_tables(const double* P128, float* out /* kEnc128TableFloats */);
+hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const float* tables, const EncodeArgs& a,
+                                 const Worklist& wl, bool grad_bf16, int num_cus, hipStream_t stream);
 // decode keeps the W*k pairs of a chunk in eight registers per lane of its 512 threads
 constexpr int kFast128MaxPairs = 4096;
 constexpr int kDec128TableFloats = 2 * 8 * 512;   // pre-split float16 fragment blocks of the even and the odd rows of P

@@ -1164,10 +1164,10 @@ hipError_t launch_encode2d(const TableView& tv, const TableView* tiles, const Ba
     if (e != hipSuccess) return e;
     return launch_enc2d_generic<64>(tv, basis, a, wl, num_cus, stream);
   }
-  if (variant >= 1 && s == 128 && a.mirror != 0 && a.k <= kFast128MaxK && wl.list != nullptr &&
+  if (variant >= 1 && s == 128 && a.mirror != 0 && a.k <= kFast128MaxK && wl.list != nullptr && bt.enc128 != nullptr &&
       (gmix == 1u || gmix == 2u)) {
     // workgroup-per-chunk kernel with the next chunk in flight, then the exact generic kernel over its queue
-    hipError_t e = launch_encode2d_wg128(tv, basis, a, wl, gmix == 1u, num_cus, stream);
+    hipError_t e = launch_encode2d_wg128(tv, basis, bt.enc128, a, wl, gmix == 1u, num_cus, stream);
     if (e != hipSuccess) return e;
     return launch_enc2d_generic<128>(tv, basis, a, wl, num_cus, stream);
   }

@@ -462,28 +462,509 @@ __global__ __launch_bounds__(W128_THREADS) void encode2d_wg128(TableView tv, con
   DEMO_PHASE_FLUSH(0);
 }
 
+// ---------------------------------------------------------------------------
+// encode on the parity quadrants (512 threads, 8 wavefronts per chunk)
+// ---------------------------------------------------------------------------
+// With A[u'][i] = P[2u'][i], O[u'][i] = P[2u'+1][i] (i < 64; row u of the DCT is even or odd under i -> 127 - i) the
+// coefficients of parities (a, b) = (u % 2, v % 2) are one 64 x 64 two-sided product each,
+//   Q[2u'+a][2v'+b] = (M_a B_ab M_b^T)[u'][v'],   M_0 = A, M_1 = O,
+//   B_ab[i][j] = D[i][j] + (-1)^b D[i][127-j] + (-1)^a D[127-i][j] + (-1)^(a+b) D[127-i][127-j]      (i, j < 64),
+// a quarter of the multiplications of the full products.  Thread t owns, for p < 2, position (i, j0..j0+3) =
+// ((t + 512 p) / 16, 4 ((t + 512 p) % 16)) of the quadrants, i.e. the four row segments (i, j0..), (i, 124 - j0..),
+// (127 - i, j0..), (127 - i, 124 - j0..) of the chunk: it loads them, forms D = beta m + g and the four folded values,
+// keeps D for the final m <- D - alpha R, and unfolds the reconstruction from the same four quadrant values.
+// The products run on the float16 matrix pipe, operands split into two parts (demo_device.h): the folded tile is
+// scaled by a power of two taken from the chunk's largest |D| to below 2^8, the basis fragments by 2^4, so that the
+// first product stays below 2^15; two wavefronts per quadrant, each with half of the columns, and the accumulators of
+// the first product are, as they lie, operands of the second (as in the decode kernel below).  The coefficients are
+// ranked at that scale and unscaled (exactly) where they leave for the payload and the reconstruction.
+// Top-k and reconstruction as in the 1024-thread kernel above: bound from 128 group maxima (groups of 4 lanes),
+// candidate list, ranks by slices, class lists, float32 MFMA gathers on the class-major basis tile.
+namespace {
+constexpr int E128_WAVES = 8;
+constexpr int E128_THREADS = 64 * E128_WAVES;
+constexpr int E128_LDT = 68;                                    // quadrant row stride (floats)
+constexpr int E128_TILE_FLOATS = 64 * E128_LDT;
+constexpr int E128_TILES_FLOATS = 4 * E128_TILE_FLOATS;
+constexpr int E128_FRAGS = 8 * kSplitHFragFloats;               // fragment table of one 64 x 64 matrix
+constexpr int E128_TABLE_FLOATS = 2 * E128_FRAGS;               // A^T, then O^T
+constexpr int E128_LDS_BYTES = 4 * (E128_TABLE_FLOATS + W128_P_FLOATS + E128_TILES_FLOATS + 128 + 16 + 16 + W128_CAP) +
+                               8 * (W128_CAP + 2 + 4 * W128_SEL);
+static_assert(E128_TABLE_FLOATS == kEnc128TableFloats, "table size");
+static_assert(E128_LDS_BYTES <= 160 * 1024, "LDS budget");
+static_assert(W128_CAP == E128_THREADS, "one candidate per thread in the selection step");
+}  // namespace
+
+// Host: pre-split float16 fragment tables of A^T and O^T (scaled by 2^kSplitHBasisLog2) from the 128 x 128 DCT matrix
+// P: per matrix M block 2 t + h, slot j of contraction group g holds M[16 t + c][16 (2 h + j / 4) + 4 g + j % 4]
+// (first product: B operand, contracts j, output columns v' = 16 t + c; second: A operand, contracts i, output rows
+// u' = 16 t + c).
+void build_enc128_tables(const double* P, float* out) {
+  for (int m = 0; m < 2; ++m)
+    for (int t = 0; t < 4; ++t)
+      for (int h = 0; h < 2; ++h)
+        for (int lane = 0; lane < 64; ++lane) {
+          float v[8];
+          for (int j = 0; j < 8; ++j) {
+            const int kk = 16 * (2 * h + (j >> 2)) + 4 * (lane >> 4) + (j & 3);
+            v[j] = (float)__builtin_ldexp(P[(2 * (16 * t + (lane & 15)) + m) * 128 + kk], kSplitHBasisLog2);
+          }
+          host_store_split8h(out + m * E128_FRAGS + (2 * t + h) * kSplitHFragFloats, lane, v);
+        }
+}
+
 template <bool GBF16>
-static hipError_t launch_enc_wg128(const TableView& tv, const float* basis, const EncodeArgs& a, const Worklist& wl,
-                                   int64_t grid, hipStream_t stream) {
+__global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, const float* __restrict__ basis,
+                                                                  const float* __restrict__ tables, EncodeArgs args,
+                                                                  Worklist wl) {
+  extern __shared__ float lds[];
+  const float* sT = lds;
+  float* sP = lds + E128_TABLE_FLOATS;
+  float* tiles = sP + W128_P_FLOATS;
+  uint32_t* gmax = reinterpret_cast<uint32_t*>(tiles + E128_TILES_FLOATS);   // [128] maxima of groups of 4 lanes
+  int* ctl = reinterpret_cast<int*>(gmax + 128);                      // [0] candidate cursor, [1] threshold, [2] all-zero flag, [4..7] class counts
+  uint32_t* wmax = reinterpret_cast<uint32_t*>(ctl + 16);             // [8] per-wavefront largest |D|
+  uint32_t* rk = wmax + 16;                                           // [CAP] rank | class rank << 16 of a candidate
+  uint2* cand = reinterpret_cast<uint2*>(rk + W128_CAP);              // [CAP + 2] {coefficient bits (scaled), flat index}
+  uint2* sel = cand + W128_CAP + 2;                                   // [4][SEL]  {basis row offsets, coefficient bits}
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int k = args.k;
+  const int total = tv.total_chunks;
+  int chunk = blockIdx.x;
+  if (chunk >= total) return;
+
+  for (int e = tid; e < E128_TABLE_FLOATS / 4; e += E128_THREADS)
+    reinterpret_cast<f32x4*>(lds)[e] = gload_f4(tables + 4 * e);
+  for (int e = tid; e < 128 * 16; e += E128_THREADS) {
+    const int u = e >> 4, c4 = (e & 15) * 4;
+    *reinterpret_cast<f32x4*>(&sP[pos3((uint32_t)u) * W128_LDP + c4]) = gload_f4(basis + u * 128 + c4);
+  }
+
+  using GT = typename std::conditional<GBF16, u32x2, f32x4>::type;
+  f32x4 mv[2][4];
+  GT gv[2][4];
+  __amdgpu_buffer_rsrc_t mres_in, gres_in;
+  uint32_t ucols_in = 0;
+  auto set_source = [&](const TensorDev& dd, int cc) {
+    const int k0 = cc / dd.cchunks, k1 = cc - k0 * dd.cchunks;
+    const int64_t origin = (int64_t)k0 * 128 * dd.cols + (int64_t)k1 * 128;
+    ucols_in = (uint32_t)dd.cols;
+    mres_in = make_rsrc(dd.mom + origin);
+    gres_in = GBF16 ? make_rsrc(static_cast<const uint16_t*>(dd.grad) + origin)
+                    : make_rsrc(static_cast<const float*>(dd.grad) + origin);
+  };
+  // element offset of segment sg of position block p in a chunk whose rows are `uc` elements apart
+  auto seg_offset = [](uint32_t t, int p, int sg, uint32_t uc) {
+    const uint32_t pb = t + E128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
+    return ((sg & 2) ? 127u - ir : ir) * uc + ((sg & 1) ? 124u - j0 : j0);
+  };
+  auto issue_rows = [&](uint32_t t) {
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int sg = 0; sg < 4; ++sg) {
+        const uint32_t eo = seg_offset(t, p, sg, ucols_in);
+        mv[p][sg] = bload_f4(mres_in, eo * 4, 0u);
+        if constexpr (GBF16) gv[p][sg] = bload_u2(gres_in, eo * 2, 0u);
+        else gv[p][sg] = bload_f4(gres_in, eo * 4, 0u);
+      }
+  };
+
+  int t = find_tensor_uniform(tv, chunk);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
+  set_source(d, chunk - t_first);
+  issue_rows((uint32_t)tid);
+  // the first chunk's rows are waited for here, outside the loop: with loads pending at the loop's entry and the
+  // momentum stores pending on its back edge, the loop's first wait would be for everything outstanding
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int sg = 0; sg < 4; ++sg) asm volatile("" : "+v"(mv[p][sg]), "+v"(gv[p][sg]));
+
+  // products: quadrant of this wavefront, its half of the columns, the two fragment tables
+  const int quad = wave >> 1, jh = wave & 1;
+  const float* tq = tiles + quad * E128_TILE_FLOATS;
+  const float* TB = sT + (quad & 1) * E128_FRAGS;              // first product: M_b^T, the column parity
+  const float* TA = sT + (quad >> 1) * E128_FRAGS;             // second product: M_a, the row parity
+
+  for (;;) {
+    int tidv = tid;
+    asm volatile("" : "+v"(tidv));   // addresses below are recomputed per chunk rather than kept (and spilled) across it
+    const int lanev = tidv & 63;
+    const uint32_t zero = (uint32_t)(tidv >> 31);                            // 0, formed per chunk like the addresses
+    if (tidv < 4 * W128_SEL) sel[tidv] = make_uint2(zero, zero);             // zero-valued padding of the class lists
+    cand[tidv] = make_uint2(zero, ~zero);                                     // entries that precede nothing
+    if (tidv < 2) cand[W128_CAP + tidv] = make_uint2(zero, ~zero);
+    rk[tidv] = zero;
+    if (tidv < 8) ctl[tidv] = (int)zero;
+    // where this chunk's results go
+    const int cc = chunk - t_first;
+    const uint32_t ucols = (uint32_t)d.cols;
+    const __amdgpu_buffer_rsrc_t mres_out =
+        make_rsrc(d.mom + ((int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128));
+    DEMO_GLOBAL int32_t* const out_idx = as_global(d.idx) + (int64_t)cc * k;
+    DEMO_GLOBAL float* const out_val = as_global(d.val) + (int64_t)cc * k;
+
+    // ---- D = beta m + g from the rows in the registers, and its largest magnitude -------------------------------
+    f32x4 D[2][4];
+    float mx = 0.f;
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+      for (int sg = 0; sg < 4; ++sg) {
+        f32x4 gf;
+        if constexpr (GBF16) {
+          gf = (f32x4){bf16_to_f32(gv[p][sg][0] & 0xffffu), bf16_to_f32(gv[p][sg][0] >> 16),
+                       bf16_to_f32(gv[p][sg][1] & 0xffffu), bf16_to_f32(gv[p][sg][1] >> 16)};
+        } else {
+          gf = gv[p][sg];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          D[p][sg][e] = __fmaf_rn(args.beta, mv[p][sg][e], args.grad_scale * gf[e]);
+          mx = fmaxf(mx, fabsf(D[p][sg][e]));
+        }
+      }
+    {
+      uint32_t mb = __float_as_uint(mx);
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x141, 0xf, 0xf, false));  // row_half_mirror
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
+      const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
+      const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
+      if (lane == 0) wmax[wave] = max(m01, m23);
+    }
+    // ---- the rows of the next chunk: in flight until the top of the next turn -------------------------------------
+    const int nxt = chunk + (int)gridDim.x;
+    const bool has_next = nxt < total;
+    if (has_next) {
+      while (nxt >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
+      }
+      set_source(d, nxt - t_first);
+      issue_rows((uint32_t)tidv);
+    }
+    wg_lds_barrier();
+    // ---- scale 2^sexp: |D| < 2^(e+1), so the folded values stay below 2^(e+3) and 2^(5-e) brings them below 2^8 ------
+    int sexp;
+    {
+      uint32_t mall = wmax[lanev & 7];
+      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0xB1, 0xf, 0xf, false));
+      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x4E, 0xf, 0xf, false));
+      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x141, 0xf, 0xf, false));
+      const int ex = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)mall) >> 23);   // biased exponent of the largest |D|
+      int se = 259 - ex;                                       // biased exponent of 2^(5 - (ex - 127))
+      se = se < 1 ? 1 : se > 254 ? 254 : se;                   // (chunks below 2^-121 keep fewer bits)
+      sexp = se - 127;
+    }
+    const float scale = __uint_as_float((uint32_t)(sexp + 127) << 23);
+    // ---- folded and scaled values into the quadrant tiles -----------------------------------------------------------
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const uint32_t pb = (uint32_t)tidv + E128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
+      f32x4 b00, b01, b10, b11;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float d0 = D[p][0][e], d1 = D[p][1][3 - e], d2 = D[p][2][e], d3 = D[p][3][3 - e];
+        const float s0 = d0 + d1, t0 = d0 - d1, s1 = d2 + d3, t1 = d2 - d3;
+        b00[e] = (s0 + s1) * scale;
+        b01[e] = (t0 + t1) * scale;
+        b10[e] = (s0 - s1) * scale;
+        b11[e] = (t0 - t1) * scale;
+      }
+      float* wq = tiles + ir * E128_LDT + j0;
+      *reinterpret_cast<f32x4*>(wq) = b00;
+      *reinterpret_cast<f32x4*>(wq + E128_TILE_FLOATS) = b01;
+      *reinterpret_cast<f32x4*>(wq + 2 * E128_TILE_FLOATS) = b10;
+      *reinterpret_cast<f32x4*>(wq + 3 * E128_TILE_FLOATS) = b11;
+    }
+    wg_lds_barrier();
+
+    // ---- the two products of this wavefront's quadrant, columns v' = 32 jh .. 32 jh + 31 ---------------------------
+    // first: Z[i][v'] = sum_j B_ab[i][j] M_b[v'][j], A = B_ab from the tile (row 16 it + c; the eight j of a slot group
+    // are two 16-byte reads), B = fragments.  The accumulators of two row tiles are, as they lie, the eight contraction
+    // slots of the second, Q[u'][v'] += sum_i M_a[u'][i] Z[i][v'], A = fragments.
+    f32x4 Q[4][2];   // [ut][vt - 2 jh]: coefficient (2 (16 ut + 4 g + r) + a, 2 (16 vt + c) + b), scaled
+    {
+      const int g = lanev >> 4, c = lanev & 15;
+#pragma unroll
+      for (int ut = 0; ut < 4; ++ut)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) Q[ut][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int hp = 0; hp < 2; ++hp) {
+        f32x4 Z[2][2];   // [it - 2 hp][vt - 2 jh]
+#pragma unroll
+        for (int uu = 0; uu < 2; ++uu)
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) Z[uu][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          SplitH8 A[2];
+#pragma unroll
+          for (int uu = 0; uu < 2; ++uu) {
+            const float* arow = &tq[(16 * (2 * hp + uu) + c) * E128_LDT + 4 * g + 32 * h];
+            const float4 a0 = *reinterpret_cast<const float4*>(arow);
+            const float4 a1 = *reinterpret_cast<const float4*>(arow + 16);
+            A[uu] = split8h(a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w);
+          }
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            const SplitH8 Bq = load_split8h(TB + (2 * (2 * jh + jj) + h) * kSplitHFragFloats, lanev);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) Z[uu][jj] = mfma_f16(A[uu].lo, Bq.hi, Z[uu][jj]);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) Z[uu][jj] = mfma_f16(A[uu].hi, Bq.lo, Z[uu][jj]);
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) Z[uu][jj] = mfma_f16(A[uu].hi, Bq.hi, Z[uu][jj]);
+          }
+        }
+        SplitH8 Bt[2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+          Bt[jj] = split8h(Z[0][jj][0], Z[0][jj][1], Z[0][jj][2], Z[0][jj][3], Z[1][jj][0], Z[1][jj][1], Z[1][jj][2], Z[1][jj][3]);
+#pragma unroll
+        for (int ut = 0; ut < 4; ++ut) {
+          const SplitH8 Ap = load_split8h(TA + (2 * ut + hp) * kSplitHFragFloats, lanev);
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) Q[ut][jj] = mfma_f16(Ap.lo, Bt[jj].hi, Q[ut][jj]);
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) Q[ut][jj] = mfma_f16(Ap.hi, Bt[jj].lo, Q[ut][jj]);
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) Q[ut][jj] = mfma_f16(Ap.hi, Bt[jj].hi, Q[ut][jj]);
+        }
+      }
+    }
+
+    // ---- top-k over the 16384 coefficients -----------------------------------------------------------------
+    // (1) lower bound of the k-th largest magnitude: the k-th largest of the 128 maxima of groups of 4 lanes
+    //     (each a coefficient of its own), resolved to its upper 16 bits
+    float gm[4][2];   // largest magnitude of each accumulator
+    float lmf = 0.f;
+#pragma unroll
+    for (int ut = 0; ut < 4; ++ut)
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) {
+        gm[ut][jj] = fmaxf(fmaxf(fabsf(Q[ut][jj][0]), fabsf(Q[ut][jj][1])), fmaxf(fabsf(Q[ut][jj][2]), fabsf(Q[ut][jj][3])));
+        lmf = fmaxf(lmf, gm[ut][jj]);
+      }
+    uint32_t lm = __float_as_uint(lmf);
+    lm = max(lm, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lm, 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    lm = max(lm, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lm, 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    if ((lanev & 3) == 0) gmax[16 * wave + (lanev >> 2)] = lm;
+    wg_lds_barrier();
+    if (wave == 0) {
+      // one wavefront bisects (eight doing the same would only queue at the scalar unit)
+      const uint32_t g0 = gmax[lanev], g1 = gmax[lanev + 64];
+      uint32_t t0 = 0;
+      for (int bit = 30; bit >= 16; --bit) {
+        const uint32_t cnd = t0 | (1u << bit);
+        if (__popcll(__ballot(g0 >= cnd)) + __popcll(__ballot(g1 >= cnd)) >= k) t0 = cnd;
+      }
+      const bool none = __ballot((g0 | g1) != 0u) == 0;
+      if (lane == 0) {
+        ctl[1] = (int)t0;
+        ctl[2] = none ? 1 : 0;
+      }
+    }
+    wg_lds_barrier();
+    const float thr_f = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane(ctl[1]));
+    // (2) candidates |q| >= thr: a wavefront reserves its range of the list with one atomic.  Accumulators whose
+    //     largest magnitude is below the threshold in every lane are passed over as a whole.
+    {
+      // lane part of the flat index 128 u + v = 4096 ut + 1024 g + 256 r + 128 a + 64 jh + 32 jj + 2 c + b
+      const uint32_t fl = (uint32_t)(1024 * (lanev >> 4) + 2 * (lanev & 15) + 128 * (quad >> 1) + 64 * jh + (quad & 1));
+      int cnt = 0;
+#pragma unroll
+      for (int ut = 0; ut < 4; ++ut)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+          if (__ballot(gm[ut][jj] >= thr_f) != 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) cnt += __popcll(__ballot(fabsf(Q[ut][jj][r]) >= thr_f));
+          }
+      int base = 0;
+      if (lane == 0 && cnt != 0) base = atomicAdd(&ctl[0], cnt);
+      base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+      for (int ut = 0; ut < 4; ++ut)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+          if (__ballot(gm[ut][jj] >= thr_f) != 0) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const bool is = fabsf(Q[ut][jj][r]) >= thr_f;
+              const uint64_t mask = __ballot(is);
+              if (mask != 0) {
+                const int pos = base + lanes_below(mask);
+                if (is && pos < W128_CAP) cand[pos] = make_uint2(__float_as_uint(Q[ut][jj][r]), fl + (uint32_t)(4096 * ut + 256 * r + 32 * jj));
+                base += __popcll(mask);
+              }
+            }
+          }
+    }
+    wg_lds_barrier();
+    const int ncand = __builtin_amdgcn_readfirstlane(ctl[0]);
+    const bool overflow = ncand > W128_CAP;
+    const bool all_zero = overflow && __builtin_amdgcn_readfirstlane(ctl[2]) != 0;
+    const bool skip = overflow && !all_zero;
+    if (skip && tid == 0) store_guarded(&wl.list[atomicAdd(wl.count, 1)], chunk);
+    if (all_zero && tid < k) {
+      // every coefficient is zero: the k lowest flat indices with zero values; m = D is stored below
+      store_guarded(out_idx + tid, (int32_t)tid);
+      store_guarded(out_val + tid, 0.f);
+    }
+    // (3) rank the candidates (magnitude descending, flat index ascending).  Wavefront w counts, for every
+    //     candidate, the entries of its slice of the list that precede it, and those among them of the same class
+    //     2 (u % 2) + v % 2; the eight partial counts meet in rk[].
+    if (!overflow) {
+      const int slice = 2 * ((ncand + 15) >> 4);
+      const int j0 = wave * slice;
+      if (j0 < ncand) {
+        for (int ib = 0; 64 * ib < ncand; ++ib) {
+          const int i = 64 * ib + lane;
+          const uint2 me = cand[i < ncand ? i : W128_CAP];
+          const uint32_t mag = me.x & 0x7fffffffu;
+          uint32_t part = 0;
+          for (int j = j0; j < j0 + slice; j += 2) {
+            const uint4 o = *reinterpret_cast<const uint4*>(&cand[j]);
+            const uint32_t m0 = o.x & 0x7fffffffu, m1 = o.z & 0x7fffffffu;
+            const bool p0 = m0 > mag || (m0 == mag && o.y < me.y), p1 = m1 > mag || (m1 == mag && o.w < me.y);
+            part += (p0 ? (((o.y ^ me.y) & 0x81u) == 0 ? 0x10001u : 1u) : 0u) +
+                    (p1 ? (((o.w ^ me.y) & 0x81u) == 0 ? 0x10001u : 1u) : 0u);
+          }
+          if (i < ncand && part != 0) atomicAdd(&rk[i], part);
+        }
+      }
+    }
+    wg_lds_barrier();
+    // ranks < k are the payload; a selected coefficient also goes to the list of its class, at the number of
+    // class members ahead of it (a deterministic order of summation for the reconstruction)
+    if (!overflow && tidv < ncand) {
+      const uint2 me = cand[tidv];
+      const uint32_t r2 = rk[tidv];
+      const int rank = (int)(r2 & 0xffffu), rcls = (int)(r2 >> 16);
+      if (rank < k) {
+        const float val = ldexpf(__uint_as_float(me.x), -sexp - 2 * kSplitHBasisLog2);   // exact
+        store_guarded(out_idx + rank, (int32_t)me.y);
+        store_guarded(out_val + rank, val);
+        const int cls = (int)(((me.y >> 6) & 2u) | (me.y & 1u));
+        // byte offsets of rows pos3(u) and pos3(v) of the basis tile, and the value
+        const uint32_t offs = (uint32_t)(pos3(me.y >> 7) * (W128_LDP * 4)) | ((uint32_t)(pos3(me.y & 127u) * (W128_LDP * 4)) << 16);
+        sel[cls * W128_SEL + rcls] = make_uint2(offs, __float_as_uint(val));
+        atomicAdd(&ctl[4 + cls], 1);
+      }
+    }
+    wg_lds_barrier();
+
+    // ---- reconstruction on the quadrant i, j < 64, one partial sum per class (a, b) = (u % 2, v % 2), written to
+    //      the quadrant tiles (the folded values are dead): row tile mt, column tiles nt0 and nt0 + 1 ---------------
+    {
+      const int mt = wave >> 1, nt0 = 2 * (wave & 1);
+      const int lqv = lanev >> 4, l16v = lanev & 15;
+      f32x4 rc[2][4];
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) rc[n][c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      // the lists are zero-padded, so every class runs to the length of the longest
+      const int4 nc = *reinterpret_cast<const int4*>(&ctl[4]);
+      const int nmax = __builtin_amdgcn_readfirstlane(max(max(nc.x, nc.y), max(nc.z, nc.w)));
+      const float* pa = sP + 16 * mt + l16v;
+      const float* pb = sP + 16 * nt0 + l16v;
+      uint2 en[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + lqv];
+      for (int st = 0; 4 * st < nmax; ++st) {
+        uint2 e[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) e[c] = en[c];
+        float a[4], b0[4], b1[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          a[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pa) + (e[c].x & 0xffffu));
+          b0[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pb) + (e[c].x >> 16));
+          b1[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pb + 16) + (e[c].x >> 16));
+        }
+        // entries of the next step (the lists are 68 long and zero past their ends: step 16 reads padding)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + 4 * (st + 1) + lqv];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float va = __uint_as_float(e[c].y) * a[c];
+          rc[0][c] = mfma4(va, b0[c], rc[0][c]);
+          rc[1][c] = mfma4(va, b1[c], rc[1][c]);
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            tiles[c * E128_TILE_FLOATS + (16 * mt + 4 * lqv + r) * E128_LDT + 16 * (nt0 + n) + l16v] = rc[n][c][r];
+    }
+    wg_lds_barrier();
+
+    // ---- m <- D - alpha R, R unfolded from the four class sums:  R[i][j] = sum s_ab,  R[i][127-j] = sum (-1)^b s_ab,
+    //      R[127-i][j] = sum (-1)^a s_ab,  R[127-i][127-j] = sum (-1)^(a+b) s_ab -----------------------------------------
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const uint32_t pb = (uint32_t)tidv + E128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
+      const float* rq = tiles + ir * E128_LDT + j0;
+      const f32x4 q00 = *reinterpret_cast<const f32x4*>(rq), q01 = *reinterpret_cast<const f32x4*>(rq + E128_TILE_FLOATS);
+      const f32x4 q10 = *reinterpret_cast<const f32x4*>(rq + 2 * E128_TILE_FLOATS);
+      const f32x4 q11 = *reinterpret_cast<const f32x4*>(rq + 3 * E128_TILE_FLOATS);
+      const f32x4 ea = q00 + q01, eb = q00 - q01, oa = q10 + q11, ob = q10 - q11;
+      f32x4 rr[4];
+      rr[0] = ea + oa;
+      rr[2] = ea - oa;
+      const f32x4 m1 = eb + ob, m3 = eb - ob;   // columns 127 - j0 - e: reversed within the segment
+      rr[1] = (f32x4){m1[3], m1[2], m1[1], m1[0]};
+      rr[3] = (f32x4){m3[3], m3[2], m3[1], m3[0]};
+      if (!skip) {
+#pragma unroll
+        for (int sg = 0; sg < 4; ++sg) {
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = __fmaf_rn(-args.alpha, rr[sg][e], D[p][sg][e]);
+          bstore_f4(mres_out, seg_offset((uint32_t)tidv, p, sg, ucols) * 4, 0u, o);
+        }
+      }
+    }
+    if (!has_next) break;
+    chunk = nxt;
+  }
+}
+
+template <bool GBF16>
+static hipError_t launch_enc_wg128(const TableView& tv, const float* basis, const float* tables, const EncodeArgs& a,
+                                   const Worklist& wl, int64_t grid, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_wg128<GBF16>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, W128_ENC_LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode2d_quad128<GBF16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, E128_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(encode2d_wg128<GBF16>, dim3((unsigned)grid), dim3(W128_THREADS), W128_ENC_LDS_BYTES, stream, tv,
-                     basis, a, wl);
+  hipLaunchKernelGGL(encode2d_quad128<GBF16>, dim3((unsigned)grid), dim3(E128_THREADS), E128_LDS_BYTES, stream, tv,
+                     basis, tables, a, wl);
   return hipGetLastError();
 }
 
-hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const EncodeArgs& a, const Worklist& wl,
-                                 bool grad_bf16, int num_cus, hipStream_t stream) {
-  if (a.k < 1 || a.k > kFast128MaxK || wl.list == nullptr) return hipErrorInvalidValue;
+hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const float* tables, const EncodeArgs& a,
+                                 const Worklist& wl, bool grad_bf16, int num_cus, hipStream_t stream) {
+  if (a.k < 1 || a.k > kFast128MaxK || wl.list == nullptr || tables == nullptr) return hipErrorInvalidValue;
   int64_t grid = num_cus;
   if (grid > tv.total_chunks) grid = tv.total_chunks;
-  return grad_bf16 ? launch_enc_wg128<true>(tv, basis, a, wl, grid, stream)
-                   : launch_enc_wg128<false>(tv, basis, a, wl, grid, stream);
+  return grad_bf16 ? launch_enc_wg128<true>(tv, basis, tables, a, wl, grid, stream)
+                   : launch_enc_wg128<false>(tv, basis, tables, a, wl, grid, stream);
 }
 
 // ---------------------------------------------------------------------------
