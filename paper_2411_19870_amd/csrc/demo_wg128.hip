@@ -559,16 +559,19 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
     const uint32_t pb = t + E128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
     return ((sg & 2) ? 127u - ir : ir) * uc + ((sg & 1) ? 124u - j0 : j0);
   };
+  // quarter q < 4 of the rows: position block q / 2, segments 2 (q % 2) and 2 (q % 2) + 1
+  auto issue_rows_part = [&](uint32_t t, int q) __attribute__((always_inline)) {
+#pragma unroll
+    for (int sg = 2 * (q & 1); sg < 2 * (q & 1) + 2; ++sg) {
+      const uint32_t eo = seg_offset(t, q >> 1, sg, ucols_in);
+      mv[q >> 1][sg] = bload_f4(mres_in, eo * 4, 0u);
+      if constexpr (GBF16) gv[q >> 1][sg] = bload_u2(gres_in, eo * 2, 0u);
+      else gv[q >> 1][sg] = bload_f4(gres_in, eo * 4, 0u);
+    }
+  };
   auto issue_rows = [&](uint32_t t) {
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
-#pragma unroll
-      for (int sg = 0; sg < 4; ++sg) {
-        const uint32_t eo = seg_offset(t, p, sg, ucols_in);
-        mv[p][sg] = bload_f4(mres_in, eo * 4, 0u);
-        if constexpr (GBF16) gv[p][sg] = bload_u2(gres_in, eo * 2, 0u);
-        else gv[p][sg] = bload_f4(gres_in, eo * 4, 0u);
-      }
+    for (int q = 0; q < 4; ++q) issue_rows_part(t, q);
   };
 
   int t = find_tensor_uniform(tv, chunk);
@@ -589,6 +592,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
   const float* TB = sT + (quad & 1) * E128_FRAGS;              // first product: M_b^T, the column parity
   const float* TA = sT + (quad >> 1) * E128_FRAGS;             // second product: M_a, the row parity
 
+  DEMO_PHASE_DECL
   for (;;) {
     int tidv = tid;
     asm volatile("" : "+v"(tidv));   // addresses below are recomputed per chunk rather than kept (and spilled) across it
@@ -602,8 +606,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
     // where this chunk's results go
     const int cc = chunk - t_first;
     const uint32_t ucols = (uint32_t)d.cols;
-    const __amdgpu_buffer_rsrc_t mres_out =
-        make_rsrc(d.mom + ((int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128));
+    float* const mom_out = d.mom + ((int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128);
     DEMO_GLOBAL int32_t* const out_idx = as_global(d.idx) + (int64_t)cc * k;
     DEMO_GLOBAL float* const out_val = as_global(d.val) + (int64_t)cc * k;
 
@@ -637,19 +640,8 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
       const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
       if (lane == 0) wmax[wave] = max(m01, m23);
     }
-    // ---- the rows of the next chunk: in flight until the top of the next turn -------------------------------------
     const int nxt = chunk + (int)gridDim.x;
     const bool has_next = nxt < total;
-    if (has_next) {
-      while (nxt >= t_next) {
-        ++t;
-        t_first = t_next;
-        t_next = uniform_prefix(tv, t + 1);
-        d = load_desc_uniform(tv, t);
-      }
-      set_source(d, nxt - t_first);
-      issue_rows((uint32_t)tidv);
-    }
     wg_lds_barrier();
     // ---- scale 2^sexp: |D| < 2^(e+1), so the folded values stay below 2^(e+3) and 2^(5-e) brings them below 2^8 ------
     int sexp;
@@ -685,7 +677,20 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
       *reinterpret_cast<f32x4*>(wq + 3 * E128_TILE_FLOATS) = b11;
     }
     wg_lds_barrier();
+    DEMO_PHASE(0);
 
+    // ---- the rows of the next chunk: requested a quarter per step of the products (sixteen requests per lane issued
+    //      at one point queue up in the memory pipeline and hold the wavefront there), in flight until the top of the
+    //      next turn -----------------------------------------------------------------------------------------------
+    if (has_next) {
+      while (nxt >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
+      }
+      set_source(d, nxt - t_first);
+    }
     // ---- the two products of this wavefront's quadrant, columns v' = 32 jh .. 32 jh + 31 ---------------------------
     // first: Z[i][v'] = sum_j B_ab[i][j] M_b[v'][j], A = B_ab from the tile (row 16 it + c; the eight j of a slot group
     // are two 16-byte reads), B = fragments.  The accumulators of two row tiles are, as they lie, the eight contraction
@@ -724,6 +729,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
 #pragma unroll
             for (int uu = 0; uu < 2; ++uu) Z[uu][jj] = mfma_f16(A[uu].hi, Bq.hi, Z[uu][jj]);
           }
+          if (has_next) issue_rows_part((uint32_t)tidv, 2 * hp + h);
         }
         SplitH8 Bt[2];
 #pragma unroll
@@ -741,6 +747,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
         }
       }
     }
+    DEMO_PHASE(1);
 
     // ---- top-k over the 16384 coefficients -----------------------------------------------------------------
     // (1) lower bound of the k-th largest magnitude: the k-th largest of the 128 maxima of groups of 4 lanes
@@ -774,6 +781,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
       }
     }
     wg_lds_barrier();
+    DEMO_PHASE(2);
     const float thr_f = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane(ctl[1]));
     // (2) candidates |q| >= thr: a wavefront reserves its range of the list with one atomic.  Accumulators whose
     //     largest magnitude is below the threshold in every lane are passed over as a whole.
@@ -810,6 +818,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
           }
     }
     wg_lds_barrier();
+    DEMO_PHASE(3);
     const int ncand = __builtin_amdgcn_readfirstlane(ctl[0]);
     const bool overflow = ncand > W128_CAP;
     const bool all_zero = overflow && __builtin_amdgcn_readfirstlane(ctl[2]) != 0;
@@ -862,6 +871,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
       }
     }
     wg_lds_barrier();
+    DEMO_PHASE(4);
 
     // ---- reconstruction on the quadrant i, j < 64, one partial sum per class (a, b) = (u % 2, v % 2), written to
     //      the quadrant tiles (the folded values are dead): row tile mt, column tiles nt0 and nt0 + 1 ---------------
@@ -911,7 +921,11 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
             tiles[c * E128_TILE_FLOATS + (16 * mt + 4 * lqv + r) * E128_LDT + 16 * (nt0 + n) + l16v] = rc[n][c][r];
     }
     wg_lds_barrier();
+    DEMO_PHASE(5);
 
+    // The stores are unconditional (a queued chunk's go to a buffer of zero records, where the range check drops
+    // them): behind conditional stores the wait for the next chunk's rows would be a wait for everything outstanding.
+    const __amdgpu_buffer_rsrc_t mres_out = skip ? make_rsrc_empty(mom_out) : make_rsrc(mom_out);
     // ---- m <- D - alpha R, R unfolded from the four class sums:  R[i][j] = sum s_ab,  R[i][127-j] = sum (-1)^b s_ab,
     //      R[127-i][j] = sum (-1)^a s_ab,  R[127-i][127-j] = sum (-1)^(a+b) s_ab -----------------------------------------
 #pragma unroll
@@ -928,19 +942,19 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
       const f32x4 m1 = eb + ob, m3 = eb - ob;   // columns 127 - j0 - e: reversed within the segment
       rr[1] = (f32x4){m1[3], m1[2], m1[1], m1[0]};
       rr[3] = (f32x4){m3[3], m3[2], m3[1], m3[0]};
-      if (!skip) {
 #pragma unroll
-        for (int sg = 0; sg < 4; ++sg) {
-          f32x4 o;
+      for (int sg = 0; sg < 4; ++sg) {
+        f32x4 o;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = __fmaf_rn(-args.alpha, rr[sg][e], D[p][sg][e]);
-          bstore_f4(mres_out, seg_offset((uint32_t)tidv, p, sg, ucols) * 4, 0u, o);
-        }
+        for (int e = 0; e < 4; ++e) o[e] = __fmaf_rn(-args.alpha, rr[sg][e], D[p][sg][e]);
+        bstore_f4(mres_out, seg_offset((uint32_t)tidv, p, sg, ucols) * 4, 0u, o);
       }
     }
+    DEMO_PHASE(6);
     if (!has_next) break;
     chunk = nxt;
   }
+  DEMO_PHASE_FLUSH(0);
 }
 
 template <bool GBF16>
@@ -1059,54 +1073,67 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
     pv[j] = 0.f;
   }
   const float rk = 1.0f / (float)k;
-  // `round` matters in STREAM mode only: units 1024 round + 512 jj + tid
-  auto load_payload = [&](const TensorDev& dd, int cc, int round = 0) {
-    const DEMO_GLOBAL int32_t* ip = as_global(dd.idx) + (int64_t)cc * k;
-    const DEMO_GLOBAL float* vp = as_global(dd.val) + (int64_t)cc * k;
+  // Payload requests in two steps: prep_payload forms every offset (units 1024 round + 512 jj + tid in STREAM mode,
+  // pairs 512 j + tid otherwise), issue_payload_part(q), q < 4, requests a quarter of the registers.  Every offset
+  // before the first load, and the loads unconditional (a slot past the end reads the chunk's first pair; mask_payload
+  // discards it where the pairs are consumed): address arithmetic between the loads can pick up a register of a load
+  // in flight as the unused high half of a 64-bit operand, and the wave then waits out that load before it issues
+  // the next.
+  const DEMO_GLOBAL int32_t* pl_ip = nullptr;
+  const DEMO_GLOBAL float* pl_vp = nullptr;
+  uint32_t pl_off[Q128_SLOTS];
+#pragma unroll
+  for (int j = 0; j < Q128_SLOTS; ++j) pl_off[j] = 0u;
+  auto prep_payload = [&](const TensorDev& dd, int cc, int round) {
+    pl_ip = as_global(dd.idx) + (int64_t)cc * k;
+    pl_vp = as_global(dd.val) + (int64_t)cc * k;
     const int wstride = dd.nchunks * k;                        // pairs of one worker for this tensor
     if constexpr (VEC4) {
       static_assert(Q128_SLOTS == 8, "two 16-byte loads per array fill the payload registers");
-      uint32_t off[2];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int unit = (STREAM ? 2 * Q128_THREADS * round : 0) + Q128_THREADS * jj + tid;
         const int p = 4 * unit;
         const int w = (int)(((float)p + 0.5f) * rk);           // as below (p < 65536)
         const int pos = p - w * k;
-        off[jj] = unit < nunits ? (uint32_t)(w * wstride + pos) : 0u;
+        pl_off[jj] = unit < nunits ? (uint32_t)(w * wstride + pos) : 0u;
       }
+    } else {
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const f32x4 vv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(vp + off[jj]));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pv[4 * jj + e] = vv[e];
-        const u32x4 iv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(ip + off[jj]));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pi[4 * jj + e] = (int32_t)iv[e];
-      }
-      return;
-    }
-    // every offset before the first load, and the loads unconditional (a slot past the end reads the chunk's first
-    // pair; mask_payload discards it where the pairs are consumed): address arithmetic between the loads can pick up
-    // a register of a load in flight as the unused high half of a 64-bit operand, and the wave then waits out that
-    // load before it issues the next
-    uint32_t off[Q128_SLOTS];
-#pragma unroll
-    for (int j = 0; j < Q128_SLOTS; ++j) {
-      const int p = Q128_THREADS * j + tid;
-      // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
-      // the rounding error of the float product for p < 4096
-      const int w = (int)(((float)p + 0.5f) * rk);
-      const int pos = p - w * k;
-      off[j] = p < npairs ? (uint32_t)w * (uint32_t)wstride + (uint32_t)pos : 0u;
-    }
-#pragma unroll
-    for (int j = 0; j < Q128_SLOTS; ++j) {
-      if (j < nslots) {                                        // uniform
-        pi[j] = payload_load<true>(ip + off[j]);
-        pv[j] = payload_load<true>(vp + off[j]);
+      for (int j = 0; j < Q128_SLOTS; ++j) {
+        const int p = Q128_THREADS * j + tid;
+        // worker p / k and position p % k; (p + 1/2) / k is never within 1/(2k) of an integer, far more than
+        // the rounding error of the float product for p < 4096
+        const int w = (int)(((float)p + 0.5f) * rk);
+        const int pos = p - w * k;
+        pl_off[j] = p < npairs ? (uint32_t)w * (uint32_t)wstride + (uint32_t)pos : 0u;
       }
     }
+  };
+  auto issue_payload_part = [&](int q) {
+    if constexpr (VEC4) {
+      if (q < 2) {
+        const f32x4 vv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL f32x4*>(pl_vp + pl_off[q]));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pv[4 * q + e] = vv[e];
+        const u32x4 iv = payload_load<true>(reinterpret_cast<const DEMO_GLOBAL u32x4*>(pl_ip + pl_off[q]));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pi[4 * q + e] = (int32_t)iv[e];
+      }
+    } else {
+#pragma unroll
+      for (int j = 2 * q; j < 2 * q + 2; ++j) {
+        if (j < nslots) {                                      // uniform
+          pi[j] = payload_load<true>(pl_ip + pl_off[j]);
+          pv[j] = payload_load<true>(pl_vp + pl_off[j]);
+        }
+      }
+    }
+  };
+  auto load_payload = [&](const TensorDev& dd, int cc, int round = 0) {
+    prep_payload(dd, cc, round);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) issue_payload_part(q);
   };
   // Slots past the end of the chunk's payload become (no index, 0).  Applied where the pairs are consumed, not where
   // they are requested: a select behind the load would make the prefetch wait for its own data.
@@ -1145,8 +1172,46 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
   const float* TB = sT + (quad & 1) * Q128_FRAGS;              // first product: M_b, the column class
   const float* TA = sT + (quad >> 1) * Q128_FRAGS;             // second product: M_a, the row class
 
+  // per-wavefront largest magnitude (as bits) of the payload registers into wmax buffer `buf`
+  auto post_wave_max = [&](int buf) {
+    float mx = 0.f;
+#pragma unroll
+    for (int j = 0; j < Q128_SLOTS; ++j)
+      if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
+    uint32_t mb = __float_as_uint(mx);
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x141, 0xf, 0xf, false));  // row_half_mirror
+    mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
+    const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
+    const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
+    if (lane == 0) wmax[16 * buf + wave] = max(m01, m23);
+  };
+  // shift of the block fixed point from the eight posted maxima (after a barrier)
+  auto shift_from = [&](int buf) {
+    uint32_t mall = wmax[16 * buf + (lane & 7)];
+    mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0xB1, 0xf, 0xf, false));
+    mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x4E, 0xf, 0xf, false));
+    mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x141, 0xf, 0xf, false));
+    mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x140, 0xf, 0xf, false));
+    int ex = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)mall) >> 23);   // biased exponent of the largest magnitude
+    ex = ex < 1 ? 1 : ex;
+    return vbits + 126 - ex;                                 // max |val| * 2^sh < 2^vbits
+  };
+  auto add_pairs = [&](int sh) {
+#pragma unroll
+    for (int j = 0; j < Q128_SLOTS; ++j)
+      if (j < nslots) atomicAdd(&itiles[slot_of(j)], __float2int_rn(ldexpf(pv[j], sh)));
+  };
+  // first chunk: pairs masked, maxima posted, tiles zero (for the others the epilogue of the chunk before does this)
+  mask_payload(0);
+  post_wave_max(0);
+  for (int e = tid; e < Q128_TILES_FLOATS / 4; e += Q128_THREADS)
+    *reinterpret_cast<f32x4*>(&tiles[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
+  wg_lds_barrier();
+
+  DEMO_PHASE_DECL
   for (;;) {
-    mask_payload(0);
     const int cc = chunk - t_first;
     const uint32_t ucols = (uint32_t)d.cols;
     const int64_t origin = (int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128;
@@ -1156,10 +1221,8 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
     if constexpr (COUNT) {
       static_assert(!COUNT || !STREAM, "the count pass needs the whole payload in registers");
       // every pair adds one to its coefficient's slot, reads the total back and is divided by it (sum of val/n over
-      // the n pairs of a slot = (sum of val) / n); the tiles are zeroed again below before the sums go in
-      for (int e = tid; e < Q128_TILES_FLOATS / 4; e += Q128_THREADS)
-        *reinterpret_cast<f32x4*>(&tiles[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
-      wg_lds_barrier();
+      // the n pairs of a slot = (sum of val) / n); the tiles are zero on entry and zeroed again below before the sums
+      // go in
 #pragma unroll
       for (int j = 0; j < Q128_SLOTS; ++j)
         if (j < nslots) atomicAdd(&itiles[slot_of(j)], 1);
@@ -1169,44 +1232,16 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
         if (j < nslots) pv[j] = pv[j] / (float)itiles[slot_of(j)];
       wg_lds_barrier();
     }
-    // ---- largest |val| of the payload registers, zero tiles ---------------------------------------------------
-    // per-wavefront largest magnitude (as bits) of the payload registers into wmax buffer `buf`
-    auto post_wave_max = [&](int buf) {
-      float mx = 0.f;
-#pragma unroll
-      for (int j = 0; j < Q128_SLOTS; ++j)
-        if (j < nslots) mx = fmaxf(mx, fabsf(pv[j]));
-      uint32_t mb = __float_as_uint(mx);
-      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
-      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
-      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x141, 0xf, 0xf, false));  // row_half_mirror
-      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
-      const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
-      const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
-      if (lane == 0) wmax[16 * buf + wave] = max(m01, m23);
-    };
-    // shift of the block fixed point from the eight posted maxima (after a barrier)
-    auto shift_from = [&](int buf) {
-      uint32_t mall = wmax[16 * buf + (lane & 7)];
-      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0xB1, 0xf, 0xf, false));
-      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x4E, 0xf, 0xf, false));
-      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x141, 0xf, 0xf, false));
-      mall = max(mall, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mall, 0x140, 0xf, 0xf, false));
-      int ex = (int)((uint32_t)__builtin_amdgcn_readfirstlane((int)mall) >> 23);   // biased exponent of the largest magnitude
-      ex = ex < 1 ? 1 : ex;
-      return vbits + 126 - ex;                                 // max |val| * 2^sh < 2^vbits
-    };
-    auto add_pairs = [&](int sh) {
-#pragma unroll
-      for (int j = 0; j < Q128_SLOTS; ++j)
-        if (j < nslots) atomicAdd(&itiles[slot_of(j)], __float2int_rn(ldexpf(pv[j], sh)));
-    };
-    post_wave_max(0);
-    for (int e = tid; e < Q128_TILES_FLOATS / 4; e += Q128_THREADS)
-      *reinterpret_cast<f32x4*>(&tiles[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
-    wg_lds_barrier();
+    if constexpr (COUNT) {
+      // (the count pass used the tiles and the registers changed: clear and post again)
+      post_wave_max(0);
+      for (int e = tid; e < Q128_TILES_FLOATS / 4; e += Q128_THREADS)
+        *reinterpret_cast<f32x4*>(&tiles[4 * e]) = (f32x4){0.f, 0.f, 0.f, 0.f};
+      wg_lds_barrier();
+    }
 
-    // ---- S[idx] += val in fixed point ------------------------------------------------------------------------
+    // ---- S[idx] += val in fixed point (the tiles are zero and the maxima posted: before the loop for the first
+    //      chunk, by the epilogue of the chunk before for the others) ---------------------------------------------
     int sh_chunk = shift_from(0);   // shift of this chunk's fixed point (undone when phi is the identity)
     add_pairs(sh_chunk);
     if constexpr (STREAM) {
@@ -1237,16 +1272,19 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
         add_pairs(sh_chunk);
       }
     }
-    // ---- payload of the next chunk and the parameters of this one, in flight during the products ---------------
+    // ---- payload of the next chunk and the parameters of this one: requested a quarter per step of the products
+    //      (sixteen requests per lane issued at one point queue up in the memory pipeline and hold the wavefront there),
+    //      in flight until the epilogue / the next turn ----------------------------------------------------------------
     const int nxt = chunk + (int)gridDim.x;
-    if (nxt < total) {
+    const bool has_next = nxt < total;
+    if (has_next) {
       while (nxt >= t_next) {
         ++t;
         t_first = t_next;
         t_next = uniform_prefix(tv, t + 1);
         d = load_desc_uniform(tv, t);
       }
-      load_payload(d, nxt - t_first, 0);
+      prep_payload(d, nxt - t_first, 0);
     }
     using XT = typename std::conditional<PBF16, u32x2, f32x4>::type;
     constexpr uint32_t XB = PBF16 ? 2u : 4u;                   // bytes per parameter
@@ -1259,13 +1297,17 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
       xo[p][1] = (ir * ucols + 124u - j0) * XB;
       xo[p][2] = ((127u - ir) * ucols + j0) * XB;
       xo[p][3] = ((127u - ir) * ucols + 124u - j0) * XB;
-#pragma unroll
-      for (int sg = 0; sg < 4; ++sg) {
-        if constexpr (PBF16) xin[p][sg] = bload_u2(xres, xo[p][sg], 0u);
-        else xin[p][sg] = bload_f4(xres, xo[p][sg], 0u);
-      }
     }
+    auto issue_step = [&](int q) __attribute__((always_inline)) {
+      if (has_next) issue_payload_part(q);
+#pragma unroll
+      for (int sg = 2 * (q & 1); sg < 2 * (q & 1) + 2; ++sg) {
+        if constexpr (PBF16) xin[q >> 1][sg] = bload_u2(xres, xo[q >> 1][sg], 0u);
+        else xin[q >> 1][sg] = bload_f4(xres, xo[q >> 1][sg], 0u);
+      }
+    };
     wg_lds_barrier();
+    DEMO_PHASE(0);
 
     // ---- the two products of this wavefront's quadrant, columns 32 jh .. 32 jh + 31 ------------------------------
     // first: Y[u][j] = sum_v S_ab[u][v] M_b[v][j], A = S from the tile (row 16 ut + c; the eight v of a slot group
@@ -1306,6 +1348,7 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
 #pragma unroll
           for (int uu = 0; uu < 2; ++uu) Y[uu][jj] = mfma_f16(A[uu].hi, Bq.hi, Y[uu][jj]);
         }
+        issue_step(2 * hp + h);
       }
       SplitH8 Bt[2];
 #pragma unroll
@@ -1322,6 +1365,7 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
         for (int jj = 0; jj < 2; ++jj) R[it][jj] = mfma_f16(Ap.hi, Bt[jj].hi, R[it][jj]);
       }
     }
+    DEMO_PHASE(1);
     wg_lds_barrier();   // every read of S is done: the R_ab replace it
     {
       float* wq = tiles + quad * Q128_TILE_FLOATS;
@@ -1333,6 +1377,7 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
           for (int r = 0; r < 4; ++r) wq[(16 * it + 4 * g + r) * Q128_LDT + 16 * (2 * jh + jj) + c] = R[it][jj][r];
     }
     wg_lds_barrier();
+    DEMO_PHASE(2);
 
     // ---- x <- x - lr (phi(R) + wd x): phi = sgn, or the identity on the aggregate (the quadrants hold R times
     //      2^sh 2^-22 2^(2 kSplitHBasisLog2); `scale` is 1 or 1/W) --------------------------------------------------
@@ -1344,6 +1389,13 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
       const f32x4 q00 = *reinterpret_cast<const f32x4*>(rq), q01 = *reinterpret_cast<const f32x4*>(rq + Q128_TILE_FLOATS);
       const f32x4 q10 = *reinterpret_cast<const f32x4*>(rq + 2 * Q128_TILE_FLOATS);
       const f32x4 q11 = *reinterpret_cast<const f32x4*>(rq + 3 * Q128_TILE_FLOATS);
+      // every element of the quadrants is read here and nowhere else: the reader leaves it zero for the next chunk
+      {
+        float* zq = tiles + ir * Q128_LDT + j0;
+        const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) *reinterpret_cast<f32x4*>(zq + qd * Q128_TILE_FLOATS) = z4;
+      }
       const f32x4 ea = q00 + q01, eb = q00 - q01, oa = q10 + q11, ob = q10 - q11;
       f32x4 rr[4];   // segments (i, j0..), (i, 124 - j0..), (127 - i, j0..), (127 - i, 124 - j0..)
       rr[0] = ea + oa;
@@ -1374,10 +1426,14 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
         }
       }
     }
-    if (nxt >= total) break;
+    DEMO_PHASE(3);
+    if (!has_next) break;
     chunk = nxt;
-    wg_lds_barrier();   // the tiles are zeroed next
+    mask_payload(0);
+    post_wave_max(0);
+    wg_lds_barrier();   // tiles zero, maxima posted
   }
+  DEMO_PHASE_FLUSH(8);
 }
 
 template <bool PBF16, bool STREAM, bool IDENT, bool COUNT = false>
