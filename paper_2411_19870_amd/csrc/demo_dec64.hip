@@ -140,6 +140,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   constexpr bool UNITS = MODE >= 3 || MODE == 0;   // unit 64 j + lane of the chunk's pairs, VW pairs per unit
   constexpr bool STREAM = MODE == 5;        // more pairs than the registers hold: rounds of 2048
   const int k = WIDE ? 32 : args.k, W = args.W;
+  [[maybe_unused]] const float m1h = opaque_minus_one();
 
   for (int e = tid; e < G_FLOATS / 4; e += D64_THREADS)
     reinterpret_cast<float4*>(lds)[e] = reinterpret_cast<const float4*>(tables + (DENSE ? 0 : D64_G))[e];
@@ -451,7 +452,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
             const float4 a0 = *reinterpret_cast<const float4*>(arow);
             const float4 a1 = *reinterpret_cast<const float4*>(arow + 16);
             constexpr float sc = 0x1p-22f;
-            A[uu] = split8h((float)__float_as_int(a0.x) * sc, (float)__float_as_int(a0.y) * sc, (float)__float_as_int(a0.z) * sc,
+            A[uu] = split8h(m1h, (float)__float_as_int(a0.x) * sc, (float)__float_as_int(a0.y) * sc, (float)__float_as_int(a0.z) * sc,
                             (float)__float_as_int(a0.w) * sc, (float)__float_as_int(a1.x) * sc, (float)__float_as_int(a1.y) * sc,
                             (float)__float_as_int(a1.z) * sc, (float)__float_as_int(a1.w) * sc);
           }
@@ -470,7 +471,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
         SplitH8 Bt[4];
 #pragma unroll
         for (int jt = 0; jt < 4; ++jt)
-          Bt[jt] = split8h(Y[0][jt][0], Y[0][jt][1], Y[0][jt][2], Y[0][jt][3], Y[1][jt][0], Y[1][jt][1], Y[1][jt][2], Y[1][jt][3]);
+          Bt[jt] = split8h(m1h, Y[0][jt][0], Y[0][jt][1], Y[0][jt][2], Y[0][jt][3], Y[1][jt][0], Y[1][jt][1], Y[1][jt][2], Y[1][jt][3]);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const SplitH8 Ap = load_split8h(sG + (2 * it + hp) * kSplitHFragFloats, lane);

@@ -306,19 +306,28 @@ struct SplitH8 {
   u32x4 hi, lo;
 };
 constexpr int kSplitHBasisLog2 = 4;
-__device__ __forceinline__ void split_pair_h(float x0, float x1, uint32_t& h, uint32_t& l) {
+// -1.0 in a scalar register that the compiler cannot see through: with it the remainder x - hi is written as
+// fma(hi, -1, x), which the mixed-precision v_fma_mix_f32 takes straight from the packed float16 (one instruction
+// instead of a conversion and a subtraction; the result is the same exact difference).  Formed once per kernel.
+__device__ __forceinline__ float opaque_minus_one() {
+  float m1;
+  asm volatile("s_mov_b32 %0, 0xbf800000" : "=s"(m1));
+  return m1;
+}
+__device__ __forceinline__ void split_pair_h(float x0, float x1, float m1, uint32_t& h, uint32_t& l) {
   const h16x2 hh = __builtin_convertvector((f32x2){x0, x1}, h16x2);
-  const float r0 = x0 - (float)hh[0], r1 = x1 - (float)hh[1];
+  const float r0 = __builtin_fmaf((float)hh[0], m1, x0), r1 = __builtin_fmaf((float)hh[1], m1, x1);
   const h16x2 ll = __builtin_convertvector((f32x2){r0, r1}, h16x2);
   h = __builtin_bit_cast(uint32_t, hh);
   l = __builtin_bit_cast(uint32_t, ll);
 }
-__device__ __forceinline__ SplitH8 split8h(float x0, float x1, float x2, float x3, float x4, float x5, float x6, float x7) {
+// `m1` = opaque_minus_one()
+__device__ __forceinline__ SplitH8 split8h(float m1, float x0, float x1, float x2, float x3, float x4, float x5, float x6, float x7) {
   uint32_t h[4], l[4];
-  split_pair_h(x0, x1, h[0], l[0]);
-  split_pair_h(x2, x3, h[1], l[1]);
-  split_pair_h(x4, x5, h[2], l[2]);
-  split_pair_h(x6, x7, h[3], l[3]);
+  split_pair_h(x0, x1, m1, h[0], l[0]);
+  split_pair_h(x2, x3, m1, h[1], l[1]);
+  split_pair_h(x4, x5, m1, h[2], l[2]);
+  split_pair_h(x6, x7, m1, h[3], l[3]);
   return SplitH8{(u32x4){h[0], h[1], h[2], h[3]}, (u32x4){l[0], l[1], l[2], l[3]}};
 }
 __device__ __forceinline__ f32x4 mfma_f16(u32x4 a, u32x4 b, f32x4 c) {

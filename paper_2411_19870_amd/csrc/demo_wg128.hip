@@ -534,6 +534,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
   int chunk = blockIdx.x;
   if (chunk >= total) return;
 
+  const float m1h = opaque_minus_one();
   for (int e = tid; e < E128_TABLE_FLOATS / 4; e += E128_THREADS)
     reinterpret_cast<f32x4*>(lds)[e] = gload_f4(tables + 4 * e);
   for (int e = tid; e < 128 * 16; e += E128_THREADS) {
@@ -717,7 +718,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
             const float* arow = &tq[(16 * (2 * hp + uu) + c) * E128_LDT + 4 * g + 32 * h];
             const float4 a0 = *reinterpret_cast<const float4*>(arow);
             const float4 a1 = *reinterpret_cast<const float4*>(arow + 16);
-            A[uu] = split8h(a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w);
+            A[uu] = split8h(m1h, a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w);
           }
 #pragma unroll
           for (int jj = 0; jj < 2; ++jj) {
@@ -734,7 +735,7 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
         SplitH8 Bt[2];
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
-          Bt[jj] = split8h(Z[0][jj][0], Z[0][jj][1], Z[0][jj][2], Z[0][jj][3], Z[1][jj][0], Z[1][jj][1], Z[1][jj][2], Z[1][jj][3]);
+          Bt[jj] = split8h(m1h, Z[0][jj][0], Z[0][jj][1], Z[0][jj][2], Z[0][jj][3], Z[1][jj][0], Z[1][jj][1], Z[1][jj][2], Z[1][jj][3]);
 #pragma unroll
         for (int ut = 0; ut < 4; ++ut) {
           const SplitH8 Ap = load_split8h(TA + (2 * ut + hp) * kSplitHFragFloats, lanev);
@@ -1062,6 +1063,7 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
   int chunk = blockIdx.x;
   if (chunk >= total) return;
 
+  const float m1h = opaque_minus_one();
   for (int e = tid; e < Q128_TABLE_FLOATS / 4; e += Q128_THREADS)
     reinterpret_cast<f32x4*>(lds)[e] = gload_f4(tables + 4 * e);
 
@@ -1334,7 +1336,7 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
           const float4 a0 = *reinterpret_cast<const float4*>(arow);
           const float4 a1 = *reinterpret_cast<const float4*>(arow + 16);
           constexpr float sc = 0x1p-22f;
-          A[uu] = split8h((float)__float_as_int(a0.x) * sc, (float)__float_as_int(a0.y) * sc, (float)__float_as_int(a0.z) * sc,
+          A[uu] = split8h(m1h, (float)__float_as_int(a0.x) * sc, (float)__float_as_int(a0.y) * sc, (float)__float_as_int(a0.z) * sc,
                           (float)__float_as_int(a0.w) * sc, (float)__float_as_int(a1.x) * sc, (float)__float_as_int(a1.y) * sc,
                           (float)__float_as_int(a1.z) * sc, (float)__float_as_int(a1.w) * sc);
         }
@@ -1353,7 +1355,7 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
       SplitH8 Bt[2];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj)
-        Bt[jj] = split8h(Y[0][jj][0], Y[0][jj][1], Y[0][jj][2], Y[0][jj][3], Y[1][jj][0], Y[1][jj][1], Y[1][jj][2], Y[1][jj][3]);
+        Bt[jj] = split8h(m1h, Y[0][jj][0], Y[0][jj][1], Y[0][jj][2], Y[0][jj][3], Y[1][jj][0], Y[1][jj][1], Y[1][jj][2], Y[1][jj][3]);
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
         const SplitH8 Ap = load_split8h(TA + (2 * it + hp) * kSplitHFragFloats, lane);
