@@ -160,8 +160,8 @@ inline bool fast128_decode_supports(int W, int k, bool payload_aligned16) {
   if ((int64_t)W * k <= kFast128MaxPairs) return true;
   return payload_aligned16 && k % 4 == 0 && (int64_t)W * k <= 65536;
 }
-hipError_t launch_decode2d_wg128(const TableView& tv, const float* tables, const DecodeArgs& a, bool param_bf16,
-                                 int num_cus, hipStream_t stream);
+hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const float* tables, const DecodeArgs& a,
+                                 bool param_bf16, int num_cus, hipStream_t stream);
 
 // ... and streams larger payloads (k a multiple of 4, 16-byte aligned arrays, at most 65536 pairs per chunk).
 inline bool fast64_decode_supports(int W, int k, bool payload_aligned16) {

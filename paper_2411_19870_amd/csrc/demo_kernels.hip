@@ -1200,7 +1200,7 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
   if (variant >= 1 && s == 128 && a.mirror != 0 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast128MaxPairs) &&
       fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 && bt.dec128 != nullptr &&
       (pmix == 1u || pmix == 2u))
-    return launch_decode2d_wg128(tv, bt.dec128, a, pmix == 1u, num_cus, stream);
+    return launch_decode2d_wg128(tv, bt.basis, bt.dec128, a, pmix == 1u, num_cus, stream);
   const float* basis = bt.basis;
   switch (s) {
     case 32: return launch_dec2d_generic<32>(tv, basis, a, num_cus, stream);

@@ -1438,6 +1438,225 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
   DEMO_PHASE_FLUSH(8);
 }
 
+// ---------------------------------------------------------------------------
+// Few pairs per chunk (W k <= 64, e.g. a worker decoding its own payload): no coefficient tile and no products.
+// R = sum_p val_p P[u_p]^T P[v_p] is accumulated per parity class by float32 MFMA chains whose operands are gathered
+// rows of P, exactly as the encode kernel reconstructs its selection: wavefront 0 files the pairs by class
+// 2 (u % 2) + v % 2 in the order of arrival (a deterministic order of summation; pairs of different workers that name
+// the same coefficient simply add up), eight wavefronts accumulate the four class sums on the quadrant i, j < 64, and
+// the epilogue of the tile kernel above unfolds them.  Sum and mean only (the count-normalised aggregate takes the
+// tile kernel).
+// ---------------------------------------------------------------------------
+namespace {
+constexpr int S128_THREADS = 512;
+constexpr int S128_LDS_BYTES = 4 * (W128_P_FLOATS + Q128_TILES_FLOATS + 16) + 8 * (4 * W128_SEL);
+}  // namespace
+
+template <bool PBF16, bool IDENT>
+__global__ __launch_bounds__(S128_THREADS) void decode2d_sparse128(TableView tv, const float* __restrict__ basis,
+                                                                    DecodeArgs args) {
+  extern __shared__ float lds[];
+  float* sP = lds;
+  float* tiles = sP + W128_P_FLOATS;
+  int* ctl = reinterpret_cast<int*>(tiles + Q128_TILES_FLOATS);       // [0..3] class counts
+  uint2* sel = reinterpret_cast<uint2*>(ctl + 16);                    // [4][SEL] {basis row offsets, value bits}
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int k = args.k, W = args.W;
+  const int npairs = W * k;                                           // <= 64: one pair per lane of wavefront 0
+  const int total = tv.total_chunks;
+  int chunk = blockIdx.x;
+  if (chunk >= total) return;
+
+  for (int e = tid; e < 128 * 16; e += S128_THREADS) {
+    const int u = e >> 4, c4 = (e & 15) * 4;
+    *reinterpret_cast<f32x4*>(&sP[pos3((uint32_t)u) * W128_LDP + c4]) = gload_f4(basis + u * 128 + c4);
+  }
+  if (tid < 4 * W128_SEL) sel[tid] = make_uint2(0u, 0u);
+
+  // pair `tid` of a chunk: worker tid / k, position tid % k
+  const int pw = tid / k, pt = tid - pw * k;
+  int32_t pi = -1;
+  float pv = 0.f;
+  auto load_pair = [&](const TensorDev& dd, int cc) {
+    if (tid < npairs) {
+      const int64_t off = ((int64_t)pw * dd.nchunks + cc) * k + pt;
+      pi = payload_load<true>(as_global(dd.idx) + off);
+      pv = payload_load<true>(as_global(dd.val) + off);
+    }
+  };
+  int t = find_tensor_uniform(tv, chunk);
+  int t_first = uniform_prefix(tv, t), t_next = uniform_prefix(tv, t + 1);
+  TensorDev d = load_desc_uniform(tv, t);
+  load_pair(d, chunk - t_first);
+  asm volatile("" : "+v"(pi), "+v"(pv));   // waited for outside the loop (see the tile kernel)
+  __syncthreads();
+
+  for (;;) {
+    const int cc = chunk - t_first;
+    const uint32_t ucols = (uint32_t)d.cols;
+    const int64_t origin = (int64_t)(cc / d.cchunks) * 128 * d.cols + (int64_t)(cc % d.cchunks) * 128;
+    const __amdgpu_buffer_rsrc_t xres = PBF16 ? make_rsrc(static_cast<const uint16_t*>(d.param) + origin)
+                                              : make_rsrc(static_cast<const float*>(d.param) + origin);
+    // ---- the parameters of this chunk: requested now, used in the epilogue -------------------------------------
+    using XT = typename std::conditional<PBF16, u32x2, f32x4>::type;
+    constexpr uint32_t XB = PBF16 ? 2u : 4u;
+    XT xin[2][4];
+    uint32_t xo[2][4];
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const uint32_t pb = (uint32_t)tid + S128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
+      xo[p][0] = (ir * ucols + j0) * XB;
+      xo[p][1] = (ir * ucols + 124u - j0) * XB;
+      xo[p][2] = ((127u - ir) * ucols + j0) * XB;
+      xo[p][3] = ((127u - ir) * ucols + 124u - j0) * XB;
+#pragma unroll
+      for (int sg = 0; sg < 4; ++sg) {
+        if constexpr (PBF16) xin[p][sg] = bload_u2(xres, xo[p][sg], 0u);
+        else xin[p][sg] = bload_f4(xres, xo[p][sg], 0u);
+      }
+    }
+    // ---- wavefront 0 files the pairs (the lists are zero: cleared before the loop / by the epilogue before) -------
+    if (wave == 0) {
+      const uint32_t fi = (uint32_t)pi;
+      const bool valid = lane < npairs && fi < 16384u;
+      const int cls = (int)(((fi >> 6) & 2u) | (fi & 1u));
+      int rcls = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint64_t m = __ballot(valid && cls == c);
+        if (cls == c) rcls = lanes_below(m);
+        if (lane == 0) ctl[c] = __popcll(m);
+      }
+      if (valid) {
+        const uint32_t offs = (uint32_t)(pos3(fi >> 7) * (W128_LDP * 4)) | ((uint32_t)(pos3(fi & 127u) * (W128_LDP * 4)) << 16);
+        sel[cls * W128_SEL + rcls] = make_uint2(offs, __float_as_uint(pv));
+      }
+    }
+    // ---- the pair of the next chunk ------------------------------------------------------------------------------
+    const int nxt = chunk + (int)gridDim.x;
+    const bool has_next = nxt < total;
+    if (has_next) {
+      while (nxt >= t_next) {
+        ++t;
+        t_first = t_next;
+        t_next = uniform_prefix(tv, t + 1);
+        d = load_desc_uniform(tv, t);
+      }
+      load_pair(d, nxt - t_first);
+    }
+    wg_lds_barrier();
+
+    // ---- class sums on the quadrant i, j < 64: row tile mt, column tiles nt0 and nt0 + 1 ---------------------------
+    {
+      const int mt = wave >> 1, nt0 = 2 * (wave & 1);
+      const int lq = lane >> 4, l16 = lane & 15;
+      f32x4 rc[2][4];
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) rc[n][c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      // the lists are zero-padded, so every class runs to the length of the longest
+      const int4 nc = *reinterpret_cast<const int4*>(&ctl[0]);
+      const int nmax = __builtin_amdgcn_readfirstlane(max(max(nc.x, nc.y), max(nc.z, nc.w)));
+      const float* pa = sP + 16 * mt + l16;
+      const float* pb = sP + 16 * nt0 + l16;
+      uint2 en[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + lq];
+      for (int st = 0; 4 * st < nmax; ++st) {
+        uint2 e[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) e[c] = en[c];
+        float a[4], b0[4], b1[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          a[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pa) + (e[c].x & 0xffffu));
+          b0[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pb) + (e[c].x >> 16));
+          b1[c] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(pb + 16) + (e[c].x >> 16));
+        }
+        // entries of the next step (the lists are 68 long and zero past their ends: step 16 reads padding)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + 4 * (st + 1) + lq];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float va = __uint_as_float(e[c].y) * a[c];
+          rc[0][c] = mfma4(va, b0[c], rc[0][c]);
+          rc[1][c] = mfma4(va, b1[c], rc[1][c]);
+        }
+      }
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            tiles[c * Q128_TILE_FLOATS + (16 * mt + 4 * lq + r) * Q128_LDT + 16 * (nt0 + n) + l16] = rc[n][c][r];
+    }
+    wg_lds_barrier();
+    // the lists are read: cleared for the next chunk (entries in use only)
+    if (tid < 4 * W128_SEL) sel[tid] = make_uint2(0u, 0u);
+
+    // ---- x <- x - lr (phi(R) + wd x) ----------------------------------------------------------------------------------
+    const float factor = IDENT ? args.scale : 0.f;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      const uint32_t pb = (uint32_t)tid + S128_THREADS * p, ir = pb >> 4, j0 = (pb & 15u) * 4u;
+      const float* rq = tiles + ir * Q128_LDT + j0;
+      const f32x4 q00 = *reinterpret_cast<const f32x4*>(rq), q01 = *reinterpret_cast<const f32x4*>(rq + Q128_TILE_FLOATS);
+      const f32x4 q10 = *reinterpret_cast<const f32x4*>(rq + 2 * Q128_TILE_FLOATS);
+      const f32x4 q11 = *reinterpret_cast<const f32x4*>(rq + 3 * Q128_TILE_FLOATS);
+      const f32x4 ea = q00 + q01, eb = q00 - q01, oa = q10 + q11, ob = q10 - q11;
+      f32x4 rr[4];   // segments (i, j0..), (i, 124 - j0..), (127 - i, j0..), (127 - i, 124 - j0..)
+      rr[0] = ea + oa;
+      rr[2] = ea - oa;
+      const f32x4 m1 = eb + ob, m3 = eb - ob;   // columns 127 - j0 - e: reversed within the segment
+      rr[1] = (f32x4){m1[3], m1[2], m1[1], m1[0]};
+      rr[3] = (f32x4){m3[3], m3[2], m3[1], m3[0]};
+#pragma unroll
+      for (int sg = 0; sg < 4; ++sg) {
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float x;
+          if constexpr (PBF16) {
+            const uint32_t raw = xin[p][sg][e >> 1];
+            x = __uint_as_float((e & 1) ? (raw & 0xffff0000u) : (raw << 16));
+          } else {
+            x = xin[p][sg][e];
+          }
+          o[e] = sign_update(x, IDENT ? rr[sg][e] * factor : sgnf(rr[sg][e]), args.lr, args.weight_decay);
+        }
+        if constexpr (PBF16) {
+          const u32x2 pk = {pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3])};
+          bstore_u2(xres, xo[p][sg], 0u, pk);
+        } else {
+          const f32x4 ov = {o[0], o[1], o[2], o[3]};
+          bstore_f4(xres, xo[p][sg], 0u, ov);
+        }
+      }
+    }
+    if (!has_next) break;
+    chunk = nxt;
+    wg_lds_barrier();   // lists cleared, quadrants read
+  }
+}
+
+template <bool PBF16, bool IDENT>
+static hipError_t launch_dec_sparse128(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
+                                       hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode2d_sparse128<PBF16, IDENT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, S128_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((decode2d_sparse128<PBF16, IDENT>), dim3((unsigned)grid), dim3(S128_THREADS), S128_LDS_BYTES, stream,
+                     tv, basis, a);
+  return hipGetLastError();
+}
+
 template <bool PBF16, bool STREAM, bool IDENT, bool COUNT = false>
 static hipError_t launch_dec_wg128_phi(const TableView& tv, const float* basis, const DecodeArgs& a, int64_t grid,
                                        hipStream_t stream) {
@@ -1464,17 +1683,24 @@ static hipError_t launch_dec_wg128(const TableView& tv, const float* basis, cons
                     : launch_dec_wg128_phi<PBF16, STREAM, false>(tv, basis, a, grid, stream);
 }
 
-hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const DecodeArgs& a, bool param_bf16,
-                                 int num_cus, hipStream_t stream) {
-  if (!fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0)) return hipErrorInvalidValue;
+hipError_t launch_decode2d_wg128(const TableView& tv, const float* basis, const float* tables, const DecodeArgs& a,
+                                 bool param_bf16, int num_cus, hipStream_t stream) {
+  if (!fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) || tables == nullptr) return hipErrorInvalidValue;
   if (a.agg == 2 && (int64_t)a.W * a.k > kFast128MaxPairs) return hipErrorInvalidValue;   // counted from registers
   int64_t grid = num_cus;
   if (grid > tv.total_chunks) grid = tv.total_chunks;
+  if ((int64_t)a.W * a.k <= 64 && a.agg != 2) {
+    if (a.phi != 0)
+      return param_bf16 ? launch_dec_sparse128<true, true>(tv, basis, a, grid, stream)
+                        : launch_dec_sparse128<false, true>(tv, basis, a, grid, stream);
+    return param_bf16 ? launch_dec_sparse128<true, false>(tv, basis, a, grid, stream)
+                      : launch_dec_sparse128<false, false>(tv, basis, a, grid, stream);
+  }
   if ((int64_t)a.W * a.k > kFast128MaxPairs)
-    return param_bf16 ? launch_dec_wg128<true, true>(tv, basis, a, grid, stream)
-                      : launch_dec_wg128<false, true>(tv, basis, a, grid, stream);
-  return param_bf16 ? launch_dec_wg128<true, false>(tv, basis, a, grid, stream)
-                    : launch_dec_wg128<false, false>(tv, basis, a, grid, stream);
+    return param_bf16 ? launch_dec_wg128<true, true>(tv, tables, a, grid, stream)
+                      : launch_dec_wg128<false, true>(tv, tables, a, grid, stream);
+  return param_bf16 ? launch_dec_wg128<true, false>(tv, tables, a, grid, stream)
+                    : launch_dec_wg128<false, false>(tv, tables, a, grid, stream);
 }
 
 }  // namespace demo
