@@ -33,6 +33,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
+MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix, published
 S, K, W = 64, 32, 64
 BETA, LR, WD = 0.999, 1e-3, 0.0
 CPU_SAMPLE_FRACTION = 0.30
@@ -63,30 +64,59 @@ def source_hash():
     return h.hexdigest()[:16]
 
 
-def mfma_flops_per_launch(kernel, s, k, W, nchunks2, idx_tensors):
-    """fp32 MFMA flops one launch of the order-2 kernel issues (v_mfma_f32_16x16x4_f32 = 2048 flop), from the
-    kernels' own instruction counts: products with the mirror folds, and for encode the reconstruction chain,
-    whose length depends on how many selected coefficients fall into each class of row frequency."""
+F32_MFMA_FLOP = 2048.0      # v_mfma_f32_16x16x4_f32
+HALF_MFMA_FLOP = 16384.0    # v_mfma_f32_16x16x32_f16 / _bf16
+
+
+def mfma_work_per_launch(kernel, s, k, W, nchunks2, idx_tensors, projection="dct", variant=1):
+    """Matrix-core work one launch of the order-2 kernel issues, by instruction type, from the kernels' own instruction
+    counts: {"f32": flops of v_mfma_f32_16x16x4_f32, "f16": ... of v_mfma_f32_16x16x32_f16 (float32 operands split
+    into two float16 parts, three instructions per 16 x 16 tile and 32 contraction indices), "bf16": ... of
+    v_mfma_f32_16x16x32_bf16 (three bfloat16 parts, six instructions)}; None where the count depends on the data in a
+    way this function does not follow (the few-pairs decode kernels) or the generic kernels run.  For encode the
+    float32 reconstruction chain depends on how many selected coefficients fall into each class."""
     import torch
+    if variant == 0:
+        return None
+    dct = projection == "dct"
+    if not dct and s != 64:
+        return None                                                        # generic kernels
     if kernel == "dec2d":
-        per_chunk = {64: 192.0, 32: 32.0, 128: 1536.0}[s]                  # both products, 3/8 (s=32: 1/2) of dense
-        if s == 64 and W * k <= 64:
-            per_chunk = None                                               # the few-pairs kernel: data dependent
-        return None if per_chunk is None else per_chunk * 2048.0 * nchunks2
-    products = {64: 192.0, 32: 32.0, 128: 1536.0}[s]
-    recon = 0.0
-    if s == 64:
-        # classes of u: 0 mod 4, 2 mod 4 (4 MFMAs per step of four coefficients), odd (8 per step)
+        if s == 32:
+            return {"f32": 32.0 * F32_MFMA_FLOP * nchunks2}                # both products, 1/2 of dense, per chunk
+        if W * k <= 64 and dct:
+            return None                                                    # the few-pairs kernels: data dependent
+        if s == 64:
+            if W * k <= 2048 and variant == 1:
+                return {"f16": 192.0 * HALF_MFMA_FLOP * nchunks2}          # full products, 96 instructions each
+            return {"f32": 192.0 * F32_MFMA_FLOP * nchunks2} if dct else None   # mirror folds: 3/8 of dense
+        return {"f16": 768.0 * HALF_MFMA_FLOP * nchunks2}                  # s = 128: four 64^3 quadrant products, twice
+    if s == 64 and dct:
+        # products with the mirror folds; reconstruction by classes of u: 0 mod 4, 2 mod 4 (4 MFMAs per step of four
+        # coefficients), odd (8 per step)
+        recon = 0.0
         for idx in idx_tensors:
             u = (idx[0].to(torch.int64) >> 6)
             c0 = ((u & 3) == 0).sum(1)
             c1 = ((u & 3) == 2).sum(1)
             c2 = ((u & 1) == 1).sum(1)
             recon += float((4 * ((c0 + 3) // 4) + 4 * ((c1 + 3) // 4) + 8 * ((c2 + 3) // 4)).sum())
-        return (products * nchunks2 + recon) * 2048.0
+        return {"f32": (192.0 * nchunks2 + recon) * F32_MFMA_FLOP}
+    if s == 64:
+        # full products of operands split into three bfloat16 parts, 192 instructions each; reconstruction in float32,
+        # 16 per four kept coefficients
+        return {"bf16": 2 * 192.0 * HALF_MFMA_FLOP * nchunks2, "f32": 16.0 * math.ceil(k / 4.0) * F32_MFMA_FLOP * nchunks2}
     if s == 32:
-        return (products + 4.0 * math.ceil(k / 4.0)) * 2048.0 * nchunks2   # four MFMAs per step of four coefficients
-    return (products + 16.0 * 12.0) * 2048.0 * nchunks2                    # s = 128: about 12 per wavefront
+        return {"f32": (32.0 + 4.0 * math.ceil(k / 4.0)) * F32_MFMA_FLOP * nchunks2}   # four MFMAs per step of four coefficients
+    # s = 128: four quadrant products, twice; reconstruction: 8 wavefronts x 2 tiles x 4 classes per step of four
+    # coefficients of the fullest class (u % 2, v % 2)
+    recon = 0.0
+    for idx in idx_tensors:
+        i64 = idx[0].to(torch.int64)
+        cls = ((i64 >> 6) & 2) | (i64 & 1)
+        nmax = torch.stack([(cls == c).sum(1) for c in range(4)]).max(0).values
+        recon += float((64 * ((nmax + 3) // 4)).sum())
+    return {"f16": 768.0 * HALF_MFMA_FLOP * nchunks2, "f32": recon * F32_MFMA_FLOP}
 
 
 def _cpu_worker_init():
@@ -256,32 +286,31 @@ def main():
     dom = "enc2d" if (kms["enc2d"] or 0) >= (kms["dec2d"] or 0) else "dec2d"
     achieved = ab[dom] / (kms[dom] * 1e-3) / 1e9
     hbm_frac = achieved / HBM_PEAK_GBS
-    mfma_flops = mfma_flops_per_launch(dom, S, K, W, nchunks2, [t.idx for t, sp in zip(tensors, specs) if sp.cols]) \
-        if a.variant == 1 and a.projection == "dct" else None
-    bf16_flops = None
-    if a.variant == 1 and a.projection != "dct" and S == 64 and K <= 64 and (dom == "enc2d" or W * K <= 2048):
-        # full products of float32 operands split into three bfloat16 parts: 6 v_mfma_f32_16x16x32_bf16 (16384 flop)
-        # per 16 x 16 tile and 32 contraction indices, 192 per product; reconstruction in float32, 16 per four kept
-        # coefficients
-        bf16_flops = 2 * 192.0 * 16384.0 * nchunks2
-        mfma_flops = (16.0 * math.ceil(K / 4.0) if dom == "enc2d" else 0.0) * 2048.0 * nchunks2
-    if bf16_flops:
-        # two instruction types: the fraction is the time the matrix pipe needs at each type's peak over the launch time
-        pipe_s = bf16_flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) + mfma_flops / (MFMA_F32_PEAK_TFLOPS * 1e12)
+    work = mfma_work_per_launch(dom, S, K, W, nchunks2, [t.idx for t, sp in zip(tensors, specs) if sp.cols],
+                                a.projection, a.variant)
+    peaks = {"f32": MFMA_F32_PEAK_TFLOPS, "f16": MFMA_F16_PEAK_TFLOPS, "bf16": MFMA_BF16_PEAK_TFLOPS}
+    if work:
+        # the fraction is the time the matrix pipe needs at each instruction type's peak over the launch time
+        pipe_s = sum(f / (peaks[ty] * 1e12) for ty, f in work.items())
+        total_flops = sum(work.values())
         mfma_frac = pipe_s / (kms[dom] * 1e-3)
-        mfma_tflops = (bf16_flops + mfma_flops) / (kms[dom] * 1e-3) / 1e12
-        mfma_peak = (bf16_flops + mfma_flops) / pipe_s / 1e12
+        mfma_tflops = total_flops / (kms[dom] * 1e-3) / 1e12
+        mfma_peak = total_flops / pipe_s / 1e12
     else:
-        mfma_tflops = mfma_flops / (kms[dom] * 1e-3) / 1e12 if mfma_flops else None
-        mfma_frac = mfma_tflops / MFMA_F32_PEAK_TFLOPS if mfma_tflops else None
+        mfma_tflops = mfma_frac = None
         mfma_peak = MFMA_F32_PEAK_TFLOPS
+    other = "dec2d" if dom == "enc2d" else "enc2d"
+    work_other = mfma_work_per_launch(other, S, K, W, nchunks2, [], a.projection, a.variant) if other == "dec2d" else None
+    split_types = sorted(ty for wk in (work, work_other) if wk for ty in wk if ty != "f32")
     bound = "mfma" if (mfma_frac or 0.0) > hbm_frac else "hbm"
     roof = {"bound": bound, "kernel": dom, "avg_launch_ms": kms[dom],
             "hbm": {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac,
                     "algorithmic_bytes_per_launch": ab[dom]},
             "mfma": {"achieved": mfma_tflops, "peak": mfma_peak, "unit": "TFLOP/s", "frac": mfma_frac,
-                     "issued_fp32_mfma_flops_per_launch": mfma_flops, "issued_bf16_mfma_flops_per_launch": bf16_flops,
-                     "peak_fp32": MFMA_F32_PEAK_TFLOPS, "peak_bf16": MFMA_BF16_PEAK_TFLOPS},
+                     "issued_fp32_mfma_flops_per_launch": (work or {}).get("f32"),
+                     "issued_f16_mfma_flops_per_launch": (work or {}).get("f16"),
+                     "issued_bf16_mfma_flops_per_launch": (work or {}).get("bf16"),
+                     "peak_fp32": MFMA_F32_PEAK_TFLOPS, "peak_f16": MFMA_F16_PEAK_TFLOPS, "peak_bf16": MFMA_BF16_PEAK_TFLOPS},
             "traffic": None, "traffic_source": None}
     roof.update({"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac} if bound == "hbm" else
                 {"achieved": mfma_tflops, "peak": mfma_peak, "unit": "TFLOP/s", "frac": mfma_frac})
@@ -293,7 +322,8 @@ def main():
         "params_per_s": nparams / (ms_step * 1e-3),
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if not bf16_flops else "f32 (products on the bf16 matrix pipe, operands split exactly into three bf16 parts)",
+        "dtype": "f32" if not split_types else "f32 (products of float32 operands split into parts on the "
+                 + " and ".join(split_types) + " matrix pipe, float32 accumulation)",
         "data": "synthetic",
         "config": {"workload": f"{a.workload}-like tensor set: encode (grad {'bf16' if gb == 2 else 'f32'}, momentum f32) "
                                f"+ decode of W={W} payloads (param {'bf16' if gb == 2 else 'f32'})",

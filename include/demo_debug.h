@@ -33,7 +33,10 @@ int demo_copy_probe(demo_ctx* ctx, void* dst, const void* src, int64_t nbytes, v
 
 /* Kernel family used by later calls: 1 (default) = the fastest kernels available
  * for the chunk size, 0 = the generic LDS-staged kernels only (kept selectable so
- * that the two families can be checked against each other).  */
+ * that the two families can be checked against each other), 2 = as 1, but the s = 64
+ * decode of the DCT stays on its mirror-folded float32 instances where the full-product
+ * instance on the float16 matrix pipe would take over (64 < W k <= 2048, sum or mean),
+ * so that the two can be timed and checked against each other.  */
 int demo_set_variant(demo_ctx* ctx, int variant);
 
 /* Memory-system probe with the launch shape of the wavefront kernels (one workgroup of eight wavefronts

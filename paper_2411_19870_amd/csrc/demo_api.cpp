@@ -27,6 +27,7 @@ struct BasisTable {
   float* dev = nullptr;      // P, s x s
   float* enc64 = nullptr;    // tables of the s = 64 wavefront-per-chunk kernels
   float* dec64 = nullptr;
+  float* dec64h = nullptr;   // DCT fragments for the full-product s = 64 decode kernel (float16 matrix pipe)
   float* enc32 = nullptr;    // dense-basis tile tables for s = 32
   float* dec32 = nullptr;    // fragment table of the s = 32 tile decode kernel
   float* dec128 = nullptr;   // fragment tables of the s = 128 kernels
@@ -169,7 +170,7 @@ int upload(demo_ctx* ctx, const std::vector<float>& host, float** dev) {
 // Host copies of the tables of one chunk size: the orthonormal DCT-II matrix P[u][n] = c_u cos(pi (2n+1) u / (2s))
 // evaluated in double precision and rounded once to float32, and the fragment tables the wavefront kernels read.
 struct HostBasis {
-  std::vector<float> P, enc64, dec64, enc32, dec32, dec128, enc128;
+  std::vector<float> P, enc64, dec64, dec64h, enc32, dec32, dec128, enc128;
 };
 
 void build_host_basis(int s, HostBasis* hb) {
@@ -185,6 +186,8 @@ void build_host_basis(int s, HostBasis* hb) {
     hb->dec64.resize(demo::kDec64TableFloats);
     demo::build_enc64_tables(P.data(), hb->enc64.data());
     demo::build_dec64_tables(P.data(), hb->dec64.data());
+    hb->dec64h.resize(demo::kDec64DenseTableFloats);
+    demo::build_dec64_dense_tables(P.data(), hb->dec64h.data());
   }
   if (s == 32) {
     // 64 x 64 block-diagonal basis diag(P32, P32): a wavefront tile holds 2 x 2 chunks
@@ -212,7 +215,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
       // kernels that read the matrix itself
       *out = b.use_custom ? demo::BasisTables{b.custom, nullptr, nullptr, nullptr, nullptr, false, b.custom_enc64, b.custom_dec64}
                           : demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
-      if (!b.use_custom) { out->dec128 = b.dec128; out->enc128 = b.enc128; }
+      if (!b.use_custom) { out->dec128 = b.dec128; out->enc128 = b.enc128; out->dec64g = b.dec64h; }
       return DEMO_OK;
     }
   HostBasis hb;
@@ -225,6 +228,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
     (void)hipFree(b.dev);
     if (b.enc64) (void)hipFree(b.enc64);
     if (b.dec64) (void)hipFree(b.dec64);
+    if (b.dec64h) (void)hipFree(b.dec64h);
     if (b.enc32) (void)hipFree(b.enc32);
     if (b.dec32) (void)hipFree(b.dec32);
     if (b.dec128) (void)hipFree(b.dec128);
@@ -232,6 +236,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   };
   if (!hb.enc64.empty() && (rc = upload(ctx, hb.enc64, &b.enc64)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec64.empty() && (rc = upload(ctx, hb.dec64, &b.dec64)) != DEMO_OK) { drop(); return rc; }
+  if (!hb.dec64h.empty() && (rc = upload(ctx, hb.dec64h, &b.dec64h)) != DEMO_OK) { drop(); return rc; }
   if (!hb.enc32.empty() && (rc = upload(ctx, hb.enc32, &b.enc32)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec32.empty() && (rc = upload(ctx, hb.dec32, &b.dec32)) != DEMO_OK) { drop(); return rc; }
   if (!hb.dec128.empty() && (rc = upload(ctx, hb.dec128, &b.dec128)) != DEMO_OK) { drop(); return rc; }
@@ -240,6 +245,7 @@ int get_basis(demo_ctx* ctx, int s, demo::BasisTables* out) {
   *out = demo::BasisTables{b.dev, b.enc64, b.dec64, b.enc32, b.dec32, true};
   out->dec128 = b.dec128;
   out->enc128 = b.enc128;
+  out->dec64g = b.dec64h;
   return DEMO_OK;
 }
 
@@ -581,6 +587,7 @@ int demo_destroy(demo_ctx* ctx) {
       (void)hipFree(b.dev);
       if (b.enc64) (void)hipFree(b.enc64);
       if (b.dec64) (void)hipFree(b.dec64);
+      if (b.dec64h) (void)hipFree(b.dec64h);
       if (b.enc32) (void)hipFree(b.enc32);
       if (b.dec32) (void)hipFree(b.dec32);
       if (b.dec128) (void)hipFree(b.dec128);
@@ -867,7 +874,7 @@ int demo_set_basis(demo_ctx* ctx, int s, int kind, const float* a_host) {
 }
 
 int demo_set_variant(demo_ctx* ctx, int variant) {
-  if (ctx == nullptr || variant < 0 || variant > 1) return DEMO_ERR_ARG;
+  if (ctx == nullptr || variant < 0 || variant > 2) return DEMO_ERR_ARG;
   ctx->variant = variant;
   return DEMO_OK;
 }

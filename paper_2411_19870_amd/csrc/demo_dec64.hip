@@ -129,6 +129,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
   extern __shared__ float lds[];
   const float* sG = lds;
   constexpr int G_FLOATS = d64_table_floats<DENSE>();
+  constexpr bool DENSE_LATE_X = false;   // (the full-product instances once had no registers for the parameters before their products)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 4, c = lane & 15;
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
 #pragma unroll
       for (int q = 0; q < 16; ++q) Xh[q] = bload_u2(xres, ((q & 1) ? vo_dn : vo_up) * 2, (uint32_t)rho_base(q) * ucols * 2);
     };
-    if (PBF16 && !DENSE) fetch_x();
+    if (PBF16 && !DENSE_LATE_X) fetch_x();
     DEMO_PHASE(0);
     mask_payload(0);
 
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
     auto comp = [](const float4& v, int r) { return r == 0 ? v.x : r == 1 ? v.y : r == 2 ? v.z : v.w; };
     if (args.stage != 0) {
       // time attribution: no products, the epilogue reads whatever the tile holds
-      if constexpr (DENSE) {
+      if constexpr (DENSE_LATE_X) {
         if (PBF16) fetch_x();
       }
     } else if constexpr (DENSE) {
@@ -492,7 +493,7 @@ __global__ __launch_bounds__(D64_THREADS) void decode2d_wave64(TableView tv, con
         for (int jt = 0; jt < 4; ++jt)
 #pragma unroll
           for (int r = 0; r < 4; ++r) tile[(16 * it + 4 * g + r) * D64_LDT + 16 * jt + c] = R[it][jt][r];
-      if (PBF16) fetch_x();
+      if (PBF16 && DENSE_LATE_X) fetch_x();
     } else {
     float4 G[6];
 #pragma unroll
@@ -861,14 +862,19 @@ hipError_t launch_decode2d_dense64(const TableView& tv, const float* tables, con
   const int64_t max_grid = ((int64_t)tv.total_chunks + DEMO_RUN - 1) / DEMO_RUN;
   if (grid > max_grid) grid = max_grid;
   const bool vec = payload_aligned16 && a.k % 4 == 0, ident = a.phi != 0;
+  const bool nt = a.k >= 32;   // rows of k pairs shorter than a 128-byte line: plain loads (as in launch_dec_wave64)
   if (param_bf16) {
-    if (vec) return ident ? launch_dec_wave64_phi<true, 3, true, false, true, true>(tv, tables, a, grid, stream)
-                          : launch_dec_wave64_phi<true, 3, false, false, true, true>(tv, tables, a, grid, stream);
+    if (vec && nt) return ident ? launch_dec_wave64_phi<true, 3, true, false, true, true>(tv, tables, a, grid, stream)
+                                : launch_dec_wave64_phi<true, 3, false, false, true, true>(tv, tables, a, grid, stream);
+    if (vec) return ident ? launch_dec_wave64_phi<true, 3, true, false, false, true>(tv, tables, a, grid, stream)
+                          : launch_dec_wave64_phi<true, 3, false, false, false, true>(tv, tables, a, grid, stream);
     return ident ? launch_dec_wave64_phi<true, 0, true, false, true, true>(tv, tables, a, grid, stream)
                  : launch_dec_wave64_phi<true, 0, false, false, true, true>(tv, tables, a, grid, stream);
   }
-  if (vec) return ident ? launch_dec_wave64_phi<false, 3, true, false, true, true>(tv, tables, a, grid, stream)
-                        : launch_dec_wave64_phi<false, 3, false, false, true, true>(tv, tables, a, grid, stream);
+  if (vec && nt) return ident ? launch_dec_wave64_phi<false, 3, true, false, true, true>(tv, tables, a, grid, stream)
+                              : launch_dec_wave64_phi<false, 3, false, false, true, true>(tv, tables, a, grid, stream);
+  if (vec) return ident ? launch_dec_wave64_phi<false, 3, true, false, false, true>(tv, tables, a, grid, stream)
+                        : launch_dec_wave64_phi<false, 3, false, false, false, true>(tv, tables, a, grid, stream);
   return ident ? launch_dec_wave64_phi<false, 0, true, false, true, true>(tv, tables, a, grid, stream)
                : launch_dec_wave64_phi<false, 0, false, false, true, true>(tv, tables, a, grid, stream);
 }

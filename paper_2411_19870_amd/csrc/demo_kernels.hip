@@ -1190,13 +1190,16 @@ hipError_t launch_decode2d(const TableView& tv, const TableView* tiles, const Ba
       fast32_decode_supports(a.W, a.k, (tiles->dtypes & 16u) == 0) && payload_fits32 && bt.dec32 != nullptr &&
       (pmix == 1u || pmix == 2u))
     return launch_decode2d_tile32(*tiles, bt.dec32, a, pmix == 1u, num_cus, stream);
-  if (variant >= 1 && s == 64 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast64CountMaxPairs) &&
+  // The full-product instance on the float16 matrix pipe (any matrix, the DCT included) has overtaken the mirror-folded
+  // float32 instances wherever it applies: more than 64 and at most 2048 pairs per chunk, sum or mean.  The DCT keeps
+  // its own kernels for fewer pairs (no coefficient tile), for streamed payloads and for the count-normalised aggregate.
+  if (variant >= 1 && s == 64 && bt.dec64g != nullptr && dense64_decode_supports(a) && payload_fits32 &&
+      (!bt.dct || (a.W * a.k > 64 && variant != 2)) && (pmix == 1u || pmix == 2u))
+    return launch_decode2d_dense64(tv, bt.dec64g, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
+  if (variant >= 1 && s == 64 && bt.dct && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast64CountMaxPairs) &&
       fast64_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 &&
       bt.dec64 != nullptr && (pmix == 1u || pmix == 2u))
     return launch_decode2d_wave64(tv, bt.dec64, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
-  if (variant >= 1 && s == 64 && !bt.dct && bt.dec64g != nullptr && dense64_decode_supports(a) && payload_fits32 &&
-      (pmix == 1u || pmix == 2u))
-    return launch_decode2d_dense64(tv, bt.dec64g, a, pmix == 1u, (tv.dtypes & 16u) == 0, num_cus, stream);
   if (variant >= 1 && s == 128 && a.mirror != 0 && (decode_is_sign_of_sum(a) || a.W * a.k <= kFast128MaxPairs) &&
       fast128_decode_supports(a.W, a.k, (tv.dtypes & 16u) == 0) && payload_fits32 && bt.dec128 != nullptr &&
       (pmix == 1u || pmix == 2u))

@@ -111,6 +111,7 @@ def test_validation_happens_before_any_launch():
     assert step(_tensor(param=None)) == B.DEMO_ERR_ARG
     assert step(_tensor(grad=None)) == B.DEMO_ERR_ARG
     assert lib.demo_set_variant(h, 5) == B.DEMO_ERR_ARG
+    assert lib.demo_set_variant(h, 2) == B.DEMO_OK and lib.demo_set_variant(h, 1) == B.DEMO_OK
     ms = ctypes.c_float()
     assert lib.demo_last_kernel_ms(h, 0, ctypes.byref(ms)) == B.DEMO_ERR_ARG   # nothing recorded
     assert lib.demo_destroy(h) == B.DEMO_OK

@@ -30,10 +30,31 @@ def test_algorithmic_bytes_per_parameter():
 
 
 def test_mfma_count_of_the_decode_products():
-    # both products of a chunk with the mirror folds: 192 (s = 64), 32 (s = 32, per chunk), 1536 (s = 128)
-    # v_mfma_f32_16x16x4_f32 of 2048 flop each
-    for s, per_chunk in ((64, 192), (32, 32), (128, 1536)):
-        assert bench.mfma_flops_per_launch("dec2d", s, 32, 64 if s != 32 else 16, 1000, []) == per_chunk * 2048.0 * 1000
+    # s = 32: both products of a chunk with the mirror fold, 32 v_mfma_f32_16x16x4_f32 of 2048 flop each
+    assert bench.mfma_work_per_launch("dec2d", 32, 32, 16, 1000, []) == {"f32": 32 * 2048.0 * 1000}
+    # s = 64, 64 < W k <= 2048: two full 64^3 products, 16 tiles x 2 blocks of 32 contraction indices x 3 partial
+    # products = 96 v_mfma_f32_16x16x32_f16 of 16384 flop each; the mirror-folded float32 instances (variant 2, and
+    # the streamed payloads beyond 2048 pairs): 192 v_mfma_f32_16x16x4_f32
+    assert bench.mfma_work_per_launch("dec2d", 64, 32, 64, 1000, []) == {"f16": 192 * 16384.0 * 1000}
+    assert bench.mfma_work_per_launch("dec2d", 64, 32, 64, 1000, [], variant=2) == {"f32": 192 * 2048.0 * 1000}
+    assert bench.mfma_work_per_launch("dec2d", 64, 32, 128, 1000, []) == {"f32": 192 * 2048.0 * 1000}
+    # s = 128: four 64^3 quadrant products, twice: 4 x 2 x 96 float16 instructions
+    assert bench.mfma_work_per_launch("dec2d", 128, 32, 64, 1000, []) == {"f16": 768 * 16384.0 * 1000}
+    # few pairs per chunk: data dependent, not counted; generic kernels: not counted
+    assert bench.mfma_work_per_launch("dec2d", 128, 32, 1, 1000, []) is None
+    assert bench.mfma_work_per_launch("dec2d", 64, 32, 64, 1000, [], variant=0) is None
+
+
+def test_mfma_count_of_the_s128_encode():
+    import torch
+    # two chunks of k = 4: all four coefficients in class (0, 0) -> one step; one per class -> one step; the products
+    # are 768 float16 instructions, a reconstruction step 8 wavefronts x 2 tiles x 4 classes = 64 float32 ones
+    idx = torch.tensor([[[0, 2, 256, 258], [0, 1, 128, 129]]], dtype=torch.int32)
+    w = bench.mfma_work_per_launch("enc2d", 128, 4, 1, 2, [idx])
+    assert w == {"f16": 768 * 16384.0 * 2, "f32": 2 * 64 * 2048.0}
+    # five in one class -> two steps
+    idx = torch.tensor([[[0, 2, 4, 6, 8]]], dtype=torch.int32)
+    assert bench.mfma_work_per_launch("enc2d", 128, 5, 1, 1, [idx])["f32"] == 2 * 64 * 2048.0
 
 
 def test_source_hash_is_stable_and_short():

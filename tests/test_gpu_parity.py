@@ -291,6 +291,7 @@ def test_s32_decode_tile_kernel(ctx, W, k, pdt):
     case.fill_payloads()
     st = run_decode_check(ctx, case, W=W, wd=0.01)
     assert sum(x["elements"] for x in st) == sum(sp.numel for sp in specs)
+    ctx.demo_set_variant(1)
 
 
 def test_s32_decode_chunks_with_very_different_scales(ctx):
@@ -444,14 +445,17 @@ def test_mixed_dtypes_in_one_list(ctx, s, variant):
 
 
 # ---- s = 64, k = 32: worker counts that are multiples of 8 read the payload with 16-byte loads ------------------
+# (variant 1: the full-product instance on the float16 matrix pipe; variant 2: the mirror-folded float32 instances)
+@pytest.mark.parametrize("variant", [1, 2])
 @pytest.mark.parametrize("W", [8, 16, 24, 40, 56, 12, 63])
 @pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
-def test_s64_decode_worker_counts(ctx, W, pdt):
-    ctx.demo_set_variant(1)
+def test_s64_decode_worker_counts(ctx, W, pdt, variant):
+    ctx.demo_set_variant(variant)
     specs = [synth.TensorSpec("a", 192, 320), synth.TensorSpec("b", 64, 64), synth.TensorSpec("v", 128, 0)]
     case = Case(specs, 64, 32, W=W, param_dtype=pdt, seed=200 + W)
     case.fill_payloads()
     run_decode_check(ctx, case, W=W, wd=0.01)
+    ctx.demo_set_variant(1)
 
 
 # ---- s = 64, other budgets: k a multiple of 4 (16-byte loads of four pairs), of 2 (8-byte loads), odd (one pair) ----
@@ -461,14 +465,16 @@ def test_s64_decode_worker_counts(ctx, W, pdt):
                                  (200, 3), (100, 1), (400, 5), (65, 31), (40, 51),
                                  # more than 2048 pairs per chunk: streamed in rounds (k a multiple of 4), else generic
                                  (128, 32), (255, 32), (100, 24), (70, 36), (130, 16), (513, 4), (90, 30)])
+@pytest.mark.parametrize("variant", [1, 2])
 @pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
-def test_s64_decode_budgets(ctx, W, k, pdt):
-    ctx.demo_set_variant(1)
+def test_s64_decode_budgets(ctx, W, k, pdt, variant):
+    ctx.demo_set_variant(variant)
     specs = [synth.TensorSpec("a", 192, 320), synth.TensorSpec("b", 64, 64), synth.TensorSpec("v", 128, 0)]
     case = Case(specs, 64, k, W=W, param_dtype=pdt, seed=300 + W + k)
     case.fill_payloads()
     st = run_decode_check(ctx, case, W=W, wd=0.01)
     assert sum(x["elements"] for x in st) == sum(sp.numel for sp in specs)
+    ctx.demo_set_variant(1)
 
 
 # ---- the context caches a few descriptor tables: more distinct tensor lists than that still work, and a list
