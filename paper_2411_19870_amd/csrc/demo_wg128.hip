@@ -908,18 +908,18 @@ __global__ __launch_bounds__(E128_THREADS) void encode2d_quad128(TableView tv, c
         for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + 4 * (st + 1) + lqv];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
+          // the column factor as A operand, the row factor as B: component r of the result is column
+          // 16 nt + 4 lq + r of row 16 mt + l16, four consecutive columns per lane
           const float va = __uint_as_float(e[c].y) * a[c];
-          rc[0][c] = mfma4(va, b0[c], rc[0][c]);
-          rc[1][c] = mfma4(va, b1[c], rc[1][c]);
+          rc[0][c] = mfma4(b0[c], va, rc[0][c]);
+          rc[1][c] = mfma4(b1[c], va, rc[1][c]);
         }
       }
 #pragma unroll
       for (int n = 0; n < 2; ++n)
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            tiles[c * E128_TILE_FLOATS + (16 * mt + 4 * lqv + r) * E128_LDT + 16 * (nt0 + n) + l16v] = rc[n][c][r];
+          *reinterpret_cast<f32x4*>(&tiles[c * E128_TILE_FLOATS + (16 * mt + l16v) * E128_LDT + 16 * (nt0 + n) + 4 * lqv]) = rc[n][c];
     }
     wg_lds_barrier();
     DEMO_PHASE(5);
@@ -994,9 +994,11 @@ hipError_t launch_encode2d_wg128(const TableView& tv, const float* basis, const 
 //   R[127-i][j] = R_00 + R_01 - R_10 - R_11,  R[127-i][127-j] = R_00 - R_01 - R_10 + R_11:
 // a quarter of the multiplications of the full products.  The quadrant products run on the float16 matrix pipe with
 // both operands split into two parts (demo_device.h; 3 instructions of 16 cycles per 32 contraction indices where the
-// float32 instruction needs 8 of 32 cycles), two wavefronts per quadrant, each with half of the output columns: columns
-// are independent through both products, the accumulators of the first are, as they lie, operands of the second
-// (as in the full-product instance of demo_dec64.hip), and nothing but S and the four R_ab passes through LDS.
+// float32 instruction needs 8 of 32 cycles), two wavefronts per quadrant, each with half of the rows i of R_ab: the
+// chain is run transposed, R_ab^T = M_b^T (S_ab^T M_a), in which rows i are independent through both products, the
+// accumulators of the first are, as they lie, operands of the second (as in the full-product instance of
+// demo_dec64.hip) and those of the second hold four consecutive columns of a row; nothing but S and the four R_ab
+// passes through LDS.
 // The W k <= 4096 pairs of a chunk sit in at most eight registers per lane (pair 512 j + tid belongs to worker p / k,
 // position p % k) and are fetched for the next chunk while the products of this one run.  S is accumulated in block
 // fixed point with integer LDS atomics (one scale per chunk: the sum is exact and independent of the order of arrival).
@@ -1148,11 +1150,13 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
       pv[j] = ok ? pv[j] : 0.f;
     }
   };
-  // coefficient (u, v) lives in quadrant 2 (u % 2) + v % 2 at (u / 2, v / 2); lanes with nothing to add use a pad slot
+  // coefficient (u, v) lives in quadrant 2 (u % 2) + v % 2, transposed, at (v / 2, u / 2): the products below form
+  // R_ab^T = M_b^T S_ab^T M_a, whose accumulators hold four consecutive columns j of a row i of R_ab per lane (16-byte
+  // stores into the quadrant).  Lanes with nothing to add use a pad slot.
   const uint32_t dummy = (uint32_t)((tid & 63) * Q128_LDT + 64 + ((tid >> 6) & 3));
   auto slot_of = [&](int j) {
     const uint32_t fi = (uint32_t)pi[j];
-    const uint32_t a = (((fi >> 6) & 2u) | (fi & 1u)) * (uint32_t)Q128_TILE_FLOATS + (fi >> 8) * (uint32_t)Q128_LDT + ((fi & 127u) >> 1);
+    const uint32_t a = (((fi >> 6) & 2u) | (fi & 1u)) * (uint32_t)Q128_TILE_FLOATS + ((fi & 127u) >> 1) * (uint32_t)Q128_LDT + (fi >> 8);
     return fi < 16384u ? a : dummy;
   };
 
@@ -1168,11 +1172,11 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
 
   int vbits = 30;
   for (int w = 1; w < W; w <<= 1) --vbits;                     // 30 - ceil(log2 W)
-  // products: quadrant of this wavefront, its half of the columns, the two fragment tables
+  // products: quadrant of this wavefront, its half of the rows i, the two fragment tables
   const int quad = wave >> 1, jh = wave & 1;
   const float* tq = tiles + quad * Q128_TILE_FLOATS;
-  const float* TB = sT + (quad & 1) * Q128_FRAGS;              // first product: M_b, the column class
-  const float* TA = sT + (quad >> 1) * Q128_FRAGS;             // second product: M_a, the row class
+  const float* TB = sT + (quad >> 1) * Q128_FRAGS;             // first product: M_a, the row class
+  const float* TA = sT + (quad & 1) * Q128_FRAGS;              // second product: M_b, the column class
 
   // per-wavefront largest magnitude (as bits) of the payload registers into wmax buffer `buf`
   auto post_wave_max = [&](int buf) {
@@ -1311,11 +1315,12 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
     wg_lds_barrier();
     DEMO_PHASE(0);
 
-    // ---- the two products of this wavefront's quadrant, columns 32 jh .. 32 jh + 31 ------------------------------
-    // first: Y[u][j] = sum_v S_ab[u][v] M_b[v][j], A = S from the tile (row 16 ut + c; the eight v of a slot group
+    // ---- the two products of this wavefront's quadrant, rows i = 32 jh .. 32 jh + 31 of R_ab ---------------------------
+    // first: Y[v][i] = sum_u S_ab[u][v] M_a[u][i], A = S^T from the tile (row 16 vt + c; the eight u of a slot group
     // are two 16-byte reads), B = fragments.  The accumulators of two row tiles are, as they lie, the eight
-    // contraction slots of the second, R_ab[i][j] += sum_u M_a[u][i] Y[u][j], A = fragments.
-    f32x4 R[4][2];   // [it][jt - 2 jh]
+    // contraction slots of the second, R_ab[i][j] += sum_v M_b[v][j] Y[v][i], A = fragments: component r of
+    // R[jt][it - 2 jh] is R_ab[16 it + c][16 jt + 4 g + r].
+    f32x4 R[4][2];   // [jt][it - 2 jh]
 #pragma unroll
     for (int it = 0; it < 4; ++it)
 #pragma unroll
@@ -1375,8 +1380,7 @@ __global__ __launch_bounds__(Q128_THREADS) void decode2d_quad128(TableView tv, c
       for (int it = 0; it < 4; ++it)
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) wq[(16 * it + 4 * g + r) * Q128_LDT + 16 * (2 * jh + jj) + c] = R[it][jj][r];
+          *reinterpret_cast<f32x4*>(&wq[(16 * (2 * jh + jj) + c) * Q128_LDT + 16 * it + 4 * g]) = R[it][jj];
     }
     wg_lds_barrier();
     DEMO_PHASE(2);
@@ -1580,18 +1584,17 @@ __global__ __launch_bounds__(S128_THREADS) void decode2d_sparse128(TableView tv,
         for (int c = 0; c < 4; ++c) en[c] = sel[c * W128_SEL + 4 * (st + 1) + lq];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
+          // the column factor as A operand, the row factor as B: four consecutive columns of a row per lane
           const float va = __uint_as_float(e[c].y) * a[c];
-          rc[0][c] = mfma4(va, b0[c], rc[0][c]);
-          rc[1][c] = mfma4(va, b1[c], rc[1][c]);
+          rc[0][c] = mfma4(b0[c], va, rc[0][c]);
+          rc[1][c] = mfma4(b1[c], va, rc[1][c]);
         }
       }
 #pragma unroll
       for (int n = 0; n < 2; ++n)
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            tiles[c * Q128_TILE_FLOATS + (16 * mt + 4 * lq + r) * Q128_LDT + 16 * (nt0 + n) + l16] = rc[n][c][r];
+          *reinterpret_cast<f32x4*>(&tiles[c * Q128_TILE_FLOATS + (16 * mt + l16) * Q128_LDT + 16 * (nt0 + n) + 4 * lq]) = rc[n][c];
     }
     wg_lds_barrier();
     // the lists are read: cleared for the next chunk (entries in use only)
