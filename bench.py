@@ -32,7 +32,6 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix, published
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix, published
 S, K, W = 64, 32, 64
 BETA, LR, WD = 0.999, 1e-3, 0.0
@@ -65,14 +64,13 @@ def source_hash():
 
 
 F32_MFMA_FLOP = 2048.0      # v_mfma_f32_16x16x4_f32
-HALF_MFMA_FLOP = 16384.0    # v_mfma_f32_16x16x32_f16 / _bf16
+HALF_MFMA_FLOP = 16384.0    # v_mfma_f32_16x16x32_f16
 
 
 def mfma_work_per_launch(kernel, s, k, W, nchunks2, idx_tensors, projection="dct", variant=1):
     """Matrix-core work one launch of the order-2 kernel issues, by instruction type, from the kernels' own instruction
     counts: {"f32": flops of v_mfma_f32_16x16x4_f32, "f16": ... of v_mfma_f32_16x16x32_f16 (float32 operands split
-    into two float16 parts, three instructions per 16 x 16 tile and 32 contraction indices), "bf16": ... of
-    v_mfma_f32_16x16x32_bf16 (three bfloat16 parts, six instructions)}; None where the count depends on the data in a
+    into two float16 parts, three instructions per 16 x 16 tile and 32 contraction indices)}; None where the count depends on the data in a
     way this function does not follow (the few-pairs decode kernels) or the generic kernels run.  For encode the
     float32 reconstruction chain depends on how many selected coefficients fall into each class."""
     import torch
@@ -103,9 +101,9 @@ def mfma_work_per_launch(kernel, s, k, W, nchunks2, idx_tensors, projection="dct
             recon += float((4 * ((c0 + 3) // 4) + 4 * ((c1 + 3) // 4) + 8 * ((c2 + 3) // 4)).sum())
         return {"f32": (192.0 * nchunks2 + recon) * F32_MFMA_FLOP}
     if s == 64:
-        # full products of operands split into three bfloat16 parts, 192 instructions each; reconstruction in float32,
+        # full products of operands split into two float16 parts, 96 instructions each; reconstruction in float32,
         # 16 per four kept coefficients
-        return {"bf16": 2 * 192.0 * HALF_MFMA_FLOP * nchunks2, "f32": 16.0 * math.ceil(k / 4.0) * F32_MFMA_FLOP * nchunks2}
+        return {"f16": 192.0 * HALF_MFMA_FLOP * nchunks2, "f32": 16.0 * math.ceil(k / 4.0) * F32_MFMA_FLOP * nchunks2}
     if s == 32:
         return {"f32": (32.0 + 4.0 * math.ceil(k / 4.0)) * F32_MFMA_FLOP * nchunks2}   # four MFMAs per step of four coefficients
     # s = 128: four quadrant products, twice; reconstruction: 8 wavefronts x 2 tiles x 4 classes per step of four
@@ -288,7 +286,7 @@ def main():
     hbm_frac = achieved / HBM_PEAK_GBS
     work = mfma_work_per_launch(dom, S, K, W, nchunks2, [t.idx for t, sp in zip(tensors, specs) if sp.cols],
                                 a.projection, a.variant)
-    peaks = {"f32": MFMA_F32_PEAK_TFLOPS, "f16": MFMA_F16_PEAK_TFLOPS, "bf16": MFMA_BF16_PEAK_TFLOPS}
+    peaks = {"f32": MFMA_F32_PEAK_TFLOPS, "f16": MFMA_F16_PEAK_TFLOPS}
     if work:
         # the fraction is the time the matrix pipe needs at each instruction type's peak over the launch time
         pipe_s = sum(f / (peaks[ty] * 1e12) for ty, f in work.items())
@@ -309,8 +307,7 @@ def main():
             "mfma": {"achieved": mfma_tflops, "peak": mfma_peak, "unit": "TFLOP/s", "frac": mfma_frac,
                      "issued_fp32_mfma_flops_per_launch": (work or {}).get("f32"),
                      "issued_f16_mfma_flops_per_launch": (work or {}).get("f16"),
-                     "issued_bf16_mfma_flops_per_launch": (work or {}).get("bf16"),
-                     "peak_fp32": MFMA_F32_PEAK_TFLOPS, "peak_f16": MFMA_F16_PEAK_TFLOPS, "peak_bf16": MFMA_BF16_PEAK_TFLOPS},
+                     "peak_fp32": MFMA_F32_PEAK_TFLOPS, "peak_f16": MFMA_F16_PEAK_TFLOPS},
             "traffic": None, "traffic_source": None}
     roof.update({"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac} if bound == "hbm" else
                 {"achieved": mfma_tflops, "peak": mfma_peak, "unit": "TFLOP/s", "frac": mfma_frac})

@@ -217,89 +217,21 @@ __device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// ---- float32 products on the bfloat16 matrix pipe (full-product instances of the s = 64 kernels) ------------
-// A float32 x is the exact sum of three bfloat16 values: hi = rne(x), mid = rne(x - hi), lo = x - hi - mid (the
-// remainders are exact in float32, and the last one has at most eight significant bits).  Of the nine partial
-// products of two such triples the six of order up to 2^-16 are kept; what is dropped (mid lo, lo mid, lo lo) is
-// below 2^-24 of the product, the rounding of a float32 multiply.  v_mfma_f32_16x16x32_bf16 contracts 32 indices in
-// 16 cycles where v_mfma_f32_16x16x4_f32 contracts 4 in 32, so six of them cost 6/16 of the float32 instructions.
+// ---- float32 products on the float16 matrix pipe ------------------------------------------------------------------
+// A float32 x whose magnitude is bounded is, to 2^-22 |x|, the sum of two float16 values: hi = rne16(x),
+// lo = rne16(x - hi) (the remainder is exact in float32), as long as x's lowest bit is not below 2^-24, the spacing of
+// the float16 subnormals, which conversion and matrix pipe both keep (checked on the device).  Three products
+// hi hi + hi lo + lo hi on v_mfma_f32_16x16x32_f16 (16 cycles for 32 contraction indices, where v_mfma_f32_16x16x4_f32
+// needs 32 cycles for 4) drop lo lo, 2^-22 of the product: float32 accumulation and a typical relative error of
+// 2^-23 per term, that of a float32 multiply, at 3/16 of the float32 instructions' time.  (Three bfloat16 parts are
+// exact for any float32 but need six products and five more vector instructions per element to form.)
+// The callers scale so that nothing reaches 65504: basis entries (|P| <= 1) by 2^kSplitHBasisLog2, the data to below
+// 2^8 (the decode's block fixed-point sums by construction, the encode's tile by a power of two taken from its
+// largest magnitude), hence a first product below 2^4 sqrt(128) 2^8 < 2^15.6; the results carry these powers of two
+// and are unscaled exactly.
 // Operand layout: lane 16 g + c holds row (A) or column (B) c and eight contraction indices of group g, two per
 // register; both operands number their eight indices alike, so any fixed assignment of indices to the eight
 // slots serves as long as A and B share it.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-struct Split8 {
-  u32x4 hi, mid, lo;
-};
-// the three parts of the pair (x0, x1), each packed as {x0 part, x1 part}
-__device__ __forceinline__ void split_pair(float x0, float x1, uint32_t& h, uint32_t& m, uint32_t& l) {
-  h = pack_bf16x2(x0, x1);
-  const float r0 = x0 - __uint_as_float(h << 16), r1 = x1 - __uint_as_float(h & 0xffff0000u);
-  m = pack_bf16x2(r0, r1);
-  const float s0 = r0 - __uint_as_float(m << 16), s1 = r1 - __uint_as_float(m & 0xffff0000u);
-  l = pack_bf16x2(s0, s1);
-}
-__device__ __forceinline__ Split8 split8(float x0, float x1, float x2, float x3, float x4, float x5, float x6, float x7) {
-  uint32_t h[4], m[4], l[4];
-  split_pair(x0, x1, h[0], m[0], l[0]);
-  split_pair(x2, x3, h[1], m[1], l[1]);
-  split_pair(x4, x5, h[2], m[2], l[2]);
-  split_pair(x6, x7, h[3], m[3], l[3]);
-  return Split8{(u32x4){h[0], h[1], h[2], h[3]}, (u32x4){m[0], m[1], m[2], m[3]}, (u32x4){l[0], l[1], l[2], l[3]}};
-}
-__device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-// part p (0 = hi, 1 = mid, 2 = lo) of a pre-split fragment table: [part][64 lanes] 16-byte entries
-__device__ __forceinline__ Split8 load_split8(const float* frag, int lane) {
-  Split8 s;
-  s.hi = *reinterpret_cast<const u32x4*>(frag + (0 * 64 + lane) * 4);
-  s.mid = *reinterpret_cast<const u32x4*>(frag + (1 * 64 + lane) * 4);
-  s.lo = *reinterpret_cast<const u32x4*>(frag + (2 * 64 + lane) * 4);
-  return s;
-}
-
-// Host: the same three parts of a finite float32 (tables of pre-split basis fragments); out[p] = bfloat16 code of part p.
-inline void host_split3(float x, uint16_t out[3]) {
-  auto rne = [](float f) {
-    uint32_t b;
-    __builtin_memcpy(&b, &f, 4);
-    return (uint16_t)((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
-  };
-  auto widen = [](uint16_t h) {
-    const uint32_t b = (uint32_t)h << 16;
-    float f;
-    __builtin_memcpy(&f, &b, 4);
-    return f;
-  };
-  out[0] = rne(x);
-  const float r = x - widen(out[0]);
-  out[1] = rne(r);
-  const float s = r - widen(out[1]);
-  out[2] = rne(s);
-}
-// Host: writes the pre-split fragment of one lane, eight values, into a [part][64 lanes][4 words] block.
-inline void host_store_split8(float* frag, int lane, const float v[8]) {
-  uint32_t* w = reinterpret_cast<uint32_t*>(frag);
-  for (int j = 0; j < 8; ++j) {
-    uint16_t p[3];
-    host_split3(v[j], p);
-    for (int part = 0; part < 3; ++part) {
-      uint32_t& word = w[(part * 64 + lane) * 4 + (j >> 1)];
-      word = (j & 1) ? (word & 0x0000ffffu) | ((uint32_t)p[part] << 16) : (word & 0xffff0000u) | p[part];
-    }
-  }
-}
-constexpr int kSplitFragFloats = 3 * 64 * 4;   // words of one pre-split fragment block
-
-// ---- float32 products on the float16 matrix pipe (decode kernels) ---------------------------------------------
-// With operands whose magnitude is bounded (the decode's block fixed-point sums, basis entries |P| <= 1) two float16
-// parts do: hi = rne16(x), lo = rne16(x - hi) (the remainder is exact in float32), |x - hi - lo| <= 2^-22 |x| as long
-// as x's lowest bit is not below 2^-24, the spacing of the float16 subnormals, which conversion and matrix pipe both
-// keep (checked on the device).  Three products hi hi + hi lo + lo hi on v_mfma_f32_16x16x32_f16 (16 cycles for 32
-// contraction indices) drop lo lo, 2^-22 of the product: float32 accumulation and a relative error of about 2^-21 per
-// term, far inside what a sign (or the 1e-5 bound of the identity rule) needs, at 3/16 of the float32 instructions'
-// time.  The callers scale so that nothing reaches 65504: basis entries by 2^4 (kSplitHBasisScale), the sums to
-// below 2^8, hence |Y| <= 2^4 sqrt(128) 2^8 < 2^15.6; the result then carries 2^8 times the scale of the sums.
 typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
 struct SplitH8 {

@@ -51,12 +51,13 @@ __host__ __device__ constexpr int kappa64(int c) { return 4 * (c & 3) + (c >> 2)
 static_assert(E64_TABLE_FLOATS == kEnc64TableFloats, "table size");
 
 // Tables of the instances for a projection matrix without mirror symmetry (DENSE).  The two products run on the
-// bfloat16 matrix pipe with every float32 operand split into three parts (demo_device.h): their basis fragments
-// are stored pre-split, one block of kSplitFragFloats words per (tile, half h of the contraction range); slot j of
-// contraction group g stands for step 8 h + j of the sixteen steps the float32 instruction form would take.
+// float16 matrix pipe with every float32 operand split into two parts (demo_device.h): their basis fragments, scaled by
+// 2^kSplitHBasisLog2, are stored pre-split, one block of kSplitHFragFloats words per (tile, half h of the contraction
+// range); slot j of contraction group g stands for step 8 h + j of the sixteen steps the float32 instruction form
+// would take.
 constexpr int E64G_T1 = 0;                        // block 2 t + h, slot j:  P[16 t + c][rho(8 h + j, g)]              (product 1, B operand)
-constexpr int E64G_T2 = 8 * kSplitFragFloats;     // block 2 vt + h, slot j: P[16 vt + c][4 chi(4g + r) + e], 4 e + r = 8 h + j  (product 2, A operand)
-constexpr int E64G_PCOL = 16 * kSplitFragFloats;  // pcol[v*64 + 4c + e]          = P[v][4 chi(c) + e]                (reconstruction, B operand)
+constexpr int E64G_T2 = 8 * kSplitHFragFloats;    // block 2 vt + h, slot j: P[16 vt + c][4 chi(4g + r) + e], 4 e + r = 8 h + j  (product 2, A operand)
+constexpr int E64G_PCOL = 16 * kSplitHFragFloats; // pcol[v*64 + 4c + e]          = P[v][4 chi(c) + e]                (reconstruction, B operand)
 constexpr int E64G_PROW = E64G_PCOL + 4096;       // prow[u*64 + 16 w + c]        = P[u][rho(4 (c%4) + w, c/4)]       (reconstruction, A operand)
 constexpr int E64G_TABLE_FLOATS = E64G_PROW + 4096;
 static_assert(E64G_TABLE_FLOATS == kEnc64DenseTableFloats, "table size");
@@ -76,11 +77,11 @@ void build_enc64_dense_tables(const double* P, float* out) {
         float v1[8], v2[8];
         for (int j = 0; j < 8; ++j) {
           const int q = 8 * h + j;   // product 1: step q; product 2: (e, r) = (q / 4, q % 4)
-          v1[j] = Pm(16 * t + c, rho(q, g));
-          v2[j] = Pm(16 * t + c, 4 * chi(4 * g + (q & 3)) + (q >> 2));
+          v1[j] = (float)__builtin_ldexp(P[(16 * t + c) * 64 + rho(q, g)], kSplitHBasisLog2);
+          v2[j] = (float)__builtin_ldexp(P[(16 * t + c) * 64 + 4 * chi(4 * g + (q & 3)) + (q >> 2)], kSplitHBasisLog2);
         }
-        host_store_split8(out + E64G_T1 + (2 * t + h) * kSplitFragFloats, lane, v1);
-        host_store_split8(out + E64G_T2 + (2 * t + h) * kSplitFragFloats, lane, v2);
+        host_store_split8h(out + E64G_T1 + (2 * t + h) * kSplitHFragFloats, lane, v1);
+        host_store_split8h(out + E64G_T2 + (2 * t + h) * kSplitHFragFloats, lane, v2);
       }
   }
   for (int u = 0; u < 64; ++u)
@@ -155,6 +156,7 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
   uint2* keys = reinterpret_cast<uint2*>(scratch + 2 * E64_LIST);        // {~flat index, magnitude bits}
   uint2* sel = reinterpret_cast<uint2*>(scratch + 2 * E64_LIST + 128);   // [3][64] {flat index, value bits} by class of u
   const int k = args.k;
+  [[maybe_unused]] const float m1h = opaque_minus_one();
   // LDS byte address of cand_v[0] as a scalar the compiler cannot take apart (it would otherwise re-add the
   // constant part of the address on every access)
   uint32_t list_base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)(lds_u32*)cand_v);
@@ -296,31 +298,46 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
     for (int e = 0; e < 4; ++e)
 #pragma unroll
       for (int tt = 0; tt < 4; ++tt) C1[e][tt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    [[maybe_unused]] int dense_unscale = 0;   // DENSE: the coefficients come out as Q 2^-dense_unscale
     if constexpr (DENSE) {
-      // contraction over the rows in two halves of 32: slot j of group g is row rho(8 h + j, g); the data are split
-      // into bfloat16 triples once per half and serve the four tiles of u
+      // scale of the chunk: |D| < 2^(e+1) for the largest magnitude's exponent e, and 2^(7-e) brings the tile below
+      // 2^8, the first product below 2^4 8 2^8 = 2^15 (float16 ends at 65504)
+      float mx = 0.f;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        Split8 A[4];
+      for (int s4 = 0; s4 < 4; ++s4)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          A[e] = split8(D[2 * h][e][0], D[2 * h][e][1], D[2 * h][e][2], D[2 * h][e][3],
-                        D[2 * h + 1][e][0], D[2 * h + 1][e][1], D[2 * h + 1][e][2], D[2 * h + 1][e][3]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) mx = fmaxf(mx, fabsf(D[s4][e][w]));
+      uint32_t mb = __float_as_uint(mx);
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x4E, 0xf, 0xf, false));   // quad_perm [2,3,0,1]
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x141, 0xf, 0xf, false));  // row_half_mirror
+      mb = max(mb, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)mb, 0x140, 0xf, 0xf, false));  // row_mirror
+      const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 0), (uint32_t)__builtin_amdgcn_readlane((int)mb, 16));
+      const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)mb, 32), (uint32_t)__builtin_amdgcn_readlane((int)mb, 48));
+      int se = 261 - (int)(max(m01, m23) >> 23);               // biased exponent of 2^(7 - (ex - 127))
+      se = se < 1 ? 1 : se > 254 ? 254 : se;                   // (chunks below 2^-119 keep fewer bits)
+      const float sc = __uint_as_float((uint32_t)se << 23);
+      dense_unscale = se - 127 + 2 * kSplitHBasisLog2;
+      // contraction over the rows in two halves of 32: slot j of group g is row rho(8 h + j, g); the data are split
+      // into float16 pairs once per half and serve the four tiles of u
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        SplitH8 A[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          A[e] = split8h(m1h, D[2 * h][e][0] * sc, D[2 * h][e][1] * sc, D[2 * h][e][2] * sc, D[2 * h][e][3] * sc,
+                         D[2 * h + 1][e][0] * sc, D[2 * h + 1][e][1] * sc, D[2 * h + 1][e][2] * sc, D[2 * h + 1][e][3] * sc);
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
-          const Split8 Bq = load_split8(sT1 + (2 * tt + h) * kSplitFragFloats, lane);
+          const SplitH8 Bq = load_split8h(sT1 + (2 * tt + h) * kSplitHFragFloats, lane);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].lo, Bq.hi, C1[e][tt]);
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_f16(A[e].lo, Bq.hi, C1[e][tt]);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].hi, Bq.lo, C1[e][tt]);
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_f16(A[e].hi, Bq.lo, C1[e][tt]);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].mid, Bq.mid, C1[e][tt]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].mid, Bq.hi, C1[e][tt]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].hi, Bq.mid, C1[e][tt]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_bf16(A[e].hi, Bq.hi, C1[e][tt]);
+          for (int e = 0; e < 4; ++e) C1[e][tt] = mfma_f16(A[e].hi, Bq.hi, C1[e][tt]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -357,29 +374,30 @@ __global__ __launch_bounds__(E64_THREADS) void encode2d_wave64(TableView tv, con
       // 4 e + r = 8 h + j'; the accumulators of product 1 are split as they lie and serve the four tiles of v
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        Split8 Bt[4];
+        SplitH8 Bt[4];
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt)
-          Bt[tt] = split8(C1[2 * h][tt][0], C1[2 * h][tt][1], C1[2 * h][tt][2], C1[2 * h][tt][3],
-                          C1[2 * h + 1][tt][0], C1[2 * h + 1][tt][1], C1[2 * h + 1][tt][2], C1[2 * h + 1][tt][3]);
+          Bt[tt] = split8h(m1h, C1[2 * h][tt][0], C1[2 * h][tt][1], C1[2 * h][tt][2], C1[2 * h][tt][3],
+                           C1[2 * h + 1][tt][0], C1[2 * h + 1][tt][1], C1[2 * h + 1][tt][2], C1[2 * h + 1][tt][3]);
 #pragma unroll
         for (int vt = 0; vt < 4; ++vt) {
-          const Split8 Ap = load_split8(sT2 + (2 * vt + h) * kSplitFragFloats, lane);
+          const SplitH8 Ap = load_split8h(sT2 + (2 * vt + h) * kSplitHFragFloats, lane);
 #pragma unroll
-          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.lo, Bt[tt].hi, C2[vt][tt]);
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_f16(Ap.lo, Bt[tt].hi, C2[vt][tt]);
 #pragma unroll
-          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.hi, Bt[tt].lo, C2[vt][tt]);
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_f16(Ap.hi, Bt[tt].lo, C2[vt][tt]);
 #pragma unroll
-          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.mid, Bt[tt].mid, C2[vt][tt]);
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.mid, Bt[tt].hi, C2[vt][tt]);
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.hi, Bt[tt].mid, C2[vt][tt]);
-#pragma unroll
-          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_bf16(Ap.hi, Bt[tt].hi, C2[vt][tt]);
+          for (int tt = 0; tt < 4; ++tt) C2[vt][tt] = mfma_f16(Ap.hi, Bt[tt].hi, C2[vt][tt]);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
+      // back to the scale of the data (exact: a power of two)
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) C2[vt][tt][r] = ldexpf(C2[vt][tt][r], -dense_unscale);
     } else {
       const float4 pee4 = *reinterpret_cast<const float4*>(&sT2[(0 * 64 + lane) * 4]);
       const float4 peo4 = *reinterpret_cast<const float4*>(&sT2[(1 * 64 + lane) * 4]);

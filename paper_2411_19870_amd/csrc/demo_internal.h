@@ -119,7 +119,7 @@ constexpr int kFast64MaxK = 64;
 void build_enc64_tables(const double* P, float* out /* kEnc64TableFloats */);
 void build_dec64_tables(const double* P, float* out /* kDec64TableFloats */);
 // ... and their instances for a projection matrix without mirror symmetry: full products, other tables
-constexpr int kEnc64DenseTableFloats = 16 * 768 + 2 * 4096;   // 16 pre-split fragment blocks, two 64 x 64 tables
+constexpr int kEnc64DenseTableFloats = 16 * 512 + 2 * 4096;   // 16 pre-split float16 fragment blocks + the reconstruction's float32 rows
 void build_enc64_dense_tables(const double* P, float* out /* kEnc64DenseTableFloats */);
 hipError_t launch_encode2d_wave64(const TableView& tv, const float* tables, const EncodeArgs& a, const Worklist& wl,
                                   bool grad_bf16, bool dense, int num_cus, hipStream_t stream);
