@@ -477,6 +477,23 @@ def test_s64_decode_budgets(ctx, W, k, pdt, variant):
     ctx.demo_set_variant(1)
 
 
+@pytest.mark.parametrize("variant", [1, 2])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+def test_s64_decode_when_every_worker_names_the_same_coefficients(ctx, pdt, variant):
+    # W equal pairs per coefficient: the sums reach W times the largest value, the top of the block fixed point and of
+    # the float16 range the full products are scaled to
+    ctx.demo_set_variant(variant)
+    W, k = 64, 32
+    specs = [synth.TensorSpec("a", 192, 320), synth.TensorSpec("v", 128, 0)]
+    case = Case(specs, 64, k, W=W, param_dtype=pdt, seed=77)
+    case.fill_payloads()
+    for ti in range(len(specs)):
+        case.idx[ti][:] = case.idx[ti][0:1]
+        case.val[ti][:] = case.val[ti][0:1].abs()
+    run_decode_check(ctx, case, W=W)
+    ctx.demo_set_variant(1)
+
+
 # ---- the context caches a few descriptor tables: more distinct tensor lists than that still work, and a list
 #      that was evicted is simply uploaded again ------------------------------------------------------------------
 def test_many_distinct_tensor_lists(ctx):

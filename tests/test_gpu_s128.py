@@ -124,3 +124,77 @@ def test_generic_and_workgroup_kernels_agree_on_the_payload(ctx):
     assert torch.equal(a.idx[0].sort(dim=-1).values, b.idx[0].sort(dim=-1).values)
     assert torch.allclose(a.val[0].abs().sum(), b.val[0].abs().sum(), rtol=1e-5)
     assert torch.allclose(a.m[0], b.m[0], rtol=0, atol=1e-6)
+
+
+# ---- few pairs per chunk (W k <= 64): the kernel without a coefficient tile -------------------------------------------
+@pytest.mark.parametrize("W,k", [(1, 32), (1, 64), (2, 32), (64, 1), (7, 9), (3, 1), (1, 5)])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("phi,agg", [("sign", "sum"), ("identity", "mean")])
+def test_few_pairs_decode(ctx, W, k, pdt, phi, agg):
+    from tests import compare as C
+    # 288 + 6 chunks on 256 workgroups (second chunks, of another tensor), an order-1 tensor in between
+    specs = [synth.TensorSpec("a", 1536, 3072), synth.TensorSpec("v", 256, 0), synth.TensorSpec("b", 384, 256)]
+    case = Case(specs, S, k, W=W, param_dtype=pdt, seed=500 + W + k)
+    case.fill_payloads()
+    # workers that name the same coefficient add up; indices out of range contribute nothing
+    if W > 1:
+        case.idx[0][1, :, 0] = case.idx[0][0, :, 0]
+        case.idx[2][W - 1, 3, 0] = case.idx[2][0, 3, 0]
+    case.idx[0][0, 5, k - 1] = 16384
+    case.idx[2][0, 1, 0] = -7
+    hp = B.demo_hparams_default(lr=LR, weight_decay=0.05, phi=B.DEMO_PHI_IDENTITY if phi == "identity" else B.DEMO_PHI_SIGN,
+                                aggregate=B.DEMO_AGG_MEAN if agg == "mean" else B.DEMO_AGG_SUM)
+    before = case.snapshot()
+    ctx.demo_decode_ex(case.args, W, hp, S, k)
+    torch.cuda.synchronize()
+    after = case.snapshot()
+    pd = "bf16" if pdt == torch.bfloat16 else "f32"
+    for ti in range(len(specs)):
+        C.check_decode(before["x"][ti], before["idx"][ti][:W], before["val"][ti][:W], LR, 0.05, S, pd, after["x"][ti],
+                       phi=phi, aggregate_mode=agg)
+
+
+# ---- the products run on the float16 matrix pipe at a scale taken from the chunk: nothing may depend on the
+#      absolute scale of the data, and patterns that line up with one basis row must stay inside the float16 range ----
+@pytest.mark.parametrize("exp2", [-100, -80, 60, 100])
+@pytest.mark.parametrize("gdt", [torch.float32, torch.bfloat16])
+def test_encode_is_scale_free_over_the_exponent_range(ctx, exp2, gdt):
+    scale = 2.0 ** exp2
+    specs = [synth.TensorSpec("a", 384, 256)]
+    case = Case(specs, S, 32, seed=61, grad_dtype=gdt, grad_std=1e-2 * scale, mom_std=1e-3 * scale)
+    st = run_encode_check(ctx, case, beta=0.9)[0]
+    assert st["chunks"] == 6
+
+
+def test_encode_of_patterns_that_line_up_with_a_basis_row(ctx):
+    # chunk 0: checkerboard (all its energy in the highest frequency pair: the largest coefficient a tile of bounded
+    # elements can have), chunk 1: one spike among values 2^-30 below it, chunk 2: a constant, chunk 3: the outer
+    # product of two basis rows (a single coefficient), chunks 4, 5: gaussian
+    specs = [synth.TensorSpec("a", 256, 384)]
+    case = Case(specs, S, 8, seed=62, mom_std=0)
+    g = case.g[0]
+    i = torch.arange(S, device=DEV)
+    g[:S, :S] = (1.0 - 2.0 * ((i[:, None] + i[None, :]) % 2)) * 3.0
+    g[:S, S:2 * S] *= 2.0 ** -30
+    g[5, S + 77] = 1.0
+    g[:S, 2 * S:3 * S] = -0.75
+    n = torch.arange(S, device=DEV, dtype=torch.float64)
+    r17 = torch.cos(torch.pi * (2 * n + 1) * 17 / (2 * S))
+    r90 = torch.cos(torch.pi * (2 * n + 1) * 90 / (2 * S))
+    g[S:2 * S, :S] = (r17[:, None] * r90[None, :]).float()
+    st = run_encode_check(ctx, case, beta=0.0)[0]
+    assert st["chunks"] == 6
+    run_decode_check(ctx, case, W=1)
+
+
+def test_decode_when_every_worker_names_the_same_coefficients(ctx):
+    # W equal pairs per coefficient: the sums reach W times the largest value, the top of the block fixed point and of
+    # the float16 range the products are scaled to
+    W, k = 64, 32
+    specs = [synth.TensorSpec("a", 256, 256), synth.TensorSpec("v", 128, 0)]
+    case = Case(specs, S, k, W=W, param_dtype=torch.bfloat16, seed=63)
+    case.fill_payloads()
+    for ti in range(len(specs)):
+        case.idx[ti][:] = case.idx[ti][0:1]
+        case.val[ti][:] = case.val[ti][0:1].abs()
+    run_decode_check(ctx, case, W=W)
