@@ -13,8 +13,9 @@ reconstructed momentum is not within rounding noise of zero (|R| > 1e-5 * max|R|
 the chunk); inside that band any of sgn in {-1, 0, +1} is accepted.  Outside the band the
 parameters are also held against the update line of Algorithm 1 evaluated in plain float64,
 x - eta (sgn(m) + lambda x), rounded once to the storage type: every element within one unit
-in the last place (taken at the largest of |x|, |x'| and the step eta |sgn(m) + lambda x|), and
-the number of elements that differ at all is reported.
+in the last place (taken at the largest of |x|, |x'| and the step eta |sgn(m) + lambda x|) plus
+eta times half a float32 unit of the inner sum, and the number of elements that differ at all is
+reported.
 """
 from __future__ import annotations
 
@@ -135,6 +136,10 @@ def check_decode(x_prev, idx, val, lr32, wd32, s, param_dtype, gpu_x, phi="sign"
     # smaller than the float32 rounding of the step itself
     step = np.abs(lr64 * (np.sign(ref["R"]) + wd64 * x_prev))
     ulp = storage_ulp(np.maximum(np.maximum(np.abs(exact), np.abs(x_prev)), step), param_dtype)
+    # ... plus the rounding of the inner sum sgn + lambda x to float32 (half a unit of 2^-23 at magnitude 1), carried
+    # through the multiplication by eta: with lambda != 0 and |x'| just above a power of two the two roundings of the
+    # float32 evaluation add up to 1.01 units (seen once in 4.7 million elements)
+    ulp = ulp + lr64 * 2.0 ** -24 * np.abs(np.sign(ref["R"]) + wd64 * x_prev)
     assert np.all(off[sure] <= ulp[sure]), (
         f"parameters more than one unit in the last place from the float64 update: worst {np.max(off[sure]):.3e}")
     stats["differs_from_f64_update"] = int(np.sum((got.astype(np.float64) != round_once(exact, param_dtype)) & sure))
