@@ -167,23 +167,29 @@ def test_encode_is_scale_free_over_the_exponent_range(ctx, exp2, gdt):
 
 
 def test_encode_of_patterns_that_line_up_with_a_basis_row(ctx):
-    # chunk 0: checkerboard (all its energy in the highest frequency pair: the largest coefficient a tile of bounded
-    # elements can have), chunk 1: one spike among values 2^-30 below it, chunk 2: a constant, chunk 3: the outer
-    # product of two basis rows (a single coefficient), chunks 4, 5: gaussian
+    # every chunk is the inverse transform of eight planted coefficients with magnitudes 1, 1/2, ..., 1/128 times an
+    # amplitude: a tile of bounded elements whose energy sits in a few basis rows has the largest coefficients such a
+    # tile can have (constant and checkerboard tiles: s times the element size), and the smallest planted one lies
+    # seven binary orders below the largest
+    import scipy.fft
     specs = [synth.TensorSpec("a", 256, 384)]
-    case = Case(specs, S, 8, seed=62, mom_std=0)
-    g = case.g[0]
-    i = torch.arange(S, device=DEV)
-    g[:S, :S] = (1.0 - 2.0 * ((i[:, None] + i[None, :]) % 2)) * 3.0
-    g[:S, S:2 * S] *= 2.0 ** -30
-    g[5, S + 77] = 1.0
-    g[:S, 2 * S:3 * S] = -0.75
-    n = torch.arange(S, device=DEV, dtype=torch.float64)
-    r17 = torch.cos(torch.pi * (2 * n + 1) * 17 / (2 * S))
-    r90 = torch.cos(torch.pi * (2 * n + 1) * 90 / (2 * S))
-    g[S:2 * S, :S] = (r17[:, None] * r90[None, :]).float()
+    case = Case(specs, S, 8, seed=62, mom_std=0, grad="zero")
+    rng = np.random.default_rng(62)
+    planted = [[(0, 0), (127, 127)], [(127, 127), (0, 0)], [(17, 90), (90, 17)], [(0, 127), (64, 64)],
+               [(1, 1), (126, 2)], [(63, 65), (127, 0)]]
+    q = np.zeros((2, 3, S, S))
+    for c, heads in enumerate(planted):
+        pos = list(heads)
+        while len(pos) < 8:
+            p = (int(rng.integers(0, S)), int(rng.integers(0, S)))
+            if p not in pos:
+                pos.append(p)
+        for j, (u, v) in enumerate(pos):
+            q[c // 3, c % 3, u, v] = (1.0 if j % 2 == 0 else -1.0) * 2.0 ** -j * (3.0 if c % 2 == 0 else 1e-3)
+    g = scipy.fft.idctn(q, type=2, norm="ortho", axes=(2, 3)).transpose(0, 2, 1, 3).reshape(256, 384)
+    case.g[0].copy_(torch.from_numpy(g).float())
     st = run_encode_check(ctx, case, beta=0.0)[0]
-    assert st["chunks"] == 6
+    assert st["chunks"] == 6 and st["sets_identical"] == 6
     run_decode_check(ctx, case, W=1)
 
 
