@@ -60,7 +60,7 @@ def main():
 
     rows = []
     names = {1: "memory stream only (loads with prefetch, momentum update, store, k pairs)",
-             2: "+ the two DCT products (192 MFMA)", 3: "+ top-k and payload", 0: "+ reconstruction = the kernel"}
+             2: "+ the two DCT products (192 float32 MFMA)", 3: "+ top-k and payload", 0: "+ reconstruction = the kernel"}
     prev = 0.0
     for stage in (1, 2, 3, 0):
         ms = time_encode(stage)
@@ -82,7 +82,7 @@ def main():
 
     drows = []
     dnames = {1: "memory stream only (payload and parameter loads with prefetch, update, stores)",
-              2: "+ scatter-add of the W k pairs into the LDS tile", 0: "+ the two IDCT products (192 MFMA) = the kernel"}
+              2: "+ scatter-add of the W k pairs into the LDS tile", 0: "+ the two IDCT products (192 float16 MFMA) = the kernel"}
     prev = 0.0
     for stage in (1, 2, 0):
         ms = time_decode(stage)
