@@ -299,7 +299,7 @@ def main():
         mfma_peak = MFMA_F32_PEAK_TFLOPS
     other = "dec2d" if dom == "enc2d" else "enc2d"
     work_other = mfma_work_per_launch(other, S, K, W, nchunks2, [], a.projection, a.variant) if other == "dec2d" else None
-    split_types = sorted(ty for wk in (work, work_other) if wk for ty in wk if ty != "f32")
+    split_types = sorted({ty for wk in (work, work_other) if wk for ty in wk if ty != "f32"})
     bound = "mfma" if (mfma_frac or 0.0) > hbm_frac else "hbm"
     roof = {"bound": bound, "kernel": dom, "avg_launch_ms": kms[dom],
             "hbm": {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm_frac,
@@ -383,6 +383,10 @@ def main():
                                      f"of these kernel sources, hash {rec['source_hash']})"
         elif not same:
             roof["traffic_source"] = f"profiles/hbm_traffic_{a.workload}.json is from other kernel sources: not quoted"
+        else:
+            roof["traffic_source"] = "no counter record for this operating point (the records cover the headline configuration of each workload)"
+    else:
+        roof["traffic_source"] = "no counter record for this workload"
     ctx.close()
     del tensors, tl
     torch.cuda.empty_cache()
