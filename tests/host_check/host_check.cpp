@@ -4,6 +4,7 @@
 // tables, called directly on exactly sized buffers.  No GPU is touched.  Exit status 0 = all checks
 // passed; a sanitizer report aborts the program.
 #include <cmath>
+#include <cstdint>
 #include <cstdio>
 #include <cstring>
 #include <limits>
@@ -190,6 +191,51 @@ int main() {
     double energy = 0.0;
     for (float x : e64) energy += (double)x * x;
     EXPECT(energy > 1.0);   // the tables hold entries of an orthonormal matrix
+  }
+
+  // pre-split float16 fragment tables (the matrix entries times 2^4 as hi + lo halves): exactly sized buffers, and
+  // every entry of the s = 128 decode and encode tables and of the full-product s = 64 decode table decoded again:
+  // hi + lo must give 16 P to 2^-21 of the entry (two float16 parts hold 22 significant bits) or 2^-25 absolute
+  // (the spacing of the float16 subnormals, halved)
+  {
+    auto half = [](uint32_t h) {   // float16 code -> value
+      const int e = (int)((h >> 10) & 31u);
+      const double m = (double)(h & 1023u);
+      const double mag = e == 0 ? std::ldexp(m, -24) : std::ldexp(m + 1024.0, e - 25);
+      return (h & 0x8000u) ? -mag : mag;
+    };
+    // block `blk` (512 words: [hi | lo][64 lanes][4 words]) of a table, lane, slot j -> hi + lo
+    auto entry = [&](const std::vector<float>& tab, int blk, int lane, int j) {
+      uint32_t wh, wl;
+      std::memcpy(&wh, &tab[(size_t)blk * 512 + (0 * 64 + lane) * 4 + (j >> 1)], 4);
+      std::memcpy(&wl, &tab[(size_t)blk * 512 + (1 * 64 + lane) * 4 + (j >> 1)], 4);
+      return half((j & 1) ? wh >> 16 : wh & 0xffffu) + half((j & 1) ? wl >> 16 : wl & 0xffffu);
+    };
+    auto close = [](double got, double want) { return std::fabs(got - want) <= std::fabs(want) * std::ldexp(1.0, -21) + std::ldexp(1.0, -25); };
+    const std::vector<double> P64 = dct(64), P128 = dct(128);
+    std::vector<float> d64g(demo::kDec64DenseTableFloats), e64g(demo::kEnc64DenseTableFloats), d128(demo::kDec128TableFloats),
+        e128(demo::kEnc128TableFloats);
+    demo::build_dec64_dense_tables(P64.data(), d64g.data());
+    demo::build_enc64_dense_tables(P64.data(), e64g.data());
+    demo::build_dec128_tables(P128.data(), d128.data());
+    demo::build_enc128_tables(P128.data(), e128.data());
+    EXPECT(all_finite(e64g));
+    int bad = 0;
+    for (int t = 0; t < 4; ++t)
+      for (int h = 0; h < 2; ++h)
+        for (int lane = 0; lane < 64; ++lane)
+          for (int j = 0; j < 8; ++j) {
+            const int g = lane >> 4, c = lane & 15;
+            const int kk = 16 * (2 * h + (j >> 2)) + 4 * g + (j & 3);   // contraction index of slot j
+            // full-product s = 64 decode: P[kk][16 t + c]
+            if (!close(entry(d64g, 2 * t + h, lane, j), 16.0 * P64[(size_t)kk * 64 + 16 * t + c])) ++bad;
+            for (int m = 0; m < 2; ++m) {
+              // s = 128 decode: rows 2 kk + m of P, columns 16 t + c; encode: the transposed fragments
+              if (!close(entry(d128, 8 * m + 2 * t + h, lane, j), 16.0 * P128[(size_t)(2 * kk + m) * 128 + 16 * t + c])) ++bad;
+              if (!close(entry(e128, 8 * m + 2 * t + h, lane, j), 16.0 * P128[(size_t)(2 * (16 * t + c) + m) * 128 + kk])) ++bad;
+            }
+          }
+    EXPECT(bad == 0);
   }
 
   EXPECT(demo_destroy(ctx) == DEMO_OK);
